@@ -1,0 +1,296 @@
+"""ctypes front end of the CPU oracle (oracle/kvp_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's
+cpu_baseline leg call this; the GPU library never does and shares nothing with
+it.  Every array that goes in or out is one byte per boolean.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kvp_oracle.c")
+_LIB = os.path.join(_HERE, "_build", "liborc.so")
+CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC"]
+
+
+def build(force: bool = False) -> str:
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        os.makedirs(os.path.dirname(_LIB), exist_ok=True)
+        tmp = _LIB + f".{os.getpid()}.tmp"
+        subprocess.check_call(["gcc", *CFLAGS, "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Problem(C.Structure):
+    _fields_ = [("L", C.c_int32), ("N", C.c_int32), ("P", C.c_int32), ("K", C.c_int32),
+                ("access", C.c_void_p), ("alive", C.c_void_p), ("persist", C.c_void_p),
+                ("written", C.c_void_p), ("plane_bytes", C.c_uint64 * 8),
+                ("page_bytes", C.c_uint64), ("token_bytes", C.c_uint64),
+                ("bw_hbm", C.c_double), ("bw_link", C.c_double), ("bw_dram", C.c_double),
+                ("cap_pages", C.c_uint64)]
+
+
+class _Move(C.Structure):
+    _fields_ = [(k, C.c_uint32) for k in ("op", "layer", "page", "n1", "len", "layer2", "page2", "dsel")]
+
+
+class _SAParams(C.Structure):
+    _fields_ = [("seed", C.c_uint64), ("total_moves", C.c_uint64), ("move_begin", C.c_uint64),
+                ("move_end", C.c_uint64), ("n_levels", C.c_uint32), ("max_len", C.c_uint32),
+                ("p0", C.c_double), ("alpha", C.c_double), ("op_prob", C.c_double * 3)]
+
+
+class _SAState(C.Structure):
+    _fields_ = [("T_cur", C.c_double), ("T_best", C.c_double), ("C0", C.c_double), ("C", C.c_double),
+                ("level", C.c_uint32), ("accepted", C.c_uint64), ("uphill", C.c_uint64),
+                ("null_moves", C.c_uint64), ("clipped", C.c_uint64), ("improved", C.c_uint64),
+                ("uphill_seen", C.c_uint64)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        L.orc_csum.restype = C.c_double
+        L.orc_csum.argtypes = [C.c_void_p, C.c_size_t]
+        L.orc_step_time.restype = C.c_double
+        L.orc_step_time.argtypes = [C.POINTER(_Problem), C.c_void_p]
+        L.orc_score.restype = C.c_double
+        L.orc_score.argtypes = [C.POINTER(_Problem), C.c_void_p, C.POINTER(C.c_uint32), C.c_void_p,
+                                C.c_void_p, C.c_void_p]
+        L.orc_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.orc_delta.restype = C.c_int
+        L.orc_delta.argtypes = [C.POINTER(_Problem), C.c_void_p, C.POINTER(_Move), C.POINTER(C.c_double),
+                                C.POINTER(C.c_int), C.c_void_p, C.c_void_p]
+        L.orc_resolve.restype = C.c_int
+        L.orc_resolve.argtypes = [C.POINTER(_Problem), C.c_void_p, C.c_void_p, C.POINTER(_Move),
+                                  C.c_void_p, C.c_void_p, C.POINTER(C.c_int)]
+        L.orc_init_static_frequency.argtypes = [C.POINTER(_Problem), C.c_void_p]
+        L.orc_init_recency.argtypes = [C.POINTER(_Problem), C.c_void_p]
+        L.orc_bruteforce.restype = C.c_int
+        L.orc_bruteforce.argtypes = [C.POINTER(_Problem), C.POINTER(C.c_double), C.c_void_p,
+                                     C.POINTER(C.c_uint64)]
+        L.orc_anneal_chain.restype = C.c_int
+        L.orc_anneal_chain.argtypes = [C.POINTER(_Problem), C.POINTER(_SAParams), C.c_uint32, C.c_void_p,
+                                       C.c_void_p, C.POINTER(_SAState)]
+        _lib = L
+    return _lib
+
+
+def _u8(a, shape):
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    assert a.shape == tuple(shape), (a.shape, shape)
+    return a
+
+
+class Problem:
+    """Holds the boolean trace arrays alive for the C side."""
+
+    def __init__(self, tr):
+        self.L, self.N, self.P, self.K = tr.L, tr.N, tr.P, tr.K
+        self.access = _u8(tr.access, (tr.L, tr.N, tr.K, tr.P))
+        self.alive = _u8(tr.alive, (tr.N, tr.P))
+        self.persist = _u8(tr.persist, (tr.N, tr.P))
+        self.written = _u8(tr.written, (tr.N, tr.P))
+        al = self.alive.astype(bool)
+        assert not (self.access.astype(bool) & ~al[None, :, None, :]).any(), "access outside alive"
+        assert not (self.written.astype(bool) & ~al).any(), "written outside alive"
+        assert not self.persist[0].any()
+        assert not (self.persist[1:].astype(bool) & ~(al[1:] & al[:-1])).any(), "persist outside alive"
+        assert 1 <= tr.K <= 8 and len(tr.plane_bytes) == tr.K
+        c = _Problem()
+        c.L, c.N, c.P, c.K = tr.L, tr.N, tr.P, tr.K
+        c.access = self.access.ctypes.data
+        c.alive = self.alive.ctypes.data
+        c.persist = self.persist.ctypes.data
+        c.written = self.written.ctypes.data
+        for k in range(tr.K):
+            c.plane_bytes[k] = int(tr.plane_bytes[k])
+        c.page_bytes, c.token_bytes = int(tr.page_bytes), int(tr.token_bytes)
+        c.bw_hbm, c.bw_link, c.bw_dram = float(tr.bw_hbm), float(tr.bw_link), float(tr.bw_dram)
+        c.cap_pages = int(tr.cap_pages)
+        self.c = c
+
+    @property
+    def shape(self):
+        return (self.L, self.N, self.P)
+
+
+def _problem(tr) -> Problem:
+    return tr if isinstance(tr, Problem) else Problem(tr)
+
+
+def csum(v) -> float:
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    return lib().orc_csum(v.ctypes.data, v.size)
+
+
+def step_time(tr, b6) -> float:
+    q = _problem(tr)
+    b = np.ascontiguousarray(b6, dtype=np.uint64)
+    assert b.shape == (6,)
+    return lib().orc_step_time(C.byref(q.c), b.ctypes.data)
+
+
+@dataclass
+class Score:
+    cost: float
+    excess: int          # max overshoot of the capacity (pages), bit 31: bits on dead pages
+    step_bytes: np.ndarray   # [L][N][6] = hr, er, hw, ew, mi, mo
+    step_t: np.ndarray       # [L][N]
+    occ: np.ndarray          # [N]
+
+    @property
+    def feasible(self):
+        return (self.excess & 0x7FFFFFFF) == 0
+
+
+def score(tr, X) -> Score:
+    q = _problem(tr)
+    X = _u8(X, q.shape)
+    ex = C.c_uint32(0)
+    sb = np.zeros((q.L, q.N, 6), dtype=np.uint64)
+    st = np.zeros((q.L, q.N), dtype=np.float64)
+    occ = np.zeros(q.N, dtype=np.uint32)
+    T = lib().orc_score(C.byref(q.c), X.ctypes.data, C.byref(ex), sb.ctypes.data, st.ctypes.data,
+                        occ.ctypes.data)
+    return Score(T, ex.value, sb, st, occ)
+
+
+def cost(tr, X) -> float:
+    q = _problem(tr)
+    X = _u8(X, q.shape)
+    return lib().orc_score(C.byref(q.c), X.ctypes.data, None, None, None, None)
+
+
+def philox4x32_10(ctr, key):
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().orc_philox4x32_10(c.ctypes.data, k.ctypes.data, out.ctypes.data)
+    return out
+
+
+def _move(m) -> _Move:
+    mv = _Move()
+    for k in ("op", "layer", "page", "n1", "len", "layer2", "page2", "dsel"):
+        setattr(mv, k, int(m[k]))
+    return mv
+
+
+def delta(tr, X, move):
+    """(verdict, dT, base, f1, f2) of one raw move, the slow way."""
+    q = _problem(tr)
+    X = _u8(X, q.shape)
+    d = C.c_double(0.0)
+    base = C.c_int(0)
+    f1 = np.zeros(q.N, dtype=np.uint8)
+    f2 = np.zeros(q.N, dtype=np.uint8)
+    v = lib().orc_delta(C.byref(q.c), X.ctypes.data, C.byref(_move(move)), C.byref(d), C.byref(base),
+                        f1.ctypes.data, f2.ctypes.data)
+    return v, d.value, base.value, f1, f2
+
+
+def apply_move(tr, X, move):
+    """Schedule after the move (a copy), and the verdict."""
+    q = _problem(tr)
+    v, _, _, f1, f2 = delta(q, X, move)
+    Y = np.array(X, dtype=np.uint8, copy=True)
+    if v != 2:
+        Y[int(move["layer"]), :, int(move["page"])] ^= f1
+        Y[int(move["layer2"]), :, int(move["page2"])] ^= f2
+    return Y, v
+
+
+def init_static_frequency(tr) -> np.ndarray:
+    q = _problem(tr)
+    X = np.zeros(q.shape, dtype=np.uint8)
+    lib().orc_init_static_frequency(C.byref(q.c), X.ctypes.data)
+    return X
+
+
+def init_recency(tr) -> np.ndarray:
+    q = _problem(tr)
+    X = np.zeros(q.shape, dtype=np.uint8)
+    lib().orc_init_recency(C.byref(q.c), X.ctypes.data)
+    return X
+
+
+def brute_force(tr):
+    """(optimal cost, an optimal schedule, number of feasible schedules)."""
+    q = _problem(tr)
+    X = np.zeros(q.shape, dtype=np.uint8)
+    best = C.c_double(0.0)
+    nf = C.c_uint64(0)
+    rc = lib().orc_bruteforce(C.byref(q.c), C.byref(best), X.ctypes.data, C.byref(nf))
+    if rc != 0:
+        raise ValueError("instance too large for exhaustive search")
+    return best.value, X, nf.value
+
+
+@dataclass
+class ChainResult:
+    chain: int
+    X: np.ndarray
+    best_X: np.ndarray
+    best_cost: float      # exact re-score of best_X
+    T_cur: float
+    T_best: float         # running value (accumulated deltas)
+    C0: float
+    accepted: int
+    uphill: int
+    null_moves: int
+    clipped: int
+    improved: int
+    state: object = None
+
+
+def anneal_chain(tr, chain, X0, *, seed, total_moves, move_begin=0, move_end=None, n_levels=100,
+                 max_len=63, p0=0.8, alpha=0.9, op_prob=(0.4, 0.4, 0.2), resume=None) -> ChainResult:
+    q = _problem(tr)
+    sp = _SAParams()
+    sp.seed, sp.total_moves = int(seed), int(total_moves)
+    sp.move_begin = int(move_begin)
+    sp.move_end = int(total_moves if move_end is None else move_end)
+    sp.n_levels, sp.max_len, sp.p0, sp.alpha = int(n_levels), int(max_len), float(p0), float(alpha)
+    for i in range(3):
+        sp.op_prob[i] = float(op_prob[i])
+    if resume is None:
+        X = np.array(_u8(X0, q.shape), copy=True)
+        best = np.zeros(q.shape, dtype=np.uint8)
+        st = _SAState()
+    else:
+        X, best, st = resume.X.copy(), resume.best_X.copy(), resume.state
+    rc = lib().orc_anneal_chain(C.byref(q.c), C.byref(sp), int(chain), X.ctypes.data, best.ctypes.data,
+                                C.byref(st))
+    if rc != 0:
+        raise ValueError(f"orc_anneal_chain failed ({rc}): bad parameters or infeasible start")
+    return ChainResult(int(chain), X, best, cost(q, best), st.T_cur, st.T_best, st.C0, st.accepted,
+                       st.uphill, st.null_moves, st.clipped, st.improved, st)
+
+
+def anneal(tr, chains, X0, threads: int = 1, **kw):
+    """Run several chains (ids in `chains`); X0 is one schedule for all or a
+    list with one per chain.  Returns the list of ChainResult and the index of
+    the best (lowest exact cost, ties to the lowest chain id)."""
+    q = _problem(tr)
+    chains = list(chains)
+    X0s = X0 if isinstance(X0, (list, tuple)) else [X0] * len(chains)
+    if threads > 1:
+        with ThreadPoolExecutor(threads) as ex:
+            res = list(ex.map(lambda a: anneal_chain(q, a[0], a[1], **kw), zip(chains, X0s)))
+    else:
+        res = [anneal_chain(q, c, x, **kw) for c, x in zip(chains, X0s)]
+    best = min(range(len(res)), key=lambda i: (res[i].best_cost, res[i].chain))
+    return res, best

@@ -1,0 +1,558 @@
+/*
+ * CPU oracle for the KV-cache placement problem of "Accelerating LLM Inference
+ * via Dynamic KV Cache Placement in Heterogeneous Memory System" (Sec. III).
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, single-threaded, slow on purpose.  It works
+ * on one byte per (layer, step, page) boolean and shares no code, table or
+ * header with the GPU library; only the tests, the smoke check and the
+ * benchmark's cpu_baseline leg may call it.
+ *
+ * Part (i), the objective, is the definition of Eqs. 1-5 written out.
+ * Part (ii), the annealer, takes the Metropolis / cooling skeleton of
+ * Sec. III-B step by step; its move set on the placement schedule itself is
+ * this project's own design (the paper anneals two policy scalars), so its
+ * effectiveness is "parity unpinned" by the paper: it is pinned only by
+ * exhaustive search on tiny instances and by its invariants.
+ *
+ * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+    int32_t L, N, P, K;
+    const uint8_t *access;   /* [L][N][K][P] page p is read by plane k at step (n,l) */
+    const uint8_t *alive;    /* [N][P] page holds data at step n                    */
+    const uint8_t *persist;  /* [N][P] same data as at step n-1                     */
+    const uint8_t *written;  /* [N][P] page receives the token generated at step n  */
+    uint64_t plane_bytes[8]; /* bytes read per accessed page of plane k             */
+    uint64_t page_bytes;     /* bytes moved when a page changes tier                */
+    uint64_t token_bytes;    /* bytes of new KV written per written page and layer  */
+    double bw_hbm, bw_link, bw_dram;   /* B_h, B_k, B_d in bytes/s                  */
+    uint64_t cap_pages;      /* HBM pool, pages, shared by all layers               */
+} orc_problem;
+
+typedef struct { uint32_t op, layer, page, n1, len, layer2, page2, dsel; } orc_move;
+
+enum { ORC_SET = 0, ORC_SWAP = 1, ORC_SHIFT = 2 };
+enum { ORC_OK = 0, ORC_CLIPPED = 1, ORC_NULL = 2 };
+#define ORC_MAX_LEN 63
+#define ORC_WIN 64
+
+/* ---- indexing helpers ---------------------------------------------------- */
+static inline size_t ix_x(const orc_problem *q, int l, int n, int p) {
+    return ((size_t)l * q->N + n) * q->P + p;
+}
+static inline int a_bit(const orc_problem *q, int l, int n, int k, int p) {
+    return q->access[(((size_t)l * q->N + n) * q->K + k) * q->P + p] != 0;
+}
+static inline int v_bit(const orc_problem *q, int n, int p) { return q->alive[(size_t)n * q->P + p] != 0; }
+static inline int pm_bit(const orc_problem *q, int n, int p) { return q->persist[(size_t)n * q->P + p] != 0; }
+static inline int wm_bit(const orc_problem *q, int n, int p) { return q->written[(size_t)n * q->P + p] != 0; }
+/* a page is in HBM at step (n,l) iff its bit is set and the page exists */
+static inline int x_bit(const orc_problem *q, const uint8_t *X, int l, int n, int p) {
+    return X[ix_x(q, l, n, p)] != 0 && v_bit(q, n, p);
+}
+
+/* ---- canonical sum (order of Eq. 1) --------------------------------------
+ * Pad to a multiple of 64 with +0.0; inside each block of 64 fold the upper
+ * half onto the lower half (32, 16, ..., 1); add the block sums in order. */
+double orc_csum(const double *v, size_t m) {
+    double total = 0.0;
+    for (size_t b = 0; b < m; b += 64) {
+        double blk[64];
+        for (int i = 0; i < 64; i++) blk[i] = (b + i < m) ? v[b + i] : 0.0;
+        for (int h = 32; h >= 1; h >>= 1)
+            for (int i = 0; i < h; i++) blk[i] = blk[i] + blk[i + h];
+        total = (b == 0) ? blk[0] : total + blk[0];
+    }
+    return total;
+}
+
+/* ---- per-step data volumes (Sec. III-A, the sets of Eqs. 3-4) ------------
+ * out = {|H^r|, |E^r|, |H^w|, |E^w|, |M^i|, |M^o|} in bytes for step (n,l).
+ * Reads and the new token's write see the placement of this step; the change
+ * from the previous step's placement of the same layer is this step's
+ * migration.  Pages that did not hold the same data one step earlier (n = 0,
+ * a page just born, a slot re-used by a new sequence) migrate nothing. */
+void orc_step_bytes(const orc_problem *q, const uint8_t *X, int l, int n, uint64_t out[6]) {
+    uint64_t hr = 0, er = 0, hw = 0, ew = 0, mi = 0, mo = 0;
+    for (int p = 0; p < q->P; p++) {
+        int x = x_bit(q, X, l, n, p);
+        for (int k = 0; k < q->K; k++)
+            if (a_bit(q, l, n, k, p)) { if (x) hr += q->plane_bytes[k]; else er += q->plane_bytes[k]; }
+        if (wm_bit(q, n, p)) { if (x) hw += q->token_bytes; else ew += q->token_bytes; }
+        if (n > 0 && pm_bit(q, n, p)) {
+            int xp = x_bit(q, X, l, n - 1, p);
+            if (x && !xp) mi += q->page_bytes;
+            if (!x && xp) mo += q->page_bytes;
+        }
+    }
+    out[0] = hr; out[1] = er; out[2] = hw; out[3] = ew; out[4] = mi; out[5] = mo;
+}
+
+static inline double dmax(double a, double b) { return a > b ? a : b; }
+
+/* ---- step latency (Eqs. 2-4) ----------------------------------------------
+ * Divisions are written as products with reciprocals formed once in fp64. */
+double orc_step_time(const orc_problem *q, const uint64_t b[6]) {
+    double inv_bh = 1.0 / q->bw_hbm, inv_bk = 1.0 / q->bw_link, inv_bd = 1.0 / q->bw_dram;
+    double inv_min = 1.0 / (q->bw_link < q->bw_dram ? q->bw_link : q->bw_dram);
+    uint64_t hr = b[0], er = b[1], hw = b[2], ew = b[3], mi = b[4], mo = b[5];
+    double t_h = (double)(hr + hw + mi + mo) * inv_bh;                         /* Eq. 3 */
+    double link_out = (double)(ew + mo) * inv_bk;
+    double link_in = (double)mi * inv_bk;
+    double chan = (double)(ew + mi + mo) * inv_bd;
+    double t_e = (double)er * inv_min + dmax(dmax(link_out, link_in), chan);   /* Eq. 4 */
+    return dmax(t_h, t_e);                                                     /* Eq. 2 */
+}
+
+static double step_time_at(const orc_problem *q, const uint8_t *X, int l, int n) {
+    uint64_t b[6];
+    orc_step_bytes(q, X, l, n, b);
+    return orc_step_time(q, b);
+}
+
+/* occupancy of the HBM pool while token step n runs (Eq. 5, per token step) */
+void orc_occupancy(const orc_problem *q, const uint8_t *X, uint32_t *occ) {
+    for (int n = 0; n < q->N; n++) {
+        uint32_t c = 0;
+        for (int l = 0; l < q->L; l++)
+            for (int p = 0; p < q->P; p++) c += (uint32_t)x_bit(q, X, l, n, p);
+        occ[n] = c;
+    }
+}
+
+/* ---- total latency and feasibility (Eqs. 1, 5) ---------------------------
+ * Steps are summed in execution order g = n*L + l.  excess = largest overshoot
+ * of the capacity over all token steps (0: feasible); bit 31 flags bits set on
+ * pages that do not exist (they are ignored).  Optional outputs:
+ * step_bytes [L][N][6], step_t [L][N], occ [N]. */
+double orc_score(const orc_problem *q, const uint8_t *X, uint32_t *excess,
+                 uint64_t *step_bytes, double *step_t, uint32_t *occ_out) {
+    int L = q->L, N = q->N;
+    double *t = (double *)malloc(sizeof(double) * (size_t)L * N);
+    uint32_t *occ = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N);
+    for (int n = 0; n < N; n++)
+        for (int l = 0; l < L; l++) {
+            uint64_t b[6];
+            orc_step_bytes(q, X, l, n, b);
+            double tt = orc_step_time(q, b);
+            t[(size_t)n * L + l] = tt;
+            if (step_bytes) memcpy(step_bytes + ((size_t)l * N + n) * 6, b, sizeof b);
+            if (step_t) step_t[(size_t)l * N + n] = tt;
+        }
+    double T = orc_csum(t, (size_t)L * N);
+    orc_occupancy(q, X, occ);
+    uint64_t ex = 0;
+    for (int n = 0; n < N; n++)
+        if ((uint64_t)occ[n] > q->cap_pages && occ[n] - q->cap_pages > ex) ex = occ[n] - q->cap_pages;
+    uint32_t flag = 0;
+    for (int l = 0; l < L && !flag; l++)
+        for (int n = 0; n < N && !flag; n++)
+            for (int p = 0; p < q->P; p++)
+                if (X[ix_x(q, l, n, p)] && !v_bit(q, n, p)) { flag = 0x80000000u; break; }
+    if (excess) *excess = (uint32_t)ex | flag;
+    if (occ_out) memcpy(occ_out, occ, sizeof(uint32_t) * (size_t)N);
+    free(t); free(occ);
+    return T;
+}
+
+/* ---- Philox4x32-10 (Salmon, Moraes, Dror, Shaw; SC'11) ------------------- */
+void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; r++) {
+        uint64_t m0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t m1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(m1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)m1;
+        uint32_t n2 = (uint32_t)(m0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)m0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* ---- moves -----------------------------------------------------------------
+ * A move edits the timeline of one (layer, page) bit, and for SWAP also of a
+ * victim (layer2, page2).  orc_resolve turns the raw record into per-step flip
+ * flags f1 (for layer,page) and f2 (for layer2,page2), both of length N, and
+ * the first step `base` of the 64-step window over which the cost change is
+ * summed.  `occ` is the occupancy of the current schedule, which must be
+ * feasible.  No move ever raises a step's occupancy above the capacity.
+ *
+ *  span   steps n1 <= n < e, e = first n > n1 with n-n1 == len, n == N, or the
+ *         page not persisting into n.  The page must exist at n1.
+ *  SET    target value v = not(bit at n1).  Ascending over the span, give the
+ *         bit value v; when v = 1 stop at the first step that is full and whose
+ *         bit is clear.
+ *  SWAP   if the bit at n1 is set: as SET (v = 0).  Otherwise, at every step of
+ *         the span whose bit is clear: set it if the step is below capacity;
+ *         else, if the victim's bit is set there, clear the victim and set it;
+ *         else leave the step alone.
+ *  SHIFT  first step nt in (n1, n1+len] (while the page persists) whose bit
+ *         differs from the step before.  With a = bit before nt and d in
+ *         {-2,-1,+1,+2}: d < 0 moves the transition earlier (steps nt-1 down to
+ *         max(nt+d, n1) take the value not(a)), d > 0 later (steps nt up to
+ *         nt+d-1, while the page persists, take a); setting stops at a full
+ *         step.  base = nt - 2.
+ */
+static const int SHIFT_D[4] = {-2, -1, 1, 2};
+
+int orc_resolve(const orc_problem *q, const uint8_t *X, const uint32_t *occ, const orc_move *m,
+                uint8_t *f1, uint8_t *f2, int *base) {
+    int L = q->L, N = q->N, P = q->P;
+    memset(f1, 0, (size_t)N); memset(f2, 0, (size_t)N);
+    *base = 0;
+    if (m->op > 2 || m->layer >= (uint32_t)L || m->page >= (uint32_t)P || m->n1 >= (uint32_t)N ||
+        m->len < 1 || m->len > ORC_MAX_LEN || m->layer2 >= (uint32_t)L || m->page2 >= (uint32_t)P)
+        return ORC_NULL;
+    int l = (int)m->layer, p = (int)m->page, n1 = (int)m->n1, len = (int)m->len;
+    int l2 = (int)m->layer2, pq = (int)m->page2;
+    uint64_t cap = q->cap_pages;
+    *base = n1;
+    if (!v_bit(q, n1, p)) return ORC_NULL;
+    int e = n1 + 1;
+    while (e < N && e - n1 < len && pm_bit(q, e, p)) e++;
+    int clipped = 0, flips = 0;
+    int x1 = x_bit(q, X, l, n1, p);
+    if (m->op == ORC_SET || (m->op == ORC_SWAP && x1)) {
+        int v = !x1;
+        for (int n = n1; n < e; n++) {
+            if (x_bit(q, X, l, n, p) == v) continue;
+            if (v && (uint64_t)occ[n] >= cap) { clipped = 1; break; }
+            f1[n] = 1; flips++;
+        }
+    } else if (m->op == ORC_SWAP) {
+        int victim_ok = !(l2 == l && pq == p);
+        for (int n = n1; n < e; n++) {
+            if (x_bit(q, X, l, n, p)) continue;
+            if ((uint64_t)occ[n] < cap) { f1[n] = 1; flips++; }
+            else if (victim_ok && x_bit(q, X, l2, n, pq)) { f1[n] = 1; f2[n] = 1; flips++; }
+            else clipped = 1;
+        }
+    } else { /* SHIFT */
+        int nt = -1;
+        for (int n = n1 + 1; n < N && n - n1 <= len && pm_bit(q, n, p); n++)
+            if (x_bit(q, X, l, n, p) != x_bit(q, X, l, n - 1, p)) { nt = n; break; }
+        if (nt < 0) return ORC_NULL;
+        int a = x_bit(q, X, l, nt - 1, p);
+        int d = SHIFT_D[m->dsel & 3];
+        *base = nt - 2;
+        if (d < 0) {
+            int lo = nt + d > n1 ? nt + d : n1;
+            for (int n = nt - 1; n >= lo; n--) {          /* these steps hold a, give them not(a) */
+                if (!a && (uint64_t)occ[n] >= cap) { clipped = 1; break; }
+                f1[n] = 1; flips++;
+            }
+        } else {
+            for (int n = nt; n < nt + d && n < N && (n == nt || pm_bit(q, n, p)); n++) {
+                if (x_bit(q, X, l, n, p) == a) continue;
+                if (a && (uint64_t)occ[n] >= cap) { clipped = 1; break; }
+                f1[n] = 1; flips++;
+            }
+        }
+    }
+    if (!flips) return ORC_NULL;
+    return clipped ? ORC_CLIPPED : ORC_OK;
+}
+
+static void apply_flips(const orc_problem *q, uint8_t *X, uint32_t *occ, const orc_move *m,
+                        const uint8_t *f1, const uint8_t *f2, int lo, int hi) {
+    for (int n = lo; n < hi; n++) {
+        if (f1[n]) {
+            size_t i = ix_x(q, (int)m->layer, n, (int)m->page);
+            int was = x_bit(q, X, (int)m->layer, n, (int)m->page);
+            X[i] = (uint8_t)!was;
+            if (occ) occ[n] += was ? (uint32_t)-1 : 1u;
+        }
+        if (f2[n]) {
+            size_t i = ix_x(q, (int)m->layer2, n, (int)m->page2);
+            int was = x_bit(q, X, (int)m->layer2, n, (int)m->page2);
+            X[i] = (uint8_t)!was;
+            if (occ) occ[n] += was ? (uint32_t)-1 : 1u;
+        }
+    }
+}
+
+static int has_second_layer(const orc_problem *q, const orc_move *m, const uint8_t *f2) {
+    if (m->layer2 == m->layer) return 0;
+    for (int n = 0; n < q->N; n++) if (f2[n]) return 1;
+    return 0;
+}
+
+/* ---- cost change of a move, the slow way -----------------------------------
+ * dT = csum over the 64-step window [base, base+64) of (t' - t) on the move's
+ * layer, plus the same on layer2 when the victim lives on another layer.  Both
+ * schedules are scored in full here; steps the move does not touch contribute
+ * an exact 0.0.  Returns the verdict; *delta = 0 for a null move. */
+int orc_delta(const orc_problem *q, const uint8_t *X, const orc_move *m, double *delta, int *base_out,
+              uint8_t *f1_out, uint8_t *f2_out) {
+    int L = q->L, N = q->N;
+    size_t sz = (size_t)L * N * q->P;
+    uint32_t *occ = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N);
+    uint8_t *f1 = (uint8_t *)malloc((size_t)N), *f2 = (uint8_t *)malloc((size_t)N);
+    orc_occupancy(q, X, occ);
+    int base;
+    int verdict = orc_resolve(q, X, occ, m, f1, f2, &base);
+    *delta = 0.0;
+    if (verdict != ORC_NULL) {
+        uint8_t *Y = (uint8_t *)malloc(sz);
+        memcpy(Y, X, sz);
+        apply_flips(q, Y, NULL, m, f1, f2, 0, N);
+        double *t0 = (double *)malloc(sizeof(double) * (size_t)L * N);
+        double *t1 = (double *)malloc(sizeof(double) * (size_t)L * N);
+        orc_score(q, X, NULL, NULL, t0, NULL);
+        orc_score(q, Y, NULL, NULL, t1, NULL);
+        double d[ORC_WIN];
+        int l = (int)m->layer;
+        for (int i = 0; i < ORC_WIN; i++) {
+            int n = base + i;
+            d[i] = (n >= 0 && n < N) ? t1[(size_t)l * N + n] - t0[(size_t)l * N + n] : 0.0;
+        }
+        double dT = orc_csum(d, ORC_WIN);
+        if (has_second_layer(q, m, f2)) {
+            int l2 = (int)m->layer2;
+            for (int i = 0; i < ORC_WIN; i++) {
+                int n = base + i;
+                d[i] = (n >= 0 && n < N) ? t1[(size_t)l2 * N + n] - t0[(size_t)l2 * N + n] : 0.0;
+            }
+            dT = dT + orc_csum(d, ORC_WIN);
+        }
+        *delta = dT;
+        free(Y); free(t0); free(t1);
+    }
+    if (base_out) *base_out = base;
+    if (f1_out) memcpy(f1_out, f1, (size_t)N);
+    if (f2_out) memcpy(f2_out, f2, (size_t)N);
+    free(occ); free(f1); free(f2);
+    return verdict;
+}
+
+/* ---- starting schedules (the paper's non-migrating and reactive baselines,
+ * Sec. IV-A, restated for a pool shared by all layers) ---------------------- */
+
+typedef struct { int64_t key; size_t idx; } rank_item;
+/* larger key first; equal keys: lower index first */
+static int rank_cmp(const void *a, const void *b) {
+    const rank_item *x = (const rank_item *)a, *y = (const rank_item *)b;
+    if (x->key != y->key) return x->key > y->key ? -1 : 1;
+    return x->idx < y->idx ? -1 : (x->idx > y->idx);
+}
+
+/* Static by frequency: the cap_pages (layer,page) pairs read most often over the
+ * whole trace stay in HBM whenever they exist; nothing ever migrates.
+ * Ties go to the lower l*P+p. */
+void orc_init_static_frequency(const orc_problem *q, uint8_t *X) {
+    int L = q->L, N = q->N, P = q->P;
+    size_t M = (size_t)L * P;
+    rank_item *it = (rank_item *)malloc(M * sizeof(rank_item));
+    uint8_t *chosen = (uint8_t *)calloc(M, 1);
+    for (size_t i = 0; i < M; i++) { it[i].key = 0; it[i].idx = i; }
+    for (int l = 0; l < L; l++)
+        for (int n = 0; n < N; n++)
+            for (int k = 0; k < q->K; k++)
+                for (int p = 0; p < P; p++) it[(size_t)l * P + p].key += a_bit(q, l, n, k, p);
+    qsort(it, M, sizeof(rank_item), rank_cmp);
+    for (size_t c = 0; c < M && (uint64_t)c < q->cap_pages; c++) chosen[it[c].idx] = 1;
+    for (int l = 0; l < L; l++)
+        for (int n = 0; n < N; n++)
+            for (int p = 0; p < P; p++)
+                X[ix_x(q, l, n, p)] = (uint8_t)(chosen[(size_t)l * P + p] && v_bit(q, n, p));
+    free(it); free(chosen);
+}
+
+/* Recency: at step n the pool holds the cap_pages existing (layer,page) pairs
+ * read most recently before n (never read: oldest).  Ties go to the lower
+ * l*P+p.  A page that stops persisting forgets its history. */
+void orc_init_recency(const orc_problem *q, uint8_t *X) {
+    int L = q->L, N = q->N, P = q->P;
+    size_t M = (size_t)L * P;
+    int32_t *last = (int32_t *)malloc(M * sizeof(int32_t));
+    rank_item *it = (rank_item *)malloc(M * sizeof(rank_item));
+    for (size_t i = 0; i < M; i++) last[i] = -1;
+    for (int n = 0; n < N; n++) {
+        if (n > 0)
+            for (int l = 0; l < L; l++)
+                for (int p = 0; p < P; p++) {
+                    size_t i = (size_t)l * P + p;
+                    if (!pm_bit(q, n, p)) { last[i] = -1; continue; }
+                    for (int k = 0; k < q->K; k++)
+                        if (a_bit(q, l, n - 1, k, p)) last[i] = n - 1;
+                }
+        size_t cnt = 0;
+        for (size_t i = 0; i < M; i++)
+            if (v_bit(q, n, (int)(i % (size_t)P))) { it[cnt].key = last[i]; it[cnt].idx = i; cnt++; }
+        qsort(it, cnt, sizeof(rank_item), rank_cmp);
+        for (int l = 0; l < L; l++)
+            for (int p = 0; p < P; p++) X[ix_x(q, l, n, p)] = 0;
+        for (size_t c = 0; c < cnt && (uint64_t)c < q->cap_pages; c++) {
+            size_t i = it[c].idx;
+            X[ix_x(q, (int)(i / (size_t)P), n, (int)(i % (size_t)P))] = 1;
+        }
+    }
+    free(last); free(it);
+}
+
+/* ---- exhaustive optimum (tiny instances only) ------------------------------
+ * Enumerates every assignment of the existing (layer, step, page) bits; returns
+ * the cheapest capacity-feasible schedule (first one found on ties). */
+int orc_bruteforce(const orc_problem *q, double *best_cost, uint8_t *best_X, uint64_t *n_feasible) {
+    int L = q->L, N = q->N, P = q->P;
+    size_t sz = (size_t)L * N * P, pos[32];
+    int m = 0;
+    for (int l = 0; l < L; l++)
+        for (int n = 0; n < N; n++)
+            for (int p = 0; p < P; p++)
+                if (v_bit(q, n, p)) { if (m >= 26) return -1; pos[m++] = ix_x(q, l, n, p); }
+    uint8_t *X = (uint8_t *)calloc(sz ? sz : 1, 1);
+    double best = INFINITY; uint64_t feas = 0;
+    for (uint64_t code = 0; code < (1ull << m); code++) {
+        for (int i = 0; i < m; i++) X[pos[i]] = (uint8_t)((code >> i) & 1);
+        uint32_t ex;
+        double T = orc_score(q, X, &ex, NULL, NULL, NULL);
+        if (ex != 0) continue;
+        feas++;
+        if (T < best) { best = T; if (best_X) memcpy(best_X, X, sz); }
+    }
+    *best_cost = best; *n_feasible = feas;
+    free(X);
+    return 0;
+}
+
+/* ---- simulated annealing over the schedule (Sec. III-B skeleton) ---------- */
+typedef struct {
+    uint64_t seed;
+    uint64_t total_moves;     /* length of the whole cooling schedule          */
+    uint64_t move_begin, move_end;   /* this call runs moves [begin, end)      */
+    uint32_t n_levels;        /* temperature levels, equal length              */
+    uint32_t max_len;         /* longest span of a move, 1..63                  */
+    double p0, alpha;         /* initial acceptance of uphill moves; cooling    */
+    double op_prob[3];        /* SET, SWAP, SHIFT                               */
+} orc_sa_params;
+
+typedef struct {
+    double T_cur, T_best, C0, C;
+    uint32_t level;
+    uint64_t accepted, uphill, null_moves, clipped, improved, uphill_seen;
+} orc_sa_state;
+
+#define ORC_CALIB 256
+
+static void draw_move(const orc_problem *q, const orc_sa_params *sp, uint32_t chain, uint64_t mi,
+                      uint32_t stream0, orc_move *m, double *u) {
+    uint32_t key[2] = {(uint32_t)sp->seed, (uint32_t)(sp->seed >> 32)};
+    uint32_t ctr[4] = {(uint32_t)mi, (uint32_t)(mi >> 32), chain, stream0};
+    uint32_t a[4], b[4], c[4];
+    orc_philox4x32_10(ctr, key, a);
+    ctr[3] = stream0 + 1; orc_philox4x32_10(ctr, key, b);
+    ctr[3] = stream0 + 2; orc_philox4x32_10(ctr, key, c);
+    uint64_t th0 = (uint64_t)(sp->op_prob[0] * 4294967296.0);
+    uint64_t th1 = (uint64_t)((sp->op_prob[0] + sp->op_prob[1]) * 4294967296.0);
+    m->op = (a[0] < th0) ? ORC_SET : (a[0] < th1) ? ORC_SWAP : ORC_SHIFT;
+    m->layer = (uint32_t)(((uint64_t)a[1] * (uint32_t)q->L) >> 32);
+    m->page = (uint32_t)(((uint64_t)a[2] * (uint32_t)q->P) >> 32);
+    m->n1 = (uint32_t)(((uint64_t)a[3] * (uint32_t)q->N) >> 32);
+    m->len = 1 + (uint32_t)(((uint64_t)b[0] * sp->max_len) >> 32);
+    m->layer2 = (uint32_t)(((uint64_t)b[1] * (uint32_t)q->L) >> 32);
+    m->page2 = (uint32_t)(((uint64_t)b[2] * (uint32_t)q->P) >> 32);
+    m->dsel = b[3] >> 30;
+    uint64_t bits = ((uint64_t)c[0] << 20) | (c[1] >> 12);        /* 52 random bits */
+    *u = ((double)bits + 0.5) * (1.0 / 4503599627370496.0);       /* (bits + 1/2) 2^-52 */
+}
+
+/* cost change over the window, recomputing only the rows of the move's
+ * layer(s) inside the window; X is left modified iff `keep`. */
+static double window_delta(const orc_problem *q, uint8_t *X, const orc_move *m, const uint8_t *f1,
+                           const uint8_t *f2, int base, const double *tcur, double *tnew1, double *tnew2,
+                           int *second) {
+    int N = q->N;
+    int lo = base < 0 ? 0 : base, hi = base + ORC_WIN < N ? base + ORC_WIN : N;
+    apply_flips(q, X, NULL, m, f1, f2, lo, hi);
+    double d[ORC_WIN];
+    int l = (int)m->layer, l2 = (int)m->layer2;
+    for (int i = 0; i < ORC_WIN; i++) {
+        int n = base + i;
+        if (n < 0 || n >= N) { d[i] = 0.0; continue; }
+        tnew1[i] = step_time_at(q, X, l, n);
+        d[i] = tnew1[i] - tcur[(size_t)l * N + n];
+    }
+    double dT = orc_csum(d, ORC_WIN);
+    *second = has_second_layer(q, m, f2);
+    if (*second) {
+        for (int i = 0; i < ORC_WIN; i++) {
+            int n = base + i;
+            if (n < 0 || n >= N) { d[i] = 0.0; continue; }
+            tnew2[i] = step_time_at(q, X, l2, n);
+            d[i] = tnew2[i] - tcur[(size_t)l2 * N + n];
+        }
+        dT = dT + orc_csum(d, ORC_WIN);
+    }
+    apply_flips(q, X, NULL, m, f1, f2, lo, hi);   /* undo */
+    return dT;
+}
+
+/* One chain.  X: current schedule (in/out, must be feasible).  best_X: best
+ * schedule seen (in/out when resuming: st->T_best must match it).  On the first
+ * call (move_begin == 0) the state is initialised and the temperature calibrated
+ * from 256 proposals that are not applied: C0 = mean(dT | dT > 0) / (-ln p0). */
+int orc_anneal_chain(const orc_problem *q, const orc_sa_params *sp, uint32_t chain, uint8_t *X,
+                     uint8_t *best_X, orc_sa_state *st) {
+    int L = q->L, N = q->N;
+    size_t sz = (size_t)L * N * q->P;
+    if (sp->max_len < 1 || sp->max_len > ORC_MAX_LEN || sp->n_levels < 1) return -1;
+    double *tcur = (double *)malloc(sizeof(double) * (size_t)L * N);
+    uint32_t *occ = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N);
+    uint8_t *f1 = (uint8_t *)malloc((size_t)N), *f2 = (uint8_t *)malloc((size_t)N);
+    double tn1[ORC_WIN], tn2[ORC_WIN];
+    uint32_t ex;
+    double T0 = orc_score(q, X, &ex, NULL, tcur, occ);
+    if (ex != 0) { free(tcur); free(occ); free(f1); free(f2); return -2; }
+    uint64_t mpl = sp->total_moves / sp->n_levels; if (mpl < 1) mpl = 1;
+
+    if (sp->move_begin == 0) {
+        memset(st, 0, sizeof *st);
+        st->T_cur = T0; st->T_best = T0;
+        memcpy(best_X, X, sz);
+        double sum = 0.0; uint32_t cnt = 0;
+        for (uint64_t j = 0; j < ORC_CALIB; j++) {
+            orc_move m; double u; int base, second;
+            draw_move(q, sp, chain, j, 8, &m, &u);
+            if (orc_resolve(q, X, occ, &m, f1, f2, &base) == ORC_NULL) continue;
+            double dT = window_delta(q, X, &m, f1, f2, base, tcur, tn1, tn2, &second);
+            if (dT > 0.0) { sum = sum + dT; cnt++; }
+        }
+        st->C0 = cnt ? (sum / (double)cnt) / (-log(sp->p0)) : 0.0;
+        st->C = st->C0; st->level = 0;
+    }
+
+    for (uint64_t mi = sp->move_begin; mi < sp->move_end; mi++) {
+        uint64_t lvl = mi / mpl; if (lvl > sp->n_levels - 1) lvl = sp->n_levels - 1;
+        while (st->level < lvl) { st->C = st->C * sp->alpha; st->level++; }
+        orc_move m; double u; int base, second;
+        draw_move(q, sp, chain, mi, 0, &m, &u);
+        int verdict = orc_resolve(q, X, occ, &m, f1, f2, &base);
+        if (verdict == ORC_NULL) { st->null_moves++; continue; }
+        if (verdict == ORC_CLIPPED) st->clipped++;
+        double dT = window_delta(q, X, &m, f1, f2, base, tcur, tn1, tn2, &second);
+        if (dT > 0.0) st->uphill_seen++;
+        int accept = (dT <= 0.0) || (st->C > 0.0 && u < exp(-dT / st->C));   /* Metropolis */
+        if (!accept) continue;
+        st->accepted++; if (dT > 0.0) st->uphill++;
+        int lo = base < 0 ? 0 : base, hi = base + ORC_WIN < N ? base + ORC_WIN : N;
+        apply_flips(q, X, occ, &m, f1, f2, lo, hi);
+        for (int i = 0; i < ORC_WIN; i++) {
+            int n = base + i;
+            if (n < 0 || n >= N) continue;
+            tcur[(size_t)m.layer * N + n] = tn1[i];
+            if (second) tcur[(size_t)m.layer2 * N + n] = tn2[i];
+        }
+        st->T_cur = st->T_cur + dT;
+        if (st->T_cur < st->T_best) { st->T_best = st->T_cur; st->improved++; memcpy(best_X, X, sz); }
+    }
+    free(tcur); free(occ); free(f1); free(f2);
+    return 0;
+}

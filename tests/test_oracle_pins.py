@@ -1,0 +1,398 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+Nothing here touches the GPU library.  Each test is chosen so that a plausible
+slip in the oracle (a dropped term of Eq. 3/4, a swapped bandwidth, a wrong
+neighbour in the migration term, a different summation tree) fails it.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle as O
+import workloads as W
+from workloads.traces import Trace
+
+
+def _frac(s):
+    a, b = s.split("/")
+    return Fraction(a) / Fraction(b)
+
+
+def _mini(L=1, N=1, P=1, K=1, bw=(4.9e12, 900e9, 500e9), cap=10**6, plane_bytes=None,
+          page_bytes=65536, token_bytes=4096):
+    z = lambda *s: np.zeros(s, np.uint8)
+    return Trace("mini", L, N, P, K, z(L, N, K, P), z(N, P), z(N, P), z(N, P),
+                 plane_bytes or [page_bytes // K] * K, page_bytes, token_bytes, bw[0], bw[1], bw[2], cap)
+
+
+# ---------------------------------------------------------------- Eqs. 2-4 --
+def test_step_time_hand_cases(golden_dir):
+    rows = 0
+    for line in open(os.path.join(golden_dir, "step_time_cases.txt")):
+        line = line.split("#")[0].split()
+        if not line:
+            continue
+        bh, bk, bd = map(float, line[:3])
+        b6 = list(map(int, line[3:9]))
+        want = float(_frac(line[9]))
+        got = O.step_time(_mini(bw=(bh, bk, bd)), b6)
+        # the oracle multiplies by a rounded reciprocal: two roundings
+        assert got == pytest.approx(want, rel=4e-16, abs=0.0), (line, got, want)
+        rows += 1
+    assert rows >= 12
+
+
+def test_step_time_is_max_of_tiers_and_monotone():
+    tr = _mini()
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        b = rng.integers(0, 1 << 24, 6).astype(np.uint64)
+        t = O.step_time(tr, b)
+        th = float(b[0] + b[2] + b[4] + b[5]) / tr.bw_hbm
+        assert t >= th * (1 - 1e-15)
+        for i in range(6):                      # more traffic of any kind never helps
+            b2 = b.copy(); b2[i] += 4096
+            assert O.step_time(tr, b2) >= t
+
+
+# ------------------------------------------------------------------- csum --
+def test_csum_tree_shape_by_hand():
+    B = 2.0 ** 53                                # B + 1 rounds back to B (ties to even)
+    v = np.zeros(64); v[0] = B; v[32] = 1.0; v[16] = -B
+    # fold 32: v0 = B+1 -> B ; fold 16: v0 = B + (-B) = 0.  A left-to-right sum gives 1.
+    assert O.csum(v) == 0.0
+    v = np.zeros(64); v[0] = B; v[1] = 1.0; v[33] = 1.0
+    # fold 32: v1 = 2 ; ... ; fold 1: v0 = B + 2 exactly.  Left-to-right: B+1 -> B, +1 -> B.
+    assert O.csum(v) == B + 2.0
+    v = np.zeros(64); v[0] = B; v[63] = 1.0; v[31] = 1.0
+    # fold 32: v31 = 2; it reaches v0 only at the last fold: B + 2
+    assert O.csum(v) == B + 2.0
+
+
+def test_csum_blocks_are_added_in_order_and_padded():
+    B = 2.0 ** 53
+    v = np.zeros(130); v[0] = B; v[64] = 1.0; v[128] = 1.0; v[129] = 1.0
+    # block sums B, 1, 2 ; (B + 1) -> B ; B + 2 exact
+    assert O.csum(v) == B + 2.0
+    v = np.zeros(130); v[0] = B; v[64] = 1.0; v[65] = 1.0; v[128] = 1.0
+    # block sums B, 2, 1 ; B + 2 exact ; (B+2) + 1 -> tie -> even mantissa = B + 4
+    assert O.csum(v) == B + 4.0
+    assert O.csum(np.zeros(0)) == 0.0
+    assert O.csum(np.array([3.25])) == 3.25
+
+
+def test_csum_close_to_exact_sum():
+    rng = np.random.default_rng(1)
+    for m in (1, 63, 64, 65, 1000, 8192):
+        v = rng.random(m) * 1e-6
+        assert O.csum(v) == pytest.approx(math.fsum(v), rel=1e-13)
+    v = rng.integers(0, 1000, 4096).astype(np.float64)      # integers: every order is exact
+    assert O.csum(v) == float(v.sum())
+
+
+# ------------------------------------------------------------------ Philox --
+def test_philox_known_answers(golden_dir):
+    n = 0
+    for line in open(os.path.join(golden_dir, "philox4x32_10_kat.txt")):
+        w = line.split("#")[0].split()
+        if not w:
+            continue
+        x = [int(t, 16) for t in w]
+        assert list(O.philox4x32_10(x[0:4], x[4:6])) == x[6:10]
+        n += 1
+    assert n == 3
+
+
+# ------------------------------------------------- the sets of Eqs. 3 and 4 --
+def _hand_instance():
+    tr = _mini(L=1, N=3, P=4, plane_bytes=[100], page_bytes=1000, token_bytes=10, cap=1,
+               bw=(1000.0, 100.0, 50.0))
+    tr.alive[:] = [[1, 1, 0, 0], [1, 1, 1, 0], [1, 0, 1, 1]]       # page 1 dies, pages 2, 3 are born
+    tr.persist[:] = [[0, 0, 0, 0], [1, 1, 0, 0], [1, 0, 1, 0]]
+    tr.written[:] = [[0, 1, 0, 0], [0, 0, 1, 0], [0, 0, 0, 1]]
+    tr.access[0, :, 0, :] = [[1, 1, 0, 0], [1, 0, 1, 0], [0, 0, 1, 1]]
+    X = np.array([[[1, 0, 0, 0], [0, 1, 1, 0], [1, 1, 0, 1]]], np.uint8)   # bit (n=2,p=1) is on a dead page
+    return tr, X
+
+
+def test_step_bytes_hand_instance():
+    tr, X = _hand_instance()
+    s = O.score(tr, X)
+    #                 hr   er   hw  ew   mi    mo
+    want = [[100, 100, 0, 10, 0, 0],          # n=0: no migration at the first step
+            [100, 100, 10, 0, 1000, 1000],    # p0 leaves, p1 enters, p2 is born in HBM for free
+            [100, 100, 10, 0, 1000, 1000]]    # p0 returns, p2 leaves, p3 born; dead bit ignored
+    assert s.step_bytes[0].tolist() == want
+    assert s.occ.tolist() == [1, 2, 2]
+    assert s.excess == (1 | 0x80000000)
+    # Eq. 3/4 by hand with B_h=1000, B_k=100, B_d=50:
+    t0 = max(100 / 1000, 100 / 50 + max(10 / 100, 0, 10 / 50))
+    t1 = max(2110 / 1000, 100 / 50 + max(1000 / 100, 1000 / 100, 2000 / 50))
+    assert s.step_t[0].tolist() == pytest.approx([t0, t1, t1], rel=1e-15)
+    assert s.cost == pytest.approx(t0 + 2 * t1, rel=1e-15)
+
+
+def test_total_is_summed_in_execution_order():
+    # Eq. 1 summed in the order the steps run, g = n*L + l.  With unit bandwidths
+    # a step's latency is its byte count, so t = [2^53, 1, 0, 1] in that order:
+    # the tree adds (t0 + t2) + (t1 + t3) = 2^53 + 2 exactly, while the layer-major
+    # order [2^53, 0, 1, 1] would give (2^53 + 1 -> 2^53) + 1 -> 2^53.
+    tr = _mini(L=2, N=2, P=1, K=2, bw=(1.0, 1.0, 1.0), plane_bytes=[2 ** 53, 1], token_bytes=0)
+    tr.alive[:] = 1
+    tr.access[0, 0, 0, 0] = 1
+    tr.access[1, 0, 1, 0] = 1
+    tr.access[1, 1, 1, 0] = 1
+    s = O.score(tr, np.zeros((2, 2, 1), np.uint8))
+    assert s.step_t.tolist() == [[2.0 ** 53, 0.0], [1.0, 1.0]]
+    assert s.cost == 2.0 ** 53 + 2.0
+
+
+# ------------------------------------------------------------ closed forms --
+@pytest.mark.parametrize("name,scale", [("tiny", 1.0), ("table1", 1.0), ("llama8b", 0.125),
+                                        ("serving", 0.06), ("gqa70b", 0.04)])
+def test_closed_forms_all_hbm_and_all_dram(name, scale):
+    tr = W.config(name, scale)
+    pb = np.array(tr.plane_bytes, dtype=np.int64)
+    acc_b = (tr.access.astype(np.int64).sum(axis=3) * pb[None, None, :]).sum(axis=2)   # [L][N]
+    wr_b = tr.written.astype(np.int64).sum(axis=1) * tr.token_bytes                     # [N]
+    allx = np.broadcast_to(tr.alive[None], (tr.L, tr.N, tr.P)).copy()
+    s = O.score(tr, allx)
+    # every page in HBM: nothing off-package, no migration: t = (reads + write)/B_h
+    want = math.fsum(((acc_b + wr_b[None]) / tr.bw_hbm).ravel())
+    assert s.cost == pytest.approx(want, rel=1e-13)
+    assert (s.step_bytes[..., 1] == 0).all() and (s.step_bytes[..., 3:] == 0).all()
+    assert s.occ.tolist() == (tr.L * tr.alive.sum(axis=1)).tolist()
+    # nothing in HBM: t = reads/min{B_k,B_d} + max(write/B_k, write/B_d)
+    e = O.score(tr, np.zeros_like(allx))
+    bmin = min(tr.bw_link, tr.bw_dram)
+    want = math.fsum((acc_b / bmin + wr_b[None] / bmin).ravel())
+    assert e.cost == pytest.approx(want, rel=1e-13)
+    assert e.excess == 0 and (e.occ == 0).all()
+    # any schedule: both tiers working flat out bound a step from below
+    lb = (acc_b + wr_b[None]) / (tr.bw_hbm + bmin)
+    for X in W.random_placements(tr, 3, seed=7):
+        r = O.score(tr, X)
+        assert (r.step_t >= lb * (1 - 1e-12)).all()
+        assert r.feasible
+        hr, er, hw, ew = (r.step_bytes[..., i].astype(np.int64) for i in range(4))
+        assert (hr + er == acc_b).all() and (hw + ew == wr_b[None]).all()
+
+
+def test_score_ignores_dead_bits_and_reports_excess():
+    tr = W.config("table1")
+    X = W.random_placements(tr, 1, seed=3)[0]
+    a = O.score(tr, X)
+    Y = X | (1 - tr.alive[None])                   # set every dead bit
+    b = O.score(tr, Y)
+    assert b.cost == a.cost and (b.occ == a.occ).all()
+    assert b.excess == (a.excess | 0x80000000)
+    full = O.score(tr, np.ones_like(X))
+    assert (full.excess & 0x7FFFFFFF) == int(tr.L * tr.alive.sum(axis=1).max() - tr.cap_pages)
+
+
+def test_single_step_optimum_is_the_balanced_split():
+    # One step, P pages all read, equal sizes: with h pages in HBM the latency is
+    # max(h b/B_h, (P-h) b/B_e).  The best h follows from that formula alone.
+    P, b = 12, 65536
+    tr = _mini(L=1, N=1, P=P, bw=(4.0e12, 0.5e12, 0.5e12), cap=P, page_bytes=b, token_bytes=0)
+    tr.alive[:] = 1
+    tr.access[:] = 1
+    want = min(max(Fraction(h * b, 4 * 10**12), Fraction((P - h) * b, 5 * 10**11)) for h in range(P + 1))
+    best, X, nf = O.brute_force(tr)
+    assert nf == 2 ** P
+    assert best == pytest.approx(float(want), rel=1e-15)
+    assert int(X.sum()) == 11          # 11 b/4e12 = 1.80e-7 > 1 b/5e11 = 1.31e-7; h = 10 gives 2.62e-7
+
+
+# -------------------------------------------------------------- brute force --
+def _micro(seed, L=2, N=3, P=3, **kw):
+    return W.random_trace(seed, L, N, P, **kw)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_bruteforce_optimum_is_monotone_in_capacity_and_bounded(seed):
+    tr = _micro(seed)
+    pb = tr.plane_bytes[0]
+    acc_b = tr.access.astype(np.int64).sum(axis=(2, 3)) * pb
+    wr_b = tr.written.astype(np.int64).sum(axis=1) * tr.token_bytes
+    lb = float(((acc_b + wr_b[None]) / (tr.bw_hbm + min(tr.bw_link, tr.bw_dram))).sum())
+    prev = None
+    for cap in range(0, int(tr.L * tr.alive.sum(axis=1).max()) + 1):
+        tr.cap_pages = cap
+        best, X, nf = O.brute_force(tr)
+        s = O.score(tr, X)
+        assert s.cost == best and s.feasible
+        assert best >= lb * (1 - 1e-12)
+        if cap == 0:                                    # only the empty schedule is feasible
+            assert nf == 1 and best == O.cost(tr, np.zeros_like(X))
+        if prev is not None:
+            assert best <= prev and nf >= prev_nf
+        prev, prev_nf = best, nf
+        for init in (O.init_static_frequency(tr), O.init_recency(tr)):
+            si = O.score(tr, init)
+            assert si.feasible and si.cost >= best
+
+
+# ------------------------------------------------------------------- moves --
+def _move(op, l, p, n1, ln, l2=0, q=0, d=0):
+    return dict(op=op, layer=l, page=p, n1=n1, len=ln, layer2=l2, page2=q, dsel=d)
+
+
+def _move_instance():
+    tr = _mini(L=2, N=8, P=2, cap=2)
+    tr.alive[:] = 1
+    tr.persist[1:] = 1
+    tr.access[:] = 1
+    X = np.zeros((2, 8, 2), np.uint8)
+    X[0, :, 0] = [0, 0, 0, 1, 1, 0, 0, 0]
+    X[0, :, 1] = [1, 1, 0, 0, 0, 0, 0, 0]
+    X[1, :, 0] = [0, 0, 1, 1, 1, 1, 0, 0]
+    return tr, X          # occupancy 1 1 1 2 2 1 0 0, capacity 2
+
+
+HAND_MOVES = [
+    # move, verdict, steps flipped on (layer,page), steps flipped on the victim, base
+    (_move(0, 0, 0, 1, 5), 0, [1, 2, 5], [], 1),            # SET to 1 skips steps already set
+    (_move(0, 1, 1, 2, 4), 1, [2], [], 2),                  # clipped at the full step 3
+    (_move(0, 1, 1, 3, 2), 2, [], [], 3),                   # starts on a full step: null
+    (_move(0, 1, 0, 3, 63), 0, [3, 4, 5], [], 3),           # SET to 0 runs to the end of the trace
+    (_move(1, 1, 1, 2, 4, 0, 0), 0, [2, 3, 4, 5], [3, 4], 2),   # SWAP evicts the victim only where full
+    (_move(1, 1, 1, 3, 2, 0, 1), 2, [], [], 3),             # victim absent on the full steps: null
+    (_move(1, 0, 0, 3, 1, 1, 0), 0, [3], [], 3),            # SWAP on a set bit acts as SET to 0
+    (_move(2, 0, 0, 0, 10, 0, 0, 0), 0, [1, 2], [], 1),     # SHIFT: rising edge at 3, two steps earlier
+    (_move(2, 0, 0, 0, 10, 0, 0, 2), 0, [3], [], 1),        # ... one step later
+    (_move(2, 0, 0, 0, 10, 0, 0, 3), 0, [3, 4], [], 1),     # ... two steps later
+    (_move(2, 1, 0, 3, 5, 0, 0, 3), 0, [6, 7], [], 4),      # falling edge at 6 moved two steps later
+    (_move(2, 1, 0, 3, 5, 0, 0, 1), 0, [5], [], 4),         # falling edge one step earlier
+    (_move(2, 1, 0, 3, 2, 0, 0, 1), 2, [], [], 3),          # no edge within (3, 5]
+    (_move(2, 1, 1, 0, 63, 0, 0, 0), 2, [], [], 0),         # constant timeline: null
+    (_move(0, 0, 0, 8, 1), 2, [], [], 0),                   # malformed record: null
+]
+
+
+@pytest.mark.parametrize("mv,verdict,f1,f2,base", HAND_MOVES)
+def test_moves_by_hand(mv, verdict, f1, f2, base):
+    tr, X = _move_instance()
+    v, dT, b, g1, g2 = O.delta(tr, X, mv)
+    assert v == verdict
+    assert np.nonzero(g1)[0].tolist() == f1 and np.nonzero(g2)[0].tolist() == f2
+    if v != 2:
+        assert b == base
+
+
+def test_shift_respects_capacity_and_span_start():
+    tr, X = _move_instance()
+    X[1, :, 1] = [0, 0, 0, 0, 0, 1, 1, 0]          # occupancy 1 1 1 2 2 2 1 0
+    v, _, _, f1, _ = O.delta(tr, X, _move(2, 1, 1, 2, 6, 0, 0, 0))     # edge at 5, wants steps 4, 3: both full
+    assert v == 2 and not f1.any()
+    v, _, _, f1, _ = O.delta(tr, X, _move(2, 1, 1, 2, 6, 0, 0, 3))     # same edge two steps later: 5, 6 cleared
+    assert v == 0 and np.nonzero(f1)[0].tolist() == [5, 6]
+    v, _, b, f1, _ = O.delta(tr, X, _move(2, 1, 1, 5, 6, 0, 0, 3))     # falling edge at 7, two later: the trace ends
+    assert v == 0 and np.nonzero(f1)[0].tolist() == [7] and b == 5
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_moves_keep_schedules_feasible_and_delta_matches_rescoring(seed):
+    tr = W.random_trace(100 + seed, L=3, N=40, P=21, K=2 if seed % 2 else 1,
+                        plane_bytes=[4096, 61440] if seed % 2 else None)
+    X = W.random_placements(tr, 1, seed=seed, density=0.45)[0]
+    base = O.score(tr, X)
+    assert base.feasible
+    mv = W.random_moves(tr, 400, seed=seed, max_len=63 if seed % 3 else 7)
+    kinds = set()
+    for i in range(400):
+        m = {k: int(v[i]) for k, v in mv.items()}
+        v, dT, b, f1, f2 = O.delta(tr, X, m)
+        kinds.add((m["op"], v))
+        if v == 2:
+            assert dT == 0.0 and not f1.any() and not f2.any()
+            continue
+        Y, _ = O.apply_move(tr, X, m)
+        after = O.score(tr, Y)
+        assert after.feasible and not (after.excess >> 31)
+        # the window sum equals the difference of the two totals up to rounding
+        assert dT == pytest.approx(after.cost - base.cost, rel=1e-9, abs=1e-12 * base.cost)
+        # edits stay on the two timelines and inside the 64-step window
+        diff = np.argwhere(Y != X)
+        for l, n, p in diff:
+            assert (l, p) in ((m["layer"], m["page"]), (m["layer2"], m["page2"]))
+            assert b <= n < b + 64
+        if f2.any():                                    # a victim is only taken on full steps
+            assert (base.occ[f2.astype(bool)] == tr.cap_pages).all()
+            assert (after.occ[f2.astype(bool)] == tr.cap_pages).all()
+    assert {(0, 0), (1, 0), (2, 0)} <= kinds and any(v == 1 for _, v in kinds)
+
+
+# --------------------------------------------------------------- annealing --
+def test_anneal_reaches_the_exhaustive_optimum_on_micro_instances():
+    hit = 0
+    for seed in range(4):
+        tr = _micro(10 + seed, L=2, N=3, P=3)
+        tr.cap_pages = 3
+        best, _, _ = O.brute_force(tr)
+        X0 = np.zeros((tr.L, tr.N, tr.P), np.uint8)
+        res, bi = O.anneal(tr, range(8), X0, seed=seed, total_moves=4000, max_len=3)
+        r = res[bi]
+        assert r.best_cost >= best * (1 - 1e-15)          # nothing beats the optimum
+        assert O.score(tr, r.best_X).feasible
+        hit += r.best_cost == best
+    assert hit >= 3
+
+
+def test_anneal_invariants_on_tiny_config():
+    tr = W.config("tiny")
+    q = O.Problem(tr)
+    starts = {"static": O.init_static_frequency(q), "recency": O.init_recency(q),
+              "empty": np.zeros(q.shape, np.uint8)}
+    for name, X0 in starts.items():
+        c0 = O.score(q, X0)
+        assert c0.feasible
+        r = O.anneal_chain(q, 3, X0, seed=0, total_moves=3000)
+        fin = O.score(q, r.X)
+        bst = O.score(q, r.best_X)
+        assert fin.feasible and bst.feasible
+        assert r.best_cost == bst.cost <= c0.cost                  # never worse than its start
+        assert r.T_best == pytest.approx(bst.cost, rel=1e-9)       # running value only drifts by rounding
+        assert r.T_cur == pytest.approx(fin.cost, rel=1e-9)
+        assert r.accepted > 0 and r.C0 >= 0
+        if name != "empty":
+            assert r.uphill > 0                                     # p0 = 0.8: uphill moves are taken early
+    # same seed, same chain: identical; another chain id: a different walk
+    a = O.anneal_chain(q, 3, starts["empty"], seed=0, total_moves=3000)
+    b = O.anneal_chain(q, 3, starts["empty"], seed=0, total_moves=3000)
+    c = O.anneal_chain(q, 4, starts["empty"], seed=0, total_moves=3000)
+    assert (a.X == b.X).all() and a.T_cur == b.T_cur
+    assert not (a.X == c.X).all()
+    # stopping and resuming continues the same walk (counter-based draws)
+    h = O.anneal_chain(q, 3, starts["empty"], seed=0, total_moves=3000, move_end=1234)
+    h2 = O.anneal_chain(q, 3, None, seed=0, total_moves=3000, move_begin=1234, resume=h)
+    assert (h2.X == a.X).all() and h2.T_cur == a.T_cur and (h2.best_X == a.best_X).all()
+
+
+def test_initial_temperature_gives_the_target_uphill_acceptance():
+    # C0 = mean uphill dT / (-ln p0) (Sec. III-B: p0 = 0.8).  Held at that
+    # temperature (alpha = 1) a walk accepts uphill proposals at a rate of at
+    # least about p0: E[exp(-dT/C0)] >= exp(-E[dT]/C0) = p0 by convexity.
+    tr = W.config("tiny")
+    X0 = O.init_static_frequency(tr)
+    for p0, lo, hi in ((0.8, 0.72, 0.97), (0.3, 0.22, 0.75)):
+        r = O.anneal_chain(tr, 0, X0, seed=5, total_moves=600, alpha=1.0, p0=p0)
+        assert r.C0 > 0 and r.state.uphill_seen > 100
+        assert lo <= r.uphill / r.state.uphill_seen <= hi
+    cold = O.anneal_chain(tr, 0, X0, seed=5, total_moves=600, alpha=1e-9, n_levels=600)
+    assert cold.uphill <= 2                      # frozen after the first move: pure descent
+
+
+def test_static_and_recency_placements_by_hand():
+    tr = _mini(L=1, N=4, P=3, cap=1)
+    tr.alive[:] = 1
+    tr.persist[1:] = 1
+    tr.access[0, :, 0, :] = [[1, 0, 0], [0, 1, 0], [0, 1, 0], [0, 0, 1]]
+    st = O.init_static_frequency(tr)
+    assert st[0].tolist() == [[0, 1, 0]] * 4                   # page 1 is read twice
+    rc = O.init_recency(tr)
+    # before step 0 nothing was read: lowest index; then the page read one step earlier
+    assert rc[0].tolist() == [[1, 0, 0], [1, 0, 0], [0, 1, 0], [0, 1, 0]]

@@ -1,0 +1,334 @@
+"""Seeded synthetic KV-cache access traces.
+
+This module only *draws inputs*: which pages exist at each decode step, which
+ones attention reads, which one receives the new token.  It contains none of
+the latency model, no scoring and no search: both the CPU oracle and the GPU
+library consume what it emits.
+
+The traces stand in for recorded layer-wise attention of a long-context decode
+(paper Sec. IV-A): importance scores follow a parametric drift, and the access
+set of a step is the top share of pages by score (the complement of the
+"attention sparsity" of Sec. IV-B) plus attention sinks and the most recent
+tokens.
+
+All arrays are plain booleans (uint8 0/1), page-indexed:
+
+    access  [L][N][K][P]   page p read by plane k at step (n, l)
+    alive   [N][P]         page p holds KV data while step n executes
+    persist [N][P]         page p held the same data at step n-1 and n
+    written [N][P]         page p receives the token generated at step n
+
+`pack_bits` turns the last axis into little-endian uint32 words
+(bit b of word w = page 32*w + b).
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field, replace
+from typing import Optional
+
+import numpy as np
+
+KV_TOKEN_BYTES = 4096  # 8 KV heads x 128 dims x (K and V) x 2 B, one layer
+
+
+@dataclass
+class Recipe:
+    name: str
+    L: int
+    N: int
+    page_tokens: int
+    prompt_lo: int
+    prompt_hi: int                      # prompt length ~ U[lo, hi] tokens
+    slots: int = 1                      # concurrent sequences
+    slot_pages: Optional[int] = None    # page slots per sequence (default: just enough)
+    K: int = 1                          # access planes (per-head sets)
+    top_frac: float = 0.10              # share of alive pages read per step
+    top_count: Optional[int] = None     # fixed count among non-forced pages
+    sink_tokens: int = 0
+    recent_tokens: int = 0
+    drift: str = "ar1"                  # "ar1" | "jump"
+    phi: float = 0.9
+    sigma: float = 0.7
+    jump_p: float = 0.02
+    jump_mean: float = 3.0
+    burn_in: int = 200
+    lifetime_mean: float = 0.0          # 0: sequences never finish
+    cap_frac: Optional[float] = None    # share of L x peak alive pages
+    cap_pages: Optional[int] = None
+    bw_hbm: float = 4.0e12
+    bw_link: float = 0.5e12
+    bw_dram: float = 0.5e12
+    plane_tokens_bytes: int = KV_TOKEN_BYTES   # bytes per token across all planes
+    chains: int = 16
+    moves: int = 20000
+    seed: int = 0
+
+
+@dataclass
+class Trace:
+    name: str
+    L: int
+    N: int
+    P: int
+    K: int
+    access: np.ndarray
+    alive: np.ndarray
+    persist: np.ndarray
+    written: np.ndarray
+    plane_bytes: list
+    page_bytes: int
+    token_bytes: int
+    bw_hbm: float
+    bw_link: float
+    bw_dram: float
+    cap_pages: int
+    chains: int = 16
+    moves: int = 20000
+    seed: int = 0
+    recipe: Optional[Recipe] = field(default=None, repr=False)
+
+    @property
+    def n_words(self) -> int:
+        return (self.P + 31) // 32
+
+    def with_bandwidth_ratio(self, r: float) -> "Trace":
+        slow = self.bw_hbm / r
+        return replace(self, bw_link=slow, bw_dram=slow)
+
+
+def pack_bits(a: np.ndarray) -> np.ndarray:
+    """Pack booleans along the last axis into uint32 words, LSB first."""
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    P = a.shape[-1]
+    Wd = (P + 31) // 32
+    if P != Wd * 32:
+        pad = np.zeros(a.shape[:-1] + (Wd * 32 - P,), dtype=np.uint8)
+        a = np.concatenate([a, pad], axis=-1)
+    by = np.packbits(a, axis=-1, bitorder="little")
+    return np.ascontiguousarray(by).view("<u4").reshape(a.shape[:-1] + (Wd,))
+
+
+def unpack_bits(w: np.ndarray, P: int) -> np.ndarray:
+    """Inverse of pack_bits."""
+    w = np.ascontiguousarray(w, dtype="<u4")
+    by = w.view(np.uint8).reshape(w.shape[:-1] + (w.shape[-1] * 4,))
+    return np.unpackbits(by, axis=-1, bitorder="little")[..., :P].copy()
+
+
+def _rng(seed: int, tag: int) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[seed & (2**64 - 1), tag]))
+
+
+def _select_top(z: np.ndarray, eligible: np.ndarray, k: int) -> np.ndarray:
+    """Exactly-k largest of z along the last axis among `eligible` (1-D mask);
+    ties go to the lower index."""
+    out = np.zeros(z.shape, dtype=bool)
+    m = int(eligible.sum())
+    k = min(k, m)
+    if k <= 0:
+        return out
+    zz = np.where(eligible, z, -np.inf)
+    kth = np.partition(zz, zz.shape[-1] - k, axis=-1)[..., zz.shape[-1] - k]
+    gt = zz > kth[..., None]
+    need = k - gt.sum(axis=-1)
+    tie = (zz == kth[..., None]) & eligible
+    rank = np.cumsum(tie, axis=-1)
+    return gt | (tie & (rank <= need[..., None]))
+
+
+def generate(r: Recipe) -> Trace:
+    rng = _rng(r.seed, 1)
+    L, N, K, S = r.L, r.N, r.K, r.slots
+    pt = r.page_tokens
+    slot_pages = r.slot_pages or -(-(r.prompt_hi + N) // pt)
+    P = S * slot_pages
+
+    access = np.zeros((L, N, K, P), dtype=np.uint8)
+    alive = np.zeros((N, P), dtype=np.uint8)
+    persist = np.zeros((N, P), dtype=np.uint8)
+    written = np.zeros((N, P), dtype=np.uint8)
+
+    def fresh_scores(shape):
+        if r.drift == "ar1":
+            sd = r.sigma / math.sqrt(1.0 - r.phi * r.phi)
+            return rng.standard_normal(shape) * sd
+        z = np.zeros(shape)
+        for _ in range(r.burn_in):
+            z = r.phi * z + _jumps(shape)
+        return z
+
+    def _jumps(shape):
+        hit = rng.random(shape) < r.jump_p
+        return np.where(hit, rng.exponential(r.jump_mean, shape), 0.0)
+
+    def draw_prompt(n):
+        if r.prompt_lo == r.prompt_hi:
+            return np.full(n, r.prompt_lo, dtype=np.int64)
+        return rng.integers(r.prompt_lo, r.prompt_hi + 1, size=n)
+
+    z = fresh_scores((L, K, S, slot_pages))
+    prompt = draw_prompt(S)
+    age = np.zeros(S, dtype=np.int64)
+    fresh = np.ones(S, dtype=bool)          # sequence started at this step
+    pages_prev = np.zeros(S, dtype=np.int64)
+    ended = np.zeros(S, dtype=bool)
+
+    for n in range(N):
+        if n > 0:
+            # finished sequences are replaced in the same slot
+            n_new = int(ended.sum())
+            fresh = ended.copy()
+            if n_new:
+                prompt[ended] = draw_prompt(n_new)
+                age[ended] = 0
+                znew = fresh_scores((L, K, n_new, slot_pages))
+                z[:, :, ended, :] = znew
+            age[~fresh] += 1
+            # importance drift of every slot that carries on
+            if r.drift == "ar1":
+                step = r.phi * z + r.sigma * rng.standard_normal(z.shape)
+            else:
+                step = r.phi * z + _jumps(z.shape)
+            z[:, :, ~fresh, :] = step[:, :, ~fresh, :]
+
+        ctx = prompt + age + 1                      # tokens incl. the new one
+        pages = -(-ctx // pt)
+        for s in range(S):
+            base = s * slot_pages
+            ap = int(pages[s])
+            a = np.zeros(slot_pages, dtype=bool)
+            a[:ap] = True
+            alive[n, base:base + ap] = 1
+            if not fresh[s]:
+                keep = int(min(ap, pages_prev[s]))
+                persist[n, base:base + keep] = 1
+            wp = int((ctx[s] - 1) // pt)
+            written[n, base + wp] = 1
+            if (ctx[s] - 1) % pt == 0 and ap > 1:
+                # a page that starts with the new token enters at the top score
+                z[:, :, s, ap - 1] = z[:, :, s, :ap - 1].max(axis=-1)
+            forced = np.zeros(slot_pages, dtype=bool)
+            if r.sink_tokens:
+                forced[: -(-min(r.sink_tokens, int(ctx[s])) // pt)] = True
+            if r.recent_tokens:
+                lo = max(int(ctx[s]) - r.recent_tokens, 0) // pt
+                forced[lo:ap] = True
+            forced &= a
+            zs = z[:, :, s, :]
+            if r.top_count is not None:
+                sel = _select_top(zs, a & ~forced, r.top_count) | forced
+            else:
+                k = int(math.ceil(r.top_frac * ap))
+                sel = _select_top(zs, a, k) | forced
+            access[:, n, :, base:base + slot_pages] = sel
+        pages_prev = pages.copy()
+        if r.lifetime_mean > 0:
+            ended = rng.random(S) < 1.0 / r.lifetime_mean
+        else:
+            ended = np.zeros(S, dtype=bool)
+
+    page_bytes = pt * r.plane_tokens_bytes
+    plane_bytes = [page_bytes // K] * K
+    if r.cap_pages is not None:
+        cap = int(r.cap_pages)
+    else:
+        peak = int(alive.sum(axis=1).max())
+        cap = int(math.floor(r.cap_frac * L * peak + 1e-9))
+    return Trace(name=r.name, L=L, N=N, P=P, K=K, access=access, alive=alive,
+                 persist=persist, written=written, plane_bytes=plane_bytes,
+                 page_bytes=page_bytes, token_bytes=r.plane_tokens_bytes,
+                 bw_hbm=r.bw_hbm, bw_link=r.bw_link, bw_dram=r.bw_dram,
+                 cap_pages=cap, chains=r.chains, moves=r.moves, seed=r.seed,
+                 recipe=r)
+
+
+def _ratio(r: float):
+    return dict(bw_hbm=4.0e12, bw_link=4.0e12 / r, bw_dram=4.0e12 / r)
+
+
+# The five workload shapes and the Table-I parity case.  "scale" shrinks the
+# large dimensions (layers, steps, prompt) for tests while keeping the recipe.
+def recipe(name: str, scale: float = 1.0) -> Recipe:
+    def sc(x, lo=1, mult=1):
+        v = max(lo, int(round(x * scale)))
+        return -(-v // mult) * mult
+
+    if name == "tiny":
+        return Recipe("tiny", L=1, N=sc(64), page_tokens=1, prompt_lo=sc(192), prompt_hi=sc(192),
+                      top_count=20, sink_tokens=4, recent_tokens=8, phi=0.95, sigma=0.5,
+                      cap_pages=sc(64), bw_hbm=4000e9, bw_link=500e9, bw_dram=500e9,
+                      chains=16, moves=20000, seed=0)
+    if name == "llama8b":
+        return Recipe("llama8b", L=sc(32, 2), N=sc(256, 8), page_tokens=16,
+                      prompt_lo=sc(4096, 64, 16), prompt_hi=sc(4096, 64, 16),
+                      top_frac=0.10, sink_tokens=4, recent_tokens=8, phi=0.9, sigma=0.7,
+                      cap_frac=0.30, **_ratio(8), chains=256, moves=100000, seed=1)
+    if name == "longctx":
+        return Recipe("longctx", L=sc(32, 2), N=sc(1024, 8), page_tokens=16,
+                      prompt_lo=sc(32768, 64, 16), prompt_hi=sc(32768, 64, 16),
+                      top_frac=0.05, drift="jump", phi=0.9, jump_p=0.02, jump_mean=3.0,
+                      cap_frac=0.20, **_ratio(8), chains=1024, moves=200000, seed=2)
+    if name == "serving":
+        return Recipe("serving", L=sc(32, 2), N=sc(512, 8), page_tokens=16, slots=sc(64, 2),
+                      prompt_lo=sc(1024, 32, 16), prompt_hi=sc(16384, 64, 16),
+                      top_frac=0.08, phi=0.9, sigma=0.7, lifetime_mean=max(300.0 * scale, 4.0),
+                      cap_frac=0.25, **_ratio(4), chains=512, moves=100000, seed=3)
+    if name == "gqa70b":
+        return Recipe("gqa70b", L=sc(80, 2), N=sc(2048, 8), page_tokens=128, K=8,
+                      prompt_lo=sc(131072, 256, 128), prompt_hi=sc(131072, 256, 128),
+                      top_frac=0.04, phi=0.9, sigma=0.7,
+                      cap_frac=0.15, **_ratio(8), chains=512, moves=50000, seed=4)
+    if name == "table1":
+        # Memory system of the paper's Table I: the one case where the link and
+        # the DRAM channels differ.  508-token prompt: a page is born at step 4,
+        # seven of the 40 page slots never hold data.
+        return Recipe("table1", L=2, N=8, page_tokens=16, prompt_lo=508, prompt_hi=508, slot_pages=40,
+                      top_frac=0.25, sink_tokens=4, recent_tokens=8, phi=0.9, sigma=0.7,
+                      cap_pages=20, bw_hbm=4.9e12, bw_link=900e9, bw_dram=500e9,
+                      chains=4, moves=2000, seed=5)
+    raise KeyError(name)
+
+
+CONFIG_NAMES = ["tiny", "llama8b", "longctx", "serving", "gqa70b"]
+
+
+def config(name: str, scale: float = 1.0) -> Trace:
+    return generate(recipe(name, scale))
+
+
+def random_trace(seed: int, L: int, N: int, P: int, K: int = 1, *, p_access: float = 0.3,
+                 rebirth: bool = True, cap_pages: Optional[int] = None,
+                 bw=(4.9e12, 900e9, 500e9), page_bytes: int = 65536,
+                 token_bytes: int = 4096, plane_bytes=None) -> Trace:
+    """Unstructured random instance: pages are born, die and are re-used at
+    random, several pages may be written in a step.  For stress and brute-force
+    tests, where the structure of a real decode would hide cases."""
+    rng = _rng(seed, 2)
+    alive = np.zeros((N, P), dtype=np.uint8)
+    persist = np.zeros((N, P), dtype=np.uint8)
+    written = np.zeros((N, P), dtype=np.uint8)
+    cur = rng.random(P) < 0.7
+    for n in range(N):
+        if n > 0:
+            die = cur & (rng.random(P) < (0.15 if rebirth else 0.0))
+            born = ~cur & (rng.random(P) < 0.3)
+            reborn = cur & ~die & (rng.random(P) < (0.05 if rebirth else 0.0))
+            nxt = (cur & ~die) | born
+            persist[n] = cur & nxt & ~reborn & ~born
+            wr_new = born | reborn
+            cur = nxt
+        else:
+            wr_new = np.zeros(P, dtype=bool)
+        alive[n] = cur
+        w = wr_new | (cur & (rng.random(P) < 0.1))
+        written[n] = w & cur
+    access = (rng.random((L, N, K, P)) < p_access) & alive[None, :, None, :].astype(bool)
+    if plane_bytes is None:
+        plane_bytes = [page_bytes // K] * K
+    if cap_pages is None:
+        cap_pages = max(1, int(0.4 * L * alive.sum(axis=1).max()))
+    return Trace(name=f"random{seed}", L=L, N=N, P=P, K=K, access=access.astype(np.uint8),
+                 alive=alive, persist=persist, written=written, plane_bytes=list(plane_bytes),
+                 page_bytes=page_bytes, token_bytes=token_bytes, bw_hbm=bw[0], bw_link=bw[1],
+                 bw_dram=bw[2], cap_pages=int(cap_pages), chains=4, moves=2000, seed=seed)
