@@ -1,0 +1,199 @@
+/*
+ * kvp.h -- C boundary of the MI355X KV-cache placement scorer and annealer.
+ *
+ * The library searches for the upper-bound dynamic placement of KV-cache pages
+ * across HBM and off-package DRAM of "Accelerating LLM Inference via Dynamic KV
+ * Cache Placement in Heterogeneous Memory System" (Sec. III).  A placement
+ * schedule says, for every inference step (n, l) and every page, whether the
+ * page sits in HBM while the step runs; its cost is the total decode latency of
+ * Eqs. 1-4 and it is admissible when it respects the HBM capacity (Eq. 5).
+ *
+ * Conventions
+ *   - Every function returns KVP_OK (0) or a negative KVP_E* code; nothing
+ *     aborts, throws or prints.  kvp_strerror names a code.
+ *   - Pointers named d_* are DEVICE memory on the context's GPU, allocated and
+ *     owned by the caller, 16-byte aligned.  Pointers named h_* are HOST memory.
+ *     The library copies what it keeps and retains no caller pointer.
+ *   - kvp_score, kvp_delta_score and kvp_anneal enqueue their work on the HIP
+ *     stream given to kvp_create and return without waiting (they may allocate
+ *     internal buffers first).  kvp_trace_upload, kvp_best, kvp_chain_placement
+ *     and kvp_chain_stats wait for the stream.
+ *   - Bit masks: uint32 words, bit b of word w is page 32*w + b; bits at or
+ *     above n_pages are zero.  A schedule is [n_layers][n_steps][n_words]
+ *     words; a batch of S schedules is S of those back to back.
+ *   - One context serves one host thread at a time.
+ */
+#ifndef KVP_H
+#define KVP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kvp_ctx kvp_ctx;
+
+enum {
+    KVP_OK = 0,
+    KVP_EINVAL = -1,      /* null pointer, misaligned pointer, value out of range        */
+    KVP_ENOTRACE = -2,    /* no trace uploaded yet                                        */
+    KVP_ENOMEM = -3,      /* device or host allocation failed                             */
+    KVP_EHIP = -4,        /* a HIP call failed                                            */
+    KVP_ESHAPE = -5,      /* sizes inconsistent with each other or beyond what is built   */
+    KVP_ETRACE = -6,      /* trace masks contradict each other (see kvp_trace_upload)     */
+    KVP_ENOCHAINS = -7,   /* no annealing state to continue or to read                    */
+    KVP_EINFEASIBLE = -8  /* a starting schedule exceeds the HBM capacity                 */
+};
+
+#define KVP_MAX_PLANES 8
+#define KVP_MAX_LEN 63     /* longest span of a move: its window fits one 64-lane wavefront */
+
+/* The placement problem (Sec. III-A): access sets per step come with the trace;
+ * this holds sizes, data volumes, the three bandwidths of Eqs. 3-4 and the
+ * capacity of Eq. 5. */
+typedef struct {
+    uint32_t n_layers;    /* L: transformer layers                                        */
+    uint32_t n_steps;     /* N: decode tokens; inference step (n,l) runs in order n*L+l   */
+    uint32_t n_pages;     /* P: page slots per layer                                      */
+    uint32_t n_words;     /* must equal ceil(P/32)                                        */
+    uint32_t n_planes;    /* K in 1..8: access sets per step (e.g. one per KV head)       */
+    uint32_t reserved;    /* 0                                                            */
+    uint64_t plane_bytes[KVP_MAX_PLANES]; /* bytes read per accessed page of plane k, >0  */
+    uint64_t page_bytes;  /* bytes moved when a page changes tier (|M^i|, |M^o| unit)     */
+    uint64_t token_bytes; /* bytes of new KV written per written page and layer (H^w,E^w) */
+    double bw_hbm;        /* B_h, bytes/s, finite and > 0                                 */
+    double bw_link;       /* B_k, one direction of the full-duplex link                   */
+    double bw_dram;       /* B_d, off-package DRAM channels                               */
+    uint64_t cap_pages;   /* HBM pool in pages, shared by all layers (Eq. 5)              */
+} kvp_problem;
+
+/* A raw move on a schedule (before clipping to the capacity).  The move set is
+ * this library's own; Sec. III-B of the paper fixes only the Metropolis rule,
+ * the three-operator mixture and the cooling constants.
+ *   op 0 SET    give the bit of (layer, page) the value opposite to the one it
+ *               has at step n1, on steps n1 .. n1+len-1 (while the page lives)
+ *   op 1 SWAP   as SET towards HBM, evicting (layer2, page2) on full steps
+ *   op 2 SHIFT  move the first 0/1 edge of the page's timeline after n1 by
+ *               {-2,-1,+1,+2}[dsel & 3] steps
+ * A record with a field out of range (len outside 1..KVP_MAX_LEN) is a null move. */
+typedef struct {
+    uint32_t op, layer, page, n1, len, layer2, page2, dsel;
+} kvp_move;
+
+enum { KVP_OP_SET = 0, KVP_OP_SWAP = 1, KVP_OP_SHIFT = 2 };
+enum { KVP_MOVE_OK = 0, KVP_MOVE_CLIPPED = 1, KVP_MOVE_NULL = 2 };
+
+enum {
+    KVP_INIT_EMPTY = 0,     /* every chain starts with nothing in HBM                     */
+    KVP_INIT_GIVEN = 1,     /* start from d_init: one schedule per chain                  */
+    KVP_INIT_BROADCAST = 2, /* start every chain from the single schedule d_init          */
+    KVP_INIT_CONTINUE = 3   /* carry on the chains of the previous call                   */
+};
+
+/* Simulated annealing (Sec. III-B): Metropolis acceptance exp(-dT/C), initial
+ * temperature from the target acceptance p0 of uphill moves, geometric cooling
+ * by alpha over n_levels levels of equal length, fixed move budget. */
+typedef struct {
+    uint32_t n_chains;     /* independent chains, one wavefront each                      */
+    uint32_t n_levels;     /* temperature levels (>= 1), e.g. 100                          */
+    uint64_t seed;         /* Philox4x32-10 key; the chain id is part of the counter      */
+    uint64_t total_moves;  /* length of the whole cooling schedule, per chain             */
+    uint64_t moves;        /* moves to run in this call, per chain (proposals, incl. null) */
+    uint32_t max_len;      /* longest span, 1..KVP_MAX_LEN                                 */
+    uint32_t init_mode;    /* KVP_INIT_*                                                   */
+    double p0;             /* 0 < p0 < 1, the paper uses 0.8                               */
+    double alpha;          /* 0 < alpha <= 1, the paper uses 0.9                           */
+    double op_prob[3];     /* SET, SWAP, SHIFT; the paper's mixture is 0.4, 0.4, 0.2       */
+} kvp_anneal_params;
+
+typedef struct {
+    double t_cur;          /* running cost of the current schedule (start + accepted dT)  */
+    double t_best;         /* lowest running cost seen                                    */
+    double c0, c;          /* initial and current temperature                             */
+    uint64_t moves_done, accepted, uphill, null_moves, clipped, improved;
+} kvp_chain_stats_t;
+
+/* Create a context on GPU `device` whose work runs on `hip_stream` (a
+ * hipStream_t, may be NULL for the default stream).  The caller keeps the
+ * stream alive until kvp_destroy.  Errors: KVP_EINVAL, KVP_EHIP, KVP_ENOMEM. */
+int kvp_create(kvp_ctx **out, int device, void *hip_stream);
+
+/* Wait for the stream, free everything the context owns.  NULL is allowed. */
+void kvp_destroy(kvp_ctx *ctx);
+
+/* Sec. III-B (access patterns known a priori) and Sec. IV-A (recorded per
+ * layer): hand over the access trace.  All four arrays are HOST memory:
+ *   h_access  [L][N][K][Wd]  pages read by plane k at step (n,l)
+ *   h_alive   [N][Wd]        pages that hold KV data while token step n runs
+ *   h_persist [N][Wd]        pages holding the same data as at step n-1
+ *   h_written [N][Wd]        pages that receive the token generated at step n
+ * Required (else KVP_ETRACE): access and written inside alive; persist[n]
+ * inside alive[n] and alive[n-1]; persist[0] empty; no bit at or above P.
+ * KVP_ESHAPE if n_words != ceil(P/32), a dimension is 0, or a byte total could
+ * reach 2^53; KVP_EINVAL for null pointers, non-finite or non-positive
+ * bandwidths, K outside 1..8.  Copies everything to the GPU (replacing any
+ * earlier trace and discarding annealing state) and waits for the copy. */
+int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *problem, const uint32_t *h_access,
+                     const uint32_t *h_alive, const uint32_t *h_persist, const uint32_t *h_written);
+
+/* Eqs. 1-5: score S schedules at once.
+ *   d_placements [S][L][N][Wd]  in
+ *   d_cost       [S]            total latency T in seconds (Eq. 1: steps summed in
+ *                               execution order by the fixed 64-wide tree)
+ *   d_excess     [S]            largest overshoot of cap_pages over all token steps
+ *                               (0 = admissible, Eq. 5); bit 31 set if the schedule
+ *                               had bits on pages that do not exist (those are ignored)
+ *   d_counters   [S][L][N][4]   nullable: per step {units read from HBM, written pages
+ *                               in HBM, pages migrated in, pages migrated out}; one
+ *                               read unit is kvp_plane_unit() bytes
+ *   d_occ        [S][N]         nullable: pages in HBM per token step
+ * An inadmissible schedule is not an error.  S = 0 is a no-op.  */
+int kvp_score(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, double *d_cost,
+              uint32_t *d_excess, uint32_t *d_counters, uint32_t *d_occ);
+
+/* Sec. III-B, dT = T_new - T_current of one proposed move per schedule, summed
+ * over the 64-step window the move can touch, without re-scoring the rest.
+ *   d_moves    [S]  raw moves
+ *   d_counters, d_occ  as written by kvp_score for the same schedules; if either
+ *                   is NULL the library computes both first (one scoring pass)
+ *   d_delta    [S]  dT in seconds (0 for a null move)
+ *   d_verdict  [S]  KVP_MOVE_OK, _CLIPPED (shortened by the capacity) or _NULL
+ * Schedules must be admissible for the clipping to mean anything. */
+int kvp_delta_score(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, const kvp_move *d_moves,
+                    const uint32_t *d_counters, const uint32_t *d_occ, double *d_delta,
+                    int32_t *d_verdict);
+
+/* Sec. III-B: run params->moves annealing moves on every chain.  d_init is
+ * [C][L][N][Wd] (KVP_INIT_GIVEN), [L][N][Wd] (KVP_INIT_BROADCAST) or NULL.
+ * Starting schedules must be admissible (checked, KVP_EINFEASIBLE) and are
+ * masked to existing pages.  KVP_INIT_CONTINUE needs the parameters of the
+ * previous call except `moves` (else KVP_EINVAL; KVP_ENOCHAINS if none). */
+int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *params, const uint32_t *d_init);
+
+/* Best schedule over all chains: each chain's best-so-far schedule is scored
+ * again in full (never the running value), the lowest cost wins, ties go to the
+ * lowest chain id.  h_placement [L][N][Wd] and h_chain_costs [C] are nullable. */
+int kvp_best(kvp_ctx *ctx, double *h_cost, uint32_t *h_chain, uint32_t *h_placement,
+             double *h_chain_costs);
+
+/* Copy one chain's current (best = 0) or best-so-far (best = 1) schedule out. */
+int kvp_chain_placement(kvp_ctx *ctx, uint32_t chain, int best, uint32_t *h_placement);
+
+/* Per-chain counters, h_stats [C]. */
+int kvp_chain_stats(kvp_ctx *ctx, kvp_chain_stats_t *h_stats);
+
+/* Bytes per read unit of d_counters (gcd of plane_bytes); 0 without a trace. */
+uint64_t kvp_plane_unit(const kvp_ctx *ctx);
+
+const char *kvp_strerror(int code);
+
+/* After a KVP_EHIP / KVP_ENOMEM return on this thread: the hipError_t value of
+ * the failing HIP call (0 if none yet); *line (nullable) gets the library
+ * source line, for bug reports. */
+int kvp_last_hip_error(int *line);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVP_H */

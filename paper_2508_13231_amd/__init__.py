@@ -1,0 +1,208 @@
+"""Python binding of libkvp (include/kvp.h): argument marshalling only.
+
+Every step of the scoring and annealing path runs in the library's HIP kernels
+on an MI355X.  There is no CPU fallback: importing this package is cheap, but
+the first call that needs the library raises if libkvp.so has not been built
+(`python -m paper_2508_13231_amd.build`).
+
+The functions carry the names of the C entry points.  Device arrays are torch
+tensors on the context's GPU (torch is used for device memory and streams
+only); host arrays are numpy.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkvp.so")
+
+KVP_OK, KVP_EINVAL, KVP_ENOTRACE, KVP_ENOMEM, KVP_EHIP = 0, -1, -2, -3, -4
+KVP_ESHAPE, KVP_ETRACE, KVP_ENOCHAINS, KVP_EINFEASIBLE = -5, -6, -7, -8
+KVP_MAX_LEN = 63
+KVP_INIT_EMPTY, KVP_INIT_GIVEN, KVP_INIT_BROADCAST, KVP_INIT_CONTINUE = 0, 1, 2, 3
+KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2
+
+EXPORTS = ["kvp_create", "kvp_destroy", "kvp_trace_upload", "kvp_score", "kvp_delta_score", "kvp_anneal",
+           "kvp_best", "kvp_chain_placement", "kvp_chain_stats", "kvp_plane_unit", "kvp_strerror", "kvp_last_hip_error"]
+
+
+class kvp_problem(C.Structure):
+    _fields_ = [("n_layers", C.c_uint32), ("n_steps", C.c_uint32), ("n_pages", C.c_uint32),
+                ("n_words", C.c_uint32), ("n_planes", C.c_uint32), ("reserved", C.c_uint32),
+                ("plane_bytes", C.c_uint64 * 8), ("page_bytes", C.c_uint64), ("token_bytes", C.c_uint64),
+                ("bw_hbm", C.c_double), ("bw_link", C.c_double), ("bw_dram", C.c_double),
+                ("cap_pages", C.c_uint64)]
+
+
+class kvp_anneal_params(C.Structure):
+    _fields_ = [("n_chains", C.c_uint32), ("n_levels", C.c_uint32), ("seed", C.c_uint64),
+                ("total_moves", C.c_uint64), ("moves", C.c_uint64), ("max_len", C.c_uint32),
+                ("init_mode", C.c_uint32), ("p0", C.c_double), ("alpha", C.c_double),
+                ("op_prob", C.c_double * 3)]
+
+
+class kvp_chain_stats_t(C.Structure):
+    _fields_ = [("t_cur", C.c_double), ("t_best", C.c_double), ("c0", C.c_double), ("c", C.c_double),
+                ("moves_done", C.c_uint64), ("accepted", C.c_uint64), ("uphill", C.c_uint64),
+                ("null_moves", C.c_uint64), ("clipped", C.c_uint64), ("improved", C.c_uint64)]
+
+
+class KvpError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        msg = f"{what}: {strerror(code)} ({code})"
+        if code in (KVP_EHIP, KVP_ENOMEM):
+            line = C.c_int(0)
+            msg += f" [hipError {lib().kvp_last_hip_error(C.byref(line))} at library line {line.value}]"
+        super().__init__(msg)
+
+
+_lib = None
+
+
+def lib():
+    """The loaded libkvp.so.  Raises if it is not built: there is no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2508_13231_amd.build`")
+        # torch ships its own HIP runtime; it must be in the process before libkvp.so is
+        # mapped, so that both use the same one (two HIP runtimes in a process do not work)
+        import torch  # noqa: F401
+        L = C.CDLL(LIB_PATH)
+        vp, u32, i32 = C.c_void_p, C.c_uint32, C.c_int
+        L.kvp_create.restype = i32
+        L.kvp_create.argtypes = [C.POINTER(vp), i32, vp]
+        L.kvp_destroy.restype = None
+        L.kvp_destroy.argtypes = [vp]
+        L.kvp_trace_upload.restype = i32
+        L.kvp_trace_upload.argtypes = [vp, C.POINTER(kvp_problem), vp, vp, vp, vp]
+        L.kvp_score.restype = i32
+        L.kvp_score.argtypes = [vp, vp, u32, vp, vp, vp, vp]
+        L.kvp_delta_score.restype = i32
+        L.kvp_delta_score.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp]
+        L.kvp_anneal.restype = i32
+        L.kvp_anneal.argtypes = [vp, C.POINTER(kvp_anneal_params), vp]
+        L.kvp_best.restype = i32
+        L.kvp_best.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u32), vp, vp]
+        L.kvp_chain_placement.restype = i32
+        L.kvp_chain_placement.argtypes = [vp, u32, i32, vp]
+        L.kvp_chain_stats.restype = i32
+        L.kvp_chain_stats.argtypes = [vp, vp]
+        L.kvp_plane_unit.restype = C.c_uint64
+        L.kvp_plane_unit.argtypes = [vp]
+        L.kvp_strerror.restype = C.c_char_p
+        L.kvp_strerror.argtypes = [i32]
+        L.kvp_last_hip_error.restype = i32
+        L.kvp_last_hip_error.argtypes = [C.POINTER(i32)]
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().kvp_strerror(int(code)).decode()
+
+
+def _check(code, what):
+    if code != KVP_OK:
+        raise KvpError(code, what)
+
+
+def _dptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _hptr(a):
+    return None if a is None else C.c_void_p(a.ctypes.data)
+
+
+def make_problem(L, N, P, K, plane_bytes, page_bytes, token_bytes, bw_hbm, bw_link, bw_dram, cap_pages,
+                 n_words=None) -> kvp_problem:
+    p = kvp_problem()
+    p.n_layers, p.n_steps, p.n_pages, p.n_planes = int(L), int(N), int(P), int(K)
+    p.n_words = int((P + 31) // 32 if n_words is None else n_words)
+    for k in range(min(int(K), 8)):
+        p.plane_bytes[k] = int(plane_bytes[k])
+    p.page_bytes, p.token_bytes = int(page_bytes), int(token_bytes)
+    p.bw_hbm, p.bw_link, p.bw_dram = float(bw_hbm), float(bw_link), float(bw_dram)
+    p.cap_pages = int(cap_pages)
+    return p
+
+
+# ---- the C entry points, same names -------------------------------------------
+def kvp_create(device: int = 0, stream=None):
+    """Returns the opaque context handle.  `stream` is a torch.cuda.Stream or None
+    (torch's current stream on that device)."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(device)
+    h = C.c_void_p()
+    _check(lib().kvp_create(C.byref(h), int(device), C.c_void_p(stream.cuda_stream)), "kvp_create")
+    return h
+
+
+def kvp_destroy(ctx):
+    lib().kvp_destroy(ctx)
+
+
+def kvp_trace_upload(ctx, problem: kvp_problem, access, alive, persist, written):
+    """Host uint32 arrays: access [L][N][K][Wd]; alive, persist, written [N][Wd]."""
+    arrs = [np.ascontiguousarray(a, dtype=np.uint32) for a in (access, alive, persist, written)]
+    L, N, K, Wd = problem.n_layers, problem.n_steps, problem.n_planes, problem.n_words
+    if arrs[0].size != L * N * K * Wd or any(a.size != N * Wd for a in arrs[1:]):
+        raise KvpError(KVP_ESHAPE, "kvp_trace_upload (array sizes)")
+    _check(lib().kvp_trace_upload(ctx, C.byref(problem), *[_hptr(a) for a in arrs]), "kvp_trace_upload")
+
+
+def kvp_score(ctx, d_placements, S, d_cost, d_excess, d_counters=None, d_occ=None):
+    _check(lib().kvp_score(ctx, _dptr(d_placements), int(S), _dptr(d_cost), _dptr(d_excess),
+                           _dptr(d_counters), _dptr(d_occ)), "kvp_score")
+
+
+def kvp_delta_score(ctx, d_placements, S, d_moves, d_counters, d_occ, d_delta, d_verdict):
+    _check(lib().kvp_delta_score(ctx, _dptr(d_placements), int(S), _dptr(d_moves), _dptr(d_counters),
+                                 _dptr(d_occ), _dptr(d_delta), _dptr(d_verdict)), "kvp_delta_score")
+
+
+def kvp_anneal(ctx, params: kvp_anneal_params, d_init=None):
+    _check(lib().kvp_anneal(ctx, C.byref(params), _dptr(d_init)), "kvp_anneal")
+
+
+def kvp_best(ctx, shape_words, n_chains=None):
+    """(cost, chain, placement words [L][N][Wd], per-chain costs or None)."""
+    cost, chain = C.c_double(0.0), C.c_uint32(0)
+    pl = np.zeros(shape_words, dtype=np.uint32)
+    cc = np.zeros(int(n_chains), dtype=np.float64) if n_chains else None
+    _check(lib().kvp_best(ctx, C.byref(cost), C.byref(chain), _hptr(pl), _hptr(cc)), "kvp_best")
+    return cost.value, chain.value, pl, cc
+
+
+def kvp_chain_placement(ctx, chain, best, shape_words):
+    pl = np.zeros(shape_words, dtype=np.uint32)
+    _check(lib().kvp_chain_placement(ctx, int(chain), int(best), _hptr(pl)), "kvp_chain_placement")
+    return pl
+
+
+def kvp_chain_stats(ctx, n_chains):
+    arr = (kvp_chain_stats_t * int(n_chains))()
+    _check(lib().kvp_chain_stats(ctx, C.cast(arr, C.c_void_p)), "kvp_chain_stats")
+    return list(arr)
+
+
+def kvp_plane_unit(ctx) -> int:
+    return int(lib().kvp_plane_unit(ctx))
+
+
+def make_anneal_params(n_chains, total_moves, moves=None, seed=0, n_levels=100, max_len=KVP_MAX_LEN,
+                       init_mode=KVP_INIT_EMPTY, p0=0.8, alpha=0.9, op_prob=(0.4, 0.4, 0.2)):
+    a = kvp_anneal_params()
+    a.n_chains, a.n_levels, a.seed = int(n_chains), int(n_levels), int(seed)
+    a.total_moves = int(total_moves)
+    a.moves = int(total_moves if moves is None else moves)
+    a.max_len, a.init_mode, a.p0, a.alpha = int(max_len), int(init_mode), float(p0), float(alpha)
+    for i in range(3):
+        a.op_prob[i] = float(op_prob[i])
+    return a

@@ -1,0 +1,129 @@
+// Internal declarations shared by the translation units of libkvp.
+// gfx950 (CDNA4) only: 64-lane wavefronts are assumed throughout.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvp.h"
+
+#define KVP_WAVE 64
+
+// Problem as the kernels see it.  Passed by value.
+struct DevProblem {
+    uint32_t L, N, P, Wd, K;
+    uint32_t cap;                 // min(cap_pages, 2^31-1)
+    const uint32_t *A;            // [L][N][K][Wd]
+    const uint32_t *V;            // [N][Wd] alive
+    const uint32_t *Pm;           // [N][Wd] persist
+    const uint32_t *Wm;           // [N][Wd] written
+    const uint32_t *acc;          // [L][N] read units of the step (all tiers)
+    const uint32_t *wr;           // [N] pages written at the step
+    uint32_t wt[KVP_MAX_PLANES];  // plane_bytes[k] / unit
+    double unit_b, page_b, token_b;          // bytes, exact integers held in fp64
+    double inv_bh, inv_bk, inv_bd, inv_min;  // reciprocals of Eqs. 3-4's bandwidths
+};
+
+struct ChainState;   // kvp_moves.hip
+
+struct kvp_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    bool has_trace = false;
+    kvp_problem prob{};
+    DevProblem dp{};
+    uint64_t unit = 0;
+    uint32_t *d_trace = nullptr;         // one allocation: A, V, Pm, Wm, acc, wr
+    // scoring scratch
+    double *d_blocksum = nullptr;  size_t blocksum_cap = 0;   // [S][nb]
+    uint32_t *d_tileflag = nullptr; size_t tileflag_cap = 0;  // [S][tiles]
+    uint32_t *d_cnt_tmp = nullptr; size_t cnt_tmp_cap = 0;    // delta: counters when not given
+    uint32_t *d_occ_tmp = nullptr; size_t occ_tmp_cap = 0;
+    // annealing state
+    bool has_chains = false;
+    kvp_anneal_params sa{};
+    uint64_t moves_done = 0;
+    uint32_t *d_X = nullptr;      // [C][L][N][Wd] current schedules
+    uint32_t *d_cnt = nullptr;    // [C][L][N][4]
+    uint32_t *d_occ = nullptr;    // [C][N]
+    ChainState *d_state = nullptr;
+    uint32_t *d_log = nullptr;    // [C][log_cap][LOG_WORDS] edits since the best schedule
+    uint64_t log_cap = 0;
+    double *d_cost = nullptr;     // [C]
+    uint32_t *d_excess = nullptr; // [C]
+    uint32_t *d_argmin = nullptr; // 1
+};
+
+// last failing HIP call of this thread: error code and source line, for kvp_last_hip_error()
+extern thread_local int kvp_tls_hip_error;
+extern thread_local int kvp_tls_hip_line;
+
+#define KVP_HIP(call)                                   \
+    do {                                                \
+        hipError_t e_ = (call);                         \
+        if (e_ != hipSuccess) {                         \
+            kvp_tls_hip_error = (int)e_;                \
+            kvp_tls_hip_line = __LINE__;                \
+            (void)hipGetLastError();                    \
+            return e_ == hipErrorOutOfMemory ? KVP_ENOMEM : KVP_EHIP; \
+        }                                               \
+    } while (0)
+
+// ---- device helpers ---------------------------------------------------------
+#if defined(__HIPCC__)
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (KVP_WAVE - 1)); }
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, KVP_WAVE);
+    return v;
+}
+__device__ __forceinline__ uint32_t wave_or_u32(uint32_t v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v |= __shfl_xor(v, o, KVP_WAVE);
+    return v;
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) { uint32_t t = __shfl_xor(v, o, KVP_WAVE); v = t > v ? t : v; }
+    return v;
+}
+// The 64-wide summation tree of the total latency: fold the upper half onto the
+// lower half (32, 16, ..., 1).  Every lane ends with the same bits because
+// a + b == b + a in IEEE arithmetic.
+__device__ __forceinline__ double wave_tree_sum_f64(double v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = v + __shfl_xor(v, o, KVP_WAVE);
+    return v;
+}
+
+// Step latency, Eqs. 2-4, from the step's counters.  hr_u: read units served by
+// HBM; hw: written pages in HBM; mi/mo: pages migrated in/out; acc_u, wr: the
+// step's totals.  Every product below is an integer < 2^53, hence exact; the
+// order of the floating-point operations is fixed (no contraction).
+__device__ __forceinline__ double step_time(const DevProblem &q, uint32_t hr_u, uint32_t hw, uint32_t mi,
+                                            uint32_t mo, uint32_t acc_u, uint32_t wr) {
+    double hr_b = (double)hr_u * q.unit_b;
+    double er_b = (double)(acc_u - hr_u) * q.unit_b;
+    double hw_b = (double)hw * q.token_b;
+    double ew_b = (double)(wr - hw) * q.token_b;
+    double mi_b = (double)mi * q.page_b;
+    double mo_b = (double)mo * q.page_b;
+    double t_h = (((hr_b + hw_b) + mi_b) + mo_b) * q.inv_bh;                 // Eq. 3
+    double link_out = (ew_b + mo_b) * q.inv_bk;
+    double link_in = mi_b * q.inv_bk;
+    double chan = ((ew_b + mi_b) + mo_b) * q.inv_bd;
+    double m = link_out > link_in ? link_out : link_in;
+    m = m > chan ? m : chan;
+    double t_e = er_b * q.inv_min + m;                                       // Eq. 4
+    return t_h > t_e ? t_h : t_e;                                            // Eq. 2
+}
+
+#endif  // __HIPCC__
+
+// ---- entry points implemented across files -----------------------------------
+int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, double *d_cost,
+                     uint32_t *d_excess, uint32_t *d_counters, uint32_t *d_occ);
+int kvp_ensure(kvp_ctx *ctx, void **p, size_t *cap, size_t bytes);
+void kvp_free_chains(kvp_ctx *ctx);

@@ -1,0 +1,627 @@
+// Moves on a placement schedule: incremental cost change, the annealing loop
+// (one wavefront per chain) and the best-so-far reduction.  gfx950 only.
+//
+// A move edits the timeline of one (layer, page) bit inside a window of at most
+// 64 token steps, so the 64 lanes of a wavefront each own one step of the
+// window: lane i <-> step base + i.  Which steps flip is decided with ballots;
+// the cost change is the 64-wide tree sum over the lanes of (t' - t), i.e. the
+// same summation tree as the total latency uses.
+#include <math.h>
+#include <string.h>
+
+#include "kvp_internal.h"
+
+#define LOG_WORDS 10   // layer, page, layer2, page2, base, flip1 lo/hi, flip2 lo/hi, spare
+#define CALIB_MOVES 256
+
+struct ChainState {
+    double t_cur, t_best, c0, c;
+    uint64_t accepted, uphill, null_moves, clipped, improved, log_len, moves_done;
+    uint32_t level, log_overflow;
+};
+
+struct SAParams {
+    uint32_t seed_lo, seed_hi;
+    uint64_t th0, th1;          // operator thresholds on a 32-bit draw
+    uint64_t mpl;               // moves per temperature level
+    uint32_t n_levels, max_len;
+    double alpha, neg_ln_p0;
+};
+
+struct MoveEval {
+    int verdict;        // uniform
+    double dT;          // uniform
+    int base;           // uniform: first step of the window
+    uint64_t flip1, flip2;
+    bool second;        // victim on another layer
+    // per lane
+    int n;              // step of this lane, -1 if outside the trace
+    bool f1, f2, touch1, touch2, xnew;
+    uint4 c1, c2;       // counters after the move of rows (layer, n) and (layer2, n)
+};
+
+__device__ __forceinline__ uint64_t ballot64(bool p) { return (uint64_t)__ballot(p); }
+__device__ __forceinline__ int ctz64(uint64_t v) { return __ffsll((unsigned long long)v) - 1; }
+__device__ __forceinline__ int msb64(uint64_t v) { return 63 - __clzll((long long)v); }
+
+// Effect on a step's counters of one page whose bit goes x_old -> x_new here and
+// xp_old -> xp_new one step earlier.
+__device__ __forceinline__ void page_effect(const DevProblem &q, uint32_t l, uint32_t n, uint32_t w, uint32_t b,
+                                            bool x_old, bool x_new, bool xp_old, bool xp_new,
+                                            int &hr, int &hw, int &mi, int &mo) {
+    if (x_old != x_new) {
+        const int s = x_new ? 1 : -1;
+        const uint32_t *a = q.A + ((size_t)l * q.N + n) * q.K * q.Wd + w;
+        int u = 0;
+        for (uint32_t k = 0; k < q.K; k++) u += (int)(q.wt[k] * ((a[(size_t)k * q.Wd] >> b) & 1u));
+        hr += s * u;
+        hw += s * (int)((q.Wm[(size_t)n * q.Wd + w] >> b) & 1u);
+    }
+    if ((q.Pm[(size_t)n * q.Wd + w] >> b) & 1u) {
+        mi += (int)(x_new && !xp_new) - (int)(x_old && !xp_old);
+        mo += (int)(!x_new && xp_new) - (int)(!x_old && xp_old);
+    }
+}
+
+// Resolve a raw move against the schedule X (with its counters and occupancy)
+// and price it.  All 64 lanes of the wavefront must call this together.
+__device__ MoveEval eval_move(const DevProblem &q, const uint32_t *X, const uint32_t *cnt, const uint32_t *occ,
+                              const kvp_move &m, int lane) {
+    MoveEval R;
+    R.verdict = KVP_MOVE_NULL; R.dT = 0.0; R.base = 0; R.flip1 = R.flip2 = 0; R.second = false;
+    R.n = -1; R.f1 = R.f2 = R.touch1 = R.touch2 = R.xnew = false;
+    R.c1 = make_uint4(0, 0, 0, 0); R.c2 = R.c1;
+    const uint32_t L = q.L, N = q.N, Wd = q.Wd, cap = q.cap;
+    if (m.op > 2 || m.layer >= L || m.page >= q.P || m.n1 >= N || m.len < 1 || m.len > KVP_MAX_LEN ||
+        m.layer2 >= L || m.page2 >= q.P)
+        return R;
+    const uint32_t l = m.layer, n1 = m.n1, len = m.len, l2 = m.layer2;
+    const uint32_t wp = m.page >> 5, bp = m.page & 31, wq = m.page2 >> 5, bq = m.page2 & 31;
+    const uint32_t *Xl = X + (size_t)l * N * Wd + wp;
+    const uint32_t *Xl2 = X + (size_t)l2 * N * Wd + wq;
+
+    int n = (int)n1 + lane;
+    bool inb = n < (int)N;
+    bool vb = inb && ((q.V[(size_t)n * Wd + wp] >> bp) & 1u);
+    bool pmb = inb && ((q.Pm[(size_t)n * Wd + wp] >> bp) & 1u);
+    bool xb = vb && ((Xl[(size_t)n * Wd] >> bp) & 1u);
+    uint32_t oc = inb ? occ[n] : 0;
+    if (!(ballot64(vb) & 1ull)) return R;                  // the page does not exist at n1
+    uint64_t xmask = ballot64(xb);
+    const bool x1 = xmask & 1ull;
+    bool f1 = false, f2 = false, clipped = false, xq = false;
+    int base = (int)n1;
+
+    if (m.op != KVP_OP_SHIFT) {
+        const bool cont = lane == 0 || (inb && (uint32_t)lane < len && pmb);
+        const uint64_t bad = ballot64(!cont);
+        const int e = bad ? ctz64(bad) : 64;
+        const bool in_span = lane < e;
+        if (m.op == KVP_OP_SET || x1) {
+            const bool v = !x1;
+            const bool differ = in_span && (xb != v);
+            if (v) {
+                const uint64_t stop = ballot64(differ && oc >= cap);
+                const int fs = stop ? ctz64(stop) : 64;
+                f1 = differ && lane < fs;
+                clipped = stop != 0;
+            } else {
+                f1 = differ;
+            }
+        } else {
+            const bool victim_ok = !(l2 == l && m.page2 == m.page);
+            xq = inb && ((q.V[(size_t)n * Wd + wq] >> bq) & 1u) && ((Xl2[(size_t)n * Wd] >> bq) & 1u);
+            const bool cand = in_span && !xb;
+            const bool room = oc < cap;
+            const bool evict = cand && !room && victim_ok && xq;
+            f1 = cand && (room || evict);
+            f2 = evict;
+            clipped = ballot64(cand && !room && !evict) != 0;
+        }
+    } else {
+        const bool cont = lane == 0 || (inb && (uint32_t)lane <= len && pmb);
+        const uint64_t bad = ballot64(!cont);
+        const int e = bad ? ctz64(bad) : 64;
+        const bool xprev = lane > 0 && ((xmask >> (lane - 1)) & 1ull);
+        const uint64_t tm = ballot64(lane >= 1 && lane < e && xb != xprev);
+        if (!tm) return R;                                  // constant timeline: nothing to shift
+        const int it = ctz64(tm);
+        const int nt = (int)n1 + it;
+        const bool a = (xmask >> (it - 1)) & 1ull;
+        const int d = (m.dsel & 2u) ? (int)(m.dsel & 1u) + 1 : (int)(m.dsel & 1u) - 2;   // -2,-1,+1,+2
+        base = nt - 2;
+        // re-map the lanes onto the five steps around the edge
+        n = base + lane;
+        inb = lane < 5 && n >= 0 && n < (int)N;
+        vb = inb && ((q.V[(size_t)n * Wd + wp] >> bp) & 1u);
+        pmb = inb && ((q.Pm[(size_t)n * Wd + wp] >> bp) & 1u);
+        xb = vb && ((Xl[(size_t)n * Wd] >> bp) & 1u);
+        oc = inb ? occ[n] : 0;
+        xmask = ballot64(xb);
+        if (d < 0) {
+            const bool target = lane == 1 || (lane == 0 && d == -2 && it >= 2);   // steps hold a, take not(a)
+            if (!a) {
+                const uint64_t full = ballot64(target && oc >= cap);
+                const int hs = full ? msb64(full) : -1;
+                f1 = target && lane > hs;
+                clipped = full != 0;
+            } else {
+                f1 = target;
+            }
+        } else {
+            const bool target = lane == 2 || (lane == 3 && d == 2 && inb && pmb);
+            const bool differ = target && (xb != a);
+            if (a) {
+                const uint64_t stop = ballot64(differ && oc >= cap);
+                const int fs = stop ? ctz64(stop) : 64;
+                f1 = differ && lane < fs;
+                clipped = stop != 0;
+            } else {
+                f1 = differ;
+            }
+        }
+    }
+    const uint64_t flip1 = ballot64(f1), flip2 = ballot64(f2);
+    if (!flip1) return R;
+
+    // ---- cost change over the window [base, base + 64) -------------------------
+    const bool same_layer = l2 == l;
+    const bool fp1 = lane > 0 && ((flip1 >> (lane - 1)) & 1ull);
+    const bool fp2 = lane > 0 && ((flip2 >> (lane - 1)) & 1ull);
+    bool xp = lane > 0 && ((xmask >> (lane - 1)) & 1ull);          // bit of the page one step earlier
+    if (lane == 0 && base >= 1 && inb) {
+        const size_t o = (size_t)(base - 1) * Wd;
+        xp = ((q.V[o + wp] >> bp) & 1u) && ((Xl[o] >> bp) & 1u);
+    }
+    bool xqp = false;
+    if (flip2) {
+        const uint64_t qmask = ballot64(xq);
+        xqp = lane > 0 && ((qmask >> (lane - 1)) & 1ull);
+        if (lane == 0 && base >= 1 && inb) {
+            const size_t o = (size_t)(base - 1) * Wd;
+            xqp = ((q.V[o + wq] >> bq) & 1u) && ((Xl2[o] >> bq) & 1u);
+        }
+    }
+    double dd = 0.0;
+    const bool touch1 = inb && (f1 || fp1 || (same_layer && (f2 || fp2)));
+    if (touch1) {
+        const size_t row = (size_t)l * N + n;
+        const uint4 c = *(const uint4 *)(cnt + row * 4);
+        const uint32_t acc = q.acc[row], wr = q.wr[n];
+        const double t_old = step_time(q, c.x, c.y, c.z, c.w, acc, wr);
+        int hr = (int)c.x, hw = (int)c.y, mi = (int)c.z, mo = (int)c.w;
+        page_effect(q, l, (uint32_t)n, wp, bp, xb, xb != f1, xp, xp != fp1, hr, hw, mi, mo);
+        if (same_layer && (f2 || fp2))
+            page_effect(q, l, (uint32_t)n, wq, bq, xq, xq != f2, xqp, xqp != fp2, hr, hw, mi, mo);
+        R.c1 = make_uint4((uint32_t)hr, (uint32_t)hw, (uint32_t)mi, (uint32_t)mo);
+        dd = step_time(q, R.c1.x, R.c1.y, R.c1.z, R.c1.w, acc, wr) - t_old;
+    }
+    double dT = wave_tree_sum_f64(dd);
+    const bool second = flip2 != 0 && !same_layer;
+    bool touch2 = false;
+    if (second) {
+        dd = 0.0;
+        touch2 = inb && (f2 || fp2);
+        if (touch2) {
+            const size_t row = (size_t)l2 * N + n;
+            const uint4 c = *(const uint4 *)(cnt + row * 4);
+            const uint32_t acc = q.acc[row], wr = q.wr[n];
+            const double t_old = step_time(q, c.x, c.y, c.z, c.w, acc, wr);
+            int hr = (int)c.x, hw = (int)c.y, mi = (int)c.z, mo = (int)c.w;
+            page_effect(q, l2, (uint32_t)n, wq, bq, xq, xq != f2, xqp, xqp != fp2, hr, hw, mi, mo);
+            R.c2 = make_uint4((uint32_t)hr, (uint32_t)hw, (uint32_t)mi, (uint32_t)mo);
+            dd = step_time(q, R.c2.x, R.c2.y, R.c2.z, R.c2.w, acc, wr) - t_old;
+        }
+        dT = dT + wave_tree_sum_f64(dd);
+    }
+    R.verdict = clipped ? KVP_MOVE_CLIPPED : KVP_MOVE_OK;
+    R.dT = dT; R.base = base; R.flip1 = flip1; R.flip2 = flip2; R.second = second;
+    R.n = inb ? n : -1; R.f1 = f1; R.f2 = f2; R.touch1 = touch1; R.touch2 = touch2; R.xnew = xb != f1;
+    return R;
+}
+
+// ---- kvp_delta_score -----------------------------------------------------------
+__global__ __launch_bounds__(256) void delta_kernel(DevProblem q, const uint32_t *__restrict__ X, uint32_t S,
+                                                    const kvp_move *__restrict__ moves,
+                                                    const uint32_t *__restrict__ cnt,
+                                                    const uint32_t *__restrict__ occ, double *__restrict__ delta,
+                                                    int32_t *__restrict__ verdict) {
+    const uint32_t s = blockIdx.x * (blockDim.x / KVP_WAVE) + threadIdx.x / KVP_WAVE;
+    if (s >= S) return;                                    // whole wavefronts leave together
+    const int lane = lane_id();
+    const size_t rows = (size_t)q.L * q.N;
+    kvp_move m = moves[s];
+    const MoveEval R = eval_move(q, X + (size_t)s * rows * q.Wd, cnt + (size_t)s * rows * 4,
+                                 occ + (size_t)s * q.N, m, lane);
+    if (lane == 0) { delta[s] = R.dT; verdict[s] = R.verdict; }
+}
+
+extern "C" int kvp_delta_score(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, const kvp_move *d_moves,
+                               const uint32_t *d_counters, const uint32_t *d_occ, double *d_delta,
+                               int32_t *d_verdict) {
+    if (!ctx) return KVP_EINVAL;
+    if (!ctx->has_trace) return KVP_ENOTRACE;
+    if (S == 0) return KVP_OK;
+    if (!d_placements || !d_moves || !d_delta || !d_verdict) return KVP_EINVAL;
+    if (((uintptr_t)d_placements & 15u) || ((uintptr_t)d_counters & 15u) || ((uintptr_t)d_moves & 3u) ||
+        ((uintptr_t)d_delta & 7u) || ((uintptr_t)d_verdict & 3u) || ((uintptr_t)d_occ & 3u))
+        return KVP_EINVAL;
+    KVP_HIP(hipSetDevice(ctx->device));
+    const DevProblem &q = ctx->dp;
+    if (!d_counters || !d_occ) {
+        // no counters from the caller: one scoring pass produces them
+        int rc;
+        const size_t rows = (size_t)q.L * q.N;
+        if ((rc = kvp_ensure(ctx, (void **)&ctx->d_cnt_tmp, &ctx->cnt_tmp_cap, (size_t)S * rows * 16 + (size_t)S * 16))) return rc;
+        if ((rc = kvp_ensure(ctx, (void **)&ctx->d_occ_tmp, &ctx->occ_tmp_cap, (size_t)S * q.N * 4))) return rc;
+        // cost/excess of that pass are not wanted: park them behind the counters
+        double *junk_cost = (double *)(ctx->d_cnt_tmp + (size_t)S * rows * 4);
+        uint32_t *junk_ex = (uint32_t *)(junk_cost + S);
+        if ((rc = kvp_score_launch(ctx, d_placements, S, junk_cost, junk_ex, ctx->d_cnt_tmp, ctx->d_occ_tmp))) return rc;
+        d_counters = ctx->d_cnt_tmp; d_occ = ctx->d_occ_tmp;
+    }
+    delta_kernel<<<dim3((S + 3) / 4), dim3(256), 0, ctx->stream>>>(q, d_placements, S, d_moves, d_counters, d_occ,
+                                                                  d_delta, d_verdict);
+    KVP_HIP(hipGetLastError());
+    return KVP_OK;
+}
+
+// ---- Philox4x32-10 (Salmon et al., SC'11), counter-based ----------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+    for (int r = 0; r < 10; r++) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t t0 = hi1 ^ c1 ^ k0, t2 = hi0 ^ c3 ^ k1;
+        c0 = t0; c1 = lo1; c2 = t2; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Proposal number `mi` of chain `chain`: three Philox blocks on counters
+// (mi, chain, stream0 + {0,1,2}).  u is uniform on (0,1) with 52 random bits.
+__device__ __forceinline__ void draw_move(const DevProblem &q, const SAParams &sp, uint32_t chain, uint64_t mi,
+                                          uint32_t stream0, kvp_move &m, double &u) {
+    uint32_t a[4], b[4], c[4];
+    philox4x32_10((uint32_t)mi, (uint32_t)(mi >> 32), chain, stream0, sp.seed_lo, sp.seed_hi, a);
+    philox4x32_10((uint32_t)mi, (uint32_t)(mi >> 32), chain, stream0 + 1, sp.seed_lo, sp.seed_hi, b);
+    philox4x32_10((uint32_t)mi, (uint32_t)(mi >> 32), chain, stream0 + 2, sp.seed_lo, sp.seed_hi, c);
+    m.op = ((uint64_t)a[0] < sp.th0) ? KVP_OP_SET : ((uint64_t)a[0] < sp.th1) ? KVP_OP_SWAP : KVP_OP_SHIFT;
+    m.layer = __umulhi(a[1], q.L);
+    m.page = __umulhi(a[2], q.P);
+    m.n1 = __umulhi(a[3], q.N);
+    m.len = 1 + __umulhi(b[0], sp.max_len);
+    m.layer2 = __umulhi(b[1], q.L);
+    m.page2 = __umulhi(b[2], q.P);
+    m.dsel = b[3] >> 30;
+    const uint64_t bits = ((uint64_t)c[0] << 20) | (uint64_t)(c[1] >> 12);
+    u = ((double)bits + 0.5) * (1.0 / 4503599627370496.0);
+}
+
+// ---- the annealing loop: one wavefront per chain --------------------------------
+__global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams sp, uint32_t *__restrict__ Xall,
+                                                          uint32_t *__restrict__ cnt_all,
+                                                          uint32_t *__restrict__ occ_all,
+                                                          ChainState *__restrict__ states,
+                                                          uint32_t *__restrict__ log_all, uint64_t log_cap,
+                                                          uint64_t move_begin, uint64_t move_end, int calibrate) {
+    const uint32_t chain = blockIdx.x;
+    const int lane = (int)threadIdx.x;
+    const size_t rows = (size_t)q.L * q.N;
+    uint32_t *X = Xall + (size_t)chain * rows * q.Wd;
+    uint32_t *cnt = cnt_all + (size_t)chain * rows * 4;
+    uint32_t *occ = occ_all + (size_t)chain * q.N;
+    uint32_t *log = log_all + (size_t)chain * log_cap * LOG_WORDS;
+    ChainState st = states[chain];
+
+    if (calibrate) {
+        // initial temperature from the target acceptance p0 of uphill moves:
+        // C0 = mean(dT | dT > 0) / (-ln p0) over proposals that are not applied
+        double sum = 0.0;
+        uint32_t k = 0;
+        for (uint64_t j = 0; j < CALIB_MOVES; j++) {
+            kvp_move m; double u;
+            draw_move(q, sp, chain, j, 8, m, u);
+            const MoveEval R = eval_move(q, X, cnt, occ, m, lane);
+            if (R.verdict != KVP_MOVE_NULL && R.dT > 0.0) { sum = sum + R.dT; k++; }
+        }
+        st.c0 = k ? (sum / (double)k) / sp.neg_ln_p0 : 0.0;
+        st.c = st.c0;
+        st.level = 0;
+    }
+
+    for (uint64_t mi = move_begin; mi < move_end; mi++) {
+        uint64_t lvl = mi / sp.mpl;
+        if (lvl > sp.n_levels - 1) lvl = sp.n_levels - 1;
+        while (st.level < lvl) { st.c = st.c * sp.alpha; st.level++; }      // geometric cooling
+        kvp_move m; double u;
+        draw_move(q, sp, chain, mi, 0, m, u);
+        const MoveEval R = eval_move(q, X, cnt, occ, m, lane);
+        st.moves_done++;
+        if (R.verdict == KVP_MOVE_NULL) { st.null_moves++; continue; }
+        if (R.verdict == KVP_MOVE_CLIPPED) st.clipped++;
+        const bool accept = (R.dT <= 0.0) || (st.c > 0.0 && u < exp(-R.dT / st.c));   // Metropolis
+        if (!accept) continue;
+        st.accepted++;
+        if (R.dT > 0.0) st.uphill++;
+        // apply: every lane owns one step of the window, so no two lanes write the same word
+        if (R.f1) {
+            const size_t o = ((size_t)m.layer * q.N + R.n) * q.Wd + (m.page >> 5);
+            X[o] ^= 1u << (m.page & 31);
+        }
+        if (R.f2) {
+            const size_t o = ((size_t)m.layer2 * q.N + R.n) * q.Wd + (m.page2 >> 5);
+            X[o] ^= 1u << (m.page2 & 31);
+        }
+        if (R.touch1) *(uint4 *)(cnt + ((size_t)m.layer * q.N + R.n) * 4) = R.c1;
+        if (R.touch2) *(uint4 *)(cnt + ((size_t)m.layer2 * q.N + R.n) * 4) = R.c2;
+        if (R.f1 && !R.f2) occ[R.n] += R.xnew ? 1u : 0xFFFFFFFFu;
+        st.t_cur = st.t_cur + R.dT;
+        // edits since the best schedule, so that it can be rebuilt by undoing them
+        if (st.log_len < log_cap) {
+            if (lane < LOG_WORDS) {
+                uint32_t w;
+                switch (lane) {
+                    case 0: w = m.layer; break;
+                    case 1: w = m.page; break;
+                    case 2: w = m.layer2; break;
+                    case 3: w = m.page2; break;
+                    case 4: w = (uint32_t)R.base; break;
+                    case 5: w = (uint32_t)R.flip1; break;
+                    case 6: w = (uint32_t)(R.flip1 >> 32); break;
+                    case 7: w = (uint32_t)R.flip2; break;
+                    case 8: w = (uint32_t)(R.flip2 >> 32); break;
+                    default: w = 0; break;
+                }
+                log[st.log_len * LOG_WORDS + lane] = w;
+            }
+            st.log_len++;
+        } else {
+            st.log_overflow = 1;
+        }
+        if (st.t_cur < st.t_best) { st.t_best = st.t_cur; st.improved++; st.log_len = 0; }
+        // the next proposal may read, from other lanes, what this one wrote
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    }
+    if (lane == 0) states[chain] = st;
+}
+
+// Apply (or, applied twice, undo) every logged edit of every chain: XOR commutes,
+// so one wavefront per log entry and atomics on the words are enough.
+__global__ __launch_bounds__(256) void log_xor_kernel(DevProblem q, uint32_t *__restrict__ Xall,
+                                                      const ChainState *__restrict__ states,
+                                                      const uint32_t *__restrict__ log_all, uint64_t log_cap,
+                                                      uint32_t chain0) {
+    const uint32_t chain = chain0 + blockIdx.y;
+    const int lane = lane_id();
+    const uint64_t n_entries = states[chain].log_len;
+    const size_t rows = (size_t)q.L * q.N;
+    uint32_t *X = Xall + (size_t)chain * rows * q.Wd;
+    const uint32_t *log = log_all + (size_t)chain * log_cap * LOG_WORDS;
+    const uint64_t wave0 = (uint64_t)blockIdx.x * (blockDim.x / KVP_WAVE) + threadIdx.x / KVP_WAVE;
+    const uint64_t nwaves = (uint64_t)gridDim.x * (blockDim.x / KVP_WAVE);
+    for (uint64_t e = wave0; e < n_entries; e += nwaves) {
+        const uint32_t *r = log + e * LOG_WORDS;
+        const uint32_t l = r[0], p = r[1], l2 = r[2], pq = r[3];
+        const int n = (int)r[4] + lane;
+        const uint64_t f1 = (uint64_t)r[5] | ((uint64_t)r[6] << 32), f2 = (uint64_t)r[7] | ((uint64_t)r[8] << 32);
+        if (n < 0 || n >= (int)q.N) continue;
+        if ((f1 >> lane) & 1ull) atomicXor(&X[((size_t)l * q.N + n) * q.Wd + (p >> 5)], 1u << (p & 31));
+        if ((f2 >> lane) & 1ull) atomicXor(&X[((size_t)l2 * q.N + n) * q.Wd + (pq >> 5)], 1u << (pq & 31));
+    }
+}
+
+__global__ void init_states_kernel(ChainState *states, const double *cost, uint32_t C) {
+    const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    ChainState s;
+    memset(&s, 0, sizeof s);
+    s.t_cur = cost[c]; s.t_best = cost[c];
+    states[c] = s;
+}
+
+// Starting schedules: copy (one per chain, or one for all) and keep existing pages only.
+__global__ __launch_bounds__(256) void init_copy_kernel(DevProblem q, uint32_t *__restrict__ X,
+                                                        const uint32_t *__restrict__ src, uint32_t C, int broadcast) {
+    const size_t per = (size_t)q.L * q.N * q.Wd;
+    const size_t total = per * C;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t j = i % per;
+        const size_t nw = j % ((size_t)q.N * q.Wd);
+        X[i] = src[broadcast ? j : i] & q.V[nw];
+    }
+}
+
+// Lowest cost, ties to the lowest chain id.  One workgroup.
+__global__ __launch_bounds__(256) void argmin_kernel(const double *__restrict__ cost, uint32_t C,
+                                                     uint32_t *__restrict__ out) {
+    __shared__ double sv[256];
+    __shared__ uint32_t si[256];
+    double bv = INFINITY; uint32_t bi = 0xFFFFFFFFu;
+    for (uint32_t c = threadIdx.x; c < C; c += blockDim.x) {
+        const double v = cost[c];
+        if (v < bv || (v == bv && c < bi)) { bv = v; bi = c; }
+    }
+    sv[threadIdx.x] = bv; si[threadIdx.x] = bi;
+    __syncthreads();
+    for (uint32_t h = 128; h >= 1; h >>= 1) {
+        if (threadIdx.x < h) {
+            const double v = sv[threadIdx.x + h]; const uint32_t i = si[threadIdx.x + h];
+            if (v < sv[threadIdx.x] || (v == sv[threadIdx.x] && i < si[threadIdx.x])) { sv[threadIdx.x] = v; si[threadIdx.x] = i; }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = si[0] == 0xFFFFFFFFu ? 0u : si[0];
+}
+
+static bool same_schedule(const kvp_anneal_params &a, const kvp_anneal_params &b) {
+    return a.n_chains == b.n_chains && a.n_levels == b.n_levels && a.seed == b.seed &&
+           a.total_moves == b.total_moves && a.max_len == b.max_len && a.p0 == b.p0 && a.alpha == b.alpha &&
+           a.op_prob[0] == b.op_prob[0] && a.op_prob[1] == b.op_prob[1] && a.op_prob[2] == b.op_prob[2];
+}
+
+static int launch_log_xor(kvp_ctx *ctx, uint32_t chain0, uint32_t nchains) {
+    log_xor_kernel<<<dim3(64, nchains), dim3(256), 0, ctx->stream>>>(ctx->dp, ctx->d_X, ctx->d_state, ctx->d_log,
+                                                                    ctx->log_cap, chain0);
+    KVP_HIP(hipGetLastError());
+    return KVP_OK;
+}
+
+extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32_t *d_init) {
+    if (!ctx || !p) return KVP_EINVAL;
+    if (!ctx->has_trace) return KVP_ENOTRACE;
+    if (p->n_chains == 0 || p->n_chains > 65535u * 16u || p->n_levels == 0 || p->max_len < 1 ||
+        p->max_len > KVP_MAX_LEN || !(p->p0 > 0.0 && p->p0 < 1.0) || !(p->alpha > 0.0 && p->alpha <= 1.0) ||
+        p->init_mode > KVP_INIT_CONTINUE || p->total_moves == 0)
+        return KVP_EINVAL;
+    double ps = 0.0;
+    for (int i = 0; i < 3; i++) { if (!(p->op_prob[i] >= 0.0)) return KVP_EINVAL; ps += p->op_prob[i]; }
+    if (!(ps > 0.0 && ps <= 1.0 + 1e-9)) return KVP_EINVAL;
+    if ((p->init_mode == KVP_INIT_GIVEN || p->init_mode == KVP_INIT_BROADCAST) &&
+        (!d_init || ((uintptr_t)d_init & 15u)))
+        return KVP_EINVAL;
+    KVP_HIP(hipSetDevice(ctx->device));
+    const DevProblem &q = ctx->dp;
+    const uint32_t C = p->n_chains;
+    const size_t rows = (size_t)q.L * q.N, per = rows * q.Wd;
+
+    if (p->init_mode == KVP_INIT_CONTINUE) {
+        if (!ctx->has_chains) return KVP_ENOCHAINS;
+        if (!same_schedule(*p, ctx->sa)) return KVP_EINVAL;
+    } else {
+        KVP_HIP(hipStreamSynchronize(ctx->stream));
+        kvp_free_chains(ctx);
+        ctx->log_cap = p->total_moves;
+        KVP_HIP(hipMalloc((void **)&ctx->d_X, per * C * 4));
+        KVP_HIP(hipMalloc((void **)&ctx->d_cnt, rows * C * 16));
+        KVP_HIP(hipMalloc((void **)&ctx->d_occ, (size_t)q.N * C * 4));
+        KVP_HIP(hipMalloc((void **)&ctx->d_state, sizeof(ChainState) * C));
+        KVP_HIP(hipMalloc((void **)&ctx->d_log, (size_t)ctx->log_cap * C * LOG_WORDS * 4));
+        KVP_HIP(hipMalloc((void **)&ctx->d_cost, sizeof(double) * C));
+        KVP_HIP(hipMalloc((void **)&ctx->d_excess, 4 * (size_t)C));
+        KVP_HIP(hipMalloc((void **)&ctx->d_argmin, 16));
+        if (p->init_mode == KVP_INIT_EMPTY) {
+            KVP_HIP(hipMemsetAsync(ctx->d_X, 0, per * C * 4, ctx->stream));
+        } else {
+            init_copy_kernel<<<dim3(2048), dim3(256), 0, ctx->stream>>>(q, ctx->d_X, d_init, C,
+                                                                       p->init_mode == KVP_INIT_BROADCAST);
+            KVP_HIP(hipGetLastError());
+        }
+        int rc = kvp_score_launch(ctx, ctx->d_X, C, ctx->d_cost, ctx->d_excess, ctx->d_cnt, ctx->d_occ);
+        if (rc) { kvp_free_chains(ctx); return rc; }
+        uint32_t *hex = (uint32_t *)malloc(4 * (size_t)C);
+        if (!hex) { kvp_free_chains(ctx); return KVP_ENOMEM; }
+        hipError_t e = hipMemcpyAsync(hex, ctx->d_excess, 4 * (size_t)C, hipMemcpyDeviceToHost, ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        bool bad = false;
+        for (uint32_t c = 0; c < C && e == hipSuccess; c++) bad = bad || (hex[c] & 0x7FFFFFFFu) != 0;
+        free(hex);
+        if (e != hipSuccess) { kvp_free_chains(ctx); return KVP_EHIP; }
+        if (bad) { kvp_free_chains(ctx); return KVP_EINFEASIBLE; }
+        init_states_kernel<<<dim3((C + 255) / 256), dim3(256), 0, ctx->stream>>>(ctx->d_state, ctx->d_cost, C);
+        KVP_HIP(hipGetLastError());
+        ctx->sa = *p;
+        ctx->moves_done = 0;
+        ctx->has_chains = true;
+    }
+    if (ctx->moves_done + p->moves > p->total_moves) return KVP_EINVAL;
+
+    SAParams sp;
+    sp.seed_lo = (uint32_t)p->seed; sp.seed_hi = (uint32_t)(p->seed >> 32);
+    sp.th0 = (uint64_t)(p->op_prob[0] * 4294967296.0);
+    sp.th1 = (uint64_t)((p->op_prob[0] + p->op_prob[1]) * 4294967296.0);
+    sp.mpl = p->total_moves / p->n_levels; if (sp.mpl < 1) sp.mpl = 1;
+    sp.n_levels = p->n_levels; sp.max_len = p->max_len;
+    sp.alpha = p->alpha; sp.neg_ln_p0 = -log(p->p0);
+    // bounded launches: every wavefront runs a fixed number of moves and exits
+    const uint64_t chunk = 16384;
+    uint64_t m0 = ctx->moves_done;
+    const uint64_t m_end = m0 + p->moves;
+    bool first = ctx->moves_done == 0;
+    if (p->moves == 0 && first) {
+        anneal_kernel<<<dim3(C), dim3(KVP_WAVE), 0, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
+                                                                 ctx->d_log, ctx->log_cap, 0, 0, 1);
+        KVP_HIP(hipGetLastError());
+    }
+    while (m0 < m_end) {
+        const uint64_t m1 = m0 + chunk < m_end ? m0 + chunk : m_end;
+        anneal_kernel<<<dim3(C), dim3(KVP_WAVE), 0, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
+                                                                 ctx->d_log, ctx->log_cap, m0, m1, first ? 1 : 0);
+        KVP_HIP(hipGetLastError());
+        first = false;
+        m0 = m1;
+    }
+    ctx->moves_done = m_end;
+    return KVP_OK;
+}
+
+extern "C" int kvp_best(kvp_ctx *ctx, double *h_cost, uint32_t *h_chain, uint32_t *h_placement,
+                        double *h_chain_costs) {
+    if (!ctx || !h_cost || !h_chain) return KVP_EINVAL;
+    if (!ctx->has_trace) return KVP_ENOTRACE;
+    if (!ctx->has_chains) return KVP_ENOCHAINS;
+    KVP_HIP(hipSetDevice(ctx->device));
+    const DevProblem &q = ctx->dp;
+    const uint32_t C = ctx->sa.n_chains;
+    const size_t per = (size_t)q.L * q.N * q.Wd;
+    int rc;
+    if ((rc = launch_log_xor(ctx, 0, C))) return rc;                       // current -> best-so-far schedules
+    rc = kvp_score_launch(ctx, ctx->d_X, C, ctx->d_cost, ctx->d_excess, nullptr, nullptr);   // exact re-score
+    if (!rc) {
+        argmin_kernel<<<dim3(1), dim3(256), 0, ctx->stream>>>(ctx->d_cost, C, ctx->d_argmin);
+        if (hipGetLastError() != hipSuccess) rc = KVP_EHIP;
+    }
+    uint32_t win = 0;
+    if (!rc && hipMemcpyAsync(&win, ctx->d_argmin, 4, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess) rc = KVP_EHIP;
+    if (!rc && hipStreamSynchronize(ctx->stream) != hipSuccess) rc = KVP_EHIP;
+    if (!rc && hipMemcpyAsync(h_cost, ctx->d_cost + win, 8, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess) rc = KVP_EHIP;
+    if (!rc && h_placement &&
+        hipMemcpyAsync(h_placement, ctx->d_X + (size_t)win * per, per * 4, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess)
+        rc = KVP_EHIP;
+    if (!rc && h_chain_costs &&
+        hipMemcpyAsync(h_chain_costs, ctx->d_cost, 8 * (size_t)C, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess)
+        rc = KVP_EHIP;
+    const int rc2 = launch_log_xor(ctx, 0, C);                             // back to the current schedules
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess && !rc) rc = KVP_EHIP;
+    *h_chain = win;
+    return rc ? rc : rc2;
+}
+
+extern "C" int kvp_chain_placement(kvp_ctx *ctx, uint32_t chain, int best, uint32_t *h_placement) {
+    if (!ctx || !h_placement) return KVP_EINVAL;
+    if (!ctx->has_chains) return KVP_ENOCHAINS;
+    if (chain >= ctx->sa.n_chains) return KVP_EINVAL;
+    KVP_HIP(hipSetDevice(ctx->device));
+    const DevProblem &q = ctx->dp;
+    const size_t per = (size_t)q.L * q.N * q.Wd;
+    int rc = KVP_OK;
+    if (best && (rc = launch_log_xor(ctx, chain, 1))) return rc;
+    if (hipMemcpyAsync(h_placement, ctx->d_X + (size_t)chain * per, per * 4, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess)
+        rc = KVP_EHIP;
+    int rc2 = KVP_OK;
+    if (best) rc2 = launch_log_xor(ctx, chain, 1);
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess && !rc) rc = KVP_EHIP;
+    return rc ? rc : rc2;
+}
+
+extern "C" int kvp_chain_stats(kvp_ctx *ctx, kvp_chain_stats_t *h_stats) {
+    if (!ctx || !h_stats) return KVP_EINVAL;
+    if (!ctx->has_chains) return KVP_ENOCHAINS;
+    KVP_HIP(hipSetDevice(ctx->device));
+    const uint32_t C = ctx->sa.n_chains;
+    ChainState *h = (ChainState *)malloc(sizeof(ChainState) * C);
+    if (!h) return KVP_ENOMEM;
+    hipError_t e = hipMemcpyAsync(h, ctx->d_state, sizeof(ChainState) * C, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) { free(h); (void)hipGetLastError(); return KVP_EHIP; }
+    for (uint32_t c = 0; c < C; c++) {
+        h_stats[c].t_cur = h[c].t_cur; h_stats[c].t_best = h[c].t_best; h_stats[c].c0 = h[c].c0; h_stats[c].c = h[c].c;
+        h_stats[c].moves_done = h[c].moves_done; h_stats[c].accepted = h[c].accepted; h_stats[c].uphill = h[c].uphill;
+        h_stats[c].null_moves = h[c].null_moves; h_stats[c].clipped = h[c].clipped; h_stats[c].improved = h[c].improved;
+    }
+    free(h);
+    return KVP_OK;
+}

@@ -1,0 +1,246 @@
+"""Parity of the HIP path (through the C-ABI) with the CPU oracle.
+
+Integer outputs (counters, occupancy, excess, verdicts) and the fp64 costs and
+cost changes must be identical bit for bit: byte counts are exact integers and
+the order of every floating-point operation is part of the definition.
+The annealer's best objective must land within 0.5 % of the oracle's at equal
+move budget; identical walks are expected but only reported.
+"""
+import numpy as np
+import pytest
+
+import oracle as O
+import workloads as W
+from workloads.traces import Trace
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    from gpu_util import Gpu
+    return Gpu
+
+
+def _cases():
+    yield "tiny", W.config("tiny")
+    yield "table1", W.config("table1")
+    yield "llama8b/4", W.config("llama8b", 0.25)                 # Wd = 3, L = 8
+    yield "longctx/8", W.config("longctx", 0.125)                # jump drift
+    yield "serving/16", W.config("serving", 0.0625)              # slots turn over, several writes per step
+    yield "gqa70b/16", W.config("gqa70b", 0.0625)                # 8 planes
+    yield "rand-odd", W.random_trace(11, L=3, N=37, P=70, K=1)   # ragged: 70 pages, 37 steps, 3 layers
+    yield "rand-wide", W.random_trace(12, L=5, N=21, P=2250, K=1)          # rows wider than a wavefront
+    yield "rand-weights", W.random_trace(13, L=2, N=50, P=100, K=3,
+                                         plane_bytes=[4096, 8192, 53248])  # unequal plane weights
+    yield "one-step", W.random_trace(14, L=1, N=1, P=33, K=1)
+
+
+CASES = list(_cases())
+
+
+@pytest.mark.parametrize("name,tr", CASES, ids=[c[0] for c in CASES])
+def test_score_matches_oracle_bit_for_bit(G, name, tr):
+    from gpu_util import expected_counters
+    X = np.concatenate([W.random_placements(tr, 5, seed=1, density=0.4),
+                        W.random_placements(tr, 2, seed=2, density=0.9, feasible=False),
+                        W.edge_placements(tr)])
+    q = O.Problem(tr)
+    with G(tr) as g:
+        cost, ex, cnt, occ = g.score(X)
+        cost2, ex2, _, _ = g.score(X, counters=False)
+        for s in range(X.shape[0]):
+            r = O.score(q, X[s])
+            assert cost[s] == r.cost, (name, s, cost[s], r.cost)
+            assert ex[s] == r.excess, (name, s)
+            assert (occ[s] == r.occ).all()
+            assert (cnt[s].astype(np.uint64) == expected_counters(r, tr, g.unit)).all()
+        assert (cost2 == cost).all() and (ex2 == ex).all()
+
+
+def test_score_every_schedule_of_a_micro_instance(G):
+    tr = W.random_trace(3, L=2, N=3, P=3)
+    tr.cap_pages = 3
+    pos = [(l, n, p) for l in range(2) for n in range(3) for p in range(3) if tr.alive[n, p]]
+    assert 8 <= len(pos) <= 16
+    S = 1 << len(pos)
+    X = np.zeros((S, 2, 3, 3), np.uint8)
+    for i, (l, n, p) in enumerate(pos):
+        X[:, l, n, p] = (np.arange(S) >> i) & 1
+    q = O.Problem(tr)
+    want = np.array([O.score(q, x).cost for x in X])
+    wex = np.array([O.score(q, x).excess for x in X], dtype=np.uint32)
+    with G(tr) as g:
+        cost, ex, _, _ = g.score(X, counters=False)
+    assert (cost == want).all() and (ex == wex).all()
+    best, _, nf = O.brute_force(tr)
+    assert cost[ex == 0].min() == best and int((ex == 0).sum()) == nf
+
+
+@pytest.mark.parametrize("name,tr", [c for c in CASES if c[0] in
+                                     ("tiny", "table1", "llama8b/4", "serving/16", "gqa70b/16", "rand-odd",
+                                      "rand-weights")],
+                         ids=lambda v: v if isinstance(v, str) else "")
+@pytest.mark.parametrize("given", [True, False])
+def test_delta_matches_oracle_bit_for_bit(G, name, tr, given):
+    S = 96
+    X = W.random_placements(tr, 6, seed=5, density=0.5)
+    X = X[np.arange(S) % 6]
+    mv = W.random_moves(tr, S, seed=9, max_len=63)
+    mv["len"][::5] = 1 + (mv["len"][::5] % 4)          # short spans too
+    mv["op"][-1] = 7                                    # malformed records are null moves
+    mv["len"][-2] = 64
+    q = O.Problem(tr)
+    with G(tr) as g:
+        d, v = g.delta(X, mv, give_counters=given)
+    kinds = set()
+    for s in range(S):
+        m = {k: int(a[s]) for k, a in mv.items()}
+        ov, od, _, _, _ = O.delta(q, X[s], m)
+        assert v[s] == ov, (name, s, m)
+        assert d[s] == od, (name, s, m, d[s], od)
+        kinds.add(ov)
+    assert {0, 2} <= kinds
+
+
+def _anneal_gpu(g, tr, chains, total, moves=None, init=None, seed=0, mode=None, **kw):
+    import paper_2508_13231_amd as K
+    if mode is None:
+        mode = K.KVP_INIT_EMPTY if init is None else K.KVP_INIT_BROADCAST
+    p = K.make_anneal_params(chains, total, moves=moves, seed=seed, init_mode=mode, **kw)
+    d_init = None if init is None else g.words(init)
+    K.kvp_anneal(g.ctx, p, d_init)
+    return p
+
+
+@pytest.mark.parametrize("name,scale,chains,total,max_len", [("tiny", 1.0, 6, 4000, 63),
+                                                             ("table1", 1.0, 4, 2000, 5),
+                                                             ("llama8b", 0.125, 4, 3000, 63),
+                                                             ("serving", 0.0625, 4, 3000, 31),
+                                                             ("gqa70b", 0.0625, 3, 3000, 63)])
+def test_anneal_against_oracle_at_equal_budget(G, name, scale, chains, total, max_len):
+    import paper_2508_13231_amd as K
+    tr = W.config(name, scale)
+    q = O.Problem(tr)
+    X0 = O.init_static_frequency(q) if name != "table1" else np.zeros(q.shape, np.uint8)
+    res, bi = O.anneal(q, range(chains), X0, seed=tr.seed, total_moves=total, max_len=max_len)
+    with G(tr) as g:
+        _anneal_gpu(g, tr, chains, total, init=X0, seed=tr.seed, max_len=max_len)
+        cost, chain, words, cc = K.kvp_best(g.ctx, g.shape_words, chains)
+        stats = K.kvp_chain_stats(g.ctx, chains)
+        bests = [g.unpack(K.kvp_chain_placement(g.ctx, c, 1, g.shape_words)) for c in range(chains)]
+        curs = [g.unpack(K.kvp_chain_placement(g.ctx, c, 0, g.shape_words)) for c in range(chains)]
+    # every returned schedule is admissible and its reported cost is the oracle's, exactly
+    for c in range(chains):
+        sb = O.score(q, bests[c])
+        assert sb.excess == 0 and sb.cost == cc[c]
+        assert O.score(q, curs[c]).excess == 0
+        assert cc[c] <= O.cost(q, X0)                        # never worse than the start
+        assert stats[c].moves_done == total and stats[c].accepted > 0
+    assert cost == cc.min() and chain == int(np.argmin(cc))
+    assert (g.unpack(words) == bests[chain]).all()
+    # the 0.5 % band at equal move budget, best over the same chain ids
+    ref = res[bi].best_cost
+    assert abs(cost - ref) <= 0.005 * ref, (cost, ref)
+    # expected (not required): the very same walk, move for move
+    same = sum((curs[c] == res[c].X).all() and cc[c] == res[c].best_cost for c in range(chains))
+    print(f"{name}: {same}/{chains} chains walk identically; best {cost:.6e} vs oracle {ref:.6e}")
+    assert same == chains
+
+
+def test_anneal_resume_and_modes(G):
+    import paper_2508_13231_amd as K
+    tr = W.config("tiny")
+    q = O.Problem(tr)
+    with G(tr) as g:
+        _anneal_gpu(g, tr, 4, 3000, seed=7)
+        c1 = K.kvp_best(g.ctx, g.shape_words, 4)
+        x1 = [K.kvp_chain_placement(g.ctx, c, 0, g.shape_words) for c in range(4)]
+        # the same schedule run in three calls
+        _anneal_gpu(g, tr, 4, 3000, moves=1000, seed=7)
+        _anneal_gpu(g, tr, 4, 3000, moves=500, seed=7, mode=K.KVP_INIT_CONTINUE)
+        _anneal_gpu(g, tr, 4, 3000, moves=1500, seed=7, mode=K.KVP_INIT_CONTINUE)
+        c2 = K.kvp_best(g.ctx, g.shape_words, 4)
+        x2 = [K.kvp_chain_placement(g.ctx, c, 0, g.shape_words) for c in range(4)]
+        assert c1[0] == c2[0] and c1[1] == c2[1] and (c1[2] == c2[2]).all() and (c1[3] == c2[3]).all()
+        assert all((a == b).all() for a, b in zip(x1, x2))
+        with pytest.raises(K.KvpError) as e:                         # the budget is used up
+            _anneal_gpu(g, tr, 4, 3000, moves=1, seed=7, mode=K.KVP_INIT_CONTINUE)
+        assert e.value.code == K.KVP_EINVAL
+        with pytest.raises(K.KvpError) as e:                         # other parameters: not a continuation
+            _anneal_gpu(g, tr, 4, 3000, moves=0, seed=8, mode=K.KVP_INIT_CONTINUE)
+        assert e.value.code == K.KVP_EINVAL
+        # one start per chain; an inadmissible start is refused
+        starts = np.stack([O.init_static_frequency(q), O.init_recency(q), np.zeros(q.shape, np.uint8)])
+        p = K.make_anneal_params(3, 1000, seed=1, init_mode=K.KVP_INIT_GIVEN)
+        K.kvp_anneal(g.ctx, p, g.words(starts))
+        cc = K.kvp_best(g.ctx, g.shape_words, 3)[3]
+        for c in range(3):
+            assert cc[c] <= O.cost(q, starts[c])
+        full = np.broadcast_to(tr.alive[None], q.shape).copy()
+        with pytest.raises(K.KvpError) as e:
+            _anneal_gpu(g, tr, 2, 100, init=full)
+        assert e.value.code == K.KVP_EINFEASIBLE
+        with pytest.raises(K.KvpError) as e:
+            K.kvp_best(g.ctx, g.shape_words, 2)
+        assert e.value.code == K.KVP_ENOCHAINS
+
+
+def test_error_paths_reach_no_kernel(G):
+    import torch
+    import paper_2508_13231_amd as K
+    tr = W.config("table1")
+    ctx = K.kvp_create(0)
+    dev = torch.device("cuda", 0)
+    try:
+        d = torch.zeros(64, dtype=torch.int32, device=dev)
+        c = torch.zeros(4, dtype=torch.float64, device=dev)
+        with pytest.raises(K.KvpError) as e:
+            K.kvp_score(ctx, d, 1, c, d)
+        assert e.value.code == K.KVP_ENOTRACE
+        acc, al, pm, wm = (W.pack_bits(a) for a in (tr.access, tr.alive, tr.persist, tr.written))
+
+        def prob(**kw):
+            base = dict(L=tr.L, N=tr.N, P=tr.P, K=tr.K, plane_bytes=tr.plane_bytes, page_bytes=tr.page_bytes,
+                        token_bytes=tr.token_bytes, bw_hbm=tr.bw_hbm, bw_link=tr.bw_link, bw_dram=tr.bw_dram,
+                        cap_pages=tr.cap_pages)
+            base.update(kw)
+            return K.make_problem(**base)
+
+        def code(p, a=acc, v=al, m=pm, w=wm):
+            with pytest.raises(K.KvpError) as e:
+                K.kvp_trace_upload(ctx, p, a, v, m, w)
+            return e.value.code
+
+        assert code(prob(n_words=5)) == K.KVP_ESHAPE
+        assert code(prob(bw_link=0.0)) == K.KVP_EINVAL
+        assert code(prob(bw_hbm=float("inf"))) == K.KVP_EINVAL
+        assert code(prob(plane_bytes=[0])) == K.KVP_EINVAL
+        assert code(prob(page_bytes=2 ** 52)) == K.KVP_ESHAPE
+        bad = al.copy(); bad[0, 0] &= ~np.uint32(1)                 # page 0 is read but not alive
+        assert code(prob(), v=bad) == K.KVP_ETRACE
+        bad = pm.copy(); bad[0, 0] |= 1                             # nothing persists into step 0
+        assert code(prob(), m=bad) == K.KVP_ETRACE
+        bad = al.copy(); bad[:, 1] |= np.uint32(1 << 31)            # a bit above the last page
+        assert code(prob(), v=bad) == K.KVP_ETRACE
+        K.kvp_trace_upload(ctx, prob(), acc, al, pm, wm)
+        with pytest.raises(K.KvpError) as e:
+            K.kvp_score(ctx, None, 1, c, d)
+        assert e.value.code == K.KVP_EINVAL
+        with pytest.raises(K.KvpError) as e:                        # misaligned schedule pointer
+            K.kvp_score(ctx, d[1:], 1, c, d)
+        assert e.value.code == K.KVP_EINVAL
+        K.kvp_score(ctx, d, 0, c, d)                                # S = 0 is a no-op
+        with pytest.raises(K.KvpError) as e:
+            K.kvp_best(ctx, (tr.L, tr.N, tr.n_words))
+        assert e.value.code == K.KVP_ENOCHAINS
+        p = K.make_anneal_params(0, 10)
+        with pytest.raises(K.KvpError) as e:
+            K.kvp_anneal(ctx, p)
+        assert e.value.code == K.KVP_EINVAL
+        p = K.make_anneal_params(2, 10, max_len=64)
+        with pytest.raises(K.KvpError) as e:
+            K.kvp_anneal(ctx, p)
+        assert e.value.code == K.KVP_EINVAL
+    finally:
+        K.kvp_destroy(ctx)
