@@ -186,6 +186,13 @@ int kvp_chain_stats(kvp_ctx *ctx, kvp_chain_stats_t *h_stats);
 /* Bytes per read unit of d_counters (gcd of plane_bytes); 0 without a trace. */
 uint64_t kvp_plane_unit(const kvp_ctx *ctx);
 
+/* Tuning knob: which scoring kernel kvp_score uses.  AUTO picks by row width;
+ * ROWS forces the general one (a wavefront per row); LANES asks for the
+ * narrow-row one (a lane per row) and falls back to ROWS where it does not
+ * apply.  Results are identical bit for bit either way. */
+enum { KVP_SCORE_AUTO = 0, KVP_SCORE_ROWS = 1, KVP_SCORE_LANES = 2 };
+int kvp_set_score_kernel(kvp_ctx *ctx, int which);
+
 const char *kvp_strerror(int code);
 
 /* After a KVP_EHIP / KVP_ENOMEM return on this thread: the hipError_t value of

@@ -26,7 +26,8 @@ KVP_INIT_EMPTY, KVP_INIT_GIVEN, KVP_INIT_BROADCAST, KVP_INIT_CONTINUE = 0, 1, 2,
 KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2
 
 EXPORTS = ["kvp_create", "kvp_destroy", "kvp_trace_upload", "kvp_score", "kvp_delta_score", "kvp_anneal",
-           "kvp_best", "kvp_chain_placement", "kvp_chain_stats", "kvp_plane_unit", "kvp_strerror", "kvp_last_hip_error"]
+           "kvp_best", "kvp_chain_placement", "kvp_chain_stats", "kvp_plane_unit", "kvp_strerror", "kvp_last_hip_error",
+           "kvp_set_score_kernel"]
 
 
 class kvp_problem(C.Structure):
@@ -96,6 +97,8 @@ def lib():
         L.kvp_plane_unit.argtypes = [vp]
         L.kvp_strerror.restype = C.c_char_p
         L.kvp_strerror.argtypes = [i32]
+        L.kvp_set_score_kernel.restype = i32
+        L.kvp_set_score_kernel.argtypes = [vp, i32]
         L.kvp_last_hip_error.restype = i32
         L.kvp_last_hip_error.argtypes = [C.POINTER(i32)]
         _lib = L
@@ -190,6 +193,13 @@ def kvp_chain_stats(ctx, n_chains):
     arr = (kvp_chain_stats_t * int(n_chains))()
     _check(lib().kvp_chain_stats(ctx, C.cast(arr, C.c_void_p)), "kvp_chain_stats")
     return list(arr)
+
+
+KVP_SCORE_AUTO, KVP_SCORE_ROWS, KVP_SCORE_LANES = 0, 1, 2
+
+
+def kvp_set_score_kernel(ctx, which: int):
+    _check(lib().kvp_set_score_kernel(ctx, int(which)), "kvp_set_score_kernel")
 
 
 def kvp_plane_unit(ctx) -> int:

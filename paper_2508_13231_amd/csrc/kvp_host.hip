@@ -78,6 +78,12 @@ extern "C" const char *kvp_strerror(int code) {
     }
 }
 
+extern "C" int kvp_set_score_kernel(kvp_ctx *ctx, int which) {
+    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_LANES) return KVP_EINVAL;
+    ctx->score_kernel = which;
+    return KVP_OK;
+}
+
 extern "C" uint64_t kvp_plane_unit(const kvp_ctx *ctx) { return ctx && ctx->has_trace ? ctx->unit : 0; }
 
 static uint64_t gcd_u64(uint64_t a, uint64_t b) { while (b) { uint64_t t = a % b; a = b; b = t; } return a; }

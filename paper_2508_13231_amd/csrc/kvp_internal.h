@@ -33,6 +33,7 @@ struct kvp_ctx {
     kvp_problem prob{};
     DevProblem dp{};
     uint64_t unit = 0;
+    int score_kernel = 0;                // KVP_SCORE_AUTO / _ROWS / _LANES
     uint32_t *d_trace = nullptr;         // one allocation: A, V, Pm, Wm, acc, wr
     // scoring scratch
     double *d_blocksum = nullptr;  size_t blocksum_cap = 0;   // [S][nb]

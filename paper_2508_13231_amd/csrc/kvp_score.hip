@@ -150,10 +150,29 @@ __global__ __launch_bounds__(256) void score_finalize_kernel(uint32_t S, uint32_
 
 static uint32_t gcd_u32(uint32_t a, uint32_t b) { while (b) { uint32_t t = a % b; a = b; b = t; } return a; }
 
+int kvp_score_tile_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+                          uint32_t *counters, uint32_t *occ);
+
 int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, double *d_cost,
                      uint32_t *d_excess, uint32_t *d_counters, uint32_t *d_occ) {
     const DevProblem &q = ctx->dp;
     if (S == 0) return KVP_OK;
+    int rc;
+    const uint32_t nb_total = (uint32_t)(((uint64_t)q.L * q.N + 63) / 64);
+    if (ctx->score_kernel != KVP_SCORE_ROWS && q.Wd <= 16) {
+        // narrow rows: one lane per row, 64 token steps per tile
+        const uint32_t tiles64 = (q.N + 63) / 64;
+        if ((rc = kvp_ensure(ctx, (void **)&ctx->d_blocksum, &ctx->blocksum_cap, (size_t)S * nb_total * sizeof(double)))) return rc;
+        if ((rc = kvp_ensure(ctx, (void **)&ctx->d_tileflag, &ctx->tileflag_cap, (size_t)S * tiles64 * sizeof(uint32_t)))) return rc;
+        rc = kvp_score_tile_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
+        if (rc < 0) return rc;
+        if (rc == KVP_OK) {
+            score_finalize_kernel<<<dim3((S + 255) / 256), dim3(256), 0, ctx->stream>>>(
+                S, nb_total, tiles64, ctx->d_blocksum, ctx->d_tileflag, d_cost, d_excess);
+            KVP_HIP(hipGetLastError());
+            return KVP_OK;
+        }
+    }
     // tile: a multiple of `unit` token steps so that Tn*L is a multiple of 64
     const uint32_t unit = 64 / gcd_u32(q.L, 64);
     uint32_t tn_max = (4096 / (q.L * unit)) * unit;        // <= 32 KB of step latencies in LDS
@@ -163,9 +182,7 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
     if (Tn < unit) Tn = unit;
     if (Tn > tn_max) Tn = tn_max;
     const uint32_t tiles = (q.N + Tn - 1) / Tn;
-    const uint32_t nb_total = (uint32_t)(((uint64_t)q.L * q.N + 63) / 64);
     if (tiles > 65535) return KVP_ESHAPE;
-    int rc;
     if ((rc = kvp_ensure(ctx, (void **)&ctx->d_blocksum, &ctx->blocksum_cap, (size_t)S * nb_total * sizeof(double)))) return rc;
     if ((rc = kvp_ensure(ctx, (void **)&ctx->d_tileflag, &ctx->tileflag_cap, (size_t)S * tiles * sizeof(uint32_t)))) return rc;
     const size_t lds = (size_t)Tn * q.L * sizeof(double) + (size_t)Tn * sizeof(uint32_t) + 16;

@@ -1,0 +1,243 @@
+// Scorer for narrow rows (n_words <= 16): one LANE per (layer, step) row.
+//
+// A row of the schedule is only a few words (9 for a 4352-token context in
+// 16-token pages), far less than a wavefront, so here each lane owns a whole
+// row: lane i of a wavefront scores token step n0 + i of one layer, and the
+// wavefront walks over the layers.  Nothing has to be reduced across lanes.
+//
+//   * The 64 rows of (schedule s, layer l, steps n0-1 .. n0+63) are contiguous in
+//     HBM.  The wavefront fetches them with 16-byte loads, lane after lane
+//     (perfectly coalesced), parks them in its private slice of LDS and reads
+//     them back row-wise (stride n_words: no bank conflict when that is odd).
+//     The previous step's row, needed for the migration term, is the
+//     neighbouring row of the same staged chunk: no second pass over HBM.
+//   * The loads for the next layer are issued before the current one is scored.
+//   * alive / persist / written words of a step are the same for every layer:
+//     they stay in registers for the whole walk.
+//   * Step latencies go to LDS (padded rows), and are summed afterwards in
+//     execution order n*L+l by the 64-wide tree, as whole blocks.
+#include "kvp_internal.h"
+
+namespace {
+
+constexpr int TILE_N = 64;     // token steps per tile = lanes per wavefront
+constexpr int TB_STRIDE = 65;  // doubles per layer in the latency buffer (odd: spreads LDS banks)
+
+template <int NV>
+struct Staged { uint4 v[NV]; };
+
+// Issue the loads of `cnt` words starting at base[start] as whole 16-byte vectors
+// from the aligned address below `start`.  Vectors that would cross `total`
+// (the end of the array) are fetched word by word.
+template <int NV>
+__device__ __forceinline__ void stage_load(Staged<NV> &st, const uint32_t *__restrict__ base, size_t start,
+                                           uint32_t cnt, size_t total, int lane, uint32_t &shift, uint32_t &nvec) {
+    const size_t a0 = start & ~(size_t)3;
+    shift = (uint32_t)(start - a0);
+    nvec = (shift + cnt + 3) >> 2;
+#pragma unroll
+    for (int j = 0; j < NV; j++) {
+        const uint32_t vi = (uint32_t)lane + 64u * j;
+        uint4 r = make_uint4(0, 0, 0, 0);
+        if (vi < nvec) {
+            const size_t idx = a0 + 4 * (size_t)vi;
+            if (idx + 4 <= total) {
+                r = *(const uint4 *)(base + idx);
+            } else {
+                if (idx + 0 < total) r.x = base[idx + 0];
+                if (idx + 1 < total) r.y = base[idx + 1];
+                if (idx + 2 < total) r.z = base[idx + 2];
+            }
+        }
+        st.v[j] = r;
+    }
+}
+
+template <int NV>
+__device__ __forceinline__ void stage_commit(const Staged<NV> &st, uint32_t *lds, uint32_t nvec, int lane) {
+#pragma unroll
+    for (int j = 0; j < NV; j++) {
+        const uint32_t vi = (uint32_t)lane + 64u * j;
+        if (vi < nvec) *(uint4 *)(lds + 4 * vi) = st.v[j];
+    }
+}
+
+constexpr int vecs_per_lane(int words) { return ((words + 3 + 3) / 4 + 63) / 64; }
+
+// WD = n_words, NW = wavefronts per workgroup, K1: exactly one access plane of weight 1.
+template <int WD, int NW, bool K1>
+__global__ __launch_bounds__(NW * 64) void score_lane_rows_kernel(
+    DevProblem q, const uint32_t *__restrict__ X, size_t x_total, size_t a_total, uint32_t tiles,
+    uint32_t nb_total, double *__restrict__ blocksum, uint32_t *__restrict__ tileflag,
+    uint32_t *__restrict__ counters, uint32_t *__restrict__ occ_out) {
+    extern __shared__ double smem_d[];
+    constexpr int XW = ((TILE_N + 1) * WD + 3 + 3) / 4 * 4;     // staged words of X per wavefront
+    constexpr int XV = vecs_per_lane((TILE_N + 1) * WD);
+    constexpr int AV1 = vecs_per_lane(TILE_N * WD);
+    const uint32_t L = q.L, N = q.N, K = q.K;
+    const uint32_t AW = (TILE_N * K * WD + 3 + 3) / 4 * 4;
+    const uint32_t s = blockIdx.x, tile = blockIdx.y;
+    const uint32_t n0 = tile * TILE_N;
+    const uint32_t rows = min((uint32_t)TILE_N, N - n0);
+    const int lane = lane_id();
+    const uint32_t wave = threadIdx.x / KVP_WAVE;
+
+    // LDS: per-wavefront staging slices (16-byte aligned), then the shared latency buffer
+    uint32_t *xbuf = (uint32_t *)smem_d + (size_t)wave * (XW + AW);
+    uint32_t *abuf = xbuf + XW;
+    double *tb = (double *)((uint32_t *)smem_d + (size_t)NW * (XW + AW));   // [L][TB_STRIDE]
+    uint32_t *occ_l = (uint32_t *)(tb + (size_t)L * TB_STRIDE);  // [64]
+    uint32_t *misc = occ_l + TILE_N;                             // [0] stray-bit flag
+    if (threadIdx.x < TILE_N) occ_l[threadIdx.x] = 0;
+    if (threadIdx.x < 4) misc[threadIdx.x] = 0;
+    __syncthreads();
+
+    const uint32_t n = n0 + lane;
+    const bool active = (uint32_t)lane < rows;
+    uint32_t vv[WD], pm[WD], wm[WD];
+#pragma unroll
+    for (int w = 0; w < WD; w++) {
+        vv[w] = active ? q.V[(size_t)n * WD + w] : 0u;
+        pm[w] = active ? q.Pm[(size_t)n * WD + w] : 0u;
+        wm[w] = active ? q.Wm[(size_t)n * WD + w] : 0u;
+    }
+    const uint32_t wr_n = active ? q.wr[n] : 0u;
+    const uint32_t halo = n0 > 0 ? WD : 0;
+    uint32_t occ_acc = 0, fl_acc = 0;
+
+    Staged<XV> sx;
+    Staged<AV1> sa;
+    uint32_t xshift = 0, xnvec = 0, ashift = 0, anvec = 0;
+    auto chunk_x = [&](uint32_t l) { return ((size_t)(s * (size_t)L + l) * N + n0) * WD - halo; };
+    auto chunk_a = [&](uint32_t l) { return ((size_t)l * N + n0) * K * WD; };
+    if (wave < L) {
+        stage_load<XV>(sx, X, chunk_x(wave), rows * WD + halo, x_total, lane, xshift, xnvec);
+        if (K1) stage_load<AV1>(sa, q.A, chunk_a(wave), rows * WD, a_total, lane, ashift, anvec);
+    }
+    for (uint32_t l = wave; l < L; l += NW) {
+        stage_commit<XV>(sx, xbuf, xnvec, lane);
+        const uint32_t xs = xshift;
+        uint32_t as;
+        if (K1) {
+            stage_commit<AV1>(sa, abuf, anvec, lane);
+            as = ashift;
+        } else {
+            // several planes: stream the trace chunk straight into LDS
+            const size_t start = chunk_a(l), a0 = start & ~(size_t)3;
+            as = (uint32_t)(start - a0);
+            const uint32_t nv = (as + rows * K * WD + 3) >> 2;
+            for (uint32_t vi = lane; vi < nv; vi += 64) {
+                const size_t idx = a0 + 4 * (size_t)vi;
+                uint4 r = make_uint4(0, 0, 0, 0);
+                if (idx + 4 <= a_total) r = *(const uint4 *)(q.A + idx);
+                else {
+                    if (idx + 0 < a_total) r.x = q.A[idx + 0];
+                    if (idx + 1 < a_total) r.y = q.A[idx + 1];
+                    if (idx + 2 < a_total) r.z = q.A[idx + 2];
+                }
+                *(uint4 *)(abuf + 4 * vi) = r;
+            }
+        }
+        if (l + NW < L) {                                       // next layer's rows are in flight meanwhile
+            stage_load<XV>(sx, X, chunk_x(l + NW), rows * WD + halo, x_total, lane, xshift, xnvec);
+            if (K1) stage_load<AV1>(sa, q.A, chunk_a(l + NW), rows * WD, a_total, lane, ashift, anvec);
+        }
+        // the wavefront's LDS writes are complete and visible to all its lanes
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (active) {
+            const uint32_t *cur = xbuf + xs + halo + (uint32_t)lane * WD;
+            const uint32_t *prv = n > 0 ? cur - WD : cur;       // step 0 migrates nothing (persist is empty)
+            const uint32_t *ar = abuf + as + (uint32_t)lane * K * WD;
+            uint32_t hr = 0, hw = 0, mi = 0, mg = 0, oc = 0;
+#pragma unroll
+            for (int w = 0; w < WD; w++) {
+                const uint32_t raw = cur[w], xp = prv[w];
+                const uint32_t x = raw & vv[w];
+                fl_acc |= raw ^ x;
+                if (K1) {
+                    hr += __popc(x & ar[w]);
+                } else {
+                    for (uint32_t k = 0; k < K; k++) hr += q.wt[k] * __popc(x & ar[k * WD + w]);
+                }
+                hw += __popc(x & wm[w]);
+                oc += __popc(x);
+                const uint32_t d = (x ^ xp) & pm[w];
+                mi += __popc(d & x);
+                mg += __popc(d);
+            }
+            const uint32_t mo = mg - mi;
+            const size_t row = (size_t)l * N + n;
+            tb[(size_t)l * TB_STRIDE + lane] = step_time(q, hr, hw, mi, mo, q.acc[row], wr_n);
+            occ_acc += oc;
+            if (counters) *(uint4 *)(counters + ((size_t)s * L * N + row) * 4) = make_uint4(hr, hw, mi, mo);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (active && occ_acc) atomicAdd(&occ_l[lane], occ_acc);
+    if (fl_acc) atomicOr(&misc[0], 1u);
+    __syncthreads();
+
+    // Eq. 1 inside the tile: element g = r*L + l of the execution order lives at tb[l][r]
+    const uint32_t nvalid = rows * L;
+    const uint32_t nblk = (nvalid + 63) / 64;
+    uint32_t g = wave * 64 + lane;
+    uint32_t r = g / L, l = g - r * L;
+    const uint32_t dr = (NW * 64) / L, dl = (NW * 64) - dr * L;
+    for (uint32_t b = wave; b < nblk; b += NW) {
+        double t = g < nvalid ? tb[(size_t)l * TB_STRIDE + r] : 0.0;
+        t = wave_tree_sum_f64(t);
+        if (lane == 0) blocksum[(size_t)s * nb_total + (size_t)tile * L + b] = t;
+        g += NW * 64; r += dr; l += dl;
+        if (l >= L) { l -= L; r++; }
+    }
+    // Eq. 5 per token step
+    if (threadIdx.x < TILE_N) {
+        uint32_t ex = 0;
+        if (threadIdx.x < rows) {
+            const uint32_t o = occ_l[threadIdx.x];
+            if (occ_out) occ_out[(size_t)s * N + n0 + threadIdx.x] = o;
+            ex = o > q.cap ? o - q.cap : 0;
+        }
+        ex = wave_max_u32(ex);
+        if (threadIdx.x == 0) tileflag[(size_t)s * tiles + tile] = ex | (misc[0] ? 0x80000000u : 0u);
+    }
+}
+
+template <int WD>
+int launch_wd(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+              uint32_t *counters, uint32_t *occ) {
+    constexpr int NW = 8;
+    const DevProblem &q = ctx->dp;
+    const size_t XW = ((TILE_N + 1) * WD + 3 + 3) / 4 * 4, AW = ((size_t)TILE_N * q.K * WD + 3 + 3) / 4 * 4;
+    const size_t lds = (size_t)q.L * TB_STRIDE * 8 + (TILE_N + 4) * 4 + NW * (XW + AW) * 4;
+    if (lds > 64 * 1024) return 1;
+    const size_t x_total = (size_t)S * q.L * q.N * WD, a_total = (size_t)q.L * q.N * q.K * WD;
+    const bool k1 = q.K == 1 && q.wt[0] == 1;
+    dim3 grid(S, tiles), block(NW * 64);
+    if (k1)
+        score_lane_rows_kernel<WD, NW, true><<<grid, block, lds, ctx->stream>>>(
+            q, X, x_total, a_total, tiles, nb_total, ctx->d_blocksum, ctx->d_tileflag, counters, occ);
+    else
+        score_lane_rows_kernel<WD, NW, false><<<grid, block, lds, ctx->stream>>>(
+            q, X, x_total, a_total, tiles, nb_total, ctx->d_blocksum, ctx->d_tileflag, counters, occ);
+    KVP_HIP(hipGetLastError());
+    return KVP_OK;
+}
+
+}  // namespace
+
+// Returns KVP_OK if launched, 1 if this kernel does not cover the shape, <0 on error.
+// blocksum/tileflag must already hold S*nb_total doubles and S*tiles words.
+int kvp_score_tile_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+                          uint32_t *counters, uint32_t *occ) {
+    switch (ctx->dp.Wd) {
+#define KVP_CASE(W) case W: return launch_wd<W>(ctx, X, S, tiles, nb_total, counters, occ);
+        KVP_CASE(1) KVP_CASE(2) KVP_CASE(3) KVP_CASE(4) KVP_CASE(5) KVP_CASE(6) KVP_CASE(7) KVP_CASE(8)
+        KVP_CASE(9) KVP_CASE(10) KVP_CASE(11) KVP_CASE(12) KVP_CASE(13) KVP_CASE(14) KVP_CASE(15) KVP_CASE(16)
+#undef KVP_CASE
+        default: return 1;
+    }
+}

@@ -8,7 +8,7 @@ import workloads as W
 class Gpu:
     """A library context with one uploaded trace; device tensors via torch."""
 
-    def __init__(self, tr, device=0):
+    def __init__(self, tr, device=0, score_kernel=None):
         import torch
         self.torch = torch
         self.tr = tr
@@ -18,6 +18,8 @@ class Gpu:
                                       tr.bw_hbm, tr.bw_link, tr.bw_dram, tr.cap_pages)
         K.kvp_trace_upload(self.ctx, self.problem, W.pack_bits(tr.access), W.pack_bits(tr.alive),
                            W.pack_bits(tr.persist), W.pack_bits(tr.written))
+        if score_kernel is not None:
+            K.kvp_set_score_kernel(self.ctx, score_kernel)
         self.unit = K.kvp_plane_unit(self.ctx)
         self.shape_words = (tr.L, tr.N, tr.n_words)
 

@@ -34,19 +34,22 @@ def _cases():
     yield "rand-weights", W.random_trace(13, L=2, N=50, P=100, K=3,
                                          plane_bytes=[4096, 8192, 53248])  # unequal plane weights
     yield "one-step", W.random_trace(14, L=1, N=1, P=33, K=1)
+    yield "rand-tiles", W.random_trace(15, L=6, N=150, P=180, K=2)         # 3 tiles of 64 steps, ragged tail
+    yield "rand-512", W.random_trace(16, L=3, N=70, P=512, K=1)            # 16 words per row, even stride
 
 
 CASES = list(_cases())
 
 
+@pytest.mark.parametrize("kernel", [1, 2], ids=["rows", "lanes"])
 @pytest.mark.parametrize("name,tr", CASES, ids=[c[0] for c in CASES])
-def test_score_matches_oracle_bit_for_bit(G, name, tr):
+def test_score_matches_oracle_bit_for_bit(G, name, tr, kernel):
     from gpu_util import expected_counters
     X = np.concatenate([W.random_placements(tr, 5, seed=1, density=0.4),
                         W.random_placements(tr, 2, seed=2, density=0.9, feasible=False),
                         W.edge_placements(tr)])
     q = O.Problem(tr)
-    with G(tr) as g:
+    with G(tr, score_kernel=kernel) as g:
         cost, ex, cnt, occ = g.score(X)
         cost2, ex2, _, _ = g.score(X, counters=False)
         for s in range(X.shape[0]):
