@@ -111,6 +111,7 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--score-only", action="store_true", help="time kvp_score alone (for profiling)")
+    ap.add_argument("--score-kernel", type=int, default=0, help="kvp_set_score_kernel value (0 = auto)")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU; chains and schedules shard trivially across GPUs "
@@ -130,6 +131,8 @@ def main():
     total = (a.steps + a.warmup) * M
     ctx = K.kvp_create(0)
     upload(K, W, ctx, tr)
+    if a.score_kernel:
+        K.kvp_set_score_kernel(ctx, a.score_kernel)
     d_x = make_batch(tr, S, dev)
     d_cost = torch.empty(S, dtype=torch.float64, device=dev)
     d_ex = torch.empty(S, dtype=torch.int32, device=dev)

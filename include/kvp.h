@@ -189,8 +189,9 @@ uint64_t kvp_plane_unit(const kvp_ctx *ctx);
 /* Tuning knob: which scoring kernel kvp_score uses.  AUTO picks by row width;
  * ROWS forces the general one (a wavefront per row); LANES asks for the
  * narrow-row one (a lane per row) and falls back to ROWS where it does not
- * apply.  Results are identical bit for bit either way. */
-enum { KVP_SCORE_AUTO = 0, KVP_SCORE_ROWS = 1, KVP_SCORE_LANES = 2 };
+ * apply; LANES_8W is LANES with 8 instead of 4 wavefronts per workgroup.
+ * Results are identical bit for bit either way. */
+enum { KVP_SCORE_AUTO = 0, KVP_SCORE_ROWS = 1, KVP_SCORE_LANES = 2, KVP_SCORE_LANES_8W = 3 };
 int kvp_set_score_kernel(kvp_ctx *ctx, int which);
 
 const char *kvp_strerror(int code);

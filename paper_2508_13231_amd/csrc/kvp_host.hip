@@ -1,11 +1,12 @@
 // Host side of libkvp: context, trace upload, argument checks.  gfx950 only.
 #include <math.h>
 #include <new>
+#include <stdlib.h>
 #include <string.h>
 
 #include "kvp_internal.h"
 
-int kvp_trace_totals_launch(kvp_ctx *ctx, uint32_t *acc, uint32_t *wr);
+int kvp_trace_totals_launch(kvp_ctx *ctx, uint32_t *acc, uint32_t *wr, uint32_t *wsel);
 
 thread_local int kvp_tls_hip_error = 0;
 thread_local int kvp_tls_hip_line = 0;
@@ -79,8 +80,9 @@ extern "C" const char *kvp_strerror(int code) {
 }
 
 extern "C" int kvp_set_score_kernel(kvp_ctx *ctx, int which) {
-    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_LANES) return KVP_EINVAL;
-    ctx->score_kernel = which;
+    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_LANES_8W) return KVP_EINVAL;
+    ctx->score_kernel = which == KVP_SCORE_LANES_8W ? KVP_SCORE_LANES : which;
+    ctx->tile_waves = which == KVP_SCORE_LANES_8W ? 8 : 4;
     return KVP_OK;
 }
 
@@ -143,7 +145,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     const size_t nA = (size_t)(L * N * K * Wd), nM = (size_t)(N * Wd);
     auto up4 = [](size_t x) { return (x + 3) & ~(size_t)3; };          // keep every array 16-byte aligned
     const size_t oV = up4(nA), oPm = oV + up4(nM), oWm = oPm + up4(nM), oAcc = oWm + up4(nM);
-    const size_t oWr = oAcc + up4((size_t)(L * N)), total = oWr + up4((size_t)N);
+    const size_t oWr = oAcc + up4((size_t)(L * N)), oSel = oWr + up4((size_t)N), total = oSel + up4((size_t)N);
     KVP_HIP(hipMalloc((void **)&ctx->d_trace, total * sizeof(uint32_t)));
     uint32_t *d = ctx->d_trace;
     KVP_HIP(hipMemcpyAsync(d, h_access, nA * 4, hipMemcpyHostToDevice, ctx->stream));
@@ -157,14 +159,22 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     q = DevProblem{};
     q.L = (uint32_t)L; q.N = (uint32_t)N; q.P = (uint32_t)P; q.Wd = (uint32_t)Wd; q.K = (uint32_t)K;
     q.cap = pr->cap_pages > 0x7FFFFFFFull ? 0x7FFFFFFFu : (uint32_t)pr->cap_pages;
-    q.A = d; q.V = d + oV; q.Pm = d + oPm; q.Wm = d + oWm; q.acc = d + oAcc; q.wr = d + oWr;
+    q.A = d; q.V = d + oV; q.Pm = d + oPm; q.Wm = d + oWm; q.acc = d + oAcc; q.wr = d + oWr; q.wsel = d + oSel;
     for (uint64_t k = 0; k < K; k++) q.wt[k] = (uint32_t)(pr->plane_bytes[k] / unit);
     q.unit_b = (double)unit; q.page_b = (double)pr->page_bytes; q.token_b = (double)pr->token_bytes;
     q.inv_bh = 1.0 / pr->bw_hbm; q.inv_bk = 1.0 / pr->bw_link; q.inv_bd = 1.0 / pr->bw_dram;
     q.inv_min = 1.0 / (pr->bw_link < pr->bw_dram ? pr->bw_link : pr->bw_dram);
-    int rc = kvp_trace_totals_launch(ctx, d + oAcc, d + oWr);
+    int rc = kvp_trace_totals_launch(ctx, d + oAcc, d + oWr, d + oSel);
     if (rc) return rc;
-    KVP_HIP(hipStreamSynchronize(ctx->stream));
+    uint32_t *hsel = (uint32_t *)malloc((size_t)N * 4);
+    if (!hsel) return KVP_ENOMEM;
+    hipError_t e = hipMemcpyAsync(hsel, d + oSel, (size_t)N * 4, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    q.single_write = 1;
+    for (uint64_t n = 0; n < N && e == hipSuccess; n++)
+        if (hsel[n] == 0xFFFFFFFFu) q.single_write = 0;
+    free(hsel);
+    KVP_HIP(e);
     ctx->has_trace = true;
     return KVP_OK;
 }

@@ -19,6 +19,8 @@ struct DevProblem {
     const uint32_t *Wm;           // [N][Wd] written
     const uint32_t *acc;          // [L][N] read units of the step (all tiers)
     const uint32_t *wr;           // [N] pages written at the step
+    const uint32_t *wsel;         // [N] index of the only word of Wm[n] with bits (0 if none), ~0 if several
+    uint32_t single_write;        // every step's written pages sit in one word
     uint32_t wt[KVP_MAX_PLANES];  // plane_bytes[k] / unit
     double unit_b, page_b, token_b;          // bytes, exact integers held in fp64
     double inv_bh, inv_bk, inv_bd, inv_min;  // reciprocals of Eqs. 3-4's bandwidths
@@ -34,6 +36,7 @@ struct kvp_ctx {
     DevProblem dp{};
     uint64_t unit = 0;
     int score_kernel = 0;                // KVP_SCORE_AUTO / _ROWS / _LANES
+    int tile_waves = 4;                  // wavefronts per workgroup of the narrow-row scorer (4 or 8)
     uint32_t *d_trace = nullptr;         // one allocation: A, V, Pm, Wm, acc, wr
     // scoring scratch
     double *d_blocksum = nullptr;  size_t blocksum_cap = 0;   // [S][nb]
@@ -115,10 +118,10 @@ __device__ __forceinline__ double step_time(const DevProblem &q, uint32_t hr_u, 
     double link_out = (ew_b + mo_b) * q.inv_bk;
     double link_in = mi_b * q.inv_bk;
     double chan = ((ew_b + mi_b) + mo_b) * q.inv_bd;
-    double m = link_out > link_in ? link_out : link_in;
-    m = m > chan ? m : chan;
+    // all operands are finite and >= +0: the hardware maximum picks the same value as a comparison
+    double m = __builtin_fmax(__builtin_fmax(link_out, link_in), chan);
     double t_e = er_b * q.inv_min + m;                                       // Eq. 4
-    return t_h > t_e ? t_h : t_e;                                            // Eq. 2
+    return __builtin_fmax(t_h, t_e);                                         // Eq. 2
 }
 
 #endif  // __HIPCC__

@@ -4,7 +4,7 @@
 #include "kvp_internal.h"
 
 // One pass over the trace: read units per step and written pages per token step.
-__global__ __launch_bounds__(256) void trace_totals_kernel(DevProblem q, uint32_t *acc, uint32_t *wr) {
+__global__ __launch_bounds__(256) void trace_totals_kernel(DevProblem q, uint32_t *acc, uint32_t *wr, uint32_t *wsel) {
     const int lane = lane_id();
     const uint32_t row = blockIdx.x * 4 + threadIdx.x / KVP_WAVE;
     const uint32_t rows = q.L * q.N;
@@ -17,17 +17,21 @@ __global__ __launch_bounds__(256) void trace_totals_kernel(DevProblem q, uint32_
         if (lane == 0) acc[row] = u;
     } else if (row < rows + q.N) {
         const uint32_t n = row - rows;
-        uint32_t c = 0;
-        for (uint32_t w = lane; w < q.Wd; w += KVP_WAVE) c += __popc(q.Wm[(size_t)n * q.Wd + w]);
-        c = wave_sum_u32(c);
-        if (lane == 0) wr[n] = c;
+        uint32_t c = 0, nz = 0, last = 0;
+        for (uint32_t w = lane; w < q.Wd; w += KVP_WAVE) {
+            const uint32_t m = q.Wm[(size_t)n * q.Wd + w];
+            c += __popc(m);
+            if (m) { nz++; last = w; }
+        }
+        c = wave_sum_u32(c); nz = wave_sum_u32(nz); last = wave_max_u32(last);
+        if (lane == 0) { wr[n] = c; wsel[n] = nz <= 1 ? last : 0xFFFFFFFFu; }
     }
 }
 
-int kvp_trace_totals_launch(kvp_ctx *ctx, uint32_t *acc, uint32_t *wr) {
+int kvp_trace_totals_launch(kvp_ctx *ctx, uint32_t *acc, uint32_t *wr, uint32_t *wsel) {
     const DevProblem &q = ctx->dp;
     uint32_t rows = q.L * q.N + q.N;
-    trace_totals_kernel<<<dim3((rows + 3) / 4), dim3(256), 0, ctx->stream>>>(q, acc, wr);
+    trace_totals_kernel<<<dim3((rows + 3) / 4), dim3(256), 0, ctx->stream>>>(q, acc, wr, wsel);
     KVP_HIP(hipGetLastError());
     return KVP_OK;
 }

@@ -27,29 +27,34 @@ template <int NV>
 struct Staged { uint4 v[NV]; };
 
 // Issue the loads of `cnt` words starting at base[start] as whole 16-byte vectors
-// from the aligned address below `start`.  Vectors that would cross `total`
-// (the end of the array) are fetched word by word.
+// from the aligned address below `start` (all arguments wavefront-uniform).
+// If the last vector would cross `total`, the end of the array, the chunk is
+// fetched word by word instead: that only ever happens for the array's last chunk.
 template <int NV>
 __device__ __forceinline__ void stage_load(Staged<NV> &st, const uint32_t *__restrict__ base, size_t start,
                                            uint32_t cnt, size_t total, int lane, uint32_t &shift, uint32_t &nvec) {
     const size_t a0 = start & ~(size_t)3;
     shift = (uint32_t)(start - a0);
     nvec = (shift + cnt + 3) >> 2;
+    const uint32_t *p = base + a0;
+    if (a0 + 4 * (size_t)nvec <= total) {
 #pragma unroll
-    for (int j = 0; j < NV; j++) {
-        const uint32_t vi = (uint32_t)lane + 64u * j;
-        uint4 r = make_uint4(0, 0, 0, 0);
-        if (vi < nvec) {
-            const size_t idx = a0 + 4 * (size_t)vi;
-            if (idx + 4 <= total) {
-                r = *(const uint4 *)(base + idx);
-            } else {
-                if (idx + 0 < total) r.x = base[idx + 0];
-                if (idx + 1 < total) r.y = base[idx + 1];
-                if (idx + 2 < total) r.z = base[idx + 2];
-            }
+        for (int j = 0; j < NV; j++) {
+            const uint32_t vi = (uint32_t)lane + 64u * j;
+            if (vi < nvec) st.v[j] = *(const uint4 *)(p + 4 * vi);
         }
-        st.v[j] = r;
+    } else {
+        const uint32_t left = (uint32_t)(total - a0);
+#pragma unroll
+        for (int j = 0; j < NV; j++) {
+            const uint32_t w = 4 * ((uint32_t)lane + 64u * j);
+            uint4 r = make_uint4(0, 0, 0, 0);
+            if (w + 0 < left) r.x = p[w + 0];
+            if (w + 1 < left) r.y = p[w + 1];
+            if (w + 2 < left) r.z = p[w + 2];
+            if (w + 3 < left) r.w = p[w + 3];
+            st.v[j] = r;
+        }
     }
 }
 
@@ -64,8 +69,9 @@ __device__ __forceinline__ void stage_commit(const Staged<NV> &st, uint32_t *lds
 
 constexpr int vecs_per_lane(int words) { return ((words + 3 + 3) / 4 + 63) / 64; }
 
-// WD = n_words, NW = wavefronts per workgroup, K1: exactly one access plane of weight 1.
-template <int WD, int NW, bool K1>
+// WD = n_words, NW = wavefronts per workgroup, K1: exactly one access plane of
+// weight 1, W1: the pages written at a step all sit in one word of the row.
+template <int WD, int NW, bool K1, bool W1>
 __global__ __launch_bounds__(NW * 64) void score_lane_rows_kernel(
     DevProblem q, const uint32_t *__restrict__ X, size_t x_total, size_t a_total, uint32_t tiles,
     uint32_t nb_total, double *__restrict__ blocksum, uint32_t *__restrict__ tileflag,
@@ -74,13 +80,15 @@ __global__ __launch_bounds__(NW * 64) void score_lane_rows_kernel(
     constexpr int XW = ((TILE_N + 1) * WD + 3 + 3) / 4 * 4;     // staged words of X per wavefront
     constexpr int XV = vecs_per_lane((TILE_N + 1) * WD);
     constexpr int AV1 = vecs_per_lane(TILE_N * WD);
+    constexpr int WREG = W1 ? 1 : WD;
     const uint32_t L = q.L, N = q.N, K = q.K;
     const uint32_t AW = (TILE_N * K * WD + 3 + 3) / 4 * 4;
     const uint32_t s = blockIdx.x, tile = blockIdx.y;
     const uint32_t n0 = tile * TILE_N;
     const uint32_t rows = min((uint32_t)TILE_N, N - n0);
     const int lane = lane_id();
-    const uint32_t wave = threadIdx.x / KVP_WAVE;
+    // wavefront index as a scalar: everything derived from it stays in scalar registers
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / KVP_WAVE));
 
     // LDS: per-wavefront staging slices (16-byte aligned), then the shared latency buffer
     uint32_t *xbuf = (uint32_t *)smem_d + (size_t)wave * (XW + AW);
@@ -94,12 +102,19 @@ __global__ __launch_bounds__(NW * 64) void score_lane_rows_kernel(
 
     const uint32_t n = n0 + lane;
     const bool active = (uint32_t)lane < rows;
-    uint32_t vv[WD], pm[WD], wm[WD];
+    uint32_t vv[WD], pm[WD], wm[WREG];
 #pragma unroll
     for (int w = 0; w < WD; w++) {
         vv[w] = active ? q.V[(size_t)n * WD + w] : 0u;
         pm[w] = active ? q.Pm[(size_t)n * WD + w] : 0u;
-        wm[w] = active ? q.Wm[(size_t)n * WD + w] : 0u;
+    }
+    uint32_t wsel = 0;
+    if (W1) {
+        wsel = active ? q.wsel[n] : 0u;
+        wm[0] = active ? q.Wm[(size_t)n * WD + wsel] : 0u;
+    } else {
+#pragma unroll
+        for (int w = 0; w < WREG; w++) wm[w] = active ? q.Wm[(size_t)n * WD + w] : 0u;
     }
     const uint32_t wr_n = active ? q.wr[n] : 0u;
     const uint32_t halo = n0 > 0 ? WD : 0;
@@ -126,14 +141,15 @@ __global__ __launch_bounds__(NW * 64) void score_lane_rows_kernel(
             const size_t start = chunk_a(l), a0 = start & ~(size_t)3;
             as = (uint32_t)(start - a0);
             const uint32_t nv = (as + rows * K * WD + 3) >> 2;
+            const uint32_t *p = q.A + a0;
+            const uint32_t left = (uint32_t)min((size_t)0xFFFFFFFFu, a_total - a0);
             for (uint32_t vi = lane; vi < nv; vi += 64) {
-                const size_t idx = a0 + 4 * (size_t)vi;
                 uint4 r = make_uint4(0, 0, 0, 0);
-                if (idx + 4 <= a_total) r = *(const uint4 *)(q.A + idx);
+                if (4 * vi + 4 <= left) r = *(const uint4 *)(p + 4 * vi);
                 else {
-                    if (idx + 0 < a_total) r.x = q.A[idx + 0];
-                    if (idx + 1 < a_total) r.y = q.A[idx + 1];
-                    if (idx + 2 < a_total) r.z = q.A[idx + 2];
+                    if (4 * vi + 0 < left) r.x = p[4 * vi + 0];
+                    if (4 * vi + 1 < left) r.y = p[4 * vi + 1];
+                    if (4 * vi + 2 < left) r.z = p[4 * vi + 2];
                 }
                 *(uint4 *)(abuf + 4 * vi) = r;
             }
@@ -155,18 +171,19 @@ __global__ __launch_bounds__(NW * 64) void score_lane_rows_kernel(
             for (int w = 0; w < WD; w++) {
                 const uint32_t raw = cur[w], xp = prv[w];
                 const uint32_t x = raw & vv[w];
-                fl_acc |= raw ^ x;
+                fl_acc |= raw & ~vv[w];
                 if (K1) {
                     hr += __popc(x & ar[w]);
                 } else {
                     for (uint32_t k = 0; k < K; k++) hr += q.wt[k] * __popc(x & ar[k * WD + w]);
                 }
-                hw += __popc(x & wm[w]);
+                if (!W1) hw += __popc(x & wm[w]);
                 oc += __popc(x);
                 const uint32_t d = (x ^ xp) & pm[w];
                 mi += __popc(d & x);
                 mg += __popc(d);
             }
+            if (W1) hw = __popc(cur[wsel] & wm[0]);            // written pages exist, so raw & wm == x & wm
             const uint32_t mo = mg - mi;
             const size_t row = (size_t)l * N + n;
             tb[(size_t)l * TB_STRIDE + lane] = step_time(q, hr, hw, mi, mo, q.acc[row], wr_n);
@@ -206,29 +223,39 @@ __global__ __launch_bounds__(NW * 64) void score_lane_rows_kernel(
     }
 }
 
-template <int WD>
-int launch_wd(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
-              uint32_t *counters, uint32_t *occ) {
-    constexpr int NW = 8;
+template <int WD, int NW>
+int launch_wd_nw(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+                 uint32_t *counters, uint32_t *occ) {
     const DevProblem &q = ctx->dp;
     const size_t XW = ((TILE_N + 1) * WD + 3 + 3) / 4 * 4, AW = ((size_t)TILE_N * q.K * WD + 3 + 3) / 4 * 4;
     const size_t lds = (size_t)q.L * TB_STRIDE * 8 + (TILE_N + 4) * 4 + NW * (XW + AW) * 4;
     if (lds > 64 * 1024) return 1;
     const size_t x_total = (size_t)S * q.L * q.N * WD, a_total = (size_t)q.L * q.N * q.K * WD;
-    const bool k1 = q.K == 1 && q.wt[0] == 1;
+    const bool k1 = q.K == 1 && q.wt[0] == 1, w1 = q.single_write != 0;
     dim3 grid(S, tiles), block(NW * 64);
-    if (k1)
-        score_lane_rows_kernel<WD, NW, true><<<grid, block, lds, ctx->stream>>>(
-            q, X, x_total, a_total, tiles, nb_total, ctx->d_blocksum, ctx->d_tileflag, counters, occ);
-    else
-        score_lane_rows_kernel<WD, NW, false><<<grid, block, lds, ctx->stream>>>(
-            q, X, x_total, a_total, tiles, nb_total, ctx->d_blocksum, ctx->d_tileflag, counters, occ);
+#define KVP_GO(KK, WW)                                                                                  \
+    score_lane_rows_kernel<WD, NW, KK, WW><<<grid, block, lds, ctx->stream>>>(                          \
+        q, X, x_total, a_total, tiles, nb_total, ctx->d_blocksum, ctx->d_tileflag, counters, occ)
+    if (k1 && w1) KVP_GO(true, true);
+    else if (k1) KVP_GO(true, false);
+    else if (w1) KVP_GO(false, true);
+    else KVP_GO(false, false);
+#undef KVP_GO
     KVP_HIP(hipGetLastError());
     return KVP_OK;
 }
 
-}  // namespace
+template <int WD>
+int launch_wd(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+              uint32_t *counters, uint32_t *occ) {
+    // more wavefronts per workgroup only when there are layers enough to keep each busy for long
+    int rc = ctx->tile_waves == 8 ? launch_wd_nw<WD, 8>(ctx, X, S, tiles, nb_total, counters, occ)
+                                  : launch_wd_nw<WD, 4>(ctx, X, S, tiles, nb_total, counters, occ);
+    if (rc == 1 && ctx->tile_waves == 8) rc = launch_wd_nw<WD, 4>(ctx, X, S, tiles, nb_total, counters, occ);
+    return rc;
+}
 
+}  // namespace
 // Returns KVP_OK if launched, 1 if this kernel does not cover the shape, <0 on error.
 // blocksum/tileflag must already hold S*nb_total doubles and S*tiles words.
 int kvp_score_tile_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,

@@ -41,7 +41,7 @@ def _cases():
 CASES = list(_cases())
 
 
-@pytest.mark.parametrize("kernel", [1, 2], ids=["rows", "lanes"])
+@pytest.mark.parametrize("kernel", [1, 2, 3], ids=["rows", "lanes", "lanes8w"])
 @pytest.mark.parametrize("name,tr", CASES, ids=[c[0] for c in CASES])
 def test_score_matches_oracle_bit_for_bit(G, name, tr, kernel):
     from gpu_util import expected_counters
