@@ -191,7 +191,9 @@ uint64_t kvp_plane_unit(const kvp_ctx *ctx);
  * narrow-row one (a lane per row) and falls back to ROWS where it does not
  * apply; LANES_8W is LANES with 8 instead of 4 wavefronts per workgroup.
  * Results are identical bit for bit either way. */
-enum { KVP_SCORE_AUTO = 0, KVP_SCORE_ROWS = 1, KVP_SCORE_LANES = 2, KVP_SCORE_LANES_8W = 3 };
+enum { KVP_SCORE_AUTO = 0, KVP_SCORE_ROWS = 1, KVP_SCORE_LANES = 2, KVP_SCORE_LANES_8W = 3,
+       KVP_SCORE_DIRECT = 4, KVP_SCORE_DIRECT_8W = 5, /* lane per row, rows loaded without LDS staging */
+       KVP_SCORE_QUAD = 6 /* lane per row, four schedules per workgroup share the trace chunk */ };
 int kvp_set_score_kernel(kvp_ctx *ctx, int which);
 
 const char *kvp_strerror(int code);

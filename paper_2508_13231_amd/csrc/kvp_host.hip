@@ -80,9 +80,11 @@ extern "C" const char *kvp_strerror(int code) {
 }
 
 extern "C" int kvp_set_score_kernel(kvp_ctx *ctx, int which) {
-    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_LANES_8W) return KVP_EINVAL;
-    ctx->score_kernel = which == KVP_SCORE_LANES_8W ? KVP_SCORE_LANES : which;
-    ctx->tile_waves = which == KVP_SCORE_LANES_8W ? 8 : 4;
+    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_QUAD) return KVP_EINVAL;
+    ctx->tile_quad = which == KVP_SCORE_AUTO || which == KVP_SCORE_QUAD;
+    ctx->score_kernel = which >= KVP_SCORE_LANES ? KVP_SCORE_LANES : which;
+    ctx->tile_waves = (which == KVP_SCORE_LANES_8W || which == KVP_SCORE_DIRECT_8W) ? 8 : 4;
+    ctx->tile_direct = which >= KVP_SCORE_DIRECT || which == KVP_SCORE_AUTO;
     return KVP_OK;
 }
 

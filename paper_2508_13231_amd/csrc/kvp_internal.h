@@ -36,6 +36,8 @@ struct kvp_ctx {
     DevProblem dp{};
     uint64_t unit = 0;
     int score_kernel = 0;                // KVP_SCORE_AUTO / _ROWS / _LANES
+    int tile_quad = 1;                   // four schedules per workgroup (power-of-two layer counts)
+    int tile_direct = 1;                 // narrow-row scorer without LDS staging (single plane only)
     int tile_waves = 4;                  // wavefronts per workgroup of the narrow-row scorer (4 or 8)
     uint32_t *d_trace = nullptr;         // one allocation: A, V, Pm, Wm, acc, wr
     // scoring scratch

@@ -156,6 +156,8 @@ static uint32_t gcd_u32(uint32_t a, uint32_t b) { while (b) { uint32_t t = a % b
 
 int kvp_score_tile_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
                           uint32_t *counters, uint32_t *occ);
+int kvp_score_quad_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+                          uint32_t *counters, uint32_t *occ);
 
 int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, double *d_cost,
                      uint32_t *d_excess, uint32_t *d_counters, uint32_t *d_occ) {
@@ -168,7 +170,9 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
         const uint32_t tiles64 = (q.N + 63) / 64;
         if ((rc = kvp_ensure(ctx, (void **)&ctx->d_blocksum, &ctx->blocksum_cap, (size_t)S * nb_total * sizeof(double)))) return rc;
         if ((rc = kvp_ensure(ctx, (void **)&ctx->d_tileflag, &ctx->tileflag_cap, (size_t)S * tiles64 * sizeof(uint32_t)))) return rc;
-        rc = kvp_score_tile_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
+        rc = 1;
+        if (ctx->tile_quad) rc = kvp_score_quad_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
+        if (rc == 1) rc = kvp_score_tile_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
         if (rc < 0) return rc;
         if (rc == KVP_OK) {
             score_finalize_kernel<<<dim3((S + 255) / 256), dim3(256), 0, ctx->stream>>>(

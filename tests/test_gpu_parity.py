@@ -36,12 +36,15 @@ def _cases():
     yield "one-step", W.random_trace(14, L=1, N=1, P=33, K=1)
     yield "rand-tiles", W.random_trace(15, L=6, N=150, P=180, K=2)         # 3 tiles of 64 steps, ragged tail
     yield "rand-512", W.random_trace(16, L=3, N=70, P=512, K=1)            # 16 words per row, even stride
+    yield "rand-L16", W.random_trace(17, L=16, N=130, P=300, K=1)          # power-of-two layers: 4 steps per block
+    yield "rand-L64", W.random_trace(18, L=64, N=66, P=40, K=1)            # one step per block
+    yield "rand-L2", W.random_trace(19, L=2, N=100, P=480, K=1)            # 15 words per row
 
 
 CASES = list(_cases())
 
 
-@pytest.mark.parametrize("kernel", [1, 2, 3], ids=["rows", "lanes", "lanes8w"])
+@pytest.mark.parametrize("kernel", [1, 2, 3, 4, 5, 6], ids=["rows", "lanes", "lanes8w", "direct", "direct8w", "quad"])
 @pytest.mark.parametrize("name,tr", CASES, ids=[c[0] for c in CASES])
 def test_score_matches_oracle_bit_for_bit(G, name, tr, kernel):
     from gpu_util import expected_counters
