@@ -193,7 +193,8 @@ uint64_t kvp_plane_unit(const kvp_ctx *ctx);
  * Results are identical bit for bit either way. */
 enum { KVP_SCORE_AUTO = 0, KVP_SCORE_ROWS = 1, KVP_SCORE_LANES = 2, KVP_SCORE_LANES_8W = 3,
        KVP_SCORE_DIRECT = 4, KVP_SCORE_DIRECT_8W = 5, /* lane per row, rows loaded without LDS staging */
-       KVP_SCORE_QUAD = 6 /* lane per row, four schedules per workgroup share the trace chunk */ };
+       KVP_SCORE_QUAD = 6, /* lane per row, four schedules per workgroup share the trace chunk */
+       KVP_SCORE_QUAD_4S = 7 /* the same with four instead of two layers in flight */ };
 int kvp_set_score_kernel(kvp_ctx *ctx, int which);
 
 const char *kvp_strerror(int code);

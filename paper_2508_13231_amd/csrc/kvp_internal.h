@@ -21,10 +21,16 @@ struct DevProblem {
     const uint32_t *wr;           // [N] pages written at the step
     const uint32_t *wsel;         // [N] index of the only word of Wm[n] with bits (0 if none), ~0 if several
     uint32_t single_write;        // every step's written pages sit in one word
+    const uint32_t *tilecls;      // [ceil(N/64)] two bits per word (n_words <= 16): see KVP_WORD_*
     uint32_t wt[KVP_MAX_PLANES];  // plane_bytes[k] / unit
     double unit_b, page_b, token_b;          // bytes, exact integers held in fp64
     double inv_bh, inv_bk, inv_bd, inv_min;  // reciprocals of Eqs. 3-4's bandwidths
 };
+
+// Class of a mask word over a tile of 64 token steps (and the step before it):
+// FULL: all 32 pages exist at every one of those steps and persist into every
+// step of the tile; EMPTY: none exists at any step of the tile; else MIXED.
+enum { KVP_WORD_MIXED = 0, KVP_WORD_FULL = 1, KVP_WORD_EMPTY = 2 };
 
 struct ChainState;   // kvp_moves.hip
 
@@ -36,6 +42,8 @@ struct kvp_ctx {
     DevProblem dp{};
     uint64_t unit = 0;
     int score_kernel = 0;                // KVP_SCORE_AUTO / _ROWS / _LANES
+    bool prefix_full = false;            // on every 64-step tile all mask words but the last are FULL
+    int quad_stages = 2;                 // register stages of the four-schedule scorer (2 or 4)
     int tile_quad = 1;                   // four schedules per workgroup (power-of-two layer counts)
     int tile_direct = 1;                 // narrow-row scorer without LDS staging (single plane only)
     int tile_waves = 4;                  // wavefronts per workgroup of the narrow-row scorer (4 or 8)

@@ -35,23 +35,30 @@ constexpr int A_SLOT = QUAD * 64 * 4;   // words of one trace slot: one 16-byte 
 // straight-line code lets the hardware counters tell exactly which stage has
 // arrived, so two stages really stay in flight.  The host guarantees that whole
 // 16-byte vectors can be read up to three words past any chunk (kvp_score_quad_launch).
-template <int WD, bool W1>
+// WD = n_words; W1: the pages written at a step sit in one word; PF: on every tile
+// all words but the last are FULL (kvp_internal.h), so only the last word needs
+// the alive / persist masks; NS: register stages (layers in flight), L % NS == 0.
+template <int WD, bool W1, bool PF, int NS>
 __global__ __launch_bounds__(QUAD * 64) void score_quad_kernel(
     DevProblem q, const uint32_t *__restrict__ X, uint32_t S, uint32_t tiles, uint32_t nb_total, uint32_t log2L,
     double *__restrict__ blocksum, uint32_t *__restrict__ tileflag, uint32_t *__restrict__ counters,
     uint32_t *__restrict__ occ_out) {
     extern __shared__ double smem_d[];
+    static_assert(NS == 2 || NS == 4, "two or four register stages");
     constexpr int XV = vecs_per_lane((TILE_N + 1) * WD);
     constexpr int XW = XV * 64 * 4;                               // a full vector slot per lane and round
-    constexpr int WREG = W1 ? 1 : WD;
+    constexpr int W0 = PF ? WD - 1 : 0;                           // first word that needs the masks
+    constexpr int MREG = WD - W0, WREG = W1 ? 1 : WD;
     const uint32_t L = 1u << log2L, N = q.N;
     const uint32_t tid = threadIdx.x;
     const int lane = lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / KVP_WAVE));
-    const uint32_t s = blockIdx.x * QUAD + wave;
+    // consecutive workgroups take the consecutive tiles of the same four schedules, so the rows of
+    // one (schedule, layer), contiguous in memory, are fetched at about the same time
+    const uint32_t tile = blockIdx.x % tiles;
+    const uint32_t s = (blockIdx.x / tiles) * QUAD + wave;
     const bool has_s = s < S;
     const uint32_t sc = has_s ? s : S - 1;                        // spare wavefronts shadow the last schedule
-    const uint32_t tile = blockIdx.y;
     const uint32_t n0 = tile * TILE_N;
     const uint32_t rows = min((uint32_t)TILE_N, N - n0);
     uint32_t *xbuf = (uint32_t *)smem_d + (size_t)wave * XW;
@@ -60,11 +67,11 @@ __global__ __launch_bounds__(QUAD * 64) void score_quad_kernel(
     const bool active = (uint32_t)lane < rows;
     const uint32_t lc = active ? (uint32_t)lane : rows - 1;           // idle lanes shadow the last row
     const uint32_t n = n0 + lc;
-    uint32_t vv[WD], pm[WD], wm[WREG];
+    uint32_t vv[MREG], pm[MREG], wm[WREG];
 #pragma unroll
-    for (int w = 0; w < WD; w++) {
-        vv[w] = q.V[(size_t)n * WD + w];
-        pm[w] = q.Pm[(size_t)n * WD + w];
+    for (int w = 0; w < MREG; w++) {
+        vv[w] = q.V[(size_t)n * WD + W0 + w];
+        pm[w] = q.Pm[(size_t)n * WD + W0 + w];
     }
     uint32_t wsel = 0;
     if (W1) {
@@ -87,7 +94,7 @@ __global__ __launch_bounds__(QUAD * 64) void score_quad_kernel(
         v4u a;
         uint32_t acc, xshift, ashift;
     };
-    Stage st0, st1;
+    Stage st0, st1, st2, st3;
     auto layer_of = [&](uint32_t it) { return log2L ? (__brev(it) >> (32 - log2L)) : 0u; };
     auto issue = [&](Stage &st, uint32_t it) __attribute__((always_inline)) {
         const uint32_t l = layer_of(it);
@@ -113,7 +120,7 @@ __global__ __launch_bounds__(QUAD * 64) void score_quad_kernel(
         for (int j = 0; j < XV; j++) *(v4u *)(xbuf + 4 * ((uint32_t)lane + 64u * j)) = st.x[j];
         *(v4u *)(aslot + 4 * tid) = st.a;
         const uint32_t xs = st.xshift, as = st.ashift, acc_n = st.acc;
-        issue(st, min(it + 2, L - 1));                          // rows of two layers ahead are now in flight
+        issue(st, min(it + NS, L - 1));                         // rows of NS layers ahead are now in flight
                                                                 // (past the end: a redundant, harmless reload)
         __syncthreads();                                        // this layer's trace slot is complete
         const uint32_t *cur = xbuf + xs + halo + lc * WD;
@@ -123,14 +130,25 @@ __global__ __launch_bounds__(QUAD * 64) void score_quad_kernel(
 #pragma unroll
         for (int w = 0; w < WD; w++) {
             const uint32_t raw = cur[w], xp = prv[w];
-            const uint32_t x = raw & vv[w];
-            fl_acc |= raw & ~vv[w];
-            hr += __popc(x & ar[w]);
-            if (!W1) hw += __popc(x & wm[w]);
-            oc += __popc(x);
-            const uint32_t d = (x ^ xp) & pm[w];
-            mi += __popc(d & x);
-            mg += __popc(d);
+            if (w < W0) {
+                // all 32 pages exist and persist on every step of the tile: no masking needed
+                // (at step 0 prv is cur, so nothing migrates there either)
+                hr += __popc(raw & ar[w]);
+                if (!W1) hw += __popc(raw & wm[w]);
+                oc += __popc(raw);
+                const uint32_t d = raw ^ xp;
+                mi += __popc(d & raw);
+                mg += __popc(d);
+            } else {
+                const uint32_t x = raw & vv[w - W0];
+                fl_acc |= raw & ~vv[w - W0];
+                hr += __popc(x & ar[w]);
+                if (!W1) hw += __popc(x & wm[w]);
+                oc += __popc(x);
+                const uint32_t d = (x ^ xp) & pm[w - W0];
+                mi += __popc(d & x);
+                mg += __popc(d);
+            }
         }
         if (W1) hw = __popc(cur[wsel] & wm[0]);                // written pages exist, so raw & wm == x & wm
         const uint32_t mo = mg - mi;
@@ -153,12 +171,14 @@ __global__ __launch_bounds__(QUAD * 64) void score_quad_kernel(
         }
         if (!parked) total = carry;                             // only at the last layer
     };
-    // L is even here (kvp_score_quad_launch): two layers per trip, one register stage each
+    // NS layers per trip, one register stage each (L is a multiple of NS)
     issue(st0, 0);
     issue(st1, 1);
-    for (uint32_t it = 0; it < L; it += 2) {
+    if (NS == 4) { issue(st2, 2); issue(st3, 3); }
+    for (uint32_t it = 0; it < L; it += NS) {
         body(st0, it);
         body(st1, it + 1);
+        if (NS == 4) { body(st2, it + 2); body(st3, it + 3); }
     }
     if (!has_s) return;
     // block sums: lane (b * 64/L) holds block b of this tile
@@ -184,13 +204,21 @@ int launch_quad(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uin
     constexpr size_t XW = (size_t)vecs_per_lane((TILE_N + 1) * WD) * 64 * 4;
     static_assert((TILE_N * WD + 3 + 3) / 4 <= QUAD * 64, "one vector per thread must cover a trace chunk");
     const size_t lds = (QUAD * XW + 2 * A_SLOT) * 4;
-    dim3 grid((S + QUAD - 1) / QUAD, tiles), block(QUAD * 64);
-    if (q.single_write)
-        score_quad_kernel<WD, true><<<grid, block, lds, ctx->stream>>>(q, X, S, tiles, nb_total, log2L, ctx->d_blocksum,
-                                                                    ctx->d_tileflag, counters, occ);
-    else
-        score_quad_kernel<WD, false><<<grid, block, lds, ctx->stream>>>(q, X, S, tiles, nb_total, log2L, ctx->d_blocksum,
-                                                                     ctx->d_tileflag, counters, occ);
+    const uint64_t nwg = (uint64_t)((S + QUAD - 1) / QUAD) * tiles;
+    if (nwg > 0x7FFFFFFFull) return 1;
+    dim3 grid((uint32_t)nwg), block(QUAD * 64);
+    const bool pf = WD > 1 && ctx->prefix_full, w1 = q.single_write != 0, deep = q.L % 4 == 0 && ctx->quad_stages == 4;
+#define KVP_GO(WW, PP, NN)                                                                             \
+    score_quad_kernel<WD, WW, PP, NN><<<grid, block, lds, ctx->stream>>>(q, X, S, tiles, nb_total, log2L, \
+                                                                        ctx->d_blocksum, ctx->d_tileflag, counters, occ)
+    if (deep) {
+        if (w1 && pf) KVP_GO(true, true, 4); else if (w1) KVP_GO(true, false, 4);
+        else if (pf) KVP_GO(false, true, 4); else KVP_GO(false, false, 4);
+    } else {
+        if (w1 && pf) KVP_GO(true, true, 2); else if (w1) KVP_GO(true, false, 2);
+        else if (pf) KVP_GO(false, true, 2); else KVP_GO(false, false, 2);
+    }
+#undef KVP_GO
     KVP_HIP(hipGetLastError());
     return KVP_OK;
 }

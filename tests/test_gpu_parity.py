@@ -44,7 +44,8 @@ def _cases():
 CASES = list(_cases())
 
 
-@pytest.mark.parametrize("kernel", [1, 2, 3, 4, 5, 6], ids=["rows", "lanes", "lanes8w", "direct", "direct8w", "quad"])
+@pytest.mark.parametrize("kernel", [1, 2, 3, 4, 5, 6, 7],
+                         ids=["rows", "lanes", "lanes8w", "direct", "direct8w", "quad", "quad4s"])
 @pytest.mark.parametrize("name,tr", CASES, ids=[c[0] for c in CASES])
 def test_score_matches_oracle_bit_for_bit(G, name, tr, kernel):
     from gpu_util import expected_counters
