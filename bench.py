@@ -26,6 +26,10 @@ import numpy as np
 
 HBM_PEAK = 8.0e12          # MI355X HBM3E, bytes/s
 GIB = 1 << 30
+# HBM bytes per kvp_score launch on the default workload with the default kernel, from rocprofv3
+# FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB device copy (profiles/kvp_score_llama8b.md).
+# Any other workload, batch size or kernel choice reports null.
+MEASURED_TRAFFIC = {("llama8b", 1.0, 14564): 4.502e9}
 
 
 def algorithmic_bytes(tr, S):
@@ -112,6 +116,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--score-only", action="store_true", help="time kvp_score alone (for profiling)")
     ap.add_argument("--score-kernel", type=int, default=0, help="kvp_set_score_kernel value (0 = auto)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain device copies of exactly 1 GiB, so that a counter run "
+                         "(FETCH_SIZE / WRITE_SIZE) sees a kernel of known traffic to scale by")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU; chains and schedules shard trivially across GPUs "
@@ -165,6 +172,13 @@ def main():
         K.kvp_best(ctx, shape_words)
         mark(4)
 
+    if a.calibrate_copy:
+        src = d_x.view(-1)[: GIB // 4]
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del dst
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
@@ -192,7 +206,8 @@ def main():
         "score_ms": score_ms, "score_ms_min": float(ph[:, 0].min()),
         "layer_steps_per_s": S * tr.N * tr.L / (score_ms * 1e-3),
         "roofline": {"bound": "hbm", "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK, "traffic": None,
+                     "frac": achieved / HBM_PEAK,
+                     "traffic": None if a.score_kernel else MEASURED_TRAFFIC.get((a.workload, a.scale, S)),
                      "kernel": "kvp_score (score kernel + block-sum finalize)", "bytes_per_launch": alg},
     }
     if not a.score_only:

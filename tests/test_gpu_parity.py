@@ -251,3 +251,32 @@ def test_error_paths_reach_no_kernel(G):
         assert e.value.code == K.KVP_EINVAL
     finally:
         K.kvp_destroy(ctx)
+
+
+def test_full_size_batch_sampled_against_oracle(G):
+    """The benchmark's own launch (config 1, S >= 4 GiB of schedules, default
+    kernel choice): sampled schedules are re-scored one by one by the oracle."""
+    import torch
+    import bench
+    import paper_2508_13231_amd as K
+    tr = W.config("llama8b")
+    S = bench.default_schedules(tr)
+    q = O.Problem(tr)
+    with G(tr) as g:
+        d_x = bench.make_batch(tr, S, g.dev)
+        d_cost = torch.empty(S, dtype=torch.float64, device=g.dev)
+        d_ex = torch.empty(S, dtype=torch.int32, device=g.dev)
+        K.kvp_score(g.ctx, d_x, S, d_cost, d_ex)
+        torch.cuda.synchronize()
+        cost = d_cost.cpu().numpy()
+        ex = d_ex.cpu().numpy().view(np.uint32)
+        pick = [0, 1, 2, 3, 4, S // 3, S // 2, S - 6, S - 5, S - 4, S - 3, S - 2, S - 1]
+        for s in pick:
+            X = g.unpack(d_x[s].cpu().numpy().view(np.uint32))
+            r = O.score(q, X)
+            assert cost[s] == r.cost and ex[s] == r.excess, s
+        # properties that hold for every schedule of the batch
+        assert np.isfinite(cost).all() and (cost > 0).all()
+        lo = O.cost(q, np.broadcast_to(tr.alive[None], q.shape).copy()) * tr.bw_hbm / (tr.bw_hbm + tr.bw_link)
+        assert cost.min() >= lo * (1 - 1e-12)                  # both tiers flat out bound every step
+        assert not (ex >> 31).any()                            # the batch is masked to existing pages
