@@ -80,8 +80,9 @@ extern "C" const char *kvp_strerror(int code) {
 }
 
 extern "C" int kvp_set_score_kernel(kvp_ctx *ctx, int which) {
-    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_QUAD_4S) return KVP_EINVAL;
-    ctx->tile_quad = which == KVP_SCORE_AUTO || which >= KVP_SCORE_QUAD;
+    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_WIDE) return KVP_EINVAL;
+    ctx->force_wide = which == KVP_SCORE_WIDE;
+    ctx->tile_quad = which == KVP_SCORE_AUTO || which == KVP_SCORE_QUAD || which == KVP_SCORE_QUAD_4S;
     ctx->quad_stages = which == KVP_SCORE_QUAD_4S ? 4 : 2;
     ctx->score_kernel = which >= KVP_SCORE_LANES ? KVP_SCORE_LANES : which;
     ctx->tile_waves = (which == KVP_SCORE_LANES_8W || which == KVP_SCORE_DIRECT_8W) ? 8 : 4;
@@ -149,7 +150,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     auto up4 = [](size_t x) { return (x + 3) & ~(size_t)3; };          // keep every array 16-byte aligned
     const size_t oV = up4(nA), oPm = oV + up4(nM), oWm = oPm + up4(nM), oAcc = oWm + up4(nM);
     const size_t oWr = oAcc + up4((size_t)(L * N)), oSel = oWr + up4((size_t)N);
-    const size_t T64 = (size_t)((N + 63) / 64), oCls = oSel + up4((size_t)N), total = oCls + up4(T64);
+    const size_t T64 = (size_t)((N + 63) / 64), oCls = oSel + up4((size_t)N), total = oCls + up4(4 * T64);
     KVP_HIP(hipMalloc((void **)&ctx->d_trace, total * sizeof(uint32_t)));
     uint32_t *d = ctx->d_trace;
     KVP_HIP(hipMemcpyAsync(d, h_access, nA * 4, hipMemcpyHostToDevice, ctx->stream));
@@ -164,34 +165,44 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     q.L = (uint32_t)L; q.N = (uint32_t)N; q.P = (uint32_t)P; q.Wd = (uint32_t)Wd; q.K = (uint32_t)K;
     q.cap = pr->cap_pages > 0x7FFFFFFFull ? 0x7FFFFFFFu : (uint32_t)pr->cap_pages;
     q.A = d; q.V = d + oV; q.Pm = d + oPm; q.Wm = d + oWm; q.acc = d + oAcc; q.wr = d + oWr; q.wsel = d + oSel; q.tilecls = d + oCls;
+    q.fullmask16 = d + oCls + T64; q.fullmask64 = d + oCls + 2 * T64; q.fullmask256 = d + oCls + 3 * T64;
     for (uint64_t k = 0; k < K; k++) q.wt[k] = (uint32_t)(pr->plane_bytes[k] / unit);
     q.unit_b = (double)unit; q.page_b = (double)pr->page_bytes; q.token_b = (double)pr->token_bytes;
     q.inv_bh = 1.0 / pr->bw_hbm; q.inv_bk = 1.0 / pr->bw_link; q.inv_bd = 1.0 / pr->bw_dram;
     q.inv_min = 1.0 / (pr->bw_link < pr->bw_dram ? pr->bw_link : pr->bw_dram);
-    {   // class of every mask word over each tile of 64 steps (narrow rows only)
-        uint32_t *cls = (uint32_t *)calloc(T64 ? T64 : 1, 4);
-        if (!cls) return KVP_ENOMEM;
-        if (Wd <= 16)
-            for (size_t t = 0; t < T64; t++) {
-                const uint64_t n0 = t * 64, n1 = n0 + 64 < N ? n0 + 64 : N;
-                for (uint64_t w = 0; w < Wd; w++) {
-                    bool full = true, empty = true;
-                    for (uint64_t n = n0 ? n0 - 1 : 0; n < n1; n++) {
-                        const uint32_t v = h_alive[n * Wd + w];
-                        if (v != 0xFFFFFFFFu) full = false;
-                        if (n >= n0 && v != 0) empty = false;
-                        if (n >= n0 && n >= 1 && h_persist[n * Wd + w] != 0xFFFFFFFFu) full = false;
-                    }
-                    cls[t] |= (uint32_t)(full ? KVP_WORD_FULL : empty ? KVP_WORD_EMPTY : KVP_WORD_MIXED) << (2 * w);
-                }
-            }
+    {   // class of every mask word over each tile of 64 steps, and groups of words that are all FULL
+        uint32_t *cls = (uint32_t *)calloc(4 * (T64 ? T64 : 1), 4);
+        uint8_t *fullw = (uint8_t *)malloc((size_t)Wd);
+        if (!cls || !fullw) { free(cls); free(fullw); return KVP_ENOMEM; }
+        uint32_t *m16 = cls + T64, *m64 = cls + 2 * T64, *m256 = cls + 3 * T64;
         ctx->prefix_full = Wd >= 2 && Wd <= 16;
-        for (size_t t = 0; t < T64 && ctx->prefix_full; t++)
-            for (uint64_t w = 0; w + 1 < Wd; w++)
-                if (((cls[t] >> (2 * w)) & 3u) != KVP_WORD_FULL) ctx->prefix_full = false;
-        hipError_t ec = hipMemcpyAsync(d + oCls, cls, T64 * 4, hipMemcpyHostToDevice, ctx->stream);
+        for (size_t t = 0; t < T64; t++) {
+            const uint64_t n0 = t * 64, n1 = n0 + 64 < N ? n0 + 64 : N;
+            for (uint64_t w = 0; w < Wd; w++) {
+                bool full = true, empty = true;
+                for (uint64_t n = n0 ? n0 - 1 : 0; n < n1; n++) {
+                    const uint32_t v = h_alive[n * Wd + w];
+                    if (v != 0xFFFFFFFFu) full = false;
+                    if (n >= n0 && v != 0) empty = false;
+                    if (n >= n0 && n >= 1 && h_persist[n * Wd + w] != 0xFFFFFFFFu) full = false;
+                }
+                fullw[w] = full;
+                if (Wd <= 16)
+                    cls[t] |= (uint32_t)(full ? KVP_WORD_FULL : empty ? KVP_WORD_EMPTY : KVP_WORD_MIXED) << (2 * w);
+                if (w + 1 < Wd && !full) ctx->prefix_full = false;
+            }
+            const uint64_t G[3] = {16, 64, 256};
+            uint32_t *M[3] = {m16, m64, m256};
+            for (int k = 0; k < 3; k++)
+                for (uint64_t i = 0; i < 16 && i * G[k] < Wd; i++) {
+                    bool all = true;                     // slots past the last word hold zeros: as good as full
+                    for (uint64_t w = i * G[k]; w < (i + 1) * G[k] && w < Wd; w++) all = all && fullw[w];
+                    if (all) M[k][t] |= 1u << i;
+                }
+        }
+        hipError_t ec = hipMemcpyAsync(d + oCls, cls, 4 * T64 * 4, hipMemcpyHostToDevice, ctx->stream);
         if (ec == hipSuccess) ec = hipStreamSynchronize(ctx->stream);
-        free(cls);
+        free(cls); free(fullw);
         KVP_HIP(ec);
     }
     int rc = kvp_trace_totals_launch(ctx, d + oAcc, d + oWr, d + oSel);

@@ -22,6 +22,8 @@ struct DevProblem {
     const uint32_t *wsel;         // [N] index of the only word of Wm[n] with bits (0 if none), ~0 if several
     uint32_t single_write;        // every step's written pages sit in one word
     const uint32_t *tilecls;      // [ceil(N/64)] two bits per word (n_words <= 16): see KVP_WORD_*
+    // [ceil(N/64)] bit i: words [i*G, (i+1)*G) are all FULL on the tile, G = 16, 64, 256 words
+    const uint32_t *fullmask16, *fullmask64, *fullmask256;
     uint32_t wt[KVP_MAX_PLANES];  // plane_bytes[k] / unit
     double unit_b, page_b, token_b;          // bytes, exact integers held in fp64
     double inv_bh, inv_bk, inv_bd, inv_min;  // reciprocals of Eqs. 3-4's bandwidths
@@ -44,6 +46,7 @@ struct kvp_ctx {
     int score_kernel = 0;                // KVP_SCORE_AUTO / _ROWS / _LANES
     bool prefix_full = false;            // on every 64-step tile all mask words but the last are FULL
     int quad_stages = 2;                 // register stages of the four-schedule scorer (2 or 4)
+    bool force_wide = false;             // use the wide-row scorer also for narrow rows
     int tile_quad = 1;                   // four schedules per workgroup (power-of-two layer counts)
     int tile_direct = 1;                 // narrow-row scorer without LDS staging (single plane only)
     int tile_waves = 4;                  // wavefronts per workgroup of the narrow-row scorer (4 or 8)

@@ -39,13 +39,17 @@ def _cases():
     yield "rand-L16", W.random_trace(17, L=16, N=130, P=300, K=1)          # power-of-two layers: 4 steps per block
     yield "rand-L64", W.random_trace(18, L=64, N=66, P=40, K=1)            # one step per block
     yield "rand-L2", W.random_trace(19, L=2, N=100, P=480, K=1)            # 15 words per row
+    yield "rand-w40", W.random_trace(20, L=3, N=70, P=1270, K=2)           # 40 words: 16 lanes per row, 3 loads
+    yield "rand-w300", W.random_trace(21, L=2, N=66, P=9600, K=1)          # 300 words, a multiple of 4: vector loads
+    yield "rand-w301", W.random_trace(22, L=2, N=20, P=9630, K=1)          # 301 words: a wavefront per row, word loads
+    yield "longctx/4", W.config("longctx", 0.25)                           # 17 words, most of them full
 
 
 CASES = list(_cases())
 
 
-@pytest.mark.parametrize("kernel", [1, 2, 3, 4, 5, 6, 7],
-                         ids=["rows", "lanes", "lanes8w", "direct", "direct8w", "quad", "quad4s"])
+@pytest.mark.parametrize("kernel", [1, 2, 3, 4, 5, 6, 7, 8],
+                         ids=["rows", "lanes", "lanes8w", "direct", "direct8w", "quad", "quad4s", "wide"])
 @pytest.mark.parametrize("name,tr", CASES, ids=[c[0] for c in CASES])
 def test_score_matches_oracle_bit_for_bit(G, name, tr, kernel):
     from gpu_util import expected_counters
