@@ -195,7 +195,8 @@ enum { KVP_SCORE_AUTO = 0, KVP_SCORE_ROWS = 1, KVP_SCORE_LANES = 2, KVP_SCORE_LA
        KVP_SCORE_DIRECT = 4, KVP_SCORE_DIRECT_8W = 5, /* lane per row, rows loaded without LDS staging */
        KVP_SCORE_QUAD = 6, /* lane per row, four schedules per workgroup share the trace chunk */
        KVP_SCORE_QUAD_4S = 7, /* the same with four instead of two layers in flight */
-       KVP_SCORE_WIDE = 8 /* 16 or 64 lanes per row (the choice for rows of more than 16 words) */ };
+       KVP_SCORE_WIDE = 8, /* 16 or 64 lanes per row, rows loaded straight from memory */
+       KVP_SCORE_CHUNK = 9 /* lane per row, wide rows walked in chunks of 16 words (choice for > 16 words) */ };
 int kvp_set_score_kernel(kvp_ctx *ctx, int which);
 
 const char *kvp_strerror(int code);

@@ -60,7 +60,7 @@ extern "C" void kvp_destroy(kvp_ctx *ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     kvp_free_chains(ctx);
     free_dev(ctx->d_trace); free_dev(ctx->d_blocksum); free_dev(ctx->d_tileflag);
-    free_dev(ctx->d_cnt_tmp); free_dev(ctx->d_occ_tmp);
+    free_dev(ctx->d_cnt_tmp); free_dev(ctx->d_occ_tmp); free_dev(ctx->d_tglobal); free_dev(ctx->d_chunkfull);
     delete ctx;
 }
 
@@ -80,11 +80,12 @@ extern "C" const char *kvp_strerror(int code) {
 }
 
 extern "C" int kvp_set_score_kernel(kvp_ctx *ctx, int which) {
-    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_WIDE) return KVP_EINVAL;
+    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_CHUNK) return KVP_EINVAL;
     ctx->force_wide = which == KVP_SCORE_WIDE;
+    ctx->use_chunk = which == KVP_SCORE_AUTO || which == KVP_SCORE_CHUNK;
     ctx->tile_quad = which == KVP_SCORE_AUTO || which == KVP_SCORE_QUAD || which == KVP_SCORE_QUAD_4S;
     ctx->quad_stages = which == KVP_SCORE_QUAD_4S ? 4 : 2;
-    ctx->score_kernel = which >= KVP_SCORE_LANES ? KVP_SCORE_LANES : which;
+    ctx->score_kernel = which == KVP_SCORE_CHUNK ? KVP_SCORE_CHUNK : which >= KVP_SCORE_LANES ? KVP_SCORE_LANES : which;
     ctx->tile_waves = (which == KVP_SCORE_LANES_8W || which == KVP_SCORE_DIRECT_8W) ? 8 : 4;
     ctx->tile_direct = which >= KVP_SCORE_DIRECT || which == KVP_SCORE_AUTO;
     return KVP_OK;
@@ -145,6 +146,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     KVP_HIP(hipStreamSynchronize(ctx->stream));
     kvp_free_chains(ctx);
     free_dev(ctx->d_trace); ctx->d_trace = nullptr; ctx->has_trace = false;
+    free_dev(ctx->d_chunkfull); ctx->d_chunkfull = nullptr; ctx->cf_words = 0;
 
     const size_t nA = (size_t)(L * N * K * Wd), nM = (size_t)(N * Wd);
     auto up4 = [](size_t x) { return (x + 3) & ~(size_t)3; };          // keep every array 16-byte aligned
@@ -173,7 +175,9 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     {   // class of every mask word over each tile of 64 steps, and groups of words that are all FULL
         uint32_t *cls = (uint32_t *)calloc(4 * (T64 ? T64 : 1), 4);
         uint8_t *fullw = (uint8_t *)malloc((size_t)Wd);
-        if (!cls || !fullw) { free(cls); free(fullw); return KVP_ENOMEM; }
+        const uint64_t NCH = (Wd + 15) / 16, CFW = (NCH + 31) / 32;
+        uint32_t *cfull = (uint32_t *)calloc((size_t)(T64 * CFW ? T64 * CFW : 1), 4);
+        if (!cls || !fullw || !cfull) { free(cls); free(fullw); free(cfull); return KVP_ENOMEM; }
         uint32_t *m16 = cls + T64, *m64 = cls + 2 * T64, *m256 = cls + 3 * T64;
         ctx->prefix_full = Wd >= 2 && Wd <= 16;
         for (size_t t = 0; t < T64; t++) {
@@ -191,6 +195,11 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
                     cls[t] |= (uint32_t)(full ? KVP_WORD_FULL : empty ? KVP_WORD_EMPTY : KVP_WORD_MIXED) << (2 * w);
                 if (w + 1 < Wd && !full) ctx->prefix_full = false;
             }
+            for (uint64_t c = 0; c < NCH; c++) {
+                bool all = true;
+                for (uint64_t w = c * 16; w < (c + 1) * 16 && w < Wd; w++) all = all && fullw[w];
+                if (all) cfull[t * CFW + c / 32] |= 1u << (c % 32);
+            }
             const uint64_t G[3] = {16, 64, 256};
             uint32_t *M[3] = {m16, m64, m256};
             for (int k = 0; k < 3; k++)
@@ -201,8 +210,12 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
                 }
         }
         hipError_t ec = hipMemcpyAsync(d + oCls, cls, 4 * T64 * 4, hipMemcpyHostToDevice, ctx->stream);
+        if (ec == hipSuccess) ec = hipMalloc((void **)&ctx->d_chunkfull, (size_t)T64 * CFW * 4);
+        if (ec == hipSuccess)
+            ec = hipMemcpyAsync(ctx->d_chunkfull, cfull, (size_t)T64 * CFW * 4, hipMemcpyHostToDevice, ctx->stream);
         if (ec == hipSuccess) ec = hipStreamSynchronize(ctx->stream);
-        free(cls); free(fullw);
+        ctx->cf_words = (uint32_t)CFW;
+        free(cls); free(fullw); free(cfull);
         KVP_HIP(ec);
     }
     int rc = kvp_trace_totals_launch(ctx, d + oAcc, d + oWr, d + oSel);

@@ -46,6 +46,7 @@ struct kvp_ctx {
     int score_kernel = 0;                // KVP_SCORE_AUTO / _ROWS / _LANES
     bool prefix_full = false;            // on every 64-step tile all mask words but the last are FULL
     int quad_stages = 2;                 // register stages of the four-schedule scorer (2 or 4)
+    bool use_chunk = true;               // chunked four-schedule scorer for wide rows
     bool force_wide = false;             // use the wide-row scorer also for narrow rows
     int tile_quad = 1;                   // four schedules per workgroup (power-of-two layer counts)
     int tile_direct = 1;                 // narrow-row scorer without LDS staging (single plane only)
@@ -54,6 +55,8 @@ struct kvp_ctx {
     // scoring scratch
     double *d_blocksum = nullptr;  size_t blocksum_cap = 0;   // [S][nb]
     uint32_t *d_tileflag = nullptr; size_t tileflag_cap = 0;  // [S][tiles]
+    double *d_tglobal = nullptr; size_t tglobal_cap = 0;      // [S][L][N] step latencies (wide rows)
+    uint32_t *d_chunkfull = nullptr; uint32_t cf_words = 0;   // [tiles][cf_words] bit c: chunk c of 16 words is FULL
     uint32_t *d_cnt_tmp = nullptr; size_t cnt_tmp_cap = 0;    // delta: counters when not given
     uint32_t *d_occ_tmp = nullptr; size_t occ_tmp_cap = 0;
     // annealing state

@@ -156,6 +156,8 @@ static uint32_t gcd_u32(uint32_t a, uint32_t b) { while (b) { uint32_t t = a % b
 
 int kvp_score_tile_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
                           uint32_t *counters, uint32_t *occ);
+int kvp_score_chunk_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+                           uint32_t *counters, uint32_t *occ);
 int kvp_score_wide_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
                           uint32_t *counters, uint32_t *occ);
 int kvp_score_quad_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
@@ -167,12 +169,15 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
     if (S == 0) return KVP_OK;
     int rc;
     const uint32_t nb_total = (uint32_t)(((uint64_t)q.L * q.N + 63) / 64);
-    if (ctx->score_kernel != KVP_SCORE_ROWS && (q.Wd > 16 || ctx->force_wide)) {
+    if (ctx->score_kernel != KVP_SCORE_ROWS && (q.Wd > 16 || ctx->force_wide || (q.Wd == 16 && ctx->score_kernel == KVP_SCORE_CHUNK))) {
         // wide rows: 16 or 64 lanes per row, 64 token steps per tile
         const uint32_t tiles64 = (q.N + 63) / 64;
         if ((rc = kvp_ensure(ctx, (void **)&ctx->d_blocksum, &ctx->blocksum_cap, (size_t)S * nb_total * sizeof(double)))) return rc;
         if ((rc = kvp_ensure(ctx, (void **)&ctx->d_tileflag, &ctx->tileflag_cap, (size_t)S * tiles64 * sizeof(uint32_t)))) return rc;
-        rc = kvp_score_wide_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
+        rc = 1;
+        if (ctx->use_chunk && !ctx->force_wide)
+            rc = kvp_score_chunk_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
+        if (rc == 1) rc = kvp_score_wide_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
         if (rc < 0) return rc;
         if (rc == KVP_OK) {
             score_finalize_kernel<<<dim3((S + 255) / 256), dim3(256), 0, ctx->stream>>>(

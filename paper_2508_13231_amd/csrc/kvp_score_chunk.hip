@@ -1,0 +1,246 @@
+// Scorer for wide rows (n_words >= 16), any layer count, any number of planes.
+//
+// The narrow-row scheme (a lane per (layer, step) row, four schedules per
+// workgroup sharing the trace, two stages in flight in registers) carried over
+// to rows of any width by walking a row in CHUNKS of 16 words:
+//
+//   * one iteration = (layer l, chunk c): the wavefront fetches words
+//     [w0, w0+16) of its 65 rows (the 64 steps of the tile and the step before)
+//     as 16-byte vectors, four per row, parks them in its LDS slice with a row
+//     stride of 17 words (odd: lane-per-row reads hit 64 different banks) and
+//     each lane adds its row's 16 words to the row's counters, which live in
+//     registers until the row's last chunk;
+//   * the trace words of the chunk (planes, alive, persist, written) are the same
+//     for the four schedules: fetched once per workgroup, one vector per thread
+//     and array, into a double-buffered LDS slot; a chunk whose words are FULL on
+//     the tile needs no alive / persist words at all;
+//   * the last chunk of a row is shifted left to end at the row's end, so that no
+//     load ever leaves the row; the words it shares with the chunk before are
+//     zeroed after the load;
+//   * step latencies go to a [S][L][N] array in HBM (16 bytes of traffic per row
+//     of >= 64 bytes) and a second kernel sums them in execution order with the
+//     64-wide tree.
+#include "kvp_internal.h"
+#include "kvp_lane_common.h"
+
+namespace {
+
+typedef uint32_t c4u __attribute__((ext_vector_type(4), aligned(4)));   // rows are only 4-byte aligned
+
+constexpr int CQ = 4;          // schedules (= wavefronts) per workgroup
+constexpr int CW = 16;         // words per chunk
+constexpr int RS = 17;         // LDS row stride in words
+constexpr int XROWS = TILE_N + 1;
+constexpr int XSLICE = XROWS * RS + 3;          // words of a wavefront's slice
+constexpr int XVEC = (XROWS * (CW / 4) + 63) / 64;   // vectors per lane: 65 rows x 4 vectors / 64 lanes -> 5
+constexpr int TPLANE = TILE_N * RS;             // words of one trace array in a slot
+
+__device__ __forceinline__ void put4(uint32_t *p, c4u v) { p[0] = v.x; p[1] = v.y; p[2] = v.z; p[3] = v.w; }
+
+// KONE: a single plane of weight one, prefetched in registers with the schedule rows.
+template <bool W1, bool KONE>
+__global__ __launch_bounds__(CQ * 64) void score_chunk_kernel(
+    DevProblem q, const uint32_t *__restrict__ X, uint32_t S, uint32_t tiles, const uint32_t *__restrict__ chunkfull,
+    uint32_t cf_words, double *__restrict__ tglobal, uint32_t *__restrict__ tileflag,
+    uint32_t *__restrict__ counters, uint32_t *__restrict__ occ_out) {
+    extern __shared__ double smem_d[];
+    const uint32_t L = q.L, N = q.N, K = q.K, Wd = q.Wd;
+    const uint32_t NCH = (Wd + CW - 1) / CW;
+    const uint32_t tid = threadIdx.x;
+    const int lane = lane_id();
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / KVP_WAVE));
+    const uint32_t tile = blockIdx.x % tiles;
+    const uint32_t s = (blockIdx.x / tiles) * CQ + wave;
+    const bool has_s = s < S;
+    const uint32_t sc = has_s ? s : S - 1;
+    const uint32_t n0 = tile * TILE_N;
+    const uint32_t rows = min((uint32_t)TILE_N, N - n0);
+    const uint32_t nplanes = K + 3;                                   // planes, alive, persist, written
+    uint32_t *xbuf = (uint32_t *)smem_d + (size_t)wave * XSLICE;
+    uint32_t *tbuf = (uint32_t *)smem_d + (size_t)CQ * XSLICE;        // two slots of nplanes * TPLANE words
+
+    const bool active = (uint32_t)lane < rows;
+    const uint32_t lc = active ? (uint32_t)lane : rows - 1;
+    const uint32_t n = n0 + lc;
+    const uint32_t wr_n = q.wr[n];
+    // X vectors of this lane: vector vi covers row vi/4 of the 65 (row 0 = the step before the tile,
+    // clamped to step 0 for the first tile: it is only used where persist allows) and part vi%4
+    uint32_t xrow[XVEC], xpart[XVEC];
+#pragma unroll
+    for (int jv = 0; jv < XVEC; jv++) {
+        const uint32_t vi = min((uint32_t)lane + 64u * jv, (uint32_t)(XROWS * 4 - 1));
+        const uint32_t r = vi >> 2;                                    // 0 .. 64
+        const uint32_t nn = n0 + r;                                    // step + 1
+        xrow[jv] = min(nn > 0 ? nn - 1 : 0u, N - 1);
+        xpart[jv] = vi & 3u;
+    }
+    // trace vector of this thread: row tid/4 of the 64, part tid%4
+    const uint32_t trow = min(n0 + (tid >> 2), N - 1), tpart = tid & 3u;
+
+    struct Stage {
+        c4u x[XVEC];
+        c4u a, v, p, w;
+    };
+    Stage st0, st1;
+    const uint32_t iters = L * NCH;
+    auto issue = [&](Stage &st, uint32_t it) __attribute__((always_inline)) {
+        const uint32_t l = it / NCH, c = it - l * NCH;
+        const uint32_t w0 = min(c * CW, Wd - CW);
+        const uint32_t *Xl = X + ((size_t)sc * L + l) * N * Wd + w0;
+#pragma unroll
+        for (int jv = 0; jv < XVEC; jv++) st.x[jv] = *(const c4u *)(Xl + (size_t)xrow[jv] * Wd + 4 * xpart[jv]);
+        if (KONE) {
+            const size_t o = (size_t)trow * Wd + w0 + 4 * tpart;
+            st.a = *(const c4u *)(q.A + (size_t)l * N * Wd + o);
+            st.v = *(const c4u *)(q.V + o);
+            st.p = *(const c4u *)(q.Pm + o);
+            if (!W1) st.w = *(const c4u *)(q.Wm + o);
+        }
+    };
+
+    uint32_t hr = 0, hw = 0, mi = 0, mg = 0, oc = 0, fl_acc = 0, occ_acc = 0;
+    auto body = [&](Stage &st, uint32_t it) __attribute__((always_inline)) {
+        const uint32_t l = it / NCH, c = it - l * NCH;
+        const uint32_t w0 = min(c * CW, Wd - CW);
+        const uint32_t skip = c * CW - w0;                           // leading words already counted (last chunk only)
+        const bool full = (chunkfull[(size_t)tile * cf_words + (c >> 5)] >> (c & 31u)) & 1u;
+        uint32_t *slot = tbuf + (it & 1u) * nplanes * TPLANE;
+        // park the rows (zeroing words that the chunk before has counted)
+#pragma unroll
+        for (int jv = 0; jv < XVEC; jv++) {
+            c4u v = st.x[jv];
+            if (skip) {
+                const uint32_t b = 4 * xpart[jv];
+                v.x = b + 0 < skip ? 0u : v.x; v.y = b + 1 < skip ? 0u : v.y;
+                v.z = b + 2 < skip ? 0u : v.z; v.w = b + 3 < skip ? 0u : v.w;
+            }
+            const uint32_t vi = (uint32_t)lane + 64u * jv;
+            if (vi < XROWS * 4) put4(xbuf + (vi >> 2) * RS + 4 * (vi & 3u), v);
+        }
+        // park the trace words of the chunk, once for the four schedules
+        const uint32_t to = (tid >> 2) * RS + 4 * tpart;
+        if (KONE) {
+            put4(slot + to, st.a);
+            if (!full) { put4(slot + (K + 0) * TPLANE + to, st.v); put4(slot + (K + 1) * TPLANE + to, st.p); }
+            if (!W1) put4(slot + (K + 2) * TPLANE + to, st.w);
+        } else {
+            const size_t o = (size_t)trow * Wd + w0 + 4 * tpart;
+            const uint32_t *Ap = q.A + ((size_t)l * N + trow) * K * Wd + w0 + 4 * tpart;
+            for (uint32_t k = 0; k < K; k++) put4(slot + k * TPLANE + to, *(const c4u *)(Ap + (size_t)k * Wd));
+            if (!full) {
+                put4(slot + (K + 0) * TPLANE + to, *(const c4u *)(q.V + o));
+                put4(slot + (K + 1) * TPLANE + to, *(const c4u *)(q.Pm + o));
+            }
+            if (!W1) put4(slot + (K + 2) * TPLANE + to, *(const c4u *)(q.Wm + o));
+        }
+        issue(st, min(it + 2, iters - 1));
+        __syncthreads();
+        const uint32_t *cur = xbuf + (lc + 1) * RS, *prv = xbuf + lc * RS;
+        const uint32_t *ts = slot + lc * RS;
+#pragma unroll
+        for (int i = 0; i < CW; i++) {
+            const uint32_t raw = cur[i], xp = prv[i];
+            uint32_t x, d;
+            if (full) {
+                x = raw;
+                d = raw ^ xp;
+            } else {
+                const uint32_t vv = ts[(K + 0) * TPLANE + i], pmw = ts[(K + 1) * TPLANE + i];
+                x = raw & vv;
+                fl_acc |= raw & ~vv;
+                d = (x ^ xp) & pmw;
+            }
+            if (KONE) {
+                hr += __popc(x & ts[i]);
+            } else {
+                for (uint32_t k = 0; k < K; k++) hr += q.wt[k] * __popc(x & ts[k * TPLANE + i]);
+            }
+            if (!W1) hw += __popc(x & ts[(K + 2) * TPLANE + i]);
+            oc += __popc(x);
+            mi += __popc(d & x);
+            mg += __popc(d);
+        }
+        if (c == NCH - 1) {
+            // the row is complete: Eqs. 2-4
+            if (n == 0) { mi = 0; mg = 0; }                          // nothing migrates at the first step
+            if (W1) {
+                const uint32_t ws = q.wsel[n];
+                hw = __popc(X[(((size_t)sc * L + l) * N + n) * Wd + ws] & q.Wm[(size_t)n * Wd + ws]);
+            }
+            const uint32_t mo = mg - mi;
+            const size_t row = (size_t)l * N + n;
+            const double t = step_time(q, hr, hw, mi, mo, q.acc[row], wr_n);
+            if (has_s && active) {
+                tglobal[(size_t)s * L * N + row] = t;
+                if (counters) *(uint4 *)(counters + ((size_t)s * L * N + row) * 4) = make_uint4(hr, hw, mi, mo);
+            }
+            occ_acc += oc;
+            hr = hw = mi = mg = oc = 0;
+        }
+    };
+    issue(st0, 0);
+    issue(st1, min(1u, iters - 1));
+    for (uint32_t it = 0; it < iters; it += 2) {
+        body(st0, it);
+        if (it + 1 < iters) body(st1, it + 1);
+    }
+    if (!has_s) return;
+    uint32_t ex = 0;
+    if (active) {
+        if (occ_out) occ_out[(size_t)s * N + n] = occ_acc;
+        ex = occ_acc > q.cap ? occ_acc - q.cap : 0;
+    }
+    ex = wave_max_u32(ex);
+    const uint32_t fl = wave_or_u32(active ? fl_acc : 0u);
+    if (lane == 0) tileflag[(size_t)s * tiles + tile] = ex | (fl ? 0x80000000u : 0u);
+}
+
+// Eq. 1 from the step latencies in HBM: one wavefront per 64-block of the
+// execution order g = n*L + l of one schedule.
+__global__ __launch_bounds__(256) void blocksum_from_t_kernel(uint32_t S, uint32_t L, uint32_t N, uint32_t nb_total,
+                                                              const double *__restrict__ tglobal,
+                                                              double *__restrict__ blocksum) {
+    const uint64_t wv = (uint64_t)blockIdx.x * 4 + threadIdx.x / KVP_WAVE;
+    if (wv >= (uint64_t)S * nb_total) return;
+    const uint32_t s = (uint32_t)(wv / nb_total), b = (uint32_t)(wv % nb_total);
+    const uint64_t g = (uint64_t)b * 64 + lane_id();
+    double t = 0.0;
+    if (g < (uint64_t)L * N) {
+        const uint32_t n = (uint32_t)(g / L), l = (uint32_t)(g % L);
+        t = tglobal[((size_t)s * L + l) * N + n];
+    }
+    t = wave_tree_sum_f64(t);
+    if (lane_id() == 0) blocksum[(size_t)s * nb_total + b] = t;
+}
+
+}  // namespace
+
+// Returns KVP_OK if launched, 1 if this kernel does not cover the shape, <0 on error.
+int kvp_score_chunk_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+                           uint32_t *counters, uint32_t *occ) {
+    const DevProblem &q = ctx->dp;
+    if (q.Wd < CW || !ctx->d_chunkfull) return 1;
+    const size_t lds = ((size_t)CQ * XSLICE + 2 * (size_t)(q.K + 3) * TPLANE) * 4;
+    if (lds > 160 * 1024) return 1;
+    const uint64_t nwg = (uint64_t)((S + CQ - 1) / CQ) * tiles;
+    if (nwg > 0x7FFFFFFFull) return 1;
+    int rc = kvp_ensure(ctx, (void **)&ctx->d_tglobal, &ctx->tglobal_cap, (size_t)S * q.L * q.N * sizeof(double));
+    if (rc) return rc;
+    const bool kone = q.K == 1 && q.wt[0] == 1, w1 = q.single_write != 0;
+    dim3 grid((uint32_t)nwg), block(CQ * 64);
+#define KVP_GO(WW, KK)                                                                                       \
+    if (lds > 48 * 1024)                                                                                     \
+        KVP_HIP(hipFuncSetAttribute((const void *)score_chunk_kernel<WW, KK>,                                \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                 \
+    score_chunk_kernel<WW, KK><<<grid, block, lds, ctx->stream>>>(q, X, S, tiles, ctx->d_chunkfull, ctx->cf_words, \
+                                                                  ctx->d_tglobal, ctx->d_tileflag, counters, occ)
+    if (w1 && kone) { KVP_GO(true, true); } else if (w1) { KVP_GO(true, false); }
+    else if (kone) { KVP_GO(false, true); } else { KVP_GO(false, false); }
+#undef KVP_GO
+    KVP_HIP(hipGetLastError());
+    const uint64_t nwv = (uint64_t)S * nb_total;
+    blocksum_from_t_kernel<<<dim3((uint32_t)((nwv + 3) / 4)), dim3(256), 0, ctx->stream>>>(S, q.L, q.N, nb_total,
+                                                                                         ctx->d_tglobal, ctx->d_blocksum);
+    KVP_HIP(hipGetLastError());
+    return KVP_OK;
+}

@@ -43,13 +43,16 @@ def _cases():
     yield "rand-w300", W.random_trace(21, L=2, N=66, P=9600, K=1)          # 300 words, a multiple of 4: vector loads
     yield "rand-w301", W.random_trace(22, L=2, N=20, P=9630, K=1)          # 301 words: a wavefront per row, word loads
     yield "longctx/4", W.config("longctx", 0.25)                           # 17 words, most of them full
+    yield "longctx/2", W.config("longctx", 0.5)                            # 33 words
+    yield "gqa70b/4", W.config("gqa70b", 0.25)                             # 9 words ... 8 planes, 20 layers
+    yield "rand-w16", W.random_trace(23, L=4, N=65, P=512, K=2)            # exactly one chunk of 16 words
 
 
 CASES = list(_cases())
 
 
-@pytest.mark.parametrize("kernel", [1, 2, 3, 4, 5, 6, 7, 8],
-                         ids=["rows", "lanes", "lanes8w", "direct", "direct8w", "quad", "quad4s", "wide"])
+@pytest.mark.parametrize("kernel", [1, 2, 3, 4, 5, 6, 7, 8, 9],
+                         ids=["rows", "lanes", "lanes8w", "direct", "direct8w", "quad", "quad4s", "wide", "chunk"])
 @pytest.mark.parametrize("name,tr", CASES, ids=[c[0] for c in CASES])
 def test_score_matches_oracle_bit_for_bit(G, name, tr, kernel):
     from gpu_util import expected_counters
