@@ -20,6 +20,8 @@
 //   * step latencies go to a [S][L][N] array in HBM (16 bytes of traffic per row
 //     of >= 64 bytes) and a second kernel sums them in execution order with the
 //     64-wide tree.
+#include <type_traits>
+
 #include "kvp_internal.h"
 #include "kvp_lane_common.h"
 
@@ -37,14 +39,18 @@ constexpr int TPLANE = TILE_N * RS;             // words of one trace array in a
 
 __device__ __forceinline__ void put4(uint32_t *p, c4u v) { p[0] = v.x; p[1] = v.y; p[2] = v.z; p[3] = v.w; }
 
-// KONE: a single plane of weight one, prefetched in registers with the schedule rows.
-template <bool W1, bool KONE>
+// KT = number of access planes (compile time: the trace vectors of a chunk sit in registers).
+// No load inside the loop is consumed in the iteration that issues it: the schedule rows are
+// requested two iterations ahead, the trace words one iteration ahead, and everything is
+// unconditional, so the hardware counters tell exactly what has arrived.
+template <bool W1, int KT>
 __global__ __launch_bounds__(CQ * 64) void score_chunk_kernel(
     DevProblem q, const uint32_t *__restrict__ X, uint32_t S, uint32_t tiles, const uint32_t *__restrict__ chunkfull,
     uint32_t cf_words, double *__restrict__ tglobal, uint32_t *__restrict__ tileflag,
     uint32_t *__restrict__ counters, uint32_t *__restrict__ occ_out) {
     extern __shared__ double smem_d[];
-    const uint32_t L = q.L, N = q.N, K = q.K, Wd = q.Wd;
+    constexpr int NT = KT + 2 + (W1 ? 0 : 1);                        // planes, alive, persist(, written)
+    const uint32_t L = q.L, N = q.N, Wd = q.Wd;
     const uint32_t NCH = (Wd + CW - 1) / CW;
     const uint32_t tid = threadIdx.x;
     const int lane = lane_id();
@@ -55,121 +61,128 @@ __global__ __launch_bounds__(CQ * 64) void score_chunk_kernel(
     const uint32_t sc = has_s ? s : S - 1;
     const uint32_t n0 = tile * TILE_N;
     const uint32_t rows = min((uint32_t)TILE_N, N - n0);
-    const uint32_t nplanes = K + 3;                                   // planes, alive, persist, written
     uint32_t *xbuf = (uint32_t *)smem_d + (size_t)wave * XSLICE;
-    uint32_t *tbuf = (uint32_t *)smem_d + (size_t)CQ * XSLICE;        // two slots of nplanes * TPLANE words
+    uint32_t *tbuf = (uint32_t *)smem_d + (size_t)CQ * XSLICE;        // two slots of NT * TPLANE words
 
     const bool active = (uint32_t)lane < rows;
     const uint32_t lc = active ? (uint32_t)lane : rows - 1;
     const uint32_t n = n0 + lc;
     const uint32_t wr_n = q.wr[n];
+    const uint32_t wsel = W1 ? q.wsel[n] : 0u;
+    const uint32_t wmw = W1 ? q.Wm[(size_t)n * Wd + wsel] : 0u;
     // X vectors of this lane: vector vi covers row vi/4 of the 65 (row 0 = the step before the tile,
-    // clamped to step 0 for the first tile: it is only used where persist allows) and part vi%4
-    uint32_t xrow[XVEC], xpart[XVEC];
+    // step 0 itself for the first tile: then nothing differs and nothing migrates) and part vi%4
+    uint32_t xoff[XVEC];
 #pragma unroll
     for (int jv = 0; jv < XVEC; jv++) {
         const uint32_t vi = min((uint32_t)lane + 64u * jv, (uint32_t)(XROWS * 4 - 1));
-        const uint32_t r = vi >> 2;                                    // 0 .. 64
-        const uint32_t nn = n0 + r;                                    // step + 1
-        xrow[jv] = min(nn > 0 ? nn - 1 : 0u, N - 1);
-        xpart[jv] = vi & 3u;
+        const uint32_t nn = n0 + (vi >> 2);                            // step + 1
+        xoff[jv] = min(nn > 0 ? nn - 1 : 0u, N - 1) * Wd + 4 * (vi & 3u);
     }
     // trace vector of this thread: row tid/4 of the 64, part tid%4
     const uint32_t trow = min(n0 + (tid >> 2), N - 1), tpart = tid & 3u;
+    const uint32_t toff = trow * Wd + 4 * tpart, tlds = (tid >> 2) * RS + 4 * tpart;
 
     struct Stage {
         c4u x[XVEC];
-        c4u a, v, p, w;
+        uint32_t acc;
     };
     Stage st0, st1;
+    c4u tr[NT];
     const uint32_t iters = L * NCH;
-    auto issue = [&](Stage &st, uint32_t it) __attribute__((always_inline)) {
-        const uint32_t l = it / NCH, c = it - l * NCH;
+    // iteration it = (layer it / NCH, chunk it % NCH); kept incrementally for the three streams
+    auto advance = [&](uint32_t &l, uint32_t &c) __attribute__((always_inline)) {
+        if (++c == NCH) { c = 0; if (l + 1 < L) l++; else c = NCH - 1; }   // past the end: stay on the last chunk
+    };
+    auto issue_x = [&](Stage &st, uint32_t l, uint32_t c) __attribute__((always_inline)) {
         const uint32_t w0 = min(c * CW, Wd - CW);
         const uint32_t *Xl = X + ((size_t)sc * L + l) * N * Wd + w0;
 #pragma unroll
-        for (int jv = 0; jv < XVEC; jv++) st.x[jv] = *(const c4u *)(Xl + (size_t)xrow[jv] * Wd + 4 * xpart[jv]);
-        if (KONE) {
-            const size_t o = (size_t)trow * Wd + w0 + 4 * tpart;
-            st.a = *(const c4u *)(q.A + (size_t)l * N * Wd + o);
-            st.v = *(const c4u *)(q.V + o);
-            st.p = *(const c4u *)(q.Pm + o);
-            if (!W1) st.w = *(const c4u *)(q.Wm + o);
-        }
+        for (int jv = 0; jv < XVEC; jv++) st.x[jv] = *(const c4u *)(Xl + xoff[jv]);
+        st.acc = q.acc[(size_t)l * N + n];
+    };
+    auto issue_t = [&](uint32_t l, uint32_t c) __attribute__((always_inline)) {
+        const uint32_t w0 = min(c * CW, Wd - CW);
+        const uint32_t *Ap = q.A + ((size_t)l * N + trow) * KT * Wd + w0 + 4 * tpart;
+#pragma unroll
+        for (int k = 0; k < KT; k++) tr[k] = *(const c4u *)(Ap + (size_t)k * Wd);
+        tr[KT] = *(const c4u *)(q.V + toff + w0);
+        tr[KT + 1] = *(const c4u *)(q.Pm + toff + w0);
+        if (!W1) tr[NT - 1] = *(const c4u *)(q.Wm + toff + w0);
+    };
+    auto commit_t = [&](uint32_t it) __attribute__((always_inline)) {
+        uint32_t *slot = tbuf + (it & 1u) * NT * TPLANE + tlds;
+#pragma unroll
+        for (int k = 0; k < NT; k++) put4(slot + k * TPLANE, tr[k]);
     };
 
     uint32_t hr = 0, hw = 0, mi = 0, mg = 0, oc = 0, fl_acc = 0, occ_acc = 0;
+    uint32_t l0 = 0, c0 = 0;                 // iteration being scored
+    uint32_t lt = 0, ct = 0;                 // iteration whose trace words are requested next
+    uint32_t lx = 0, cx = 0;                 // iteration whose rows are requested next
     auto body = [&](Stage &st, uint32_t it) __attribute__((always_inline)) {
-        const uint32_t l = it / NCH, c = it - l * NCH;
+        const uint32_t l = l0, c = c0;
         const uint32_t w0 = min(c * CW, Wd - CW);
         const uint32_t skip = c * CW - w0;                           // leading words already counted (last chunk only)
         const bool full = (chunkfull[(size_t)tile * cf_words + (c >> 5)] >> (c & 31u)) & 1u;
-        uint32_t *slot = tbuf + (it & 1u) * nplanes * TPLANE;
+        const uint32_t *slot = tbuf + (it & 1u) * NT * TPLANE;
         // park the rows (zeroing words that the chunk before has counted)
 #pragma unroll
         for (int jv = 0; jv < XVEC; jv++) {
             c4u v = st.x[jv];
+            const uint32_t vi = (uint32_t)lane + 64u * jv;
             if (skip) {
-                const uint32_t b = 4 * xpart[jv];
+                const uint32_t b = 4 * (vi & 3u);
                 v.x = b + 0 < skip ? 0u : v.x; v.y = b + 1 < skip ? 0u : v.y;
                 v.z = b + 2 < skip ? 0u : v.z; v.w = b + 3 < skip ? 0u : v.w;
             }
-            const uint32_t vi = (uint32_t)lane + 64u * jv;
             if (vi < XROWS * 4) put4(xbuf + (vi >> 2) * RS + 4 * (vi & 3u), v);
         }
-        // park the trace words of the chunk, once for the four schedules
-        const uint32_t to = (tid >> 2) * RS + 4 * tpart;
-        if (KONE) {
-            put4(slot + to, st.a);
-            if (!full) { put4(slot + (K + 0) * TPLANE + to, st.v); put4(slot + (K + 1) * TPLANE + to, st.p); }
-            if (!W1) put4(slot + (K + 2) * TPLANE + to, st.w);
-        } else {
-            const size_t o = (size_t)trow * Wd + w0 + 4 * tpart;
-            const uint32_t *Ap = q.A + ((size_t)l * N + trow) * K * Wd + w0 + 4 * tpart;
-            for (uint32_t k = 0; k < K; k++) put4(slot + k * TPLANE + to, *(const c4u *)(Ap + (size_t)k * Wd));
-            if (!full) {
-                put4(slot + (K + 0) * TPLANE + to, *(const c4u *)(q.V + o));
-                put4(slot + (K + 1) * TPLANE + to, *(const c4u *)(q.Pm + o));
-            }
-            if (!W1) put4(slot + (K + 2) * TPLANE + to, *(const c4u *)(q.Wm + o));
-        }
-        issue(st, min(it + 2, iters - 1));
-        __syncthreads();
+        const uint32_t acc_n = st.acc;
+        issue_t(lt, ct); advance(lt, ct);                            // trace words of the next iteration
+        issue_x(st, lx, cx); advance(lx, cx);                        // rows of two iterations ahead
+        __syncthreads();                                             // this iteration's trace slot is complete
         const uint32_t *cur = xbuf + (lc + 1) * RS, *prv = xbuf + lc * RS;
         const uint32_t *ts = slot + lc * RS;
+        // two copies of the word loop, chosen once per chunk: with and without the alive / persist masks
+        auto words = [&](auto fc) __attribute__((always_inline)) {
+            constexpr bool FULLC = decltype(fc)::value;
 #pragma unroll
-        for (int i = 0; i < CW; i++) {
-            const uint32_t raw = cur[i], xp = prv[i];
-            uint32_t x, d;
-            if (full) {
-                x = raw;
-                d = raw ^ xp;
-            } else {
-                const uint32_t vv = ts[(K + 0) * TPLANE + i], pmw = ts[(K + 1) * TPLANE + i];
-                x = raw & vv;
-                fl_acc |= raw & ~vv;
-                d = (x ^ xp) & pmw;
+            for (int i = 0; i < CW; i++) {
+                const uint32_t raw = cur[i], xp = prv[i];
+                uint32_t x, d;
+                if (FULLC) {
+                    x = raw;
+                    d = raw ^ xp;
+                } else {
+                    const uint32_t vv = ts[KT * TPLANE + i], pmw = ts[(KT + 1) * TPLANE + i];
+                    x = raw & vv;
+                    fl_acc |= raw & ~vv;
+                    d = (x ^ xp) & pmw;
+                }
+                if (KT == 1) {
+                    hr += __popc(x & ts[i]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < KT; k++) hr += q.wt[k] * __popc(x & ts[k * TPLANE + i]);
+                }
+                if (!W1) hw += __popc(x & ts[(NT - 1) * TPLANE + i]);
+                oc += __popc(x);
+                mi += __popc(d & x);
+                mg += __popc(d);
             }
-            if (KONE) {
-                hr += __popc(x & ts[i]);
-            } else {
-                for (uint32_t k = 0; k < K; k++) hr += q.wt[k] * __popc(x & ts[k * TPLANE + i]);
-            }
-            if (!W1) hw += __popc(x & ts[(K + 2) * TPLANE + i]);
-            oc += __popc(x);
-            mi += __popc(d & x);
-            mg += __popc(d);
+        };
+        if (full) words(std::true_type{}); else words(std::false_type{});
+        if (W1) {
+            // the word that holds the written page passes through this chunk or another
+            const uint32_t ci = wsel - w0;
+            if (ci < CW && ci >= skip) hw = __popc(cur[ci] & wmw);   // written pages exist: no alive mask needed
         }
         if (c == NCH - 1) {
             // the row is complete: Eqs. 2-4
-            if (n == 0) { mi = 0; mg = 0; }                          // nothing migrates at the first step
-            if (W1) {
-                const uint32_t ws = q.wsel[n];
-                hw = __popc(X[(((size_t)sc * L + l) * N + n) * Wd + ws] & q.Wm[(size_t)n * Wd + ws]);
-            }
             const uint32_t mo = mg - mi;
             const size_t row = (size_t)l * N + n;
-            const double t = step_time(q, hr, hw, mi, mo, q.acc[row], wr_n);
+            const double t = step_time(q, hr, hw, mi, mo, acc_n, wr_n);
             if (has_s && active) {
                 tglobal[(size_t)s * L * N + row] = t;
                 if (counters) *(uint4 *)(counters + ((size_t)s * L * N + row) * 4) = make_uint4(hr, hw, mi, mo);
@@ -177,9 +190,13 @@ __global__ __launch_bounds__(CQ * 64) void score_chunk_kernel(
             occ_acc += oc;
             hr = hw = mi = mg = oc = 0;
         }
+        advance(l0, c0);
+        commit_t(it + 1);                                            // arrived while this iteration was scored
     };
-    issue(st0, 0);
-    issue(st1, min(1u, iters - 1));
+    issue_t(lt, ct); advance(lt, ct);
+    issue_x(st0, lx, cx); advance(lx, cx);
+    issue_x(st1, lx, cx); advance(lx, cx);
+    commit_t(0);
     for (uint32_t it = 0; it < iters; it += 2) {
         body(st0, it);
         if (it + 1 < iters) body(st1, it + 1);
@@ -220,22 +237,30 @@ int kvp_score_chunk_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t
                            uint32_t *counters, uint32_t *occ) {
     const DevProblem &q = ctx->dp;
     if (q.Wd < CW || !ctx->d_chunkfull) return 1;
-    const size_t lds = ((size_t)CQ * XSLICE + 2 * (size_t)(q.K + 3) * TPLANE) * 4;
+    const bool w1 = q.single_write != 0;
+    const size_t nt = q.K + 2 + (w1 ? 0 : 1);
+    const size_t lds = ((size_t)CQ * XSLICE + 2 * nt * TPLANE) * 4;
     if (lds > 160 * 1024) return 1;
     const uint64_t nwg = (uint64_t)((S + CQ - 1) / CQ) * tiles;
     if (nwg > 0x7FFFFFFFull) return 1;
     int rc = kvp_ensure(ctx, (void **)&ctx->d_tglobal, &ctx->tglobal_cap, (size_t)S * q.L * q.N * sizeof(double));
     if (rc) return rc;
-    const bool kone = q.K == 1 && q.wt[0] == 1, w1 = q.single_write != 0;
     dim3 grid((uint32_t)nwg), block(CQ * 64);
-#define KVP_GO(WW, KK)                                                                                       \
-    if (lds > 48 * 1024)                                                                                     \
-        KVP_HIP(hipFuncSetAttribute((const void *)score_chunk_kernel<WW, KK>,                                \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                 \
-    score_chunk_kernel<WW, KK><<<grid, block, lds, ctx->stream>>>(q, X, S, tiles, ctx->d_chunkfull, ctx->cf_words, \
-                                                                  ctx->d_tglobal, ctx->d_tileflag, counters, occ)
-    if (w1 && kone) { KVP_GO(true, true); } else if (w1) { KVP_GO(true, false); }
-    else if (kone) { KVP_GO(false, true); } else { KVP_GO(false, false); }
+#define KVP_GO(WW, KK)                                                                                        \
+    do {                                                                                                      \
+        if (lds > 48 * 1024)                                                                                  \
+            KVP_HIP(hipFuncSetAttribute((const void *)score_chunk_kernel<WW, KK>,                             \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));              \
+        score_chunk_kernel<WW, KK><<<grid, block, lds, ctx->stream>>>(q, X, S, tiles, ctx->d_chunkfull,        \
+                                                                      ctx->cf_words, ctx->d_tglobal,          \
+                                                                      ctx->d_tileflag, counters, occ);        \
+    } while (0)
+#define KVP_K(KK) case KK: if (w1) KVP_GO(true, KK); else KVP_GO(false, KK); break;
+    switch (q.K) {
+        KVP_K(1) KVP_K(2) KVP_K(3) KVP_K(4) KVP_K(5) KVP_K(6) KVP_K(7) KVP_K(8)
+        default: return 1;
+    }
+#undef KVP_K
 #undef KVP_GO
     KVP_HIP(hipGetLastError());
     const uint64_t nwv = (uint64_t)S * nb_total;
