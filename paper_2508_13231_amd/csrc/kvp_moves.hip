@@ -44,22 +44,43 @@ __device__ __forceinline__ uint64_t ballot64(bool p) { return (uint64_t)__ballot
 __device__ __forceinline__ int ctz64(uint64_t v) { return __ffsll((unsigned long long)v) - 1; }
 __device__ __forceinline__ int msb64(uint64_t v) { return 63 - __clzll((long long)v); }
 
-// Effect on a step's counters of one page whose bit goes x_old -> x_new here and
-// xp_old -> xp_new one step earlier.
-__device__ __forceinline__ void page_effect(const DevProblem &q, uint32_t l, uint32_t n, uint32_t w, uint32_t b,
-                                            bool x_old, bool x_new, bool xp_old, bool xp_new,
-                                            int &hr, int &hw, int &mi, int &mo) {
-    if (x_old != x_new) {
+// Everything a lane needs to know about one (layer, page) at its step, gathered with
+// independent loads that are all issued together: one memory round trip per move.
+struct PageBits {
+    bool v, pm, wm, x, xprev;   // exists, persists, written, in HBM now, in HBM one step earlier
+    int au;                     // read units the page accounts for at this step (sum of its planes' weights)
+};
+
+__device__ __forceinline__ PageBits gather_page(const DevProblem &q, const uint32_t *X, uint32_t l, uint32_t n,
+                                                bool ok, uint32_t w, uint32_t b) {
+    const size_t o = (size_t)n * q.Wd + w, op = (size_t)(n > 0 ? n - 1 : 0) * q.Wd + w;
+    const uint32_t *Xl = X + (size_t)l * q.N * q.Wd;
+    const uint32_t vw = q.V[o], pw = q.Pm[o], ww = q.Wm[o], xw = Xl[o], vpw = q.V[op], xpw = Xl[op];
+    const uint32_t *a = q.A + ((size_t)l * q.N + n) * q.K * q.Wd + w;
+    int au = 0;
+    for (uint32_t k = 0; k < q.K; k++) au += (int)(q.wt[k] * ((a[(size_t)k * q.Wd] >> b) & 1u));
+    PageBits r;
+    r.v = ok && ((vw >> b) & 1u);
+    r.pm = ok && ((pw >> b) & 1u);
+    r.wm = ok && ((ww >> b) & 1u);
+    r.x = r.v && ((xw >> b) & 1u);
+    r.xprev = ok && n > 0 && ((vpw >> b) & 1u) && ((xpw >> b) & 1u);
+    r.au = au;
+    return r;
+}
+
+// Effect on a step's counters of one page whose bit goes x -> x_new here and
+// xprev -> xp_new one step earlier.
+__device__ __forceinline__ void page_effect(const PageBits &g, bool x_new, bool xp_new, int &hr, int &hw, int &mi,
+                                            int &mo) {
+    if (g.x != x_new) {
         const int s = x_new ? 1 : -1;
-        const uint32_t *a = q.A + ((size_t)l * q.N + n) * q.K * q.Wd + w;
-        int u = 0;
-        for (uint32_t k = 0; k < q.K; k++) u += (int)(q.wt[k] * ((a[(size_t)k * q.Wd] >> b) & 1u));
-        hr += s * u;
-        hw += s * (int)((q.Wm[(size_t)n * q.Wd + w] >> b) & 1u);
+        hr += s * g.au;
+        hw += s * (int)g.wm;
     }
-    if ((q.Pm[(size_t)n * q.Wd + w] >> b) & 1u) {
-        mi += (int)(x_new && !xp_new) - (int)(x_old && !xp_old);
-        mo += (int)(!x_new && xp_new) - (int)(!x_old && xp_old);
+    if (g.pm) {
+        mi += (int)(x_new && !xp_new) - (int)(g.x && !g.xprev);
+        mo += (int)(!x_new && xp_new) - (int)(!g.x && g.xprev);
     }
 }
 
@@ -71,35 +92,43 @@ __device__ MoveEval eval_move(const DevProblem &q, const uint32_t *X, const uint
     R.verdict = KVP_MOVE_NULL; R.dT = 0.0; R.base = 0; R.flip1 = R.flip2 = 0; R.second = false;
     R.n = -1; R.f1 = R.f2 = R.touch1 = R.touch2 = R.xnew = false;
     R.c1 = make_uint4(0, 0, 0, 0); R.c2 = R.c1;
-    const uint32_t L = q.L, N = q.N, Wd = q.Wd, cap = q.cap;
+    const uint32_t L = q.L, N = q.N, cap = q.cap;
     if (m.op > 2 || m.layer >= L || m.page >= q.P || m.n1 >= N || m.len < 1 || m.len > KVP_MAX_LEN ||
         m.layer2 >= L || m.page2 >= q.P)
         return R;
     const uint32_t l = m.layer, n1 = m.n1, len = m.len, l2 = m.layer2;
     const uint32_t wp = m.page >> 5, bp = m.page & 31, wq = m.page2 >> 5, bq = m.page2 & 31;
-    const uint32_t *Xl = X + (size_t)l * N * Wd + wp;
-    const uint32_t *Xl2 = X + (size_t)l2 * N * Wd + wq;
+    const bool swap = m.op == KVP_OP_SWAP;
+    const bool same_layer = l2 == l;
 
+    // lane <-> step n1 + lane; steps past the trace shadow the last one and count as absent
     int n = (int)n1 + lane;
     bool inb = n < (int)N;
-    bool vb = inb && ((q.V[(size_t)n * Wd + wp] >> bp) & 1u);
-    bool pmb = inb && ((q.Pm[(size_t)n * Wd + wp] >> bp) & 1u);
-    bool xb = vb && ((Xl[(size_t)n * Wd] >> bp) & 1u);
-    uint32_t oc = inb ? occ[n] : 0;
-    if (!(ballot64(vb) & 1ull)) return R;                  // the page does not exist at n1
-    uint64_t xmask = ballot64(xb);
+    uint32_t nc = inb ? (uint32_t)n : N - 1;
+    PageBits P = gather_page(q, X, l, nc, inb, wp, bp);
+    PageBits Q = P;
+    uint32_t oc = occ[nc];
+    uint4 C1 = *(const uint4 *)(cnt + ((size_t)l * N + nc) * 4), C2 = C1;
+    uint32_t acc1 = q.acc[(size_t)l * N + nc], acc2 = acc1, wr = q.wr[nc];
+    if (swap) {
+        Q = gather_page(q, X, l2, nc, inb, wq, bq);
+        C2 = *(const uint4 *)(cnt + ((size_t)l2 * N + nc) * 4);
+        acc2 = q.acc[(size_t)l2 * N + nc];
+    }
+    if (!(ballot64(P.v) & 1ull)) return R;                 // the page does not exist at n1
+    const uint64_t xmask = ballot64(P.x);
     const bool x1 = xmask & 1ull;
-    bool f1 = false, f2 = false, clipped = false, xq = false;
+    bool f1 = false, f2 = false, clipped = false;
     int base = (int)n1;
 
     if (m.op != KVP_OP_SHIFT) {
-        const bool cont = lane == 0 || (inb && (uint32_t)lane < len && pmb);
+        const bool cont = lane == 0 || (inb && (uint32_t)lane < len && P.pm);
         const uint64_t bad = ballot64(!cont);
         const int e = bad ? ctz64(bad) : 64;
         const bool in_span = lane < e;
         if (m.op == KVP_OP_SET || x1) {
             const bool v = !x1;
-            const bool differ = in_span && (xb != v);
+            const bool differ = in_span && (P.x != v);
             if (v) {
                 const uint64_t stop = ballot64(differ && oc >= cap);
                 const int fs = stop ? ctz64(stop) : 64;
@@ -109,35 +138,35 @@ __device__ MoveEval eval_move(const DevProblem &q, const uint32_t *X, const uint
                 f1 = differ;
             }
         } else {
-            const bool victim_ok = !(l2 == l && m.page2 == m.page);
-            xq = inb && ((q.V[(size_t)n * Wd + wq] >> bq) & 1u) && ((Xl2[(size_t)n * Wd] >> bq) & 1u);
-            const bool cand = in_span && !xb;
+            const bool victim_ok = !(same_layer && m.page2 == m.page);
+            const bool cand = in_span && !P.x;
             const bool room = oc < cap;
-            const bool evict = cand && !room && victim_ok && xq;
+            const bool evict = cand && !room && victim_ok && Q.x;
             f1 = cand && (room || evict);
             f2 = evict;
             clipped = ballot64(cand && !room && !evict) != 0;
         }
     } else {
-        const bool cont = lane == 0 || (inb && (uint32_t)lane <= len && pmb);
+        const bool cont = lane == 0 || (inb && (uint32_t)lane <= len && P.pm);
         const uint64_t bad = ballot64(!cont);
         const int e = bad ? ctz64(bad) : 64;
         const bool xprev = lane > 0 && ((xmask >> (lane - 1)) & 1ull);
-        const uint64_t tm = ballot64(lane >= 1 && lane < e && xb != xprev);
+        const uint64_t tm = ballot64(lane >= 1 && lane < e && P.x != xprev);
         if (!tm) return R;                                  // constant timeline: nothing to shift
         const int it = ctz64(tm);
         const int nt = (int)n1 + it;
         const bool a = (xmask >> (it - 1)) & 1ull;
         const int d = (m.dsel & 2u) ? (int)(m.dsel & 1u) + 1 : (int)(m.dsel & 1u) - 2;   // -2,-1,+1,+2
         base = nt - 2;
-        // re-map the lanes onto the five steps around the edge
+        // re-map the lanes onto the five steps around the edge (a second round trip, SHIFT only)
         n = base + lane;
         inb = lane < 5 && n >= 0 && n < (int)N;
-        vb = inb && ((q.V[(size_t)n * Wd + wp] >> bp) & 1u);
-        pmb = inb && ((q.Pm[(size_t)n * Wd + wp] >> bp) & 1u);
-        xb = vb && ((Xl[(size_t)n * Wd] >> bp) & 1u);
-        oc = inb ? occ[n] : 0;
-        xmask = ballot64(xb);
+        nc = inb ? (uint32_t)n : 0u;
+        P = gather_page(q, X, l, nc, inb, wp, bp);
+        oc = occ[nc];
+        C1 = *(const uint4 *)(cnt + ((size_t)l * N + nc) * 4);
+        acc1 = q.acc[(size_t)l * N + nc];
+        wr = q.wr[nc];
         if (d < 0) {
             const bool target = lane == 1 || (lane == 0 && d == -2 && it >= 2);   // steps hold a, take not(a)
             if (!a) {
@@ -149,8 +178,8 @@ __device__ MoveEval eval_move(const DevProblem &q, const uint32_t *X, const uint
                 f1 = target;
             }
         } else {
-            const bool target = lane == 2 || (lane == 3 && d == 2 && inb && pmb);
-            const bool differ = target && (xb != a);
+            const bool target = lane == 2 || (lane == 3 && d == 2 && inb && P.pm);
+            const bool differ = target && (P.x != a);
             if (a) {
                 const uint64_t stop = ballot64(differ && oc >= cap);
                 const int fs = stop ? ctz64(stop) : 64;
@@ -164,37 +193,18 @@ __device__ MoveEval eval_move(const DevProblem &q, const uint32_t *X, const uint
     const uint64_t flip1 = ballot64(f1), flip2 = ballot64(f2);
     if (!flip1) return R;
 
-    // ---- cost change over the window [base, base + 64) -------------------------
-    const bool same_layer = l2 == l;
+    // ---- cost change over the window [base, base + 64): all from registers -----
     const bool fp1 = lane > 0 && ((flip1 >> (lane - 1)) & 1ull);
     const bool fp2 = lane > 0 && ((flip2 >> (lane - 1)) & 1ull);
-    bool xp = lane > 0 && ((xmask >> (lane - 1)) & 1ull);          // bit of the page one step earlier
-    if (lane == 0 && base >= 1 && inb) {
-        const size_t o = (size_t)(base - 1) * Wd;
-        xp = ((q.V[o + wp] >> bp) & 1u) && ((Xl[o] >> bp) & 1u);
-    }
-    bool xqp = false;
-    if (flip2) {
-        const uint64_t qmask = ballot64(xq);
-        xqp = lane > 0 && ((qmask >> (lane - 1)) & 1ull);
-        if (lane == 0 && base >= 1 && inb) {
-            const size_t o = (size_t)(base - 1) * Wd;
-            xqp = ((q.V[o + wq] >> bq) & 1u) && ((Xl2[o] >> bq) & 1u);
-        }
-    }
     double dd = 0.0;
     const bool touch1 = inb && (f1 || fp1 || (same_layer && (f2 || fp2)));
     if (touch1) {
-        const size_t row = (size_t)l * N + n;
-        const uint4 c = *(const uint4 *)(cnt + row * 4);
-        const uint32_t acc = q.acc[row], wr = q.wr[n];
-        const double t_old = step_time(q, c.x, c.y, c.z, c.w, acc, wr);
-        int hr = (int)c.x, hw = (int)c.y, mi = (int)c.z, mo = (int)c.w;
-        page_effect(q, l, (uint32_t)n, wp, bp, xb, xb != f1, xp, xp != fp1, hr, hw, mi, mo);
-        if (same_layer && (f2 || fp2))
-            page_effect(q, l, (uint32_t)n, wq, bq, xq, xq != f2, xqp, xqp != fp2, hr, hw, mi, mo);
+        const double t_old = step_time(q, C1.x, C1.y, C1.z, C1.w, acc1, wr);
+        int hr = (int)C1.x, hw = (int)C1.y, mi = (int)C1.z, mo = (int)C1.w;
+        page_effect(P, P.x != f1, P.xprev != fp1, hr, hw, mi, mo);
+        if (same_layer && (f2 || fp2)) page_effect(Q, Q.x != f2, Q.xprev != fp2, hr, hw, mi, mo);
         R.c1 = make_uint4((uint32_t)hr, (uint32_t)hw, (uint32_t)mi, (uint32_t)mo);
-        dd = step_time(q, R.c1.x, R.c1.y, R.c1.z, R.c1.w, acc, wr) - t_old;
+        dd = step_time(q, R.c1.x, R.c1.y, R.c1.z, R.c1.w, acc1, wr) - t_old;
     }
     double dT = wave_tree_sum_f64(dd);
     const bool second = flip2 != 0 && !same_layer;
@@ -203,20 +213,17 @@ __device__ MoveEval eval_move(const DevProblem &q, const uint32_t *X, const uint
         dd = 0.0;
         touch2 = inb && (f2 || fp2);
         if (touch2) {
-            const size_t row = (size_t)l2 * N + n;
-            const uint4 c = *(const uint4 *)(cnt + row * 4);
-            const uint32_t acc = q.acc[row], wr = q.wr[n];
-            const double t_old = step_time(q, c.x, c.y, c.z, c.w, acc, wr);
-            int hr = (int)c.x, hw = (int)c.y, mi = (int)c.z, mo = (int)c.w;
-            page_effect(q, l2, (uint32_t)n, wq, bq, xq, xq != f2, xqp, xqp != fp2, hr, hw, mi, mo);
+            const double t_old = step_time(q, C2.x, C2.y, C2.z, C2.w, acc2, wr);
+            int hr = (int)C2.x, hw = (int)C2.y, mi = (int)C2.z, mo = (int)C2.w;
+            page_effect(Q, Q.x != f2, Q.xprev != fp2, hr, hw, mi, mo);
             R.c2 = make_uint4((uint32_t)hr, (uint32_t)hw, (uint32_t)mi, (uint32_t)mo);
-            dd = step_time(q, R.c2.x, R.c2.y, R.c2.z, R.c2.w, acc, wr) - t_old;
+            dd = step_time(q, R.c2.x, R.c2.y, R.c2.z, R.c2.w, acc2, wr) - t_old;
         }
         dT = dT + wave_tree_sum_f64(dd);
     }
     R.verdict = clipped ? KVP_MOVE_CLIPPED : KVP_MOVE_OK;
     R.dT = dT; R.base = base; R.flip1 = flip1; R.flip2 = flip2; R.second = second;
-    R.n = inb ? n : -1; R.f1 = f1; R.f2 = f2; R.touch1 = touch1; R.touch2 = touch2; R.xnew = xb != f1;
+    R.n = inb ? n : -1; R.f1 = f1; R.f2 = f2; R.touch1 = touch1; R.touch2 = touch2; R.xnew = P.x != f1;
     return R;
 }
 
