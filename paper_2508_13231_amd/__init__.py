@@ -27,7 +27,7 @@ KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2
 
 EXPORTS = ["kvp_create", "kvp_destroy", "kvp_trace_upload", "kvp_score", "kvp_delta_score", "kvp_anneal",
            "kvp_best", "kvp_chain_placement", "kvp_chain_stats", "kvp_plane_unit", "kvp_strerror", "kvp_last_hip_error",
-           "kvp_set_score_kernel"]
+           "kvp_set_score_kernel", "kvp_score_kernel_used"]
 
 
 class kvp_problem(C.Structure):
@@ -99,6 +99,8 @@ def lib():
         L.kvp_strerror.argtypes = [i32]
         L.kvp_set_score_kernel.restype = i32
         L.kvp_set_score_kernel.argtypes = [vp, i32]
+        L.kvp_score_kernel_used.restype = i32
+        L.kvp_score_kernel_used.argtypes = [vp]
         L.kvp_last_hip_error.restype = i32
         L.kvp_last_hip_error.argtypes = [C.POINTER(i32)]
         _lib = L
@@ -195,11 +197,16 @@ def kvp_chain_stats(ctx, n_chains):
     return list(arr)
 
 
-KVP_SCORE_AUTO, KVP_SCORE_ROWS, KVP_SCORE_LANES = 0, 1, 2
+(KVP_SCORE_AUTO, KVP_SCORE_ROWS, KVP_SCORE_LANES, KVP_SCORE_LANES_8W, KVP_SCORE_DIRECT, KVP_SCORE_DIRECT_8W,
+ KVP_SCORE_QUAD, KVP_SCORE_QUAD_4S, KVP_SCORE_WIDE, KVP_SCORE_CHUNK, KVP_SCORE_ROWBLOCK) = range(11)
 
 
 def kvp_set_score_kernel(ctx, which: int):
     _check(lib().kvp_set_score_kernel(ctx, int(which)), "kvp_set_score_kernel")
+
+
+def kvp_score_kernel_used(ctx) -> int:
+    return int(lib().kvp_score_kernel_used(ctx))
 
 
 def kvp_plane_unit(ctx) -> int:

@@ -61,6 +61,7 @@ extern "C" void kvp_destroy(kvp_ctx *ctx) {
     kvp_free_chains(ctx);
     free_dev(ctx->d_trace); free_dev(ctx->d_blocksum); free_dev(ctx->d_tileflag);
     free_dev(ctx->d_cnt_tmp); free_dev(ctx->d_occ_tmp); free_dev(ctx->d_tglobal); free_dev(ctx->d_chunkfull);
+    free_dev(ctx->d_aw);
     delete ctx;
 }
 
@@ -80,16 +81,19 @@ extern "C" const char *kvp_strerror(int code) {
 }
 
 extern "C" int kvp_set_score_kernel(kvp_ctx *ctx, int which) {
-    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_CHUNK) return KVP_EINVAL;
+    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_ROWBLOCK) return KVP_EINVAL;
     ctx->force_wide = which == KVP_SCORE_WIDE;
     ctx->use_chunk = which == KVP_SCORE_AUTO || which == KVP_SCORE_CHUNK;
+    ctx->use_rowblock = which == KVP_SCORE_AUTO || which == KVP_SCORE_ROWBLOCK;
     ctx->tile_quad = which == KVP_SCORE_AUTO || which == KVP_SCORE_QUAD || which == KVP_SCORE_QUAD_4S;
     ctx->quad_stages = which == KVP_SCORE_QUAD_4S ? 4 : 2;
-    ctx->score_kernel = which == KVP_SCORE_CHUNK ? KVP_SCORE_CHUNK : which >= KVP_SCORE_LANES ? KVP_SCORE_LANES : which;
+    ctx->score_kernel = which == KVP_SCORE_CHUNK || which == KVP_SCORE_ROWBLOCK ? KVP_SCORE_CHUNK : which >= KVP_SCORE_LANES ? KVP_SCORE_LANES : which;
     ctx->tile_waves = (which == KVP_SCORE_LANES_8W || which == KVP_SCORE_DIRECT_8W) ? 8 : 4;
-    ctx->tile_direct = which >= KVP_SCORE_DIRECT || which == KVP_SCORE_AUTO;
+    ctx->tile_direct = (which >= KVP_SCORE_DIRECT && which <= KVP_SCORE_QUAD_4S) || which == KVP_SCORE_AUTO;
     return KVP_OK;
 }
+
+extern "C" int kvp_score_kernel_used(const kvp_ctx *ctx) { return ctx ? ctx->last_kernel : 0; }
 
 extern "C" uint64_t kvp_plane_unit(const kvp_ctx *ctx) { return ctx && ctx->has_trace ? ctx->unit : 0; }
 
@@ -147,6 +151,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     kvp_free_chains(ctx);
     free_dev(ctx->d_trace); ctx->d_trace = nullptr; ctx->has_trace = false;
     free_dev(ctx->d_chunkfull); ctx->d_chunkfull = nullptr; ctx->cf_words = 0;
+    free_dev(ctx->d_aw); ctx->d_aw = nullptr; ctx->aw = nullptr; ctx->kb = 0;
 
     const size_t nA = (size_t)(L * N * K * Wd), nM = (size_t)(N * Wd);
     auto up4 = [](size_t x) { return (x + 3) & ~(size_t)3; };          // keep every array 16-byte aligned
@@ -180,6 +185,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
         if (!cls || !fullw || !cfull) { free(cls); free(fullw); free(cfull); return KVP_ENOMEM; }
         uint32_t *m16 = cls + T64, *m64 = cls + 2 * T64, *m256 = cls + 3 * T64;
         ctx->prefix_full = Wd >= 2 && Wd <= 16;
+        ctx->pfw = (uint32_t)Wd;
         for (size_t t = 0; t < T64; t++) {
             const uint64_t n0 = t * 64, n1 = n0 + 64 < N ? n0 + 64 : N;
             for (uint64_t w = 0; w < Wd; w++) {
@@ -194,6 +200,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
                 if (Wd <= 16)
                     cls[t] |= (uint32_t)(full ? KVP_WORD_FULL : empty ? KVP_WORD_EMPTY : KVP_WORD_MIXED) << (2 * w);
                 if (w + 1 < Wd && !full) ctx->prefix_full = false;
+                if (!full && w < ctx->pfw) ctx->pfw = (uint32_t)w;
             }
             for (uint64_t c = 0; c < NCH; c++) {
                 bool all = true;
@@ -229,6 +236,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
         if (hsel[n] == 0xFFFFFFFFu) q.single_write = 0;
     free(hsel);
     KVP_HIP(e);
+    if ((rc = kvp_bitslice_build(ctx))) return rc;
     ctx->has_trace = true;
     return KVP_OK;
 }

@@ -44,9 +44,15 @@ struct kvp_ctx {
     DevProblem dp{};
     uint64_t unit = 0;
     int score_kernel = 0;                // KVP_SCORE_AUTO / _ROWS / _LANES
+    int last_kernel = 0;                 // scorer that the last kvp_score ran (KVP_SCORE_*), 0 before the first
     bool prefix_full = false;            // on every 64-step tile all mask words but the last are FULL
     int quad_stages = 2;                 // register stages of the four-schedule scorer (2 or 4)
     bool use_chunk = true;               // chunked four-schedule scorer for wide rows
+    bool use_rowblock = true;            // whole-row four-schedule scorer for rows of 16..68 words
+    uint32_t pfw = 0;                    // leading mask words that are FULL on every 64-step tile
+    const uint32_t *aw = nullptr;        // [L][N][kb][Wd] binary digits of the pages' read weights (may alias A)
+    uint32_t kb = 0;                     // digit planes, 0 if the weights need more than four
+    uint32_t *d_aw = nullptr;            // owned storage of aw when it is not A
     bool force_wide = false;             // use the wide-row scorer also for narrow rows
     int tile_quad = 1;                   // four schedules per workgroup (power-of-two layer counts)
     int tile_direct = 1;                 // narrow-row scorer without LDS staging (single plane only)
@@ -146,4 +152,5 @@ __device__ __forceinline__ double step_time(const DevProblem &q, uint32_t hr_u, 
 int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, double *d_cost,
                      uint32_t *d_excess, uint32_t *d_counters, uint32_t *d_occ);
 int kvp_ensure(kvp_ctx *ctx, void **p, size_t *cap, size_t bytes);
+int kvp_bitslice_build(kvp_ctx *ctx);
 void kvp_free_chains(kvp_ctx *ctx);

@@ -162,6 +162,8 @@ int kvp_score_wide_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t 
                           uint32_t *counters, uint32_t *occ);
 int kvp_score_quad_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
                           uint32_t *counters, uint32_t *occ);
+int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+                              uint32_t *counters, uint32_t *occ);
 
 int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, double *d_cost,
                      uint32_t *d_excess, uint32_t *d_counters, uint32_t *d_occ) {
@@ -175,7 +177,9 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
         if ((rc = kvp_ensure(ctx, (void **)&ctx->d_blocksum, &ctx->blocksum_cap, (size_t)S * nb_total * sizeof(double)))) return rc;
         if ((rc = kvp_ensure(ctx, (void **)&ctx->d_tileflag, &ctx->tileflag_cap, (size_t)S * tiles64 * sizeof(uint32_t)))) return rc;
         rc = 1;
-        if (ctx->use_chunk && !ctx->force_wide)
+        if (ctx->use_rowblock && !ctx->force_wide)
+            rc = kvp_score_rowblock_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
+        if (rc == 1 && ctx->use_chunk && !ctx->force_wide)
             rc = kvp_score_chunk_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
         if (rc == 1) rc = kvp_score_wide_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
         if (rc < 0) return rc;
@@ -226,6 +230,7 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
         score_rows_kernel<false><<<grid, block, lds, ctx->stream>>>(q, d_placements, Tn, tiles, nb_total,
                                                                    ctx->d_blocksum, ctx->d_tileflag, d_counters, d_occ);
     KVP_HIP(hipGetLastError());
+    ctx->last_kernel = KVP_SCORE_ROWS;
     score_finalize_kernel<<<dim3((S + 255) / 256), dim3(256), 0, ctx->stream>>>(S, nb_total, tiles, ctx->d_blocksum,
                                                                                ctx->d_tileflag, d_cost, d_excess);
     KVP_HIP(hipGetLastError());

@@ -55,8 +55,13 @@ __global__ __launch_bounds__(CQ * 64) void score_chunk_kernel(
     const uint32_t tid = threadIdx.x;
     const int lane = lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / KVP_WAVE));
-    const uint32_t tile = blockIdx.x % tiles;
-    const uint32_t s = (blockIdx.x / tiles) * CQ + wave;
+    // Workgroups are handed to the eight XCDs in turn.  The ones that land on an XCD take the
+    // schedule groups of one tile after the other, so that the trace of that tile is fetched from
+    // HBM once and then served by the XCD's L2 to all of them.
+    const uint32_t groups = (S + CQ - 1) / CQ;
+    const uint32_t tile = ((blockIdx.x >> 3) / groups) * 8 + (blockIdx.x & 7u);
+    if (tile >= tiles) return;
+    const uint32_t s = ((blockIdx.x >> 3) % groups) * CQ + wave;
     const bool has_s = s < S;
     const uint32_t sc = has_s ? s : S - 1;
     const uint32_t n0 = tile * TILE_N;
@@ -232,6 +237,16 @@ __global__ __launch_bounds__(256) void blocksum_from_t_kernel(uint32_t S, uint32
 
 }  // namespace
 
+// Block sums of Eq. 1 from the step latencies in ctx->d_tglobal ([S][L][N]).
+int kvp_blocksum_from_t_launch(kvp_ctx *ctx, uint32_t S, uint32_t nb_total) {
+    const DevProblem &q = ctx->dp;
+    const uint64_t nwv = (uint64_t)S * nb_total;
+    blocksum_from_t_kernel<<<dim3((uint32_t)((nwv + 3) / 4)), dim3(256), 0, ctx->stream>>>(S, q.L, q.N, nb_total,
+                                                                                         ctx->d_tglobal, ctx->d_blocksum);
+    KVP_HIP(hipGetLastError());
+    return KVP_OK;
+}
+
 // Returns KVP_OK if launched, 1 if this kernel does not cover the shape, <0 on error.
 int kvp_score_chunk_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
                            uint32_t *counters, uint32_t *occ) {
@@ -241,7 +256,7 @@ int kvp_score_chunk_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t
     const size_t nt = q.K + 2 + (w1 ? 0 : 1);
     const size_t lds = ((size_t)CQ * XSLICE + 2 * nt * TPLANE) * 4;
     if (lds > 160 * 1024) return 1;
-    const uint64_t nwg = (uint64_t)((S + CQ - 1) / CQ) * tiles;
+    const uint64_t nwg = (uint64_t)((S + CQ - 1) / CQ) * ((tiles + 7) / 8) * 8;   // whole rounds over the XCDs
     if (nwg > 0x7FFFFFFFull) return 1;
     int rc = kvp_ensure(ctx, (void **)&ctx->d_tglobal, &ctx->tglobal_cap, (size_t)S * q.L * q.N * sizeof(double));
     if (rc) return rc;
@@ -263,9 +278,6 @@ int kvp_score_chunk_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t
 #undef KVP_K
 #undef KVP_GO
     KVP_HIP(hipGetLastError());
-    const uint64_t nwv = (uint64_t)S * nb_total;
-    blocksum_from_t_kernel<<<dim3((uint32_t)((nwv + 3) / 4)), dim3(256), 0, ctx->stream>>>(S, q.L, q.N, nb_total,
-                                                                                         ctx->d_tglobal, ctx->d_blocksum);
-    KVP_HIP(hipGetLastError());
-    return KVP_OK;
+    ctx->last_kernel = KVP_SCORE_CHUNK;
+    return kvp_blocksum_from_t_launch(ctx, S, nb_total);
 }

@@ -220,6 +220,7 @@ int launch_quad(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uin
     }
 #undef KVP_GO
     KVP_HIP(hipGetLastError());
+    ctx->last_kernel = deep ? KVP_SCORE_QUAD_4S : KVP_SCORE_QUAD;
     return KVP_OK;
 }
 

@@ -1,0 +1,342 @@
+// Scorer for rows of 16 to 68 words whose pages almost all exist from the first
+// step on (a single decoding sequence: the prompt's pages are there at step 0,
+// the few pages born later sit in the last words) and where one page is written
+// per step.
+//
+//   * A workgroup is four wavefronts scoring the same 64 token steps of four
+//     schedules.  Per layer the tile is taken in two passes of 32 steps; in a pass
+//     a wavefront fetches its 33 rows (32 steps and the step before) WHOLE, as
+//     16-byte vectors that follow each other in memory, so every 128-byte line is
+//     requested once and by one instruction group.  The vectors are parked in LDS
+//     with an odd row stride and two lanes share a row, one taking the even words
+//     and one the odd: 64 lanes hit 64 different bank slots.
+//   * The access planes are replaced by the binary digits of each page's read
+//     weight (sum over planes of plane_bytes/unit): K planes of equal size become
+//     floor(log2 K) + 1 digit planes, and hr = sum_j 2^j popcount(x & digit_j).
+//     The digit planes of a pass are fetched once per workgroup into a
+//     double-buffered LDS slot, one pass ahead; the rows two passes ahead.
+//   * Words below the first word that is not FULL on some tile need no masks; the
+//     at most four words from there on use alive / persist words that do not depend
+//     on the layer and stay in registers for the whole kernel.
+//   * Step latencies are summed on the fly when L is a power of two (bit-reversed
+//     layer order, binary counter of partial sums: the 64-wide tree of the
+//     definition); otherwise they go to a [S][L][N] array that a second kernel sums.
+#include "kvp_internal.h"
+
+namespace {
+
+typedef uint32_t r4u __attribute__((ext_vector_type(4), aligned(4)));   // rows are only 4-byte aligned
+
+constexpr int RQ = 4;          // schedules (= wavefronts) per workgroup
+constexpr int RR = 32;         // token steps per pass (two lanes per step)
+constexpr int TWMAX = 4;       // words at the end of a row that may need masks
+
+__device__ __forceinline__ void put4(uint32_t *p, r4u v) { p[0] = v.x; p[1] = v.y; p[2] = v.z; p[3] = v.w; }
+__device__ __forceinline__ uint32_t pair_sum(uint32_t v) {            // v + the other lane of the row
+    return v + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
+}
+
+// binary digit planes of the read weights: Aw[l][n][j][w], j < KB
+__global__ __launch_bounds__(256) void bitslice_kernel(DevProblem q, uint32_t KB, uint32_t *__restrict__ Aw) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;           // (l*N + n)*Wd + w
+    const size_t total = (size_t)q.L * q.N * q.Wd;
+    if (i >= total) return;
+    const size_t row = i / q.Wd;
+    const uint32_t w = (uint32_t)(i - row * q.Wd);
+    uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (uint32_t k = 0; k < q.K; k++) {
+        const uint32_t a = q.A[(row * q.K + k) * q.Wd + w];
+        for (uint32_t b = 0; b < 8; b++) {
+            if (!((q.wt[k] >> b) & 1u)) continue;
+            uint32_t carry = a;                                        // add a * 2^b to the digit planes
+#pragma unroll
+            for (uint32_t j = 0; j < 8; j++) {
+                if (j < b) continue;
+                const uint32_t t = d[j] & carry;
+                d[j] ^= carry;
+                carry = t;
+            }
+        }
+    }
+    for (uint32_t j = 0; j < KB; j++) Aw[(row * KB + j) * q.Wd + w] = d[j];
+}
+
+// XV: 16-byte vectors per lane and pass (33 rows); KB: digit planes; POW2: L is a power of two >= 2.
+// No load is consumed in the pass that issues it, and all are unconditional: offsets that would
+// leave the schedule (or the planes) are clamped, and what they fetch is never used.
+//
+// Lane (r, h2), r = lane / 2, h2 = lane % 2: in pass p it counts the words w = h2 (mod 2) of step
+// 32 p + r; the two lanes of a row then add their counters.  After pass 1 lane (r, h2) keeps the
+// counters of step 32 h2 + r, "its own" step: Eqs. 2-4, the occupancy and the summation tree then
+// run once per layer with all 64 lanes busy.  The masked words at the end of a row are taken by the
+// lane that owns the row.
+template <int XV, int KB, bool POW2>
+__global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
+    DevProblem q, const uint32_t *__restrict__ Aw, const uint32_t *__restrict__ X, uint32_t S, uint32_t tiles,
+    uint32_t nb_total, uint32_t log2L, uint32_t pfw2, double *__restrict__ blocksum, double *__restrict__ tglobal,
+    uint32_t *__restrict__ tileflag, uint32_t *__restrict__ counters, uint32_t *__restrict__ occ_out) {
+    extern __shared__ double smem_d[];
+    constexpr int TV = (KB * XV * 8 + 32) / 33;                        // trace vectors per thread and pass
+    const uint32_t L = q.L, N = q.N, Wd = q.Wd;
+    const uint32_t RS = Wd | 1u, PPR = (Wd + 3) / 4;                   // LDS row stride (odd), vectors per row
+    const uint32_t TPL = RR * RS;                                      // words of one digit plane in a slot
+    const uint32_t tid = threadIdx.x;
+    const int lane = lane_id();
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / KVP_WAVE));
+    // Workgroups are handed to the eight XCDs in turn; those of one XCD take the schedule groups of
+    // one tile after the other, so the tile's digit planes are served by that XCD's L2.
+    const uint32_t groups = (S + RQ - 1) / RQ;
+    const uint32_t tile = ((blockIdx.x >> 3) / groups) * 8 + (blockIdx.x & 7u);
+    if (tile >= tiles) return;
+    const uint32_t s = ((blockIdx.x >> 3) % groups) * RQ + wave;
+    const bool has_s = s < S;
+    const uint32_t sc = has_s ? s : S - 1;                            // spare wavefronts shadow the last schedule
+    const uint32_t n0 = tile * 64;
+    const uint32_t rows = min(64u, N - n0);
+    uint32_t *xbuf = (uint32_t *)smem_d + (size_t)wave * (RR + 1) * RS;
+    uint32_t *tbuf = (uint32_t *)smem_d + (size_t)RQ * (RR + 1) * RS;  // two slots of KB * TPL words
+    const uint32_t r = (uint32_t)lane >> 1, h2 = (uint32_t)lane & 1u;
+    const uint32_t tw = Wd - pfw2;                                     // masked words at the end of a row (<= TWMAX)
+
+    // the lane's own step
+    const uint32_t rho = h2 * RR + r;
+    const bool active = rho < rows;
+    const uint32_t n = n0 + (active ? rho : rows - 1);                // idle lanes shadow the last row
+    const uint32_t wr_n = q.wr[n], wsel = q.wsel[n];
+    const uint32_t wmw = q.Wm[(size_t)n * Wd + wsel];
+    uint32_t vt[TWMAX], pt[TWMAX];
+#pragma unroll
+    for (int t = 0; t < TWMAX; t++) {
+        const uint32_t w = min(pfw2 + t, Wd - 1);
+        vt[t] = q.V[(size_t)n * Wd + w];
+        pt[t] = q.Pm[(size_t)n * Wd + w];
+    }
+    // vector slots of the lane: word offsets from the first row of a pass, in memory and in LDS
+    uint32_t xrel[XV], xlds[XV], trel[TV], tlds[TV];
+#pragma unroll
+    for (int jv = 0; jv < XV; jv++) {
+        const uint32_t vi = min((uint32_t)lane + 64u * jv, (RR + 1) * PPR - 1);
+        const uint32_t row = vi / PPR, part = vi - row * PPR;
+        const uint32_t w0 = min(4 * part, Wd - 4);                     // a row's last vector ends at the row's end
+        xrel[jv] = row * Wd + w0;
+        xlds[jv] = row * RS + w0;
+    }
+#pragma unroll
+    for (int jt = 0; jt < TV; jt++) {
+        const uint32_t ti = min(tid + 256u * jt, KB * RR * PPR - 1);
+        const uint32_t k = ti / (RR * PPR), rem = ti - k * RR * PPR;
+        const uint32_t row = rem / PPR, part = rem - row * PPR;
+        const uint32_t w0 = min(4 * part, Wd - 4);
+        trel[jt] = (row * KB + k) * Wd + w0;
+        tlds[jt] = k * TPL + row * RS + w0;
+    }
+    // Pass p of layer l starts at word ((l*N + n0 + 32p) - 1) * Wd of the schedule: the step before
+    // comes first.  Step 0 has none: there the offsets are clamped from below and the lanes of step 0
+    // use the step itself as its predecessor (nothing migrates at step 0).
+    const uint32_t sched_words = L * N * Wd;                           // < 2^31 (checked by the host)
+    const uint32_t prow0 = (n0 == 0 && r == 0) ? 1u : r;               // LDS row of the predecessor in pass 0
+
+    struct Stage { r4u x[XV]; };
+    Stage st0, st1;
+    uint32_t acc_nx = 0;                                               // read units of the lane's step, next layer
+    r4u tr[TV];
+    auto layer_of = [&](uint32_t i) { return POW2 ? (__brev(i) >> (32 - log2L)) : i; };
+    auto issue_x = [&](Stage &st, uint32_t p, uint32_t l) __attribute__((always_inline)) {
+        const uint32_t *Xs = X + (size_t)sc * sched_words;
+        const int before = (int)((l * N + n0 + RR * p) * Wd) - (int)Wd;   // word of the step before the pass; -Wd at step 0
+        const int hi = (int)sched_words - 4;
+#pragma unroll
+        for (int jv = 0; jv < XV; jv++) st.x[jv] = *(const r4u *)(Xs + min(max(before + (int)xrel[jv], 0), hi));
+    };
+    auto issue_t = [&](uint32_t p, uint32_t l) __attribute__((always_inline)) {
+        const uint32_t first = (l * N + n0 + RR * p) * KB * Wd, hi = L * N * KB * Wd - 4;
+#pragma unroll
+        for (int jt = 0; jt < TV; jt++) tr[jt] = *(const r4u *)(Aw + min(first + trel[jt], hi));
+    };
+    auto commit_t = [&](uint32_t slot) __attribute__((always_inline)) {
+        uint32_t *dst = tbuf + slot * KB * TPL;
+#pragma unroll
+        for (int jt = 0; jt < TV; jt++) put4(dst + tlds[jt], tr[jt]);
+    };
+
+    uint32_t fl_acc = 0, occ_acc = 0;
+    double stk[6] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0}, total = 0.0;
+    const uint32_t nfull = pfw2 >> 1;                                  // unmasked words per lane
+    uint32_t hr, hw, oc, mi, mg;                                       // the lane's own step, this layer
+    // one pass: stage st holds the rows of (layer i-th in visiting order, pass p)
+    auto pass = [&](Stage &st, const uint32_t p, uint32_t i) __attribute__((always_inline)) {
+        const uint32_t lnext = layer_of(min(i + 1, L - 1));
+#pragma unroll
+        for (int jv = 0; jv < XV; jv++) put4(xbuf + xlds[jv], st.x[jv]);
+        issue_t(p ^ 1u, p ? lnext : layer_of(i));                      // digit planes of the next pass
+        issue_x(st, p, lnext);                                         // rows of two passes ahead
+        __syncthreads();                                               // this pass's trace slot is complete
+        const uint32_t *cur = xbuf + (r + 1) * RS, *prv = xbuf + (p ? r : prow0) * RS;
+        const uint32_t *ts = tbuf + p * KB * TPL + r * RS;
+        const bool own = h2 == p;
+        uint32_t hrk[KB], c_oc = 0, c_mi = 0, c_mg = 0;
+#pragma unroll
+        for (int k = 0; k < KB; k++) hrk[k] = 0;
+#pragma unroll 8
+        for (uint32_t j = 0; j < nfull; j++) {
+            const uint32_t w = 2 * j + h2;
+            const uint32_t raw = cur[w], d = raw ^ prv[w];
+#pragma unroll
+            for (int k = 0; k < KB; k++) hrk[k] += __popc(raw & ts[k * TPL + w]);
+            c_oc += __popc(raw);
+            c_mi += __popc(d & raw);
+            c_mg += __popc(d);
+        }
+        uint32_t flt = 0;
+#pragma unroll
+        for (int t = 0; t < TWMAX; t++) {
+            if ((uint32_t)t < tw) {
+                const uint32_t w = pfw2 + t;
+                const uint32_t vv = own ? vt[t] : 0u, pp = own ? pt[t] : 0u;
+                const uint32_t raw = cur[w], x = raw & vv;
+                flt |= raw & ~vv;
+                const uint32_t d = (x ^ prv[w]) & pp;
+#pragma unroll
+                for (int k = 0; k < KB; k++) hrk[k] += __popc(x & ts[k * TPL + w]);
+                c_oc += __popc(x);
+                c_mi += __popc(d & x);
+                c_mg += __popc(d);
+            }
+        }
+        fl_acc |= (own && active) ? flt : 0u;
+        uint32_t c_hr = 0;
+#pragma unroll
+        for (int k = 0; k < KB; k++) c_hr += hrk[k] << k;
+        c_hr = pair_sum(c_hr); c_oc = pair_sum(c_oc); c_mi = pair_sum(c_mi); c_mg = pair_sum(c_mg);
+        const uint32_t c_hw = __popc(cur[wsel] & wmw);                 // written pages exist: no alive mask needed
+        if (p == 0) { hr = c_hr; oc = c_oc; mi = c_mi; mg = c_mg; hw = c_hw; }
+        else if (h2) { hr = c_hr; oc = c_oc; mi = c_mi; mg = c_mg; hw = c_hw; }
+        commit_t(p ^ 1u);                                              // arrived while this pass was scored
+    };
+    // once per layer, after both passes: Eqs. 2-4 and the layer's place in the summation tree
+    auto layer_end = [&](uint32_t i, uint32_t acc_n) __attribute__((always_inline)) {
+        const uint32_t l = layer_of(i);
+        const uint32_t mo = mg - mi;
+        double t = step_time(q, hr, hw, mi, mo, acc_n, wr_n);
+        t = active ? t : 0.0;                                          // rows past the end of the trace pad with +0.0
+        occ_acc += oc;
+        if (counters && has_s && active)
+            *(uint4 *)(counters + (((size_t)s * L + l) * N + n) * 4) = make_uint4(hr, hw, mi, mo);
+        if (POW2) {
+            // folds of the summation tree that join the steps of one block (steps are two lanes apart)
+            for (uint32_t m = (64u >> log2L) >> 1; m >= 1; m >>= 1) t = t + __shfl_xor(t, (int)(2 * m), KVP_WAVE);
+            // folds that join layers: binary counter over the bit-reversed visiting order
+            double carry = t;
+            bool parked = false;
+#pragma unroll
+            for (int j = 0; j < 6; j++) {
+                if (!parked && (uint32_t)j < log2L) {
+                    if (((i >> j) & 1u) == 0) { stk[j] = carry; parked = true; }
+                    else carry = stk[j] + carry;
+                }
+            }
+            if (!parked) total = carry;                                // only at the last layer
+        } else if (has_s && active) {
+            tglobal[((size_t)s * L + l) * N + n] = t;
+        }
+    };
+    issue_t(0, layer_of(0));
+    issue_x(st0, 0, layer_of(0));
+    issue_x(st1, 1, layer_of(0));
+    acc_nx = q.acc[(size_t)layer_of(0) * N + n];
+    commit_t(0);
+    for (uint32_t i = 0; i < L; i++) {
+        const uint32_t acc_n = acc_nx;
+        acc_nx = q.acc[(size_t)layer_of(min(i + 1, L - 1)) * N + n];
+        pass(st0, 0, i);
+        pass(st1, 1, i);
+        layer_end(i, acc_n);
+    }
+    if (!has_s) return;
+    if (POW2) {
+        const uint32_t bpl = 64u >> log2L;                             // block b of the tile: steps [b*bpl, (b+1)*bpl)
+        if ((r & (bpl - 1)) == 0 && rho < rows) blocksum[(size_t)s * nb_total + (size_t)tile * L + rho / bpl] = total;
+    }
+    uint32_t ex = 0;
+    if (active) {
+        if (occ_out) occ_out[(size_t)s * N + n] = occ_acc;            // Eq. 5 per token step
+        ex = occ_acc > q.cap ? occ_acc - q.cap : 0;
+    }
+    ex = wave_max_u32(ex);
+    const uint32_t fl = wave_or_u32(fl_acc);
+    if (lane == 0) tileflag[(size_t)s * tiles + tile] = ex | (fl ? 0x80000000u : 0u);
+}
+
+}  // namespace
+
+int kvp_blocksum_from_t_launch(kvp_ctx *ctx, uint32_t S, uint32_t nb_total);
+
+// Digit planes of the read weights, built once per trace.  Leaves ctx->d_aw null (and the scorer
+// above unavailable) when the weights need more than four digits.
+int kvp_bitslice_build(kvp_ctx *ctx) {
+    DevProblem &q = ctx->dp;
+    ctx->aw = nullptr; ctx->kb = 0;
+    uint64_t sum = 0;
+    for (uint32_t k = 0; k < q.K; k++) sum += q.wt[k];
+    uint32_t kb = 0;
+    while ((sum >> kb) != 0) kb++;
+    if (kb > 4) return KVP_OK;
+    if (q.K == 1 && q.wt[0] == 1) { ctx->aw = q.A; ctx->kb = 1; return KVP_OK; }
+    const size_t words = (size_t)q.L * q.N * kb * q.Wd;
+    KVP_HIP(hipMalloc((void **)&ctx->d_aw, words * 4));
+    const size_t cells = (size_t)q.L * q.N * q.Wd;
+    bitslice_kernel<<<dim3((uint32_t)((cells + 255) / 256)), dim3(256), 0, ctx->stream>>>(q, kb, ctx->d_aw);
+    KVP_HIP(hipGetLastError());
+    KVP_HIP(hipStreamSynchronize(ctx->stream));
+    ctx->aw = ctx->d_aw; ctx->kb = kb;
+    return KVP_OK;
+}
+
+// Returns KVP_OK if launched, 1 if this kernel does not cover the shape, <0 on error.
+int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+                              uint32_t *counters, uint32_t *occ) {
+    const DevProblem &q = ctx->dp;
+    if (!ctx->aw || !q.single_write || q.Wd < 16 || q.Wd > 68) return 1;
+    const uint32_t pfw2 = ctx->pfw & ~1u;
+    if (q.Wd - pfw2 > TWMAX) return 1;
+    const uint32_t PPR = (q.Wd + 3) / 4, RS = q.Wd | 1u, KB = ctx->kb;
+    const uint32_t need = ((RR + 1) * PPR + 63) / 64;
+    const int xv = need <= 5 ? 5 : 9;
+    if (need > 9) return 1;
+    if ((size_t)q.L * q.N * KB * q.Wd >= (1ull << 31)) return 1;      // 32-bit word offsets inside the digit planes
+    if ((size_t)q.L * q.N * q.Wd >= (1ull << 31)) return 1;           // and inside a schedule
+    uint32_t log2L = 0;
+    while ((1u << log2L) < q.L) log2L++;
+    const bool pow2 = q.L >= 2 && q.L <= 64 && (1u << log2L) == q.L;
+    const size_t lds = ((size_t)RQ * (RR + 1) * RS + 2 * (size_t)KB * RR * RS) * 4;
+    if (lds > 160 * 1024) return 1;
+    const uint64_t nwg = (uint64_t)((S + RQ - 1) / RQ) * ((tiles + 7) / 8) * 8;   // whole rounds over the XCDs
+    if (nwg > 0x7FFFFFFFull) return 1;
+    if (!pow2) {
+        int rc = kvp_ensure(ctx, (void **)&ctx->d_tglobal, &ctx->tglobal_cap, (size_t)S * q.L * q.N * sizeof(double));
+        if (rc) return rc;
+    }
+    dim3 grid((uint32_t)nwg), block(RQ * 64);
+#define KVP_GO(XX, KK, PP)                                                                                          \
+    do {                                                                                                            \
+        if (lds > 48 * 1024)                                                                                        \
+            KVP_HIP(hipFuncSetAttribute((const void *)score_rowblock_kernel<XX, KK, PP>,                            \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                    \
+        score_rowblock_kernel<XX, KK, PP><<<grid, block, lds, ctx->stream>>>(                                       \
+            q, ctx->aw, X, S, tiles, nb_total, log2L, pfw2, ctx->d_blocksum, ctx->d_tglobal, ctx->d_tileflag,      \
+            counters, occ);                                                                                         \
+    } while (0)
+#define KVP_P(XX, KK) do { if (pow2) KVP_GO(XX, KK, true); else KVP_GO(XX, KK, false); } while (0)
+#define KVP_K(KK) case KK: if (xv == 5) KVP_P(5, KK); else KVP_P(9, KK); break;
+    switch (KB) {
+        KVP_K(1) KVP_K(2) KVP_K(3) KVP_K(4)
+        default: return 1;
+    }
+#undef KVP_K
+#undef KVP_P
+#undef KVP_GO
+    KVP_HIP(hipGetLastError());
+    ctx->last_kernel = KVP_SCORE_ROWBLOCK;
+    if (!pow2) return kvp_blocksum_from_t_launch(ctx, S, nb_total);
+    return KVP_OK;
+}

@@ -362,6 +362,7 @@ int launch_direct(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, u
         score_lane_direct_kernel<WD, NW, false><<<grid, block, lds, ctx->stream>>>(
             q, X, tiles, nb_total, ctx->d_blocksum, ctx->d_tileflag, counters, occ);
     KVP_HIP(hipGetLastError());
+    ctx->last_kernel = NW == 8 ? KVP_SCORE_DIRECT_8W : KVP_SCORE_DIRECT;
     return KVP_OK;
 }
 
@@ -376,7 +377,9 @@ int launch_wd(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint3
     // more wavefronts per workgroup only when there are layers enough to keep each busy for long
     int rc = ctx->tile_waves == 8 ? launch_wd_nw<WD, 8>(ctx, X, S, tiles, nb_total, counters, occ)
                                   : launch_wd_nw<WD, 4>(ctx, X, S, tiles, nb_total, counters, occ);
-    if (rc == 1 && ctx->tile_waves == 8) rc = launch_wd_nw<WD, 4>(ctx, X, S, tiles, nb_total, counters, occ);
+    bool eight = ctx->tile_waves == 8;
+    if (rc == 1 && eight) { rc = launch_wd_nw<WD, 4>(ctx, X, S, tiles, nb_total, counters, occ); eight = false; }
+    if (rc == KVP_OK) ctx->last_kernel = eight ? KVP_SCORE_LANES_8W : KVP_SCORE_LANES;
     return rc;
 }
 

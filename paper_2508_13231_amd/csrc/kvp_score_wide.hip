@@ -228,6 +228,7 @@ int launch_wide(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uin
         score_wide_kernel<R, VEC, NI, false><<<grid, block, lds, ctx->stream>>>(
             q, X, fullmask, tiles, nb_total, ctx->d_blocksum, ctx->d_tileflag, counters, occ);
     KVP_HIP(hipGetLastError());
+    ctx->last_kernel = KVP_SCORE_WIDE;
     return KVP_OK;
 }
 

@@ -59,6 +59,9 @@ class Gpu:
         out += [d_cnt.cpu().numpy().view(np.uint32), d_occ.cpu().numpy().view(np.uint32)] if counters else [None, None]
         return out
 
+    def kernel_used(self):
+        return K.kvp_score_kernel_used(self.ctx)
+
     def delta(self, X, moves, give_counters):
         torch = self.torch
         tr = self.tr

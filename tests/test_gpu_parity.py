@@ -46,13 +46,40 @@ def _cases():
     yield "longctx/2", W.config("longctx", 0.5)                            # 33 words
     yield "gqa70b/4", W.config("gqa70b", 0.25)                             # 9 words ... 8 planes, 20 layers
     yield "rand-w16", W.random_trace(23, L=4, N=65, P=512, K=2)            # exactly one chunk of 16 words
+    # single decoding sequences (one page written per step, new pages only in the last words of a row)
+    yield "dec-w21-L3", _decode(31, L=3, N=100, words=20, page_tokens=4)   # odd stride, layers not a power of two
+    yield "dec-w38-k3", _decode(32, L=4, N=70, words=37, page_tokens=2, K=3,
+                                plane_bytes=[4096, 8192, 12288])           # weights 1, 2, 3: three digit planes
+    yield "dec-w68-k2", _decode(33, L=2, N=40, words=67, page_tokens=2, K=2)   # widest rows, second pass empty
+    yield "dec-w16", _decode(34, L=8, N=129, words=15, page_tokens=8)      # 16 words, three tiles, the last of one step
+    yield "dec-w24-tail", _decode(35, L=2, N=200, words=18, page_tokens=1)     # 200 new pages: too many masked words
+    yield "gqa70b/2", W.config("gqa70b", 0.5)                              # 17 words, 8 planes -> 4 digits, 40 layers
+
+
+def _decode(seed, L, N, words, page_tokens, K=1, plane_bytes=None):
+    """Decode of one sequence whose prompt fills `words` mask words exactly."""
+    from workloads.traces import Recipe, generate
+    prompt = words * 32 * page_tokens
+    tr = generate(Recipe("dec", L=L, N=N, page_tokens=page_tokens, prompt_lo=prompt, prompt_hi=prompt, K=K,
+                         top_frac=0.2, sink_tokens=4, recent_tokens=8, cap_frac=0.3, seed=seed))
+    if plane_bytes is not None:
+        tr.plane_bytes = list(plane_bytes)
+    return tr
 
 
 CASES = list(_cases())
+# scorers that must run natively (not be replaced by another) on a case
+NATIVE = {
+    "rowblock": {"longctx/2", "gqa70b/2", "dec-w21-L3", "dec-w38-k3", "dec-w68-k2", "dec-w16"},
+    "chunk": {"rand-wide", "rand-w40", "rand-w300", "rand-w301", "longctx/4", "longctx/2", "rand-w16", "dec-w24-tail"},
+    "quad": {"llama8b/4", "rand-L16", "rand-L64", "rand-L2"},
+}
 
 
-@pytest.mark.parametrize("kernel", [1, 2, 3, 4, 5, 6, 7, 8, 9],
-                         ids=["rows", "lanes", "lanes8w", "direct", "direct8w", "quad", "quad4s", "wide", "chunk"])
+KERNEL_IDS = ["rows", "lanes", "lanes8w", "direct", "direct8w", "quad", "quad4s", "wide", "chunk", "rowblock"]
+
+
+@pytest.mark.parametrize("kernel", list(range(1, 11)), ids=KERNEL_IDS)
 @pytest.mark.parametrize("name,tr", CASES, ids=[c[0] for c in CASES])
 def test_score_matches_oracle_bit_for_bit(G, name, tr, kernel):
     from gpu_util import expected_counters
@@ -62,6 +89,9 @@ def test_score_matches_oracle_bit_for_bit(G, name, tr, kernel):
     q = O.Problem(tr)
     with G(tr, score_kernel=kernel) as g:
         cost, ex, cnt, occ = g.score(X)
+        used = g.kernel_used()
+        if name in NATIVE.get(KERNEL_IDS[kernel - 1], ()):
+            assert used == kernel, (name, KERNEL_IDS[kernel - 1], "replaced by", KERNEL_IDS[used - 1])
         cost2, ex2, _, _ = g.score(X, counters=False)
         for s in range(X.shape[0]):
             r = O.score(q, X[s])
