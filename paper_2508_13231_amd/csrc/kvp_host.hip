@@ -61,7 +61,7 @@ extern "C" void kvp_destroy(kvp_ctx *ctx) {
     kvp_free_chains(ctx);
     free_dev(ctx->d_trace); free_dev(ctx->d_blocksum); free_dev(ctx->d_tileflag);
     free_dev(ctx->d_cnt_tmp); free_dev(ctx->d_occ_tmp); free_dev(ctx->d_tglobal); free_dev(ctx->d_chunkfull);
-    free_dev(ctx->d_aw);
+    free_dev(ctx->d_aw); free_dev(ctx->d_empty32);
     delete ctx;
 }
 
@@ -81,13 +81,14 @@ extern "C" const char *kvp_strerror(int code) {
 }
 
 extern "C" int kvp_set_score_kernel(kvp_ctx *ctx, int which) {
-    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_ROWBLOCK) return KVP_EINVAL;
+    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_LINE) return KVP_EINVAL;
     ctx->force_wide = which == KVP_SCORE_WIDE;
     ctx->use_chunk = which == KVP_SCORE_AUTO || which == KVP_SCORE_CHUNK;
     ctx->use_rowblock = which == KVP_SCORE_AUTO || which == KVP_SCORE_ROWBLOCK;
+    ctx->use_line = which == KVP_SCORE_AUTO || which == KVP_SCORE_LINE;
     ctx->tile_quad = which == KVP_SCORE_AUTO || which == KVP_SCORE_QUAD || which == KVP_SCORE_QUAD_4S;
     ctx->quad_stages = which == KVP_SCORE_QUAD_4S ? 4 : 2;
-    ctx->score_kernel = which == KVP_SCORE_CHUNK || which == KVP_SCORE_ROWBLOCK ? KVP_SCORE_CHUNK : which >= KVP_SCORE_LANES ? KVP_SCORE_LANES : which;
+    ctx->score_kernel = which == KVP_SCORE_CHUNK || which == KVP_SCORE_ROWBLOCK || which == KVP_SCORE_LINE ? KVP_SCORE_CHUNK : which >= KVP_SCORE_LANES ? KVP_SCORE_LANES : which;
     ctx->tile_waves = (which == KVP_SCORE_LANES_8W || which == KVP_SCORE_DIRECT_8W) ? 8 : 4;
     ctx->tile_direct = (which >= KVP_SCORE_DIRECT && which <= KVP_SCORE_QUAD_4S) || which == KVP_SCORE_AUTO;
     return KVP_OK;
@@ -152,6 +153,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     free_dev(ctx->d_trace); ctx->d_trace = nullptr; ctx->has_trace = false;
     free_dev(ctx->d_chunkfull); ctx->d_chunkfull = nullptr; ctx->cf_words = 0;
     free_dev(ctx->d_aw); ctx->d_aw = nullptr; ctx->aw = nullptr; ctx->kb = 0;
+    free_dev(ctx->d_empty32); ctx->d_empty32 = nullptr;
 
     const size_t nA = (size_t)(L * N * K * Wd), nM = (size_t)(N * Wd);
     auto up4 = [](size_t x) { return (x + 3) & ~(size_t)3; };          // keep every array 16-byte aligned
@@ -182,7 +184,9 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
         uint8_t *fullw = (uint8_t *)malloc((size_t)Wd);
         const uint64_t NCH = (Wd + 15) / 16, CFW = (NCH + 31) / 32;
         uint32_t *cfull = (uint32_t *)calloc((size_t)(T64 * CFW ? T64 * CFW : 1), 4);
-        if (!cls || !fullw || !cfull) { free(cls); free(fullw); free(cfull); return KVP_ENOMEM; }
+        const uint64_t NC32 = (Wd + 31) / 32;
+        uint8_t *emp = (uint8_t *)calloc((size_t)(T64 * NC32 ? T64 * NC32 : 1), 1);
+        if (!cls || !fullw || !cfull || !emp) { free(cls); free(fullw); free(cfull); free(emp); return KVP_ENOMEM; }
         uint32_t *m16 = cls + T64, *m64 = cls + 2 * T64, *m256 = cls + 3 * T64;
         ctx->prefix_full = Wd >= 2 && Wd <= 16;
         ctx->pfw = (uint32_t)Wd;
@@ -197,6 +201,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
                     if (n >= n0 && n >= 1 && h_persist[n * Wd + w] != 0xFFFFFFFFu) full = false;
                 }
                 fullw[w] = full;
+                if (!empty) emp[t * NC32 + w / 32] = 1;              // for now: 1 = some page exists
                 if (Wd <= 16)
                     cls[t] |= (uint32_t)(full ? KVP_WORD_FULL : empty ? KVP_WORD_EMPTY : KVP_WORD_MIXED) << (2 * w);
                 if (w + 1 < Wd && !full) ctx->prefix_full = false;
@@ -216,13 +221,17 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
                     if (all) M[k][t] |= 1u << i;
                 }
         }
+        for (size_t i = 0; i < T64 * NC32; i++) emp[i] = !emp[i];
         hipError_t ec = hipMemcpyAsync(d + oCls, cls, 4 * T64 * 4, hipMemcpyHostToDevice, ctx->stream);
+        if (ec == hipSuccess) ec = hipMalloc((void **)&ctx->d_empty32, (size_t)(T64 * NC32 ? T64 * NC32 : 1));
+        if (ec == hipSuccess)
+            ec = hipMemcpyAsync(ctx->d_empty32, emp, (size_t)(T64 * NC32), hipMemcpyHostToDevice, ctx->stream);
         if (ec == hipSuccess) ec = hipMalloc((void **)&ctx->d_chunkfull, (size_t)T64 * CFW * 4);
         if (ec == hipSuccess)
             ec = hipMemcpyAsync(ctx->d_chunkfull, cfull, (size_t)T64 * CFW * 4, hipMemcpyHostToDevice, ctx->stream);
         if (ec == hipSuccess) ec = hipStreamSynchronize(ctx->stream);
         ctx->cf_words = (uint32_t)CFW;
-        free(cls); free(fullw); free(cfull);
+        free(cls); free(fullw); free(cfull); free(emp);
         KVP_HIP(ec);
     }
     int rc = kvp_trace_totals_launch(ctx, d + oAcc, d + oWr, d + oSel);

@@ -49,6 +49,7 @@ struct kvp_ctx {
     int quad_stages = 2;                 // register stages of the four-schedule scorer (2 or 4)
     bool use_chunk = true;               // chunked four-schedule scorer for wide rows
     bool use_rowblock = true;            // whole-row four-schedule scorer for rows of 16..68 words
+    bool use_line = true;                // line-chunk four-schedule scorer for rows of >= 32 words
     uint32_t pfw = 0;                    // leading mask words that are FULL on every 64-step tile
     const uint32_t *aw = nullptr;        // [L][N][kb][Wd] binary digits of the pages' read weights (may alias A)
     uint32_t kb = 0;                     // digit planes, 0 if the weights need more than four
@@ -63,6 +64,7 @@ struct kvp_ctx {
     uint32_t *d_tileflag = nullptr; size_t tileflag_cap = 0;  // [S][tiles]
     double *d_tglobal = nullptr; size_t tglobal_cap = 0;      // [S][L][N] step latencies (wide rows)
     uint32_t *d_chunkfull = nullptr; uint32_t cf_words = 0;   // [tiles][cf_words] bit c: chunk c of 16 words is FULL
+    uint8_t *d_empty32 = nullptr;        // [tiles][ceil(Wd/32)] 1: no page of words [32c, 32c+32) exists on the tile
     uint32_t *d_cnt_tmp = nullptr; size_t cnt_tmp_cap = 0;    // delta: counters when not given
     uint32_t *d_occ_tmp = nullptr; size_t occ_tmp_cap = 0;
     // annealing state

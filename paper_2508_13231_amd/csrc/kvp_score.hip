@@ -164,6 +164,8 @@ int kvp_score_quad_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t 
                           uint32_t *counters, uint32_t *occ);
 int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
                               uint32_t *counters, uint32_t *occ);
+int kvp_score_line_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+                          uint32_t *counters, uint32_t *occ);
 
 int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, double *d_cost,
                      uint32_t *d_excess, uint32_t *d_counters, uint32_t *d_occ) {
@@ -179,6 +181,8 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
         rc = 1;
         if (ctx->use_rowblock && !ctx->force_wide)
             rc = kvp_score_rowblock_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
+        if (rc == 1 && ctx->use_line && !ctx->force_wide)
+            rc = kvp_score_line_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
         if (rc == 1 && ctx->use_chunk && !ctx->force_wide)
             rc = kvp_score_chunk_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
         if (rc == 1) rc = kvp_score_wide_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);

@@ -1,0 +1,309 @@
+// Scorer for wide rows (n_words >= 32): the schedule rows never touch LDS.
+//
+//   * A workgroup is four wavefronts scoring the same 64 token steps of four
+//     schedules.  A row is walked in chunks of 32 words = one 128-byte line when
+//     rows are line-aligned.  Lane (g, p), g = lane / 8, p = lane % 8, takes the
+//     16-byte part p of the chunk for the steps 8g .. 8g+7 and for step 8g-1: nine
+//     loads per lane and chunk, each wavefront instruction covering whole lines.
+//     A lane scores its parts straight from registers, the row above being the
+//     previous register, and keeps five counters per step until the row ends.
+//   * The trace words of a chunk (binary digit planes of the read weights, alive,
+//     persist, written) are the same for the four schedules: fetched once per
+//     workgroup, one chunk ahead, into a double-buffered LDS slot laid out in the
+//     order the lanes read it (16 bytes per lane, consecutive lanes consecutive).
+//     Chunks none of whose pages exists on the tile are only checked for stray bits.
+//   * At the end of a row the eight lanes of a group add their counters and lane
+//     (g, p) keeps step 8g + p: Eqs. 2-4 and the summation tree then run once per
+//     layer with one step per lane, as in the other lane-per-step scorers.
+//   * The last chunk of a row is shifted left to end at the row's end; the words
+//     it shares with the chunk before are zeroed after the load.
+#include "kvp_internal.h"
+
+namespace {
+
+typedef uint32_t l4u __attribute__((ext_vector_type(4), aligned(4)));    // rows may be only 4-byte aligned
+typedef uint32_t a4u __attribute__((ext_vector_type(4)));                // LDS vectors are 16-byte aligned
+
+constexpr int LQ = 4;           // schedules (= wavefronts) per workgroup
+constexpr int LCW = 32;         // words per chunk
+constexpr int PLANE = 64 * LCW; // words of one trace array in a slot
+
+__device__ __forceinline__ uint32_t oct_sum(uint32_t v) {               // sum over the 8 lanes of a group
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false);    // quad_perm [1,0,3,2]
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, false);    // quad_perm [2,3,0,1]
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, false);   // row_half_mirror
+    return v;
+}
+// acc += popcount(v) as the one instruction the hardware has for it (left to itself the compiler
+// counts into fresh registers and adds them up afterwards)
+__device__ __forceinline__ void count(uint32_t &acc, uint32_t v) {
+    asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(v));
+}
+__device__ __forceinline__ int clamp_i32(int v, int lo, int hi) { return min(max(v, lo), hi); }
+
+// KB: digit planes of the read weights; POW2: L is a power of two in 2..64.
+// No load is consumed in the iteration that issues it, and all are unconditional.
+template <int KB, bool POW2>
+__global__ __launch_bounds__(LQ * 64) void score_line_kernel(
+    DevProblem q, const uint32_t *__restrict__ Aw, const uint32_t *__restrict__ X, uint32_t S, uint32_t tiles,
+    uint32_t nb_total, uint32_t log2L, const uint8_t *__restrict__ chunkempty,
+    double *__restrict__ blocksum, double *__restrict__ tglobal, uint32_t *__restrict__ tileflag,
+    uint32_t *__restrict__ counters, uint32_t *__restrict__ occ_out) {
+    extern __shared__ double smem_d[];
+    constexpr int NT = KB + 3;                                          // digit planes, alive, persist, written
+    const uint32_t L = q.L, N = q.N, Wd = q.Wd;
+    const uint32_t NCH = (Wd + LCW - 1) / LCW;
+    const uint32_t tid = threadIdx.x;
+    const int lane = lane_id();
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / KVP_WAVE));
+    // Workgroups are handed to the eight XCDs in turn; those of one XCD take the schedule groups of
+    // one tile after the other, so the tile's trace is served by that XCD's L2.
+    const uint32_t groups = (S + LQ - 1) / LQ;
+    const uint32_t tile = ((blockIdx.x >> 3) / groups) * 8 + (blockIdx.x & 7u);
+    if (tile >= tiles) return;
+    const uint32_t s = ((blockIdx.x >> 3) % groups) * LQ + wave;
+    const bool has_s = s < S;
+    const uint32_t sc = has_s ? s : S - 1;                             // spare wavefronts shadow the last schedule
+    const uint32_t n0 = tile * 64;
+    const uint32_t rows = min(64u, N - n0);
+    uint32_t *tbuf = (uint32_t *)smem_d;                               // two slots of NT * PLANE words
+    const uint32_t g = (uint32_t)lane >> 3, p = (uint32_t)lane & 7u;
+
+    // the lane's own step
+    const bool active = (uint32_t)lane < rows;
+    const uint32_t n = n0 + (active ? (uint32_t)lane : rows - 1);      // idle lanes shadow the last row
+    const uint32_t wr_n = q.wr[n];
+    // Steps of the lane's nine loads: 8g-1 .. 8g+7 of the tile, kept inside the trace.  Step 0 is its
+    // own predecessor (nothing differs, nothing migrates); steps past the end repeat the last one,
+    // whose trace words the loader repeats too, and are never owned by an active lane.
+    const int step0 = (int)(n0 + 8 * g) - 1;
+    const uint32_t sched_words = L * N * Wd;                           // < 2^31 (checked by the host)
+    // trace vectors of this thread: rows tid/8 and 32 + tid/8 of the tile, part tid%8
+    const uint32_t trow0 = min(n0 + (tid >> 3), N - 1), trow1 = min(n0 + 32 + (tid >> 3), N - 1), tpart = tid & 7u;
+    // LDS word of (array a, row) for part tpart: [a][row % 8][row / 8][part][4]
+    auto lds_of = [&](uint32_t row) { return (((row & 7u) * 8 + (row >> 3)) * 8 + tpart) * 4; };
+    const uint32_t tl0 = lds_of(tid >> 3), tl1 = lds_of(32 + (tid >> 3));
+
+    // The nine row vectors of the lane.  Vector j is reloaded for the next iteration as soon as the
+    // current one has no more use for it, so one iteration's worth of rows is in flight all the time
+    // and nothing needs a second set of registers.
+    l4u x[9];
+    auto layer_of = [&](uint32_t i) { return POW2 ? (__brev(i) >> (32 - log2L)) : i; };
+    auto advance = [&](uint32_t &i, uint32_t &c) __attribute__((always_inline)) {
+        if (++c == NCH) { c = 0; if (i + 1 < L) i++; else c = NCH - 1; }   // past the end: stay on the last chunk
+    };
+    // All addresses are a wavefront-uniform base plus a 32-bit byte offset (the host checks that a
+    // schedule and the digit planes stay below 4 GiB).
+    const char *Xs = (const char *)(X + (size_t)sc * sched_words);
+    auto x_base = [&](uint32_t i, uint32_t c) { return 4 * (layer_of(i) * N * Wd + min(c * LCW, Wd - LCW) + 4 * p); };
+    auto issue_x = [&](int j, uint32_t base, int last_step) __attribute__((always_inline)) {
+        x[j] = *(const l4u *)(Xs + (base + (uint32_t)clamp_i32(step0 + j, 0, last_step) * (4 * Wd)));
+    };
+    l4u tr[2 * NT];
+    const uint32_t tb0 = 4 * (trow0 * Wd + 4 * tpart), tb1 = 4 * (trow1 * Wd + 4 * tpart);   // byte offsets in V, Pm, Wm
+    const uint32_t ta0 = 4 * (trow0 * KB * Wd + 4 * tpart), ta1 = 4 * (trow1 * KB * Wd + 4 * tpart);   // in the digit planes
+    auto issue_t = [&](uint32_t i, uint32_t c) __attribute__((always_inline)) {
+        const uint32_t w0b = 4 * min(c * LCW, Wd - LCW);
+        const char *Al = (const char *)Aw + (size_t)layer_of(i) * N * KB * Wd * 4 + w0b;
+#pragma unroll
+        for (int k = 0; k < KB; k++) {
+            tr[2 * k] = *(const l4u *)(Al + (ta0 + 4 * k * Wd));
+            tr[2 * k + 1] = *(const l4u *)(Al + (ta1 + 4 * k * Wd));
+        }
+        const char *Vb = (const char *)q.V + w0b, *Pb = (const char *)q.Pm + w0b, *Wb = (const char *)q.Wm + w0b;
+        tr[2 * KB] = *(const l4u *)(Vb + tb0);     tr[2 * KB + 1] = *(const l4u *)(Vb + tb1);
+        tr[2 * KB + 2] = *(const l4u *)(Pb + tb0); tr[2 * KB + 3] = *(const l4u *)(Pb + tb1);
+        tr[2 * KB + 4] = *(const l4u *)(Wb + tb0); tr[2 * KB + 5] = *(const l4u *)(Wb + tb1);
+    };
+    auto commit_t = [&](uint32_t it) __attribute__((always_inline)) {
+        uint32_t *slot = tbuf + (it & 1u) * NT * PLANE;
+#pragma unroll
+        for (int a = 0; a < NT; a++) {
+            *(a4u *)(slot + a * PLANE + tl0) = (a4u)tr[2 * a];
+            *(a4u *)(slot + a * PLANE + tl1) = (a4u)tr[2 * a + 1];
+        }
+    };
+
+    uint32_t fl_acc = 0, occ_acc = 0;
+    // partial sums of the binary counter: touched once per layer, so they live in LDS ([level][thread])
+    double *stk = smem_d + (size_t)NT * PLANE + tid;
+    double total = 0.0;
+    uint32_t it_ = 0, ct = 0;                // iteration whose trace words are requested next
+    uint32_t ix = 0, cx = 0;                 // the iteration after the one being scored
+    uint32_t it = 0;                         // iterations done: (layer, chunk) pairs in order
+
+    issue_t(it_, ct); advance(it_, ct);
+    {
+        const uint32_t b0 = x_base(0, 0);
+#pragma unroll
+        for (int j = 0; j < 9; j++) issue_x(j, b0, (int)N - 1);
+        advance(ix, cx);
+    }
+    commit_t(0);
+    for (uint32_t i = 0; i < L; i++) {
+        const uint32_t l = layer_of(i);
+        const uint32_t acc_n = q.acc[(size_t)l * N + n];               // used when the row ends
+        // counters of the steps 8g .. 8g+7 on this layer, this lane's parts only
+        uint32_t chr[8][KB], chw[8], coc[8], cmi[8], cmg[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+#pragma unroll
+            for (int k = 0; k < KB; k++) chr[j][k] = 0;
+            chw[j] = coc[j] = cmi[j] = cmg[j] = 0;
+        }
+        for (uint32_t c = 0; c < NCH; c++, it++) {
+            const uint32_t w0 = min(c * LCW, Wd - LCW);
+            const uint32_t skip = c * LCW - w0;                       // leading words already counted (last chunk only)
+            const bool empty = skip == 0 && chunkempty[(size_t)tile * NCH + c] != 0;
+            if (skip) {
+                const uint32_t b = 4 * p;
+#pragma unroll
+                for (int j = 0; j < 9; j++) {
+                    x[j].x = b + 0 < skip ? 0u : x[j].x; x[j].y = b + 1 < skip ? 0u : x[j].y;
+                    x[j].z = b + 2 < skip ? 0u : x[j].z; x[j].w = b + 3 < skip ? 0u : x[j].w;
+                }
+            }
+            const uint32_t nbase = x_base(ix, cx);
+            advance(ix, cx);
+            int last_step = (int)N - 1;
+            asm volatile("" : "+s"(last_step));                        // keeps the nine row offsets out of registers
+            issue_t(it_, ct); advance(it_, ct);                        // trace words of the next iteration
+            __syncthreads();                                           // this iteration's trace slot is complete
+            const uint32_t *slot = tbuf + (it & 1u) * NT * PLANE + 4 * (uint32_t)lane;
+            if (empty) {
+                // no page of these 32 words exists on any step of the tile: any bit is a bit too many
+#pragma unroll
+                for (int j = 1; j < 9; j++) fl_acc |= x[j].x | x[j].y | x[j].z | x[j].w;
+#pragma unroll
+                for (int j = 0; j < 9; j++) issue_x(j, nbase, last_step);
+            } else {
+                // The trace vectors of step j+1 are requested from LDS before step j is scored, and
+                // the scheduler is kept from hoisting them any further: otherwise all eight steps'
+                // vectors would be live at once.
+                a4u tv[2][NT];
+                auto fetch = [&](int j, a4u *dst) __attribute__((always_inline)) {
+                    const uint32_t *sj = slot + j * 256;               // [row % 8 = j][lane][4]
+#pragma unroll
+                    for (int a = 0; a < NT; a++) dst[a] = *(const a4u *)(sj + a * PLANE);
+                };
+                fetch(0, tv[0]);
+#pragma unroll
+                for (int j = 0; j < 8; j++) {
+                    if (j < 7) fetch(j + 1, tv[(j + 1) & 1]);
+                    const a4u *cv = tv[j & 1];
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        const uint32_t raw = x[j + 1][e], xp = x[j][e];
+                        const uint32_t xx = raw & cv[KB][e];           // alive
+                        fl_acc |= raw & ~cv[KB][e];
+                        const uint32_t d = (xx ^ xp) & cv[KB + 1][e];  // persist
+#pragma unroll
+                        for (int k = 0; k < KB; k++) count(chr[j][k], xx & cv[k][e]);
+                        count(chw[j], xx & cv[KB + 2][e]);             // written
+                        count(coc[j], xx);
+                        count(cmi[j], d & xx);
+                        count(cmg[j], d);
+                    }
+                    issue_x(j, nbase, last_step);                      // its last use was as the step before
+                    if (j == 7) issue_x(8, nbase, last_step);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            commit_t(it + 1);                                          // arrived while this iteration was scored
+        }
+        // the rows are complete: the group's lanes add up, lane (g, p) keeps step 8g + p
+        uint32_t hr = 0, hw = 0, oc = 0, mi = 0, mg = 0;
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            uint32_t h = 0;
+#pragma unroll
+            for (int k = 0; k < KB; k++) h += chr[j][k] << k;
+            h = oct_sum(h);
+            const uint32_t w = oct_sum(chw[j]), o = oct_sum(coc[j]), m1 = oct_sum(cmi[j]), m2 = oct_sum(cmg[j]);
+            const bool mine = p == (uint32_t)j;
+            hr = mine ? h : hr; hw = mine ? w : hw; oc = mine ? o : oc; mi = mine ? m1 : mi; mg = mine ? m2 : mg;
+            __builtin_amdgcn_sched_barrier(0);                         // one step at a time: few temporaries
+        }
+        const uint32_t mo = mg - mi;
+        double t = step_time(q, hr, hw, mi, mo, acc_n, wr_n);          // Eqs. 2-4
+        t = active ? t : 0.0;                                          // rows past the end of the trace pad with +0.0
+        occ_acc += oc;
+        if (counters && has_s && active)
+            *(uint4 *)(counters + (((size_t)s * L + l) * N + n) * 4) = make_uint4(hr, hw, mi, mo);
+        if (POW2) {
+            // folds of the summation tree that join the steps of one block (lanes)
+            for (uint32_t m = (64u >> log2L) >> 1; m >= 1; m >>= 1) t = t + __shfl_xor(t, (int)m, KVP_WAVE);
+            // folds that join layers: binary counter over the bit-reversed visiting order
+            double carry = t;
+            bool parked = false;
+#pragma unroll
+            for (int j = 0; j < 6; j++) {
+                if (!parked && (uint32_t)j < log2L) {
+                    if (((i >> j) & 1u) == 0) { stk[j * LQ * 64] = carry; parked = true; }
+                    else carry = stk[j * LQ * 64] + carry;
+                }
+            }
+            if (!parked) total = carry;                                // only at the last layer
+        } else if (has_s && active) {
+            tglobal[((size_t)s * L + l) * N + n] = t;
+        }
+    }
+    if (!has_s) return;
+    if (POW2) {
+        const uint32_t bpl = 64u >> log2L;                             // block b of the tile: steps [b*bpl, (b+1)*bpl)
+        if (((uint32_t)lane & (bpl - 1)) == 0 && (uint32_t)lane < rows)
+            blocksum[(size_t)s * nb_total + (size_t)tile * L + (uint32_t)lane / bpl] = total;
+    }
+    uint32_t ex = 0;
+    if (active) {
+        if (occ_out) occ_out[(size_t)s * N + n] = occ_acc;            // Eq. 5 per token step
+        ex = occ_acc > q.cap ? occ_acc - q.cap : 0;
+    }
+    ex = wave_max_u32(ex);
+    const uint32_t fl = wave_or_u32(fl_acc);
+    if (lane == 0) tileflag[(size_t)s * tiles + tile] = ex | (fl ? 0x80000000u : 0u);
+}
+
+}  // namespace
+
+int kvp_blocksum_from_t_launch(kvp_ctx *ctx, uint32_t S, uint32_t nb_total);
+
+// Returns KVP_OK if launched, 1 if this kernel does not cover the shape, <0 on error.
+int kvp_score_line_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+                          uint32_t *counters, uint32_t *occ) {
+    const DevProblem &q = ctx->dp;
+    if (!ctx->aw || !ctx->d_empty32 || q.Wd < LCW) return 1;
+    const uint32_t KB = ctx->kb;
+    if ((size_t)q.L * q.N * q.Wd * KB >= (1ull << 30)) return 1;      // 32-bit byte offsets inside a schedule and the planes
+    uint32_t log2L = 0;
+    while ((1u << log2L) < q.L) log2L++;
+    const bool pow2 = q.L >= 2 && q.L <= 64 && (1u << log2L) == q.L;
+    const size_t lds = 2 * (size_t)(KB + 3) * PLANE * 4 + (pow2 ? (size_t)6 * LQ * 64 * 8 : 0);
+    if (lds > 160 * 1024) return 1;
+    const uint64_t nwg = (uint64_t)((S + LQ - 1) / LQ) * ((tiles + 7) / 8) * 8;   // whole rounds over the XCDs
+    if (nwg > 0x7FFFFFFFull) return 1;
+    if (!pow2) {
+        int rc = kvp_ensure(ctx, (void **)&ctx->d_tglobal, &ctx->tglobal_cap, (size_t)S * q.L * q.N * sizeof(double));
+        if (rc) return rc;
+    }
+    dim3 grid((uint32_t)nwg), block(LQ * 64);
+#define KVP_GO(KK, PP)                                                                                         \
+    do {                                                                                                       \
+        KVP_HIP(hipFuncSetAttribute((const void *)score_line_kernel<KK, PP>,                                   \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                   \
+        score_line_kernel<KK, PP><<<grid, block, lds, ctx->stream>>>(                                          \
+            q, ctx->aw, X, S, tiles, nb_total, log2L, ctx->d_empty32, ctx->d_blocksum,                          \
+            ctx->d_tglobal, ctx->d_tileflag, counters, occ);                                                   \
+    } while (0)
+#define KVP_K(KK) case KK: if (pow2) KVP_GO(KK, true); else KVP_GO(KK, false); break;
+    switch (KB) {
+        KVP_K(1) KVP_K(2) KVP_K(3) KVP_K(4)
+        default: return 1;
+    }
+#undef KVP_K
+#undef KVP_GO
+    KVP_HIP(hipGetLastError());
+    ctx->last_kernel = KVP_SCORE_LINE;
+    if (!pow2) return kvp_blocksum_from_t_launch(ctx, S, nb_total);
+    return KVP_OK;
+}

@@ -72,14 +72,15 @@ CASES = list(_cases())
 NATIVE = {
     "rowblock": {"longctx/2", "gqa70b/2", "dec-w21-L3", "dec-w38-k3", "dec-w68-k2", "dec-w16"},
     "chunk": {"rand-wide", "rand-w40", "rand-w300", "rand-w301", "longctx/4", "longctx/2", "rand-w16", "dec-w24-tail"},
+    "line": {"rand-wide", "rand-w40", "rand-w300", "rand-w301", "longctx/2", "dec-w38-k3", "dec-w68-k2"},
     "quad": {"llama8b/4", "rand-L16", "rand-L64", "rand-L2"},
 }
 
 
-KERNEL_IDS = ["rows", "lanes", "lanes8w", "direct", "direct8w", "quad", "quad4s", "wide", "chunk", "rowblock"]
+KERNEL_IDS = ["rows", "lanes", "lanes8w", "direct", "direct8w", "quad", "quad4s", "wide", "chunk", "rowblock", "line"]
 
 
-@pytest.mark.parametrize("kernel", list(range(1, 11)), ids=KERNEL_IDS)
+@pytest.mark.parametrize("kernel", list(range(1, 12)), ids=KERNEL_IDS)
 @pytest.mark.parametrize("name,tr", CASES, ids=[c[0] for c in CASES])
 def test_score_matches_oracle_bit_for_bit(G, name, tr, kernel):
     from gpu_util import expected_counters
