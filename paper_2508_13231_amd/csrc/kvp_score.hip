@@ -130,26 +130,51 @@ __global__ __launch_bounds__(256) void score_rows_kernel(DevProblem q, const uin
 }
 
 // Block sums are added in order from block 0 (the sequential part of the
-// summation order), tile verdicts are merged.
+// summation order), tile verdicts are merged.  One wavefront per schedule: 64
+// block sums are fetched at a time, one per lane, and added one after the other
+// through lane broadcasts; every lane carries the same running total.
 __global__ __launch_bounds__(256) void score_finalize_kernel(uint32_t S, uint32_t nb_total, uint32_t tiles,
                                                              const double *__restrict__ blocksum,
                                                              const uint32_t *__restrict__ tileflag,
                                                              double *__restrict__ cost,
                                                              uint32_t *__restrict__ excess) {
-    const uint32_t s = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t s = blockIdx.x * 4 + threadIdx.x / KVP_WAVE;
     if (s >= S) return;
+    const uint32_t lane = (uint32_t)lane_id();
     const double *b = blocksum + (size_t)s * nb_total;
-    double T = nb_total ? b[0] : 0.0;
-    for (uint32_t i = 1; i < nb_total; i++) T = T + b[i];
+    double T = 0.0;
+    double v = lane < nb_total ? b[lane] : 0.0;
+    for (uint32_t i0 = 0; i0 < nb_total; i0 += 64) {
+        const double cur = v;
+        const uint32_t nx = i0 + 64 + lane;
+        v = nx < nb_total ? b[nx] : 0.0;                               // next 64 while these are added
+        const uint32_t cnt = min(64u, nb_total - i0);
+        if (cnt == 64) {
+#pragma unroll
+            for (int j = 0; j < 64; j++) {
+                const double bj = __shfl(cur, j, KVP_WAVE);
+                T = (i0 == 0 && j == 0) ? bj : T + bj;
+            }
+        } else {
+            for (uint32_t j = 0; j < cnt; j++) {
+                const double bj = __shfl(cur, (int)j, KVP_WAVE);
+                T = (i0 == 0 && j == 0) ? bj : T + bj;
+            }
+        }
+    }
     uint32_t ex = 0, fl = 0;
-    for (uint32_t t = 0; t < tiles; t++) {
+    for (uint32_t t = lane; t < tiles; t += 64) {
         const uint32_t f = tileflag[(size_t)s * tiles + t];
         fl |= f & 0x80000000u;
         const uint32_t e = f & 0x7FFFFFFFu;
         ex = e > ex ? e : ex;
     }
-    cost[s] = T;
-    excess[s] = ex | fl;
+    ex = wave_max_u32(ex);
+    fl = wave_or_u32(fl);
+    if (lane == 0) {
+        cost[s] = T;
+        excess[s] = ex | fl;
+    }
 }
 
 static uint32_t gcd_u32(uint32_t a, uint32_t b) { while (b) { uint32_t t = a % b; a = b; b = t; } return a; }
@@ -188,7 +213,7 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
         if (rc == 1) rc = kvp_score_wide_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
         if (rc < 0) return rc;
         if (rc == KVP_OK) {
-            score_finalize_kernel<<<dim3((S + 255) / 256), dim3(256), 0, ctx->stream>>>(
+            score_finalize_kernel<<<dim3((S + 3) / 4), dim3(256), 0, ctx->stream>>>(
                 S, nb_total, tiles64, ctx->d_blocksum, ctx->d_tileflag, d_cost, d_excess);
             KVP_HIP(hipGetLastError());
             return KVP_OK;
@@ -204,7 +229,7 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
         if (rc == 1) rc = kvp_score_tile_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
         if (rc < 0) return rc;
         if (rc == KVP_OK) {
-            score_finalize_kernel<<<dim3((S + 255) / 256), dim3(256), 0, ctx->stream>>>(
+            score_finalize_kernel<<<dim3((S + 3) / 4), dim3(256), 0, ctx->stream>>>(
                 S, nb_total, tiles64, ctx->d_blocksum, ctx->d_tileflag, d_cost, d_excess);
             KVP_HIP(hipGetLastError());
             return KVP_OK;
@@ -235,7 +260,7 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
                                                                    ctx->d_blocksum, ctx->d_tileflag, d_counters, d_occ);
     KVP_HIP(hipGetLastError());
     ctx->last_kernel = KVP_SCORE_ROWS;
-    score_finalize_kernel<<<dim3((S + 255) / 256), dim3(256), 0, ctx->stream>>>(S, nb_total, tiles, ctx->d_blocksum,
+    score_finalize_kernel<<<dim3((S + 3) / 4), dim3(256), 0, ctx->stream>>>(S, nb_total, tiles, ctx->d_blocksum,
                                                                                ctx->d_tileflag, d_cost, d_excess);
     KVP_HIP(hipGetLastError());
     return KVP_OK;

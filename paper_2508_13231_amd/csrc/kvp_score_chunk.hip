@@ -217,9 +217,33 @@ __global__ __launch_bounds__(CQ * 64) void score_chunk_kernel(
     if (lane == 0) tileflag[(size_t)s * tiles + tile] = ex | (fl ? 0x80000000u : 0u);
 }
 
-// Eq. 1 from the step latencies in HBM: one wavefront per 64-block of the
-// execution order g = n*L + l of one schedule.
-__global__ __launch_bounds__(256) void blocksum_from_t_kernel(uint32_t S, uint32_t L, uint32_t N, uint32_t nb_total,
+// Eq. 1 from the step latencies in HBM.  A workgroup takes 64 token steps of one
+// schedule: the L rows of 64 latencies are read as they lie in memory, turned in
+// LDS, and each wavefront folds every fourth of the tile's 64-blocks of the
+// execution order g = n*L + l.
+__global__ __launch_bounds__(256) void blocksum_from_t_kernel(uint32_t L, uint32_t N, uint32_t tiles, uint32_t nb_total,
+                                                              const double *__restrict__ tglobal,
+                                                              double *__restrict__ blocksum) {
+    extern __shared__ double tb[];                                     // [L][65]
+    const uint32_t s = blockIdx.x / tiles, tile = blockIdx.x % tiles;
+    const uint32_t n0 = tile * 64, rows = min(64u, N - n0);
+    const uint32_t wave = threadIdx.x / KVP_WAVE, lane = (uint32_t)lane_id();
+    for (uint32_t l = wave; l < L; l += 4)
+        tb[l * 65 + lane] = lane < rows ? tglobal[((size_t)s * L + l) * N + n0 + lane] : 0.0;
+    __syncthreads();
+    const uint32_t nvalid = rows * L, nblk = (nvalid + 63) / 64;
+    for (uint32_t b = wave; b < nblk; b += 4) {
+        const uint32_t g = b * 64 + lane;
+        const uint32_t r = g / L, l = g - r * L;
+        double t = g < nvalid ? tb[l * 65 + r] : 0.0;
+        t = wave_tree_sum_f64(t);
+        if (lane == 0) blocksum[(size_t)s * nb_total + (size_t)tile * L + b] = t;
+    }
+}
+
+// The same for layer counts whose tile does not fit LDS: one wavefront per 64-block gathers its
+// latencies straight from memory.
+__global__ __launch_bounds__(256) void blocksum_gather_kernel(uint32_t S, uint32_t L, uint32_t N, uint32_t nb_total,
                                                               const double *__restrict__ tglobal,
                                                               double *__restrict__ blocksum) {
     const uint64_t wv = (uint64_t)blockIdx.x * 4 + threadIdx.x / KVP_WAVE;
@@ -240,9 +264,21 @@ __global__ __launch_bounds__(256) void blocksum_from_t_kernel(uint32_t S, uint32
 // Block sums of Eq. 1 from the step latencies in ctx->d_tglobal ([S][L][N]).
 int kvp_blocksum_from_t_launch(kvp_ctx *ctx, uint32_t S, uint32_t nb_total) {
     const DevProblem &q = ctx->dp;
-    const uint64_t nwv = (uint64_t)S * nb_total;
-    blocksum_from_t_kernel<<<dim3((uint32_t)((nwv + 3) / 4)), dim3(256), 0, ctx->stream>>>(S, q.L, q.N, nb_total,
-                                                                                         ctx->d_tglobal, ctx->d_blocksum);
+    const uint32_t tiles = (q.N + 63) / 64;
+    const size_t lds = (size_t)q.L * 65 * sizeof(double);
+    if (lds > 160 * 1024 || (uint64_t)S * tiles > 0x7FFFFFFFull) {
+        const uint64_t nwv = (uint64_t)S * nb_total;
+        if ((nwv + 3) / 4 > 0x7FFFFFFFull) return KVP_ESHAPE;
+        blocksum_gather_kernel<<<dim3((uint32_t)((nwv + 3) / 4)), dim3(256), 0, ctx->stream>>>(
+            S, q.L, q.N, nb_total, ctx->d_tglobal, ctx->d_blocksum);
+        KVP_HIP(hipGetLastError());
+        return KVP_OK;
+    }
+    if (lds > 48 * 1024)
+        KVP_HIP(hipFuncSetAttribute((const void *)blocksum_from_t_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds));
+    blocksum_from_t_kernel<<<dim3(S * tiles), dim3(256), lds, ctx->stream>>>(q.L, q.N, tiles, nb_total, ctx->d_tglobal,
+                                                                             ctx->d_blocksum);
     KVP_HIP(hipGetLastError());
     return KVP_OK;
 }
