@@ -8,8 +8,9 @@
 //     a wavefront fetches its 33 rows (32 steps and the step before) WHOLE, as
 //     16-byte vectors that follow each other in memory, so every 128-byte line is
 //     requested once and by one instruction group.  The vectors are parked in LDS
-//     with an odd row stride and two lanes share a row, one taking the even words
-//     and one the odd: 64 lanes hit 64 different bank slots.
+//     with a row stride of 2 (mod 4) words and two lanes share a row, one taking
+//     the even words and one the odd: the 32 lanes that the LDS serves per cycle
+//     hit its 32 banks once each.
 //   * The access planes are replaced by the binary digits of each page's read
 //     weight (sum over planes of plane_bytes/unit): K planes of equal size become
 //     floor(log2 K) + 1 digit planes, and hr = sum_j 2^j popcount(x & digit_j).
@@ -78,7 +79,9 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
     extern __shared__ double smem_d[];
     constexpr int TV = (KB * XV * 8 + 32) / 33;                        // trace vectors per thread and pass
     const uint32_t L = q.L, N = q.N, Wd = q.Wd;
-    const uint32_t RS = Wd | 1u, PPR = (Wd + 3) / 4;                   // LDS row stride (odd), vectors per row
+    // LDS row stride = 2 (mod 4): the LDS serves 32 lanes per cycle from 32 banks, and lanes (r, h2),
+    // r < 16, then read words 2r + h2 + const (mod 32) of their rows: all different
+    const uint32_t RS = Wd + ((6 - (Wd & 3u)) & 3u), PPR = (Wd + 3) / 4;
     const uint32_t TPL = RR * RS;                                      // words of one digit plane in a slot
     const uint32_t tid = threadIdx.x;
     const int lane = lane_id();
@@ -299,7 +302,7 @@ int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint3
     if (!ctx->aw || !q.single_write || q.Wd < 16 || q.Wd > 68) return 1;
     const uint32_t pfw2 = ctx->pfw & ~1u;
     if (q.Wd - pfw2 > TWMAX) return 1;
-    const uint32_t PPR = (q.Wd + 3) / 4, RS = q.Wd | 1u, KB = ctx->kb;
+    const uint32_t PPR = (q.Wd + 3) / 4, RS = q.Wd + ((6 - (q.Wd & 3u)) & 3u), KB = ctx->kb;
     const uint32_t need = ((RR + 1) * PPR + 63) / 64;
     const int xv = need <= 5 ? 5 : 9;
     if (need > 9) return 1;
