@@ -150,9 +150,12 @@ __global__ __launch_bounds__(256) void score_finalize_kernel(uint32_t S, uint32_
         v = nx < nb_total ? b[nx] : 0.0;                               // next 64 while these are added
         const uint32_t cnt = min(64u, nb_total - i0);
         if (cnt == 64) {
+            // lane j's value through the scalar unit: a few cycles, where a cross-lane shuffle would
+            // put an LDS round trip into every link of this chain of additions
+            const int lo = __double2loint(cur), hi = __double2hiint(cur);
 #pragma unroll
             for (int j = 0; j < 64; j++) {
-                const double bj = __shfl(cur, j, KVP_WAVE);
+                const double bj = __hiloint2double(__builtin_amdgcn_readlane(hi, j), __builtin_amdgcn_readlane(lo, j));
                 T = (i0 == 0 && j == 0) ? bj : T + bj;
             }
         } else {

@@ -228,8 +228,15 @@ __global__ __launch_bounds__(256) void blocksum_from_t_kernel(uint32_t L, uint32
     const uint32_t s = blockIdx.x / tiles, tile = blockIdx.x % tiles;
     const uint32_t n0 = tile * 64, rows = min(64u, N - n0);
     const uint32_t wave = threadIdx.x / KVP_WAVE, lane = (uint32_t)lane_id();
-    for (uint32_t l = wave; l < L; l += 4)
-        tb[l * 65 + lane] = lane < rows ? tglobal[((size_t)s * L + l) * N + n0 + lane] : 0.0;
+    const double *ts = tglobal + (size_t)s * L * N + n0 + min(lane, rows - 1);
+    for (uint32_t l0 = wave; l0 < L; l0 += 32) {                       // eight rows in flight per wavefront
+        double v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) v[u] = ts[(size_t)min(l0 + 4 * u, L - 1) * N];
+#pragma unroll
+        for (int u = 0; u < 8; u++)
+            if (l0 + 4 * u < L) tb[(l0 + 4 * u) * 65 + lane] = lane < rows ? v[u] : 0.0;
+    }
     __syncthreads();
     const uint32_t nvalid = rows * L, nblk = (nvalid + 63) / 64;
     for (uint32_t b = wave; b < nblk; b += 4) {

@@ -137,7 +137,6 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
     // comes first.  Step 0 has none: there the offsets are clamped from below and the lanes of step 0
     // use the step itself as its predecessor (nothing migrates at step 0).
     const uint32_t sched_words = L * N * Wd;                           // < 2^31 (checked by the host)
-    const uint32_t prow0 = (n0 == 0 && r == 0) ? 1u : r;               // LDS row of the predecessor in pass 0
 
     struct Stage { r4u x[XV]; };
     Stage st0, st1;
@@ -174,15 +173,21 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
         issue_t(p ^ 1u, p ? lnext : layer_of(i));                      // digit planes of the next pass
         issue_x(st, p, lnext);                                         // rows of two passes ahead
         __syncthreads();                                               // this pass's trace slot is complete
-        const uint32_t *cur = xbuf + (r + 1) * RS, *prv = xbuf + (p ? r : prow0) * RS;
-        const uint32_t *ts = tbuf + p * KB * TPL + r * RS;
-        const bool own = h2 == p;
+        // (addresses and masks below are rebuilt in every pass from these two copies: kept across the
+        // layer loop they would occupy some sixty registers)
+        uint32_t rv = r, hv = h2;
+        asm volatile("" : "+v"(rv), "+v"(hv));
+        const uint32_t *cur = xbuf + (rv + 1) * RS, *prv = xbuf + ((p || !(n0 == 0 && rv == 0)) ? rv : 1u) * RS;
+        const uint32_t *ts = tbuf + p * KB * TPL + rv * RS;
+        const bool own = hv == p;
         uint32_t hrk[KB], c_oc = 0, c_mi = 0, c_mg = 0;
 #pragma unroll
         for (int k = 0; k < KB; k++) hrk[k] = 0;
-#pragma unroll 8
+        // (a deeper unroll keeps more LDS words in flight per wavefront; with several planes the
+        // registers are better spent on a third wavefront per SIMD)
+#pragma unroll KB >= 2 ? 4 : 8
         for (uint32_t j = 0; j < nfull; j++) {
-            const uint32_t w = 2 * j + h2;
+            const uint32_t w = 2 * j + hv;
             const uint32_t raw = cur[w], d = raw ^ prv[w];
 #pragma unroll
             for (int k = 0; k < KB; k++) hrk[k] += __popc(raw & ts[k * TPL + w]);
