@@ -291,14 +291,32 @@ def test_error_paths_reach_no_kernel(G):
         K.kvp_destroy(ctx)
 
 
-def test_full_size_batch_sampled_against_oracle(G):
-    """The benchmark's own launch (config 1, S >= 4 GiB of schedules, default
-    kernel choice): sampled schedules are re-scored one by one by the oracle."""
+def _full_shape(name):
+    """Trace and batch size of a benchmark config.  Config 1 is taken whole (the benchmark's own launch);
+    the two configs whose trace takes minutes to draw keep their layers, row width and planes but
+    fewer token steps."""
+    import dataclasses
+    import bench
+    from workloads.traces import generate, recipe
+    if name == "llama8b":
+        tr = W.config("llama8b")
+        return tr, bench.default_schedules(tr)
+    if name == "longctx":
+        return W.config("longctx"), 1024
+    if name == "gqa70b":
+        return generate(dataclasses.replace(recipe("gqa70b"), N=256)), 510
+    return generate(dataclasses.replace(recipe("serving"), N=128)), 126
+
+
+@pytest.mark.parametrize("name,kernel", [("llama8b", "quad"), ("longctx", "rowblock"), ("gqa70b", "rowblock"),
+                                         ("serving", "line")])
+def test_full_size_batch_sampled_against_oracle(G, name, kernel):
+    """Full row shapes and batch sizes, default kernel choice: sampled schedules are re-scored one by
+    one by the oracle, and the scorer meant for the shape is the one that ran."""
     import torch
     import bench
     import paper_2508_13231_amd as K
-    tr = W.config("llama8b")
-    S = bench.default_schedules(tr)
+    tr, S = _full_shape(name)
     q = O.Problem(tr)
     with G(tr) as g:
         d_x = bench.make_batch(tr, S, g.dev)
@@ -306,9 +324,12 @@ def test_full_size_batch_sampled_against_oracle(G):
         d_ex = torch.empty(S, dtype=torch.int32, device=g.dev)
         K.kvp_score(g.ctx, d_x, S, d_cost, d_ex)
         torch.cuda.synchronize()
+        assert KERNEL_IDS[g.kernel_used() - 1] == kernel
         cost = d_cost.cpu().numpy()
         ex = d_ex.cpu().numpy().view(np.uint32)
         pick = [0, 1, 2, 3, 4, S // 3, S // 2, S - 6, S - 5, S - 4, S - 3, S - 2, S - 1]
+        if name != "llama8b":
+            pick = [0, 3, S // 2, S - 2, S - 1]
         for s in pick:
             X = g.unpack(d_x[s].cpu().numpy().view(np.uint32))
             r = O.score(q, X)
