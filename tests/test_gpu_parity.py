@@ -52,6 +52,7 @@ def _cases():
                                 plane_bytes=[4096, 8192, 12288])           # weights 1, 2, 3: three digit planes
     yield "dec-w68-k2", _decode(33, L=2, N=40, words=67, page_tokens=2, K=2)   # widest rows, second pass empty
     yield "dec-w16", _decode(34, L=8, N=129, words=15, page_tokens=8)      # 16 words, three tiles, the last of one step
+    yield "dec-w16-L30", _decode(36, L=30, N=70, words=15, page_tokens=8)     # step latencies too many for the LDS at hand
     yield "dec-w24-tail", _decode(35, L=2, N=200, words=18, page_tokens=1)     # 200 new pages: too many masked words
     yield "gqa70b/2", W.config("gqa70b", 0.5)                              # 17 words, 8 planes -> 4 digits, 40 layers
 
@@ -70,7 +71,7 @@ def _decode(seed, L, N, words, page_tokens, K=1, plane_bytes=None):
 CASES = list(_cases())
 # scorers that must run natively (not be replaced by another) on a case
 NATIVE = {
-    "rowblock": {"longctx/2", "gqa70b/2", "dec-w21-L3", "dec-w38-k3", "dec-w68-k2", "dec-w16"},
+    "rowblock": {"longctx/2", "gqa70b/2", "dec-w21-L3", "dec-w38-k3", "dec-w68-k2", "dec-w16", "dec-w16-L30"},
     "chunk": {"rand-wide", "rand-w40", "rand-w300", "rand-w301", "longctx/4", "longctx/2", "rand-w16", "dec-w24-tail"},
     "line": {"rand-wide", "rand-w40", "rand-w300", "rand-w301", "longctx/2", "dec-w38-k3", "dec-w68-k2"},
     "quad": {"llama8b/4", "rand-L16", "rand-L64", "rand-L2"},
