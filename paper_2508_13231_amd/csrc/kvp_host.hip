@@ -82,15 +82,7 @@ extern "C" const char *kvp_strerror(int code) {
 
 extern "C" int kvp_set_score_kernel(kvp_ctx *ctx, int which) {
     if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_LINE) return KVP_EINVAL;
-    ctx->force_wide = which == KVP_SCORE_WIDE;
-    ctx->use_chunk = which == KVP_SCORE_AUTO || which == KVP_SCORE_CHUNK;
-    ctx->use_rowblock = which == KVP_SCORE_AUTO || which == KVP_SCORE_ROWBLOCK;
-    ctx->use_line = which == KVP_SCORE_AUTO || which == KVP_SCORE_LINE;
-    ctx->tile_quad = which == KVP_SCORE_AUTO || which == KVP_SCORE_QUAD || which == KVP_SCORE_QUAD_4S;
-    ctx->quad_stages = which == KVP_SCORE_QUAD_4S ? 4 : 2;
-    ctx->score_kernel = which == KVP_SCORE_CHUNK || which == KVP_SCORE_ROWBLOCK || which == KVP_SCORE_LINE ? KVP_SCORE_CHUNK : which >= KVP_SCORE_LANES ? KVP_SCORE_LANES : which;
-    ctx->tile_waves = (which == KVP_SCORE_LANES_8W || which == KVP_SCORE_DIRECT_8W) ? 8 : 4;
-    ctx->tile_direct = (which >= KVP_SCORE_DIRECT && which <= KVP_SCORE_QUAD_4S) || which == KVP_SCORE_AUTO;
+    ctx->score_kernel = which;
     return KVP_OK;
 }
 

@@ -43,21 +43,13 @@ struct kvp_ctx {
     kvp_problem prob{};
     DevProblem dp{};
     uint64_t unit = 0;
-    int score_kernel = 0;                // KVP_SCORE_AUTO / _ROWS / _LANES
+    int score_kernel = 0;                // KVP_SCORE_AUTO, or the scorer kvp_score tries first
     int last_kernel = 0;                 // scorer that the last kvp_score ran (KVP_SCORE_*), 0 before the first
     bool prefix_full = false;            // on every 64-step tile all mask words but the last are FULL
-    int quad_stages = 2;                 // register stages of the four-schedule scorer (2 or 4)
-    bool use_chunk = true;               // chunked four-schedule scorer for wide rows
-    bool use_rowblock = true;            // whole-row four-schedule scorer for rows of 16..68 words
-    bool use_line = true;                // line-chunk four-schedule scorer for rows of >= 32 words
     uint32_t pfw = 0;                    // leading mask words that are FULL on every 64-step tile
     const uint32_t *aw = nullptr;        // [L][N][kb][Wd] binary digits of the pages' read weights (may alias A)
     uint32_t kb = 0;                     // digit planes, 0 if the weights need more than four
     uint32_t *d_aw = nullptr;            // owned storage of aw when it is not A
-    bool force_wide = false;             // use the wide-row scorer also for narrow rows
-    int tile_quad = 1;                   // four schedules per workgroup (power-of-two layer counts)
-    int tile_direct = 1;                 // narrow-row scorer without LDS staging (single plane only)
-    int tile_waves = 4;                  // wavefronts per workgroup of the narrow-row scorer (4 or 8)
     uint32_t *d_trace = nullptr;         // one allocation: A, V, Pm, Wm, acc, wr
     // scoring scratch
     double *d_blocksum = nullptr;  size_t blocksum_cap = 0;   // [S][nb]

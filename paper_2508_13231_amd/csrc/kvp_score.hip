@@ -201,35 +201,28 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
     if (S == 0) return KVP_OK;
     int rc;
     const uint32_t nb_total = (uint32_t)(((uint64_t)q.L * q.N + 63) / 64);
-    if (ctx->score_kernel != KVP_SCORE_ROWS && (q.Wd > 16 || ctx->force_wide || (q.Wd == 16 && ctx->score_kernel == KVP_SCORE_CHUNK))) {
-        // wide rows: 16 or 64 lanes per row, 64 token steps per tile
+    const int forced = ctx->score_kernel;                  // KVP_SCORE_AUTO or the scorer to try first
+    if (forced != KVP_SCORE_ROWS) {
+        // scorers with one lane per token step: tiles of 64 steps
         const uint32_t tiles64 = (q.N + 63) / 64;
         if ((rc = kvp_ensure(ctx, (void **)&ctx->d_blocksum, &ctx->blocksum_cap, (size_t)S * nb_total * sizeof(double)))) return rc;
         if ((rc = kvp_ensure(ctx, (void **)&ctx->d_tileflag, &ctx->tileflag_cap, (size_t)S * tiles64 * sizeof(uint32_t)))) return rc;
+        typedef int (*launch_fn)(kvp_ctx *, const uint32_t *, uint32_t, uint32_t, uint32_t, uint32_t *, uint32_t *);
+        // the order AUTO tries them in: narrow rows first, then by how close each comes to the HBM rate
+        struct { int id; launch_fn fn; bool narrow; } const order[] = {
+            {KVP_SCORE_QUAD, kvp_score_quad_launch, true},     {KVP_SCORE_LANES, kvp_score_tile_launch, true},
+            {KVP_SCORE_ROWBLOCK, kvp_score_rowblock_launch, false}, {KVP_SCORE_LINE, kvp_score_line_launch, false},
+            {KVP_SCORE_CHUNK, kvp_score_chunk_launch, false},  {KVP_SCORE_WIDE, kvp_score_wide_launch, false},
+        };
+        // variants of one launcher share its entry: which variant runs is read from ctx->score_kernel there
+        const int family = forced == KVP_SCORE_QUAD_4S ? KVP_SCORE_QUAD
+                           : (forced >= KVP_SCORE_LANES && forced <= KVP_SCORE_DIRECT_8W) ? KVP_SCORE_LANES : forced;
         rc = 1;
-        if (ctx->use_rowblock && !ctx->force_wide)
-            rc = kvp_score_rowblock_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
-        if (rc == 1 && ctx->use_line && !ctx->force_wide)
-            rc = kvp_score_line_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
-        if (rc == 1 && ctx->use_chunk && !ctx->force_wide)
-            rc = kvp_score_chunk_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
-        if (rc == 1) rc = kvp_score_wide_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
-        if (rc < 0) return rc;
-        if (rc == KVP_OK) {
-            score_finalize_kernel<<<dim3((S + 3) / 4), dim3(256), 0, ctx->stream>>>(
-                S, nb_total, tiles64, ctx->d_blocksum, ctx->d_tileflag, d_cost, d_excess);
-            KVP_HIP(hipGetLastError());
-            return KVP_OK;
-        }
-    }
-    if (ctx->score_kernel != KVP_SCORE_ROWS && q.Wd <= 16 && !ctx->force_wide) {
-        // narrow rows: one lane per row, 64 token steps per tile
-        const uint32_t tiles64 = (q.N + 63) / 64;
-        if ((rc = kvp_ensure(ctx, (void **)&ctx->d_blocksum, &ctx->blocksum_cap, (size_t)S * nb_total * sizeof(double)))) return rc;
-        if ((rc = kvp_ensure(ctx, (void **)&ctx->d_tileflag, &ctx->tileflag_cap, (size_t)S * tiles64 * sizeof(uint32_t)))) return rc;
-        rc = 1;
-        if (ctx->tile_quad) rc = kvp_score_quad_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
-        if (rc == 1) rc = kvp_score_tile_launch(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
+        for (const auto &o : order)                            // the forced scorer, wherever it is in the order
+            if (rc == 1 && o.id == family) rc = o.fn(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
+        for (const auto &o : order)                            // then (or under AUTO) the first that covers the shape
+            if (rc == 1 && o.id != family && o.narrow == (q.Wd <= 16))
+                rc = o.fn(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);
         if (rc < 0) return rc;
         if (rc == KVP_OK) {
             score_finalize_kernel<<<dim3((S + 3) / 4), dim3(256), 0, ctx->stream>>>(

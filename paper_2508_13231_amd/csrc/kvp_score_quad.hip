@@ -207,7 +207,7 @@ int launch_quad(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uin
     const uint64_t nwg = (uint64_t)((S + QUAD - 1) / QUAD) * tiles;
     if (nwg > 0x7FFFFFFFull) return 1;
     dim3 grid((uint32_t)nwg), block(QUAD * 64);
-    const bool pf = WD > 1 && ctx->prefix_full, w1 = q.single_write != 0, deep = q.L % 4 == 0 && ctx->quad_stages == 4;
+    const bool pf = WD > 1 && ctx->prefix_full, w1 = q.single_write != 0, deep = q.L % 4 == 0 && ctx->score_kernel == KVP_SCORE_QUAD_4S;
 #define KVP_GO(WW, PP, NN)                                                                             \
     score_quad_kernel<WD, WW, PP, NN><<<grid, block, lds, ctx->stream>>>(q, X, S, tiles, nb_total, log2L, \
                                                                         ctx->d_blocksum, ctx->d_tileflag, counters, occ)

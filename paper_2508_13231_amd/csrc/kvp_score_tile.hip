@@ -369,15 +369,19 @@ int launch_direct(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, u
 template <int WD>
 int launch_wd(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
               uint32_t *counters, uint32_t *occ) {
-    if (ctx->tile_direct) {
-        int rd = ctx->tile_waves == 8 ? launch_direct<WD, 8>(ctx, X, S, tiles, nb_total, counters, occ)
+    // the variant asked for, if any: LDS-staged (LANES) or not (DIRECT), 4 or 8 wavefronts per workgroup
+    const int f = ctx->score_kernel;
+    const bool direct = f != KVP_SCORE_LANES && f != KVP_SCORE_LANES_8W;
+    const int waves = (f == KVP_SCORE_LANES_8W || f == KVP_SCORE_DIRECT_8W) ? 8 : 4;
+    if (direct) {
+        int rd = waves == 8 ? launch_direct<WD, 8>(ctx, X, S, tiles, nb_total, counters, occ)
                                       : launch_direct<WD, 4>(ctx, X, S, tiles, nb_total, counters, occ);
         if (rd != 1) return rd;
     }
     // more wavefronts per workgroup only when there are layers enough to keep each busy for long
-    int rc = ctx->tile_waves == 8 ? launch_wd_nw<WD, 8>(ctx, X, S, tiles, nb_total, counters, occ)
+    int rc = waves == 8 ? launch_wd_nw<WD, 8>(ctx, X, S, tiles, nb_total, counters, occ)
                                   : launch_wd_nw<WD, 4>(ctx, X, S, tiles, nb_total, counters, occ);
-    bool eight = ctx->tile_waves == 8;
+    bool eight = waves == 8;
     if (rc == 1 && eight) { rc = launch_wd_nw<WD, 4>(ctx, X, S, tiles, nb_total, counters, occ); eight = false; }
     if (rc == KVP_OK) ctx->last_kernel = eight ? KVP_SCORE_LANES_8W : KVP_SCORE_LANES;
     return rc;
