@@ -25,6 +25,11 @@ struct DevProblem {
     // [ceil(N/64)] bit i: words [i*G, (i+1)*G) are all FULL on the tile, G = 16, 64, 256 words
     const uint32_t *fullmask16, *fullmask64, *fullmask256;
     uint32_t wt[KVP_MAX_PLANES];  // plane_bytes[k] / unit
+    // weight planes for single-page look-ups: the access planes with their weights, or (fewer) the
+    // binary digit planes of the pages' read weights; pw[j] = 0 for j >= pn
+    const uint32_t *pl;           // [L][N][pn][Wd]
+    uint32_t pn;
+    uint32_t pw[KVP_MAX_PLANES];
     double unit_b, page_b, token_b;          // bytes, exact integers held in fp64
     double inv_bh, inv_bk, inv_bd, inv_min;  // reciprocals of Eqs. 3-4's bandwidths
 };

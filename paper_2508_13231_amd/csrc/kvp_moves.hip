@@ -51,20 +51,48 @@ struct PageBits {
     int au;                     // read units the page accounts for at this step (sum of its planes' weights)
 };
 
-__device__ __forceinline__ PageBits gather_page(const DevProblem &q, const uint32_t *X, uint32_t l, uint32_t n,
-                                                bool ok, uint32_t w, uint32_t b) {
+// The words that hold one (layer, page) at a lane's step: requested together, looked at later.
+// NP: weight planes looked at (>= q.pn; the surplus repeats the last plane with weight 0), so that
+// the loads are a fixed, branch-free set.
+template <int NP>
+struct PageWords {
+    uint32_t vw, pw, ww, xw, vpw, xpw, aw[NP];
+};
+
+template <int NP>
+__device__ __forceinline__ PageWords<NP> request_page(const DevProblem &q, const uint32_t *X, uint32_t l, uint32_t n,
+                                                      uint32_t w) {
     const size_t o = (size_t)n * q.Wd + w, op = (size_t)(n > 0 ? n - 1 : 0) * q.Wd + w;
     const uint32_t *Xl = X + (size_t)l * q.N * q.Wd;
-    const uint32_t vw = q.V[o], pw = q.Pm[o], ww = q.Wm[o], xw = Xl[o], vpw = q.V[op], xpw = Xl[op];
-    const uint32_t *a = q.A + ((size_t)l * q.N + n) * q.K * q.Wd + w;
+    PageWords<NP> r;
+    r.vw = q.V[o]; r.pw = q.Pm[o]; r.ww = q.Wm[o]; r.xw = Xl[o]; r.vpw = q.V[op]; r.xpw = Xl[op];
+    const uint32_t *a = q.pl + ((size_t)l * q.N + n) * q.pn * q.Wd + w;
+#pragma unroll
+    for (int j = 0; j < NP; j++) r.aw[j] = a[(size_t)min((uint32_t)j, q.pn - 1) * q.Wd];
+    return r;
+}
+
+// Makes the compiler treat the words as used here, unconditionally: without it the loads of words
+// that only matter under a condition sink into branches and wait there one after the other.
+template <int NP>
+__device__ __forceinline__ void arrive(PageWords<NP> &r) {
+    asm volatile("" : "+v"(r.vw), "+v"(r.pw), "+v"(r.ww), "+v"(r.xw), "+v"(r.vpw), "+v"(r.xpw));
+#pragma unroll
+    for (int j = 0; j < NP; j++) asm volatile("" : "+v"(r.aw[j]));
+}
+
+template <int NP>
+__device__ __forceinline__ PageBits page_bits(const DevProblem &q, const PageWords<NP> &g, uint32_t n, bool ok,
+                                              uint32_t b) {
     int au = 0;
-    for (uint32_t k = 0; k < q.K; k++) au += (int)(q.wt[k] * ((a[(size_t)k * q.Wd] >> b) & 1u));
+#pragma unroll
+    for (int j = 0; j < NP; j++) au += (int)(q.pw[j] * ((g.aw[j] >> b) & 1u));
     PageBits r;
-    r.v = ok && ((vw >> b) & 1u);
-    r.pm = ok && ((pw >> b) & 1u);
-    r.wm = ok && ((ww >> b) & 1u);
-    r.x = r.v && ((xw >> b) & 1u);
-    r.xprev = ok && n > 0 && ((vpw >> b) & 1u) && ((xpw >> b) & 1u);
+    r.v = ok && ((g.vw >> b) & 1u);
+    r.pm = ok && ((g.pw >> b) & 1u);
+    r.wm = ok && ((g.ww >> b) & 1u);
+    r.x = r.v && ((g.xw >> b) & 1u);
+    r.xprev = ok && n > 0 && ((g.vpw >> b) & 1u) && ((g.xpw >> b) & 1u);
     r.au = au;
     return r;
 }
@@ -86,16 +114,22 @@ __device__ __forceinline__ void page_effect(const PageBits &g, bool x_new, bool 
 
 // Resolve a raw move against the schedule X (with its counters and occupancy)
 // and price it.  All 64 lanes of the wavefront must call this together.
-__device__ MoveEval eval_move(const DevProblem &q, const uint32_t *X, const uint32_t *cnt, const uint32_t *occ,
-                              const kvp_move &m, int lane) {
+// `meanwhile` is run once, after the move's loads have been issued and before
+// anything waits for them: work that does not depend on the schedule (drawing the
+// next proposal) then costs no time of its own.
+template <int NP, class F>
+__device__ __forceinline__ MoveEval eval_move(const DevProblem &q, const uint32_t *X, const uint32_t *cnt,
+                                              const uint32_t *occ, const kvp_move &m, int lane, F meanwhile) {
     MoveEval R;
     R.verdict = KVP_MOVE_NULL; R.dT = 0.0; R.base = 0; R.flip1 = R.flip2 = 0; R.second = false;
     R.n = -1; R.f1 = R.f2 = R.touch1 = R.touch2 = R.xnew = false;
     R.c1 = make_uint4(0, 0, 0, 0); R.c2 = R.c1;
     const uint32_t L = q.L, N = q.N, cap = q.cap;
     if (m.op > 2 || m.layer >= L || m.page >= q.P || m.n1 >= N || m.len < 1 || m.len > KVP_MAX_LEN ||
-        m.layer2 >= L || m.page2 >= q.P)
+        m.layer2 >= L || m.page2 >= q.P) {
+        meanwhile();
         return R;
+    }
     const uint32_t l = m.layer, n1 = m.n1, len = m.len, l2 = m.layer2;
     const uint32_t wp = m.page >> 5, bp = m.page & 31, wq = m.page2 >> 5, bq = m.page2 & 31;
     const bool swap = m.op == KVP_OP_SWAP;
@@ -105,16 +139,18 @@ __device__ MoveEval eval_move(const DevProblem &q, const uint32_t *X, const uint
     int n = (int)n1 + lane;
     bool inb = n < (int)N;
     uint32_t nc = inb ? (uint32_t)n : N - 1;
-    PageBits P = gather_page(q, X, l, nc, inb, wp, bp);
-    PageBits Q = P;
+    // every load of the move, the victim's included (a SET or SHIFT looks at the page itself again)
+    const uint32_t lv = swap ? l2 : l, wv = swap ? wq : wp;
+    PageWords<NP> gp = request_page<NP>(q, X, l, nc, wp), gq = request_page<NP>(q, X, lv, nc, wv);
     uint32_t oc = occ[nc];
-    uint4 C1 = *(const uint4 *)(cnt + ((size_t)l * N + nc) * 4), C2 = C1;
-    uint32_t acc1 = q.acc[(size_t)l * N + nc], acc2 = acc1, wr = q.wr[nc];
-    if (swap) {
-        Q = gather_page(q, X, l2, nc, inb, wq, bq);
-        C2 = *(const uint4 *)(cnt + ((size_t)l2 * N + nc) * 4);
-        acc2 = q.acc[(size_t)l2 * N + nc];
-    }
+    uint4 C1 = *(const uint4 *)(cnt + ((size_t)l * N + nc) * 4), C2 = *(const uint4 *)(cnt + ((size_t)lv * N + nc) * 4);
+    uint32_t acc1 = q.acc[(size_t)l * N + nc], acc2 = q.acc[(size_t)lv * N + nc], wr = q.wr[nc];
+    meanwhile();
+    arrive(gp); arrive(gq);
+    asm volatile("" : "+v"(oc), "+v"(C1.x), "+v"(C1.y), "+v"(C1.z), "+v"(C1.w), "+v"(C2.x), "+v"(C2.y), "+v"(C2.z),
+                 "+v"(C2.w), "+v"(acc1), "+v"(acc2), "+v"(wr));
+    PageBits P = page_bits<NP>(q, gp, nc, inb, bp);
+    PageBits Q = swap ? page_bits<NP>(q, gq, nc, inb, bq) : P;
     if (!(ballot64(P.v) & 1ull)) return R;                 // the page does not exist at n1
     const uint64_t xmask = ballot64(P.x);
     const bool x1 = xmask & 1ull;
@@ -162,11 +198,13 @@ __device__ MoveEval eval_move(const DevProblem &q, const uint32_t *X, const uint
         n = base + lane;
         inb = lane < 5 && n >= 0 && n < (int)N;
         nc = inb ? (uint32_t)n : 0u;
-        P = gather_page(q, X, l, nc, inb, wp, bp);
+        gp = request_page<NP>(q, X, l, nc, wp);
         oc = occ[nc];
         C1 = *(const uint4 *)(cnt + ((size_t)l * N + nc) * 4);
         acc1 = q.acc[(size_t)l * N + nc];
         wr = q.wr[nc];
+        arrive(gp);
+        P = page_bits<NP>(q, gp, nc, inb, bp);
         if (d < 0) {
             const bool target = lane == 1 || (lane == 0 && d == -2 && it >= 2);   // steps hold a, take not(a)
             if (!a) {
@@ -228,6 +266,7 @@ __device__ MoveEval eval_move(const DevProblem &q, const uint32_t *X, const uint
 }
 
 // ---- kvp_delta_score -----------------------------------------------------------
+template <int NP>
 __global__ __launch_bounds__(256) void delta_kernel(DevProblem q, const uint32_t *__restrict__ X, uint32_t S,
                                                     const kvp_move *__restrict__ moves,
                                                     const uint32_t *__restrict__ cnt,
@@ -238,8 +277,8 @@ __global__ __launch_bounds__(256) void delta_kernel(DevProblem q, const uint32_t
     const int lane = lane_id();
     const size_t rows = (size_t)q.L * q.N;
     kvp_move m = moves[s];
-    const MoveEval R = eval_move(q, X + (size_t)s * rows * q.Wd, cnt + (size_t)s * rows * 4,
-                                 occ + (size_t)s * q.N, m, lane);
+    const MoveEval R = eval_move<NP>(q, X + (size_t)s * rows * q.Wd, cnt + (size_t)s * rows * 4,
+                                 occ + (size_t)s * q.N, m, lane, [] {});
     if (lane == 0) { delta[s] = R.dT; verdict[s] = R.verdict; }
 }
 
@@ -267,8 +306,10 @@ extern "C" int kvp_delta_score(kvp_ctx *ctx, const uint32_t *d_placements, uint3
         if ((rc = kvp_score_launch(ctx, d_placements, S, junk_cost, junk_ex, ctx->d_cnt_tmp, ctx->d_occ_tmp))) return rc;
         d_counters = ctx->d_cnt_tmp; d_occ = ctx->d_occ_tmp;
     }
-    delta_kernel<<<dim3((S + 3) / 4), dim3(256), 0, ctx->stream>>>(q, d_placements, S, d_moves, d_counters, d_occ,
-                                                                  d_delta, d_verdict);
+    const dim3 grid((S + 3) / 4), block(256);
+    if (q.pn == 1) delta_kernel<1><<<grid, block, 0, ctx->stream>>>(q, d_placements, S, d_moves, d_counters, d_occ, d_delta, d_verdict);
+    else if (q.pn <= 4) delta_kernel<4><<<grid, block, 0, ctx->stream>>>(q, d_placements, S, d_moves, d_counters, d_occ, d_delta, d_verdict);
+    else delta_kernel<KVP_MAX_PLANES><<<grid, block, 0, ctx->stream>>>(q, d_placements, S, d_moves, d_counters, d_occ, d_delta, d_verdict);
     KVP_HIP(hipGetLastError());
     return KVP_OK;
 }
@@ -305,9 +346,14 @@ __device__ __forceinline__ void draw_move(const DevProblem &q, const SAParams &s
     m.dsel = b[3] >> 30;
     const uint64_t bits = ((uint64_t)c[0] << 20) | (uint64_t)(c[1] >> 12);
     u = ((double)bits + 0.5) * (1.0 / 4503599627370496.0);
+    // The draw is complete HERE: it keeps its place among the other pinned statements (the point
+    // where a move's loads are waited for), instead of drifting behind that wait.
+    asm volatile("" : "+s"(m.op), "+s"(m.layer), "+s"(m.page), "+s"(m.n1), "+s"(m.len), "+s"(m.layer2), "+s"(m.page2),
+                 "+s"(m.dsel), "+v"(u));
 }
 
 // ---- the annealing loop: one wavefront per chain --------------------------------
+template <int NP>
 __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams sp, uint32_t *__restrict__ Xall,
                                                           uint32_t *__restrict__ cnt_all,
                                                           uint32_t *__restrict__ occ_all,
@@ -328,10 +374,11 @@ __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams
         // C0 = mean(dT | dT > 0) / (-ln p0) over proposals that are not applied
         double sum = 0.0;
         uint32_t k = 0;
+        kvp_move m, mn; double u, un;
+        draw_move(q, sp, chain, 0, 8, m, u);
         for (uint64_t j = 0; j < CALIB_MOVES; j++) {
-            kvp_move m; double u;
-            draw_move(q, sp, chain, j, 8, m, u);
-            const MoveEval R = eval_move(q, X, cnt, occ, m, lane);
+            const MoveEval R = eval_move<NP>(q, X, cnt, occ, m, lane, [&] { draw_move(q, sp, chain, j + 1, 8, mn, un); });
+            m = mn;
             if (R.verdict != KVP_MOVE_NULL && R.dT > 0.0) { sum = sum + R.dT; k++; }
         }
         st.c0 = k ? (sum / (double)k) / sp.neg_ln_p0 : 0.0;
@@ -339,13 +386,17 @@ __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams
         st.level = 0;
     }
 
+    // The proposal after the current one is drawn while the current one's loads are in flight:
+    // proposals depend on the counters (move number, chain, seed) only, never on the schedule.
+    kvp_move m_next; double u_next;
+    draw_move(q, sp, chain, move_begin, 0, m_next, u_next);
     for (uint64_t mi = move_begin; mi < move_end; mi++) {
         uint64_t lvl = mi / sp.mpl;
         if (lvl > sp.n_levels - 1) lvl = sp.n_levels - 1;
         while (st.level < lvl) { st.c = st.c * sp.alpha; st.level++; }      // geometric cooling
-        kvp_move m; double u;
-        draw_move(q, sp, chain, mi, 0, m, u);
-        const MoveEval R = eval_move(q, X, cnt, occ, m, lane);
+        const kvp_move m = m_next;
+        const double u = u_next;
+        const MoveEval R = eval_move<NP>(q, X, cnt, occ, m, lane, [&] { draw_move(q, sp, chain, mi + 1, 0, m_next, u_next); });
         st.moves_done++;
         if (R.verdict == KVP_MOVE_NULL) { st.null_moves++; continue; }
         if (R.verdict == KVP_MOVE_CLIPPED) st.clipped++;
@@ -548,15 +599,25 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
     uint64_t m0 = ctx->moves_done;
     const uint64_t m_end = m0 + p->moves;
     bool first = ctx->moves_done == 0;
+    auto launch = [&](uint64_t b, uint64_t e, int calibrate) {
+        const dim3 grid(C), block(KVP_WAVE);
+        if (q.pn == 1)
+            anneal_kernel<1><<<grid, block, 0, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
+                                                             ctx->d_log, ctx->log_cap, b, e, calibrate);
+        else if (q.pn <= 4)
+            anneal_kernel<4><<<grid, block, 0, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
+                                                             ctx->d_log, ctx->log_cap, b, e, calibrate);
+        else
+            anneal_kernel<KVP_MAX_PLANES><<<grid, block, 0, ctx->stream>>>(
+                q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state, ctx->d_log, ctx->log_cap, b, e, calibrate);
+    };
     if (p->moves == 0 && first) {
-        anneal_kernel<<<dim3(C), dim3(KVP_WAVE), 0, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
-                                                                 ctx->d_log, ctx->log_cap, 0, 0, 1);
+        launch(0, 0, 1);
         KVP_HIP(hipGetLastError());
     }
     while (m0 < m_end) {
         const uint64_t m1 = m0 + chunk < m_end ? m0 + chunk : m_end;
-        anneal_kernel<<<dim3(C), dim3(KVP_WAVE), 0, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
-                                                                 ctx->d_log, ctx->log_cap, m0, m1, first ? 1 : 0);
+        launch(m0, m1, first ? 1 : 0);
         KVP_HIP(hipGetLastError());
         first = false;
         m0 = m1;

@@ -284,6 +284,8 @@ int kvp_blocksum_from_t_launch(kvp_ctx *ctx, uint32_t S, uint32_t nb_total);
 int kvp_bitslice_build(kvp_ctx *ctx) {
     DevProblem &q = ctx->dp;
     ctx->aw = nullptr; ctx->kb = 0;
+    q.pl = q.A; q.pn = q.K;
+    for (uint32_t k = 0; k < KVP_MAX_PLANES; k++) q.pw[k] = k < q.K ? q.wt[k] : 0;
     uint64_t sum = 0;
     for (uint32_t k = 0; k < q.K; k++) sum += q.wt[k];
     uint32_t kb = 0;
@@ -297,6 +299,8 @@ int kvp_bitslice_build(kvp_ctx *ctx) {
     KVP_HIP(hipGetLastError());
     KVP_HIP(hipStreamSynchronize(ctx->stream));
     ctx->aw = ctx->d_aw; ctx->kb = kb;
+    q.pl = ctx->d_aw; q.pn = kb;
+    for (uint32_t k = 0; k < KVP_MAX_PLANES; k++) q.pw[k] = k < kb ? 1u << k : 0;
     return KVP_OK;
 }
 
