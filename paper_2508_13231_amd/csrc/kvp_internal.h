@@ -116,10 +116,35 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
 }
 // The 64-wide summation tree of the total latency: fold the upper half onto the
 // lower half (32, 16, ..., 1).  Every lane ends with the same bits because
-// a + b == b + a in IEEE arithmetic.
+// a + b == b + a in IEEE arithmetic.  All 64 lanes must be active.
+// Folds 32 and 16 use the gfx950 half / row swaps (v_permlane32_swap with both operands v leaves
+// (low half, low half) and (high half, high half): their sum is v[i] + v[i ^ 32] in every lane;
+// v_permlane16_swap does the same with the 16-lane rows).  Folds 8..1 rotate within rows of 16:
+// after the folds before it the values repeat with period 2k, so the lane k places away holds
+// the same bits as lane i ^ k.  No LDS round trips, unlike a cross-lane shuffle.
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
 __device__ __forceinline__ double wave_tree_sum_f64(double v) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v = v + __shfl_xor(v, o, KVP_WAVE);
+    {
+        const uint32_t lo = (uint32_t)__double2loint(v), hi = (uint32_t)__double2hiint(v);
+        const auto a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+        const auto b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+        v = __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+    }
+    {
+        const uint32_t lo = (uint32_t)__double2loint(v), hi = (uint32_t)__double2hiint(v);
+        const auto a = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+        const auto b = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+        v = __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+    }
+    v = v + dpp_f64<0x128>(v);   // row_ror:8
+    v = v + dpp_f64<0x124>(v);   // row_ror:4
+    v = v + dpp_f64<0x122>(v);   // row_ror:2
+    v = v + dpp_f64<0x121>(v);   // row_ror:1
     return v;
 }
 
