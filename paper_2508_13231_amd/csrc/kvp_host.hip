@@ -171,6 +171,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     q.unit_b = (double)unit; q.page_b = (double)pr->page_bytes; q.token_b = (double)pr->token_bytes;
     q.inv_bh = 1.0 / pr->bw_hbm; q.inv_bk = 1.0 / pr->bw_link; q.inv_bd = 1.0 / pr->bw_dram;
     q.inv_min = 1.0 / (pr->bw_link < pr->bw_dram ? pr->bw_link : pr->bw_dram);
+    q.dram_bound = q.inv_bd >= q.inv_bk;
     {   // class of every mask word over each tile of 64 steps, and groups of words that are all FULL
         uint32_t *cls = (uint32_t *)calloc(4 * (T64 ? T64 : 1), 4);
         uint8_t *fullw = (uint8_t *)malloc((size_t)Wd);

@@ -32,6 +32,7 @@ struct DevProblem {
     uint32_t pw[KVP_MAX_PLANES];
     double unit_b, page_b, token_b;          // bytes, exact integers held in fp64
     double inv_bh, inv_bk, inv_bd, inv_min;  // reciprocals of Eqs. 3-4's bandwidths
+    uint32_t dram_bound;          // the DRAM channels are no faster than the link (inv_bd >= inv_bk)
 };
 
 // Class of a mask word over a tile of 64 token steps (and the step before it):
@@ -148,6 +149,29 @@ __device__ __forceinline__ double wave_tree_sum_f64(double v) {
     return v;
 }
 
+// v[i] + v[i ^ m] in every lane, m a power of two (the same for the whole wavefront), all lanes
+// active: one fold of the summation tree across lanes, without LDS where the hardware allows.
+__device__ __forceinline__ double fold_xor_f64(double v, uint32_t m) {
+    switch (m) {
+        case 1: return v + dpp_f64<0xB1>(v);    // quad_perm [1,0,3,2]
+        case 2: return v + dpp_f64<0x4E>(v);    // quad_perm [2,3,0,1]
+        case 8: return v + dpp_f64<0x128>(v);   // row_ror:8 is i ^ 8 within a row of 16
+        case 16: {
+            const uint32_t lo = (uint32_t)__double2loint(v), hi = (uint32_t)__double2hiint(v);
+            const auto a = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+            const auto b = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+            return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+        }
+        case 32: {
+            const uint32_t lo = (uint32_t)__double2loint(v), hi = (uint32_t)__double2hiint(v);
+            const auto a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+            const auto b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+            return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+        }
+        default: return v + __shfl_xor(v, (int)m, KVP_WAVE);
+    }
+}
+
 // Step latency, Eqs. 2-4, from the step's counters.  hr_u: read units served by
 // HBM; hw: written pages in HBM; mi/mo: pages migrated in/out; acc_u, wr: the
 // step's totals.  Every product below is an integer < 2^53, hence exact; the
@@ -161,11 +185,17 @@ __device__ __forceinline__ double step_time(const DevProblem &q, uint32_t hr_u, 
     double mi_b = (double)mi * q.page_b;
     double mo_b = (double)mo * q.page_b;
     double t_h = (((hr_b + hw_b) + mi_b) + mo_b) * q.inv_bh;                 // Eq. 3
-    double link_out = (ew_b + mo_b) * q.inv_bk;
-    double link_in = mi_b * q.inv_bk;
     double chan = ((ew_b + mi_b) + mo_b) * q.inv_bd;
-    // all operands are finite and >= +0: the hardware maximum picks the same value as a comparison
-    double m = __builtin_fmax(__builtin_fmax(link_out, link_in), chan);
+    double m = chan;
+    if (!q.dram_bound) {
+        // Otherwise the channel term is the largest of the three as it stands: its byte count (an
+        // exact integer) is no smaller than the other two, its factor no smaller than theirs, and
+        // rounding a product is monotonic.
+        double link_out = (ew_b + mo_b) * q.inv_bk;
+        double link_in = mi_b * q.inv_bk;
+        // all operands are finite and >= +0: the hardware maximum picks the same value as a comparison
+        m = __builtin_fmax(__builtin_fmax(link_out, link_in), chan);
+    }
     double t_e = er_b * q.inv_min + m;                                       // Eq. 4
     return __builtin_fmax(t_h, t_e);                                         // Eq. 2
 }

@@ -158,7 +158,7 @@ __global__ __launch_bounds__(QUAD * 64) void score_quad_kernel(
         if (counters && has_s && active)
             *(uint4 *)(counters + (((size_t)s * L + l) * N + n) * 4) = make_uint4(hr, hw, mi, mo);
         // folds of the summation tree that join the steps of one block (lanes)
-        for (uint32_t m = (64u >> log2L) >> 1; m >= 1; m >>= 1) t = t + __shfl_xor(t, (int)m, KVP_WAVE);
+        for (uint32_t m = (64u >> log2L) >> 1; m >= 1; m >>= 1) t = fold_xor_f64(t, m);
         // folds that join layers: binary counter over the bit-reversed visiting order
         double carry = t;
         bool parked = false;

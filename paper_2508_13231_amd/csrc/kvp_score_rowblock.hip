@@ -232,7 +232,7 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
             *(uint4 *)(counters + (((size_t)s * L + l) * N + n) * 4) = make_uint4(hr, hw, mi, mo);
         if (POW2) {
             // folds of the summation tree that join the steps of one block (steps are two lanes apart)
-            for (uint32_t m = (64u >> log2L) >> 1; m >= 1; m >>= 1) t = t + __shfl_xor(t, (int)(2 * m), KVP_WAVE);
+            for (uint32_t m = (64u >> log2L) >> 1; m >= 1; m >>= 1) t = fold_xor_f64(t, 2 * m);
             // folds that join layers: binary counter over the bit-reversed visiting order
             double carry = t;
             bool parked = false;

@@ -33,6 +33,7 @@ def _cases():
     yield "rand-wide", W.random_trace(12, L=5, N=21, P=2250, K=1)          # rows wider than a wavefront
     yield "rand-weights", W.random_trace(13, L=2, N=50, P=100, K=3,
                                          plane_bytes=[4096, 8192, 53248])  # unequal plane weights
+    yield "rand-fastdram", W.random_trace(24, L=4, N=70, P=200, K=1, bw=(4e12, 300e9, 800e9))   # link slower than DRAM
     yield "one-step", W.random_trace(14, L=1, N=1, P=33, K=1)
     yield "rand-tiles", W.random_trace(15, L=6, N=150, P=180, K=2)         # 3 tiles of 64 steps, ragged tail
     yield "rand-512", W.random_trace(16, L=3, N=70, P=512, K=1)            # 16 words per row, even stride
@@ -128,7 +129,7 @@ def test_score_every_schedule_of_a_micro_instance(G):
 
 
 @pytest.mark.parametrize("name,tr", [c for c in CASES if c[0] in
-                                     ("tiny", "table1", "llama8b/4", "serving/16", "gqa70b/16", "rand-odd",
+                                     ("tiny", "table1", "llama8b/4", "serving/16", "gqa70b/16", "rand-odd", "rand-fastdram",
                                       "rand-weights")],
                          ids=lambda v: v if isinstance(v, str) else "")
 @pytest.mark.parametrize("given", [True, False])
