@@ -27,9 +27,9 @@ import numpy as np
 HBM_PEAK = 8.0e12          # MI355X HBM3E, bytes/s
 GIB = 1 << 30
 # HBM bytes per kvp_score launch on the default workload with the default kernel, from rocprofv3
-# FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB device copy (profiles/kvp_score_llama8b.md).
+# FETCH_SIZE / WRITE_SIZE scaled by a 1 GiB device copy (profiles/kvp_bench_llama8b.md).
 # Any other workload, batch size or kernel choice reports null.
-MEASURED_TRAFFIC = {("llama8b", 1.0, 14564): 4.502e9}
+MEASURED_TRAFFIC = {("llama8b", 1.0, 14564): 4.513e9}
 
 
 def algorithmic_bytes(tr, S):
