@@ -121,7 +121,7 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
         const uint32_t vi = min((uint32_t)lane + 64u * jv, (RR + 1) * PPR - 1);
         const uint32_t row = vi / PPR, part = vi - row * PPR;
         const uint32_t w0 = min(4 * part, Wd - 4);                     // a row's last vector ends at the row's end
-        xrel[jv] = row * Wd + w0;
+        xrel[jv] = 4 * (row * Wd + w0);                                // bytes from the first row of a pass
         xlds[jv] = row * RS + w0;
     }
 #pragma unroll
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
         const uint32_t k = ti / (RR * PPR), rem = ti - k * RR * PPR;
         const uint32_t row = rem / PPR, part = rem - row * PPR;
         const uint32_t w0 = min(4 * part, Wd - 4);
-        trel[jt] = (row * KB + k) * Wd + w0;
+        trel[jt] = 4 * ((row * KB + k) * Wd + w0);
         tlds[jt] = k * TPL + row * RS + w0;
     }
     // Pass p of layer l starts at word ((l*N + n0 + 32p) - 1) * Wd of the schedule: the step before
@@ -143,17 +143,33 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
     uint32_t acc_nx = 0;                                               // read units of the lane's step, next layer
     r4u tr[TV];
     auto layer_of = [&](uint32_t i) { return POW2 ? (__brev(i) >> (32 - log2L)) : i; };
+    // Addresses are a wavefront-uniform base plus a 32-bit byte offset per lane (the host checks
+    // that a schedule and the digit planes stay below 4 GiB).  A pass whose 33 rows all lie inside the
+    // schedule (no step before step 0, no steps past the trace) needs no clamping.
+    const char *Xs = (const char *)(X + (size_t)sc * sched_words);
+    const bool edge_tile = rows < 64;
     auto issue_x = [&](Stage &st, uint32_t p, uint32_t l) __attribute__((always_inline)) {
-        const uint32_t *Xs = X + (size_t)sc * sched_words;
-        const int before = (int)((l * N + n0 + RR * p) * Wd) - (int)Wd;   // word of the step before the pass; -Wd at step 0
-        const int hi = (int)sched_words - 4;
+        const int before = 4 * ((int)((l * N + n0 + RR * p) * Wd) - (int)Wd);   // byte of the step before the pass; < 0 at step 0
+        if (before >= 0 && !edge_tile) {
 #pragma unroll
-        for (int jv = 0; jv < XV; jv++) st.x[jv] = *(const r4u *)(Xs + min(max(before + (int)xrel[jv], 0), hi));
+            for (int jv = 0; jv < XV; jv++) st.x[jv] = *(const r4u *)(Xs + ((uint32_t)before + xrel[jv]));
+        } else {
+            const int hi = 4 * ((int)sched_words - 4);
+#pragma unroll
+            for (int jv = 0; jv < XV; jv++) st.x[jv] = *(const r4u *)(Xs + (uint32_t)min(max(before + (int)xrel[jv], 0), hi));
+        }
     };
     auto issue_t = [&](uint32_t p, uint32_t l) __attribute__((always_inline)) {
-        const uint32_t first = (l * N + n0 + RR * p) * KB * Wd, hi = L * N * KB * Wd - 4;
+        const uint32_t first = 4 * (l * N + n0 + RR * p) * KB * Wd;
+        const char *Ab = (const char *)Aw;
+        if (!edge_tile) {
 #pragma unroll
-        for (int jt = 0; jt < TV; jt++) tr[jt] = *(const r4u *)(Aw + min(first + trel[jt], hi));
+            for (int jt = 0; jt < TV; jt++) tr[jt] = *(const r4u *)(Ab + (first + trel[jt]));
+        } else {
+            const uint32_t hi = 4 * (L * N * KB * Wd - 4);
+#pragma unroll
+            for (int jt = 0; jt < TV; jt++) tr[jt] = *(const r4u *)(Ab + min(first + trel[jt], hi));
+        }
     };
     auto commit_t = [&](uint32_t slot) __attribute__((always_inline)) {
         uint32_t *dst = tbuf + slot * KB * TPL;
@@ -315,8 +331,8 @@ int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint3
     const uint32_t need = ((RR + 1) * PPR + 63) / 64;
     const int xv = need <= 5 ? 5 : 9;
     if (need > 9) return 1;
-    if ((size_t)q.L * q.N * KB * q.Wd >= (1ull << 31)) return 1;      // 32-bit word offsets inside the digit planes
-    if ((size_t)q.L * q.N * q.Wd >= (1ull << 31)) return 1;           // and inside a schedule
+    if ((size_t)q.L * q.N * KB * q.Wd >= (1ull << 29)) return 1;      // 32-bit (signed) byte offsets inside the digit planes
+    if ((size_t)q.L * q.N * q.Wd >= (1ull << 29)) return 1;           // and inside a schedule
     uint32_t log2L = 0;
     while ((1u << log2L) < q.L) log2L++;
     const bool pow2 = q.L >= 2 && q.L <= 64 && (1u << log2L) == q.L;
