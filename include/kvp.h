@@ -208,6 +208,26 @@ int kvp_set_score_kernel(kvp_ctx *ctx, int which);
  * not cover the trace's shape is replaced by one that does: this tells which. */
 int kvp_score_kernel_used(const kvp_ctx *ctx);
 
+/* Two placements that need no search, to start one from or to compare it with
+ * (the evaluation section of the paper sets its search against a static and a
+ * reactive least-recently-used placement; these are their counterparts on this
+ * problem's terms: a pool of cap_pages shared by the layers, whole pages, no
+ * migration cost model of their own).
+ *   KVP_BASELINE_STATIC:  the cap_pages (layer, page) pairs read most often over
+ *     the whole trace (accesses summed over the planes) are in HBM at every step
+ *     at which they exist; nothing ever migrates.
+ *   KVP_BASELINE_RECENCY: at step n the pool holds the cap_pages existing pairs
+ *     read most recently before n (never read: oldest); a page that stops
+ *     persisting forgets its history.
+ * Ties go to the lower l * n_pages + p in both.  d_placement: DEVICE, one
+ * schedule [L][N][Wd] uint32, written in full; the caller owns it.  The result
+ * never exceeds the capacity.  Runs on the context's stream.
+ * Errors: KVP_EINVAL (null or misaligned pointer, unknown kind), KVP_ENOTRACE,
+ * KVP_ESHAPE (more than 32767 steps, or steps x planes above 32767, for the
+ * histogram of the selection), KVP_ENOMEM, KVP_EHIP. */
+enum { KVP_BASELINE_STATIC = 0, KVP_BASELINE_RECENCY = 1 };
+int kvp_baseline(kvp_ctx *ctx, int kind, uint32_t *d_placement);
+
 const char *kvp_strerror(int code);
 
 /* After a KVP_EHIP / KVP_ENOMEM return on this thread: the hipError_t value of

@@ -27,7 +27,7 @@ KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2
 
 EXPORTS = ["kvp_create", "kvp_destroy", "kvp_trace_upload", "kvp_score", "kvp_delta_score", "kvp_anneal",
            "kvp_best", "kvp_chain_placement", "kvp_chain_stats", "kvp_plane_unit", "kvp_strerror", "kvp_last_hip_error",
-           "kvp_set_score_kernel", "kvp_score_kernel_used"]
+           "kvp_set_score_kernel", "kvp_score_kernel_used", "kvp_baseline"]
 
 
 class kvp_problem(C.Structure):
@@ -99,6 +99,8 @@ def lib():
         L.kvp_strerror.argtypes = [i32]
         L.kvp_set_score_kernel.restype = i32
         L.kvp_set_score_kernel.argtypes = [vp, i32]
+        L.kvp_baseline.restype = i32
+        L.kvp_baseline.argtypes = [vp, i32, vp]
         L.kvp_score_kernel_used.restype = i32
         L.kvp_score_kernel_used.argtypes = [vp]
         L.kvp_last_hip_error.restype = i32
@@ -203,6 +205,14 @@ def kvp_chain_stats(ctx, n_chains):
 
 def kvp_set_score_kernel(ctx, which: int):
     _check(lib().kvp_set_score_kernel(ctx, int(which)), "kvp_set_score_kernel")
+
+
+KVP_BASELINE_STATIC, KVP_BASELINE_RECENCY = 0, 1
+
+
+def kvp_baseline(ctx, kind: int, d_placement):
+    """One schedule [L][N][Wd] int32 (device tensor), written in full."""
+    _check(lib().kvp_baseline(ctx, int(kind), _dptr(d_placement)), "kvp_baseline")
 
 
 def kvp_score_kernel_used(ctx) -> int:

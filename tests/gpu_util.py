@@ -59,6 +59,15 @@ class Gpu:
         out += [d_cnt.cpu().numpy().view(np.uint32), d_occ.cpu().numpy().view(np.uint32)] if counters else [None, None]
         return out
 
+    def baseline(self, kind):
+        """Schedule of kvp_baseline as bool [L][N][P]."""
+        torch = self.torch
+        tr = self.tr
+        d = torch.full((tr.L, tr.N, tr.n_words), -1, dtype=torch.int32, device=self.dev)
+        K.kvp_baseline(self.ctx, kind, d)
+        torch.cuda.synchronize()
+        return self.unpack(d.cpu().numpy().view(np.uint32))
+
     def kernel_used(self):
         return K.kvp_score_kernel_used(self.ctx)
 

@@ -297,6 +297,44 @@ def test_error_paths_reach_no_kernel(G):
         K.kvp_destroy(ctx)
 
 
+BASELINE_CASES = ("tiny", "table1", "llama8b/4", "longctx/8", "serving/16", "gqa70b/16", "rand-odd", "rand-weights",
+                  "one-step", "rand-tiles", "rand-512", "rand-w40", "dec-w21-L3", "dec-w38-k3")
+
+
+@pytest.mark.parametrize("name,tr", [c for c in CASES if c[0] in BASELINE_CASES], ids=lambda v: v if isinstance(v, str) else "")
+@pytest.mark.parametrize("kind", ["static", "recency"])
+def test_baseline_placements_match_oracle(G, name, tr, kind):
+    """Bit for bit, and for the capacities at which the selection has nothing to decide."""
+    import dataclasses
+    import paper_2508_13231_amd as K
+    peak = int(tr.alive.sum(axis=1).max()) * tr.L
+    for cap in (tr.cap_pages, 0, 1, peak - 1, peak, tr.L * tr.P + 5):
+        t2 = dataclasses.replace(tr, cap_pages=max(0, cap))
+        want = O.init_static_frequency(t2) if kind == "static" else O.init_recency(t2)
+        with G(t2) as g:
+            got = g.baseline(K.KVP_BASELINE_STATIC if kind == "static" else K.KVP_BASELINE_RECENCY)
+        assert got.shape == want.shape and (got == want.astype(bool)).all(), (name, kind, cap)
+        assert int(got.sum(axis=(0, 2)).max()) <= t2.cap_pages
+
+
+def test_anneal_from_a_baseline_start_is_no_worse_than_the_baseline(G):
+    import torch
+    import paper_2508_13231_amd as K
+    tr = W.config("llama8b", 0.25)
+    q = O.Problem(tr)
+    with G(tr) as g:
+        for kind in (K.KVP_BASELINE_STATIC, K.KVP_BASELINE_RECENCY):
+            d = torch.empty((tr.L, tr.N, tr.n_words), dtype=torch.int32, device=g.dev)
+            K.kvp_baseline(g.ctx, kind, d)
+            start = O.score(q, g.unpack(d.cpu().numpy().view(np.uint32)))
+            assert start.excess == 0
+            p = K.make_anneal_params(8, 4000, seed=5, init_mode=K.KVP_INIT_BROADCAST)
+            K.kvp_anneal(g.ctx, p, d)
+            cost, chain, X, _ = K.kvp_best(g.ctx, (tr.L, tr.N, tr.n_words))
+            r = O.score(q, g.unpack(X.view(np.uint32)))
+            assert r.cost == cost and r.excess == 0 and cost <= start.cost
+
+
 def _full_shape(name):
     """Trace and batch size of a benchmark config.  Config 1 is taken whole (the benchmark's own launch);
     the two configs whose trace takes minutes to draw keep their layers, row width and planes but
