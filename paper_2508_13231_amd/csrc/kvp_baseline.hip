@@ -40,14 +40,22 @@ __device__ __forceinline__ void block_select(uint32_t G, uint32_t nbins, uint64_
     const uint32_t c_lo = min(wave * cpw, nchunks), c_hi = min(c_lo + cpw, nchunks);
     for (uint32_t k = tid; k < nbins; k += BT) hist[k] = 0;
     __syncthreads();
-    // keys into the histogram; the two most crowded bins (0 and the last) are counted with ballots
+    // keys into the histogram; the two most crowded bins (0 and the last) are counted with ballots.
+    // Four chunks at a time, so that four sets of loads are in flight per wavefront.
     uint32_t n0 = 0, nl = 0;
-    for (uint32_t c = c_lo; c < c_hi; c++) {
-        const uint32_t g = c * 64 + lane;
-        const uint32_t k = g < G ? first_key(g) : NOT_A_CANDIDATE;
-        n0 += __popcll(__ballot(k == 0));
-        nl += __popcll(__ballot(k == nbins - 1 && k != 0));
-        if (k != NOT_A_CANDIDATE && k != 0 && k != nbins - 1) atomicAdd(&hist[k], 1u);
+    for (uint32_t c = c_lo; c < c_hi; c += 4) {
+        uint32_t k[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const uint32_t g = (c + u) * 64 + lane;
+            k[u] = (c + u < c_hi && g < G) ? first_key(g) : NOT_A_CANDIDATE;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            n0 += __popcll(__ballot(k[u] == 0));
+            nl += __popcll(__ballot(k[u] == nbins - 1 && k[u] != 0));
+            if (k[u] != NOT_A_CANDIDATE && k[u] != 0 && k[u] != nbins - 1) atomicAdd(&hist[k[u]], 1u);
+        }
     }
     if (lane == 0) {
         if (n0) atomicAdd(&hist[0], n0);
@@ -85,25 +93,39 @@ __device__ __forceinline__ void block_select(uint32_t G, uint32_t nbins, uint64_
     // items at the threshold, counted per wavefront, then numbered in index order
     uint32_t ties = 0;
     if (!all)
-        for (uint32_t c = c_lo; c < c_hi; c++) {
-            const uint32_t g = c * 64 + lane;
-            const uint32_t k = g < G ? key(g) : NOT_A_CANDIDATE;
-            ties += __popcll(__ballot(k == T));
+        for (uint32_t c = c_lo; c < c_hi; c += 4) {
+            uint32_t k[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const uint32_t g = (c + u) * 64 + lane;
+                k[u] = (c + u < c_hi && g < G) ? key(g) : NOT_A_CANDIDATE;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++) ties += __popcll(__ballot(k[u] == T));
         }
     if (lane == 0) sh.wave_ties[wave] = ties;
     __syncthreads();
     uint32_t rank0 = 0;
     for (uint32_t w = 0; w < wave; w++) rank0 += sh.wave_ties[w];
-    for (uint32_t c = c_lo; c < c_hi; c++) {
-        const uint32_t g = c * 64 + lane;
-        const uint32_t k = g < G ? key(g) : NOT_A_CANDIDATE;
-        const uint64_t tie = __ballot(k == T);
-        const uint32_t rank = rank0 + __popcll(tie & ((1ull << lane) - 1ull));
-        const bool chosen = k != NOT_A_CANDIDATE && (all || k > T || (k == T && rank < r));
-        rank0 += __popcll(tie);
-        const uint64_t bits = __ballot(chosen);
-        if (lane == 0) emit(2 * c, (uint32_t)bits);
-        if (lane == 32 && (2 * c + 1) * 32 < G) emit(2 * c + 1, (uint32_t)(bits >> 32));
+    for (uint32_t c0 = c_lo; c0 < c_hi; c0 += 4) {
+        uint32_t kk[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const uint32_t g = (c0 + u) * 64 + lane;
+            kk[u] = (c0 + u < c_hi && g < G) ? key(g) : NOT_A_CANDIDATE;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const uint32_t c = c0 + u, k = kk[u];
+            if (c >= c_hi) break;                                      // the same for the whole wavefront
+            const uint64_t tie = __ballot(k == T);
+            const uint32_t rank = rank0 + __popcll(tie & ((1ull << lane) - 1ull));
+            const bool chosen = k != NOT_A_CANDIDATE && (all || k > T || (k == T && rank < r));
+            rank0 += __popcll(tie);
+            const uint64_t bits = __ballot(chosen);
+            if (lane == 0) emit(2 * c, (uint32_t)bits);
+            if (lane == 32 && (2 * c + 1) * 32 < G) emit(2 * c + 1, (uint32_t)(bits >> 32));
+        }
     }
     __syncthreads();
 }
@@ -154,8 +176,10 @@ __global__ __launch_bounds__(BT) void recency_kernel(DevProblem q, uint64_t cap,
     for (uint32_t n = 0; n < q.N; n++) {
         auto key = [&](uint32_t g) {
             const uint32_t w = (g >> 5) % q.Wd, b = g & 31u;
-            const bool alive = (q.V[(size_t)n * q.Wd + w] >> b) & 1u;  // dead bits of the last word are never alive
-            return alive ? (uint32_t)(last[g] + 1) : NOT_A_CANDIDATE;
+            const uint32_t vw = q.V[(size_t)n * q.Wd + w];             // dead bits of the last word are never alive
+            int32_t lv = last[g];
+            asm volatile("" : "+v"(lv));                               // loaded whether alive or not: no branch, loads overlap
+            return ((vw >> b) & 1u) ? (uint32_t)(lv + 1) : NOT_A_CANDIDATE;
         };
         auto first_key = [&](uint32_t g) {
             if (n > 0) {
