@@ -55,6 +55,19 @@ class _SAState(C.Structure):
                 ("uphill_seen", C.c_uint64)]
 
 
+class _WRParams(C.Structure):
+    _fields_ = [("w_max", C.c_uint32), ("w0", C.c_uint32), ("r10_0", C.c_uint32), ("n_levels", C.c_uint32),
+                ("seed", C.c_uint64), ("total_moves", C.c_uint64), ("p0", C.c_double), ("alpha", C.c_double),
+                ("op_prob", C.c_double * 3), ("stop_rel", C.c_double), ("c_min_frac", C.c_double)]
+
+
+class WRResult(C.Structure):
+    _fields_ = [("best_w", C.c_uint32), ("best_r10", C.c_uint32), ("cur_w", C.c_uint32), ("cur_r10", C.c_uint32),
+                ("levels_done", C.c_uint32), ("stop_reason", C.c_uint32), ("proposals", C.c_uint64),
+                ("accepted", C.c_uint64), ("out_of_range", C.c_uint64), ("evaluated", C.c_uint64),
+                ("best_T", C.c_double), ("cur_T", C.c_double), ("c0", C.c_double)]
+
+
 _lib = None
 
 
@@ -84,6 +97,9 @@ def lib():
         L.orc_anneal_chain.restype = C.c_int
         L.orc_anneal_chain.argtypes = [C.POINTER(_Problem), C.POINTER(_SAParams), C.c_uint32, C.c_void_p,
                                        C.c_void_p, C.POINTER(_SAState)]
+        L.orc_wr_policy.argtypes = [C.POINTER(_Problem), C.c_uint32, C.c_uint32, C.c_void_p]
+        L.orc_wr_search.restype = C.c_uint64
+        L.orc_wr_search.argtypes = [C.POINTER(_Problem), C.POINTER(_WRParams), C.c_void_p, C.POINTER(WRResult)]
         _lib = L
     return _lib
 
@@ -225,6 +241,28 @@ def init_recency(tr) -> np.ndarray:
     X = np.zeros(q.shape, dtype=np.uint8)
     lib().orc_init_recency(C.byref(q.c), X.ctypes.data)
     return X
+
+
+def wr_policy(tr, W: int, r10: int) -> np.ndarray:
+    """Schedule of the (W, R = r10/10) look-ahead policy, bool bytes [L][N][P]."""
+    q = _problem(tr)
+    X = np.zeros(q.shape, dtype=np.uint8)
+    lib().orc_wr_policy(C.byref(q.c), int(W), int(r10), X.ctypes.data)
+    return X
+
+
+def wr_search(tr, w_max, total_moves, n_levels=20, seed=0, w0=1, r10_0=5, p0=0.8, alpha=0.9,
+              op_prob=(0.4, 0.4, 0.2), stop_rel=1e-3, c_min_frac=1e-3, table=None):
+    """The annealing over (W, R).  Returns (WRResult, table [w_max][11] of the costs evaluated, -1 elsewhere)."""
+    q = _problem(tr)
+    sp = _WRParams(int(w_max), int(w0), int(r10_0), int(n_levels), int(seed), int(total_moves), float(p0),
+                   float(alpha), (C.c_double * 3)(*op_prob), float(stop_rel), float(c_min_frac))
+    if table is None:
+        table = np.full((int(w_max), 11), -1.0)
+    res = WRResult()
+    assert table.dtype == np.float64 and table.shape == (int(w_max), 11) and table.flags.c_contiguous
+    lib().orc_wr_search(C.byref(q.c), C.byref(sp), table.ctypes.data, C.byref(res))
+    return res, table
 
 
 def brute_force(tr):

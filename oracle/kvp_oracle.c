@@ -13,6 +13,11 @@
  * this project's own design (the paper anneals two policy scalars), so its
  * effectiveness is "parity unpinned" by the paper: it is pinned only by
  * exhaustive search on tiny instances and by its invariants.
+ * Part (iii), at the end, is the paper's own search: a look-ahead policy with the
+ * two scalars W and R, and the annealing over them.  The paper states the
+ * policy in two sentences; the reading taken is written out step by step above
+ * orc_wr_policy and pinned by hand-worked instances ("parity unpinned" by the
+ * paper beyond that: it prints no worked example).
  *
  * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC
  */
@@ -555,4 +560,177 @@ int orc_anneal_chain(const orc_problem *q, const orc_sa_params *sp, uint32_t cha
     }
     free(tcur); free(occ); free(f1); free(f2);
     return 0;
+}
+
+/* ---- the (W, R) look-ahead policy and its search (Sec. III-B) ---------------
+ * The paper anneals two scalars of a placement policy: W, how many coming
+ * token steps are looked at, and R, the share of the pages "qualified for
+ * migration" that really migrate.  It gives the policy in two sentences; this
+ * is the reading taken here, step by step, once per token step n (one decision
+ * for all layers, on the shared pool of cap_pages):
+ *   1. pages that do not hold the same data as one step earlier leave the pool
+ *      (a page born at n starts outside, like every page at n = 0);
+ *   2. collect the existing pages that are read in steps n .. n+W-1, with their
+ *      read frequency f there (summed over the planes);
+ *   3. rank them, f descending, ties to the lower l*P+p ("priority queue"); the
+ *      first cap_pages of the ranking are the wanted set;
+ *   4. qualified for migration: the wanted pages that are not in the pool, in
+ *      rank order; the first m = round(R * their number) of them migrate in,
+ *      R = r10 / 10 and m = (r10 * number + 5) div 10;
+ *   5. if the pool would overflow, as many pool pages that are not wanted leave,
+ *      least-read-in-the-window first, ties to the lower l*P+p;
+ *   6. the pool is the placement of step n in every layer's row.
+ * The schedule is then scored like any other (Eqs. 1-5): T(W, R). */
+void orc_wr_policy(const orc_problem *q, uint32_t W, uint32_t r10, uint8_t *X) {
+    int L = q->L, N = q->N, P = q->P;
+    size_t M = (size_t)L * P;
+    uint8_t *pool = (uint8_t *)calloc(M, 1), *wanted = (uint8_t *)malloc(M);
+    int64_t *f = (int64_t *)malloc(M * sizeof(int64_t));
+    rank_item *it = (rank_item *)malloc(M * sizeof(rank_item));
+    for (int n = 0; n < N; n++) {
+        /* 1 */
+        for (int l = 0; l < L; l++)
+            for (int p = 0; p < P; p++)
+                if (!pm_bit(q, n, p)) pool[(size_t)l * P + p] = 0;
+        /* 2 */
+        int end = (uint64_t)n + W < (uint64_t)N ? n + (int)W : N;
+        size_t cnt = 0;
+        for (int l = 0; l < L; l++)
+            for (int p = 0; p < P; p++) {
+                size_t i = (size_t)l * P + p;
+                f[i] = 0;
+                wanted[i] = 0;
+                if (!v_bit(q, n, p)) continue;
+                for (int m = n; m < end; m++)
+                    for (int k = 0; k < q->K; k++) f[i] += a_bit(q, l, m, k, p);
+                if (f[i] > 0) { it[cnt].key = f[i]; it[cnt].idx = i; cnt++; }
+            }
+        /* 3 */
+        qsort(it, cnt, sizeof(rank_item), rank_cmp);
+        size_t nw = cnt < q->cap_pages ? cnt : (size_t)q->cap_pages;
+        for (size_t c = 0; c < nw; c++) wanted[it[c].idx] = 1;
+        /* 4 */
+        size_t nq = 0;
+        for (size_t c = 0; c < nw; c++)
+            if (!pool[it[c].idx]) nq++;
+        size_t m_in = (size_t)(((uint64_t)r10 * nq + 5) / 10);
+        size_t in_pool = 0;
+        for (size_t i = 0; i < M; i++) in_pool += pool[i];
+        /* 5 */
+        if (in_pool + m_in > q->cap_pages) {
+            size_t need = in_pool + m_in - (size_t)q->cap_pages, ne = 0;
+            rank_item *ev = (rank_item *)malloc(M * sizeof(rank_item));
+            for (size_t i = 0; i < M; i++)
+                if (pool[i] && !wanted[i]) { ev[ne].key = -f[i]; ev[ne].idx = i; ne++; }
+            qsort(ev, ne, sizeof(rank_item), rank_cmp);          /* -f descending = f ascending */
+            for (size_t c = 0; c < need && c < ne; c++) pool[ev[c].idx] = 0;
+            free(ev);
+        }
+        /* 4, carried out */
+        size_t taken = 0;
+        for (size_t c = 0; c < nw && taken < m_in; c++)
+            if (!pool[it[c].idx]) { pool[it[c].idx] = 1; taken++; }
+        /* 6 */
+        for (int l = 0; l < L; l++)
+            for (int p = 0; p < P; p++) X[ix_x(q, l, n, p)] = pool[(size_t)l * P + p];
+    }
+    free(pool); free(wanted); free(f); free(it);
+}
+
+/* The annealing over (W, R), Sec. III-B: proposals are a window move (W by
+ * -2, -1, +1 or +2), a ratio move (R by -0.1 or +0.1) or both at once, with
+ * probabilities op_prob[0..2] (the paper: 0.4, 0.4, 0.2); Metropolis acceptance;
+ * the temperature starts where an average uphill proposal from the start state
+ * is accepted with probability p0 and is multiplied by alpha after every level
+ * of total_moves / n_levels proposals; the search ends when the budget is spent,
+ * when the best cost improved by less than stop_rel (the paper: 0.1 %) over a
+ * level, or when the temperature falls below c_min_frac times its start value.
+ * Proposals that leave 1 <= W <= w_max or 0 <= R <= 1 are counted and skipped.
+ * Proposal i uses Philox block (i, 0, 0, 16) under the seed: word 0 picks the
+ * operator, the top two bits of word 1 the window step, the top bit of word 2 the
+ * ratio step, u = (word 3 + 0.5) / 2^32; the 32 calibration proposals use
+ * stream 24.  table: [w_max][11] costs T(W, r10) (W from 1), < 0 where not yet
+ * evaluated; filled on demand.  Returns the number of proposals made. */
+typedef struct {
+    uint32_t w_max, w0, r10_0, n_levels;
+    uint64_t seed, total_moves;
+    double p0, alpha, op_prob[3], stop_rel, c_min_frac;
+} orc_wr_params;
+
+typedef struct {
+    uint32_t best_w, best_r10, cur_w, cur_r10, levels_done, stop_reason;   /* 0 budget, 1 stalled, 2 cold */
+    uint64_t proposals, accepted, out_of_range, evaluated;
+    double best_T, cur_T, c0;
+} orc_wr_result;
+
+static double wr_cost(const orc_problem *q, uint32_t w_max, double *table, uint32_t w, uint32_t r10, uint8_t *X,
+                      uint64_t *evaluated) {
+    double *slot = &table[(size_t)(w - 1) * 11 + r10];
+    (void)w_max;
+    if (*slot < 0.0) {
+        orc_wr_policy(q, w, r10, X);
+        *slot = orc_score(q, X, NULL, NULL, NULL, NULL);
+        (*evaluated)++;
+    }
+    return *slot;
+}
+
+static int wr_propose(const orc_wr_params *sp, uint64_t i, uint32_t stream, uint32_t w, uint32_t r10, uint32_t *w2,
+                      uint32_t *r2, double *u) {
+    uint32_t ctr[4] = {(uint32_t)i, (uint32_t)(i >> 32), 0, stream};
+    uint32_t key[2] = {(uint32_t)sp->seed, (uint32_t)(sp->seed >> 32)}, a[4];
+    orc_philox4x32_10(ctr, key, a);
+    uint64_t th0 = (uint64_t)(sp->op_prob[0] * 4294967296.0);
+    uint64_t th1 = (uint64_t)((sp->op_prob[0] + sp->op_prob[1]) * 4294967296.0);
+    int op = (uint64_t)a[0] < th0 ? 0 : (uint64_t)a[0] < th1 ? 1 : 2;
+    static const int dws[4] = {-2, -1, 1, 2};
+    int dw = op != 1 ? dws[a[1] >> 30] : 0;
+    int dr = op != 0 ? ((a[2] >> 31) ? 1 : -1) : 0;
+    *u = ((double)a[3] + 0.5) * (1.0 / 4294967296.0);
+    int64_t nw = (int64_t)w + dw, nr = (int64_t)r10 + dr;
+    if (nw < 1 || nw > (int64_t)sp->w_max || nr < 0 || nr > 10) return 0;
+    *w2 = (uint32_t)nw; *r2 = (uint32_t)nr;
+    return 1;
+}
+
+uint64_t orc_wr_search(const orc_problem *q, const orc_wr_params *sp, double *table, orc_wr_result *res) {
+    uint8_t *X = (uint8_t *)malloc((size_t)q->L * q->N * q->P);
+    memset(res, 0, sizeof *res);
+    uint32_t w = sp->w0, r10 = sp->r10_0;
+    double T = wr_cost(q, sp->w_max, table, w, r10, X, &res->evaluated);
+    res->best_w = w; res->best_r10 = r10; res->best_T = T;
+    double sum = 0.0; uint32_t cnt = 0;
+    for (uint64_t j = 0; j < 32; j++) {
+        uint32_t w2, r2; double u;
+        if (!wr_propose(sp, j, 24, w, r10, &w2, &r2, &u)) continue;
+        double dT = wr_cost(q, sp->w_max, table, w2, r2, X, &res->evaluated) - T;
+        if (dT > 0.0) { sum = sum + dT; cnt++; }
+    }
+    res->c0 = cnt ? (sum / (double)cnt) / (-log(sp->p0)) : 0.0;
+    double C = res->c0, best_at_level_start = res->best_T;
+    uint64_t mpl = sp->total_moves / sp->n_levels; if (mpl < 1) mpl = 1;
+    uint64_t i = 0;
+    res->stop_reason = 0;
+    for (; i < sp->total_moves; i++) {
+        if (i > 0 && i % mpl == 0) {                              /* a level ends */
+            res->levels_done++;
+            if (best_at_level_start - res->best_T < sp->stop_rel * best_at_level_start) { res->stop_reason = 1; break; }
+            best_at_level_start = res->best_T;
+            C = C * sp->alpha;
+            if (C < sp->c_min_frac * res->c0) { res->stop_reason = 2; break; }
+        }
+        uint32_t w2, r2; double u;
+        res->proposals++;
+        if (!wr_propose(sp, i, 16, w, r10, &w2, &r2, &u)) { res->out_of_range++; continue; }
+        double T2 = wr_cost(q, sp->w_max, table, w2, r2, X, &res->evaluated);
+        double dT = T2 - T;
+        int accept = (dT <= 0.0) || (C > 0.0 && u < exp(-dT / C));    /* Metropolis */
+        if (!accept) continue;
+        res->accepted++;
+        w = w2; r10 = r2; T = T2;
+        if (T < res->best_T) { res->best_T = T; res->best_w = w; res->best_r10 = r10; }
+    }
+    res->cur_w = w; res->cur_r10 = r10; res->cur_T = T;
+    free(X);
+    return res->proposals;
 }

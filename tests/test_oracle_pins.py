@@ -396,3 +396,89 @@ def test_static_and_recency_placements_by_hand():
     rc = O.init_recency(tr)
     # before step 0 nothing was read: lowest index; then the page read one step earlier
     assert rc[0].tolist() == [[1, 0, 0], [1, 0, 0], [0, 1, 0], [0, 1, 0]]
+
+
+# ---- the (W, R) look-ahead policy and its search (Sec. III-B), pinned to the reading stated in the oracle ----
+
+def _wr_mini():
+    tr = _mini(L=1, N=4, P=4, cap=2)
+    tr.alive[:] = 1
+    tr.persist[1:] = 1
+    tr.access[0, :, 0, :] = [[1, 1, 0, 0], [0, 1, 1, 0], [0, 0, 1, 1], [0, 0, 0, 1]]
+    return tr
+
+
+def test_wr_policy_by_hand():
+    tr = _wr_mini()
+    # W = 2, R = 1.  n=0: reads in steps 0,1 are (1,2,1,0): ranking 1,0,2: wanted {1,0}, both come in.
+    # n=1: (0,1,2,1): wanted {2,1}; 2 comes in, the pool is full: the unwanted page 0 leaves.
+    # n=2: (0,0,1,2): wanted {3,2}; 3 comes in, 1 leaves.  n=3: wanted {3}: nothing to do.
+    assert O.wr_policy(tr, 2, 10)[0].tolist() == [[1, 1, 0, 0], [0, 1, 1, 0], [0, 0, 1, 1], [0, 0, 1, 1]]
+    # R = 0.5: of the two qualified pages at n=0 only round(0.5 * 2) = 1 comes in, the better ranked (page 1);
+    # n=1: one qualified, round(0.5) = 1 (half rounds up): page 2, no eviction needed
+    assert O.wr_policy(tr, 2, 5)[0].tolist() == [[0, 1, 0, 0], [0, 1, 1, 0], [0, 0, 1, 1], [0, 0, 1, 1]]
+    # R = 0.4: round(0.8) = 1 at n=0 (page 1), round(0.4) = 0 at n=1; at n=2 pages 3 and 2 are qualified:
+    # round(0.8) = 1, page 3, and there is room for it
+    assert O.wr_policy(tr, 2, 4)[0].tolist() == [[0, 1, 0, 0], [0, 1, 0, 0], [0, 1, 0, 1], [0, 1, 0, 1]]
+    # W = 1 only sees the current step: ties to the lower page
+    assert O.wr_policy(tr, 1, 10)[0].tolist() == [[1, 1, 0, 0], [0, 1, 1, 0], [0, 0, 1, 1], [0, 0, 1, 1]]
+    # R = 0: nothing ever migrates
+    assert not O.wr_policy(tr, 3, 0).any()
+
+
+def test_wr_policy_forgets_pages_that_stop_persisting_and_counts_planes():
+    tr = _wr_mini()
+    tr.persist[2, 1] = 0                                         # page 1 is re-used at step 2
+    got = O.wr_policy(tr, 4, 10)[0].tolist()
+    # n=0: reads ahead (1,2,2,2): ranking 1,2,3,0: pool {1,2}; n=1: (0,1,2,2): ranking 2,3,1: wanted {2,3}: 3 in, 1 out
+    # n=2: page 1 would have left anyway; (0,0,1,2): pool {2,3} stays
+    assert got == [[0, 1, 1, 0], [0, 0, 1, 1], [0, 0, 1, 1], [0, 0, 1, 1]]
+    tr2 = _mini(L=2, N=2, P=2, K=2, cap=1)
+    tr2.alive[:] = 1
+    tr2.persist[1:] = 1
+    tr2.access[0, 0, :, 0] = [1, 0]                              # (layer 0, page 0): one plane reads it
+    tr2.access[1, 0, :, 1] = [1, 1]                              # (layer 1, page 1): both planes read it
+    X = O.wr_policy(tr2, 1, 10)
+    assert X[:, 0, :].tolist() == [[0, 0], [0, 1]]              # the pool is shared by the layers: frequency 2 beats 1
+    assert X[:, 1, :].tolist() == [[0, 0], [0, 1]]              # nothing is read at step 1: the pool stays
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_wr_policy_invariants(seed):
+    tr = W.random_trace(100 + seed, L=2, N=12, P=9, K=2, cap_pages=5)
+    q = O.Problem(tr)
+    for Wn in (1, 3, 12, 40):
+        for r10 in (0, 3, 10):
+            X = O.wr_policy(tr, Wn, r10).astype(bool)
+            assert not (X & ~tr.alive.astype(bool)[None]).any()          # only existing pages
+            assert X.sum(axis=(0, 2)).max() <= tr.cap_pages               # the shared pool is never overfull
+            assert O.score(q, X).excess == 0
+            if r10 == 0:
+                assert not X.any()
+    # capacity for everything and R = 1: whatever is read within the window is in HBM when it is read
+    big = W.random_trace(100 + seed, L=2, N=12, P=9, K=2, cap_pages=2 * 9)
+    X = O.wr_policy(big, 2, 10).astype(bool)
+    read_now = big.access.astype(bool).any(axis=2)                        # [L][N][P]
+    assert not (read_now & ~X).any()
+
+
+def test_wr_search_walks_the_grid_as_stated():
+    tr = W.config("tiny")
+    q = O.Problem(tr)
+    res, tab = O.wr_search(tr, w_max=12, total_moves=300, n_levels=10, seed=7, stop_rel=0.0, c_min_frac=0.0)
+    known = tab >= 0
+    assert res.stop_reason == 0 and res.proposals == 300 and res.evaluated == known.sum()
+    assert res.best_T == tab[known].min() and tab[res.best_w - 1, res.best_r10] == res.best_T
+    assert tab[res.cur_w - 1, res.cur_r10] == res.cur_T
+    # every table entry is the score of the policy's schedule
+    for w, r in [(res.best_w, res.best_r10), (1, 5), (res.cur_w, res.cur_r10)]:
+        assert tab[w - 1, r] == O.score(q, O.wr_policy(tr, w, r)).cost
+    # start temperature: an average uphill proposal from the start is accepted with probability p0
+    assert res.c0 > 0
+    # the paper's stop rules end the walk early: no 0.1 % improvement over a level
+    res2, _ = O.wr_search(tr, w_max=12, total_moves=3000, n_levels=10, seed=7)
+    assert res2.stop_reason in (1, 2) and res2.proposals < 3000
+    # the search over placements themselves does at least as well from the same start
+    best = O.wr_policy(tr, res.best_w, res.best_r10)
+    out, _ = O.anneal(tr, chains=[0], X0=best, total_moves=3000, seed=1)
+    assert out[0].T_best <= res.best_T
