@@ -228,6 +228,60 @@ int kvp_score_kernel_used(const kvp_ctx *ctx);
 enum { KVP_BASELINE_STATIC = 0, KVP_BASELINE_RECENCY = 1 };
 int kvp_baseline(kvp_ctx *ctx, int kind, uint32_t *d_placement);
 
+/* ---- the paper's own search: a look-ahead policy with two scalars (Sec. III-B) ----
+ * W >= 1: token steps looked ahead; R = r10 / 10, r10 in 0..10: share of the pages
+ * qualified for migration that migrate.  The policy, once per token step n on the
+ * pool of cap_pages shared by the layers (the paper states it in two sentences;
+ * this is the reading taken, the same as the oracle's):
+ *   1. pages that do not persist into n leave the pool;
+ *   2. the existing pages read in steps n .. n+W-1 are collected with their read
+ *      frequency f there (summed over the planes);
+ *   3. ranked by f descending, ties to the lower l * n_pages + p; the first
+ *      cap_pages of the ranking are wanted;
+ *   4. wanted pages outside the pool are qualified; the first
+ *      (r10 * their number + 5) div 10 of them, in rank order, come in;
+ *   5. if the pool would overflow, as many unwanted pool pages leave, smallest f
+ *      first, ties to the lower l * n_pages + p;
+ *   6. the pool is the placement of step n in every layer.
+ *
+ * kvp_wr_policy: n candidates (h_w[i], h_r10[i]), HOST arrays, read before the
+ * call returns; d_placements: DEVICE [n][L][N][Wd] uint32, written in full, owned
+ * by the caller.  One workgroup per candidate.  W above n_steps acts as n_steps.
+ * Errors: KVP_EINVAL (null pointer, W = 0, r10 > 10), KVP_ENOTRACE, KVP_ESHAPE
+ * (W x planes above 32767), KVP_ENOMEM, KVP_EHIP. */
+int kvp_wr_policy(kvp_ctx *ctx, uint32_t n, const uint32_t *h_w, const uint32_t *h_r10, uint32_t *d_placements);
+
+/* The annealing over (W, R) as Sec. III-B describes it: window moves (W by -2, -1,
+ * +1, +2), ratio moves (R by -0.1, +0.1) and diagonal moves (both), drawn with
+ * probabilities op_prob[0..2] (the paper: 0.4, 0.4, 0.2); Metropolis acceptance;
+ * the temperature starts where an average uphill proposal from the start state
+ * is accepted with probability p0 (0.8) and is multiplied by alpha (0.9) after
+ * each level of total_moves / n_levels proposals; the walk ends when the budget
+ * is spent (stop_reason 0), when the best cost improved by less than stop_rel
+ * (0.001) over a level (1), or when the temperature is below c_min_frac times its
+ * start (2).  Proposals that leave 1 <= W <= w_max or 0 <= R <= 1 are counted and
+ * skipped.  Proposal i uses Philox4x32-10 block (i, 0, 0, 16) under the seed
+ * (word 0: operator; top two bits of word 1: window step; top bit of word 2:
+ * ratio step; u = (word 3 + 0.5) / 2^32); the 32 proposals that set the start
+ * temperature use stream 24.  Costs are those of kvp_score on the policy's
+ * schedules, kept in h_table (HOST, [w_max][11] doubles, row W-1, column r10;
+ * negative = not yet known; in/out, so that a table can be carried from one walk
+ * to the next); unknown neighbours of the current state are evaluated together.
+ * d_best_placement: DEVICE [L][N][Wd] or null; receives the best policy's schedule.
+ * Errors: KVP_EINVAL, KVP_ENOTRACE, KVP_ESHAPE, KVP_ENOMEM, KVP_EHIP. */
+typedef struct {
+    uint32_t w_max, w0, r10_0, n_levels;
+    uint64_t seed, total_moves;
+    double p0, alpha, op_prob[3], stop_rel, c_min_frac;
+} kvp_wr_params;
+typedef struct {
+    uint32_t best_w, best_r10, cur_w, cur_r10, levels_done, stop_reason;
+    uint64_t proposals, accepted, out_of_range, evaluated;
+    double best_T, cur_T, c0;
+} kvp_wr_result;
+int kvp_wr_search(kvp_ctx *ctx, const kvp_wr_params *params, double *h_table, kvp_wr_result *result,
+                  uint32_t *d_best_placement);
+
 const char *kvp_strerror(int code);
 
 /* After a KVP_EHIP / KVP_ENOMEM return on this thread: the hipError_t value of

@@ -27,7 +27,21 @@ KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2
 
 EXPORTS = ["kvp_create", "kvp_destroy", "kvp_trace_upload", "kvp_score", "kvp_delta_score", "kvp_anneal",
            "kvp_best", "kvp_chain_placement", "kvp_chain_stats", "kvp_plane_unit", "kvp_strerror", "kvp_last_hip_error",
-           "kvp_set_score_kernel", "kvp_score_kernel_used", "kvp_baseline"]
+           "kvp_set_score_kernel", "kvp_score_kernel_used", "kvp_baseline", "kvp_wr_policy",
+           "kvp_wr_search"]
+
+
+class kvp_wr_params(C.Structure):
+    _fields_ = [("w_max", C.c_uint32), ("w0", C.c_uint32), ("r10_0", C.c_uint32), ("n_levels", C.c_uint32),
+                ("seed", C.c_uint64), ("total_moves", C.c_uint64), ("p0", C.c_double), ("alpha", C.c_double),
+                ("op_prob", C.c_double * 3), ("stop_rel", C.c_double), ("c_min_frac", C.c_double)]
+
+
+class kvp_wr_result(C.Structure):
+    _fields_ = [("best_w", C.c_uint32), ("best_r10", C.c_uint32), ("cur_w", C.c_uint32), ("cur_r10", C.c_uint32),
+                ("levels_done", C.c_uint32), ("stop_reason", C.c_uint32), ("proposals", C.c_uint64),
+                ("accepted", C.c_uint64), ("out_of_range", C.c_uint64), ("evaluated", C.c_uint64),
+                ("best_T", C.c_double), ("cur_T", C.c_double), ("c0", C.c_double)]
 
 
 class kvp_problem(C.Structure):
@@ -99,6 +113,10 @@ def lib():
         L.kvp_strerror.argtypes = [i32]
         L.kvp_set_score_kernel.restype = i32
         L.kvp_set_score_kernel.argtypes = [vp, i32]
+        L.kvp_wr_policy.restype = i32
+        L.kvp_wr_policy.argtypes = [vp, C.c_uint32, vp, vp, vp]
+        L.kvp_wr_search.restype = i32
+        L.kvp_wr_search.argtypes = [vp, C.POINTER(kvp_wr_params), vp, C.POINTER(kvp_wr_result), vp]
         L.kvp_baseline.restype = i32
         L.kvp_baseline.argtypes = [vp, i32, vp]
         L.kvp_score_kernel_used.restype = i32
@@ -208,6 +226,28 @@ def kvp_set_score_kernel(ctx, which: int):
 
 
 KVP_BASELINE_STATIC, KVP_BASELINE_RECENCY = 0, 1
+
+
+def kvp_wr_policy(ctx, ws, r10s, d_placements):
+    """Schedules of the (W, R = r10/10) look-ahead policy for a batch of candidates into the device
+    tensor d_placements [n][L][N][Wd] int32."""
+    w = np.ascontiguousarray(ws, dtype=np.uint32)
+    r = np.ascontiguousarray(r10s, dtype=np.uint32)
+    assert w.shape == r.shape and w.ndim == 1
+    _check(lib().kvp_wr_policy(ctx, int(w.size), _hptr(w), _hptr(r), _dptr(d_placements)), "kvp_wr_policy")
+
+
+def kvp_wr_search(ctx, w_max, total_moves, n_levels=20, seed=0, w0=1, r10_0=5, p0=0.8, alpha=0.9,
+                  op_prob=(0.4, 0.4, 0.2), stop_rel=1e-3, c_min_frac=1e-3, table=None, d_best_placement=None):
+    """The annealing over (W, R).  Returns (kvp_wr_result, table [w_max][11] of the costs known, < 0 elsewhere)."""
+    sp = kvp_wr_params(int(w_max), int(w0), int(r10_0), int(n_levels), int(seed), int(total_moves), float(p0),
+                       float(alpha), (C.c_double * 3)(*op_prob), float(stop_rel), float(c_min_frac))
+    if table is None:
+        table = np.full((int(w_max), 11), -1.0)
+    assert table.dtype == np.float64 and table.shape == (int(w_max), 11) and table.flags.c_contiguous
+    res = kvp_wr_result()
+    _check(lib().kvp_wr_search(ctx, C.byref(sp), _hptr(table), C.byref(res), _dptr(d_best_placement)), "kvp_wr_search")
+    return res, table
 
 
 def kvp_baseline(ctx, kind: int, d_placement):

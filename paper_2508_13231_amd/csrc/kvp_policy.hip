@@ -1,0 +1,279 @@
+// The paper's own search (Sec. III-B): a look-ahead placement policy with two
+// scalars, the window W (token steps looked ahead) and the ratio R (share of the
+// pages qualified for migration that really migrate), and the annealing over
+// (W, R).  The reading of the policy, once per token step n, one pool of
+// cap_pages for all layers:
+//   1. pages that do not hold the same data as one step earlier leave the pool;
+//   2. the existing pages read in steps n .. n+W-1 are collected with their read
+//      frequency f there (summed over the planes);
+//   3. ranked by f descending, ties to the lower l*P+p, the first cap_pages are
+//      the wanted set;
+//   4. the wanted pages outside the pool are qualified for migration; the first
+//      m = (r10 * their number + 5) div 10 of them, in rank order, come in (R = r10/10);
+//   5. if the pool would overflow, as many pool pages that are not wanted leave,
+//      least-read-in-the-window first, ties to the lower l*P+p;
+//   6. the pool is the placement of step n in every layer's row.
+//
+// kvp_wr_policy turns a batch of (W, R) candidates into schedules, one workgroup
+// per candidate: the window counts slide (one step leaves, one enters), and
+// steps 3 to 5 are three selections by histogram threshold and index-ordered ties
+// (kvp_select.h).  kvp_wr_search is the annealing itself: a host loop over a
+// memoised table T(W, R), filled by scoring whole neighbourhoods of candidates at
+// once (generator + kvp_score), so the accelerator sees batches, not single points.
+#include <math.h>
+
+#include <vector>
+
+#include "kvp_internal.h"
+#include "kvp_select.h"
+
+namespace {
+
+// reads of (layer l, word w, bit b) at step m, summed over the planes
+__device__ __forceinline__ uint32_t reads_at(const DevProblem &q, uint32_t l, uint32_t m, uint32_t w, uint32_t b) {
+    const uint32_t *a = q.A + ((size_t)l * q.N + m) * q.K * q.Wd + w;
+    uint32_t s = 0;
+    for (uint32_t k = 0; k < q.K; k++) s += (a[(size_t)k * q.Wd] >> b) & 1u;
+    return s;
+}
+
+// work per candidate: f[G] window counts, pool[LW] and wanted[LW] mask words
+__global__ __launch_bounds__(BT) void wr_policy_kernel(DevProblem q, uint64_t cap, const uint32_t *__restrict__ cand_w,
+                                                       const uint32_t *__restrict__ cand_r10, uint32_t *work,
+                                                       size_t work_stride, uint32_t *Xall) {
+    extern __shared__ uint32_t lds_u[];
+    __shared__ SelectShared sh;
+    __shared__ uint32_t counts[2];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t LW = q.L * q.Wd, G = LW * 32;
+    const uint32_t W = min(cand_w[blockIdx.x], q.N), r10 = cand_r10[blockIdx.x];
+    uint32_t *f = work + (size_t)blockIdx.x * work_stride, *pool = f + G, *wanted = pool + LW;
+    uint32_t *X = Xall + (size_t)blockIdx.x * q.L * q.N * q.Wd;
+    const uint32_t fmax = W * q.K, nbins = fmax + 1;
+
+    for (uint32_t wi = tid; wi < LW; wi += BT) pool[wi] = 0;
+    for (uint32_t g = tid; g < G; g += BT) {
+        const uint32_t wi = g >> 5, b = g & 31u, l = wi / q.Wd, w = wi - l * q.Wd;
+        uint32_t s = 0;
+        for (uint32_t m = 0; m < W; m++) s += reads_at(q, l, m, w, b);
+        f[g] = s;
+    }
+    __syncthreads();
+    for (uint32_t n = 0; n < q.N; n++) {
+        if (n > 0)                                                     // the window slides: step n-1 leaves, n+W-1 enters
+            for (uint32_t g = tid; g < G; g += BT) {
+                const uint32_t wi = g >> 5, b = g & 31u, l = wi / q.Wd, w = wi - l * q.Wd;
+                uint32_t s = f[g] - reads_at(q, l, n - 1, w, b);
+                if (n + W - 1 < q.N) s += reads_at(q, l, n + W - 1, w, b);
+                f[g] = s;
+            }
+        for (uint32_t wi = tid; wi < LW; wi += BT) pool[wi] &= q.Pm[(size_t)n * q.Wd + wi % q.Wd];   // step 1
+        if (tid < 2) counts[tid] = 0;
+        __syncthreads();
+        // steps 2 and 3: the wanted set
+        auto key_want = [&](uint32_t g) {
+            const uint32_t w = (g >> 5) % q.Wd, b = g & 31u;
+            const uint32_t vw = q.V[(size_t)n * q.Wd + w];
+            uint32_t fv = f[g];
+            asm volatile("" : "+v"(fv));                               // loaded whether the page exists or not
+            return ((vw >> b) & 1u) && fv > 0 ? fv : NOT_A_CANDIDATE;
+        };
+        block_select(G, nbins, cap, lds_u, sh, key_want, key_want,
+                     [&](uint32_t word, uint32_t bits) { wanted[word] = bits; });
+        // how many are qualified, how many are in the pool
+        uint32_t nq = 0, np = 0;
+        for (uint32_t wi = tid; wi < LW; wi += BT) {
+            const uint32_t pw = pool[wi];
+            nq += __popc(wanted[wi] & ~pw);
+            np += __popc(pw);
+        }
+        nq = wave_sum_u32(nq); np = wave_sum_u32(np);
+        if (lane == 0) { atomicAdd(&counts[0], nq); atomicAdd(&counts[1], np); }
+        __syncthreads();
+        const uint64_t m_in = ((uint64_t)r10 * counts[0] + 5) / 10;    // step 4
+        const uint64_t in_pool = counts[1];
+        const uint64_t need = in_pool + m_in > cap ? in_pool + m_in - cap : 0;
+        if (need > 0) {                                                // step 5
+            auto key_out = [&](uint32_t g) {
+                const uint32_t wi = g >> 5, b = g & 31u;
+                const uint32_t pw = pool[wi], ww = wanted[wi];
+                uint32_t fv = f[g];
+                asm volatile("" : "+v"(fv));
+                return ((pw & ~ww) >> b) & 1u ? fmax - fv : NOT_A_CANDIDATE;
+            };
+            block_select(G, nbins, need, lds_u, sh, key_out, key_out,
+                         [&](uint32_t word, uint32_t bits) { pool[word] &= ~bits; });
+        }
+        if (m_in > 0) {                                                // step 4, carried out
+            auto key_in = [&](uint32_t g) {
+                const uint32_t wi = g >> 5, b = g & 31u;
+                const uint32_t pw = pool[wi], ww = wanted[wi];
+                uint32_t fv = f[g];
+                asm volatile("" : "+v"(fv));
+                return ((ww & ~pw) >> b) & 1u ? fv : NOT_A_CANDIDATE;
+            };
+            block_select(G, nbins, m_in, lds_u, sh, key_in, key_in,
+                         [&](uint32_t word, uint32_t bits) { pool[word] |= bits; });
+        }
+        for (uint32_t wi = tid; wi < LW; wi += BT) {                   // step 6
+            const uint32_t l = wi / q.Wd, w = wi - l * q.Wd;
+            X[((size_t)l * q.N + n) * q.Wd + w] = pool[wi];
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace
+
+extern "C" int kvp_wr_policy(kvp_ctx *ctx, uint32_t n, const uint32_t *h_w, const uint32_t *h_r10,
+                             uint32_t *d_placements) {
+    if (!ctx) return KVP_EINVAL;
+    if (!ctx->has_trace) return KVP_ENOTRACE;
+    if (n == 0) return KVP_OK;
+    if (!h_w || !h_r10 || !d_placements || ((uintptr_t)d_placements & 3u)) return KVP_EINVAL;
+    const DevProblem &q = ctx->dp;
+    uint32_t wmax = 0;
+    for (uint32_t i = 0; i < n; i++) {
+        if (h_w[i] < 1 || h_r10[i] > 10) return KVP_EINVAL;
+        const uint32_t w = h_w[i] < q.N ? h_w[i] : q.N;
+        wmax = w > wmax ? w : wmax;
+    }
+    const uint64_t G64 = (uint64_t)q.L * q.Wd * 32;
+    if (G64 >= (1ull << 31)) return KVP_ESHAPE;
+    const size_t lds = ((size_t)wmax * q.K + 1) * 4;
+    if (lds > 128 * 1024) return KVP_ESHAPE;
+    KVP_HIP(hipSetDevice(ctx->device));
+    const size_t LW = (size_t)q.L * q.Wd, stride = (size_t)G64 + 2 * LW;
+    int rc = kvp_ensure(ctx, (void **)&ctx->d_policy_work, &ctx->policy_work_cap, ((size_t)n * stride + 2 * (size_t)n) * 4);
+    if (rc) return rc;
+    uint32_t *d_w = ctx->d_policy_work + (size_t)n * stride, *d_r = d_w + n;
+    KVP_HIP(hipMemcpyAsync(d_w, h_w, (size_t)n * 4, hipMemcpyHostToDevice, ctx->stream));
+    KVP_HIP(hipMemcpyAsync(d_r, h_r10, (size_t)n * 4, hipMemcpyHostToDevice, ctx->stream));
+    KVP_HIP(hipStreamSynchronize(ctx->stream));                        // the host arrays may go away after the call
+    if (lds > 48 * 1024)
+        KVP_HIP(hipFuncSetAttribute((const void *)wr_policy_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    wr_policy_kernel<<<dim3(n), dim3(BT), lds, ctx->stream>>>(q, ctx->prob.cap_pages, d_w, d_r, ctx->d_policy_work, stride,
+                                                             d_placements);
+    KVP_HIP(hipGetLastError());
+    return KVP_OK;
+}
+
+namespace {
+
+// proposal i of the walk: Philox4x32-10 block (i, 0, 0, stream) under the seed
+void philox_host(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1, uint32_t out[4]) {
+    for (int r = 0; r < 10; r++) {
+        const uint64_t m0 = (uint64_t)0xD2511F53u * c0, m1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(m1 >> 32) ^ c1 ^ k0, n2 = (uint32_t)(m0 >> 32) ^ c3 ^ k1;
+        c0 = n0; c1 = (uint32_t)m1; c2 = n2; c3 = (uint32_t)m0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+bool propose(const kvp_wr_params &sp, uint64_t i, uint32_t stream, uint32_t w, uint32_t r10, uint32_t &w2, uint32_t &r2,
+             double &u) {
+    uint32_t a[4];
+    philox_host((uint32_t)i, (uint32_t)(i >> 32), 0, stream, (uint32_t)sp.seed, (uint32_t)(sp.seed >> 32), a);
+    const uint64_t th0 = (uint64_t)(sp.op_prob[0] * 4294967296.0);
+    const uint64_t th1 = (uint64_t)((sp.op_prob[0] + sp.op_prob[1]) * 4294967296.0);
+    const int op = (uint64_t)a[0] < th0 ? 0 : (uint64_t)a[0] < th1 ? 1 : 2;   // window, ratio, both
+    static const int steps[4] = {-2, -1, 1, 2};
+    const int dw = op != 1 ? steps[a[1] >> 30] : 0;
+    const int dr = op != 0 ? ((a[2] >> 31) ? 1 : -1) : 0;
+    u = ((double)a[3] + 0.5) * (1.0 / 4294967296.0);
+    const int64_t nw = (int64_t)w + dw, nr = (int64_t)r10 + dr;
+    if (nw < 1 || nw > (int64_t)sp.w_max || nr < 0 || nr > 10) return false;
+    w2 = (uint32_t)nw; r2 = (uint32_t)nr;
+    return true;
+}
+
+}  // namespace
+
+extern "C" int kvp_wr_search(kvp_ctx *ctx, const kvp_wr_params *sp, double *h_table, kvp_wr_result *res,
+                             uint32_t *d_best_placement) {
+    if (!ctx || !sp || !h_table || !res) return KVP_EINVAL;
+    if (!ctx->has_trace) return KVP_ENOTRACE;
+    if (sp->w_max < 1 || sp->w0 < 1 || sp->w0 > sp->w_max || sp->r10_0 > 10 || sp->n_levels < 1 || !(sp->p0 > 0.0) ||
+        !(sp->p0 < 1.0))
+        return KVP_EINVAL;
+    const DevProblem &q = ctx->dp;
+    const size_t words = (size_t)q.L * q.N * q.Wd;
+    KVP_HIP(hipSetDevice(ctx->device));
+    *res = kvp_wr_result{};
+    // T(w, r10), evaluating with it every neighbour of (cw, cr) that a proposal can reach and that is
+    // still unknown: one batch for the generator and the scorer
+    int err = KVP_OK;
+    auto cost = [&](uint32_t w, uint32_t r10, uint32_t cw, uint32_t cr) -> double {
+        double &slot = h_table[(size_t)(w - 1) * 11 + r10];
+        if (slot >= 0.0 || err) return slot;
+        std::vector<uint32_t> ws{w}, rs{r10};
+        for (int dw = -2; dw <= 2; dw++)
+            for (int dr = -1; dr <= 1; dr++) {
+                const int64_t nw = (int64_t)cw + dw, nr = (int64_t)cr + dr;
+                if ((dw == 0 && dr == 0) || nw < 1 || nw > (int64_t)sp->w_max || nr < 0 || nr > 10) continue;
+                if (h_table[(size_t)(nw - 1) * 11 + nr] >= 0.0 || ((uint32_t)nw == w && (uint32_t)nr == r10)) continue;
+                ws.push_back((uint32_t)nw); rs.push_back((uint32_t)nr);
+            }
+        const uint32_t nb = (uint32_t)ws.size();
+        const size_t xwords = ((size_t)nb * words + 3) & ~(size_t)3;     // results start 16-byte aligned
+        if ((err = kvp_ensure(ctx, (void **)&ctx->d_policy_x, &ctx->policy_x_cap, xwords * 4 + (size_t)nb * 16)))
+            return slot;
+        double *d_cost = (double *)(ctx->d_policy_x + xwords);
+        uint32_t *d_ex = (uint32_t *)(d_cost + nb);
+        if ((err = kvp_wr_policy(ctx, nb, ws.data(), rs.data(), ctx->d_policy_x))) return slot;
+        if ((err = kvp_score_launch(ctx, ctx->d_policy_x, nb, d_cost, d_ex, nullptr, nullptr))) return slot;
+        std::vector<double> hc(nb);
+        hipError_t e = hipMemcpyAsync(hc.data(), d_cost, (size_t)nb * 8, hipMemcpyDeviceToHost, ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+        if (e != hipSuccess) { err = KVP_EHIP; return slot; }
+        for (uint32_t j = 0; j < nb; j++) h_table[(size_t)(ws[j] - 1) * 11 + rs[j]] = hc[j];
+        res->evaluated += nb;
+        return slot;
+    };
+    uint32_t w = sp->w0, r10 = sp->r10_0;
+    double T = cost(w, r10, w, r10);
+    if (err) return err;
+    res->best_w = w; res->best_r10 = r10; res->best_T = T;
+    double sum = 0.0;
+    uint32_t cnt = 0;
+    for (uint64_t j = 0; j < 32; j++) {                                // start temperature from p0
+        uint32_t w2, r2; double u;
+        if (!propose(*sp, j, 24, w, r10, w2, r2, u)) continue;
+        const double dT = cost(w2, r2, w, r10) - T;
+        if (err) return err;
+        if (dT > 0.0) { sum = sum + dT; cnt++; }
+    }
+    res->c0 = cnt ? (sum / (double)cnt) / (-log(sp->p0)) : 0.0;
+    double C = res->c0, best_at_level_start = res->best_T;
+    uint64_t mpl = sp->total_moves / sp->n_levels;
+    if (mpl < 1) mpl = 1;
+    res->stop_reason = 0;
+    for (uint64_t i = 0; i < sp->total_moves; i++) {
+        if (i > 0 && i % mpl == 0) {                                   // a level ends
+            res->levels_done++;
+            if (best_at_level_start - res->best_T < sp->stop_rel * best_at_level_start) { res->stop_reason = 1; break; }
+            best_at_level_start = res->best_T;
+            C = C * sp->alpha;
+            if (C < sp->c_min_frac * res->c0) { res->stop_reason = 2; break; }
+        }
+        uint32_t w2, r2; double u;
+        res->proposals++;
+        if (!propose(*sp, i, 16, w, r10, w2, r2, u)) { res->out_of_range++; continue; }
+        const double T2 = cost(w2, r2, w, r10);
+        if (err) return err;
+        const double dT = T2 - T;
+        const bool accept = dT <= 0.0 || (C > 0.0 && u < exp(-dT / C));   // Metropolis
+        if (!accept) continue;
+        res->accepted++;
+        w = w2; r10 = r2; T = T2;
+        if (T < res->best_T) { res->best_T = T; res->best_w = w; res->best_r10 = r10; }
+    }
+    res->cur_w = w; res->cur_r10 = r10; res->cur_T = T;
+    if (d_best_placement) {
+        if (((uintptr_t)d_best_placement & 3u)) return KVP_EINVAL;
+        if ((err = kvp_wr_policy(ctx, 1, &res->best_w, &res->best_r10, d_best_placement))) return err;
+        KVP_HIP(hipStreamSynchronize(ctx->stream));
+    }
+    return KVP_OK;
+}

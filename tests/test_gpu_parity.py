@@ -335,6 +335,53 @@ def test_anneal_from_a_baseline_start_is_no_worse_than_the_baseline(G):
             assert r.cost == cost and r.excess == 0 and cost <= start.cost
 
 
+WR_CASES = ("tiny", "table1", "llama8b/4", "serving/16", "gqa70b/16", "rand-odd", "rand-weights", "one-step",
+            "rand-tiles", "rand-w40", "dec-w21-L3")
+
+
+@pytest.mark.parametrize("name,tr", [c for c in CASES if c[0] in WR_CASES], ids=lambda v: v if isinstance(v, str) else "")
+def test_wr_policy_matches_oracle(G, name, tr):
+    """Schedules of the look-ahead policy, bit for bit, for a batch of (W, R) candidates at once."""
+    import torch
+    import paper_2508_13231_amd as K
+    cands = [(1, 10), (2, 5), (4, 4), (8, 10), (tr.N + 5, 7), (3, 0), (5, 1), (16, 9)]
+    with G(tr) as g:
+        d = torch.full((len(cands), tr.L, tr.N, tr.n_words), -1, dtype=torch.int32, device=g.dev)
+        K.kvp_wr_policy(g.ctx, [c[0] for c in cands], [c[1] for c in cands], d)
+        torch.cuda.synchronize()
+        got = d.cpu().numpy().view(np.uint32)
+        for i, (w, r) in enumerate(cands):
+            want = O.wr_policy(tr, w, r).astype(bool)
+            assert (g.unpack(got[i]) == want).all(), (name, w, r)
+
+
+@pytest.mark.parametrize("name,scale,kw", [("tiny", 1.0, dict(w_max=12, total_moves=300, seed=7, stop_rel=0.0, c_min_frac=0.0)),
+                                           ("tiny", 1.0, dict(w_max=20, total_moves=2000, seed=1)),
+                                           ("llama8b", 0.25, dict(w_max=8, total_moves=60, n_levels=6, seed=3, w0=3, r10_0=9))])
+def test_wr_search_walks_like_the_oracle(G, name, scale, kw):
+    """Same proposals, same costs, same walk: every field of the result and every cost both sides know."""
+    import torch
+    import paper_2508_13231_amd as K
+    tr = W.config(name, scale)
+    want, wtab = O.wr_search(tr, **kw)
+    with G(tr) as g:
+        d = torch.empty((tr.L, tr.N, tr.n_words), dtype=torch.int32, device=g.dev)
+        got, gtab = K.kvp_wr_search(g.ctx, d_best_placement=d, **kw)
+        for f in ("best_w", "best_r10", "cur_w", "cur_r10", "levels_done", "stop_reason", "proposals", "accepted",
+                  "out_of_range", "best_T", "cur_T", "c0"):
+            assert getattr(got, f) == getattr(want, f), f
+        known = wtab >= 0
+        assert (gtab[known] == wtab[known]).all() and (gtab >= 0).sum() >= known.sum()
+        assert got.evaluated == (gtab >= 0).sum()
+        best = g.unpack(d.cpu().numpy().view(np.uint32))
+        assert (best == O.wr_policy(tr, want.best_w, want.best_r10).astype(bool)).all()
+        # the direct search over placements does at least as well from the policy's best schedule
+        p = K.make_anneal_params(4, 2000, seed=9, init_mode=K.KVP_INIT_BROADCAST)
+        K.kvp_anneal(g.ctx, p, d)
+        cost, _, _, _ = K.kvp_best(g.ctx, (tr.L, tr.N, tr.n_words))
+        assert cost <= want.best_T
+
+
 def _full_shape(name):
     """Trace and batch size of a benchmark config.  Config 1 is taken whole (the benchmark's own launch);
     the two configs whose trace takes minutes to draw keep their layers, row width and planes but
