@@ -201,20 +201,25 @@ extern "C" int kvp_wr_search(kvp_ctx *ctx, const kvp_wr_params *sp, double *h_ta
     const size_t words = (size_t)q.L * q.N * q.Wd;
     KVP_HIP(hipSetDevice(ctx->device));
     *res = kvp_wr_result{};
-    // T(w, r10), evaluating with it every neighbour of (cw, cr) that a proposal can reach and that is
-    // still unknown: one batch for the generator and the scorer
+    // T(w, r10).  An unknown cost is never evaluated alone: the states nearest to the current one
+    // (cw, cr) that are still unknown go with it, as many as fit 4 GiB of schedules (at least the
+    // 14 states one proposal away), in one batch for the generator and the scorer.
     int err = KVP_OK;
+    const size_t fit = (size_t)(4ull << 30) / (words * 4);
+    const size_t batch_max = fit > 15 ? fit : 15;
     auto cost = [&](uint32_t w, uint32_t r10, uint32_t cw, uint32_t cr) -> double {
         double &slot = h_table[(size_t)(w - 1) * 11 + r10];
         if (slot >= 0.0 || err) return slot;
         std::vector<uint32_t> ws{w}, rs{r10};
-        for (int dw = -2; dw <= 2; dw++)
-            for (int dr = -1; dr <= 1; dr++) {
-                const int64_t nw = (int64_t)cw + dw, nr = (int64_t)cr + dr;
-                if ((dw == 0 && dr == 0) || nw < 1 || nw > (int64_t)sp->w_max || nr < 0 || nr > 10) continue;
-                if (h_table[(size_t)(nw - 1) * 11 + nr] >= 0.0 || ((uint32_t)nw == w && (uint32_t)nr == r10)) continue;
-                ws.push_back((uint32_t)nw); rs.push_back((uint32_t)nr);
-            }
+        for (uint32_t ring = 1; ring <= sp->w_max + 10 && ws.size() < batch_max; ring++)
+            for (int64_t nw = (int64_t)cw - ring; nw <= (int64_t)cw + ring && ws.size() < batch_max; nw++)
+                for (int64_t nr = (int64_t)cr - ring; nr <= (int64_t)cr + ring && ws.size() < batch_max; nr++) {
+                    const int64_t dw = nw > (int64_t)cw ? nw - cw : (int64_t)cw - nw, dr = nr > (int64_t)cr ? nr - cr : (int64_t)cr - nr;
+                    if ((dw > dr ? dw : dr) != (int64_t)ring) continue;             // only the ring itself
+                    if (nw < 1 || nw > (int64_t)sp->w_max || nr < 0 || nr > 10) continue;
+                    if (h_table[(size_t)(nw - 1) * 11 + nr] >= 0.0 || ((uint32_t)nw == w && (uint32_t)nr == r10)) continue;
+                    ws.push_back((uint32_t)nw); rs.push_back((uint32_t)nr);
+                }
         const uint32_t nb = (uint32_t)ws.size();
         const size_t xwords = ((size_t)nb * words + 3) & ~(size_t)3;     // results start 16-byte aligned
         if ((err = kvp_ensure(ctx, (void **)&ctx->d_policy_x, &ctx->policy_x_cap, xwords * 4 + (size_t)nb * 16)))
