@@ -21,7 +21,8 @@
 //     on the layer and stay in registers for the whole kernel.
 //   * Step latencies are summed on the fly when L is a power of two (bit-reversed
 //     layer order, binary counter of partial sums: the 64-wide tree of the
-//     definition); otherwise they go to a [S][L][N] array that a second kernel sums.
+//     definition) and when L = 2^k q with 3 <= k <= 5 and q in {3, 5, 7} (see
+//     MIXED below); otherwise they go to a [S][L][N] array that a second kernel sums.
 #include "kvp_internal.h"
 
 namespace {
@@ -62,7 +63,22 @@ __global__ __launch_bounds__(256) void bitslice_kernel(DevProblem q, uint32_t KB
     for (uint32_t j = 0; j < KB; j++) Aw[(row * KB + j) * q.Wd + w] = d[j];
 }
 
-// XV: 16-byte vectors per lane and pass (33 rows); KB: digit planes; POW2: L is a power of two >= 2.
+// How the step latencies of a tile reach the 64-wide summation tree.
+//   SPILL: written to a [S][L][N] array; a second kernel sums them.
+//   POW2:  L = 2^k <= 64.  Position g = n L + l has the layer in its low k bits, so the tree first
+//          joins the 64 / L steps of a block (cross-lane adds) and then layers that differ in bit
+//          k-1, k-2, ...: with the layers visited in bit-reversed order that is a binary counter of
+//          k partial sums per lane.
+//   MIXED: L = 2^k q, q odd.  Write l = 2^k lh + ll; then g = 2^k (q n + lh) + ll, so for a fixed ll
+//          the values m = q n + lh = 0, 1, 2, ... of a tile fall into the blocks c = 64 / 2^k at a
+//          time (block m / c, upper tree bits m % c), and the 64 q values of a tile make exactly L
+//          blocks.  Layers are visited ll-major (ll bit-reversed, lh = 0 .. q-1 inside): after the q
+//          layers of one ll a wavefront has 64 q latencies in LDS, every lane adds the c values of
+//          "its" blocks in tree order, and the partial block sums of the 2^k values of ll meet in a
+//          binary counter as above, kept in LDS (k levels of L sums).
+enum { SPILL = 0, POW2 = 1, MIXED = 2 };
+
+// XV: 16-byte vectors per lane and pass (33 rows); KB: digit planes; MODE: see above.
 // No load is consumed in the pass that issues it, and all are unconditional: offsets that would
 // leave the schedule (or the planes) are clamped, and what they fetch is never used.
 //
@@ -71,12 +87,13 @@ __global__ __launch_bounds__(256) void bitslice_kernel(DevProblem q, uint32_t KB
 // counters of step 32 h2 + r, "its own" step: Eqs. 2-4, the occupancy and the summation tree then
 // run once per layer with all 64 lanes busy.  The masked words at the end of a row are taken by the
 // lane that owns the row.
-template <int XV, int KB, bool POW2>
+template <int XV, int KB, int MODE>
 __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
     DevProblem q, const uint32_t *__restrict__ Aw, const uint32_t *__restrict__ X, uint32_t S, uint32_t tiles,
-    uint32_t nb_total, uint32_t log2L, uint32_t pfw2, double *__restrict__ blocksum, double *__restrict__ tglobal,
+    uint32_t nb_total, uint32_t log2L, uint32_t qodd, uint32_t pfw2, double *__restrict__ blocksum, double *__restrict__ tglobal,
     uint32_t *__restrict__ tileflag, uint32_t *__restrict__ counters, uint32_t *__restrict__ occ_out) {
     extern __shared__ double smem_d[];
+    constexpr int UN = (KB >= 2 && MODE != MIXED) ? 4 : 8;             // unroll of the word loop
     constexpr int TV = (KB * XV * 8 + 32) / 33;                        // trace vectors per thread and pass
     const uint32_t L = q.L, N = q.N, Wd = q.Wd;
     // LDS row stride = 2 (mod 4): the LDS serves 32 lanes per cycle from 32 banks, and lanes (r, h2),
@@ -98,6 +115,9 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
     const uint32_t rows = min(64u, N - n0);
     uint32_t *xbuf = (uint32_t *)smem_d + (size_t)wave * (RR + 1) * RS;
     uint32_t *tbuf = (uint32_t *)smem_d + (size_t)RQ * (RR + 1) * RS;  // two slots of KB * TPL words
+    // MIXED: the wavefront's 64 q latencies of one ll, then its k levels of L partial block sums
+    double *stage = (double *)(tbuf + 2 * KB * TPL) + (size_t)wave * (64 * qodd + log2L * L);
+    double *level = stage + 64 * qodd;
     const uint32_t r = (uint32_t)lane >> 1, h2 = (uint32_t)lane & 1u;
     const uint32_t tw = Wd - pfw2;                                     // masked words at the end of a row (<= TWMAX)
 
@@ -142,7 +162,16 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
     Stage st0, st1;
     uint32_t acc_nx = 0;                                               // read units of the lane's step, next layer
     r4u tr[TV];
-    auto layer_of = [&](uint32_t i) { return POW2 ? (__brev(i) >> (32 - log2L)) : i; };
+    // i-th layer in visiting order (i / q by a multiplication: exact for i < 256, q <= 7; the host checks)
+    const uint32_t qinv = 65536u / qodd + 1u;
+    auto layer_of = [&](uint32_t i) {
+        if (MODE == POW2) return __brev(i) >> (32 - log2L);
+        if (MODE == MIXED) {
+            const uint32_t vi = (i * qinv) >> 16, lh = i - vi * qodd;
+            return (lh << log2L) + (__brev(vi) >> (32 - log2L));
+        }
+        return i;
+    };
     // Addresses are a wavefront-uniform base plus a 32-bit byte offset per lane (the host checks
     // that a schedule and the digit planes stay below 4 GiB).  A pass whose 33 rows all lie inside the
     // schedule (no step before step 0, no steps past the trace) needs no clamping.
@@ -201,7 +230,7 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
         for (int k = 0; k < KB; k++) hrk[k] = 0;
         // (a deeper unroll keeps more LDS words in flight per wavefront; with several planes the
         // registers are better spent on a third wavefront per SIMD)
-#pragma unroll KB >= 2 ? 4 : 8
+#pragma unroll UN
         for (uint32_t j = 0; j < nfull; j++) {
             const uint32_t w = 2 * j + hv;
             const uint32_t raw = cur[w], d = raw ^ prv[w];
@@ -246,7 +275,7 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
         occ_acc += oc;
         if (counters && has_s && active)
             *(uint4 *)(counters + (((size_t)s * L + l) * N + n) * 4) = make_uint4(hr, hw, mi, mo);
-        if (POW2) {
+        if (MODE == POW2) {
             // folds of the summation tree that join the steps of one block (steps are two lanes apart)
             for (uint32_t m = (64u >> log2L) >> 1; m >= 1; m >>= 1) t = fold_xor_f64(t, 2 * m);
             // folds that join layers: binary counter over the bit-reversed visiting order
@@ -260,6 +289,40 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
                 }
             }
             if (!parked) total = carry;                                // only at the last layer
+        } else if (MODE == MIXED) {
+            const uint32_t vi = (i * qinv) >> 16, lh = i - vi * qodd, c = 64u >> log2L;
+            stage[qodd * rho + lh] = t;
+            if (lh == qodd - 1) {                                      // the q layers of this ll are in
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (uint32_t b = 0; b < 2; b++) {
+                    const uint32_t B = (uint32_t)lane + 64u * b;       // block of the tile
+                    if (B < L) {
+                        double v[8];
+#pragma unroll
+                        for (uint32_t j = 0; j < 8; j++) v[j] = j < c ? stage[c * B + j] : 0.0;   // + 0.0 changes nothing
+#pragma unroll
+                        for (uint32_t h = 4; h >= 1; h >>= 1)
+#pragma unroll
+                            for (uint32_t j = 0; j < h; j++) v[j] = v[j] + v[j + h];
+                        double carry = v[0];
+                        bool parked = false;
+#pragma unroll
+                        for (uint32_t j = 0; j < 5; j++) {
+                            if (!parked && j < log2L) {
+                                if (((vi >> j) & 1u) == 0) { level[j * L + B] = carry; parked = true; }
+                                else carry = level[j * L + B] + carry;
+                            }
+                        }
+                        // only after the last ll; blocks past the end of the trace do not exist
+                        if (!parked && has_s && 64u * B < rows * L) blocksum[(size_t)s * nb_total + (size_t)tile * L + B] = carry;
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
         } else if (has_s && active) {
             tglobal[((size_t)s * L + l) * N + n] = t;
         }
@@ -277,7 +340,7 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
         layer_end(i, acc_n);
     }
     if (!has_s) return;
-    if (POW2) {
+    if (MODE == POW2) {
         const uint32_t bpl = 64u >> log2L;                             // block b of the tile: steps [b*bpl, (b+1)*bpl)
         if ((r & (bpl - 1)) == 0 && rho < rows) blocksum[(size_t)s * nb_total + (size_t)tile * L + rho / bpl] = total;
     }
@@ -336,11 +399,20 @@ int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint3
     uint32_t log2L = 0;
     while ((1u << log2L) < q.L) log2L++;
     const bool pow2 = q.L >= 2 && q.L <= 64 && (1u << log2L) == q.L;
-    const size_t lds = ((size_t)RQ * (RR + 1) * RS + 2 * (size_t)KB * RR * RS) * 4;
+    // L = 2^k q with q odd: summed on chip for 3 <= k <= 5, q in {3, 5, 7}, L <= 128
+    uint32_t k2 = 0;
+    while (!((q.L >> k2) & 1u)) k2++;
+    const uint32_t qodd = q.L >> k2;
+    bool mixed = !pow2 && k2 >= 3 && k2 <= 5 && qodd >= 3 && qodd <= 7 && q.L <= 128;
+    for (uint32_t i = 0; mixed && i < q.L; i++) mixed = ((i * (65536u / qodd + 1u)) >> 16) == i / qodd;
+    size_t lds = ((size_t)RQ * (RR + 1) * RS + 2 * (size_t)KB * RR * RS) * 4;
+    if (mixed) lds += (size_t)RQ * (64 * qodd + k2 * q.L) * sizeof(double);
     if (lds > 160 * 1024) return 1;
     const uint64_t nwg = (uint64_t)((S + RQ - 1) / RQ) * ((tiles + 7) / 8) * 8;   // whole rounds over the XCDs
     if (nwg > 0x7FFFFFFFull) return 1;
-    if (!pow2) {
+    const int mode = pow2 ? POW2 : mixed ? MIXED : SPILL;
+    if (mode == MIXED) log2L = k2;
+    if (mode == SPILL) {
         int rc = kvp_ensure(ctx, (void **)&ctx->d_tglobal, &ctx->tglobal_cap, (size_t)S * q.L * q.N * sizeof(double));
         if (rc) return rc;
     }
@@ -351,10 +423,15 @@ int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint3
             KVP_HIP(hipFuncSetAttribute((const void *)score_rowblock_kernel<XX, KK, PP>,                            \
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                    \
         score_rowblock_kernel<XX, KK, PP><<<grid, block, lds, ctx->stream>>>(                                       \
-            q, ctx->aw, X, S, tiles, nb_total, log2L, pfw2, ctx->d_blocksum, ctx->d_tglobal, ctx->d_tileflag,      \
+            q, ctx->aw, X, S, tiles, nb_total, log2L, qodd, pfw2, ctx->d_blocksum, ctx->d_tglobal, ctx->d_tileflag,      \
             counters, occ);                                                                                         \
     } while (0)
-#define KVP_P(XX, KK) do { if (pow2) KVP_GO(XX, KK, true); else KVP_GO(XX, KK, false); } while (0)
+#define KVP_P(XX, KK)                                                                                               \
+    do {                                                                                                            \
+        if (mode == POW2) KVP_GO(XX, KK, POW2);                                                                     \
+        else if (mode == MIXED) KVP_GO(XX, KK, MIXED);                                                              \
+        else KVP_GO(XX, KK, SPILL);                                                                                 \
+    } while (0)
 #define KVP_K(KK) case KK: if (xv == 5) KVP_P(5, KK); else KVP_P(9, KK); break;
     switch (KB) {
         KVP_K(1) KVP_K(2) KVP_K(3) KVP_K(4)
@@ -365,6 +442,6 @@ int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint3
 #undef KVP_GO
     KVP_HIP(hipGetLastError());
     ctx->last_kernel = KVP_SCORE_ROWBLOCK;
-    if (!pow2) return kvp_blocksum_from_t_launch(ctx, S, nb_total);
+    if (mode == SPILL) return kvp_blocksum_from_t_launch(ctx, S, nb_total);
     return KVP_OK;
 }

@@ -56,6 +56,12 @@ def _cases():
     yield "dec-w16-L30", _decode(36, L=30, N=70, words=15, page_tokens=8)     # step latencies too many for the LDS at hand
     yield "dec-w24-tail", _decode(35, L=2, N=200, words=18, page_tokens=1)     # 200 new pages: too many masked words
     yield "gqa70b/2", W.config("gqa70b", 0.5)                              # 17 words, 8 planes -> 4 digits, 40 layers
+    # layer counts 2^k q whose summation tree stays on chip: block boundaries fall inside a token step
+    yield "dec-L80-k8", _decode(37, L=80, N=130, words=32, page_tokens=2, K=8)     # 80 = 16 * 5, three tiles, the last of 2 steps
+    yield "dec-L24", _decode(38, L=24, N=70, words=19, page_tokens=4)              # 8 * 3
+    yield "dec-L48", _decode(39, L=48, N=65, words=17, page_tokens=4)              # 16 * 3
+    yield "dec-L96", _decode(40, L=96, N=64, words=16, page_tokens=4)              # 32 * 3: more blocks than lanes
+    yield "dec-L112", _decode(41, L=112, N=40, words=20, page_tokens=4, K=2)       # 16 * 7, one short tile
 
 
 def _decode(seed, L, N, words, page_tokens, K=1, plane_bytes=None):
@@ -72,7 +78,8 @@ def _decode(seed, L, N, words, page_tokens, K=1, plane_bytes=None):
 CASES = list(_cases())
 # scorers that must run natively (not be replaced by another) on a case
 NATIVE = {
-    "rowblock": {"longctx/2", "gqa70b/2", "dec-w21-L3", "dec-w38-k3", "dec-w68-k2", "dec-w16", "dec-w16-L30"},
+    "rowblock": {"longctx/2", "gqa70b/2", "dec-w21-L3", "dec-w38-k3", "dec-w68-k2", "dec-w16", "dec-w16-L30",
+                 "dec-L80-k8", "dec-L24", "dec-L48", "dec-L96", "dec-L112"},
     "chunk": {"rand-wide", "rand-w40", "rand-w300", "rand-w301", "longctx/4", "longctx/2", "rand-w16", "dec-w24-tail"},
     "line": {"rand-wide", "rand-w40", "rand-w300", "rand-w301", "longctx/2", "dec-w38-k3", "dec-w68-k2"},
     "rows": {c[0] for c in CASES},
