@@ -208,7 +208,7 @@ int kvp_set_score_kernel(kvp_ctx *ctx, int which);
  * not cover the trace's shape is replaced by one that does: this tells which. */
 int kvp_score_kernel_used(const kvp_ctx *ctx);
 
-/* Two placements that need no search, to start one from or to compare it with
+/* Three placements that need no search, to start one from or to compare it with
  * (the evaluation section of the paper sets its search against a static and a
  * reactive least-recently-used placement; these are their counterparts on this
  * problem's terms: a pool of cap_pages shared by the layers, whole pages, no
@@ -219,13 +219,19 @@ int kvp_score_kernel_used(const kvp_ctx *ctx);
  *   KVP_BASELINE_RECENCY: at step n the pool holds the cap_pages existing pairs
  *     read most recently before n (never read: oldest); a page that stops
  *     persisting forgets its history.
- * Ties go to the lower l * n_pages + p in both.  d_placement: DEVICE, one
+ *   KVP_BASELINE_FILL:    the paper's "Static Placement": an entry is placed when
+ *     it is first written and never moves, HBM first while there is room.  Step
+ *     by step, pages that stop persisting give their place back, then the pages
+ *     new at this step take the free places in the order of l * n_pages + p
+ *     (layer after layer, as a prefill writes them); the rest stay outside for
+ *     as long as they live.
+ * Ties go to the lower l * n_pages + p in the first two.  d_placement: DEVICE, one
  * schedule [L][N][Wd] uint32, written in full; the caller owns it.  The result
  * never exceeds the capacity.  Runs on the context's stream.
  * Errors: KVP_EINVAL (null or misaligned pointer, unknown kind), KVP_ENOTRACE,
- * KVP_ESHAPE (more than 32767 steps, or steps x planes above 32767, for the
- * histogram of the selection), KVP_ENOMEM, KVP_EHIP. */
-enum { KVP_BASELINE_STATIC = 0, KVP_BASELINE_RECENCY = 1 };
+ * KVP_ESHAPE (STATIC, RECENCY: more than 32767 steps, or steps x planes above
+ * 32767, for the histogram of the selection), KVP_ENOMEM, KVP_EHIP. */
+enum { KVP_BASELINE_STATIC = 0, KVP_BASELINE_RECENCY = 1, KVP_BASELINE_FILL = 2 };
 int kvp_baseline(kvp_ctx *ctx, int kind, uint32_t *d_placement);
 
 /* ---- the paper's own search: a look-ahead policy with two scalars (Sec. III-B) ----

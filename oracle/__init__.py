@@ -91,6 +91,7 @@ def lib():
                                   C.c_void_p, C.c_void_p, C.POINTER(C.c_int)]
         L.orc_init_static_frequency.argtypes = [C.POINTER(_Problem), C.c_void_p]
         L.orc_init_recency.argtypes = [C.POINTER(_Problem), C.c_void_p]
+        L.orc_init_static_fill.argtypes = [C.POINTER(_Problem), C.c_void_p]
         L.orc_bruteforce.restype = C.c_int
         L.orc_bruteforce.argtypes = [C.POINTER(_Problem), C.POINTER(C.c_double), C.c_void_p,
                                      C.POINTER(C.c_uint64)]
@@ -240,6 +241,13 @@ def init_recency(tr) -> np.ndarray:
     q = _problem(tr)
     X = np.zeros(q.shape, dtype=np.uint8)
     lib().orc_init_recency(C.byref(q.c), X.ctypes.data)
+    return X
+
+
+def init_static_fill(tr) -> np.ndarray:
+    q = _problem(tr)
+    X = np.zeros(q.shape, dtype=np.uint8)
+    lib().orc_init_static_fill(C.byref(q.c), X.ctypes.data)
     return X
 
 

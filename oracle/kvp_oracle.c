@@ -402,6 +402,32 @@ void orc_init_recency(const orc_problem *q, uint8_t *X) {
     free(last); free(it);
 }
 
+/* Static fill (the paper's "Static Placement", Sec. IV-A): an entry is placed
+ * when it is first written and never moves; HBM is taken while there is room.
+ * Reading for a pool shared by all layers and for slots that are re-used: step
+ * by step, pages that stop persisting give their place back; then the pages new
+ * at this step (existing, not persisting) take the free places in the order of
+ * l*P+p (layer after layer, as a prefill writes them), the rest stay outside
+ * for as long as they live. */
+void orc_init_static_fill(const orc_problem *q, uint8_t *X) {
+    int L = q->L, N = q->N, P = q->P;
+    size_t M = (size_t)L * P;
+    uint8_t *in = (uint8_t *)calloc(M ? M : 1, 1);
+    uint64_t occ = 0;
+    for (int n = 0; n < N; n++) {
+        for (size_t i = 0; i < M; i++)
+            if (in[i] && !(n > 0 && pm_bit(q, n, (int)(i % (size_t)P)))) { in[i] = 0; occ--; }
+        for (size_t i = 0; i < M; i++) {
+            int p = (int)(i % (size_t)P);
+            int is_new = v_bit(q, n, p) && !(n > 0 && pm_bit(q, n, p));
+            if (is_new && occ < q->cap_pages) { in[i] = 1; occ++; }
+        }
+        for (int l = 0; l < L; l++)
+            for (int p = 0; p < P; p++) X[ix_x(q, l, n, p)] = in[(size_t)l * P + p];
+    }
+    free(in);
+}
+
 /* ---- exhaustive optimum (tiny instances only) ------------------------------
  * Enumerates every assignment of the existing (layer, step, page) bits; returns
  * the cheapest capacity-feasible schedule (first one found on ties). */

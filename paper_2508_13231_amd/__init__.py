@@ -225,7 +225,7 @@ def kvp_set_score_kernel(ctx, which: int):
     _check(lib().kvp_set_score_kernel(ctx, int(which)), "kvp_set_score_kernel")
 
 
-KVP_BASELINE_STATIC, KVP_BASELINE_RECENCY = 0, 1
+KVP_BASELINE_STATIC, KVP_BASELINE_RECENCY, KVP_BASELINE_FILL = 0, 1, 2
 
 
 def kvp_wr_policy(ctx, ws, r10s, d_placements):

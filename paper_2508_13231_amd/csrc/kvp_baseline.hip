@@ -1,7 +1,10 @@
-// Two foresight-free placements to start a search from or to compare it with:
-// a static one (the pages read most often over the whole trace stay in HBM for
-// as long as they exist; nothing migrates) and a recency one (at every token step
-// the pool holds the existing pages read most recently, LRU order).  Both are
+// Foresight-free placements to start a search from or to compare it with: a
+// static one (the pages read most often over the whole trace stay in HBM for
+// as long as they exist; nothing migrates), a recency one (at every token step
+// the pool holds the existing pages read most recently, LRU order) and a fill
+// one (pages take HBM in the order in which they are written while there is
+// room, and never move: the "Static Placement" of the paper's evaluation; see
+// fill_kernel).  The first two are
 // "the cap_pages (layer, page) pairs with the largest key, ties to the lower
 // l * P + p", once for the static placement and once per token step for the
 // recency placement; the evaluation section of the paper compares its search with
@@ -89,20 +92,88 @@ __global__ __launch_bounds__(BT) void recency_kernel(DevProblem q, uint64_t cap,
     }
 }
 
+// Static fill, step after step, in one workgroup.  The state is one mask word per (layer, word):
+// the pages now in HBM.  Per step: entries that stop persisting leave (AND with the persist word),
+// the survivors are counted, and the pages new at this step take the free places in the order of
+// l * P + p: a running count over the words, in chunks of BT words, finds the word at which the room
+// ends.  Thread t owns the words t, t + BT, ... in every pass, so the state needs no barrier of its own.
+__global__ __launch_bounds__(BT) void fill_kernel(DevProblem q, uint64_t cap, uint32_t *__restrict__ in,
+                                                  uint32_t *__restrict__ X) {
+    __shared__ uint32_t wave_sum[BW];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t NW = q.L * q.Wd;
+    // sum over the workgroup (every thread gets it) and, optionally, the sum over the threads before this one
+    auto block_scan = [&](uint32_t v, uint32_t *before) {
+        uint32_t inc = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(inc, d, 64);
+            if ((int)lane >= d) inc += o;
+        }
+        __syncthreads();                                               // wave_sum of the previous call is read
+        if (lane == 63) wave_sum[wave] = inc;
+        __syncthreads();
+        uint32_t total = 0, pre = 0;
+        for (uint32_t w = 0; w < (uint32_t)BW; w++) {
+            const uint32_t x = wave_sum[w];
+            if (w < wave) pre += x;
+            total += x;
+        }
+        if (before) *before = pre + inc - v;
+        return total;
+    };
+    for (uint32_t i = tid; i < NW; i += BT) in[i] = 0;
+    for (uint32_t n = 0; n < q.N; n++) {
+        uint32_t mine = 0;
+        for (uint32_t i = tid; i < NW; i += BT) {
+            const uint32_t w = i % q.Wd;
+            const uint32_t v = n ? in[i] & q.Pm[(size_t)n * q.Wd + w] : 0u;
+            in[i] = v;
+            mine += __popc(v);
+        }
+        const uint32_t occ = block_scan(mine, nullptr);
+        uint64_t room = cap > occ ? cap - occ : 0;
+        for (uint32_t base = 0; base < NW; base += BT) {               // same trip count for every thread
+            const uint32_t i = base + tid;
+            const bool has = i < NW;
+            const uint32_t l = has ? i / q.Wd : 0, w = has ? i - l * q.Wd : 0;
+            uint32_t v = has ? in[i] : 0u;
+            if (room != 0) {                                           // uniform
+                const uint32_t fresh = has ? q.V[(size_t)n * q.Wd + w] & ~(n ? q.Pm[(size_t)n * q.Wd + w] : 0u) : 0u;
+                uint32_t before;
+                const uint32_t total = block_scan(__popc(fresh), &before);
+                uint32_t take = 0;
+                if (before + __popc(fresh) <= room) {
+                    take = fresh;
+                } else if (before < room) {                            // the word at which the room ends
+                    uint32_t rest = fresh;
+                    for (uint64_t c = room - before; c != 0; c--) { const uint32_t b = rest & (0u - rest); take |= b; rest ^= b; }
+                }
+                v |= take;
+                room -= room < total ? room : total;
+            }
+            if (has) {
+                in[i] = v;
+                X[((size_t)l * q.N + n) * q.Wd + w] = v;
+            }
+        }
+    }
+}
+
 }  // namespace
 
 extern "C" int kvp_baseline(kvp_ctx *ctx, int kind, uint32_t *d_placement) {
     if (!ctx) return KVP_EINVAL;
     if (!ctx->has_trace) return KVP_ENOTRACE;
     if (!d_placement || ((uintptr_t)d_placement & 3u)) return KVP_EINVAL;
-    if (kind != KVP_BASELINE_STATIC && kind != KVP_BASELINE_RECENCY) return KVP_EINVAL;
+    if (kind != KVP_BASELINE_STATIC && kind != KVP_BASELINE_RECENCY && kind != KVP_BASELINE_FILL) return KVP_EINVAL;
     KVP_HIP(hipSetDevice(ctx->device));
     const DevProblem &q = ctx->dp;
     const uint64_t G64 = (uint64_t)q.L * q.Wd * 32;
     if (G64 >= (1ull << 31)) return KVP_ESHAPE;
     const uint32_t G = (uint32_t)G64;
     const uint64_t cap = ctx->prob.cap_pages;
-    const uint32_t nbins = kind == KVP_BASELINE_STATIC ? q.N * q.K + 1 : q.N + 1;
+    const uint32_t nbins = kind == KVP_BASELINE_STATIC ? q.N * q.K + 1 : kind == KVP_BASELINE_RECENCY ? q.N + 1 : 0;
     const size_t lds = (size_t)nbins * 4;
     if (lds > 128 * 1024) return KVP_ESHAPE;
     int rc = kvp_ensure(ctx, (void **)&ctx->d_cnt_tmp, &ctx->cnt_tmp_cap, (size_t)G * 4 + (size_t)q.L * q.Wd * 4);
@@ -118,6 +189,9 @@ extern "C" int kvp_baseline(kvp_ctx *ctx, int kind, uint32_t *d_placement) {
         KVP_HIP(hipGetLastError());
         const size_t words = (size_t)q.L * q.N * q.Wd;
         static_fill_kernel<<<dim3((uint32_t)((words + 255) / 256)), dim3(256), 0, ctx->stream>>>(q, chosen, d_placement);
+        KVP_HIP(hipGetLastError());
+    } else if (kind == KVP_BASELINE_FILL) {
+        fill_kernel<<<dim3(1), dim3(BT), 0, ctx->stream>>>(q, cap, work, d_placement);
         KVP_HIP(hipGetLastError());
     } else {
         if (lds > 48 * 1024)

@@ -309,7 +309,7 @@ BASELINE_CASES = ("tiny", "table1", "llama8b/4", "longctx/8", "serving/16", "gqa
 
 
 @pytest.mark.parametrize("name,tr", [c for c in CASES if c[0] in BASELINE_CASES], ids=lambda v: v if isinstance(v, str) else "")
-@pytest.mark.parametrize("kind", ["static", "recency"])
+@pytest.mark.parametrize("kind", ["static", "recency", "fill"])
 def test_baseline_placements_match_oracle(G, name, tr, kind):
     """Bit for bit, and for the capacities at which the selection has nothing to decide."""
     import dataclasses
@@ -317,9 +317,10 @@ def test_baseline_placements_match_oracle(G, name, tr, kind):
     peak = int(tr.alive.sum(axis=1).max()) * tr.L
     for cap in (tr.cap_pages, 0, 1, peak - 1, peak, tr.L * tr.P + 5):
         t2 = dataclasses.replace(tr, cap_pages=max(0, cap))
-        want = O.init_static_frequency(t2) if kind == "static" else O.init_recency(t2)
+        want = {"static": O.init_static_frequency, "recency": O.init_recency, "fill": O.init_static_fill}[kind](t2)
         with G(t2) as g:
-            got = g.baseline(K.KVP_BASELINE_STATIC if kind == "static" else K.KVP_BASELINE_RECENCY)
+            got = g.baseline({"static": K.KVP_BASELINE_STATIC, "recency": K.KVP_BASELINE_RECENCY,
+                              "fill": K.KVP_BASELINE_FILL}[kind])
         assert got.shape == want.shape and (got == want.astype(bool)).all(), (name, kind, cap)
         assert int(got.sum(axis=(0, 2)).max()) <= t2.cap_pages
 

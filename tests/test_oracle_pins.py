@@ -398,6 +398,39 @@ def test_static_and_recency_placements_by_hand():
     assert rc[0].tolist() == [[1, 0, 0], [1, 0, 0], [0, 1, 0], [0, 1, 0]]
 
 
+def test_static_fill_by_hand():
+    # two layers, three page slots, room for three pages.  Step 0: pages 0 and 1 exist in both layers and take
+    # the places in the order (l0,p0) (l0,p1) (l1,p0); (l1,p1) stays outside for good.  Step 1: page 2 is
+    # born: no room.  Step 2: slot 0 is re-used by new data: both old entries leave (one place was taken,
+    # (l0,p0)), the new (l0,p0) takes it again, and with (l1,p0) gone one more place is free for (l1,p0) new.
+    tr = _mini(L=2, N=4, P=3, cap=3)
+    tr.alive[:] = [[1, 1, 0], [1, 1, 1], [1, 1, 1], [0, 1, 1]]
+    tr.persist[:] = [[0, 0, 0], [1, 1, 0], [0, 1, 1], [0, 1, 1]]
+    X = O.init_static_fill(tr)
+    assert X[0].tolist() == [[1, 1, 0], [1, 1, 0], [1, 1, 0], [0, 1, 0]]
+    assert X[1].tolist() == [[1, 0, 0], [1, 0, 0], [1, 0, 0], [0, 0, 0]]
+
+
+@pytest.mark.parametrize("name,scale", [("tiny", 1.0), ("llama8b", 0.25), ("serving", 0.0625)])
+def test_static_fill_never_migrates_and_fills_what_fits(name, scale):
+    tr = W.config(name, scale)
+    X = O.init_static_fill(tr)
+    r = O.score(tr, X)
+    assert r.feasible
+    assert not (X & ~tr.alive[None]).any()
+    assert int(r.step_bytes[..., 4].sum()) == 0 and int(r.step_bytes[..., 5].sum()) == 0     # nothing moves in or out
+    occ = X.sum(axis=(0, 2))
+    # a page outside HBM while there is room can only be one that was born when there was none
+    born = tr.alive.astype(bool) & ~tr.persist.astype(bool)
+    born[0] = tr.alive[0].astype(bool)
+    for n in range(tr.N):
+        if occ[n] < tr.cap_pages:
+            assert not (born[n][None] & ~X[:, n].astype(bool)).any()
+    # with room for everything, everything that exists is inside
+    import dataclasses
+    assert (O.init_static_fill(dataclasses.replace(tr, cap_pages=tr.L * tr.P)) == np.broadcast_to(tr.alive[None], X.shape)).all()
+
+
 # ---- the (W, R) look-ahead policy and its search (Sec. III-B), pinned to the reading stated in the oracle ----
 
 def _wr_mini():
