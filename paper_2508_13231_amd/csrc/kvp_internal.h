@@ -54,7 +54,7 @@ struct kvp_ctx {
     bool prefix_full = false;            // on every 64-step tile all mask words but the last are FULL
     uint32_t pfw = 0;                    // leading mask words that are FULL on every 64-step tile
     const uint32_t *aw = nullptr;        // [L][N][kb][Wd] binary digits of the pages' read weights (may alias A)
-    uint32_t kb = 0;                     // digit planes, 0 if the weights need more than four
+    uint32_t kb = 0;                     // digit planes, 0 if the weights need more than five
     uint32_t *d_aw = nullptr;            // owned storage of aw when it is not A
     uint32_t *d_trace = nullptr;         // one allocation: A, V, Pm, Wm, acc, wr
     // scoring scratch

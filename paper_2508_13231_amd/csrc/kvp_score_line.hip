@@ -274,6 +274,7 @@ int kvp_score_line_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t 
     const DevProblem &q = ctx->dp;
     if (!ctx->aw || !ctx->d_empty32 || q.Wd < LCW) return 1;
     const uint32_t KB = ctx->kb;
+    if (KB > 4) return 1;                                             // registers: five counters per step and digit
     if ((size_t)q.L * q.N * q.Wd * KB >= (1ull << 30)) return 1;      // 32-bit byte offsets inside a schedule and the planes
     uint32_t log2L = 0;
     while ((1u << log2L) < q.L) log2L++;

@@ -359,7 +359,8 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
 int kvp_blocksum_from_t_launch(kvp_ctx *ctx, uint32_t S, uint32_t nb_total);
 
 // Digit planes of the read weights, built once per trace.  Leaves ctx->d_aw null (and the scorer
-// above unavailable) when the weights need more than four digits.
+// above unavailable) when the weights need more than five digits (five: the tokens read in a page
+// of 16, with reads priced per token).
 int kvp_bitslice_build(kvp_ctx *ctx) {
     DevProblem &q = ctx->dp;
     ctx->aw = nullptr; ctx->kb = 0;
@@ -369,7 +370,7 @@ int kvp_bitslice_build(kvp_ctx *ctx) {
     for (uint32_t k = 0; k < q.K; k++) sum += q.wt[k];
     uint32_t kb = 0;
     while ((sum >> kb) != 0) kb++;
-    if (kb > 4) return KVP_OK;
+    if (kb > 5) return KVP_OK;
     if (q.K == 1 && q.wt[0] == 1) { ctx->aw = q.A; ctx->kb = 1; return KVP_OK; }
     const size_t words = (size_t)q.L * q.N * kb * q.Wd;
     KVP_HIP(hipMalloc((void **)&ctx->d_aw, words * 4));
@@ -434,7 +435,7 @@ int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint3
     } while (0)
 #define KVP_K(KK) case KK: if (xv == 5) KVP_P(5, KK); else KVP_P(9, KK); break;
     switch (KB) {
-        KVP_K(1) KVP_K(2) KVP_K(3) KVP_K(4)
+        KVP_K(1) KVP_K(2) KVP_K(3) KVP_K(4) KVP_K(5)
         default: return 1;
     }
 #undef KVP_K

@@ -56,12 +56,23 @@ def _cases():
     yield "dec-w16-L30", _decode(36, L=30, N=70, words=15, page_tokens=8)     # step latencies too many for the LDS at hand
     yield "dec-w24-tail", _decode(35, L=2, N=200, words=18, page_tokens=1)     # 200 new pages: too many masked words
     yield "gqa70b/2", W.config("gqa70b", 0.5)                              # 17 words, 8 planes -> 4 digits, 40 layers
+    # reads priced per token inside pages of 4 and 16 tokens: binary-weighted planes (3 and 5 digits)
+    yield "tok-p16", W.regroup(_tokens(42, L=8, N=64, prompt=1024), 16, "token")             # 3 words, 5 planes
+    yield "tok-p4-w20", W.regroup(_tokens(43, L=4, N=70, prompt=19 * 32 * 4), 4, "token")    # 20 words, 3 planes
+    yield "tok-p16-w17", W.regroup(_tokens(44, L=2, N=66, prompt=16 * 32 * 16), 16, "token") # 17 words, 5 planes
     # layer counts 2^k q whose summation tree stays on chip: block boundaries fall inside a token step
     yield "dec-L80-k8", _decode(37, L=80, N=130, words=32, page_tokens=2, K=8)     # 80 = 16 * 5, three tiles, the last of 2 steps
     yield "dec-L24", _decode(38, L=24, N=70, words=19, page_tokens=4)              # 8 * 3
     yield "dec-L48", _decode(39, L=48, N=65, words=17, page_tokens=4)              # 16 * 3
     yield "dec-L96", _decode(40, L=96, N=64, words=16, page_tokens=4)              # 32 * 3: more blocks than lanes
     yield "dec-L112", _decode(41, L=112, N=40, words=20, page_tokens=4, K=2)       # 16 * 7, one short tile
+
+
+def _tokens(seed, L, N, prompt):
+    """Token-level decode of one sequence (a page is a token), to be regrouped into pages."""
+    from workloads.traces import Recipe, generate
+    return generate(Recipe("tok", L=L, N=N, page_tokens=1, prompt_lo=prompt, prompt_hi=prompt, top_frac=0.15,
+                           sink_tokens=4, recent_tokens=8, cap_frac=0.3, seed=seed))
 
 
 def _decode(seed, L, N, words, page_tokens, K=1, plane_bytes=None):
@@ -79,11 +90,11 @@ CASES = list(_cases())
 # scorers that must run natively (not be replaced by another) on a case
 NATIVE = {
     "rowblock": {"longctx/2", "gqa70b/2", "dec-w21-L3", "dec-w38-k3", "dec-w68-k2", "dec-w16", "dec-w16-L30",
-                 "dec-L80-k8", "dec-L24", "dec-L48", "dec-L96", "dec-L112"},
+                 "dec-L80-k8", "dec-L24", "dec-L48", "dec-L96", "dec-L112", "tok-p4-w20", "tok-p16-w17"},
     "chunk": {"rand-wide", "rand-w40", "rand-w300", "rand-w301", "longctx/4", "longctx/2", "rand-w16", "dec-w24-tail"},
     "line": {"rand-wide", "rand-w40", "rand-w300", "rand-w301", "longctx/2", "dec-w38-k3", "dec-w68-k2"},
     "rows": {c[0] for c in CASES},
-    "lanes": {"tiny", "table1", "rand-odd", "rand-tiles", "gqa70b/16", "rand-512"},
+    "lanes": {"tiny", "table1", "rand-odd", "rand-tiles", "gqa70b/16", "rand-512", "tok-p16"},
     "direct": {"tiny", "table1", "llama8b/4", "rand-odd"},
     "wide": {"rand-wide", "rand-w40", "rand-w300", "rand-w301"},
     "quad": {"llama8b/4", "rand-L16", "rand-L64", "rand-L2"},
@@ -137,7 +148,7 @@ def test_score_every_schedule_of_a_micro_instance(G):
 
 @pytest.mark.parametrize("name,tr", [c for c in CASES if c[0] in
                                      ("tiny", "table1", "llama8b/4", "serving/16", "gqa70b/16", "rand-odd", "rand-fastdram",
-                                      "rand-weights")],
+                                      "rand-weights", "tok-p16")],
                          ids=lambda v: v if isinstance(v, str) else "")
 @pytest.mark.parametrize("given", [True, False])
 def test_delta_matches_oracle_bit_for_bit(G, name, tr, given):

@@ -431,6 +431,33 @@ def test_static_fill_never_migrates_and_fills_what_fits(name, scale):
     assert (O.init_static_fill(dataclasses.replace(tr, cap_pages=tr.L * tr.P)) == np.broadcast_to(tr.alive[None], X.shape)).all()
 
 
+# ---- token-granular reads inside pages: the plane encoding against the token-level definition ----
+
+def _token_trace(seed=9):
+    return W.generate(W.Recipe("tok", L=3, N=40, page_tokens=1, prompt_lo=200, prompt_hi=200, top_frac=0.3,
+                               sink_tokens=4, recent_tokens=8, cap_frac=0.3, seed=seed))
+
+
+@pytest.mark.parametrize("pt", [4, 16])
+def test_token_granular_reads_cost_what_their_tokens_cost(pt):
+    """A page placement scored on the regrouped trace moves, in reads and writes of every step, exactly the
+    bytes that the same placement moves token by token; reading whole pages moves at least as much."""
+    tok = _token_trace()
+    pg, whole = W.regroup(tok, pt, "token"), W.regroup(tok, pt, "page")
+    assert pg.K == pt.bit_length() and pg.plane_bytes == [tok.token_bytes << k for k in range(pg.K)]
+    assert pg.page_bytes == pt * tok.token_bytes and pg.cap_pages == tok.cap_pages // pt
+    touched = (np.add.reduceat(np.pad(tok.access[:, :, 0, :], ((0, 0), (0, 0), (0, pg.P * pt - tok.P))),
+                               np.arange(0, pg.P * pt, pt), axis=-1) > 0)
+    for x in W.random_placements(pg, 3, seed=3, density=0.4):
+        xt = np.repeat(x, pt, axis=-1)[..., :tok.P] & tok.alive[None]
+        a, b, w = O.score(pg, x).step_bytes, O.score(tok, xt).step_bytes, O.score(whole, x).step_bytes
+        assert (a[..., :4] == b[..., :4]).all()                       # hr, er, hw, ew
+        assert (a[..., 0] + a[..., 1] == tok.token_bytes * tok.access[:, :, 0, :].sum(axis=-1)).all()
+        assert (w[..., 0] + w[..., 1] == pg.page_bytes * touched.sum(axis=-1)).all()
+        assert (w[..., 0] >= a[..., 0]).all() and (w[..., 1] >= a[..., 1]).all()
+        assert (w[..., 2:] == a[..., 2:]).all()                       # writes and migration do not depend on the read model
+
+
 # ---- the (W, R) look-ahead policy and its search (Sec. III-B), pinned to the reading stated in the oracle ----
 
 def _wr_mini():

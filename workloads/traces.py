@@ -243,6 +243,51 @@ def generate(r: Recipe) -> Trace:
                  recipe=r)
 
 
+def regroup(tok: Trace, page_tokens: int, reads: str = "token") -> Trace:
+    """Pages of `page_tokens` consecutive tokens from a trace whose pages are single
+    tokens (a Recipe with page_tokens = 1; with several slots, slot_pages must be
+    a multiple of page_tokens).  Placement and migration are then per page, as
+    in the paper's page-granularity strategy (Sec. IV-A), and
+
+      reads = "page":   a page with any accessed token is read whole (the overhead
+                        of retrieving a page for a few important tokens), one plane;
+      reads = "token":  a page's read costs its accessed tokens only: plane k holds
+                        bit k of the number of accessed tokens in the page and
+                        weighs token_bytes * 2^k.
+
+    The capacity keeps its size in bytes (cap_pages = token capacity // page_tokens)."""
+    if tok.K != 1 or tok.page_bytes != tok.token_bytes or tok.plane_bytes != [tok.token_bytes]:
+        raise ValueError("regroup needs a trace whose pages are single tokens")
+    pt = int(page_tokens)
+    T = tok.P
+    P = -(-T // pt)
+
+    def group(a):
+        pad = P * pt - T
+        if pad:
+            a = np.concatenate([a, np.zeros(a.shape[:-1] + (pad,), a.dtype)], axis=-1)
+        return a.reshape(a.shape[:-1] + (P, pt))
+
+    counts = group(tok.access[:, :, 0, :]).sum(axis=-1, dtype=np.int64)          # [L][N][P]
+    alive = group(tok.alive).any(axis=-1).astype(np.uint8)
+    persist = group(tok.persist).any(axis=-1).astype(np.uint8)
+    written = group(tok.written).any(axis=-1).astype(np.uint8)
+    if reads == "page":
+        access = (counts > 0).astype(np.uint8)[:, :, None, :]
+        plane_bytes = [pt * tok.token_bytes]
+    elif reads == "token":
+        K = int(pt).bit_length()
+        access = np.stack([(counts >> k) & 1 for k in range(K)], axis=2).astype(np.uint8)
+        plane_bytes = [tok.token_bytes << k for k in range(K)]
+    else:
+        raise ValueError(reads)
+    return Trace(name=f"{tok.name}/p{pt}{reads[0]}", L=tok.L, N=tok.N, P=P, K=access.shape[2], access=access,
+                 alive=alive, persist=persist, written=written, plane_bytes=plane_bytes,
+                 page_bytes=pt * tok.token_bytes, token_bytes=tok.token_bytes, bw_hbm=tok.bw_hbm,
+                 bw_link=tok.bw_link, bw_dram=tok.bw_dram, cap_pages=tok.cap_pages // pt,
+                 chains=tok.chains, moves=tok.moves, seed=tok.seed, recipe=tok.recipe)
+
+
 def _ratio(r: float):
     return dict(bw_hbm=4.0e12, bw_link=4.0e12 / r, bw_dram=4.0e12 / r)
 
