@@ -90,6 +90,7 @@ def cpu_baseline(tr, X_sample, seconds):
         list(ex.map(lambda i: O.cost(q, X_sample[i]), idx))
     wall = time.perf_counter() - t0
     out = {"value": n * tr.N / wall, "unit": "token-steps/s", "cores": cores, "kind": "oracle",
+           "one_core_value": tr.N / t1,
            "sample": f"{n} schedule scorings of the same workload ({len(X_sample)} distinct schedules drawn "
                      f"from the GPU batch), {n * t1:.0f} s of single-core work spread over {cores} threads"}
     # annealing: one chain per core, a short budget
@@ -210,7 +211,7 @@ def main():
                                f"Wd={tr.n_words}, S={S} schedules ({S * tr.L * tr.N * tr.n_words * 4 / GIB:.2f} GiB), "
                                f"{C} chains x {M} moves per step, delta batch {D}",
                    "schedules": S, "chains": C, "moves_per_step": M},
-        "score_ms": score_ms, "score_ms_min": float(ph[:, 0].min()),
+        "score_ms": score_ms, "score_ms_median": float(np.median(ph[:, 0])), "score_ms_min": float(ph[:, 0].min()),
         "layer_steps_per_s": S * tr.N * tr.L / (score_ms * 1e-3),
         "roofline": {"bound": "hbm", "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK,
