@@ -206,6 +206,8 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
         for (int jt = 0; jt < TV; jt++) put4(dst + tlds[jt], tr[jt]);
     };
 
+    const uint32_t row_off = r * RS;
+    const bool very_first = n0 == 0 && r == 0;                         // the lane's row in pass 0 is step 0
     uint32_t fl_acc = 0, occ_acc = 0;
     double stk[6] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0}, total = 0.0;
     const uint32_t nfull = pfw2 >> 1;                                  // unmasked words per lane
@@ -220,10 +222,10 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
         __syncthreads();                                               // this pass's trace slot is complete
         // (addresses and masks below are rebuilt in every pass from these two copies: kept across the
         // layer loop they would occupy some sixty registers)
-        uint32_t rv = r, hv = h2;
-        asm volatile("" : "+v"(rv), "+v"(hv));
-        const uint32_t *cur = xbuf + (rv + 1) * RS, *prv = xbuf + ((p || !(n0 == 0 && rv == 0)) ? rv : 1u) * RS;
-        const uint32_t *ts = tbuf + p * KB * TPL + rv * RS;
+        uint32_t ro = row_off, hv = h2;                                // ro: the row's offset in a parked pass, words
+        asm volatile("" : "+v"(ro), "+v"(hv));
+        const uint32_t *cur = xbuf + RS + ro, *prv = xbuf + ((p == 0 && very_first) ? RS : ro);
+        const uint32_t *ts = tbuf + p * KB * TPL + ro;
         const bool own = hv == p;
         uint32_t hrk[KB], c_oc = 0, c_mi = 0, c_mg = 0;
 #pragma unroll
