@@ -217,6 +217,30 @@ def test_anneal_against_oracle_at_equal_budget(G, name, scale, chains, total, ma
     assert same == chains
 
 
+@pytest.mark.parametrize("name,total,ids", [("llama8b", 6000, (0, 3, 128, 255)), ("longctx", 1500, (0, 1023))])
+def test_full_size_anneal_sampled_chains_against_oracle(G, name, total, ids):
+    """The launch configuration of the benchmark (all chains of the config, the start broadcast);
+    the oracle walks a few of the chain ids and must arrive where the GPU's chains of those ids did."""
+    import paper_2508_13231_amd as K
+    tr = W.config(name)
+    q = O.Problem(tr)
+    X0 = W.random_placements(tr, 1, seed=tr.seed, density=0.25)[0]
+    res, _ = O.anneal(q, list(ids), X0, threads=len(ids), seed=tr.seed, total_moves=total)
+    with G(tr) as g:
+        _anneal_gpu(g, tr, tr.chains, total, init=X0, seed=tr.seed)
+        cost, chain, words, cc = K.kvp_best(g.ctx, g.shape_words, tr.chains)
+        stats = K.kvp_chain_stats(g.ctx, tr.chains)
+        bests = {c: g.unpack(K.kvp_chain_placement(g.ctx, c, 1, g.shape_words)) for c in ids}
+        curs = {c: g.unpack(K.kvp_chain_placement(g.ctx, c, 0, g.shape_words)) for c in ids}
+    assert cost == cc.min() and chain == int(np.argmin(cc))
+    assert all(st.moves_done == total for st in stats)
+    for i, c in enumerate(ids):
+        sb = O.score(q, bests[c])
+        assert sb.excess == 0 and sb.cost == cc[c]
+        assert abs(cc[c] - res[i].best_cost) <= 0.005 * res[i].best_cost
+        assert (curs[c] == res[i].X).all() and cc[c] == res[i].best_cost, (name, c)     # the same walk, move for move
+
+
 def test_anneal_resume_and_modes(G):
     import paper_2508_13231_amd as K
     tr = W.config("tiny")
