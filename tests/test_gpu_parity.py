@@ -468,6 +468,23 @@ def test_full_size_batch_sampled_against_oracle(G, name, kernel):
             X = g.unpack(d_x[s].cpu().numpy().view(np.uint32))
             r = O.score(q, X)
             assert cost[s] == r.cost and ex[s] == r.excess, s
+        if name == "llama8b":
+            # the benchmark's delta phase: one move on each schedule, counters resident
+            D = min(16384, S)
+            mv = W.random_moves(tr, D, seed=77)
+            d_mv = torch.from_numpy(W.moves_to_records(mv).view(np.int32)).to(g.dev)
+            d_cnt = torch.empty((D, tr.L, tr.N, 4), dtype=torch.int32, device=g.dev)
+            d_occ = torch.empty((D, tr.N), dtype=torch.int32, device=g.dev)
+            d_dt = torch.empty(D, dtype=torch.float64, device=g.dev)
+            d_ver = torch.empty(D, dtype=torch.int32, device=g.dev)
+            K.kvp_score(g.ctx, d_x, D, d_cost, d_ex, d_cnt, d_occ)
+            K.kvp_delta_score(g.ctx, d_x, D, d_mv, d_cnt, d_occ, d_dt, d_ver)
+            torch.cuda.synchronize()
+            dt, ver = d_dt.cpu().numpy(), d_ver.cpu().numpy()
+            for s2 in list(range(0, D, D // 40)) + [D - 1]:
+                X = g.unpack(d_x[s2].cpu().numpy().view(np.uint32))
+                ov, od, _, _, _ = O.delta(q, X, {k: int(v[s2]) for k, v in mv.items()})
+                assert ver[s2] == ov and dt[s2] == od, (s2, ver[s2], ov, dt[s2], od)
         # properties that hold for every schedule of the batch
         assert np.isfinite(cost).all() and (cost > 0).all()
         lo = O.cost(q, np.broadcast_to(tr.alive[None], q.shape).copy()) * tr.bw_hbm / (tr.bw_hbm + tr.bw_link)
