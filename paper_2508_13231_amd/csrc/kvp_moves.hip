@@ -112,43 +112,69 @@ __device__ __forceinline__ void page_effect(const PageBits &g, bool x_new, bool 
     }
 }
 
+// The first round trip of a move: every word, counter row and occupancy that pricing it may look
+// at, requested together.  Fields of a malformed record are clamped so that the requests are valid
+// and unconditional; `ok` tells.
+template <int NP>
+struct MoveLoads {
+    bool ok;                        // uniform: the record is well formed
+    PageWords<NP> gp, gq;           // the page, and the victim (a SET or SHIFT looks at the page itself again)
+    uint32_t oc, acc1, acc2, wr;
+    uint4 C1, C2;
+};
+
+template <int NP>
+__device__ __forceinline__ MoveLoads<NP> issue_move(const DevProblem &q, const uint32_t *X, const uint32_t *cnt,
+                                                    const uint32_t *occ, const kvp_move &m, int lane) {
+    MoveLoads<NP> Ld;
+    const uint32_t L = q.L, N = q.N;
+    Ld.ok = !(m.op > 2 || m.layer >= L || m.page >= q.P || m.n1 >= N || m.len < 1 || m.len > KVP_MAX_LEN ||
+              m.layer2 >= L || m.page2 >= q.P);
+    const uint32_t l = min(m.layer, L - 1), l2 = min(m.layer2, L - 1);
+    const uint32_t wp = min(m.page, q.P - 1) >> 5, wq = min(m.page2, q.P - 1) >> 5;
+    const bool swap = m.op == KVP_OP_SWAP;
+    // lane <-> step n1 + lane; steps past the trace shadow the last one
+    const uint32_t nc = min(min(m.n1, N - 1) + (uint32_t)lane, N - 1);
+    const uint32_t lv = swap ? l2 : l, wv = swap ? wq : wp;
+    Ld.gp = request_page<NP>(q, X, l, nc, wp);
+    Ld.gq = request_page<NP>(q, X, lv, nc, wv);
+    Ld.oc = occ[nc];
+    Ld.C1 = *(const uint4 *)(cnt + ((size_t)l * N + nc) * 4);
+    Ld.C2 = *(const uint4 *)(cnt + ((size_t)lv * N + nc) * 4);
+    Ld.acc1 = q.acc[(size_t)l * N + nc];
+    Ld.acc2 = q.acc[(size_t)lv * N + nc];
+    Ld.wr = q.wr[nc];
+    return Ld;
+}
+
 // Resolve a raw move against the schedule X (with its counters and occupancy)
-// and price it.  All 64 lanes of the wavefront must call this together.
-// `meanwhile` is run once, after the move's loads have been issued and before
-// anything waits for them: work that does not depend on the schedule (drawing the
-// next proposal) then costs no time of its own.
-template <int NP, class F>
-__device__ __forceinline__ MoveEval eval_move(const DevProblem &q, const uint32_t *X, const uint32_t *cnt,
-                                              const uint32_t *occ, const kvp_move &m, int lane, F meanwhile) {
+// and price it, from the words that issue_move requested.  All 64 lanes of the
+// wavefront must call this together.
+template <int NP>
+__device__ __forceinline__ MoveEval finish_move(const DevProblem &q, const uint32_t *X, const uint32_t *cnt,
+                                                const uint32_t *occ, const kvp_move &m, int lane, MoveLoads<NP> &Ld) {
     MoveEval R;
     R.verdict = KVP_MOVE_NULL; R.dT = 0.0; R.base = 0; R.flip1 = R.flip2 = 0; R.second = false;
     R.n = -1; R.f1 = R.f2 = R.touch1 = R.touch2 = R.xnew = false;
     R.c1 = make_uint4(0, 0, 0, 0); R.c2 = R.c1;
     const uint32_t L = q.L, N = q.N, cap = q.cap;
-    if (m.op > 2 || m.layer >= L || m.page >= q.P || m.n1 >= N || m.len < 1 || m.len > KVP_MAX_LEN ||
-        m.layer2 >= L || m.page2 >= q.P) {
-        meanwhile();
-        return R;
-    }
-    const uint32_t l = m.layer, n1 = m.n1, len = m.len, l2 = m.layer2;
-    const uint32_t wp = m.page >> 5, bp = m.page & 31, wq = m.page2 >> 5, bq = m.page2 & 31;
-    const bool swap = m.op == KVP_OP_SWAP;
-    const bool same_layer = l2 == l;
-
-    // lane <-> step n1 + lane; steps past the trace shadow the last one and count as absent
-    int n = (int)n1 + lane;
-    bool inb = n < (int)N;
-    uint32_t nc = inb ? (uint32_t)n : N - 1;
-    // every load of the move, the victim's included (a SET or SHIFT looks at the page itself again)
-    const uint32_t lv = swap ? l2 : l, wv = swap ? wq : wp;
-    PageWords<NP> gp = request_page<NP>(q, X, l, nc, wp), gq = request_page<NP>(q, X, lv, nc, wv);
-    uint32_t oc = occ[nc];
-    uint4 C1 = *(const uint4 *)(cnt + ((size_t)l * N + nc) * 4), C2 = *(const uint4 *)(cnt + ((size_t)lv * N + nc) * 4);
-    uint32_t acc1 = q.acc[(size_t)l * N + nc], acc2 = q.acc[(size_t)lv * N + nc], wr = q.wr[nc];
-    meanwhile();
+    (void)L;
+    PageWords<NP> gp = Ld.gp, gq = Ld.gq;
+    uint32_t oc = Ld.oc, acc1 = Ld.acc1, acc2 = Ld.acc2, wr = Ld.wr;
+    uint4 C1 = Ld.C1, C2 = Ld.C2;
+    // everything counts as used here, whether the move turns out to need it or not: otherwise the
+    // loads of words that matter only under a condition sink into branches and wait there in turn
     arrive(gp); arrive(gq);
     asm volatile("" : "+v"(oc), "+v"(C1.x), "+v"(C1.y), "+v"(C1.z), "+v"(C1.w), "+v"(C2.x), "+v"(C2.y), "+v"(C2.z),
                  "+v"(C2.w), "+v"(acc1), "+v"(acc2), "+v"(wr));
+    if (!Ld.ok) return R;
+    const uint32_t l = m.layer, n1 = m.n1, len = m.len, l2 = m.layer2;
+    const uint32_t wp = m.page >> 5, bp = m.page & 31, bq = m.page2 & 31;
+    const bool swap = m.op == KVP_OP_SWAP;
+    const bool same_layer = l2 == l;
+    int n = (int)n1 + lane;
+    bool inb = n < (int)N;
+    uint32_t nc = inb ? (uint32_t)n : N - 1;
     PageBits P = page_bits<NP>(q, gp, nc, inb, bp);
     PageBits Q = swap ? page_bits<NP>(q, gq, nc, inb, bq) : P;
     if (!(ballot64(P.v) & 1ull)) return R;                 // the page does not exist at n1
@@ -265,6 +291,17 @@ __device__ __forceinline__ MoveEval eval_move(const DevProblem &q, const uint32_
     return R;
 }
 
+// Both halves in one go.  `meanwhile` is run once, after the move's loads have been issued and
+// before anything waits for them: work that does not depend on the schedule (drawing the next
+// proposal) then costs no time of its own.
+template <int NP, class F>
+__device__ __forceinline__ MoveEval eval_move(const DevProblem &q, const uint32_t *X, const uint32_t *cnt,
+                                              const uint32_t *occ, const kvp_move &m, int lane, F meanwhile) {
+    MoveLoads<NP> Ld = issue_move<NP>(q, X, cnt, occ, m, lane);
+    meanwhile();
+    return finish_move<NP>(q, X, cnt, occ, m, lane, Ld);
+}
+
 // ---- kvp_delta_score -----------------------------------------------------------
 template <int NP>
 __global__ __launch_bounds__(256) void delta_kernel(DevProblem q, const uint32_t *__restrict__ X, uint32_t S,
@@ -328,28 +365,56 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// Proposal number `mi` of chain `chain`: three Philox blocks on counters
-// (mi, chain, stream0 + {0,1,2}).  u is uniform on (0,1) with 52 random bits.
-__device__ __forceinline__ void draw_move(const DevProblem &q, const SAParams &sp, uint32_t chain, uint64_t mi,
-                                          uint32_t stream0, kvp_move &m, double &u) {
-    uint32_t a[4], b[4], c[4];
-    philox4x32_10((uint32_t)mi, (uint32_t)(mi >> 32), chain, stream0, sp.seed_lo, sp.seed_hi, a);
-    philox4x32_10((uint32_t)mi, (uint32_t)(mi >> 32), chain, stream0 + 1, sp.seed_lo, sp.seed_hi, b);
-    philox4x32_10((uint32_t)mi, (uint32_t)(mi >> 32), chain, stream0 + 2, sp.seed_lo, sp.seed_hi, c);
-    m.op = ((uint64_t)a[0] < sp.th0) ? KVP_OP_SET : ((uint64_t)a[0] < sp.th1) ? KVP_OP_SWAP : KVP_OP_SHIFT;
-    m.layer = __umulhi(a[1], q.L);
-    m.page = __umulhi(a[2], q.P);
-    m.n1 = __umulhi(a[3], q.N);
-    m.len = 1 + __umulhi(b[0], sp.max_len);
-    m.layer2 = __umulhi(b[1], q.L);
-    m.page2 = __umulhi(b[2], q.P);
-    m.dsel = b[3] >> 30;
-    const uint64_t bits = ((uint64_t)c[0] << 20) | (uint64_t)(c[1] >> 12);
+// Proposal number `mi` of chain `chain` is made of three Philox blocks on counters
+// (mi, chain, stream0 + {0,1,2}).  A wavefront computes the blocks of sixteen consecutive proposals
+// at once, lane 4 j + t the block t of proposal first + j (the fourth lane of a group idles), and a
+// proposal is then read out of the three lanes that hold it: the generator costs one pass of ten
+// rounds per sixteen proposals instead of three per proposal.
+constexpr uint32_t DRAW_BATCH = 16;
+
+struct DrawBatch {
+    uint32_t o0, o1, o2, o3;    // per lane: the four words of its block
+    uint64_t first;             // uniform: the proposal of lanes 0..3
+};
+
+__device__ __forceinline__ void fill_draws(const SAParams &sp, uint32_t chain, uint64_t first, uint32_t stream0,
+                                           int lane, DrawBatch &B) {
+    const uint64_t mi = first + (uint32_t)(lane >> 2);
+    uint32_t out[4];
+    philox4x32_10((uint32_t)mi, (uint32_t)(mi >> 32), chain, stream0 + ((uint32_t)lane & 3u), sp.seed_lo, sp.seed_hi, out);
+    B.o0 = out[0]; B.o1 = out[1]; B.o2 = out[2]; B.o3 = out[3];
+    B.first = first;
+}
+
+// u is uniform on (0,1) with 52 random bits.  mi must lie in [B.first, B.first + DRAW_BATCH).
+__device__ __forceinline__ void take_move(const DevProblem &q, const SAParams &sp, const DrawBatch &B, uint64_t mi,
+                                          kvp_move &m, double &u) {
+    const int j = (int)(uint32_t)(mi - B.first) * 4;
+    auto word = [&](uint32_t v, int at) { return (uint32_t)__builtin_amdgcn_readlane((int)v, at); };
+    const uint32_t a0 = word(B.o0, j), a1 = word(B.o1, j), a2 = word(B.o2, j), a3 = word(B.o3, j);
+    const uint32_t b0 = word(B.o0, j + 1), b1 = word(B.o1, j + 1), b2 = word(B.o2, j + 1), b3 = word(B.o3, j + 1);
+    const uint32_t c0 = word(B.o0, j + 2), c1 = word(B.o1, j + 2);
+    m.op = ((uint64_t)a0 < sp.th0) ? KVP_OP_SET : ((uint64_t)a0 < sp.th1) ? KVP_OP_SWAP : KVP_OP_SHIFT;
+    m.layer = __umulhi(a1, q.L);
+    m.page = __umulhi(a2, q.P);
+    m.n1 = __umulhi(a3, q.N);
+    m.len = 1 + __umulhi(b0, sp.max_len);
+    m.layer2 = __umulhi(b1, q.L);
+    m.page2 = __umulhi(b2, q.P);
+    m.dsel = b3 >> 30;
+    const uint64_t bits = ((uint64_t)c0 << 20) | (uint64_t)(c1 >> 12);
     u = ((double)bits + 0.5) * (1.0 / 4503599627370496.0);
     // The draw is complete HERE: it keeps its place among the other pinned statements (the point
     // where a move's loads are waited for), instead of drifting behind that wait.
     asm volatile("" : "+s"(m.op), "+s"(m.layer), "+s"(m.page), "+s"(m.n1), "+s"(m.len), "+s"(m.layer2), "+s"(m.page2),
                  "+s"(m.dsel), "+v"(u));
+}
+
+// proposal mi, refilling the batch when mi has run past it
+__device__ __forceinline__ void next_move(const DevProblem &q, const SAParams &sp, uint32_t chain, uint32_t stream0,
+                                          int lane, DrawBatch &B, uint64_t mi, kvp_move &m, double &u) {
+    if (mi - B.first >= DRAW_BATCH) fill_draws(sp, chain, mi, stream0, lane, B);
+    take_move(q, sp, B, mi, m, u);
 }
 
 // ---- the annealing loop: one wavefront per chain --------------------------------
@@ -375,9 +440,11 @@ __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams
         double sum = 0.0;
         uint32_t k = 0;
         kvp_move m, mn; double u, un;
-        draw_move(q, sp, chain, 0, 8, m, u);
+        DrawBatch B;
+        fill_draws(sp, chain, 0, 8, lane, B);
+        take_move(q, sp, B, 0, m, u);
         for (uint64_t j = 0; j < CALIB_MOVES; j++) {
-            const MoveEval R = eval_move<NP>(q, X, cnt, occ, m, lane, [&] { draw_move(q, sp, chain, j + 1, 8, mn, un); });
+            const MoveEval R = eval_move<NP>(q, X, cnt, occ, m, lane, [&] { next_move(q, sp, chain, 8, lane, B, j + 1, mn, un); });
             m = mn;
             if (R.verdict != KVP_MOVE_NULL && R.dT > 0.0) { sum = sum + R.dT; k++; }
         }
@@ -386,63 +453,87 @@ __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams
         st.level = 0;
     }
 
-    // The proposal after the current one is drawn while the current one's loads are in flight:
-    // proposals depend on the counters (move number, chain, seed) only, never on the schedule.
-    kvp_move m_next; double u_next;
-    draw_move(q, sp, chain, move_begin, 0, m_next, u_next);
+    // Two proposals are in the pipeline: while move mi is priced from words that were requested one
+    // iteration ago, the words of move mi + 1 are already on their way (proposals depend on the move
+    // number, chain and seed only, never on the schedule).  When move mi is accepted and what it
+    // writes may be among the words requested for mi + 1, they are requested again after the writes.
+    kvp_move m_cur, m_nxt;
+    double u_cur, u_nxt;
+    DrawBatch B;
+    fill_draws(sp, chain, move_begin, 0, lane, B);
+    take_move(q, sp, B, move_begin, m_cur, u_cur);
+    MoveLoads<NP> Lc = issue_move<NP>(q, X, cnt, occ, m_cur, lane);
     for (uint64_t mi = move_begin; mi < move_end; mi++) {
         uint64_t lvl = mi / sp.mpl;
         if (lvl > sp.n_levels - 1) lvl = sp.n_levels - 1;
         while (st.level < lvl) { st.c = st.c * sp.alpha; st.level++; }      // geometric cooling
-        const kvp_move m = m_next;
-        const double u = u_next;
-        const MoveEval R = eval_move<NP>(q, X, cnt, occ, m, lane, [&] { draw_move(q, sp, chain, mi + 1, 0, m_next, u_next); });
+        next_move(q, sp, chain, 0, lane, B, mi + 1, m_nxt, u_nxt);
+        MoveLoads<NP> Ln = issue_move<NP>(q, X, cnt, occ, m_nxt, lane);
+        const kvp_move m = m_cur;
+        const double u = u_cur;
+        const MoveEval R = finish_move<NP>(q, X, cnt, occ, m, lane, Lc);
         st.moves_done++;
-        if (R.verdict == KVP_MOVE_NULL) { st.null_moves++; continue; }
-        if (R.verdict == KVP_MOVE_CLIPPED) st.clipped++;
-        const bool accept = (R.dT <= 0.0) || (st.c > 0.0 && u < exp(-R.dT / st.c));   // Metropolis
-        if (!accept) continue;
-        st.accepted++;
-        if (R.dT > 0.0) st.uphill++;
-        // apply: every lane owns one step of the window, so no two lanes write the same word
-        if (R.f1) {
-            const size_t o = ((size_t)m.layer * q.N + R.n) * q.Wd + (m.page >> 5);
-            X[o] ^= 1u << (m.page & 31);
-        }
-        if (R.f2) {
-            const size_t o = ((size_t)m.layer2 * q.N + R.n) * q.Wd + (m.page2 >> 5);
-            X[o] ^= 1u << (m.page2 & 31);
-        }
-        if (R.touch1) *(uint4 *)(cnt + ((size_t)m.layer * q.N + R.n) * 4) = R.c1;
-        if (R.touch2) *(uint4 *)(cnt + ((size_t)m.layer2 * q.N + R.n) * 4) = R.c2;
-        if (R.f1 && !R.f2) occ[R.n] += R.xnew ? 1u : 0xFFFFFFFFu;
-        st.t_cur = st.t_cur + R.dT;
-        // edits since the best schedule, so that it can be rebuilt by undoing them
-        if (st.log_len < log_cap) {
-            if (lane < LOG_WORDS) {
-                uint32_t w;
-                switch (lane) {
-                    case 0: w = m.layer; break;
-                    case 1: w = m.page; break;
-                    case 2: w = m.layer2; break;
-                    case 3: w = m.page2; break;
-                    case 4: w = (uint32_t)R.base; break;
-                    case 5: w = (uint32_t)R.flip1; break;
-                    case 6: w = (uint32_t)(R.flip1 >> 32); break;
-                    case 7: w = (uint32_t)R.flip2; break;
-                    case 8: w = (uint32_t)(R.flip2 >> 32); break;
-                    default: w = 0; break;
-                }
-                log[st.log_len * LOG_WORDS + lane] = w;
-            }
-            st.log_len++;
+        bool accept = false;
+        if (R.verdict == KVP_MOVE_NULL) {
+            st.null_moves++;
         } else {
-            st.log_overflow = 1;
+            if (R.verdict == KVP_MOVE_CLIPPED) st.clipped++;
+            accept = (R.dT <= 0.0) || (st.c > 0.0 && u < exp(-R.dT / st.c));   // Metropolis
         }
-        if (st.t_cur < st.t_best) { st.t_best = st.t_cur; st.improved++; st.log_len = 0; }
-        // the next proposal may read, from other lanes, what this one wrote
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        if (accept) {
+            st.accepted++;
+            if (R.dT > 0.0) st.uphill++;
+            // apply: every lane owns one step of the window, so no two lanes write the same word
+            if (R.f1) {
+                const size_t o = ((size_t)m.layer * q.N + R.n) * q.Wd + (m.page >> 5);
+                X[o] ^= 1u << (m.page & 31);
+            }
+            if (R.f2) {
+                const size_t o = ((size_t)m.layer2 * q.N + R.n) * q.Wd + (m.page2 >> 5);
+                X[o] ^= 1u << (m.page2 & 31);
+            }
+            if (R.touch1) *(uint4 *)(cnt + ((size_t)m.layer * q.N + R.n) * 4) = R.c1;
+            if (R.touch2) *(uint4 *)(cnt + ((size_t)m.layer2 * q.N + R.n) * 4) = R.c2;
+            if (R.f1 && !R.f2) occ[R.n] += R.xnew ? 1u : 0xFFFFFFFFu;
+            st.t_cur = st.t_cur + R.dT;
+            // edits since the best schedule, so that it can be rebuilt by undoing them
+            if (st.log_len < log_cap) {
+                if (lane < LOG_WORDS) {
+                    uint32_t w;
+                    switch (lane) {
+                        case 0: w = m.layer; break;
+                        case 1: w = m.page; break;
+                        case 2: w = m.layer2; break;
+                        case 3: w = m.page2; break;
+                        case 4: w = (uint32_t)R.base; break;
+                        case 5: w = (uint32_t)R.flip1; break;
+                        case 6: w = (uint32_t)(R.flip1 >> 32); break;
+                        case 7: w = (uint32_t)R.flip2; break;
+                        case 8: w = (uint32_t)(R.flip2 >> 32); break;
+                        default: w = 0; break;
+                    }
+                    log[st.log_len * LOG_WORDS + lane] = w;
+                }
+                st.log_len++;
+            } else {
+                st.log_overflow = 1;
+            }
+            if (st.t_cur < st.t_best) { st.t_best = st.t_cur; st.improved++; st.log_len = 0; }
+            // Later proposals read, from other lanes, what this one wrote.  The chain is one wavefront:
+            // its memory instructions reach the cache in program order, so a fence of wavefront scope
+            // (no wait; it only keeps the compiler from moving accesses across) is all that is needed.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            // Written: schedule words and counter rows of the move's layers, and the occupancy, at
+            // steps [base + first flip, base + last flip + 1].  Requested for the next move: rows
+            // n1 - 1 .. n1 + 63 of its layers and the occupancy of those steps.
+            const uint64_t fl = R.flip1 | R.flip2;
+            const int w_lo = R.base + ctz64(fl), w_hi = R.base + msb64(fl) + 1;
+            const int r_lo = (int)m_nxt.n1 - 1, r_hi = (int)m_nxt.n1 + 63;
+            if (w_lo <= r_hi && w_hi >= r_lo) Ln = issue_move<NP>(q, X, cnt, occ, m_nxt, lane);
+        }
+        Lc = Ln;
+        m_cur = m_nxt; u_cur = u_nxt;
     }
     if (lane == 0) states[chain] = st;
 }
