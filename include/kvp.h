@@ -164,6 +164,13 @@ int kvp_delta_score(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, cons
                     const uint32_t *d_counters, const uint32_t *d_occ, double *d_delta,
                     int32_t *d_verdict);
 
+/* Tuning knob of kvp_anneal: how many consecutive proposals of a chain are priced at once, each
+ * by a wavefront of its own (the walk takes them in order up to the first accepted one, so it is
+ * the same walk whatever the number).  0 (default): chosen from the number of chains and the
+ * size of the GPU; 1: one wavefront per chain prices one proposal after the other; 4: four per
+ * round.  Other values: KVP_EINVAL. */
+int kvp_set_anneal_lookahead(kvp_ctx *ctx, int proposals_per_round);
+
 /* Sec. III-B: run params->moves annealing moves on every chain.  d_init is
  * [C][L][N][Wd] (KVP_INIT_GIVEN), [L][N][Wd] (KVP_INIT_BROADCAST) or NULL.
  * Starting schedules must be admissible (checked, KVP_EINFEASIBLE) and are

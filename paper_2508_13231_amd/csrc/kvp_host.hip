@@ -80,6 +80,12 @@ extern "C" const char *kvp_strerror(int code) {
     }
 }
 
+extern "C" int kvp_set_anneal_lookahead(kvp_ctx *ctx, int proposals_per_round) {
+    if (!ctx || (proposals_per_round != 0 && proposals_per_round != 1 && proposals_per_round != 4)) return KVP_EINVAL;
+    ctx->anneal_lookahead = proposals_per_round;
+    return KVP_OK;
+}
+
 extern "C" int kvp_set_score_kernel(kvp_ctx *ctx, int which) {
     if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_LINE) return KVP_EINVAL;
     ctx->score_kernel = which;

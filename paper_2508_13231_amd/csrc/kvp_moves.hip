@@ -220,16 +220,29 @@ __device__ __forceinline__ MoveEval finish_move(const DevProblem &q, const uint3
         const bool a = (xmask >> (it - 1)) & 1ull;
         const int d = (m.dsel & 2u) ? (int)(m.dsel & 1u) + 1 : (int)(m.dsel & 1u) - 2;   // -2,-1,+1,+2
         base = nt - 2;
-        // re-map the lanes onto the five steps around the edge (a second round trip, SHIFT only)
+        // re-map the lanes onto the five steps around the edge: lane k takes step nt - 2 + k
         n = base + lane;
         inb = lane < 5 && n >= 0 && n < (int)N;
         nc = inb ? (uint32_t)n : 0u;
-        gp = request_page<NP>(q, X, l, nc, wp);
-        oc = occ[nc];
-        C1 = *(const uint4 *)(cnt + ((size_t)l * N + nc) * 4);
-        acc1 = q.acc[(size_t)l * N + nc];
-        wr = q.wr[nc];
-        arrive(gp);
+        if (it <= 61) {
+            // those steps are lanes it - 2 .. it + 2 of the window just loaded: a cross-lane move of
+            // what they hold.  (For it = 1 lane 0 would be the step before the window; it is then neither
+            // a target nor the neighbour of one, so what it gets is never looked at.)
+            const int src = min(max(it - 2 + lane, 0), 63);
+            auto take = [&](uint32_t &v) { v = (uint32_t)__shfl((int)v, src, KVP_WAVE); };
+            take(gp.vw); take(gp.pw); take(gp.ww); take(gp.xw); take(gp.vpw); take(gp.xpw);
+#pragma unroll
+            for (int j = 0; j < NP; j++) take(gp.aw[j]);
+            take(oc); take(C1.x); take(C1.y); take(C1.z); take(C1.w); take(acc1); take(wr);
+        } else {
+            // an edge at the far end of a long span: a second round trip
+            gp = request_page<NP>(q, X, l, nc, wp);
+            oc = occ[nc];
+            C1 = *(const uint4 *)(cnt + ((size_t)l * N + nc) * 4);
+            acc1 = q.acc[(size_t)l * N + nc];
+            wr = q.wr[nc];
+            arrive(gp);
+        }
         P = page_bits<NP>(q, gp, nc, inb, bp);
         if (d < 0) {
             const bool target = lane == 1 || (lane == 0 && d == -2 && it >= 2);   // steps hold a, take not(a)
@@ -538,6 +551,123 @@ __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams
     if (lane == 0) states[chain] = st;
 }
 
+// ---- the annealing loop, several proposals per round ---------------------------------
+// A chain is a serial walk, but its proposals are known in advance (they depend on the move number,
+// the chain and the seed only) and most are rejected.  SPEC wavefronts therefore price the next SPEC
+// proposals against the same schedule at once; the walk then takes them in order up to and including
+// the first one that is accepted (everything before it was rejected, so it was priced on the right
+// schedule), that wavefront applies its move, and the next round starts behind it.  The walk is the
+// serial one, move for move; a round costs one memory round trip and one pricing for 1/a proposals or
+// so at acceptance rate a.  Every wavefront keeps a copy of the chain's running state and updates it
+// alike from what the round's wavefronts publish in LDS.
+
+__device__ __forceinline__ int uniform_i32(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ double uniform_f64(double v) {
+    return __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(v)),
+                            __builtin_amdgcn_readfirstlane(__double2loint(v)));
+}
+
+template <int NP, int SPEC>
+__global__ __launch_bounds__(SPEC * KVP_WAVE) void anneal_rounds_kernel(
+    DevProblem q, SAParams sp, uint32_t *__restrict__ Xall, uint32_t *__restrict__ cnt_all,
+    uint32_t *__restrict__ occ_all, ChainState *__restrict__ states, uint32_t *__restrict__ log_all, uint64_t log_cap,
+    uint64_t move_begin, uint64_t move_end) {
+    __shared__ double s_dT[SPEC];
+    __shared__ int s_verdict[SPEC], s_accept[SPEC];
+    const uint32_t chain = blockIdx.x;
+    const int lane = lane_id();
+    const int w = uniform_i32((int)(threadIdx.x / KVP_WAVE));
+    const size_t rows = (size_t)q.L * q.N;
+    uint32_t *X = Xall + (size_t)chain * rows * q.Wd;
+    uint32_t *cnt = cnt_all + (size_t)chain * rows * 4;
+    uint32_t *occ = occ_all + (size_t)chain * q.N;
+    uint32_t *log = log_all + (size_t)chain * log_cap * LOG_WORDS;
+    ChainState st = states[chain];
+    DrawBatch B;
+    B.first = ~0ull - DRAW_BATCH;                                      // empty: the first proposal fills it
+    B.o0 = B.o1 = B.o2 = B.o3 = 0;
+    auto level_of = [&](uint64_t mi) {
+        const uint64_t lvl = mi / sp.mpl;
+        return (uint32_t)(lvl > sp.n_levels - 1 ? sp.n_levels - 1 : lvl);
+    };
+    uint64_t mi = move_begin;
+    while (mi < move_end) {                                            // the same trip count in every wavefront
+        const uint64_t my = mi + (uint32_t)w;
+        const bool valid = my < move_end;
+        kvp_move m; double u;
+        next_move(q, sp, chain, 0, lane, B, valid ? my : mi, m, u);
+        // temperature of this proposal: geometric cooling, continued from the chain's state
+        double c = st.c;
+        for (uint32_t lev = st.level, to = level_of(my); lev < to; lev++) c = c * sp.alpha;
+        const MoveEval R = eval_move<NP>(q, X, cnt, occ, m, lane, [] {});
+        bool accept = false;
+        if (valid && R.verdict != KVP_MOVE_NULL) accept = (R.dT <= 0.0) || (c > 0.0 && u < exp(-R.dT / c));   // Metropolis
+        if (lane == 0) { s_dT[w] = R.dT; s_verdict[w] = valid ? R.verdict : -1; s_accept[w] = accept ? 1 : 0; }
+        __syncthreads();
+        // the proposals of this round that the walk reaches
+        int f = SPEC;
+        uint32_t reached = 0;
+#pragma unroll
+        for (int k = 0; k < SPEC; k++) {
+            const int v = uniform_i32(s_verdict[k]), acc = uniform_i32(s_accept[k]);
+            if (f == SPEC && v >= 0 && reached == (uint32_t)k) {
+                reached++;
+                st.moves_done++;
+                if (v == KVP_MOVE_NULL) st.null_moves++;
+                else {
+                    if (v == KVP_MOVE_CLIPPED) st.clipped++;
+                    if (acc) f = k;
+                }
+            }
+        }
+        if (f < SPEC) {
+            const double dT = uniform_f64(s_dT[f]);
+            st.accepted++;
+            if (dT > 0.0) st.uphill++;
+            if (w == f) {
+                // apply: every lane owns one step of the window, so no two lanes write the same word
+                if (R.f1) {
+                    const size_t o = ((size_t)m.layer * q.N + R.n) * q.Wd + (m.page >> 5);
+                    X[o] ^= 1u << (m.page & 31);
+                }
+                if (R.f2) {
+                    const size_t o = ((size_t)m.layer2 * q.N + R.n) * q.Wd + (m.page2 >> 5);
+                    X[o] ^= 1u << (m.page2 & 31);
+                }
+                if (R.touch1) *(uint4 *)(cnt + ((size_t)m.layer * q.N + R.n) * 4) = R.c1;
+                if (R.touch2) *(uint4 *)(cnt + ((size_t)m.layer2 * q.N + R.n) * 4) = R.c2;
+                if (R.f1 && !R.f2) occ[R.n] += R.xnew ? 1u : 0xFFFFFFFFu;
+                // edits since the best schedule, so that it can be rebuilt by undoing them
+                if (st.log_len < log_cap && lane < LOG_WORDS) {
+                    uint32_t e;
+                    switch (lane) {
+                        case 0: e = m.layer; break;
+                        case 1: e = m.page; break;
+                        case 2: e = m.layer2; break;
+                        case 3: e = m.page2; break;
+                        case 4: e = (uint32_t)R.base; break;
+                        case 5: e = (uint32_t)R.flip1; break;
+                        case 6: e = (uint32_t)(R.flip1 >> 32); break;
+                        case 7: e = (uint32_t)R.flip2; break;
+                        case 8: e = (uint32_t)(R.flip2 >> 32); break;
+                        default: e = 0; break;
+                    }
+                    log[st.log_len * LOG_WORDS + lane] = e;
+                }
+            }
+            st.t_cur = st.t_cur + dT;
+            if (st.log_len < log_cap) st.log_len++;
+            else st.log_overflow = 1;
+            if (st.t_cur < st.t_best) { st.t_best = st.t_cur; st.improved++; st.log_len = 0; }
+        }
+        // the cooling state as the last proposal reached leaves it
+        for (const uint32_t to = level_of(mi + reached - 1); st.level < to; st.level++) st.c = st.c * sp.alpha;
+        mi += reached;
+        __syncthreads();        // this round's writes before the next round's reads (and the LDS slots are free again)
+    }
+    if (threadIdx.x == 0) states[chain] = st;
+}
+
 // Apply (or, applied twice, undo) every logged edit of every chain: XOR commutes,
 // so one wavefront per log entry and atomics on the words are enough.
 __global__ __launch_bounds__(256) void log_xor_kernel(DevProblem q, uint32_t *__restrict__ Xall,
@@ -702,15 +832,37 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
             anneal_kernel<KVP_MAX_PLANES><<<grid, block, 0, ctx->stream>>>(
                 q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state, ctx->d_log, ctx->log_cap, b, e, calibrate);
     };
-    if (p->moves == 0 && first) {
+    // Proposals priced per round: four, each by a wavefront of its own, while that leaves every
+    // wavefront a SIMD to itself (four SIMDs per compute unit); with more chains than that the
+    // serial loop, one wavefront per chain, is the faster one (measured: 512 and 1024 chains).
+    int spec = ctx->anneal_lookahead;
+    if (spec == 0) {
+        hipDeviceProp_t prop;
+        KVP_HIP(hipGetDeviceProperties(&prop, ctx->device));
+        spec = (uint64_t)C * 4 <= 4ull * (uint64_t)prop.multiProcessorCount ? 4 : 1;
+    }
+    auto launch_rounds = [&](uint64_t b, uint64_t e) {
+        const dim3 grid(C), block(4 * KVP_WAVE);
+        if (q.pn == 1)
+            anneal_rounds_kernel<1, 4><<<grid, block, 0, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
+                                                                       ctx->d_log, ctx->log_cap, b, e);
+        else if (q.pn <= 4)
+            anneal_rounds_kernel<4, 4><<<grid, block, 0, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
+                                                                       ctx->d_log, ctx->log_cap, b, e);
+        else
+            anneal_rounds_kernel<KVP_MAX_PLANES, 4><<<grid, block, 0, ctx->stream>>>(
+                q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state, ctx->d_log, ctx->log_cap, b, e);
+    };
+    const bool rounds = spec == 4;
+    if (first) {                                                       // the initial temperature, once per chain
         launch(0, 0, 1);
         KVP_HIP(hipGetLastError());
     }
     while (m0 < m_end) {
         const uint64_t m1 = m0 + chunk < m_end ? m0 + chunk : m_end;
-        launch(m0, m1, first ? 1 : 0);
+        if (rounds) launch_rounds(m0, m1);
+        else launch(m0, m1, 0);
         KVP_HIP(hipGetLastError());
-        first = false;
         m0 = m1;
     }
     ctx->moves_done = m_end;

@@ -182,18 +182,20 @@ def _anneal_gpu(g, tr, chains, total, moves=None, init=None, seed=0, mode=None, 
     return p
 
 
+@pytest.mark.parametrize("lookahead", [1, 4], ids=["serial", "four-per-round"])
 @pytest.mark.parametrize("name,scale,chains,total,max_len", [("tiny", 1.0, 6, 4000, 63),
                                                              ("table1", 1.0, 4, 2000, 5),
                                                              ("llama8b", 0.125, 4, 3000, 63),
                                                              ("serving", 0.0625, 4, 3000, 31),
                                                              ("gqa70b", 0.0625, 3, 3000, 63)])
-def test_anneal_against_oracle_at_equal_budget(G, name, scale, chains, total, max_len):
+def test_anneal_against_oracle_at_equal_budget(G, name, scale, chains, total, max_len, lookahead):
     import paper_2508_13231_amd as K
     tr = W.config(name, scale)
     q = O.Problem(tr)
     X0 = O.init_static_frequency(q) if name != "table1" else np.zeros(q.shape, np.uint8)
     res, bi = O.anneal(q, range(chains), X0, seed=tr.seed, total_moves=total, max_len=max_len)
     with G(tr) as g:
+        K.kvp_set_anneal_lookahead(g.ctx, lookahead)
         _anneal_gpu(g, tr, chains, total, init=X0, seed=tr.seed, max_len=max_len)
         cost, chain, words, cc = K.kvp_best(g.ctx, g.shape_words, chains)
         stats = K.kvp_chain_stats(g.ctx, chains)
@@ -217,8 +219,9 @@ def test_anneal_against_oracle_at_equal_budget(G, name, scale, chains, total, ma
     assert same == chains
 
 
-@pytest.mark.parametrize("name,total,ids", [("llama8b", 6000, (0, 3, 128, 255)), ("longctx", 1500, (0, 1023))])
-def test_full_size_anneal_sampled_chains_against_oracle(G, name, total, ids):
+@pytest.mark.parametrize("name,total,ids,lookahead", [("llama8b", 6000, (0, 3, 128, 255), 0), ("llama8b", 6000, (1, 254), 1),
+                                                      ("longctx", 1500, (0, 1023), 0)])
+def test_full_size_anneal_sampled_chains_against_oracle(G, name, total, ids, lookahead):
     """The launch configuration of the benchmark (all chains of the config, the start broadcast);
     the oracle walks a few of the chain ids and must arrive where the GPU's chains of those ids did."""
     import paper_2508_13231_amd as K
@@ -227,6 +230,7 @@ def test_full_size_anneal_sampled_chains_against_oracle(G, name, total, ids):
     X0 = W.random_placements(tr, 1, seed=tr.seed, density=0.25)[0]
     res, _ = O.anneal(q, list(ids), X0, threads=len(ids), seed=tr.seed, total_moves=total)
     with G(tr) as g:
+        K.kvp_set_anneal_lookahead(g.ctx, lookahead)
         _anneal_gpu(g, tr, tr.chains, total, init=X0, seed=tr.seed)
         cost, chain, words, cc = K.kvp_best(g.ctx, g.shape_words, tr.chains)
         stats = K.kvp_chain_stats(g.ctx, tr.chains)
@@ -246,13 +250,20 @@ def test_anneal_resume_and_modes(G):
     tr = W.config("tiny")
     q = O.Problem(tr)
     with G(tr) as g:
+        K.kvp_set_anneal_lookahead(g.ctx, 1)
         _anneal_gpu(g, tr, 4, 3000, seed=7)
         c1 = K.kvp_best(g.ctx, g.shape_words, 4)
         x1 = [K.kvp_chain_placement(g.ctx, c, 0, g.shape_words) for c in range(4)]
-        # the same schedule run in three calls
+        # the same schedule run in three calls, four proposals per round, then serially, then four again
+        K.kvp_set_anneal_lookahead(g.ctx, 4)
         _anneal_gpu(g, tr, 4, 3000, moves=1000, seed=7)
+        K.kvp_set_anneal_lookahead(g.ctx, 1)
         _anneal_gpu(g, tr, 4, 3000, moves=500, seed=7, mode=K.KVP_INIT_CONTINUE)
+        K.kvp_set_anneal_lookahead(g.ctx, 4)
         _anneal_gpu(g, tr, 4, 3000, moves=1500, seed=7, mode=K.KVP_INIT_CONTINUE)
+        with pytest.raises(K.KvpError) as e:
+            K.kvp_set_anneal_lookahead(g.ctx, 3)
+        assert e.value.code == K.KVP_EINVAL
         c2 = K.kvp_best(g.ctx, g.shape_words, 4)
         x2 = [K.kvp_chain_placement(g.ctx, c, 0, g.shape_words) for c in range(4)]
         assert c1[0] == c2[0] and c1[1] == c2[1] and (c1[2] == c2[2]).all() and (c1[3] == c2[3]).all()
