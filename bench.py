@@ -122,7 +122,7 @@ def main():
                          "(FETCH_SIZE / WRITE_SIZE) sees a kernel of known traffic to scale by")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU; chains and schedules shard trivially across GPUs "
+        print("bench.py: the library runs on one GPU; chains and schedules shard trivially across GPUs "
               "but no multi-GPU path is built.  Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
