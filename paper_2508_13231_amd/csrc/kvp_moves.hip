@@ -38,6 +38,8 @@ struct MoveEval {
     int n;              // step of this lane, -1 if outside the trace
     bool f1, f2, touch1, touch2, xnew;
     uint4 c1, c2;       // counters after the move of rows (layer, n) and (layer2, n)
+    uint32_t xw1, xw2;  // the schedule words of the page and of the victim at step n, as loaded
+    uint32_t oc;        // pages in HBM at step n, as loaded
 };
 
 __device__ __forceinline__ uint64_t ballot64(bool p) { return (uint64_t)__ballot(p); }
@@ -157,6 +159,7 @@ __device__ __forceinline__ MoveEval finish_move(const DevProblem &q, const uint3
     R.verdict = KVP_MOVE_NULL; R.dT = 0.0; R.base = 0; R.flip1 = R.flip2 = 0; R.second = false;
     R.n = -1; R.f1 = R.f2 = R.touch1 = R.touch2 = R.xnew = false;
     R.c1 = make_uint4(0, 0, 0, 0); R.c2 = R.c1;
+    R.xw1 = R.xw2 = R.oc = 0;
     const uint32_t L = q.L, N = q.N, cap = q.cap;
     (void)L;
     PageWords<NP> gp = Ld.gp, gq = Ld.gq;
@@ -301,6 +304,7 @@ __device__ __forceinline__ MoveEval finish_move(const DevProblem &q, const uint3
     R.verdict = clipped ? KVP_MOVE_CLIPPED : KVP_MOVE_OK;
     R.dT = dT; R.base = base; R.flip1 = flip1; R.flip2 = flip2; R.second = second;
     R.n = inb ? n : -1; R.f1 = f1; R.f2 = f2; R.touch1 = touch1; R.touch2 = touch2; R.xnew = P.x != f1;
+    R.xw1 = gp.xw; R.xw2 = gq.xw; R.oc = oc;
     return R;
 }
 
@@ -430,6 +434,22 @@ __device__ __forceinline__ void next_move(const DevProblem &q, const SAParams &s
     take_move(q, sp, B, mi, m, u);
 }
 
+// Write an accepted move into the chain's schedule, counters and occupancy.  Every lane owns one
+// step of the window, so no two lanes write the same word; the new words are made from the ones the
+// move was priced on, so nothing is read back from memory here.
+__device__ __forceinline__ void apply_move(const DevProblem &q, uint32_t *X, uint32_t *cnt, uint32_t *occ,
+                                           const kvp_move &m, const MoveEval &R) {
+    const bool same_word = m.layer == m.layer2 && (m.page >> 5) == (m.page2 >> 5);
+    uint32_t w1 = R.xw1, w2 = R.xw2;
+    if (R.f1) w1 ^= 1u << (m.page & 31);
+    if (R.f2) { if (same_word) w1 ^= 1u << (m.page2 & 31); else w2 ^= 1u << (m.page2 & 31); }
+    if (R.f1 || (R.f2 && same_word)) X[((size_t)m.layer * q.N + R.n) * q.Wd + (m.page >> 5)] = w1;
+    if (R.f2 && !same_word) X[((size_t)m.layer2 * q.N + R.n) * q.Wd + (m.page2 >> 5)] = w2;
+    if (R.touch1) *(uint4 *)(cnt + ((size_t)m.layer * q.N + R.n) * 4) = R.c1;
+    if (R.touch2) *(uint4 *)(cnt + ((size_t)m.layer2 * q.N + R.n) * 4) = R.c2;
+    if (R.f1 && !R.f2) occ[R.n] = R.oc + (R.xnew ? 1u : 0xFFFFFFFFu);
+}
+
 // ---- the annealing loop: one wavefront per chain --------------------------------
 template <int NP>
 __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams sp, uint32_t *__restrict__ Xall,
@@ -496,18 +516,7 @@ __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams
         if (accept) {
             st.accepted++;
             if (R.dT > 0.0) st.uphill++;
-            // apply: every lane owns one step of the window, so no two lanes write the same word
-            if (R.f1) {
-                const size_t o = ((size_t)m.layer * q.N + R.n) * q.Wd + (m.page >> 5);
-                X[o] ^= 1u << (m.page & 31);
-            }
-            if (R.f2) {
-                const size_t o = ((size_t)m.layer2 * q.N + R.n) * q.Wd + (m.page2 >> 5);
-                X[o] ^= 1u << (m.page2 & 31);
-            }
-            if (R.touch1) *(uint4 *)(cnt + ((size_t)m.layer * q.N + R.n) * 4) = R.c1;
-            if (R.touch2) *(uint4 *)(cnt + ((size_t)m.layer2 * q.N + R.n) * 4) = R.c2;
-            if (R.f1 && !R.f2) occ[R.n] += R.xnew ? 1u : 0xFFFFFFFFu;
+            apply_move(q, X, cnt, occ, m, R);
             st.t_cur = st.t_cur + R.dT;
             // edits since the best schedule, so that it can be rebuilt by undoing them
             if (st.log_len < log_cap) {
@@ -625,18 +634,7 @@ __global__ __launch_bounds__(SPEC * KVP_WAVE) void anneal_rounds_kernel(
             st.accepted++;
             if (dT > 0.0) st.uphill++;
             if (w == f) {
-                // apply: every lane owns one step of the window, so no two lanes write the same word
-                if (R.f1) {
-                    const size_t o = ((size_t)m.layer * q.N + R.n) * q.Wd + (m.page >> 5);
-                    X[o] ^= 1u << (m.page & 31);
-                }
-                if (R.f2) {
-                    const size_t o = ((size_t)m.layer2 * q.N + R.n) * q.Wd + (m.page2 >> 5);
-                    X[o] ^= 1u << (m.page2 & 31);
-                }
-                if (R.touch1) *(uint4 *)(cnt + ((size_t)m.layer * q.N + R.n) * 4) = R.c1;
-                if (R.touch2) *(uint4 *)(cnt + ((size_t)m.layer2 * q.N + R.n) * 4) = R.c2;
-                if (R.f1 && !R.f2) occ[R.n] += R.xnew ? 1u : 0xFFFFFFFFu;
+                apply_move(q, X, cnt, occ, m, R);
                 // edits since the best schedule, so that it can be rebuilt by undoing them
                 if (st.log_len < log_cap && lane < LOG_WORDS) {
                     uint32_t e;
