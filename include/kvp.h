@@ -168,7 +168,8 @@ int kvp_delta_score(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, cons
  * by a wavefront of its own (the walk takes them in order up to the first accepted one, so it is
  * the same walk whatever the number).  0 (default): chosen from the number of chains and the
  * size of the GPU; 1: one wavefront per chain prices one proposal after the other; 4: four per
- * round.  Other values: KVP_EINVAL. */
+ * round (traces of more than 12288 token steps are always walked the first way).  Other values:
+ * KVP_EINVAL. */
 int kvp_set_anneal_lookahead(kvp_ctx *ctx, int proposals_per_round);
 
 /* Sec. III-B: run params->moves annealing moves on every chain.  d_init is

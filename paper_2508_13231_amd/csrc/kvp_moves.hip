@@ -125,7 +125,9 @@ struct MoveLoads {
     uint4 C1, C2;
 };
 
-template <int NP>
+// OCC_LATE: the occupancy is not requested here; finish_move reads it when it starts (from a copy
+// that is cheap to read and may change until then).
+template <int NP, bool OCC_LATE = false>
 __device__ __forceinline__ MoveLoads<NP> issue_move(const DevProblem &q, const uint32_t *X, const uint32_t *cnt,
                                                     const uint32_t *occ, const kvp_move &m, int lane) {
     MoveLoads<NP> Ld;
@@ -140,7 +142,7 @@ __device__ __forceinline__ MoveLoads<NP> issue_move(const DevProblem &q, const u
     const uint32_t lv = swap ? l2 : l, wv = swap ? wq : wp;
     Ld.gp = request_page<NP>(q, X, l, nc, wp);
     Ld.gq = request_page<NP>(q, X, lv, nc, wv);
-    Ld.oc = occ[nc];
+    Ld.oc = OCC_LATE ? 0u : occ[nc];
     Ld.C1 = *(const uint4 *)(cnt + ((size_t)l * N + nc) * 4);
     Ld.C2 = *(const uint4 *)(cnt + ((size_t)lv * N + nc) * 4);
     Ld.acc1 = q.acc[(size_t)l * N + nc];
@@ -152,7 +154,7 @@ __device__ __forceinline__ MoveLoads<NP> issue_move(const DevProblem &q, const u
 // Resolve a raw move against the schedule X (with its counters and occupancy)
 // and price it, from the words that issue_move requested.  All 64 lanes of the
 // wavefront must call this together.
-template <int NP>
+template <int NP, bool OCC_LATE = false>
 __device__ __forceinline__ MoveEval finish_move(const DevProblem &q, const uint32_t *X, const uint32_t *cnt,
                                                 const uint32_t *occ, const kvp_move &m, int lane, MoveLoads<NP> &Ld) {
     MoveEval R;
@@ -178,6 +180,7 @@ __device__ __forceinline__ MoveEval finish_move(const DevProblem &q, const uint3
     int n = (int)n1 + lane;
     bool inb = n < (int)N;
     uint32_t nc = inb ? (uint32_t)n : N - 1;
+    if (OCC_LATE) oc = occ[nc];
     PageBits P = page_bits<NP>(q, gp, nc, inb, bp);
     PageBits Q = swap ? page_bits<NP>(q, gq, nc, inb, bq) : P;
     if (!(ballot64(P.v) & 1ull)) return R;                 // the page does not exist at n1
@@ -581,8 +584,14 @@ __global__ __launch_bounds__(SPEC * KVP_WAVE) void anneal_rounds_kernel(
     DevProblem q, SAParams sp, uint32_t *__restrict__ Xall, uint32_t *__restrict__ cnt_all,
     uint32_t *__restrict__ occ_all, ChainState *__restrict__ states, uint32_t *__restrict__ log_all, uint64_t log_cap,
     uint64_t move_begin, uint64_t move_end) {
-    __shared__ double s_dT[SPEC];
-    __shared__ int s_verdict[SPEC], s_accept[SPEC];
+    // The chain's occupancy per token step lives in LDS for the launch: every accepted move changes it
+    // over its span, so it is the one thing that proposals requested ahead would nearly always find
+    // changed; from LDS it is read when a proposal is priced, not when its words are requested.
+    extern __shared__ uint32_t s_occ[];
+    // what the round's wavefronts publish, in two sets used in turn (a set is still being read when
+    // the next round's is written)
+    __shared__ double s_dT[2][SPEC];
+    __shared__ int s_verdict[2][SPEC], s_accept[2][SPEC], s_wlo[2][SPEC], s_whi[2][SPEC], s_l1[2][SPEC], s_l2[2][SPEC];
     const uint32_t chain = blockIdx.x;
     const int lane = lane_id();
     const int w = uniform_i32((int)(threadIdx.x / KVP_WAVE));
@@ -592,6 +601,8 @@ __global__ __launch_bounds__(SPEC * KVP_WAVE) void anneal_rounds_kernel(
     uint32_t *occ = occ_all + (size_t)chain * q.N;
     uint32_t *log = log_all + (size_t)chain * log_cap * LOG_WORDS;
     ChainState st = states[chain];
+    for (uint32_t i = threadIdx.x; i < q.N; i += SPEC * KVP_WAVE) s_occ[i] = occ[i];
+    __syncthreads();
     DrawBatch B;
     B.first = ~0ull - DRAW_BATCH;                                      // empty: the first proposal fills it
     B.o0 = B.o1 = B.o2 = B.o3 = 0;
@@ -600,25 +611,40 @@ __global__ __launch_bounds__(SPEC * KVP_WAVE) void anneal_rounds_kernel(
         return (uint32_t)(lvl > sp.n_levels - 1 ? sp.n_levels - 1 : lvl);
     };
     uint64_t mi = move_begin;
+    kvp_move m; double u;
+    m.op = m.layer = m.page = m.n1 = m.layer2 = m.page2 = m.dsel = 0; m.len = 1; u = 0.5;
+    MoveLoads<NP> Ld;
+    if (mi < move_end) {
+        next_move(q, sp, chain, 0, lane, B, mi + (uint32_t)w < move_end ? mi + (uint32_t)w : mi, m, u);
+        Ld = issue_move<NP, true>(q, X, cnt, nullptr, m, lane);
+    }
+    uint32_t set = 0;
     while (mi < move_end) {                                            // the same trip count in every wavefront
         const uint64_t my = mi + (uint32_t)w;
         const bool valid = my < move_end;
-        kvp_move m; double u;
-        next_move(q, sp, chain, 0, lane, B, valid ? my : mi, m, u);
         // temperature of this proposal: geometric cooling, continued from the chain's state
         double c = st.c;
         for (uint32_t lev = st.level, to = level_of(my); lev < to; lev++) c = c * sp.alpha;
-        const MoveEval R = eval_move<NP>(q, X, cnt, occ, m, lane, [] {});
+        const MoveEval R = finish_move<NP, true>(q, X, cnt, s_occ, m, lane, Ld);
         bool accept = false;
         if (valid && R.verdict != KVP_MOVE_NULL) accept = (R.dT <= 0.0) || (c > 0.0 && u < exp(-R.dT / c));   // Metropolis
-        if (lane == 0) { s_dT[w] = R.dT; s_verdict[w] = valid ? R.verdict : -1; s_accept[w] = accept ? 1 : 0; }
+        if (lane == 0) {
+            s_dT[set][w] = R.dT; s_verdict[set][w] = valid ? R.verdict : -1; s_accept[set][w] = accept ? 1 : 0;
+            // what the move writes if it is the one applied: schedule words and counter rows of its
+            // layers at steps [base + first flip, base + last flip + 1]
+            const uint64_t fl = R.flip1 | R.flip2;
+            s_wlo[set][w] = fl ? R.base + ctz64(fl) : 0;
+            s_whi[set][w] = fl ? R.base + msb64(fl) + 1 : -1;
+            s_l1[set][w] = (int)m.layer;
+            s_l2[set][w] = R.flip2 ? (int)m.layer2 : (int)m.layer;
+        }
         __syncthreads();
         // the proposals of this round that the walk reaches
         int f = SPEC;
         uint32_t reached = 0;
 #pragma unroll
         for (int k = 0; k < SPEC; k++) {
-            const int v = uniform_i32(s_verdict[k]), acc = uniform_i32(s_accept[k]);
+            const int v = uniform_i32(s_verdict[set][k]), acc = uniform_i32(s_accept[set][k]);
             if (f == SPEC && v >= 0 && reached == (uint32_t)k) {
                 reached++;
                 st.moves_done++;
@@ -630,11 +656,11 @@ __global__ __launch_bounds__(SPEC * KVP_WAVE) void anneal_rounds_kernel(
             }
         }
         if (f < SPEC) {
-            const double dT = uniform_f64(s_dT[f]);
+            const double dT = uniform_f64(s_dT[set][f]);
             st.accepted++;
             if (dT > 0.0) st.uphill++;
             if (w == f) {
-                apply_move(q, X, cnt, occ, m, R);
+                apply_move(q, X, cnt, s_occ, m, R);
                 // edits since the best schedule, so that it can be rebuilt by undoing them
                 if (st.log_len < log_cap && lane < LOG_WORDS) {
                     uint32_t e;
@@ -661,8 +687,27 @@ __global__ __launch_bounds__(SPEC * KVP_WAVE) void anneal_rounds_kernel(
         // the cooling state as the last proposal reached leaves it
         for (const uint32_t to = level_of(mi + reached - 1); st.level < to; st.level++) st.c = st.c * sp.alpha;
         mi += reached;
-        __syncthreads();        // this round's writes before the next round's reads (and the LDS slots are free again)
+        // The next round's proposal and its words, requested while the accepted move is on its way to
+        // memory: the two round trips overlap.
+        const bool more = mi < move_end;
+        if (more) {
+            next_move(q, sp, chain, 0, lane, B, mi + (uint32_t)w < move_end ? mi + (uint32_t)w : mi, m, u);
+            Ld = issue_move<NP, true>(q, X, cnt, nullptr, m, lane);
+        }
+        __syncthreads();        // this round's writes are in memory (and the occupancy in LDS) for every wavefront
+        // words requested before an accepted move that writes among them are requested again
+        if (more && f < SPEC && w != f) {
+            const int w_lo = uniform_i32(s_wlo[set][f]), w_hi = uniform_i32(s_whi[set][f]);
+            const int a1 = uniform_i32(s_l1[set][f]), a2 = uniform_i32(s_l2[set][f]);
+            const int r_lo = (int)m.n1 - 1, r_hi = (int)m.n1 + 63;
+            const int b1 = (int)m.layer, b2 = m.op == KVP_OP_SWAP ? (int)m.layer2 : (int)m.layer;
+            if (w_lo <= r_hi && w_hi >= r_lo && (b1 == a1 || b1 == a2 || b2 == a1 || b2 == a2))
+                Ld = issue_move<NP, true>(q, X, cnt, nullptr, m, lane);
+        }
+        set ^= 1u;
     }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < q.N; i += SPEC * KVP_WAVE) occ[i] = s_occ[i];
     if (threadIdx.x == 0) states[chain] = st;
 }
 
@@ -839,16 +884,18 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
         KVP_HIP(hipGetDeviceProperties(&prop, ctx->device));
         spec = (uint64_t)C * 4 <= 4ull * (uint64_t)prop.multiProcessorCount ? 4 : 1;
     }
+    if ((size_t)q.N * 4 > 48 * 1024) spec = 1;                         // the rounds keep the occupancy of all steps in LDS
     auto launch_rounds = [&](uint64_t b, uint64_t e) {
         const dim3 grid(C), block(4 * KVP_WAVE);
+        const size_t lds = (size_t)q.N * 4;                            // the chain's occupancy
         if (q.pn == 1)
-            anneal_rounds_kernel<1, 4><<<grid, block, 0, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
+            anneal_rounds_kernel<1, 4><<<grid, block, lds, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
                                                                        ctx->d_log, ctx->log_cap, b, e);
         else if (q.pn <= 4)
-            anneal_rounds_kernel<4, 4><<<grid, block, 0, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
+            anneal_rounds_kernel<4, 4><<<grid, block, lds, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
                                                                        ctx->d_log, ctx->log_cap, b, e);
         else
-            anneal_rounds_kernel<KVP_MAX_PLANES, 4><<<grid, block, 0, ctx->stream>>>(
+            anneal_rounds_kernel<KVP_MAX_PLANES, 4><<<grid, block, lds, ctx->stream>>>(
                 q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state, ctx->d_log, ctx->log_cap, b, e);
     };
     const bool rounds = spec == 4;
