@@ -469,6 +469,14 @@ __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams
     uint32_t *occ = occ_all + (size_t)chain * q.N;
     uint32_t *log = log_all + (size_t)chain * log_cap * LOG_WORDS;
     ChainState st = states[chain];
+    // values that only ever enter vector arithmetic or per-lane addresses are moved to vector registers:
+    // the scalar file is the scarce one here, and what does not fit in it is spilled and re-read every move
+    asm volatile("" : "+v"(q.unit_b), "+v"(q.page_b), "+v"(q.token_b), "+v"(q.inv_bh), "+v"(q.inv_bk), "+v"(q.inv_bd),
+                 "+v"(q.inv_min));
+    asm volatile("" : "+v"(q.V), "+v"(q.Pm), "+v"(q.Wm), "+v"(q.acc), "+v"(q.wr), "+v"(q.pl), "+v"(X), "+v"(cnt), "+v"(occ));
+    asm volatile("" : "+v"(st.t_cur), "+v"(st.t_best), "+v"(st.c), "+v"(st.c0), "+v"(sp.alpha));
+    asm volatile("" : "+v"(st.accepted), "+v"(st.uphill), "+v"(st.null_moves), "+v"(st.clipped), "+v"(st.improved),
+                 "+v"(st.moves_done), "+v"(log));
 
     if (calibrate) {
         // initial temperature from the target acceptance p0 of uphill moves:
@@ -601,6 +609,14 @@ __global__ __launch_bounds__(SPEC * KVP_WAVE) void anneal_rounds_kernel(
     uint32_t *occ = occ_all + (size_t)chain * q.N;
     uint32_t *log = log_all + (size_t)chain * log_cap * LOG_WORDS;
     ChainState st = states[chain];
+    // values that only ever enter vector arithmetic or per-lane addresses are moved to vector registers:
+    // the scalar file is the scarce one here, and what does not fit in it is spilled and re-read every move
+    asm volatile("" : "+v"(q.unit_b), "+v"(q.page_b), "+v"(q.token_b), "+v"(q.inv_bh), "+v"(q.inv_bk), "+v"(q.inv_bd),
+                 "+v"(q.inv_min));
+    asm volatile("" : "+v"(q.V), "+v"(q.Pm), "+v"(q.Wm), "+v"(q.acc), "+v"(q.wr), "+v"(q.pl), "+v"(X), "+v"(cnt));
+    asm volatile("" : "+v"(st.t_cur), "+v"(st.t_best), "+v"(st.c), "+v"(st.c0), "+v"(sp.alpha));
+    asm volatile("" : "+v"(st.accepted), "+v"(st.uphill), "+v"(st.null_moves), "+v"(st.clipped), "+v"(st.improved),
+                 "+v"(st.moves_done), "+v"(log));
     for (uint32_t i = threadIdx.x; i < q.N; i += SPEC * KVP_WAVE) s_occ[i] = occ[i];
     __syncthreads();
     DrawBatch B;
