@@ -503,6 +503,38 @@ def test_wr_policy_forgets_pages_that_stop_persisting_and_counts_planes():
     assert X[:, 1, :].tolist() == [[0, 0], [0, 1]]              # nothing is read at step 1: the pool stays
 
 
+def _wr_rows(rows, cap=2):
+    tr = _mini(L=1, N=len(rows), P=len(rows[0]), cap=cap)
+    tr.alive[:] = 1
+    tr.persist[1:] = 1
+    tr.access[0, :, 0, :] = rows
+    return tr
+
+
+def test_wr_policy_evictions_by_hand():
+    """Who leaves a full pool, and how many: three instances worked by hand from the stated reading."""
+    # W = 1, R = 0.5, room for 2.  n=0: only page 2 is read: it comes in (round(0.5) = 1).  n=1: reads (1,1,0,1):
+    # wanted {0,1}, one of the two qualified comes in (page 0), there is room.  n=2: wanted {1} comes in, the pool
+    # {0,2} is full: ONE page leaves, both candidates are unread, so the lower index, page 0.
+    assert O.wr_policy(_wr_rows([[0, 0, 1, 0], [1, 1, 0, 1], [0, 1, 0, 0]]), 1, 5)[0].tolist() == \
+        [[0, 0, 1, 0], [1, 0, 1, 0], [0, 1, 1, 0]]
+    # W = 1, R = 1.  n=0: reads (1,0,1,1): wanted {0,2} come in.  n=1: every page is read once: ranking 0,1,2,3, wanted
+    # {0,1}; page 1 comes in and the unwanted page 2 leaves -- not the wanted page 0, which is read as often and has
+    # the lower index.  n=2: wanted {1,2}: 2 in, 0 out.
+    assert O.wr_policy(_wr_rows([[1, 0, 1, 1], [1, 1, 1, 1], [0, 1, 1, 0]]), 1, 10)[0].tolist() == \
+        [[1, 0, 1, 0], [1, 1, 0, 0], [0, 1, 1, 0]]
+    # W = 2, R = 0.5.  n=0: reads over steps 0,1 are (0,1,2,1): wanted {2,1}, one comes in: page 2.  n=1: steps 1,2:
+    # (1,1,1,2): ranking 3,0,1,2: wanted {3,0}, page 3 comes in, there is room.  n=2: only step 2 is left: (1,1,0,1):
+    # wanted {0,1}, page 0 comes in; of the unwanted pool pages 2 (unread) and 3 (read once) the LEAST read leaves.
+    assert O.wr_policy(_wr_rows([[0, 1, 1, 0], [0, 0, 1, 1], [1, 1, 0, 1]]), 2, 5)[0].tolist() == \
+        [[0, 0, 1, 0], [0, 0, 1, 1], [1, 0, 0, 1]]
+    # a slot re-used by new data at step 1 (it exists before and after, but does not persist): the old entry leaves
+    # the pool, and the new one is not read, so it stays outside
+    tr = _wr_rows([[1, 1], [0, 1]])
+    tr.persist[1, 0] = 0
+    assert O.wr_policy(tr, 1, 10)[0].tolist() == [[1, 1], [0, 1]]
+
+
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_wr_policy_invariants(seed):
     tr = W.random_trace(100 + seed, L=2, N=12, P=9, K=2, cap_pages=5)
