@@ -164,6 +164,17 @@ int kvp_delta_score(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, cons
                     const uint32_t *d_counters, const uint32_t *d_occ, double *d_delta,
                     int32_t *d_verdict);
 
+/* Eq. 5 counted slot by slot.  kvp_score checks the capacity once per token step; here the layers of
+ * a step change their placement one after the other, each at its own slot (n, l), so after slot
+ * (n, l) the pool holds the step-n placement of layers 0..l and still the step-(n-1) placement of
+ * the layers to come (less the pages that do not persist into step n).
+ *   d_placements [S][L][N][Wd]  in (bits on pages that do not exist are ignored)
+ *   d_excess     [S]            largest overshoot of cap_pages over all slots; never less than the
+ *                               excess kvp_score reports, equal to it for a schedule that never migrates
+ * Runs on the context's stream.  S = 0 is a no-op.  Errors: KVP_EINVAL (null or misaligned pointer),
+ * KVP_ENOTRACE, KVP_ESHAPE (more than 2048 layers), KVP_EHIP. */
+int kvp_strict_excess(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, uint32_t *d_excess);
+
 /* Tuning knob of kvp_anneal: how many consecutive proposals of a chain are priced at once, each
  * by a wavefront of its own (the walk takes them in order up to the first accepted one, so it is
  * the same walk whatever the number).  0 (default): chosen from the number of chains and the

@@ -92,6 +92,8 @@ def lib():
         L.orc_init_static_frequency.argtypes = [C.POINTER(_Problem), C.c_void_p]
         L.orc_init_recency.argtypes = [C.POINTER(_Problem), C.c_void_p]
         L.orc_init_static_fill.argtypes = [C.POINTER(_Problem), C.c_void_p]
+        L.orc_strict_excess.restype = C.c_uint32
+        L.orc_strict_excess.argtypes = [C.POINTER(_Problem), C.c_void_p]
         L.orc_bruteforce.restype = C.c_int
         L.orc_bruteforce.argtypes = [C.POINTER(_Problem), C.POINTER(C.c_double), C.c_void_p,
                                      C.POINTER(C.c_uint64)]
@@ -189,6 +191,13 @@ def cost(tr, X) -> float:
     q = _problem(tr)
     X = _u8(X, q.shape)
     return lib().orc_score(C.byref(q.c), X.ctypes.data, None, None, None, None)
+
+
+def strict_excess(tr, X) -> int:
+    """Largest overshoot of the capacity when it is counted after every (step, layer) slot."""
+    q = _problem(tr)
+    X = _u8(X, q.shape)
+    return int(lib().orc_strict_excess(C.byref(q.c), X.ctypes.data))
 
 
 def philox4x32_10(ctr, key):

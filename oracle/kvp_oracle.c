@@ -337,6 +337,33 @@ int orc_delta(const orc_problem *q, const uint8_t *X, const orc_move *m, double 
     return verdict;
 }
 
+/* Occupancy slot by slot (Eq. 5 read strictly): the layers of a token step change
+ * their placement one after the other, each at its own step (n, l), so between
+ * two layers of step n the pool holds the new placement of the layers done and
+ * still the old one of the layers to come.  Simulated as it happens: at the start
+ * of step n the pages that do not persist into it are gone; then layer after layer
+ * takes its placement of step n, and the pool is counted after each.  Returns the
+ * largest overshoot of cap_pages over all (n, l); never less than the overshoot
+ * counted once per token step. */
+uint32_t orc_strict_excess(const orc_problem *q, const uint8_t *X) {
+    int L = q->L, N = q->N, P = q->P;
+    uint8_t *cur = (uint8_t *)calloc((size_t)L * P ? (size_t)L * P : 1, 1);
+    uint64_t worst = 0;
+    for (int n = 0; n < N; n++) {
+        for (int l = 0; l < L; l++)
+            for (int p = 0; p < P; p++)
+                if (!(n > 0 && pm_bit(q, n, p))) cur[(size_t)l * P + p] = 0;
+        for (int l = 0; l < L; l++) {
+            for (int p = 0; p < P; p++) cur[(size_t)l * P + p] = (uint8_t)(x_bit(q, X, l, n, p) && v_bit(q, n, p));
+            uint64_t occ = 0;
+            for (size_t i = 0; i < (size_t)L * P; i++) occ += cur[i];
+            if (occ > q->cap_pages && occ - q->cap_pages > worst) worst = occ - q->cap_pages;
+        }
+    }
+    free(cur);
+    return (uint32_t)(worst > 0x7FFFFFFFull ? 0x7FFFFFFFull : worst);
+}
+
 /* ---- starting schedules (the paper's non-migrating and reactive baselines,
  * Sec. IV-A, restated for a pool shared by all layers) ---------------------- */
 

@@ -28,7 +28,7 @@ KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2
 EXPORTS = ["kvp_create", "kvp_destroy", "kvp_trace_upload", "kvp_score", "kvp_delta_score", "kvp_anneal",
            "kvp_best", "kvp_chain_placement", "kvp_chain_stats", "kvp_plane_unit", "kvp_strerror", "kvp_last_hip_error",
            "kvp_set_score_kernel", "kvp_set_anneal_lookahead", "kvp_score_kernel_used", "kvp_baseline", "kvp_wr_policy",
-           "kvp_wr_search"]
+           "kvp_wr_search", "kvp_strict_excess"]
 
 
 class kvp_wr_params(C.Structure):
@@ -111,6 +111,8 @@ def lib():
         L.kvp_plane_unit.argtypes = [vp]
         L.kvp_strerror.restype = C.c_char_p
         L.kvp_strerror.argtypes = [i32]
+        L.kvp_strict_excess.restype = i32
+        L.kvp_strict_excess.argtypes = [vp, vp, C.c_uint32, vp]
         L.kvp_set_anneal_lookahead.restype = i32
         L.kvp_set_anneal_lookahead.argtypes = [vp, i32]
         L.kvp_set_score_kernel.restype = i32
@@ -221,6 +223,10 @@ def kvp_chain_stats(ctx, n_chains):
 
 (KVP_SCORE_AUTO, KVP_SCORE_ROWS, KVP_SCORE_LANES, KVP_SCORE_LANES_8W, KVP_SCORE_DIRECT, KVP_SCORE_DIRECT_8W,
  KVP_SCORE_QUAD, KVP_SCORE_QUAD_4S, KVP_SCORE_WIDE, KVP_SCORE_CHUNK, KVP_SCORE_ROWBLOCK, KVP_SCORE_LINE) = range(12)
+
+
+def kvp_strict_excess(ctx, d_placements, S, d_excess):
+    _check(lib().kvp_strict_excess(ctx, _dptr(d_placements), int(S), _dptr(d_excess)), "kvp_strict_excess")
 
 
 def kvp_set_anneal_lookahead(ctx, proposals_per_round: int):

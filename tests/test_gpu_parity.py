@@ -350,6 +350,31 @@ def test_error_paths_reach_no_kernel(G):
         K.kvp_destroy(ctx)
 
 
+STRICT_CASES = ("tiny", "table1", "llama8b/4", "serving/16", "gqa70b/16", "rand-odd", "rand-tiles", "rand-w40", "one-step",
+                "dec-L80-k8", "dec-L112", "tok-p16")
+
+
+@pytest.mark.parametrize("name,tr", [c for c in CASES if c[0] in STRICT_CASES], ids=lambda v: v if isinstance(v, str) else "")
+def test_strict_excess_matches_oracle(G, name, tr):
+    """Occupancy counted after every (step, layer) slot: bit for bit, and never below the per-step excess."""
+    import torch
+    import paper_2508_13231_amd as K
+    X = np.concatenate([W.random_placements(tr, 4, seed=11, density=0.4),
+                        W.random_placements(tr, 3, seed=12, density=0.9, feasible=False),
+                        W.edge_placements(tr)])
+    q = O.Problem(tr)
+    with G(tr) as g:
+        d_x = g.words(X)
+        d_ex = torch.full((X.shape[0],), -1, dtype=torch.int32, device=g.dev)
+        K.kvp_strict_excess(g.ctx, d_x, X.shape[0], d_ex)
+        torch.cuda.synchronize()
+        got = d_ex.cpu().numpy().view(np.uint32)
+        _, ex, _, _ = g.score(X, counters=False)
+    for s in range(X.shape[0]):
+        assert got[s] == O.strict_excess(q, X[s] & tr.alive[None]), (name, s)
+        assert got[s] >= (ex[s] & 0x7FFFFFFF)
+
+
 BASELINE_CASES = ("tiny", "table1", "llama8b/4", "longctx/8", "serving/16", "gqa70b/16", "rand-odd", "rand-weights",
                   "one-step", "rand-tiles", "rand-512", "rand-w40", "dec-w21-L3", "dec-w38-k3")
 
@@ -496,6 +521,20 @@ def test_full_size_batch_sampled_against_oracle(G, name, kernel):
                 X = g.unpack(d_x[s2].cpu().numpy().view(np.uint32))
                 ov, od, _, _, _ = O.delta(q, X, {k: int(v[s2]) for k, v in mv.items()})
                 assert ver[s2] == ov and dt[s2] == od, (s2, ver[s2], ov, dt[s2], od)
+        if name in ("llama8b", "gqa70b"):
+            # occupancy slot by slot on the whole batch: sampled against the oracle, bounded below by the per-step one
+            d_sx = torch.empty(S, dtype=torch.int32, device=g.dev)
+            t0 = torch.cuda.Event(enable_timing=True); t1 = torch.cuda.Event(enable_timing=True)
+            t0.record()
+            K.kvp_strict_excess(g.ctx, d_x, S, d_sx)
+            t1.record()
+            torch.cuda.synchronize()
+            print(f"{name}: kvp_strict_excess on {S} schedules: {t0.elapsed_time(t1):.2f} ms")
+            sx = d_sx.cpu().numpy().view(np.uint32)
+            assert (sx >= (ex & 0x7FFFFFFF)).all()
+            for s2 in pick[:4]:
+                X = g.unpack(d_x[s2].cpu().numpy().view(np.uint32))
+                assert sx[s2] == O.strict_excess(q, X), s2
         # properties that hold for every schedule of the batch
         assert np.isfinite(cost).all() and (cost > 0).all()
         lo = O.cost(q, np.broadcast_to(tr.alive[None], q.shape).copy()) * tr.bw_hbm / (tr.bw_hbm + tr.bw_link)

@@ -431,6 +431,48 @@ def test_static_fill_never_migrates_and_fills_what_fits(name, scale):
     assert (O.init_static_fill(dataclasses.replace(tr, cap_pages=tr.L * tr.P)) == np.broadcast_to(tr.alive[None], X.shape)).all()
 
 
+# ---- occupancy counted after every (step, layer) slot ----
+
+def test_strict_excess_by_hand():
+    # two layers, one page each, room for one.  Step 0: layer 1 holds its page.  Step 1: layer 0 takes its page in at
+    # slot (1,0), while layer 1 gives its page up only at slot (1,1): two pages in between, one too many, although
+    # every token step as a whole holds one page.
+    tr = _mini(L=2, N=2, P=1, cap=1)
+    tr.alive[:] = 1
+    tr.persist[1:] = 1
+    X = np.zeros((2, 2, 1), np.uint8)
+    X[1, 0, 0] = 1
+    X[0, 1, 0] = 1
+    assert O.score(tr, X).excess == 0 and O.strict_excess(tr, X) == 1
+    # the other way round the page leaves first: no overshoot
+    Y = np.zeros((2, 2, 1), np.uint8)
+    Y[0, 0, 0] = 1
+    Y[1, 1, 0] = 1
+    assert O.score(tr, Y).excess == 0 and O.strict_excess(tr, Y) == 0
+    # a page of layer 1 that does not persist into step 1 is gone before slot (1,0)
+    tr.persist[1, 0] = 0
+    assert O.strict_excess(tr, X) == 0
+
+
+@pytest.mark.parametrize("name,scale", [("tiny", 1.0), ("llama8b", 0.25), ("serving", 0.0625), ("gqa70b", 0.0625)])
+def test_strict_excess_bounds(name, scale):
+    tr = W.config(name, scale)
+    q = O.Problem(tr)
+    # placements that never migrate fill the pool monotonically inside a step: slot by slot is step by step
+    for X in (O.init_static_fill(q), O.init_static_frequency(q)):
+        assert O.strict_excess(q, X) == O.score(q, X).excess == 0
+    # any schedule: never less than the per-step count; at most one layer's swing more
+    for X in W.random_placements(tr, 3, seed=4, density=0.5, feasible=False):
+        per_step = O.score(q, X).excess & 0x7FFFFFFF
+        strict = O.strict_excess(q, X)
+        occ_l = (X & tr.alive[None]).sum(axis=2)                       # [L][N]
+        assert per_step <= strict <= per_step + int(occ_l.sum(axis=0).max())
+    # the last slot of a step is the step: with one layer the two counts agree
+    if tr.L == 1:
+        X = W.random_placements(tr, 1, seed=5, density=0.9, feasible=False)[0]
+        assert O.strict_excess(q, X) == O.score(q, X).excess & 0x7FFFFFFF
+
+
 # ---- token-granular reads inside pages: the plane encoding against the token-level definition ----
 
 def _token_trace(seed=9):
