@@ -21,12 +21,19 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t *p, uint32_t n, 
     if (i < n) p[i] = v;
 }
 
-__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int lane) {
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = (uint32_t)__shfl_up((int)v, d, KVP_WAVE);
-        if (lane >= d) v += o;
-    }
+// Inclusive prefix sum over the 64 lanes without LDS: shifts inside the rows of 16 lanes, then the
+// last lane of a row is broadcast into the next row (rows 1 and 3), then lane 31 into rows 2 and 3.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);   // lanes without a source get 0
+}
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
+    v += dpp_or_zero<0x111, 0xf>(v);     // row_shr:1
+    v += dpp_or_zero<0x112, 0xf>(v);     // row_shr:2
+    v += dpp_or_zero<0x114, 0xf>(v);     // row_shr:4
+    v += dpp_or_zero<0x118, 0xf>(v);     // row_shr:8
+    v += dpp_or_zero<0x142, 0xa>(v);     // row_bcast:15 into rows 1 and 3
+    v += dpp_or_zero<0x143, 0xc>(v);     // row_bcast:31 into rows 2 and 3
     return v;
 }
 
@@ -63,7 +70,7 @@ __global__ __launch_bounds__(SW * KVP_WAVE) void strict_excess_kernel(DevProblem
     for (uint32_t base = 0; base < L; base += KVP_WAVE) {
         const uint32_t l = base + (uint32_t)lane;
         const uint32_t a = l < L ? cnt_new[l] : 0u, b = l < L ? cnt_old[l] : 0u;
-        const uint32_t a_in = wave_incl_scan_u32(a, lane) + new_before, b_in = wave_incl_scan_u32(b, lane) + old_before;
+        const uint32_t a_in = wave_incl_scan_u32(a) + new_before, b_in = wave_incl_scan_u32(b) + old_before;
         if (l < L) worst = max(worst, a_in + (old_total - b_in));      // slot (n, l)
         new_before = (uint32_t)__builtin_amdgcn_readlane((int)a_in, 63);
         old_before = (uint32_t)__builtin_amdgcn_readlane((int)b_in, 63);
