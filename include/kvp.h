@@ -14,9 +14,9 @@
  *   - Pointers named d_* are DEVICE memory on the context's GPU, allocated and
  *     owned by the caller, 16-byte aligned.  Pointers named h_* are HOST memory.
  *     The library copies what it keeps and retains no caller pointer.
- *   - kvp_score, kvp_delta_score and kvp_anneal enqueue their work on the HIP
- *     stream given to kvp_create and return without waiting (they may allocate
- *     internal buffers first).  kvp_trace_upload, kvp_best, kvp_chain_placement
+ *   - kvp_score, kvp_delta_score, kvp_anneal, kvp_baseline, kvp_strict_excess
+ *     enqueue their work on the HIP stream given to kvp_create and return
+ *     without waiting (they may allocate internal buffers first).  kvp_trace_upload, kvp_best, kvp_chain_placement
  *     and kvp_chain_stats wait for the stream.
  *   - Bit masks: uint32 words, bit b of word w is page 32*w + b; bits at or
  *     above n_pages are zero.  A schedule is [n_layers][n_steps][n_words]
@@ -95,7 +95,7 @@ enum {
  * temperature from the target acceptance p0 of uphill moves, geometric cooling
  * by alpha over n_levels levels of equal length, fixed move budget. */
 typedef struct {
-    uint32_t n_chains;     /* independent chains, one wavefront each                      */
+    uint32_t n_chains;     /* independent chains (one to four wavefronts each)            */
     uint32_t n_levels;     /* temperature levels (>= 1), e.g. 100                          */
     uint64_t seed;         /* Philox4x32-10 key; the chain id is part of the counter      */
     uint64_t total_moves;  /* length of the whole cooling schedule, per chain             */
