@@ -202,10 +202,14 @@ extern "C" int kvp_wr_search(kvp_ctx *ctx, const kvp_wr_params *sp, double *h_ta
     KVP_HIP(hipSetDevice(ctx->device));
     *res = kvp_wr_result{};
     // T(w, r10).  An unknown cost is never evaluated alone: the states nearest to the current one
-    // (cw, cr) that are still unknown go with it, as many as fit 4 GiB of schedules (at least the
-    // 14 states one proposal away), in one batch for the generator and the scorer.
+    // (cw, cr) that are still unknown go with it, in one batch for the generator (a workgroup per
+    // state: a batch should have a few hundred to fill the GPU) and the scorer.  The batch takes up
+    // to a third of the free device memory, at least 4 GiB and at least the 14 states one proposal away.
     int err = KVP_OK;
-    const size_t fit = (size_t)(4ull << 30) / (words * 4);
+    size_t mem_free = 0, mem_total = 0;
+    KVP_HIP(hipMemGetInfo(&mem_free, &mem_total));
+    const size_t budget = mem_free / 3 > ((size_t)4 << 30) ? mem_free / 3 : ((size_t)4 << 30);
+    const size_t fit = budget / (words * 4);
     const size_t batch_max = fit > 15 ? fit : 15;
     auto cost = [&](uint32_t w, uint32_t r10, uint32_t cw, uint32_t cr) -> double {
         double &slot = h_table[(size_t)(w - 1) * 11 + r10];
