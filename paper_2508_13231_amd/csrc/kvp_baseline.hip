@@ -22,24 +22,24 @@
 namespace {
 
 // how often each (layer, page) is read over the trace, summed over the planes: [L][Wd][32]
-__global__ __launch_bounds__(256) void read_counts_kernel(DevProblem q, uint32_t *__restrict__ freq) {
+__global__ __launch_bounds__(256) void read_counts_kernel(DevProblem q, RowDiv rd, uint32_t *__restrict__ freq) {
     const uint32_t g = blockIdx.x * 256 + threadIdx.x;
     if (g >= q.L * q.Wd * 32) return;
-    const uint32_t wi = g >> 5, b = g & 31u, l = wi / q.Wd, w = wi - l * q.Wd;
+    const uint32_t wi = g >> 5, b = g & 31u, l = rd.quot(wi), w = wi - l * q.Wd;
     uint32_t f = 0;
     for (uint32_t n = 0; n < q.N; n++)
         for (uint32_t k = 0; k < q.K; k++) f += (q.A[(((size_t)l * q.N + n) * q.K + k) * q.Wd + w] >> b) & 1u;
     freq[g] = f;
 }
 
-__global__ __launch_bounds__(BT) void static_select_kernel(DevProblem q, uint64_t cap, uint32_t nbins,
+__global__ __launch_bounds__(BT) void static_select_kernel(DevProblem q, RowDiv rd, uint64_t cap, uint32_t nbins,
                                                            const uint32_t *__restrict__ freq,
                                                            uint32_t *__restrict__ chosen) {
     extern __shared__ uint32_t lds_u[];
     __shared__ SelectShared sh;
     const uint32_t G = q.L * q.Wd * 32;
     auto key = [&](uint32_t g) {
-        const uint32_t w = (g >> 5) % q.Wd, p = 32 * w + (g & 31u);
+        const uint32_t w = rd.rem(g >> 5), p = 32 * w + (g & 31u);
         return p < q.P ? freq[g] : NOT_A_CANDIDATE;                    // every pair competes, existing or not
     };
     block_select(G, nbins, cap, lds_u, sh, key, key, [&](uint32_t word, uint32_t bits) { chosen[word] = bits; });
@@ -57,7 +57,7 @@ __global__ __launch_bounds__(256) void static_fill_kernel(DevProblem q, const ui
 
 // the whole recency placement, step after step, in one workgroup: last[g] = last step at which the
 // pair was read since it last (re)started to persist, -1 if never
-__global__ __launch_bounds__(BT) void recency_kernel(DevProblem q, uint64_t cap, int32_t *__restrict__ last,
+__global__ __launch_bounds__(BT) void recency_kernel(DevProblem q, RowDiv rd, uint64_t cap, int32_t *__restrict__ last,
                                                      uint32_t *__restrict__ X) {
     extern __shared__ uint32_t lds_u[];
     __shared__ SelectShared sh;
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(BT) void recency_kernel(DevProblem q, uint64_t cap,
     __syncthreads();
     for (uint32_t n = 0; n < q.N; n++) {
         auto key = [&](uint32_t g) {
-            const uint32_t w = (g >> 5) % q.Wd, b = g & 31u;
+            const uint32_t w = rd.rem(g >> 5), b = g & 31u;
             const uint32_t vw = q.V[(size_t)n * q.Wd + w];             // dead bits of the last word are never alive
             int32_t lv = last[g];
             asm volatile("" : "+v"(lv));                               // loaded whether alive or not: no branch, loads overlap
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(BT) void recency_kernel(DevProblem q, uint64_t cap,
         };
         auto first_key = [&](uint32_t g) {
             if (n > 0) {
-                const uint32_t wi = g >> 5, b = g & 31u, l = wi / q.Wd, w = wi - l * q.Wd;
+                const uint32_t wi = g >> 5, b = g & 31u, l = rd.quot(wi), w = wi - l * q.Wd;
                 if (!((q.Pm[(size_t)n * q.Wd + w] >> b) & 1u)) {
                     last[g] = -1;                                      // a page that stops persisting forgets its history
                 } else {
@@ -173,6 +173,7 @@ extern "C" int kvp_baseline(kvp_ctx *ctx, int kind, uint32_t *d_placement) {
     if (G64 >= (1ull << 31)) return KVP_ESHAPE;
     const uint32_t G = (uint32_t)G64;
     const uint64_t cap = ctx->prob.cap_pages;
+    const RowDiv rd(q.Wd, (uint64_t)q.L * q.Wd);
     const uint32_t nbins = kind == KVP_BASELINE_STATIC ? q.N * q.K + 1 : kind == KVP_BASELINE_RECENCY ? q.N + 1 : 0;
     const size_t lds = (size_t)nbins * 4;
     if (lds > 128 * 1024) return KVP_ESHAPE;
@@ -181,11 +182,11 @@ extern "C" int kvp_baseline(kvp_ctx *ctx, int kind, uint32_t *d_placement) {
     uint32_t *work = ctx->d_cnt_tmp;                                   // [G] keys, then [L][Wd] chosen words
     if (kind == KVP_BASELINE_STATIC) {
         uint32_t *chosen = work + G;
-        read_counts_kernel<<<dim3((G + 255) / 256), dim3(256), 0, ctx->stream>>>(q, work);
+        read_counts_kernel<<<dim3((G + 255) / 256), dim3(256), 0, ctx->stream>>>(q, rd, work);
         KVP_HIP(hipGetLastError());
         if (lds > 48 * 1024)
             KVP_HIP(hipFuncSetAttribute((const void *)static_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        static_select_kernel<<<dim3(1), dim3(BT), lds, ctx->stream>>>(q, cap, nbins, work, chosen);
+        static_select_kernel<<<dim3(1), dim3(BT), lds, ctx->stream>>>(q, rd, cap, nbins, work, chosen);
         KVP_HIP(hipGetLastError());
         const size_t words = (size_t)q.L * q.N * q.Wd;
         static_fill_kernel<<<dim3((uint32_t)((words + 255) / 256)), dim3(256), 0, ctx->stream>>>(q, chosen, d_placement);
@@ -196,7 +197,7 @@ extern "C" int kvp_baseline(kvp_ctx *ctx, int kind, uint32_t *d_placement) {
     } else {
         if (lds > 48 * 1024)
             KVP_HIP(hipFuncSetAttribute((const void *)recency_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        recency_kernel<<<dim3(1), dim3(BT), lds, ctx->stream>>>(q, cap, (int32_t *)work, d_placement);
+        recency_kernel<<<dim3(1), dim3(BT), lds, ctx->stream>>>(q, rd, cap, (int32_t *)work, d_placement);
         KVP_HIP(hipGetLastError());
     }
     return KVP_OK;

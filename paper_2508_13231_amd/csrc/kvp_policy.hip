@@ -37,8 +37,11 @@ __device__ __forceinline__ uint32_t reads_at(const DevProblem &q, uint32_t l, ui
     return s;
 }
 
-// work per candidate: f[G] window counts, pool[LW] and wanted[LW] mask words
-__global__ __launch_bounds__(BT) void wr_policy_kernel(DevProblem q, uint64_t cap, const uint32_t *__restrict__ cand_w,
+// work per candidate: pool[LW] and wanted[LW] mask words, then f[G] window counts.  The counts are
+// what the kernel streams through, several times per step: FT is the narrowest type that holds
+// W * K (a byte for one plane and any window up to 255 steps).
+template <class FT>
+__global__ __launch_bounds__(BT) void wr_policy_kernel(DevProblem q, RowDiv rd, uint64_t cap, const uint32_t *__restrict__ cand_w,
                                                        const uint32_t *__restrict__ cand_r10, uint32_t *work,
                                                        size_t work_stride, uint32_t *Xall) {
     extern __shared__ uint32_t lds_u[];
@@ -47,34 +50,35 @@ __global__ __launch_bounds__(BT) void wr_policy_kernel(DevProblem q, uint64_t ca
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t LW = q.L * q.Wd, G = LW * 32;
     const uint32_t W = min(cand_w[blockIdx.x], q.N), r10 = cand_r10[blockIdx.x];
-    uint32_t *f = work + (size_t)blockIdx.x * work_stride, *pool = f + G, *wanted = pool + LW;
+    uint32_t *pool = work + (size_t)blockIdx.x * work_stride, *wanted = pool + LW;
+    FT *f = (FT *)(wanted + LW);
     uint32_t *X = Xall + (size_t)blockIdx.x * q.L * q.N * q.Wd;
     const uint32_t fmax = W * q.K, nbins = fmax + 1;
 
     for (uint32_t wi = tid; wi < LW; wi += BT) pool[wi] = 0;
     for (uint32_t g = tid; g < G; g += BT) {
-        const uint32_t wi = g >> 5, b = g & 31u, l = wi / q.Wd, w = wi - l * q.Wd;
+        const uint32_t wi = g >> 5, b = g & 31u, l = rd.quot(wi), w = wi - l * q.Wd;
         uint32_t s = 0;
         for (uint32_t m = 0; m < W; m++) s += reads_at(q, l, m, w, b);
-        f[g] = s;
+        f[g] = (FT)s;
     }
     __syncthreads();
     for (uint32_t n = 0; n < q.N; n++) {
         if (n > 0)                                                     // the window slides: step n-1 leaves, n+W-1 enters
             for (uint32_t g = tid; g < G; g += BT) {
-                const uint32_t wi = g >> 5, b = g & 31u, l = wi / q.Wd, w = wi - l * q.Wd;
-                uint32_t s = f[g] - reads_at(q, l, n - 1, w, b);
+                const uint32_t wi = g >> 5, b = g & 31u, l = rd.quot(wi), w = wi - l * q.Wd;
+                uint32_t s = (uint32_t)f[g] - reads_at(q, l, n - 1, w, b);
                 if (n + W - 1 < q.N) s += reads_at(q, l, n + W - 1, w, b);
-                f[g] = s;
+                f[g] = (FT)s;
             }
-        for (uint32_t wi = tid; wi < LW; wi += BT) pool[wi] &= q.Pm[(size_t)n * q.Wd + wi % q.Wd];   // step 1
+        for (uint32_t wi = tid; wi < LW; wi += BT) pool[wi] &= q.Pm[(size_t)n * q.Wd + rd.rem(wi)];   // step 1
         if (tid < 2) counts[tid] = 0;
         __syncthreads();
         // steps 2 and 3: the wanted set
         auto key_want = [&](uint32_t g) {
-            const uint32_t w = (g >> 5) % q.Wd, b = g & 31u;
+            const uint32_t w = rd.rem(g >> 5), b = g & 31u;
             const uint32_t vw = q.V[(size_t)n * q.Wd + w];
-            uint32_t fv = f[g];
+            uint32_t fv = (uint32_t)f[g];
             asm volatile("" : "+v"(fv));                               // loaded whether the page exists or not
             return ((vw >> b) & 1u) && fv > 0 ? fv : NOT_A_CANDIDATE;
         };
@@ -97,7 +101,7 @@ __global__ __launch_bounds__(BT) void wr_policy_kernel(DevProblem q, uint64_t ca
             auto key_out = [&](uint32_t g) {
                 const uint32_t wi = g >> 5, b = g & 31u;
                 const uint32_t pw = pool[wi], ww = wanted[wi];
-                uint32_t fv = f[g];
+                uint32_t fv = (uint32_t)f[g];
                 asm volatile("" : "+v"(fv));
                 return ((pw & ~ww) >> b) & 1u ? fmax - fv : NOT_A_CANDIDATE;
             };
@@ -108,7 +112,7 @@ __global__ __launch_bounds__(BT) void wr_policy_kernel(DevProblem q, uint64_t ca
             auto key_in = [&](uint32_t g) {
                 const uint32_t wi = g >> 5, b = g & 31u;
                 const uint32_t pw = pool[wi], ww = wanted[wi];
-                uint32_t fv = f[g];
+                uint32_t fv = (uint32_t)f[g];
                 asm volatile("" : "+v"(fv));
                 return ((ww & ~pw) >> b) & 1u ? fv : NOT_A_CANDIDATE;
             };
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(BT) void wr_policy_kernel(DevProblem q, uint64_t ca
                          [&](uint32_t word, uint32_t bits) { pool[word] |= bits; });
         }
         for (uint32_t wi = tid; wi < LW; wi += BT) {                   // step 6
-            const uint32_t l = wi / q.Wd, w = wi - l * q.Wd;
+            const uint32_t l = rd.quot(wi), w = wi - l * q.Wd;
             X[((size_t)l * q.N + n) * q.Wd + w] = pool[wi];
         }
         __syncthreads();
@@ -143,17 +147,28 @@ extern "C" int kvp_wr_policy(kvp_ctx *ctx, uint32_t n, const uint32_t *h_w, cons
     const size_t lds = ((size_t)wmax * q.K + 1) * 4;
     if (lds > 128 * 1024) return KVP_ESHAPE;
     KVP_HIP(hipSetDevice(ctx->device));
-    const size_t LW = (size_t)q.L * q.Wd, stride = (size_t)G64 + 2 * LW;
+    const RowDiv rd(q.Wd, (uint64_t)q.L * q.Wd);
+    const uint64_t fmax = (uint64_t)wmax * q.K;
+    const size_t fbytes = fmax <= 0xFF ? 1 : fmax <= 0xFFFF ? 2 : 4;
+    const size_t LW = (size_t)q.L * q.Wd, stride = 2 * LW + ((size_t)G64 * fbytes + 3) / 4;      // words per candidate
     int rc = kvp_ensure(ctx, (void **)&ctx->d_policy_work, &ctx->policy_work_cap, ((size_t)n * stride + 2 * (size_t)n) * 4);
     if (rc) return rc;
     uint32_t *d_w = ctx->d_policy_work + (size_t)n * stride, *d_r = d_w + n;
     KVP_HIP(hipMemcpyAsync(d_w, h_w, (size_t)n * 4, hipMemcpyHostToDevice, ctx->stream));
     KVP_HIP(hipMemcpyAsync(d_r, h_r10, (size_t)n * 4, hipMemcpyHostToDevice, ctx->stream));
     KVP_HIP(hipStreamSynchronize(ctx->stream));                        // the host arrays may go away after the call
-    if (lds > 48 * 1024)
-        KVP_HIP(hipFuncSetAttribute((const void *)wr_policy_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    wr_policy_kernel<<<dim3(n), dim3(BT), lds, ctx->stream>>>(q, ctx->prob.cap_pages, d_w, d_r, ctx->d_policy_work, stride,
-                                                             d_placements);
+#define KVP_POLICY(FT)                                                                                              \
+    do {                                                                                                            \
+        if (lds > 48 * 1024)                                                                                        \
+            KVP_HIP(hipFuncSetAttribute((const void *)wr_policy_kernel<FT>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                        (int)lds));                                                                 \
+        wr_policy_kernel<FT><<<dim3(n), dim3(BT), lds, ctx->stream>>>(q, rd, ctx->prob.cap_pages, d_w, d_r,           \
+                                                                       ctx->d_policy_work, stride, d_placements);   \
+    } while (0)
+    if (fbytes == 1) KVP_POLICY(uint8_t);
+    else if (fbytes == 2) KVP_POLICY(uint16_t);
+    else KVP_POLICY(uint32_t);
+#undef KVP_POLICY
     KVP_HIP(hipGetLastError());
     return KVP_OK;
 }

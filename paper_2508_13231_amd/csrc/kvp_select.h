@@ -6,9 +6,25 @@
 
 namespace {
 
+// Division of a word index by the row width without the integer-division sequence: one multiply.
+// m = ceil(2^32 / d) gives floor(x / d) = mulhi(x, m) for every x with x * d < 2^32 (the error term
+// m * d - 2^32 is below d); wider problems keep m = 0 and divide.
+struct RowDiv {
+    uint32_t d, m;
+    __host__ __device__ RowDiv() : d(1), m(0) {}
+    __host__ RowDiv(uint32_t width, uint64_t largest_x) : d(width), m(0) {
+        if (width > 1 && largest_x * width < (1ull << 32)) m = (uint32_t)(((1ull << 32) + width - 1) / width);
+    }
+#ifdef __HIPCC__
+    __device__ __forceinline__ uint32_t quot(uint32_t x) const { return m ? __umulhi(x, m) : x / d; }
+    __device__ __forceinline__ uint32_t rem(uint32_t x) const { return x - quot(x) * d; }
+#endif
+};
+
 constexpr int BT = 1024;                 // threads of the selecting workgroup
 constexpr int BW = BT / KVP_WAVE;        // its wavefronts
 constexpr uint32_t NOT_A_CANDIDATE = 0xFFFFFFFFu;
+constexpr int CU = 8;                    // chunks of 64 items whose loads a wavefront keeps in flight
 
 struct SelectShared {
     uint32_t part[BT];                   // partial sums of the histogram scan
@@ -30,17 +46,18 @@ __device__ __forceinline__ void block_select(uint32_t G, uint32_t nbins, uint64_
     for (uint32_t k = tid; k < nbins; k += BT) hist[k] = 0;
     __syncthreads();
     // keys into the histogram; the two most crowded bins (0 and the last) are counted with ballots.
-    // Four chunks at a time, so that four sets of loads are in flight per wavefront.
+    // CU chunks at a time, so that as many sets of loads are in flight per wavefront (the passes
+    // are bound by memory latency: one workgroup has a whole problem's pairs to walk).
     uint32_t n0 = 0, nl = 0;
-    for (uint32_t c = c_lo; c < c_hi; c += 4) {
-        uint32_t k[4];
+    for (uint32_t c = c_lo; c < c_hi; c += CU) {
+        uint32_t k[CU];
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
+        for (int u = 0; u < CU; u++) {
             const uint32_t g = (c + u) * 64 + lane;
             k[u] = (c + u < c_hi && g < G) ? first_key(g) : NOT_A_CANDIDATE;
         }
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
+        for (int u = 0; u < CU; u++) {
             n0 += __popcll(__ballot(k[u] == 0));
             nl += __popcll(__ballot(k[u] == nbins - 1 && k[u] != 0));
             if (k[u] != NOT_A_CANDIDATE && k[u] != 0 && k[u] != nbins - 1) atomicAdd(&hist[k[u]], 1u);
@@ -82,29 +99,29 @@ __device__ __forceinline__ void block_select(uint32_t G, uint32_t nbins, uint64_
     // items at the threshold, counted per wavefront, then numbered in index order
     uint32_t ties = 0;
     if (!all)
-        for (uint32_t c = c_lo; c < c_hi; c += 4) {
-            uint32_t k[4];
+        for (uint32_t c = c_lo; c < c_hi; c += CU) {
+            uint32_t k[CU];
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
+            for (int u = 0; u < CU; u++) {
                 const uint32_t g = (c + u) * 64 + lane;
                 k[u] = (c + u < c_hi && g < G) ? key(g) : NOT_A_CANDIDATE;
             }
 #pragma unroll
-            for (int u = 0; u < 4; u++) ties += __popcll(__ballot(k[u] == T));
+            for (int u = 0; u < CU; u++) ties += __popcll(__ballot(k[u] == T));
         }
     if (lane == 0) sh.wave_ties[wave] = ties;
     __syncthreads();
     uint32_t rank0 = 0;
     for (uint32_t w = 0; w < wave; w++) rank0 += sh.wave_ties[w];
-    for (uint32_t c0 = c_lo; c0 < c_hi; c0 += 4) {
-        uint32_t kk[4];
+    for (uint32_t c0 = c_lo; c0 < c_hi; c0 += CU) {
+        uint32_t kk[CU];
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
+        for (int u = 0; u < CU; u++) {
             const uint32_t g = (c0 + u) * 64 + lane;
             kk[u] = (c0 + u < c_hi && g < G) ? key(g) : NOT_A_CANDIDATE;
         }
 #pragma unroll
-        for (int u = 0; u < 4; u++) {
+        for (int u = 0; u < CU; u++) {
             const uint32_t c = c0 + u, k = kk[u];
             if (c >= c_hi) break;                                      // the same for the whole wavefront
             const uint64_t tie = __ballot(k == T);
