@@ -187,10 +187,11 @@ def _anneal_gpu(g, tr, chains, total, moves=None, init=None, seed=0, mode=None, 
                                                              ("table1", 1.0, 4, 2000, 5),
                                                              ("llama8b", 0.125, 4, 3000, 63),
                                                              ("serving", 0.0625, 4, 3000, 31),
-                                                             ("gqa70b", 0.0625, 3, 3000, 63)])
+                                                             ("gqa70b", 0.0625, 3, 3000, 63),
+                                                             ("tok-p16", None, 3, 3000, 63)])   # five weight planes
 def test_anneal_against_oracle_at_equal_budget(G, name, scale, chains, total, max_len, lookahead):
     import paper_2508_13231_amd as K
-    tr = W.config(name, scale)
+    tr = dict(CASES)[name] if scale is None else W.config(name, scale)
     q = O.Problem(tr)
     X0 = O.init_static_frequency(q) if name != "table1" else np.zeros(q.shape, np.uint8)
     res, bi = O.anneal(q, range(chains), X0, seed=tr.seed, total_moves=total, max_len=max_len)
