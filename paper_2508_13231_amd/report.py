@@ -6,6 +6,7 @@ rate under low and high variation of token importance.
 
     python -m paper_2508_13231_amd.report            # 4096-token prompt, 256 decode steps, 32 layers
     python -m paper_2508_13231_amd.report --quick    # a small shape, seconds
+    python -m paper_2508_13231_amd.report --config longctx   # one of the benchmark workloads instead
 
 Everything runs on the GPU through the library; the traces are synthetic (the
 paper's are recorded attention of LLaMA-3.1-8B on NarrativeQA), so the numbers
@@ -135,13 +136,38 @@ def evaluate(tok, w_max, refine_moves, chains):
 ORDER = ["unlimited", "static", "reactive", "page-16", "page-16/t", "SA-guided"]
 
 
+def config_row(name, w_max):
+    """The named benchmark workload (pages as the trace has them): total decode latency of each
+    strategy, the search refined by the workload's own chains and move budget."""
+    tr = W.config(name)
+    with Session(tr) as s:
+        out = {"unlimited": s.unlimited(), "fill": s.baseline(K.KVP_BASELINE_FILL),
+               "by frequency": s.baseline(K.KVP_BASELINE_STATIC), "recency": s.baseline(K.KVP_BASELINE_RECENCY)}
+        t0 = time.perf_counter()
+        r = s.policy_search(w_max)
+        t1 = time.perf_counter()
+        out[f"(W,R) policy, W={r['W']} R={r['R']:.1f} ({t1 - t0:.2f} s)"] = (r["T"], r["hit"])
+        r2 = s.policy_search(w_max, refine_moves=tr.moves, chains=tr.chains)
+        out[f"direct search from it, {tr.chains} chains x {tr.moves} moves ({time.perf_counter() - t1:.2f} s)"] = (r2["T"], r2["hit"])
+    print(f"{name}: L={tr.L} N={tr.N} P={tr.P} K={tr.K}, HBM for {tr.cap_pages} pages\n")
+    print("| strategy | total decode latency T (s) | HBM hit rate |")
+    print("|---|---|---|")
+    for k, (T, hit) in out.items():
+        print(f"| {k} | {T:.6e} | {hit:.1%} |")
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--quick", action="store_true")
     ap.add_argument("--w-max", type=int, default=32)
     ap.add_argument("--refine-moves", type=int, default=20000, help="direct-search moves per chain (0: none)")
     ap.add_argument("--chains", type=int, default=64)
+    ap.add_argument("--config", default=None, help="one of the benchmark workloads instead of the sweeps: "
+                                                   "tiny | llama8b | longctx | serving | gqa70b")
     a = ap.parse_args()
+    if a.config:
+        config_row(a.config, a.w_max)
+        return
     shape = (4, 64, 1024) if a.quick else (32, 256, 4096)
     print(f"shape: {shape[0]} layers, {shape[1]} decode steps, prompt of {shape[2]} tokens; HBM holds 30 % of the "
           f"entries; HBM : link : DRAM = 8 : 1 : 1\n")
