@@ -892,13 +892,16 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
                 q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state, ctx->d_log, ctx->log_cap, b, e, calibrate);
     };
     // Proposals priced per round: four, each by a wavefront of its own, while that leaves every
-    // wavefront a SIMD to itself (four SIMDs per compute unit); with more chains than that the
-    // serial loop, one wavefront per chain, is the faster one (measured: 512 and 1024 chains).
+    // wavefront a SIMD to itself (four SIMDs per compute unit) and while the chains' state stays in
+    // the 256 MB last-level cache.  Otherwise the serial loop, one wavefront per chain, is the faster
+    // one: with more wavefronts they share SIMDs, and with the state out in HBM a round waits for
+    // the slowest of four sets of scattered loads (measured: 512 and 1024 chains; 256 chains of 32 MB).
     int spec = ctx->anneal_lookahead;
     if (spec == 0) {
         hipDeviceProp_t prop;
         KVP_HIP(hipGetDeviceProperties(&prop, ctx->device));
-        spec = (uint64_t)C * 4 <= 4ull * (uint64_t)prop.multiProcessorCount ? 4 : 1;
+        const uint64_t state = (uint64_t)C * ((uint64_t)q.L * q.N * ((uint64_t)q.Wd * 4 + 16) + (uint64_t)q.N * 4);
+        spec = (uint64_t)C * 4 <= 4ull * (uint64_t)prop.multiProcessorCount && state <= (256ull << 20) ? 4 : 1;
     }
     if ((size_t)q.N * 4 > 48 * 1024) spec = 1;                         // the rounds keep the occupancy of all steps in LDS
     auto launch_rounds = [&](uint64_t b, uint64_t e) {
