@@ -50,6 +50,9 @@ extern "C" int kvp_create(kvp_ctx **out, int device, void *hip_stream) {
     if (!c) return KVP_ENOMEM;
     c->device = device;
     c->stream = (hipStream_t)hip_stream;
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1) cus = 1;
+    c->compute_units = (uint32_t)cus;
     *out = c;
     return KVP_OK;
 }

@@ -50,6 +50,7 @@ struct kvp_ctx {
     DevProblem dp{};
     uint64_t unit = 0;
     int score_kernel = 0;                // KVP_SCORE_AUTO, or the scorer kvp_score tries first
+    uint32_t compute_units = 1;          // of the context's GPU
     int anneal_lookahead = 0;            // proposals per round in kvp_anneal: 0 auto, 1 or 4
     int last_kernel = 0;                 // scorer that the last kvp_score ran (KVP_SCORE_*), 0 before the first
     bool prefix_full = false;            // on every 64-step tile all mask words but the last are FULL

@@ -898,10 +898,8 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
     // the slowest of four sets of scattered loads (measured: 512 and 1024 chains; 256 chains of 32 MB).
     int spec = ctx->anneal_lookahead;
     if (spec == 0) {
-        hipDeviceProp_t prop;
-        KVP_HIP(hipGetDeviceProperties(&prop, ctx->device));
         const uint64_t state = (uint64_t)C * ((uint64_t)q.L * q.N * ((uint64_t)q.Wd * 4 + 16) + (uint64_t)q.N * 4);
-        spec = (uint64_t)C * 4 <= 4ull * (uint64_t)prop.multiProcessorCount && state <= (256ull << 20) ? 4 : 1;
+        spec = (uint64_t)C * 4 <= 4ull * ctx->compute_units && state <= (256ull << 20) ? 4 : 1;
     }
     if ((size_t)q.N * 4 > 48 * 1024) spec = 1;                         // the rounds keep the occupancy of all steps in LDS
     auto launch_rounds = [&](uint64_t b, uint64_t e) {
