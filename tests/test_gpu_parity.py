@@ -303,6 +303,11 @@ def test_error_paths_reach_no_kernel(G):
         with pytest.raises(K.KvpError) as e:
             K.kvp_score(ctx, d, 1, c, d)
         assert e.value.code == K.KVP_ENOTRACE
+        for call in (lambda: K.kvp_baseline(ctx, K.KVP_BASELINE_FILL, d), lambda: K.kvp_strict_excess(ctx, d, 1, d),
+                     lambda: K.kvp_wr_policy(ctx, [1], [5], d), lambda: K.kvp_wr_search(ctx, 4, 10)):
+            with pytest.raises(K.KvpError) as e:                    # the newer calls need a trace too
+                call()
+            assert e.value.code == K.KVP_ENOTRACE
         acc, al, pm, wm = (W.pack_bits(a) for a in (tr.access, tr.alive, tr.persist, tr.written))
 
         def prob(**kw):
@@ -336,6 +341,20 @@ def test_error_paths_reach_no_kernel(G):
             K.kvp_score(ctx, d[1:], 1, c, d)
         assert e.value.code == K.KVP_EINVAL
         K.kvp_score(ctx, d, 0, c, d)                                # S = 0 is a no-op
+        K.kvp_strict_excess(ctx, d, 0, d)
+        K.kvp_wr_policy(ctx, [], [], d)
+        for call, want in ((lambda: K.kvp_baseline(ctx, 7, d), K.KVP_EINVAL),                 # unknown kind
+                           (lambda: K.kvp_baseline(ctx, K.KVP_BASELINE_FILL, None), K.KVP_EINVAL),
+                           (lambda: K.kvp_strict_excess(ctx, None, 1, d), K.KVP_EINVAL),
+                           (lambda: K.kvp_strict_excess(ctx, d, 1, None), K.KVP_EINVAL),
+                           (lambda: K.kvp_wr_policy(ctx, [0], [5], d), K.KVP_EINVAL),       # a window of no steps
+                           (lambda: K.kvp_wr_policy(ctx, [1], [11], d), K.KVP_EINVAL),      # R above 1
+                           (lambda: K.kvp_wr_search(ctx, 0, 10), K.KVP_EINVAL),
+                           (lambda: K.kvp_wr_search(ctx, 4, 10, w0=5), K.KVP_EINVAL),
+                           (lambda: K.kvp_wr_search(ctx, 4, 10, p0=1.0), K.KVP_EINVAL)):
+            with pytest.raises(K.KvpError) as e:
+                call()
+            assert e.value.code == want
         with pytest.raises(K.KvpError) as e:
             K.kvp_best(ctx, (tr.L, tr.N, tr.n_words))
         assert e.value.code == K.KVP_ENOCHAINS
