@@ -33,7 +33,9 @@ __global__ __launch_bounds__(NW * 64) void score_lane_rows_kernel(
     constexpr int XV = vecs_per_lane((TILE_N + 1) * WD);
     constexpr int AV1 = vecs_per_lane(TILE_N * WD);
     constexpr int WREG = W1 ? 1 : WD;
-    const uint32_t L = q.L, N = q.N, K = q.K;
+    // the read weights come as weight planes: the access planes themselves, or (fewer) the binary digits
+    // of the pages' read weights
+    const uint32_t L = q.L, N = q.N, K = q.pn;
     const uint32_t AW = (TILE_N * K * WD + 3 + 3) / 4 * 4;
     const uint32_t s = blockIdx.x, tile = blockIdx.y;
     const uint32_t n0 = tile * TILE_N;
@@ -79,7 +81,7 @@ __global__ __launch_bounds__(NW * 64) void score_lane_rows_kernel(
     auto chunk_a = [&](uint32_t l) { return ((size_t)l * N + n0) * K * WD; };
     if (wave < L) {
         stage_load<XV>(sx, X, chunk_x(wave), rows * WD + halo, x_total, lane, xshift, xnvec);
-        if (K1) stage_load<AV1>(sa, q.A, chunk_a(wave), rows * WD, a_total, lane, ashift, anvec);
+        if (K1) stage_load<AV1>(sa, q.pl, chunk_a(wave), rows * WD, a_total, lane, ashift, anvec);
     }
     for (uint32_t l = wave; l < L; l += NW) {
         stage_commit<XV>(sx, xbuf, xnvec, lane);
@@ -93,7 +95,7 @@ __global__ __launch_bounds__(NW * 64) void score_lane_rows_kernel(
             const size_t start = chunk_a(l), a0 = start & ~(size_t)3;
             as = (uint32_t)(start - a0);
             const uint32_t nv = (as + rows * K * WD + 3) >> 2;
-            const uint32_t *p = q.A + a0;
+            const uint32_t *p = q.pl + a0;
             const uint32_t left = (uint32_t)min((size_t)0xFFFFFFFFu, a_total - a0);
             for (uint32_t vi = lane; vi < nv; vi += 64) {
                 uint4 r = make_uint4(0, 0, 0, 0);
@@ -108,7 +110,7 @@ __global__ __launch_bounds__(NW * 64) void score_lane_rows_kernel(
         }
         if (l + NW < L) {                                       // next layer's rows are in flight meanwhile
             stage_load<XV>(sx, X, chunk_x(l + NW), rows * WD + halo, x_total, lane, xshift, xnvec);
-            if (K1) stage_load<AV1>(sa, q.A, chunk_a(l + NW), rows * WD, a_total, lane, ashift, anvec);
+            if (K1) stage_load<AV1>(sa, q.pl, chunk_a(l + NW), rows * WD, a_total, lane, ashift, anvec);
         }
         // the wavefront's LDS writes are complete and visible to all its lanes
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -127,7 +129,7 @@ __global__ __launch_bounds__(NW * 64) void score_lane_rows_kernel(
                 if (K1) {
                     hr += __popc(x & ar[w]);
                 } else {
-                    for (uint32_t k = 0; k < K; k++) hr += q.wt[k] * __popc(x & ar[k * WD + w]);
+                    for (uint32_t k = 0; k < K; k++) hr += q.pw[k] * __popc(x & ar[k * WD + w]);
                 }
                 if (!W1) hw += __popc(x & wm[w]);
                 oc += __popc(x);
@@ -179,11 +181,11 @@ template <int WD, int NW>
 int launch_wd_nw(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
                  uint32_t *counters, uint32_t *occ) {
     const DevProblem &q = ctx->dp;
-    const size_t XW = ((TILE_N + 1) * WD + 3 + 3) / 4 * 4, AW = ((size_t)TILE_N * q.K * WD + 3 + 3) / 4 * 4;
+    const size_t XW = ((TILE_N + 1) * WD + 3 + 3) / 4 * 4, AW = ((size_t)TILE_N * q.pn * WD + 3 + 3) / 4 * 4;
     const size_t lds = (size_t)q.L * TB_STRIDE * 8 + (TILE_N + 4) * 4 + NW * (XW + AW) * 4;
     if (lds > 64 * 1024) return 1;
-    const size_t x_total = (size_t)S * q.L * q.N * WD, a_total = (size_t)q.L * q.N * q.K * WD;
-    const bool k1 = q.K == 1 && q.wt[0] == 1, w1 = q.single_write != 0;
+    const size_t x_total = (size_t)S * q.L * q.N * WD, a_total = (size_t)q.L * q.N * q.pn * WD;
+    const bool k1 = q.pn == 1 && q.pw[0] == 1, w1 = q.single_write != 0;
     dim3 grid(S, tiles), block(NW * 64);
 #define KVP_GO(KK, WW)                                                                                  \
     score_lane_rows_kernel<WD, NW, KK, WW><<<grid, block, lds, ctx->stream>>>(                          \

@@ -94,7 +94,7 @@ NATIVE = {
     "chunk": {"rand-wide", "rand-w40", "rand-w300", "rand-w301", "longctx/4", "longctx/2", "rand-w16", "dec-w24-tail"},
     "line": {"rand-wide", "rand-w40", "rand-w300", "rand-w301", "longctx/2", "dec-w38-k3", "dec-w68-k2"},
     "rows": {c[0] for c in CASES},
-    "lanes": {"tiny", "table1", "rand-odd", "rand-tiles", "gqa70b/16", "rand-512", "tok-p16"},
+    "lanes": {"tiny", "table1", "rand-odd", "rand-tiles", "gqa70b/16", "gqa70b/4", "rand-512", "tok-p16"},
     "direct": {"tiny", "table1", "llama8b/4", "rand-odd"},
     "wide": {"rand-wide", "rand-w40", "rand-w300", "rand-w301"},
     "quad": {"llama8b/4", "rand-L16", "rand-L64", "rand-L2"},
