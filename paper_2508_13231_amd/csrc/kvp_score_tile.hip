@@ -183,13 +183,18 @@ int launch_wd_nw(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, ui
     const DevProblem &q = ctx->dp;
     const size_t XW = ((TILE_N + 1) * WD + 3 + 3) / 4 * 4, AW = ((size_t)TILE_N * q.pn * WD + 3 + 3) / 4 * 4;
     const size_t lds = (size_t)q.L * TB_STRIDE * 8 + (TILE_N + 4) * 4 + NW * (XW + AW) * 4;
-    if (lds > 64 * 1024) return 1;
+    if (lds > 160 * 1024) return 1;
     const size_t x_total = (size_t)S * q.L * q.N * WD, a_total = (size_t)q.L * q.N * q.pn * WD;
     const bool k1 = q.pn == 1 && q.pw[0] == 1, w1 = q.single_write != 0;
     dim3 grid(S, tiles), block(NW * 64);
 #define KVP_GO(KK, WW)                                                                                  \
-    score_lane_rows_kernel<WD, NW, KK, WW><<<grid, block, lds, ctx->stream>>>(                          \
-        q, X, x_total, a_total, tiles, nb_total, ctx->d_blocksum, ctx->d_tileflag, counters, occ)
+    do {                                                                                                \
+        if (lds > 48 * 1024)                                                                            \
+            KVP_HIP(hipFuncSetAttribute((const void *)score_lane_rows_kernel<WD, NW, KK, WW>,           \
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));         \
+        score_lane_rows_kernel<WD, NW, KK, WW><<<grid, block, lds, ctx->stream>>>(                      \
+            q, X, x_total, a_total, tiles, nb_total, ctx->d_blocksum, ctx->d_tileflag, counters, occ);  \
+    } while (0)
     if (k1 && w1) KVP_GO(true, true);
     else if (k1) KVP_GO(true, false);
     else if (w1) KVP_GO(false, true);
