@@ -218,8 +218,10 @@ enum { KVP_SCORE_AUTO = 0, KVP_SCORE_ROWS = 1, KVP_SCORE_LANES = 2, KVP_SCORE_LA
        KVP_SCORE_CHUNK = 9, /* lane per row, wide rows walked in chunks of 16 words (choice for > 16 words) */
        KVP_SCORE_ROWBLOCK = 10, /* two lanes per row, whole rows of 16..68 words staged at once, read weights as
                                    binary digit planes (choice where it applies) */
-       KVP_SCORE_LINE = 11 /* rows of >= 32 words in 128-byte chunks scored from registers, eight lanes per
-                              chunk (choice for wide rows) */ };
+       KVP_SCORE_LINE = 11, /* rows of >= 32 words in 128-byte chunks scored from registers, eight lanes per
+                               chunk (choice for wide rows of several sequences) */
+       KVP_SCORE_ROWSEG = 12 /* ROWBLOCK's scheme for rows of more than 68 words, walked in equal segments of
+                                40..64 words (choice for wide rows of one sequence) */ };
 int kvp_set_score_kernel(kvp_ctx *ctx, int which);
 
 /* The scorer that the last kvp_score on ctx ran (a KVP_SCORE_* value other than

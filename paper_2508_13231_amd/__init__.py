@@ -222,7 +222,7 @@ def kvp_chain_stats(ctx, n_chains):
 
 
 (KVP_SCORE_AUTO, KVP_SCORE_ROWS, KVP_SCORE_LANES, KVP_SCORE_LANES_8W, KVP_SCORE_DIRECT, KVP_SCORE_DIRECT_8W,
- KVP_SCORE_QUAD, KVP_SCORE_QUAD_4S, KVP_SCORE_WIDE, KVP_SCORE_CHUNK, KVP_SCORE_ROWBLOCK, KVP_SCORE_LINE) = range(12)
+ KVP_SCORE_QUAD, KVP_SCORE_QUAD_4S, KVP_SCORE_WIDE, KVP_SCORE_CHUNK, KVP_SCORE_ROWBLOCK, KVP_SCORE_LINE, KVP_SCORE_ROWSEG) = range(13)
 
 
 def kvp_strict_excess(ctx, d_placements, S, d_excess):

@@ -90,7 +90,7 @@ extern "C" int kvp_set_anneal_lookahead(kvp_ctx *ctx, int proposals_per_round) {
 }
 
 extern "C" int kvp_set_score_kernel(kvp_ctx *ctx, int which) {
-    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_LINE) return KVP_EINVAL;
+    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_ROWSEG) return KVP_EINVAL;
     ctx->score_kernel = which;
     return KVP_OK;
 }

@@ -102,6 +102,22 @@ extern thread_local int kvp_tls_hip_line;
 // ---- device helpers ---------------------------------------------------------
 #if defined(__HIPCC__)
 
+// Placement of workgroups that each take one (tile of token steps, group of schedules): the
+// hardware hands consecutive workgroups to the eight XCDs in turn (blockIdx & 7), each XCD with an
+// L2 of its own.  The pairs, tile-major, are cut into eight equal runs, one per XCD, and the
+// workgroups of an XCD walk its run in order: the XCD works on one tile at a time (that tile's trace
+// is fetched from HBM once and then served by its L2), and every XCD gets the same amount of work
+// whatever the number of tiles.  Returns false for the few workgroups past the end of a run.
+__device__ __forceinline__ bool xcd_pair(uint32_t tiles, uint32_t groups, uint32_t &tile, uint32_t &group) {
+    const uint32_t pairs = tiles * groups, per = (pairs + 7) / 8;
+    const uint32_t pair = (blockIdx.x & 7u) * per + (blockIdx.x >> 3);
+    tile = pair / groups;
+    group = pair - tile * groups;
+    return (blockIdx.x >> 3) < per && pair < pairs;
+}
+// workgroups to launch for xcd_pair
+static inline uint64_t xcd_grid(uint32_t tiles, uint32_t groups) { return ((uint64_t)tiles * groups + 7) / 8 * 8; }
+
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (KVP_WAVE - 1)); }
 
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {

@@ -55,13 +55,9 @@ __global__ __launch_bounds__(CQ * 64) void score_chunk_kernel(
     const uint32_t tid = threadIdx.x;
     const int lane = lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / KVP_WAVE));
-    // Workgroups are handed to the eight XCDs in turn.  The ones that land on an XCD take the
-    // schedule groups of one tile after the other, so that the trace of that tile is fetched from
-    // HBM once and then served by the XCD's L2 to all of them.
-    const uint32_t groups = (S + CQ - 1) / CQ;
-    const uint32_t tile = ((blockIdx.x >> 3) / groups) * 8 + (blockIdx.x & 7u);
-    if (tile >= tiles) return;
-    const uint32_t s = ((blockIdx.x >> 3) % groups) * CQ + wave;
+    uint32_t tile, group;                                             // see xcd_pair for the placement
+    if (!xcd_pair(tiles, (S + CQ - 1) / CQ, tile, group)) return;
+    const uint32_t s = group * CQ + wave;
     const bool has_s = s < S;
     const uint32_t sc = has_s ? s : S - 1;
     const uint32_t n0 = tile * TILE_N;
@@ -299,7 +295,7 @@ int kvp_score_chunk_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t
     const size_t nt = q.K + 2 + (w1 ? 0 : 1);
     const size_t lds = ((size_t)CQ * XSLICE + 2 * nt * TPLANE) * 4;
     if (lds > 160 * 1024) return 1;
-    const uint64_t nwg = (uint64_t)((S + CQ - 1) / CQ) * ((tiles + 7) / 8) * 8;   // whole rounds over the XCDs
+    const uint64_t nwg = xcd_grid(tiles, (S + CQ - 1) / CQ);
     if (nwg > 0x7FFFFFFFull) return 1;
     int rc = kvp_ensure(ctx, (void **)&ctx->d_tglobal, &ctx->tglobal_cap, (size_t)S * q.L * q.N * sizeof(double));
     if (rc) return rc;

@@ -56,12 +56,9 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     const uint32_t tid = threadIdx.x;
     const int lane = lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / KVP_WAVE));
-    // Workgroups are handed to the eight XCDs in turn; those of one XCD take the schedule groups of
-    // one tile after the other, so the tile's trace is served by that XCD's L2.
-    const uint32_t groups = (S + LQ - 1) / LQ;
-    const uint32_t tile = ((blockIdx.x >> 3) / groups) * 8 + (blockIdx.x & 7u);
-    if (tile >= tiles) return;
-    const uint32_t s = ((blockIdx.x >> 3) % groups) * LQ + wave;
+    uint32_t tile, group;                                             // see xcd_pair for the placement
+    if (!xcd_pair(tiles, (S + LQ - 1) / LQ, tile, group)) return;
+    const uint32_t s = group * LQ + wave;
     const bool has_s = s < S;
     const uint32_t sc = has_s ? s : S - 1;                             // spare wavefronts shadow the last schedule
     const uint32_t n0 = tile * 64;
@@ -281,7 +278,7 @@ int kvp_score_line_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t 
     const bool pow2 = q.L >= 2 && q.L <= 64 && (1u << log2L) == q.L;
     const size_t lds = 2 * (size_t)(KB + 3) * PLANE * 4 + (pow2 ? (size_t)6 * LQ * 64 * 8 : 0);
     if (lds > 160 * 1024) return 1;
-    const uint64_t nwg = (uint64_t)((S + LQ - 1) / LQ) * ((tiles + 7) / 8) * 8;   // whole rounds over the XCDs
+    const uint64_t nwg = xcd_grid(tiles, (S + LQ - 1) / LQ);
     if (nwg > 0x7FFFFFFFull) return 1;
     if (!pow2) {
         int rc = kvp_ensure(ctx, (void **)&ctx->d_tglobal, &ctx->tglobal_cap, (size_t)S * q.L * q.N * sizeof(double));

@@ -103,12 +103,9 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
     const uint32_t tid = threadIdx.x;
     const int lane = lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / KVP_WAVE));
-    // Workgroups are handed to the eight XCDs in turn; those of one XCD take the schedule groups of
-    // one tile after the other, so the tile's digit planes are served by that XCD's L2.
-    const uint32_t groups = (S + RQ - 1) / RQ;
-    const uint32_t tile = ((blockIdx.x >> 3) / groups) * 8 + (blockIdx.x & 7u);
-    if (tile >= tiles) return;
-    const uint32_t s = ((blockIdx.x >> 3) % groups) * RQ + wave;
+    uint32_t tile, group;                                             // see xcd_pair for the placement
+    if (!xcd_pair(tiles, (S + RQ - 1) / RQ, tile, group)) return;
+    const uint32_t s = group * RQ + wave;
     const bool has_s = s < S;
     const uint32_t sc = has_s ? s : S - 1;                            // spare wavefronts shadow the last schedule
     const uint32_t n0 = tile * 64;
@@ -411,7 +408,7 @@ int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint3
     size_t lds = ((size_t)RQ * (RR + 1) * RS + 2 * (size_t)KB * RR * RS) * 4;
     if (mixed) lds += (size_t)RQ * (64 * qodd + k2 * q.L) * sizeof(double);
     if (lds > 160 * 1024) return 1;
-    const uint64_t nwg = (uint64_t)((S + RQ - 1) / RQ) * ((tiles + 7) / 8) * 8;   // whole rounds over the XCDs
+    const uint64_t nwg = xcd_grid(tiles, (S + RQ - 1) / RQ);
     if (nwg > 0x7FFFFFFFull) return 1;
     const int mode = pow2 ? POW2 : mixed ? MIXED : SPILL;
     if (mode == MIXED) log2L = k2;

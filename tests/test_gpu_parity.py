@@ -60,6 +60,12 @@ def _cases():
     yield "tok-p16", W.regroup(_tokens(42, L=8, N=64, prompt=1024), 16, "token")             # 3 words, 5 planes
     yield "tok-p4-w20", W.regroup(_tokens(43, L=4, N=70, prompt=19 * 32 * 4), 4, "token")    # 20 words, 3 planes
     yield "tok-p16-w17", W.regroup(_tokens(44, L=2, N=66, prompt=16 * 32 * 16), 16, "token") # 17 words, 5 planes
+    # one sequence with rows wider than 68 words: walked in segments of 64
+    yield "dec-w70", _decode(45, L=4, N=70, words=69, page_tokens=1)               # 71 words: the last segment overlaps by 57
+    yield "dec-w128", _decode(46, L=8, N=130, words=126, page_tokens=2)            # 129 words, odd: three segments, tail apart
+    yield "dec-w130-k3", _decode(47, L=3, N=66, words=128, page_tokens=4, K=3)     # masked words start before the last segment; two digit planes
+    yield "dec-w200", _decode(48, L=2, N=40, words=199, page_tokens=8)             # one short tile, four segments
+    yield "dec-w80-tail6", _decode(49, L=2, N=170, words=80, page_tokens=1)        # six masked words, ragged third tile
     # layer counts 2^k q whose summation tree stays on chip: block boundaries fall inside a token step
     yield "dec-L80-k8", _decode(37, L=80, N=130, words=32, page_tokens=2, K=8)     # 80 = 16 * 5, three tiles, the last of 2 steps
     yield "dec-L24", _decode(38, L=24, N=70, words=19, page_tokens=4)              # 8 * 3
@@ -98,13 +104,15 @@ NATIVE = {
     "direct": {"tiny", "table1", "llama8b/4", "rand-odd"},
     "wide": {"rand-wide", "rand-w40", "rand-w300", "rand-w301"},
     "quad": {"llama8b/4", "rand-L16", "rand-L64", "rand-L2"},
+    "rowseg": {"dec-w70", "dec-w128", "dec-w130-k3", "dec-w200", "dec-w80-tail6"},
 }
 
 
-KERNEL_IDS = ["rows", "lanes", "lanes8w", "direct", "direct8w", "quad", "quad4s", "wide", "chunk", "rowblock", "line"]
+KERNEL_IDS = ["rows", "lanes", "lanes8w", "direct", "direct8w", "quad", "quad4s", "wide", "chunk", "rowblock", "line",
+              "rowseg"]
 
 
-@pytest.mark.parametrize("kernel", list(range(1, 12)), ids=KERNEL_IDS)
+@pytest.mark.parametrize("kernel", list(range(1, 13)), ids=KERNEL_IDS)
 @pytest.mark.parametrize("name,tr", CASES, ids=[c[0] for c in CASES])
 def test_score_matches_oracle_bit_for_bit(G, name, tr, kernel):
     from gpu_util import expected_counters
