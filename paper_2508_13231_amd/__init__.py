@@ -23,6 +23,8 @@ KVP_OK, KVP_EINVAL, KVP_ENOTRACE, KVP_ENOMEM, KVP_EHIP = 0, -1, -2, -3, -4
 KVP_ESHAPE, KVP_ETRACE, KVP_ENOCHAINS, KVP_EINFEASIBLE = -5, -6, -7, -8
 KVP_MAX_LEN = 63
 KVP_INIT_EMPTY, KVP_INIT_GIVEN, KVP_INIT_BROADCAST, KVP_INIT_CONTINUE = 0, 1, 2, 3
+KVP_OP_SET, KVP_OP_SWAP, KVP_OP_SHIFT = 0, 1, 2              # kvp_move.op
+KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2       # verdicts of kvp_delta_score
 KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2
 
 EXPORTS = ["kvp_create", "kvp_destroy", "kvp_trace_upload", "kvp_score", "kvp_delta_score", "kvp_anneal",

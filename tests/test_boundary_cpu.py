@@ -32,3 +32,15 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(K.kvp_chain_stats_t) == 80
     assert K.kvp_problem.plane_bytes.offset == 24 and K.kvp_problem.bw_hbm.offset == 104
     assert K.kvp_anneal_params.p0.offset == 40
+
+
+def test_enumerators_match_the_header():
+    """Every `NAME = value` of the header's enums has the same value in the binding."""
+    src = open(os.path.join(ROOT, "include", "kvp.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    seen = 0
+    for body in re.findall(r"enum\s*\w*\s*\{(.*?)\}", src, flags=re.S):
+        for name, value in re.findall(r"\b(KVP_[A-Z0-9_]+)\s*=\s*(-?\d+)", body):
+            assert getattr(K, name) == int(value), name
+            seen += 1
+    assert seen >= 25 and K.KVP_SCORE_ROWSEG == 12
