@@ -101,6 +101,8 @@ def lib():
         L.orc_anneal_chain.argtypes = [C.POINTER(_Problem), C.POINTER(_SAParams), C.c_uint32, C.c_void_p,
                                        C.c_void_p, C.POINTER(_SAState)]
         L.orc_wr_policy.argtypes = [C.POINTER(_Problem), C.c_uint32, C.c_uint32, C.c_void_p]
+        L.orc_exchange.restype = C.c_uint32
+        L.orc_exchange.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.orc_wr_search.restype = C.c_uint64
         L.orc_wr_search.argtypes = [C.POINTER(_Problem), C.POINTER(_WRParams), C.c_void_p, C.POINTER(WRResult)]
         _lib = L
@@ -333,6 +335,35 @@ def anneal_chain(tr, chain, X0, *, seed, total_moves, move_begin=0, move_end=Non
         raise ValueError(f"orc_anneal_chain failed ({rc}): bad parameters or infeasible start")
     return ChainResult(int(chain), X, best, cost(q, best), st.T_cur, st.T_best, st.C0, st.accepted,
                        st.uphill, st.null_moves, st.clipped, st.improved, st)
+
+
+def temper(results, factors) -> None:
+    """Spread the chains over a ladder of temperatures: chain i's current and initial
+    temperature are multiplied by factors[i].  For results of a first `anneal_chain`
+    slice with at least one move: a slice that begins at move 0 calibrates anew."""
+    for r, f in zip(results, factors):
+        r.state.C = r.state.C * float(f)
+        r.state.C0 = r.state.C0 * float(f)
+        r.C0 = r.state.C0
+
+
+def exchange_step(seed: int, rnd: int, T, C, C0):
+    """One replica-exchange round on plain arrays (see orc_exchange): returns (C, C0, pairs traded)."""
+    T = np.ascontiguousarray(T, dtype=np.float64)
+    C1 = np.array(C, dtype=np.float64, copy=True)
+    C01 = np.array(C0, dtype=np.float64, copy=True)
+    n = lib().orc_exchange(int(seed), int(rnd), len(T), T.ctypes.data, C1.ctypes.data, C01.ctypes.data)
+    return C1, C01, int(n)
+
+
+def exchange(results, seed: int, rnd: int) -> int:
+    """Replica exchange between neighbouring chains of `results` (in list order), in place: the
+    chains carry on from the traded temperatures at their next `anneal_chain(resume=...)`."""
+    C1, C01, n = exchange_step(seed, rnd, [r.state.T_cur for r in results], [r.state.C for r in results],
+                               [r.state.C0 for r in results])
+    for r, c, c0 in zip(results, C1, C01):
+        r.state.C, r.state.C0, r.C0 = float(c), float(c0), float(c0)
+    return n
 
 
 def anneal(tr, chains, X0, threads: int = 1, **kw):

@@ -12,7 +12,10 @@
  * Sec. III-B step by step; its move set on the placement schedule itself is
  * this project's own design (the paper anneals two policy scalars), so its
  * effectiveness is "parity unpinned" by the paper: it is pinned only by
- * exhaustive search on tiny instances and by its invariants.
+ * exhaustive search on tiny instances and by its invariants.  The exchange of
+ * temperatures between chains (orc_exchange, parallel tempering) is an
+ * extension of the same standing: pinned by hand-worked pairs, by the
+ * acceptance frequency 1/e of a pair with exponent -1 and by its invariants.
  * Part (iii), at the end, is the paper's own search: a look-ahead policy with the
  * two scalars W and R, and the annealing over them.  The paper states the
  * policy in two sentences; the reading taken is written out step by step above
@@ -613,6 +616,38 @@ int orc_anneal_chain(const orc_problem *q, const orc_sa_params *sp, uint32_t cha
     }
     free(tcur); free(occ); free(f1); free(f2);
     return 0;
+}
+
+/* ---- replica exchange between the chains (parallel tempering) ---------------
+ * Not in the paper (its search is one annealing run): the standard exchange
+ * step of parallel tempering (Swendsen & Wang 1986; Geyer 1991), offered
+ * between two slices of the annealing.  Chains that stand next to each other in
+ * the chain order, (a, a+1) with a = round mod 2, round mod 2 + 2, ..., trade
+ * their temperatures (the current one C and the initial one C0; each chain goes
+ * on cooling from what it holds) with the Metropolis probability of the pair,
+ *     min(1, exp((1/C_a - 1/C_b) (T_a - T_b))),   T = the chain's current cost,
+ * so the better schedule tends to end up at the lower temperature.  One uniform
+ * number per pair and round: Philox counter (round, a, 16), the mapping to (0,1)
+ * that the acceptance test of a move uses.  A pair with a temperature that is
+ * not positive is left alone.  Returns the number of pairs that traded. */
+uint32_t orc_exchange(uint64_t seed, uint64_t round, uint32_t n, const double *T, double *C, double *C0) {
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t traded = 0;
+    for (uint32_t a = (uint32_t)(round & 1u); a + 1 < n; a += 2) {
+        uint32_t b = a + 1;
+        if (!(C[a] > 0.0) || !(C[b] > 0.0)) continue;
+        uint32_t ctr[4] = {(uint32_t)round, (uint32_t)(round >> 32), a, 16u}, r[4];
+        orc_philox4x32_10(ctr, key, r);
+        uint64_t bits = ((uint64_t)r[0] << 20) | (r[1] >> 12);
+        double u = ((double)bits + 0.5) * (1.0 / 4503599627370496.0);
+        double d = (1.0 / C[a] - 1.0 / C[b]) * (T[a] - T[b]);
+        if (d >= 0.0 || u < exp(d)) {
+            double t = C[a]; C[a] = C[b]; C[b] = t;
+            t = C0[a]; C0[a] = C0[b]; C0[b] = t;
+            traded++;
+        }
+    }
+    return traded;
 }
 
 /* ---- the (W, R) look-ahead policy and its search (Sec. III-B) ---------------

@@ -616,3 +616,80 @@ def test_wr_search_walks_the_grid_as_stated():
     best = O.wr_policy(tr, res.best_w, res.best_r10)
     out, _ = O.anneal(tr, chains=[0], X0=best, total_moves=3000, seed=1)
     assert out[0].T_best <= res.best_T
+
+
+# ---- replica exchange between chains (parallel tempering; an extension, not in the paper) ---------
+
+def test_exchange_by_hand():
+    # the colder chain holds the worse schedule: (1/1 - 1/2)(10 - 8) = 1 > 0, they always trade
+    C, C0, n = O.exchange_step(3, 0, [10.0, 8.0], [1.0, 2.0], [1.5, 2.5])
+    assert (list(C), list(C0), n) == ([2.0, 1.0], [2.5, 1.5], 1)
+    # odd rounds pair (1, 2), (3, 4), ...: chain 0 and, with four chains, chain 3 sit out
+    C, C0, n = O.exchange_step(3, 1, [0.0, 9.0, 1.0, 0.0], [7.0, 1.0, 4.0, 9.0], [7.0, 1.0, 4.0, 9.0])
+    assert (list(C), n) == ([7.0, 4.0, 1.0, 9.0], 1)
+    # equal costs or equal temperatures: exponent 0, the trade is accepted (and changes nothing that matters)
+    assert O.exchange_step(3, 0, [5.0, 5.0], [1.0, 2.0], [1.0, 2.0])[2] == 1
+    assert list(O.exchange_step(3, 0, [5.0, 6.0], [2.0, 2.0], [1.0, 3.0])[1]) == [3.0, 1.0]
+    # a temperature that is not positive: the pair is left alone
+    C, C0, n = O.exchange_step(3, 0, [10.0, 8.0], [0.0, 2.0], [0.0, 2.0])
+    assert (list(C), n) == ([0.0, 2.0], 0)
+    # a single chain, and the last chain of an odd count in an even round
+    assert O.exchange_step(3, 0, [1.0], [1.0], [1.0])[2] == 0
+    assert list(O.exchange_step(3, 0, [9.0, 1.0, 5.0], [1.0, 2.0, 3.0], [1.0, 2.0, 3.0])[0]) == [2.0, 1.0, 3.0]
+
+
+def test_exchange_accepts_with_the_metropolis_probability():
+    # the colder chain holds the better schedule: exponent (1/1 - 1/2)(8 - 10) = -1, traded with probability 1/e
+    rounds = 20000
+    k = sum(O.exchange_step(11, 2 * r, [8.0, 10.0], [1.0, 2.0], [1.0, 2.0])[2] for r in range(rounds))
+    p = math.exp(-1.0)
+    assert abs(k / rounds - p) < 4.0 * math.sqrt(p * (1 - p) / rounds)
+    # the same by the position of the pair instead of the round
+    n = 4000
+    T = np.tile([8.0, 10.0], n)
+    C = np.tile([1.0, 2.0], n)
+    k = O.exchange_step(12, 0, T, C, C)[2]
+    assert abs(k / n - p) < 4.0 * math.sqrt(p * (1 - p) / n)
+
+
+def test_exchange_draw_is_the_stated_philox_block():
+    seed, rnd, a = 0x1234_5678_9ABC_DEF0, (5 << 32) | 6, 2
+    r = O.philox4x32_10([rnd & 0xFFFFFFFF, rnd >> 32, a, 16], [seed & 0xFFFFFFFF, seed >> 32])
+    u = ((int(r[0]) << 20 | int(r[1]) >> 12) + 0.5) * 2.0 ** -52
+    # chains 2 and 3 with temperatures 1 and 2 and cost gap g: exponent -g / 2; trade iff u < exp(-g / 2)
+    g = -2.0 * math.log(u)
+    for gap, want in ((g * (1 - 1e-9), 1), (g * (1 + 1e-9), 0)):
+        T = [0.0, 0.0, 1.0, 1.0 + gap]
+        assert O.exchange_step(seed, rnd, T, [1.0, 1.0, 1.0, 2.0], [1.0, 1.0, 1.0, 2.0])[2] == 1 + want
+        # (the pair (0, 1) has equal costs and always trades)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_exchange_keeps_the_ladder_and_feeds_the_next_slice(seed):
+    tr = W.config("tiny")
+    kw = dict(seed=seed, total_moves=4000, n_levels=10)
+    X0 = O.init_static_frequency(O.Problem(tr))
+    res = [O.anneal_chain(tr, c, X0, move_end=1000, **kw) for c in range(5)]       # calibrates, then the first moves
+    O.temper(res, [1.0, 2.0, 4.0, 8.0, 16.0])
+    ladder = sorted(r.state.C for r in res)
+    level0 = res[0].state.level
+    assert all(r.state.C0 == r.C0 for r in res)
+    traded = 0
+    for rnd in range(1, 4):
+        before = sorted((r.state.C, r.state.C0) for r in res)
+        traded += O.exchange(res, seed, rnd)
+        assert sorted((r.state.C, r.state.C0) for r in res) == before             # temperatures move, none is lost
+        res = [O.anneal_chain(tr, r.chain, None, move_begin=1000 * rnd, move_end=1000 * (rnd + 1), resume=r, **kw)
+               for r in res]
+    assert traded > 0
+    # every chain cooled by the same factor: what they hold is still the ladder times alpha^level
+    level = res[0].state.level
+    assert all(r.state.level == level for r in res)
+    want = []
+    for c in ladder:
+        for _ in range(level - level0):
+            c = c * 0.9
+        want.append(c)
+    assert sorted(r.state.C for r in res) == want
+    for r in res:
+        assert O.score(O.Problem(tr), r.X).excess == 0 and r.T_best <= O.cost(O.Problem(tr), X0)
