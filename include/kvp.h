@@ -175,6 +175,30 @@ int kvp_delta_score(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, cons
  * KVP_ENOTRACE, KVP_ESHAPE (more than 2048 layers), KVP_EHIP. */
 int kvp_strict_excess(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, uint32_t *d_excess);
 
+/* Parallel tempering across the chains of kvp_anneal: an extension, not in the paper, whose search
+ * (Sec. III-B) is one annealing run; the exchange step is the standard one (Swendsen & Wang 1986,
+ * Geyer 1991).  Used between slices of kvp_anneal (KVP_INIT_CONTINUE):
+ *
+ * kvp_temper multiplies the temperature of chain c (the current one and the initial one that
+ * kvp_chain_stats reports) by h_factor[c], e.g. a geometric ladder; every chain goes on cooling by
+ * alpha per level from what it holds.
+ *   h_factor   host, [n_chains] doubles, finite and > 0; free again on return
+ * Errors: KVP_EINVAL (null pointer, a factor that is not positive and finite, or no move made yet:
+ * the slice that begins at move 0 sets the initial temperatures), KVP_ENOCHAINS, KVP_ENOMEM, KVP_EHIP.
+ *
+ * kvp_exchange lets neighbouring chains trade their temperatures: in round r the pairs (a, a+1),
+ * a = r mod 2, r mod 2 + 2, ..., trade with probability min(1, exp((1/C_a - 1/C_b)(T_a - T_b))),
+ * T the chain's current cost and C its temperature, so the better schedule tends to the lower
+ * temperature.  One uniform number per pair: Philox4x32-10 with the seed of kvp_anneal as key and
+ * counter (round lo, round hi, a, 16), mapped to (0,1) like the acceptance draw of a move.  Pairs
+ * with a temperature that is not positive are left alone.
+ *   round      any number; its parity picks the pairs, callers count it up
+ *   h_traded   host, may be null: receives the number of pairs that traded (the call then waits
+ *              for the stream; otherwise it only enqueues)
+ * Errors: KVP_EINVAL (null ctx), KVP_ENOCHAINS, KVP_EHIP. */
+int kvp_temper(kvp_ctx *ctx, const double *h_factor);
+int kvp_exchange(kvp_ctx *ctx, uint64_t round, uint32_t *h_traded);
+
 /* Tuning knob of kvp_anneal: how many consecutive proposals of a chain are priced at once, each
  * by a wavefront of its own (the walk takes them in order up to the first accepted one, so it is
  * the same walk whatever the number).  0 (default): chosen from the number of chains and the

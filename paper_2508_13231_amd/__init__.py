@@ -30,7 +30,7 @@ KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2
 EXPORTS = ["kvp_create", "kvp_destroy", "kvp_trace_upload", "kvp_score", "kvp_delta_score", "kvp_anneal",
            "kvp_best", "kvp_chain_placement", "kvp_chain_stats", "kvp_plane_unit", "kvp_strerror", "kvp_last_hip_error",
            "kvp_set_score_kernel", "kvp_set_anneal_lookahead", "kvp_score_kernel_used", "kvp_baseline", "kvp_wr_policy",
-           "kvp_wr_search", "kvp_strict_excess"]
+           "kvp_wr_search", "kvp_strict_excess", "kvp_temper", "kvp_exchange"]
 
 
 class kvp_wr_params(C.Structure):
@@ -115,6 +115,10 @@ def lib():
         L.kvp_strerror.argtypes = [i32]
         L.kvp_strict_excess.restype = i32
         L.kvp_strict_excess.argtypes = [vp, vp, C.c_uint32, vp]
+        L.kvp_temper.restype = i32
+        L.kvp_temper.argtypes = [vp, vp]
+        L.kvp_exchange.restype = i32
+        L.kvp_exchange.argtypes = [vp, C.c_uint64, vp]
         L.kvp_set_anneal_lookahead.restype = i32
         L.kvp_set_anneal_lookahead.argtypes = [vp, i32]
         L.kvp_set_score_kernel.restype = i32
@@ -229,6 +233,21 @@ def kvp_chain_stats(ctx, n_chains):
 
 def kvp_strict_excess(ctx, d_placements, S, d_excess):
     _check(lib().kvp_strict_excess(ctx, _dptr(d_placements), int(S), _dptr(d_excess)), "kvp_strict_excess")
+
+
+def kvp_temper(ctx, factors):
+    """Multiply chain c's temperature by factors[c] (host array of n_chains doubles)."""
+    import numpy as np
+    f = np.ascontiguousarray(factors, dtype=np.float64)
+    _check(lib().kvp_temper(ctx, f.ctypes.data), "kvp_temper")
+
+
+def kvp_exchange(ctx, round: int, count: bool = True) -> int:
+    """One replica-exchange round between neighbouring chains; returns the pairs that traded
+    (-1 with count=False: the call then does not wait for the stream)."""
+    n = C.c_uint32(0)
+    _check(lib().kvp_exchange(ctx, int(round), C.byref(n) if count else None), "kvp_exchange")
+    return int(n.value) if count else -1
 
 
 def kvp_set_anneal_lookahead(ctx, proposals_per_round: int):

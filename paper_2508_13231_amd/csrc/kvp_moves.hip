@@ -931,6 +931,81 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
     return KVP_OK;
 }
 
+// ---- parallel tempering: the chains' temperatures spread over a ladder and traded between slices ----
+
+namespace {
+
+__global__ __launch_bounds__(256) void temper_kernel(ChainState *__restrict__ st, const double *__restrict__ factor,
+                                                     uint32_t C) {
+    const uint32_t c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    st[c].c0 = st[c].c0 * factor[c];
+    st[c].c = st[c].c * factor[c];
+}
+
+// One workgroup walks the pairs (a, a + 1), a = round mod 2, + 2, ...: the pairs of a round are
+// disjoint, so every thread owns both chains of its pairs.  out[0] = pairs that traded.
+__global__ __launch_bounds__(256) void exchange_kernel(ChainState *__restrict__ st, uint32_t C, uint32_t seed_lo,
+                                                       uint32_t seed_hi, uint64_t round, uint32_t *__restrict__ out) {
+    __shared__ uint32_t traded;
+    if (threadIdx.x == 0) traded = 0;
+    __syncthreads();
+    uint32_t mine = 0;
+    for (uint64_t a64 = (round & 1u) + 2ull * threadIdx.x; a64 + 1 < C; a64 += 512) {
+        const uint32_t a = (uint32_t)a64, b = a + 1;
+        const double ca = st[a].c, cb = st[b].c;
+        if (!(ca > 0.0) || !(cb > 0.0)) continue;
+        uint32_t r[4];
+        philox4x32_10((uint32_t)round, (uint32_t)(round >> 32), a, 16u, seed_lo, seed_hi, r);
+        const uint64_t bits = ((uint64_t)r[0] << 20) | (uint64_t)(r[1] >> 12);
+        const double u = ((double)bits + 0.5) * (1.0 / 4503599627370496.0);
+        const double d = (1.0 / ca - 1.0 / cb) * (st[a].t_cur - st[b].t_cur);
+        if (d >= 0.0 || u < exp(d)) {
+            const double c0a = st[a].c0, c0b = st[b].c0;
+            st[a].c = cb; st[b].c = ca;
+            st[a].c0 = c0b; st[b].c0 = c0a;
+            mine++;
+        }
+    }
+    if (mine) atomicAdd(&traded, mine);
+    __syncthreads();
+    if (threadIdx.x == 0) out[0] = traded;
+}
+
+}  // namespace
+
+extern "C" int kvp_temper(kvp_ctx *ctx, const double *h_factor) {
+    if (!ctx || !h_factor) return KVP_EINVAL;
+    if (!ctx->has_chains) return KVP_ENOCHAINS;
+    if (ctx->moves_done == 0) return KVP_EINVAL;                       // the next slice would calibrate anew
+    const uint32_t C = ctx->sa.n_chains;
+    for (uint32_t c = 0; c < C; c++)
+        if (!(h_factor[c] > 0.0) || !(h_factor[c] <= 1.7976931348623157e308)) return KVP_EINVAL;
+    KVP_HIP(hipSetDevice(ctx->device));
+    int rc = kvp_ensure(ctx, (void **)&ctx->d_cnt_tmp, &ctx->cnt_tmp_cap, sizeof(double) * (size_t)C);
+    if (rc) return rc;
+    double *d_factor = (double *)ctx->d_cnt_tmp;
+    KVP_HIP(hipMemcpyAsync(d_factor, h_factor, sizeof(double) * (size_t)C, hipMemcpyHostToDevice, ctx->stream));
+    temper_kernel<<<dim3((C + 255) / 256), dim3(256), 0, ctx->stream>>>(ctx->d_state, d_factor, C);
+    KVP_HIP(hipGetLastError());
+    KVP_HIP(hipStreamSynchronize(ctx->stream));                        // h_factor may be pageable: it is free again
+    return KVP_OK;
+}
+
+extern "C" int kvp_exchange(kvp_ctx *ctx, uint64_t round, uint32_t *h_traded) {
+    if (!ctx) return KVP_EINVAL;
+    if (!ctx->has_chains) return KVP_ENOCHAINS;
+    KVP_HIP(hipSetDevice(ctx->device));
+    exchange_kernel<<<dim3(1), dim3(256), 0, ctx->stream>>>(ctx->d_state, ctx->sa.n_chains, (uint32_t)ctx->sa.seed,
+                                                            (uint32_t)(ctx->sa.seed >> 32), round, ctx->d_argmin + 2);
+    KVP_HIP(hipGetLastError());
+    if (h_traded) {
+        KVP_HIP(hipMemcpyAsync(h_traded, ctx->d_argmin + 2, 4, hipMemcpyDeviceToHost, ctx->stream));
+        KVP_HIP(hipStreamSynchronize(ctx->stream));
+    }
+    return KVP_OK;
+}
+
 extern "C" int kvp_best(kvp_ctx *ctx, double *h_cost, uint32_t *h_chain, uint32_t *h_placement,
                         double *h_chain_costs) {
     if (!ctx || !h_cost || !h_chain) return KVP_EINVAL;

@@ -254,6 +254,57 @@ def test_full_size_anneal_sampled_chains_against_oracle(G, name, total, ids, loo
         assert (curs[c] == res[i].X).all() and cc[c] == res[i].best_cost, (name, c)     # the same walk, move for move
 
 
+@pytest.mark.parametrize("lookahead", [1, 4], ids=["serial", "four-per-round"])
+@pytest.mark.parametrize("name,scale,chains,total", [("tiny", 1.0, 7, 6000), ("llama8b", 0.125, 4, 4000)])
+def test_tempering_against_oracle(G, name, scale, chains, total, lookahead):
+    """Slices of the annealing with a temperature ladder and an exchange round between them: the
+    chains hold the oracle's temperatures and costs after every round and end on its schedules."""
+    import paper_2508_13231_amd as K
+    tr = W.config(name, scale)
+    q = O.Problem(tr)
+    X0 = O.init_static_frequency(q)
+    slices, per = 8, total // 8
+    factors = [1.05 ** c for c in range(chains)]       # a dense ladder: the chains' costs are many temperatures apart
+    kw = dict(seed=tr.seed, total_moves=total)
+    res = [O.anneal_chain(q, c, X0, move_end=per, **kw) for c in range(chains)]
+    O.temper(res, factors)
+    want_traded, want_state = [], []
+    for rnd in range(1, slices):
+        want_traded.append(O.exchange(res, tr.seed, rnd))
+        want_state.append([(r.state.C, r.state.C0, r.state.T_cur) for r in res])
+        res = [O.anneal_chain(q, r.chain, None, move_begin=per * rnd, move_end=per * (rnd + 1), resume=r, **kw) for r in res]
+    assert sum(want_traded) > 0 and any(t < (chains - (rnd & 1)) // 2 for rnd, t in enumerate(want_traded, 1))
+    with G(tr) as g:
+        K.kvp_set_anneal_lookahead(g.ctx, lookahead)
+        with pytest.raises(K.KvpError) as e:
+            K.kvp_exchange(g.ctx, 0)
+        assert e.value.code == K.KVP_ENOCHAINS
+        _anneal_gpu(g, tr, chains, total, moves=per, init=X0, seed=tr.seed)
+        K.kvp_temper(g.ctx, factors)
+        for rnd in range(1, slices):
+            traded = K.kvp_exchange(g.ctx, rnd, count=rnd != 2)          # once without waiting for the count
+            st = K.kvp_chain_stats(g.ctx, chains)
+            assert traded == (want_traded[rnd - 1] if rnd != 2 else -1)
+            assert [(x.c, x.c0, x.t_cur) for x in st] == want_state[rnd - 1], rnd
+            _anneal_gpu(g, tr, chains, total, moves=per, seed=tr.seed, mode=K.KVP_INIT_CONTINUE)
+        st = K.kvp_chain_stats(g.ctx, chains)
+        cc = K.kvp_best(g.ctx, g.shape_words, chains)[3]
+        curs = [g.unpack(K.kvp_chain_placement(g.ctx, c, 0, g.shape_words)) for c in range(chains)]
+        for c in range(chains):
+            assert (curs[c] == res[c].X).all() and cc[c] == res[c].best_cost
+            assert (st[c].c, st[c].c0, st[c].t_cur, st[c].accepted) == (res[c].state.C, res[c].state.C0, res[c].state.T_cur,
+                                                                       res[c].state.accepted)
+        # errors: factors that are not positive and finite; tempering before the first move
+        for bad in (0.0, -1.0, float("inf"), float("nan")):
+            with pytest.raises(K.KvpError) as e:
+                K.kvp_temper(g.ctx, [1.0] * (chains - 1) + [bad])
+            assert e.value.code == K.KVP_EINVAL
+        _anneal_gpu(g, tr, chains, total, moves=0, init=X0, seed=tr.seed)
+        with pytest.raises(K.KvpError) as e:
+            K.kvp_temper(g.ctx, factors)
+        assert e.value.code == K.KVP_EINVAL
+
+
 def test_anneal_resume_and_modes(G):
     import paper_2508_13231_amd as K
     tr = W.config("tiny")
