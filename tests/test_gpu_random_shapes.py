@@ -78,6 +78,40 @@ def test_random_shape_everything_but_the_walk(G, seed):
                 assert verdict[s] == ov and dT[s] == od, s
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_wide_single_sequence_every_scorer(G, seed):
+    """One decoding sequence with rows of 66 to 260 words (the shapes of the segment-walking scorer),
+    one to three tiles, up to six masked words at the end of a row and more."""
+    import torch
+    import paper_2508_13231_amd as K
+    from gpu_util import expected_counters
+    rng = np.random.default_rng(3000 + seed)
+    pt = int(rng.choice([1, 2, 4, 8]))
+    words = int(rng.integers(66, 260))
+    tr = generate(Recipe("dec", L=int(rng.choice([2, 3, 4, 6, 8])), N=int(rng.integers(1, 200)), page_tokens=pt,
+                         prompt_lo=words * 32 * pt, prompt_hi=words * 32 * pt, K=int(rng.choice([1, 1, 2, 3])),
+                         top_frac=0.15, sink_tokens=4, recent_tokens=8, cap_frac=float(rng.choice([0.1, 0.3, 0.6])),
+                         seed=int(rng.integers(1 << 30))))
+    q = O.Problem(tr)
+    X = np.concatenate([W.random_placements(tr, 5, seed=seed, density=0.4),
+                        W.random_placements(tr, 2, seed=seed + 1, density=0.9, feasible=False)])
+    want = [O.score(q, x) for x in X]
+    used = set()
+    for kernel in range(13):
+        with G(tr, score_kernel=kernel) as g:
+            cost, ex, cnt, occ = g.score(X)
+            used.add(K.kvp_score_kernel_used(g.ctx))
+            for s, r in enumerate(want):
+                assert cost[s] == r.cost and ex[s] == r.excess, (kernel, s)
+                assert (occ[s] == r.occ).all() and (cnt[s].astype(np.uint64) == expected_counters(r, tr, g.unit)).all()
+            if kernel == 0:
+                d = torch.full((len(X),), -1, dtype=torch.int32, device=g.dev)
+                K.kvp_strict_excess(g.ctx, g.words(X), len(X), d)
+                torch.cuda.synchronize()
+                assert d.cpu().numpy().view(np.uint32).tolist() == [O.strict_excess(q, x) for x in X]
+    assert K.KVP_SCORE_LINE in used and K.KVP_SCORE_ROWS in used
+
+
 @pytest.mark.parametrize("seed", range(16))
 def test_random_shape_walks(G, seed):
     """Serial and four-per-round annealing both walk as the oracle does: same schedules, costs and tallies."""
