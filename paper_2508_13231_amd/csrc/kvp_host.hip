@@ -160,7 +160,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     auto up4 = [](size_t x) { return (x + 3) & ~(size_t)3; };          // keep every array 16-byte aligned
     const size_t oV = up4(nA), oPm = oV + up4(nM), oWm = oPm + up4(nM), oAcc = oWm + up4(nM);
     const size_t oWr = oAcc + up4((size_t)(L * N)), oSel = oWr + up4((size_t)N);
-    const size_t T64 = (size_t)((N + 63) / 64), oCls = oSel + up4((size_t)N), total = oCls + up4(4 * T64);
+    const size_t T64 = (size_t)((N + 63) / 64), oCls = oSel + up4((size_t)N), oTile = oCls + up4(4 * T64), total = oTile + up4(2 * T64);
     KVP_HIP(hipMalloc((void **)&ctx->d_trace, total * sizeof(uint32_t)));
     uint32_t *d = ctx->d_trace;
     KVP_HIP(hipMemcpyAsync(d, h_access, nA * 4, hipMemcpyHostToDevice, ctx->stream));
@@ -176,6 +176,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     q.cap = pr->cap_pages > 0x7FFFFFFFull ? 0x7FFFFFFFu : (uint32_t)pr->cap_pages;
     q.A = d; q.V = d + oV; q.Pm = d + oPm; q.Wm = d + oWm; q.acc = d + oAcc; q.wr = d + oWr; q.wsel = d + oSel; q.tilecls = d + oCls;
     q.fullmask16 = d + oCls + T64; q.fullmask64 = d + oCls + 2 * T64; q.fullmask256 = d + oCls + 3 * T64;
+    q.tile_pfw = d + oTile; q.tile_end = d + oTile + T64;
     for (uint64_t k = 0; k < K; k++) q.wt[k] = (uint32_t)(pr->plane_bytes[k] / unit);
     q.unit_b = (double)unit; q.page_b = (double)pr->page_bytes; q.token_b = (double)pr->token_bytes;
     q.inv_bh = 1.0 / pr->bw_hbm; q.inv_bk = 1.0 / pr->bw_link; q.inv_bd = 1.0 / pr->bw_dram;
@@ -183,17 +184,20 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     q.dram_bound = q.inv_bd >= q.inv_bk;
     {   // class of every mask word over each tile of 64 steps, and groups of words that are all FULL
         uint32_t *cls = (uint32_t *)calloc(4 * (T64 ? T64 : 1), 4);
+        uint32_t *tpe = (uint32_t *)calloc(2 * (T64 ? T64 : 1), 4);   // tile_pfw, tile_end
         uint8_t *fullw = (uint8_t *)malloc((size_t)Wd);
         const uint64_t NCH = (Wd + 15) / 16, CFW = (NCH + 31) / 32;
         uint32_t *cfull = (uint32_t *)calloc((size_t)(T64 * CFW ? T64 * CFW : 1), 4);
         const uint64_t NC32 = (Wd + 31) / 32;
         uint8_t *emp = (uint8_t *)calloc((size_t)(T64 * NC32 ? T64 * NC32 : 1), 1);
-        if (!cls || !fullw || !cfull || !emp) { free(cls); free(fullw); free(cfull); free(emp); return KVP_ENOMEM; }
+        if (!cls || !tpe || !fullw || !cfull || !emp) { free(cls); free(tpe); free(fullw); free(cfull); free(emp); return KVP_ENOMEM; }
         uint32_t *m16 = cls + T64, *m64 = cls + 2 * T64, *m256 = cls + 3 * T64;
         ctx->prefix_full = Wd >= 2 && Wd <= 16;
         ctx->pfw = (uint32_t)Wd;
+        ctx->max_tail = 0;
         for (size_t t = 0; t < T64; t++) {
             const uint64_t n0 = t * 64, n1 = n0 + 64 < N ? n0 + 64 : N;
+            uint32_t t_pfw = (uint32_t)Wd, t_end = 0;
             for (uint64_t w = 0; w < Wd; w++) {
                 bool full = true, empty = true;
                 for (uint64_t n = n0 ? n0 - 1 : 0; n < n1; n++) {
@@ -208,7 +212,12 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
                     cls[t] |= (uint32_t)(full ? KVP_WORD_FULL : empty ? KVP_WORD_EMPTY : KVP_WORD_MIXED) << (2 * w);
                 if (w + 1 < Wd && !full) ctx->prefix_full = false;
                 if (!full && w < ctx->pfw) ctx->pfw = (uint32_t)w;
+                if (!full && w < t_pfw) t_pfw = (uint32_t)w;
+                if (!empty) t_end = (uint32_t)w + 1;
             }
+            if (t_end < t_pfw) t_end = t_pfw;                            // (cannot happen: a FULL word is not empty)
+            tpe[t] = t_pfw; tpe[T64 + t] = t_end;
+            if (t_end - (t_pfw & ~1u) > ctx->max_tail) ctx->max_tail = t_end - (t_pfw & ~1u);
             for (uint64_t c = 0; c < NCH; c++) {
                 bool all = true;
                 for (uint64_t w = c * 16; w < (c + 1) * 16 && w < Wd; w++) all = all && fullw[w];
@@ -225,6 +234,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
         }
         for (size_t i = 0; i < T64 * NC32; i++) emp[i] = !emp[i];
         hipError_t ec = hipMemcpyAsync(d + oCls, cls, 4 * T64 * 4, hipMemcpyHostToDevice, ctx->stream);
+        if (ec == hipSuccess) ec = hipMemcpyAsync(d + oTile, tpe, 2 * T64 * 4, hipMemcpyHostToDevice, ctx->stream);
         if (ec == hipSuccess) ec = hipMalloc((void **)&ctx->d_empty32, (size_t)(T64 * NC32 ? T64 * NC32 : 1));
         if (ec == hipSuccess)
             ec = hipMemcpyAsync(ctx->d_empty32, emp, (size_t)(T64 * NC32), hipMemcpyHostToDevice, ctx->stream);
@@ -233,7 +243,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
             ec = hipMemcpyAsync(ctx->d_chunkfull, cfull, (size_t)T64 * CFW * 4, hipMemcpyHostToDevice, ctx->stream);
         if (ec == hipSuccess) ec = hipStreamSynchronize(ctx->stream);
         ctx->cf_words = (uint32_t)CFW;
-        free(cls); free(fullw); free(cfull); free(emp);
+        free(cls); free(tpe); free(fullw); free(cfull); free(emp);
         KVP_HIP(ec);
     }
     int rc = kvp_trace_totals_launch(ctx, d + oAcc, d + oWr, d + oSel);

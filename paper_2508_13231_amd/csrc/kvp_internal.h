@@ -24,6 +24,9 @@ struct DevProblem {
     const uint32_t *tilecls;      // [ceil(N/64)] two bits per word (n_words <= 16): see KVP_WORD_*
     // [ceil(N/64)] bit i: words [i*G, (i+1)*G) are all FULL on the tile, G = 16, 64, 256 words
     const uint32_t *fullmask16, *fullmask64, *fullmask256;
+    // per tile of 64 steps: leading words that are FULL on the tile; one past the last word in which a
+    // page exists at some step of the tile (the words from there on hold no page: only stray bits)
+    const uint32_t *tile_pfw, *tile_end;
     uint32_t wt[KVP_MAX_PLANES];  // plane_bytes[k] / unit
     // weight planes for single-page look-ups: the access planes with their weights, or (fewer) the
     // binary digit planes of the pages' read weights; pw[j] = 0 for j >= pn
@@ -55,6 +58,7 @@ struct kvp_ctx {
     int last_kernel = 0;                 // scorer that the last kvp_score ran (KVP_SCORE_*), 0 before the first
     bool prefix_full = false;            // on every 64-step tile all mask words but the last are FULL
     uint32_t pfw = 0;                    // leading mask words that are FULL on every 64-step tile
+    uint32_t max_tail = 0;               // most words of a tile between its FULL prefix (rounded down to even) and tile_end
     const uint32_t *aw = nullptr;        // [L][N][kb][Wd] binary digits of the pages' read weights (may alias A)
     uint32_t kb = 0;                     // digit planes, 0 if the weights need more than five
     uint32_t *d_aw = nullptr;            // owned storage of aw when it is not A

@@ -1,7 +1,6 @@
-// Scorer for rows of 16 to 68 words whose pages almost all exist from the first
-// step on (a single decoding sequence: the prompt's pages are there at step 0,
-// the few pages born later sit in the last words) and where one page is written
-// per step.
+// Scorer for rows of 16 to 68 words of a single decoding sequence (the prompt's
+// pages are there at step 0, pages born later follow them in the row) where one
+// page is written per step.
 //
 //   * A workgroup is four wavefronts scoring the same 64 token steps of four
 //     schedules.  Per layer the tile is taken in two passes of 32 steps; in a pass
@@ -16,9 +15,11 @@
 //     floor(log2 K) + 1 digit planes, and hr = sum_j 2^j popcount(x & digit_j).
 //     The digit planes of a pass are fetched once per workgroup into a
 //     double-buffered LDS slot, one pass ahead; the rows two passes ahead.
-//   * Words below the first word that is not FULL on some tile need no masks; the
-//     at most four words from there on use alive / persist words that do not depend
-//     on the layer and stay in registers for the whole kernel.
+//   * On a tile of 64 steps the words below the first one that is not FULL there need
+//     no masks; the at most four words from there to the sequence's end use alive /
+//     persist words that do not depend on the layer and stay in registers for the
+//     whole kernel; the words past the end hold no page and are only checked for
+//     stray bits.  The ranges are the tile's own, so the sequence may grow for long.
 //   * Step latencies are summed on the fly when L is a power of two (bit-reversed
 //     layer order, binary counter of partial sums: the 64-wide tree of the
 //     definition) and when L = 2^k q with 3 <= k <= 5 and q in {3, 5, 7} (see
@@ -90,7 +91,7 @@ enum { SPILL = 0, POW2 = 1, MIXED = 2 };
 template <int XV, int KB, int MODE>
 __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
     DevProblem q, const uint32_t *__restrict__ Aw, const uint32_t *__restrict__ X, uint32_t S, uint32_t tiles,
-    uint32_t nb_total, uint32_t log2L, uint32_t qodd, uint32_t pfw2, double *__restrict__ blocksum, double *__restrict__ tglobal,
+    uint32_t nb_total, uint32_t log2L, uint32_t qodd, double *__restrict__ blocksum, double *__restrict__ tglobal,
     uint32_t *__restrict__ tileflag, uint32_t *__restrict__ counters, uint32_t *__restrict__ occ_out) {
     extern __shared__ double smem_d[];
     constexpr int UN = (KB >= 2 && MODE != MIXED) ? 4 : 8;             // unroll of the word loop
@@ -116,7 +117,10 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
     double *stage = (double *)(tbuf + 2 * KB * TPL) + (size_t)wave * (64 * qodd + log2L * L);
     double *level = stage + 64 * qodd;
     const uint32_t r = (uint32_t)lane >> 1, h2 = (uint32_t)lane & 1u;
-    const uint32_t tw = Wd - pfw2;                                     // masked words at the end of a row (<= TWMAX)
+    // The words of a row on this tile: [0, pfw2) FULL at every step (no masks needed), [pfw2, wend) with
+    // masks (at most TWMAX: the host checks), [wend, Wd) without a page at any step (only stray bits).
+    const uint32_t pfw2 = q.tile_pfw[tile] & ~1u, wend = q.tile_end[tile];
+    const uint32_t tw = wend - pfw2;
 
     // the lane's own step
     const uint32_t rho = h2 * RR + r;
@@ -256,6 +260,9 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
             }
         }
         fl_acc |= (own && active) ? flt : 0u;
+        uint32_t fdead = 0;                                            // bits where no page exists: the row's lanes take turns
+        for (uint32_t w = wend + ((wend ^ hv) & 1u); w < Wd; w += 2) fdead |= cur[w];
+        fl_acc |= (RR * p + r < rows) ? fdead : 0u;
         uint32_t c_hr = 0;
 #pragma unroll
         for (int k = 0; k < KB; k++) c_hr += hrk[k] << k;
@@ -388,8 +395,7 @@ int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint3
                               uint32_t *counters, uint32_t *occ) {
     const DevProblem &q = ctx->dp;
     if (!ctx->aw || !q.single_write || q.Wd < 16 || q.Wd > 68) return 1;
-    const uint32_t pfw2 = ctx->pfw & ~1u;
-    if (q.Wd - pfw2 > TWMAX) return 1;
+    if (ctx->max_tail > TWMAX) return 1;
     const uint32_t PPR = (q.Wd + 3) / 4, RS = q.Wd + ((6 - (q.Wd & 3u)) & 3u), KB = ctx->kb;
     const uint32_t need = ((RR + 1) * PPR + 63) / 64;
     const int xv = need <= 5 ? 5 : 9;
@@ -423,7 +429,7 @@ int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint3
             KVP_HIP(hipFuncSetAttribute((const void *)score_rowblock_kernel<XX, KK, PP>,                            \
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                    \
         score_rowblock_kernel<XX, KK, PP><<<grid, block, lds, ctx->stream>>>(                                       \
-            q, ctx->aw, X, S, tiles, nb_total, log2L, qodd, pfw2, ctx->d_blocksum, ctx->d_tglobal, ctx->d_tileflag,      \
+            q, ctx->aw, X, S, tiles, nb_total, log2L, qodd, ctx->d_blocksum, ctx->d_tglobal, ctx->d_tileflag,      \
             counters, occ);                                                                                         \
     } while (0)
 #define KVP_P(XX, KK)                                                                                               \

@@ -1,19 +1,22 @@
 // Scorer for rows of more than 68 words under the conditions of the rowblock scorer (a single
-// decoding sequence: every word but the last few is FULL on every tile, one page written per step).
+// decoding sequence, one page written per step: on every 64-step tile the words of a row are a
+// FULL prefix, a few words that need masks and then words in which no page exists yet).
 //
 // The row is walked in G = ceil(Wd / 64) segments of equal width, the least of 40, 48, 56 and 64
 // words that covers it (the width is a template parameter: every loop over a segment has a fixed
-// trip count); a (layer, pass of 32 token steps, segment) is one unit, handled the
-// way the rowblock scorer handles a pass: a wavefront fetches the 33 row pieces of its schedule as
-// 16-byte vectors (a piece is up to 256 contiguous bytes), parks them in LDS with a row stride of 66
-// words, and two lanes share a row, one on the even words and one on the odd.  The trace words of a unit (binary digit planes of the read
-// weights) are fetched once per workgroup of four schedules into a double-buffered LDS slot, one
-// unit ahead; the row pieces two units ahead.  Counters stay in registers over the segments of a
-// pass; Eqs. 2-4 and the summation tree run once per layer.
+// trip count); a (layer, pass of 32 token steps, segment) is one unit, handled the way the
+// rowblock scorer handles a pass: a wavefront fetches the 33 row pieces of its schedule as 16-byte
+// vectors (a piece is up to 256 contiguous bytes), parks them in LDS with a row stride of 66
+// words, and two lanes share a row, one on the even words and one on the odd.  The trace words of
+// a unit (binary digit planes of the read weights) are fetched once per workgroup of four
+// schedules into a double-buffered LDS slot, one unit ahead; the row pieces two units ahead.
+// Counters stay in registers over the segments of a pass; Eqs. 2-4 and the summation tree run
+// once per layer.
 //
 // The last segment ends at the end of the row: it overlaps its neighbour when the segments do not
-// tile the row exactly and then starts counting behind the overlap.  The masked words at the end of the
-// row and whatever unmasked words lie beyond the last full segment belong to it.
+// tile the row exactly and owns only the words that its neighbour does not reach.  Masked words,
+// the word that receives the step's token and the words past the sequence's end are handled by
+// the segment that owns them.
 #include "kvp_internal.h"
 
 namespace {
@@ -38,7 +41,7 @@ __device__ __forceinline__ uint32_t seg_pair_sum(uint32_t v) {        // v + the
 template <int KB, bool POW2, int SPP>
 __global__ __launch_bounds__(SQ * 64) void score_rowseg_kernel(
     DevProblem q, const uint32_t *__restrict__ Aw, const uint32_t *__restrict__ X, uint32_t S, uint32_t tiles,
-    uint32_t nb_total, uint32_t log2L, uint32_t pfw2, double *__restrict__ blocksum, double *__restrict__ tglobal,
+    uint32_t nb_total, uint32_t log2L, double *__restrict__ blocksum, double *__restrict__ tglobal,
     uint32_t *__restrict__ tileflag, uint32_t *__restrict__ counters, uint32_t *__restrict__ occ_out) {
     extern __shared__ double smem_d[];
     constexpr int SXV = ((SR + 1) * SPP + 63) / 64;                    // row vectors per lane and unit (<= 9)
@@ -59,13 +62,16 @@ __global__ __launch_bounds__(SQ * 64) void score_rowseg_kernel(
     uint32_t *xbuf = (uint32_t *)smem_d + (size_t)wave * (SR + 1) * SRS;
     uint32_t *tbuf = (uint32_t *)smem_d + (size_t)SQ * (SR + 1) * SRS; // two slots of KB * STPL words
     const uint32_t r = (uint32_t)lane >> 1, h2 = (uint32_t)lane & 1u;
-    const uint32_t tw = Wd - pfw2;                                     // masked words at the end of a row (<= STW)
+    // The words of a row on this tile: [0, pfw2) FULL at every step (no masks needed), [pfw2, wend) with
+    // masks (at most STW: the host checks), [wend, Wd) without a page at any step (only stray bits).
+    const uint32_t pfw2 = q.tile_pfw[tile] & ~1u, wend = q.tile_end[tile];
+    const uint32_t tw = wend - pfw2;
 
-    // what a segment covers: words [start, start + segw) are loaded, the unmasked words [lo, hi) are
-    // counted by the word loop (lo, hi relative to start)
+    // What a segment covers: words [start, start + segw) are loaded; it OWNS the words [own_lo, own_hi)
+    // (the last segment ends at the end of the row and owns what the one before it does not reach).
     auto seg_start = [&](uint32_t g) { return g + 1 < G ? g * segw : Wd - segw; };
-    auto seg_lo = [&](uint32_t g) { return g + 1 < G ? 0u : min((G - 1) * segw, pfw2) - (Wd - segw); };
-    auto seg_hi = [&](uint32_t g) { const uint32_t st = seg_start(g); return pfw2 > st ? min(segw, pfw2 - st) : 0u; };
+    auto seg_own_lo = [&](uint32_t g) { return g * segw; };
+    auto seg_own_hi = [&](uint32_t g) { return g + 1 < G ? (g + 1) * segw : Wd; };
 
     // the lane's own step
     const uint32_t rho = h2 * SR + r;
@@ -174,7 +180,9 @@ __global__ __launch_bounds__(SQ * 64) void score_rowseg_kernel(
         asm volatile("" : "+v"(ro), "+v"(hv));
         const uint32_t *cur = xbuf + SRS + ro, *prv = xbuf + ((p == 0 && very_first) ? (uint32_t)SRS : ro);
         const uint32_t *ts = tbuf + slot * KB * STPL + ro;
-        const uint32_t start = seg_start(g), lo = seg_lo(g), hi = seg_hi(g);
+        const uint32_t start = seg_start(g), own_lo = seg_own_lo(g), own_hi = seg_own_hi(g);
+        // the unmasked words among the owned ones, relative to start: the word loop counts [lo, hi)
+        const uint32_t lo = own_lo - start, hi = min(own_hi, max(pfw2, own_lo)) - start;
         auto word = [&](uint32_t w) __attribute__((always_inline)) {
             const uint32_t raw = cur[w], d = raw ^ prv[w];
 #pragma unroll
@@ -191,12 +199,12 @@ __global__ __launch_bounds__(SQ * 64) void score_rowseg_kernel(
             for (uint32_t j = j_lo; j < j_hi; j++) word(2 * j + hv);
         }
         const bool own = hv == p;
-        if (g + 1 == G) {
-            // the masked words at the end of the row, taken by the lane that owns the row
+        if (pfw2 < own_hi && wend > own_lo) {
+            // the masked words that this segment owns, taken by the lane that owns the row
             uint32_t flt = 0;
 #pragma unroll
             for (int t = 0; t < STW; t++) {
-                if ((uint32_t)t < tw) {
+                if ((uint32_t)t < tw && pfw2 + t >= own_lo && pfw2 + t < own_hi) {
                     const uint32_t w = pfw2 + t - start;
                     const uint32_t vv = own ? vt[t] : 0u, pp = own ? pt[t] : 0u;
                     const uint32_t raw = cur[w], x = raw & vv;
@@ -211,10 +219,15 @@ __global__ __launch_bounds__(SQ * 64) void score_rowseg_kernel(
             }
             fl_acc |= (own && active) ? flt : 0u;
         }
+        if (wend < own_hi) {                                           // bits where no page exists: the row's lanes take turns
+            uint32_t fdead = 0;
+            const uint32_t first = max(wend, own_lo) - start;
+            for (uint32_t w = first + ((first ^ hv) & 1u); w < own_hi - start; w += 2) fdead |= cur[w];
+            fl_acc |= (SR * p + r < rows) ? fdead : 0u;
+        }
         // the word that receives the step's token, in the segment that counts it (written pages exist:
         // no alive mask needed); every lane looks, the row's owner keeps it
         {
-            const uint32_t own_lo = g + 1 < G ? start : start + lo, own_hi = g + 1 < G ? start + hi : Wd;
             const bool here = wsel >= own_lo && wsel < own_hi;
             const uint32_t col = here ? wsel - start : 0u;
             c_hw += here ? (uint32_t)__popc(cur[col] & wmw) : 0u;
@@ -298,8 +311,8 @@ int kvp_score_rowseg_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_
                             uint32_t *counters, uint32_t *occ) {
     const DevProblem &q = ctx->dp;
     if (!ctx->aw || !q.single_write || q.Wd <= 68) return 1;
-    const uint32_t pfw2 = ctx->pfw & ~1u, KB = ctx->kb;
-    if (q.Wd - pfw2 > STW || KB > 2) return 1;
+    const uint32_t KB = ctx->kb;
+    if (ctx->max_tail > STW || KB > 2) return 1;
     // 32-bit (signed) byte offsets inside the digit planes and inside a schedule, the rows that a
     // ragged last tile asks for past the end included (they are clamped after the addition)
     if (((size_t)q.L * q.N + 64) * KB * q.Wd >= (1ull << 29)) return 1;
@@ -320,7 +333,7 @@ int kvp_score_rowseg_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_
         KVP_HIP(hipFuncSetAttribute((const void *)score_rowseg_kernel<KK, PP, SS>,                                 \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                       \
         score_rowseg_kernel<KK, PP, SS><<<grid, block, lds, ctx->stream>>>(q, ctx->aw, X, S, tiles, nb_total,      \
-                                                                           log2L, pfw2, ctx->d_blocksum,           \
+                                                                           log2L, ctx->d_blocksum,                 \
                                                                            ctx->d_tglobal, ctx->d_tileflag,        \
                                                                            counters, occ);                         \
     } while (0)

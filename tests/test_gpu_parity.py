@@ -66,6 +66,10 @@ def _cases():
     yield "dec-w130-k3", _decode(47, L=3, N=66, words=128, page_tokens=4, K=3)     # masked words start before the last segment; two digit planes
     yield "dec-w200", _decode(48, L=2, N=40, words=199, page_tokens=8)             # one short tile, four segments
     yield "dec-w80-tail6", _decode(49, L=2, N=170, words=80, page_tokens=1)        # six masked words, ragged third tile
+    # long decodes: the masked words differ from tile to tile, and words past the sequence's end hold no page yet
+    yield "dec-long-w20", _decode(50, L=4, N=300, words=20, page_tokens=1)         # 30 words, the live end moves by two a tile
+    yield "dec-long-w70", _decode(51, L=2, N=400, words=70, page_tokens=1)         # 83 words in two segments
+    yield "dec-grow-w93", _decode(52, L=2, N=2000, words=30, page_tokens=1, K=2)   # the live end crosses from one segment into the next
     # layer counts 2^k q whose summation tree stays on chip: block boundaries fall inside a token step
     yield "dec-L80-k8", _decode(37, L=80, N=130, words=32, page_tokens=2, K=8)     # 80 = 16 * 5, three tiles, the last of 2 steps
     yield "dec-L24", _decode(38, L=24, N=70, words=19, page_tokens=4)              # 8 * 3
@@ -96,7 +100,7 @@ CASES = list(_cases())
 # scorers that must run natively (not be replaced by another) on a case
 NATIVE = {
     "rowblock": {"longctx/2", "gqa70b/2", "dec-w21-L3", "dec-w38-k3", "dec-w68-k2", "dec-w16", "dec-w16-L30",
-                 "dec-L80-k8", "dec-L24", "dec-L48", "dec-L96", "dec-L112", "tok-p4-w20", "tok-p16-w17"},
+                 "dec-L80-k8", "dec-L24", "dec-L48", "dec-L96", "dec-L112", "tok-p4-w20", "tok-p16-w17", "dec-long-w20"},
     "chunk": {"rand-wide", "rand-w40", "rand-w300", "rand-w301", "longctx/4", "longctx/2", "rand-w16", "dec-w24-tail"},
     "line": {"rand-wide", "rand-w40", "rand-w300", "rand-w301", "longctx/2", "dec-w38-k3", "dec-w68-k2"},
     "rows": {c[0] for c in CASES},
@@ -104,7 +108,7 @@ NATIVE = {
     "direct": {"tiny", "table1", "llama8b/4", "rand-odd"},
     "wide": {"rand-wide", "rand-w40", "rand-w300", "rand-w301"},
     "quad": {"llama8b/4", "rand-L16", "rand-L64", "rand-L2"},
-    "rowseg": {"dec-w70", "dec-w128", "dec-w130-k3", "dec-w200", "dec-w80-tail6"},
+    "rowseg": {"dec-w70", "dec-w128", "dec-w130-k3", "dec-w200", "dec-w80-tail6", "dec-long-w70", "dec-grow-w93"},
 }
 
 
