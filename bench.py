@@ -107,7 +107,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="llama8b", help="tiny|llama8b|longctx|serving|gqa70b")
+    ap.add_argument("--workload", default="llama8b", help="tiny|llama8b|longctx|serving|gqa70b (the benchmark list), decode36k")
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--schedules", type=int, default=0, help="S (default: >= 4 GiB of placements)")
     ap.add_argument("--chains", type=int, default=0)

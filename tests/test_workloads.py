@@ -34,6 +34,16 @@ def test_llama_shape_and_determinism():
     assert a.cap_pages == int(0.30 * a.L * a.alive.sum(axis=1).max())
 
 
+def test_long_decode_recipe():
+    full = W.recipe("decode36k")
+    assert (full.L, full.N, full.prompt_lo, full.page_tokens) == (32, 4096, 36864, 16)      # rows of 80 mask words
+    tr = W.config("decode36k", 0.0625)
+    assert tr.written.sum(axis=1).tolist() == [1] * tr.N                                    # one sequence
+    ctx = tr.alive.sum(axis=1)
+    assert (np.diff(ctx) >= 0).all() and ctx[-1] == tr.P                                    # it only grows
+    assert "decode36k" not in W.CONFIG_NAMES                                                # not a benchmark configuration
+
+
 def test_serving_slots_turn_over():
     tr = W.config("serving", 0.08)
     assert tr.written.sum(axis=1).min() == tr.recipe.slots      # every sequence writes one token per step

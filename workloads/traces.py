@@ -324,6 +324,14 @@ def recipe(name: str, scale: float = 1.0) -> Recipe:
                       prompt_lo=sc(131072, 256, 128), prompt_hi=sc(131072, 256, 128),
                       top_frac=0.04, phi=0.9, sigma=0.7,
                       cap_frac=0.15, **_ratio(8), chains=512, moves=50000, seed=4)
+    if name == "decode36k":
+        # Not one of the benchmark's configurations: one long sequence in the manner of the paper's own
+        # workload (Sec. IV-A: a prompt of some 30k tokens, thousands of decoded tokens), with rows of 80
+        # mask words, wider than the widest single-sequence configuration above.
+        return Recipe("decode36k", L=sc(32, 2), N=sc(4096, 8), page_tokens=16,
+                      prompt_lo=sc(36864, 64, 16), prompt_hi=sc(36864, 64, 16),
+                      top_frac=0.05, phi=0.9, sigma=0.7,
+                      cap_frac=0.20, **_ratio(8), chains=256, moves=100000, seed=6)
     if name == "table1":
         # Memory system of the paper's Table I: the one case where the link and
         # the DRAM channels differ.  508-token prompt: a page is born at step 4,
