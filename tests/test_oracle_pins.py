@@ -452,6 +452,15 @@ def test_strict_excess_by_hand():
     # a page of layer 1 that does not persist into step 1 is gone before slot (1,0)
     tr.persist[1, 0] = 0
     assert O.strict_excess(tr, X) == 0
+    # a bit on a page that does not exist takes no room: page 1 of two is never alive
+    t2 = _mini(L=2, N=2, P=2, cap=1)
+    t2.alive[:, 0] = 1
+    t2.persist[1, 0] = 1
+    Z = np.zeros((2, 2, 2), np.uint8)
+    Z[0, :, 0] = 1                                                     # layer 0 keeps its page: the pool is full
+    assert O.strict_excess(t2, Z) == 0
+    Z[1, :, 1] = 1                                                     # stray bits of layer 1
+    assert O.strict_excess(t2, Z) == 0
 
 
 @pytest.mark.parametrize("name,scale", [("tiny", 1.0), ("llama8b", 0.25), ("serving", 0.0625), ("gqa70b", 0.0625)])
