@@ -545,9 +545,9 @@ def test_wr_search_walks_like_the_oracle(G, name, scale, kw):
 
 
 def _full_shape(name):
-    """Trace and batch size of a benchmark config.  Config 1 is taken whole (the benchmark's own launch);
-    the two configs whose trace takes minutes to draw keep their layers, row width and planes but
-    fewer token steps."""
+    """Trace and batch size of a benchmark workload.  `llama8b` and `longctx` are taken whole (the
+    benchmark's own launch); the two workloads whose trace takes minutes to draw keep their layers,
+    row width and planes but fewer token steps."""
     import dataclasses
     import bench
     from workloads.traces import generate, recipe
