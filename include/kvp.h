@@ -15,9 +15,10 @@
  *     owned by the caller, 16-byte aligned.  Pointers named h_* are HOST memory.
  *     The library copies what it keeps and retains no caller pointer.
  *   - kvp_score, kvp_delta_score, kvp_anneal, kvp_baseline, kvp_strict_excess
- *     enqueue their work on the HIP stream given to kvp_create and return
- *     without waiting (they may allocate internal buffers first).  kvp_trace_upload, kvp_best, kvp_chain_placement
- *     and kvp_chain_stats wait for the stream.
+ *     and kvp_exchange (without a count) enqueue their work on the HIP stream
+ *     given to kvp_create and return without waiting (they may allocate
+ *     internal buffers first).  kvp_trace_upload, kvp_best, kvp_temper,
+ *     kvp_chain_placement and kvp_chain_stats wait for the stream.
  *   - Bit masks: uint32 words, bit b of word w is page 32*w + b; bits at or
  *     above n_pages are zero.  A schedule is [n_layers][n_steps][n_words]
  *     words; a batch of S schedules is S of those back to back.
