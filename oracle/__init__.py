@@ -20,13 +20,21 @@ _LIB = os.path.join(_HERE, "_build", "liborc.so")
 CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC"]
 
 
-def build(force: bool = False) -> str:
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        os.makedirs(os.path.dirname(_LIB), exist_ok=True)
-        tmp = _LIB + f".{os.getpid()}.tmp"
-        subprocess.check_call(["gcc", *CFLAGS, "-o", tmp, _SRC, "-lm"])
-        os.replace(tmp, _LIB)
-    return _LIB
+SANITIZE_FLAGS = ["-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"]
+_LIB_SAN = os.path.join(_HERE, "_build", "liborc_san.so")
+
+
+def build(force: bool = False, sanitize: bool = False) -> str:
+    """Compile the oracle.  sanitize=True builds a second library with AddressSanitizer and
+    UBSan (any finding aborts); a process loads it with libasan preloaded and
+    KVP_ORACLE_SANITIZE=1 in its environment."""
+    out = _LIB_SAN if sanitize else _LIB
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        os.makedirs(os.path.dirname(out), exist_ok=True)
+        tmp = out + f".{os.getpid()}.tmp"
+        subprocess.check_call(["gcc", *CFLAGS, *(SANITIZE_FLAGS if sanitize else []), "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, out)
+    return out
 
 
 class _Problem(C.Structure):
@@ -74,7 +82,7 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        L = C.CDLL(build())
+        L = C.CDLL(build(sanitize=os.environ.get("KVP_ORACLE_SANITIZE") == "1"))
         L.orc_csum.restype = C.c_double
         L.orc_csum.argtypes = [C.c_void_p, C.c_size_t]
         L.orc_step_time.restype = C.c_double
@@ -103,6 +111,12 @@ def lib():
         L.orc_wr_policy.argtypes = [C.POINTER(_Problem), C.c_uint32, C.c_uint32, C.c_void_p]
         L.orc_exchange.restype = C.c_uint32
         L.orc_exchange.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.orc_draw_move.restype = None
+        L.orc_draw_move.argtypes = [C.POINTER(_Problem), C.POINTER(_SAParams), C.c_uint32, C.c_uint64, C.c_uint32,
+                                    C.POINTER(_Move), C.POINTER(C.c_double)]
+        L.orc_wr_propose.restype = C.c_int
+        L.orc_wr_propose.argtypes = [C.POINTER(_WRParams), C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32,
+                                     C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_double)]
         L.orc_wr_search.restype = C.c_uint64
         L.orc_wr_search.argtypes = [C.POINTER(_Problem), C.POINTER(_WRParams), C.c_void_p, C.POINTER(WRResult)]
         _lib = L
@@ -335,6 +349,39 @@ def anneal_chain(tr, chain, X0, *, seed, total_moves, move_begin=0, move_end=Non
         raise ValueError(f"orc_anneal_chain failed ({rc}): bad parameters or infeasible start")
     return ChainResult(int(chain), X, best, cost(q, best), st.T_cur, st.T_best, st.C0, st.accepted,
                        st.uphill, st.null_moves, st.clipped, st.improved, st)
+
+
+def draw_moves(tr, chain, first, count, *, seed, stream0=0, max_len=63, op_prob=(0.4, 0.4, 0.2)):
+    """Proposals first .. first+count-1 of `chain` as the annealer draws them: a dict of uint32 arrays
+    (the fields of a raw move) and the acceptance draws u."""
+    q = _problem(tr)
+    sp = _SAParams()
+    sp.seed, sp.max_len = int(seed), int(max_len)
+    for i in range(3):
+        sp.op_prob[i] = float(op_prob[i])
+    names = ("op", "layer", "page", "n1", "len", "layer2", "page2", "dsel")
+    out = {k: np.zeros(count, np.uint32) for k in names}
+    us = np.zeros(count)
+    m, u, f = _Move(), C.c_double(0.0), lib().orc_draw_move
+    for j in range(count):
+        f(C.byref(q.c), C.byref(sp), int(chain), int(first) + j, int(stream0), C.byref(m), C.byref(u))
+        for k in names:
+            out[k][j] = getattr(m, k)
+        us[j] = u.value
+    return out, us
+
+
+def wr_proposals(w, r10, first, count, *, seed, stream=16, w_max=1 << 20, op_prob=(0.4, 0.4, 0.2)):
+    """Proposals first .. first+count-1 of the (W, R) walk, all from the state (w, r10): arrays
+    in_range (0/1), w2, r2 (valid where in_range) and u."""
+    sp = _WRParams(int(w_max), int(w), int(r10), 1, int(seed), 0, 0.8, 0.9, (C.c_double * 3)(*op_prob), 0.0, 0.0)
+    ok = np.zeros(count, np.int32)
+    w2s, r2s, us = np.zeros(count, np.int64), np.zeros(count, np.int64), np.zeros(count)
+    w2, r2, u, f = C.c_uint32(0), C.c_uint32(0), C.c_double(0.0), lib().orc_wr_propose
+    for j in range(count):
+        ok[j] = f(C.byref(sp), int(first) + j, int(stream), int(w), int(r10), C.byref(w2), C.byref(r2), C.byref(u))
+        w2s[j], r2s[j], us[j] = w2.value, r2.value, u.value
+    return ok, w2s, r2s, us
 
 
 def temper(results, factors) -> None:

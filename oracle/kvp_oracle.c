@@ -503,8 +503,13 @@ typedef struct {
 
 #define ORC_CALIB 256
 
-static void draw_move(const orc_problem *q, const orc_sa_params *sp, uint32_t chain, uint64_t mi,
-                      uint32_t stream0, orc_move *m, double *u) {
+/* Proposal `mi` of chain `chain`: three Philox blocks, counter (mi lo, mi hi, chain, stream0 + 0..2)
+ * under the seed.  Block 0: operator (word 0 against the cumulative shares of op_prob: the
+ * three-operator mixture of Sec. III-B), layer, page, first step; block 1: span 1..max_len, victim
+ * layer and page, direction of a SHIFT; block 2: the 52 bits of the acceptance draw u in (0, 1).
+ * An index in 0..n-1 is the high word of (32 random bits) x n.  Exported for the pins. */
+void orc_draw_move(const orc_problem *q, const orc_sa_params *sp, uint32_t chain, uint64_t mi,
+                   uint32_t stream0, orc_move *m, double *u) {
     uint32_t key[2] = {(uint32_t)sp->seed, (uint32_t)(sp->seed >> 32)};
     uint32_t ctr[4] = {(uint32_t)mi, (uint32_t)(mi >> 32), chain, stream0};
     uint32_t a[4], b[4], c[4];
@@ -581,7 +586,7 @@ int orc_anneal_chain(const orc_problem *q, const orc_sa_params *sp, uint32_t cha
         double sum = 0.0; uint32_t cnt = 0;
         for (uint64_t j = 0; j < ORC_CALIB; j++) {
             orc_move m; double u; int base, second;
-            draw_move(q, sp, chain, j, 8, &m, &u);
+            orc_draw_move(q, sp, chain, j, 8, &m, &u);
             if (orc_resolve(q, X, occ, &m, f1, f2, &base) == ORC_NULL) continue;
             double dT = window_delta(q, X, &m, f1, f2, base, tcur, tn1, tn2, &second);
             if (dT > 0.0) { sum = sum + dT; cnt++; }
@@ -594,7 +599,7 @@ int orc_anneal_chain(const orc_problem *q, const orc_sa_params *sp, uint32_t cha
         uint64_t lvl = mi / mpl; if (lvl > sp->n_levels - 1) lvl = sp->n_levels - 1;
         while (st->level < lvl) { st->C = st->C * sp->alpha; st->level++; }
         orc_move m; double u; int base, second;
-        draw_move(q, sp, chain, mi, 0, &m, &u);
+        orc_draw_move(q, sp, chain, mi, 0, &m, &u);
         int verdict = orc_resolve(q, X, occ, &m, f1, f2, &base);
         if (verdict == ORC_NULL) { st->null_moves++; continue; }
         if (verdict == ORC_CLIPPED) st->clipped++;
@@ -763,8 +768,9 @@ static double wr_cost(const orc_problem *q, uint32_t w_max, double *table, uint3
     return *slot;
 }
 
-static int wr_propose(const orc_wr_params *sp, uint64_t i, uint32_t stream, uint32_t w, uint32_t r10, uint32_t *w2,
-                      uint32_t *r2, double *u) {
+/* Proposal i from state (w, r10): returns 0 if it leaves the grid.  Exported for the pins. */
+int orc_wr_propose(const orc_wr_params *sp, uint64_t i, uint32_t stream, uint32_t w, uint32_t r10, uint32_t *w2,
+                   uint32_t *r2, double *u) {
     uint32_t ctr[4] = {(uint32_t)i, (uint32_t)(i >> 32), 0, stream};
     uint32_t key[2] = {(uint32_t)sp->seed, (uint32_t)(sp->seed >> 32)}, a[4];
     orc_philox4x32_10(ctr, key, a);
@@ -790,7 +796,7 @@ uint64_t orc_wr_search(const orc_problem *q, const orc_wr_params *sp, double *ta
     double sum = 0.0; uint32_t cnt = 0;
     for (uint64_t j = 0; j < 32; j++) {
         uint32_t w2, r2; double u;
-        if (!wr_propose(sp, j, 24, w, r10, &w2, &r2, &u)) continue;
+        if (!orc_wr_propose(sp, j, 24, w, r10, &w2, &r2, &u)) continue;
         double dT = wr_cost(q, sp->w_max, table, w2, r2, X, &res->evaluated) - T;
         if (dT > 0.0) { sum = sum + dT; cnt++; }
     }
@@ -809,7 +815,7 @@ uint64_t orc_wr_search(const orc_problem *q, const orc_wr_params *sp, double *ta
         }
         uint32_t w2, r2; double u;
         res->proposals++;
-        if (!wr_propose(sp, i, 16, w, r10, &w2, &r2, &u)) { res->out_of_range++; continue; }
+        if (!orc_wr_propose(sp, i, 16, w, r10, &w2, &r2, &u)) { res->out_of_range++; continue; }
         double T2 = wr_cost(q, sp->w_max, table, w2, r2, X, &res->evaluated);
         double dT = T2 - T;
         int accept = (dT <= 0.0) || (C > 0.0 && u < exp(-dT / C));    /* Metropolis */

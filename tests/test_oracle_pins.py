@@ -702,3 +702,185 @@ def test_exchange_keeps_the_ladder_and_feeds_the_next_slice(seed):
     assert sorted(r.state.C for r in res) == want
     for r in res:
         assert O.score(O.Problem(tr), r.X).excess == 0 and r.T_best <= O.cost(O.Problem(tr), X0)
+
+
+# ---- the two proposal generators (Sec. III-B: three operators with shares 0.4, 0.4, 0.2; window
+# ---- steps -2, -1, +1, +2; ratio steps -0.1, +0.1) ------------------------------------------------
+
+def _within(k, n, p, sigmas=4.0):
+    return abs(k / n - p) < sigmas * math.sqrt(p * (1 - p) / n)
+
+
+def test_draw_move_decoded_by_hand_from_the_published_block():
+    # Seed 0, chain 0, move 0, stream 0: block 0 of the proposal is Philox4x32-10 of counter 0 under
+    # key 0, the first published vector: 6627e8d5 e169c58d bc57ac4c 9b00dbd8.
+    #   word 0 = 1713891541 = 0.39905 * 2^32, below 0.4 * 2^32 (floor 1717986918): the first operator
+    #   word 1 / 2^32 = 0.880520: layer floor(0.880520 * 32)  = floor(28.18)  = 28
+    #   word 2 / 2^32 = 0.735713: page  floor(0.735713 * 272) = floor(200.11) = 200
+    #   word 3 / 2^32 = 0.605482: step  floor(0.605482 * 256) = floor(155.003) = 155
+    tr = _mini(L=32, N=256, P=272)
+    m, _ = O.draw_moves(tr, 0, 0, 1, seed=0)
+    assert (m["op"][0], m["layer"][0], m["page"][0], m["n1"][0]) == (0, 28, 200, 155)
+    # the shares are cumulative: with 0.39 for the first operator the same word (0.39905) falls to the
+    # second, and with 0.39 + 0.009 for the first two to the third
+    assert O.draw_moves(tr, 0, 0, 1, seed=0, op_prob=(0.39, 0.41, 0.2))[0]["op"][0] == 1
+    assert O.draw_moves(tr, 0, 0, 1, seed=0, op_prob=(0.39, 0.009, 0.601))[0]["op"][0] == 2
+    # another shape, the same block: floor(0.880520 * 80) = 70, floor(0.735713 * 1040) = 765,
+    # floor(0.605482 * 2048) = 1240
+    m, _ = O.draw_moves(_mini(L=80, N=2048, P=1040), 0, 0, 1, seed=0)
+    assert (m["layer"][0], m["page"][0], m["n1"][0]) == (70, 765, 1240)
+    # the third published vector as (move, chain, stream) = counter and seed = key
+    ctr, key = [0x243f6a88, 0x85a308d3, 0x13198a2e, 0x03707344], [0xa4093822, 0x299f31d0]
+    blk = [0xd16cfe09, 0x94fdcceb, 0x5001e420, 0x24126ea1]
+    m, _ = O.draw_moves(tr, ctr[2], ctr[0] | ctr[1] << 32, 1, seed=key[0] | key[1] << 32, stream0=ctr[3])
+    # 0xd16cfe09 / 2^32 = 0.818: beyond 0.4 + 0.4, the third operator
+    assert (m["op"][0], m["layer"][0], m["page"][0], m["n1"][0]) == (
+        2, blk[1] * 32 >> 32, blk[2] * 272 >> 32, blk[3] * 256 >> 32) == (2, 18, 85, 36)
+
+
+def test_draw_move_second_and_third_block_feed_span_victim_direction_and_u():
+    tr = _mini(L=7, N=50, P=90)
+    seed, chain, mi = 0x0123_4567_89AB_CDEF, 5, (3 << 32) | 17
+    m, u = O.draw_moves(tr, chain, mi, 1, seed=seed, stream0=8, max_len=11)
+    key = [seed & 0xFFFFFFFF, seed >> 32]
+    b = [int(x) for x in O.philox4x32_10([mi & 0xFFFFFFFF, mi >> 32, chain, 9], key)]
+    c = [int(x) for x in O.philox4x32_10([mi & 0xFFFFFFFF, mi >> 32, chain, 10], key)]
+    assert (m["len"][0], m["layer2"][0], m["page2"][0], m["dsel"][0]) == (
+        1 + (b[0] * 11 >> 32), b[1] * 7 >> 32, b[2] * 90 >> 32, b[3] >> 30)
+    assert u[0] == ((c[0] << 20 | c[1] >> 12) + 0.5) * 2.0 ** -52
+
+
+def test_draw_move_frequencies():
+    n = 200_000
+    L, N, P, max_len = 5, 12, 37, 9
+    m, u = O.draw_moves(_mini(L=L, N=N, P=P), 3, 0, n, seed=77, max_len=max_len)
+    # the three operators at 0.4, 0.4, 0.2 (Sec. III-B)
+    for op, p in ((0, 0.4), (1, 0.4), (2, 0.2)):
+        assert _within((m["op"] == op).sum(), n, p), op
+    # every index uniform on exactly its range
+    for name, size in (("layer", L), ("page", P), ("n1", N), ("layer2", L), ("page2", P), ("dsel", 4)):
+        cnt = np.bincount(m[name], minlength=size)
+        assert len(cnt) == size and all(_within(k, n, 1.0 / size) for k in cnt), name
+    # spans 1 .. max_len, each equally often
+    cnt = np.bincount(m["len"], minlength=max_len + 1)
+    assert len(cnt) == max_len + 1 and cnt[0] == 0 and all(_within(k, n, 1.0 / max_len) for k in cnt[1:])
+    # the acceptance draw: inside (0, 1), mean 1/2, variance 1/12, every decile equally often
+    assert u.min() > 0.0 and u.max() < 1.0
+    assert abs(u.mean() - 0.5) < 4.0 * math.sqrt(1 / 12 / n) and abs(u.var() - 1 / 12) < 0.002
+    assert all(_within(k, n, 0.1) for k in np.bincount((u * 10).astype(int), minlength=10))
+    # fields do not lean on each other: operator against direction, span against step, page against victim
+    for a, b, sa, sb in (("op", "dsel", 3, 4), ("len", "n1", max_len + 1, N), ("layer", "layer2", L, L)):
+        joint = np.zeros((sa, sb))
+        np.add.at(joint, (m[a], m[b]), 1)
+        pa, pb = joint.sum(1) / n, joint.sum(0) / n
+        for i in range(sa):
+            for j in range(sb):
+                if pa[i] * pb[j] > 0:
+                    assert _within(joint[i, j], n, pa[i] * pb[j], 4.5), (a, b, i, j)
+    # other shares are honoured as given
+    m2, _ = O.draw_moves(_mini(L=L, N=N, P=P), 0, 0, 50_000, seed=5, op_prob=(0.1, 0.6, 0.3))
+    for op, p in ((0, 0.1), (1, 0.6), (2, 0.3)):
+        assert _within((m2["op"] == op).sum(), 50_000, p), op
+    # a proposal depends on (seed, chain, move) only and differs between chains and between moves
+    again, _ = O.draw_moves(_mini(L=L, N=N, P=P), 3, 1000, 50, seed=77, max_len=max_len)
+    assert all((again[k] == m[k][1000:1050]).all() for k in again)
+    other, _ = O.draw_moves(_mini(L=L, N=N, P=P), 4, 0, 50, seed=77, max_len=max_len)
+    assert any((other[k] != m[k][:50]).any() for k in other)
+
+
+def test_wr_propose_decoded_by_hand_from_the_published_block():
+    # Proposal 0 on stream 0 under seed 0 is the first published vector 6627e8d5 e169c58d bc57ac4c 9b00dbd8:
+    #   word 0 / 2^32 = 0.39905 < 0.4: a window move; top two bits of word 1 (0xe...) = 3: the last of
+    #   (-2, -1, +1, +2); top bit of word 2 (0xb...) = 1: ratio up, used only by a ratio or diagonal move
+    u_want = (0x9b00dbd8 + 0.5) / 2.0 ** 32
+    ok, w2, r2, u = O.wr_proposals(5, 5, 0, 1, seed=0, stream=0)
+    assert (ok[0], w2[0], r2[0], u[0]) == (1, 7, 5, u_want)
+    ok, w2, r2, _ = O.wr_proposals(5, 5, 0, 1, seed=0, stream=0, op_prob=(0.39, 0.41, 0.2))     # a ratio move
+    assert (ok[0], w2[0], r2[0]) == (1, 5, 6)
+    ok, w2, r2, _ = O.wr_proposals(5, 5, 0, 1, seed=0, stream=0, op_prob=(0.39, 0.009, 0.601))  # diagonal
+    assert (ok[0], w2[0], r2[0]) == (1, 7, 6)
+    # proposals that leave 1 <= W <= w_max or 0 <= R <= 1 are refused
+    assert O.wr_proposals(5, 5, 0, 1, seed=0, stream=0, w_max=6)[0][0] == 0
+    assert O.wr_proposals(5, 5, 0, 1, seed=0, stream=0, w_max=7)[0][0] == 1
+    assert O.wr_proposals(5, 10, 0, 1, seed=0, stream=0, op_prob=(0.39, 0.41, 0.2))[0][0] == 0
+
+
+def test_wr_propose_frequencies():
+    n = 200_000
+    ok, w2, r2, u = O.wr_proposals(50, 5, 0, n, seed=9)
+    assert ok.all()
+    dw, dr = w2 - 50, r2 - 5
+    # step sets: window by -2, -1, +1, +2 (never 0 on its own), ratio by one tenth up or down
+    assert set(np.unique(dw)) == {-2, -1, 0, 1, 2} and set(np.unique(dr)) == {-1, 0, 1}
+    window, ratio, diag = (dw != 0) & (dr == 0), (dw == 0) & (dr != 0), (dw != 0) & (dr != 0)
+    assert not ((dw == 0) & (dr == 0)).any()
+    for sel, p in ((window, 0.4), (ratio, 0.4), (diag, 0.2)):
+        assert _within(sel.sum(), n, p)
+    # the steps of each kind equally often, alone and in a diagonal move
+    for sel in (window, diag):
+        k = sel.sum()
+        assert all(_within((dw[sel] == d).sum(), k, 0.25) for d in (-2, -1, 1, 2))
+    for sel in (ratio, diag):
+        assert _within((dr[sel] == 1).sum(), sel.sum(), 0.5)
+    k = diag.sum()
+    for d in (-2, -1, 1, 2):
+        for e in (-1, 1):
+            assert _within(((dw == d) & (dr == e)).sum(), k, 0.125, 4.5)
+    assert u.min() > 0.0 and u.max() < 1.0 and abs(u.mean() - 0.5) < 4.0 * math.sqrt(1 / 12 / n)
+    # u does not lean on the kind of move
+    for sel in (window, ratio, diag):
+        assert abs(u[sel].mean() - 0.5) < 4.5 * math.sqrt(1 / 12 / sel.sum())
+    # at the edge of the grid exactly the proposals that would leave it are refused
+    ok, w2, r2, _ = O.wr_proposals(1, 0, 0, 50_000, seed=10, w_max=2)
+    ok50 = O.wr_proposals(50, 5, 0, 50_000, seed=10)
+    dw, dr = ok50[1] - 50, ok50[2] - 5
+    assert ((ok == 1) == ((dw >= 0) & (dw <= 1) & (dr >= 0))).all()
+    assert (w2[ok == 1] == 1 + dw[ok == 1]).all() and (r2[ok == 1] == dr[ok == 1]).all()
+
+
+def _flat_table(w_max, value):
+    return np.full((w_max, 11), float(value))
+
+
+def test_wr_search_on_given_cost_tables_by_hand():
+    tr = W.config("tiny")      # the table is given in full, so the trace is never looked at
+    # (a) every state costs the same: each proposal inside the grid has dT = 0 and is accepted, no proposal is
+    # uphill so the start temperature is 0, and the best cost does not improve over the first level: the
+    # stagnation rule (Sec. III-B: less than 0.1 % over a level) ends the walk there
+    res, tab = O.wr_search(tr, w_max=40, total_moves=1000, n_levels=10, seed=3, w0=20, r10_0=5,
+                           table=_flat_table(40, 2.5))
+    assert (res.stop_reason, res.levels_done, res.proposals, res.c0) == (1, 1, 100, 0.0)
+    assert res.accepted == res.proposals - res.out_of_range and res.evaluated == 0
+    assert (res.best_w, res.best_r10, res.best_T, res.cur_T) == (20, 5, 2.5, 2.5)
+    # (b) the start costs 1, every other state 2: each calibration proposal is uphill by exactly 1, so the
+    # start temperature is 1 / (-ln 0.8) and a first uphill move is accepted with probability 0.8; with the
+    # stagnation rule off the walk cools by 0.9 per level until 0.9^k < c_min_frac = 0.5, i.e. k = 7
+    # (0.9^6 = 0.531, 0.9^7 = 0.478), and stops there for the temperature
+    t = _flat_table(40, 2.0)
+    t[19, 5] = 1.0
+    res, _ = O.wr_search(tr, w_max=40, total_moves=1000, n_levels=10, seed=3, w0=20, r10_0=5, stop_rel=0.0,
+                         c_min_frac=0.5, table=t)
+    assert res.c0 == 1.0 / -math.log(0.8)
+    assert (res.stop_reason, res.levels_done, res.proposals) == (2, 7, 700)
+    assert (res.best_w, res.best_r10, res.best_T) == (20, 5, 1.0)
+    # ... and with both rules off the budget ends it
+    res, _ = O.wr_search(tr, w_max=40, total_moves=1000, n_levels=10, seed=3, w0=20, r10_0=5, stop_rel=0.0,
+                         c_min_frac=0.0, table=t.copy())
+    assert (res.stop_reason, res.levels_done, res.proposals) == (0, 9, 1000)
+    # (c) the Metropolis rule at the start temperature: over many seeds, the first proposal (always uphill by
+    # 1) is accepted 8 times in 10
+    acc = sum(O.wr_search(tr, w_max=40, total_moves=1, n_levels=1, seed=s, w0=20, r10_0=5, stop_rel=0.0,
+                          c_min_frac=0.0, table=t.copy())[0].accepted for s in range(6000))
+    assert _within(acc, 6000, 0.8)
+    # (d) a slope with the start at its top corner: no proposal inside the grid is uphill (c0 = 0), the walk
+    # is a pure descent, so the current state is the best one and costs what the table says
+    w_max = 30
+    t = np.array([[1000.0 - (w + 1) - r for r in range(11)] for w in range(w_max)])
+    res, _ = O.wr_search(tr, w_max=w_max, total_moves=60, n_levels=1, seed=4, w0=1, r10_0=0, stop_rel=0.0,
+                         c_min_frac=0.0, table=t.copy())
+    assert res.c0 == 0.0 and res.stop_reason == 0 and res.proposals == 60
+    assert (res.best_w, res.best_r10) == (res.cur_w, res.cur_r10) and res.best_T == res.cur_T
+    assert res.cur_T == t[res.cur_w - 1, res.cur_r10] and res.cur_T < 1000.0 - 1
+    # accepted moves are exactly the proposals inside the grid that do not go up; each lowers W + R by 0..3
+    assert 0 < res.accepted <= res.proposals - res.out_of_range
+    assert 1000.0 - res.cur_T - 1 <= 3 * res.accepted
