@@ -153,6 +153,26 @@ int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *problem, const uint32_t *h
 int kvp_score(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, double *d_cost,
               uint32_t *d_excess, uint32_t *d_counters, uint32_t *d_occ);
 
+/* kvp_score for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments and results as kvp_score with
+ * d_counters = d_occ = NULL, bit for bit, and the same kernels; what kvp_score keeps in buffers
+ * that it allocates and grows (the partial sums of Eq. 1 per block of 64 inference steps, the
+ * capacity verdict of every tile of token steps, and, for layer counts that are not 2^k or
+ * 2^k * {3, 5, 7}, the step latencies) lives here in a static device array of
+ * KVP_STATIC_SCRATCH_BYTES that every GPU on which the library is used holds until the process
+ * ends.  The call makes no hipMalloc, hipFree or other allocating call.
+ *   d_placements [S][L][N][Wd]  in, DEVICE, caller-owned, 16-byte aligned
+ *   d_cost [S], d_excess [S]    out, DEVICE, caller-owned
+ * Errors: as kvp_score, and KVP_ESHAPE when the batch needs more scratch than the array holds:
+ * S * (ceil(L*N/64) * 8 + N * 4) bytes, each of the two terms rounded up to 256, must not exceed
+ * KVP_STATIC_SCRATCH_BYTES (plus S*L*N*8 for the layer counts named above).  Nothing is launched
+ * then.  All calls on one GPU share the one array, whatever their context: two such calls that
+ * overlap in time on a GPU (different streams or threads) race; calls on one stream do not.
+ * Nothing in the array needs to start at zero: every word that a launch reads it has written. */
+#define KVP_STATIC_SCRATCH_BYTES (32u << 20)
+int kvp_score_static(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, double *d_cost,
+                     uint32_t *d_excess);
+
 /* Sec. III-B, dT = T_new - T_current of one proposed move per schedule, summed
  * over the 64-step window the move can touch, without re-scoring the rest.
  *   d_moves    [S]  raw moves
@@ -215,7 +235,8 @@ int kvp_set_anneal_lookahead(kvp_ctx *ctx, int proposals_per_round);
  * previous call except `moves` (else KVP_EINVAL; KVP_ENOCHAINS if none). */
 int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *params, const uint32_t *d_init);
 
-/* Best schedule over all chains: each chain's best-so-far schedule is scored
+/* Sec. III-B (the search returns the schedule of the best latency found).
+ * Best schedule over all chains: each chain's best-so-far schedule is scored
  * again in full (never the running value), the lowest cost wins, ties go to the
  * lowest chain id.  h_placement [L][N][Wd] and h_chain_costs [C] are nullable. */
 int kvp_best(kvp_ctx *ctx, double *h_cost, uint32_t *h_chain, uint32_t *h_placement,

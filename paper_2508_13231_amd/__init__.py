@@ -30,7 +30,8 @@ KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2
 EXPORTS = ["kvp_create", "kvp_destroy", "kvp_trace_upload", "kvp_score", "kvp_delta_score", "kvp_anneal",
            "kvp_best", "kvp_chain_placement", "kvp_chain_stats", "kvp_plane_unit", "kvp_strerror", "kvp_last_hip_error",
            "kvp_set_score_kernel", "kvp_set_anneal_lookahead", "kvp_score_kernel_used", "kvp_baseline", "kvp_wr_policy",
-           "kvp_wr_search", "kvp_strict_excess", "kvp_temper", "kvp_exchange"]
+           "kvp_wr_search", "kvp_strict_excess", "kvp_temper", "kvp_exchange", "kvp_score_static"]
+KVP_STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class kvp_wr_params(C.Structure):
@@ -99,6 +100,8 @@ def lib():
         L.kvp_trace_upload.argtypes = [vp, C.POINTER(kvp_problem), vp, vp, vp, vp]
         L.kvp_score.restype = i32
         L.kvp_score.argtypes = [vp, vp, u32, vp, vp, vp, vp]
+        L.kvp_score_static.restype = i32
+        L.kvp_score_static.argtypes = [vp, vp, u32, vp, vp]
         L.kvp_delta_score.restype = i32
         L.kvp_delta_score.argtypes = [vp, vp, u32, vp, vp, vp, vp, vp]
         L.kvp_anneal.restype = i32
@@ -195,6 +198,11 @@ def kvp_trace_upload(ctx, problem: kvp_problem, access, alive, persist, written)
 def kvp_score(ctx, d_placements, S, d_cost, d_excess, d_counters=None, d_occ=None):
     _check(lib().kvp_score(ctx, _dptr(d_placements), int(S), _dptr(d_cost), _dptr(d_excess),
                            _dptr(d_counters), _dptr(d_occ)), "kvp_score")
+
+
+def kvp_score_static(ctx, d_placements, S, d_cost, d_excess):
+    _check(lib().kvp_score_static(ctx, _dptr(d_placements), int(S), _dptr(d_cost), _dptr(d_excess)),
+           "kvp_score_static")
 
 
 def kvp_delta_score(ctx, d_placements, S, d_moves, d_counters, d_occ, d_delta, d_verdict):

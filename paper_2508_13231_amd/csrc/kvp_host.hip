@@ -18,6 +18,7 @@ extern "C" int kvp_last_hip_error(int *line) {
 
 int kvp_ensure(kvp_ctx *ctx, void **p, size_t *cap, size_t bytes) {
     if (bytes <= *cap && *p) return KVP_OK;
+    if (ctx->no_alloc) return KVP_ESHAPE;             // the caller cannot allocate and what it brought is too small
     if (*p) {
         KVP_HIP(hipStreamSynchronize(ctx->stream));   // earlier work may still read the old buffer
         KVP_HIP(hipFree(*p));
@@ -46,6 +47,10 @@ extern "C" int kvp_create(kvp_ctx **out, int device, void *hip_stream) {
     KVP_HIP(hipGetDeviceCount(&ndev));
     if (device < 0 || device >= ndev) return KVP_EINVAL;
     KVP_HIP(hipSetDevice(device));
+    {
+        const int rc = kvp_static_scratch_init(device);
+        if (rc) return rc;
+    }
     kvp_ctx *c = new (std::nothrow) kvp_ctx();
     if (!c) return KVP_ENOMEM;
     c->device = device;
@@ -275,4 +280,17 @@ extern "C" int kvp_score(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S,
         return KVP_EINVAL;
     KVP_HIP(hipSetDevice(ctx->device));
     return kvp_score_launch(ctx, d_placements, S, d_cost, d_excess, d_counters, d_occ);
+}
+
+int kvp_score_static_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, double *d_cost, uint32_t *d_excess);
+
+extern "C" int kvp_score_static(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, double *d_cost,
+                                uint32_t *d_excess) {
+    if (!ctx) return KVP_EINVAL;
+    if (!ctx->has_trace) return KVP_ENOTRACE;
+    if (S == 0) return KVP_OK;
+    if (!d_placements || !d_cost || !d_excess) return KVP_EINVAL;
+    if (!aligned16(d_placements) || ((uintptr_t)d_cost & 7u) || ((uintptr_t)d_excess & 3u)) return KVP_EINVAL;
+    KVP_HIP(hipSetDevice(ctx->device));
+    return kvp_score_static_launch(ctx, d_placements, S, d_cost, d_excess);
 }

@@ -55,6 +55,7 @@ struct kvp_ctx {
     int score_kernel = 0;                // KVP_SCORE_AUTO, or the scorer kvp_score tries first
     uint32_t compute_units = 1;          // of the context's GPU
     int anneal_lookahead = 0;            // proposals per round in kvp_anneal: 0 auto, 1 or 4
+    bool no_alloc = false;               // set while kvp_score_static runs: kvp_ensure must not allocate
     int last_kernel = 0;                 // scorer that the last kvp_score ran (KVP_SCORE_*), 0 before the first
     bool prefix_full = false;            // on every 64-step tile all mask words but the last are FULL
     uint32_t pfw = 0;                    // leading mask words that are FULL on every 64-step tile
@@ -230,5 +231,6 @@ __device__ __forceinline__ double step_time(const DevProblem &q, uint32_t hr_u, 
 int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, double *d_cost,
                      uint32_t *d_excess, uint32_t *d_counters, uint32_t *d_occ);
 int kvp_ensure(kvp_ctx *ctx, void **p, size_t *cap, size_t bytes);
+int kvp_static_scratch_init(int device);     // kvp_score.hip: resolves the device address of the static scratch
 int kvp_bitslice_build(kvp_ctx *ctx);
 void kvp_free_chains(kvp_ctx *ctx);

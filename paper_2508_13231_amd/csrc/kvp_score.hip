@@ -264,3 +264,48 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
     KVP_HIP(hipGetLastError());
     return KVP_OK;
 }
+
+// ---- scoring for callers that cannot allocate ------------------------------------------------
+// The block sums, the tile verdicts and (for the layer counts whose summation tree is not kept on
+// chip) the step latencies of a launch live in device memory beyond the caller's inputs and
+// outputs.  kvp_score keeps them in buffers that it allocates and grows; kvp_score_static keeps
+// them in this array instead, which every GPU the library runs on holds from load to exit.
+static __device__ __align__(256) unsigned char scratch[KVP_STATIC_SCRATCH_BYTES];
+
+// The array's name is a host-side handle, not a device address: each device has its own copy at
+// its own address, resolved once per device (with that device current) and kept here.
+#define KVP_MAX_DEVICES 64
+static unsigned char *scratch_ptr[KVP_MAX_DEVICES];
+
+int kvp_static_scratch_init(int device) {
+    if (device < 0 || device >= KVP_MAX_DEVICES) return KVP_EINVAL;
+    if (scratch_ptr[device]) return KVP_OK;
+    void *p = nullptr;
+    KVP_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || ((uintptr_t)p & 255u)) return KVP_EHIP;
+    scratch_ptr[device] = (unsigned char *)p;
+    return KVP_OK;
+}
+
+int kvp_score_static_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, double *d_cost, uint32_t *d_excess) {
+    const DevProblem &q = ctx->dp;
+    unsigned char *base = scratch_ptr[ctx->device];
+    if (!base) return KVP_EHIP;                                // kvp_create resolves it; never null after that
+    const uint64_t nb_total = ((uint64_t)q.L * q.N + 63) / 64;
+    auto up = [](uint64_t x) { return (x + 255) & ~(uint64_t)255; };
+    // the general scorer may cut the steps into more tiles than the others' 64-step tiles; N bounds both
+    const uint64_t need_bs = up((uint64_t)S * nb_total * sizeof(double)), need_tf = up((uint64_t)S * q.N * sizeof(uint32_t));
+    if (need_bs + need_tf > KVP_STATIC_SCRATCH_BYTES) return KVP_ESHAPE;
+    // swap the context's own buffers for parts of the static array for the length of this call
+    struct Saved { double *bs; size_t bsc; uint32_t *tf; size_t tfc; double *tg; size_t tgc; } const old = {
+        ctx->d_blocksum, ctx->blocksum_cap, ctx->d_tileflag, ctx->tileflag_cap, ctx->d_tglobal, ctx->tglobal_cap};
+    ctx->d_blocksum = (double *)base;                      ctx->blocksum_cap = (size_t)need_bs;
+    ctx->d_tileflag = (uint32_t *)(base + need_bs);        ctx->tileflag_cap = (size_t)need_tf;
+    ctx->d_tglobal = (double *)(base + need_bs + need_tf); ctx->tglobal_cap = (size_t)(KVP_STATIC_SCRATCH_BYTES - need_bs - need_tf);
+    ctx->no_alloc = true;                                  // a scorer that needs more gets KVP_ESHAPE from kvp_ensure
+    const int rc = kvp_score_launch(ctx, d_placements, S, d_cost, d_excess, nullptr, nullptr);
+    ctx->no_alloc = false;
+    ctx->d_blocksum = old.bs; ctx->blocksum_cap = old.bsc; ctx->d_tileflag = old.tf; ctx->tileflag_cap = old.tfc;
+    ctx->d_tglobal = old.tg; ctx->tglobal_cap = old.tgc;
+    return rc;
+}
