@@ -120,120 +120,152 @@ def _rng(seed: int, tag: int) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=[seed & (2**64 - 1), tag]))
 
 
-def _select_top(z: np.ndarray, eligible: np.ndarray, k: int) -> np.ndarray:
-    """Exactly-k largest of z along the last axis among `eligible` (1-D mask);
-    ties go to the lower index."""
-    out = np.zeros(z.shape, dtype=bool)
-    m = int(eligible.sum())
-    k = min(k, m)
-    if k <= 0:
-        return out
+def _select_top(z: np.ndarray, eligible: np.ndarray, k: np.ndarray) -> np.ndarray:
+    """Exactly-k largest of z along the last axis among `eligible`; ties go to the
+    lower index.  z: [..., S, M]; eligible: bool [S, M]; k: int [S] (a count per
+    row of `eligible`, cut to the number of eligible entries)."""
+    M = z.shape[-1]
+    k = np.minimum(k, eligible.sum(axis=-1))
     zz = np.where(eligible, z, -np.inf)
-    kth = np.partition(zz, zz.shape[-1] - k, axis=-1)[..., zz.shape[-1] - k]
-    gt = zz > kth[..., None]
-    need = k - gt.sum(axis=-1)
-    tie = (zz == kth[..., None]) & eligible
+    pos = np.clip(M - k, 0, M - 1)
+    srt = np.partition(zz, np.unique(pos), axis=-1)                   # every needed position in its sorted place
+    idx = np.broadcast_to(pos[:, None], zz.shape[:-1] + (1,))
+    kth = np.take_along_axis(srt, idx, axis=-1)                       # [..., S, 1]: the k-th largest
+    kth = np.where((k > 0)[:, None], kth, np.inf)
+    gt = zz > kth
+    tie = (zz == kth) & eligible
+    need = k[:, None] - gt.sum(axis=-1, keepdims=True)
+    if (tie.sum(axis=-1, keepdims=True) == need).all():               # no surplus of equal scores: take them all
+        return gt | tie
     rank = np.cumsum(tie, axis=-1)
-    return gt | (tie & (rank <= need[..., None]))
+    return gt | (tie & (rank <= need))
 
 
-def generate(r: Recipe) -> Trace:
+def _plan(r: Recipe, slot_pages: int):
+    """The sequences of every slot, step by step (no importance scores yet): context length [N][S],
+    whether the slot's sequence started at the step [N][S], and the page masks that follow."""
     rng = _rng(r.seed, 1)
-    L, N, K, S = r.L, r.N, r.K, r.slots
-    pt = r.page_tokens
-    slot_pages = r.slot_pages or -(-(r.prompt_hi + N) // pt)
+    N, S, pt = r.N, r.slots, r.page_tokens
     P = S * slot_pages
-
-    access = np.zeros((L, N, K, P), dtype=np.uint8)
-    alive = np.zeros((N, P), dtype=np.uint8)
-    persist = np.zeros((N, P), dtype=np.uint8)
-    written = np.zeros((N, P), dtype=np.uint8)
-
-    def fresh_scores(shape):
-        if r.drift == "ar1":
-            sd = r.sigma / math.sqrt(1.0 - r.phi * r.phi)
-            return rng.standard_normal(shape) * sd
-        z = np.zeros(shape)
-        for _ in range(r.burn_in):
-            z = r.phi * z + _jumps(shape)
-        return z
-
-    def _jumps(shape):
-        hit = rng.random(shape) < r.jump_p
-        return np.where(hit, rng.exponential(r.jump_mean, shape), 0.0)
 
     def draw_prompt(n):
         if r.prompt_lo == r.prompt_hi:
             return np.full(n, r.prompt_lo, dtype=np.int64)
         return rng.integers(r.prompt_lo, r.prompt_hi + 1, size=n)
 
-    z = fresh_scores((L, K, S, slot_pages))
+    ctx = np.zeros((N, S), dtype=np.int64)
+    fresh = np.zeros((N, S), dtype=bool)
     prompt = draw_prompt(S)
     age = np.zeros(S, dtype=np.int64)
-    fresh = np.ones(S, dtype=bool)          # sequence started at this step
-    pages_prev = np.zeros(S, dtype=np.int64)
     ended = np.zeros(S, dtype=bool)
+    for n in range(N):
+        if n == 0:
+            fresh[n] = True
+        else:
+            fresh[n] = ended                         # finished sequences are replaced in the same slot
+            if ended.any():
+                prompt[ended] = draw_prompt(int(ended.sum()))
+                age[ended] = 0
+            age[~ended] += 1
+        ctx[n] = prompt + age + 1                    # tokens incl. the new one
+        ended = rng.random(S) < 1.0 / r.lifetime_mean if r.lifetime_mean > 0 else np.zeros(S, dtype=bool)
+    pages = -(-ctx // pt)                            # [N][S]
+    col = np.arange(slot_pages)
+    alive = col[None, None, :] < pages[:, :, None]                               # [N][S][slot_pages]
+    prev = np.concatenate([np.zeros((1, S), np.int64), pages[:-1]])
+    persist = (col[None, None, :] < np.minimum(pages, prev)[:, :, None]) & ~fresh[:, :, None]
+    written = col[None, None, :] == ((ctx - 1) // pt)[:, :, None]
+    forced = np.zeros((N, S, slot_pages), dtype=bool)
+    if r.sink_tokens:
+        forced |= col[None, None, :] < (-(-np.minimum(r.sink_tokens, ctx) // pt))[:, :, None]
+    if r.recent_tokens:
+        forced |= col[None, None, :] >= (np.maximum(ctx - r.recent_tokens, 0) // pt)[:, :, None]
+    forced &= alive
+    u8 = lambda a: a.reshape(N, P).astype(np.uint8)
+    return ctx, pages, fresh, alive, forced, u8(alive), u8(persist), u8(written)
 
+
+def _layer_group(r: Recipe, layers, slot_pages, plan, access):
+    """Importance scores and access sets of a run of consecutive layers.  Every layer draws from a
+    stream of its own, so the trace does not depend on how the layers are grouped."""
+    ctx, pages, fresh, alive, forced = plan
+    N, K, S, pt = r.N, r.K, r.slots, r.page_tokens
+    G = len(layers)
+    rngs = [_rng(r.seed, 16 + l) for l in layers]
+    sd = r.sigma / math.sqrt(1.0 - r.phi * r.phi) if r.drift == "ar1" else 0.0
+
+    def jumps(rng, shape):
+        hit = rng.random(shape) < r.jump_p
+        return np.where(hit, rng.exponential(r.jump_mean, shape), 0.0)
+
+    def fresh_scores(rng, shape):
+        if r.drift == "ar1":
+            return rng.standard_normal(shape) * sd
+        z = np.zeros(shape)
+        for _ in range(r.burn_in):
+            z = r.phi * z + jumps(rng, shape)
+        return z
+
+    z = np.stack([fresh_scores(rng, (K, S, slot_pages)) for rng in rngs])          # [G][K][S][slot_pages]
+    eps = np.empty_like(z)
     for n in range(N):
         if n > 0:
-            # finished sequences are replaced in the same slot
-            n_new = int(ended.sum())
-            fresh = ended.copy()
-            if n_new:
-                prompt[ended] = draw_prompt(n_new)
-                age[ended] = 0
-                znew = fresh_scores((L, K, n_new, slot_pages))
-                z[:, :, ended, :] = znew
-            age[~fresh] += 1
-            # importance drift of every slot that carries on
+            # importance drift of every slot; a slot whose sequence starts now gets fresh scores instead
+            for g, rng in enumerate(rngs):
+                if r.drift == "ar1":
+                    rng.standard_normal(out=eps[g])
+                else:
+                    eps[g] = jumps(rng, eps[g].shape)
+            z *= r.phi
             if r.drift == "ar1":
-                step = r.phi * z + r.sigma * rng.standard_normal(z.shape)
-            else:
-                step = r.phi * z + _jumps(z.shape)
-            z[:, :, ~fresh, :] = step[:, :, ~fresh, :]
-
-        ctx = prompt + age + 1                      # tokens incl. the new one
-        pages = -(-ctx // pt)
-        for s in range(S):
-            base = s * slot_pages
-            ap = int(pages[s])
-            a = np.zeros(slot_pages, dtype=bool)
-            a[:ap] = True
-            alive[n, base:base + ap] = 1
-            if not fresh[s]:
-                keep = int(min(ap, pages_prev[s]))
-                persist[n, base:base + keep] = 1
-            wp = int((ctx[s] - 1) // pt)
-            written[n, base + wp] = 1
-            if (ctx[s] - 1) % pt == 0 and ap > 1:
-                # a page that starts with the new token enters at the top score
-                z[:, :, s, ap - 1] = z[:, :, s, :ap - 1].max(axis=-1)
-            forced = np.zeros(slot_pages, dtype=bool)
-            if r.sink_tokens:
-                forced[: -(-min(r.sink_tokens, int(ctx[s])) // pt)] = True
-            if r.recent_tokens:
-                lo = max(int(ctx[s]) - r.recent_tokens, 0) // pt
-                forced[lo:ap] = True
-            forced &= a
-            zs = z[:, :, s, :]
-            if r.top_count is not None:
-                sel = _select_top(zs, a & ~forced, r.top_count) | forced
-            else:
-                k = int(math.ceil(r.top_frac * ap))
-                sel = _select_top(zs, a, k) | forced
-            access[:, n, :, base:base + slot_pages] = sel
-        pages_prev = pages.copy()
-        if r.lifetime_mean > 0:
-            ended = rng.random(S) < 1.0 / r.lifetime_mean
+                eps *= r.sigma
+            z += eps
+            new = np.flatnonzero(fresh[n])
+            if new.size:
+                for g, rng in enumerate(rngs):
+                    z[g][:, new, :] = fresh_scores(rng, (K, new.size, slot_pages))
+        # a page that starts with the new token enters at the top score of its sequence
+        for s in np.flatnonzero(((ctx[n] - 1) % pt == 0) & (pages[n] > 1)):
+            ap = int(pages[n, s])
+            z[:, :, s, ap - 1] = z[:, :, s, :ap - 1].max(axis=-1)
+        if r.top_count is not None:
+            sel = _select_top(z, alive[n] & ~forced[n], np.full(S, r.top_count, dtype=np.int64))
         else:
-            ended = np.zeros(S, dtype=bool)
+            sel = _select_top(z, alive[n], np.ceil(r.top_frac * pages[n]).astype(np.int64))
+        sel |= forced[n]
+        access[layers[0]:layers[0] + G, n] = sel.reshape(G, K, S * slot_pages)
+
+
+def generate(r: Recipe, threads: Optional[int] = None) -> Trace:
+    """Draw the trace of a recipe.  Layers are independent given the sequences, so runs of layers
+    are drawn by a few threads (numpy releases the interpreter lock in its loops)."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    L, N, K, S = r.L, r.N, r.K, r.slots
+    pt = r.page_tokens
+    slot_pages = r.slot_pages or -(-(r.prompt_hi + N) // pt)
+    P = S * slot_pages
+    ctx, pages, fresh, alive_b, forced, alive, persist, written = _plan(r, slot_pages)
+    access = np.zeros((L, N, K, P), dtype=np.uint8)
+    if threads is None:
+        threads = max(1, min(len(os.sched_getaffinity(0)) // 2, 8))
+    # small traces: one run of layers (the per-call overhead of numpy dominates); large: a run per thread
+    n_groups = 1 if L * K * P < 200_000 else max(1, min(L, threads))
+    bounds = [L * g // n_groups for g in range(n_groups + 1)]
+    groups = [list(range(bounds[g], bounds[g + 1])) for g in range(n_groups) if bounds[g + 1] > bounds[g]]
+    plan = (ctx, pages, fresh, alive_b, forced)
+    if len(groups) == 1:
+        _layer_group(r, groups[0], slot_pages, plan, access)
+    else:
+        with ThreadPoolExecutor(len(groups)) as ex:
+            list(ex.map(lambda ls: _layer_group(r, ls, slot_pages, plan, access), groups))
 
     page_bytes = pt * r.plane_tokens_bytes
     plane_bytes = [page_bytes // K] * K
     if r.cap_pages is not None:
         cap = int(r.cap_pages)
     else:
-        peak = int(alive.sum(axis=1).max())
+        peak = int(alive.sum(axis=1, dtype=np.int64).max())
         cap = int(math.floor(r.cap_frac * L * peak + 1e-9))
     return Trace(name=r.name, L=L, N=N, P=P, K=K, access=access, alive=alive,
                  persist=persist, written=written, plane_bytes=plane_bytes,
