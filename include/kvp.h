@@ -232,13 +232,21 @@ int kvp_set_anneal_lookahead(kvp_ctx *ctx, int proposals_per_round);
  * [C][L][N][Wd] (KVP_INIT_GIVEN), [L][N][Wd] (KVP_INIT_BROADCAST) or NULL.
  * Starting schedules must be admissible (checked, KVP_EINFEASIBLE) and are
  * masked to existing pages.  KVP_INIT_CONTINUE needs the parameters of the
- * previous call except `moves` (else KVP_EINVAL; KVP_ENOCHAINS if none). */
+ * previous call except `moves` (else KVP_EINVAL; KVP_ENOCHAINS if none).
+ * moves beyond what is left of total_moves: KVP_EINVAL, and the chains of an
+ * earlier call stay as they are.  More than 65535 chains: KVP_ESHAPE.
+ * Device memory per chain, held until the next trace or the next fresh start:
+ * the schedule (L*N*Wd*4 bytes), its step counters (L*N*16), occupancy (N*4)
+ * and the log of accepted edits since the chain's best schedule, sized for the
+ * worst case of every move accepted: total_moves * 40 bytes. */
 int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *params, const uint32_t *d_init);
 
 /* Sec. III-B (the search returns the schedule of the best latency found).
  * Best schedule over all chains: each chain's best-so-far schedule is scored
  * again in full (never the running value), the lowest cost wins, ties go to the
- * lowest chain id.  h_placement [L][N][Wd] and h_chain_costs [C] are nullable. */
+ * lowest chain id.  h_placement [L][N][Wd] and h_chain_costs [C] are nullable.
+ * Outputs are written on success only (h_placement and h_chain_costs may be
+ * partly written when a copy fails). */
 int kvp_best(kvp_ctx *ctx, double *h_cost, uint32_t *h_chain, uint32_t *h_placement,
              double *h_chain_costs);
 
@@ -251,23 +259,22 @@ int kvp_chain_stats(kvp_ctx *ctx, kvp_chain_stats_t *h_stats);
 /* Bytes per read unit of d_counters (gcd of plane_bytes); 0 without a trace. */
 uint64_t kvp_plane_unit(const kvp_ctx *ctx);
 
-/* Tuning knob: which scoring kernel kvp_score uses.  AUTO picks by row width;
- * ROWS forces the general one (a wavefront per row); LANES asks for the
- * narrow-row one (a lane per row) and falls back to ROWS where it does not
- * apply; LANES_8W is LANES with 8 instead of 4 wavefronts per workgroup.
- * Results are identical bit for bit either way. */
-enum { KVP_SCORE_AUTO = 0, KVP_SCORE_ROWS = 1, KVP_SCORE_LANES = 2, KVP_SCORE_LANES_8W = 3,
-       KVP_SCORE_DIRECT = 4, KVP_SCORE_DIRECT_8W = 5, /* lane per row, rows loaded without LDS staging */
-       KVP_SCORE_QUAD = 6, /* lane per row, four schedules per workgroup share the trace chunk */
-       KVP_SCORE_QUAD_4S = 7, /* the same with four instead of two layers in flight */
-       KVP_SCORE_WIDE = 8, /* 16 or 64 lanes per row, rows loaded straight from memory */
-       KVP_SCORE_CHUNK = 9, /* lane per row, wide rows walked in chunks of 16 words (choice for > 16 words) */
-       KVP_SCORE_ROWBLOCK = 10, /* two lanes per row, whole rows of 16..68 words staged at once, read weights as
-                                   binary digit planes (choice where it applies) */
-       KVP_SCORE_LINE = 11, /* rows of >= 32 words in 128-byte chunks scored from registers, eight lanes per
-                               chunk (choice for wide rows of several sequences) */
-       KVP_SCORE_ROWSEG = 12 /* ROWBLOCK's scheme for rows of more than 68 words, walked in equal segments of
-                                40..64 words (choice for wide rows of one sequence) */ };
+/* Tuning knob: which scoring kernel kvp_score uses.  AUTO picks by the shape of the rows and of the
+ * trace; a forced scorer that does not cover the shape is replaced by the next one that does.
+ * Results are identical bit for bit whichever runs.  Values that name no scorer: KVP_EINVAL. */
+enum { KVP_SCORE_AUTO = 0,
+       KVP_SCORE_ROWS = 1,      /* any shape: a wavefront per (layer, step) row, lanes across words */
+       KVP_SCORE_LANES = 2,     /* rows of <= 16 words: a lane per row, rows staged through LDS */
+       KVP_SCORE_QUAD = 6,      /* rows of <= 15 words, one plane, 2^k layers: a lane per row, four
+                                   schedules per workgroup share the trace chunk */
+       KVP_SCORE_CHUNK = 9,     /* rows of >= 16 words, any masks: a lane per row, rows walked in chunks of
+                                   16 words */
+       KVP_SCORE_ROWBLOCK = 10, /* one decoding sequence, rows of 16..68 words: two lanes per row, whole rows
+                                   staged at once, read weights as binary digit planes */
+       KVP_SCORE_LINE = 11,     /* rows of >= 32 words, any masks: 128-byte chunks scored from registers,
+                                   eight lanes per chunk (several sequences) */
+       KVP_SCORE_ROWSEG = 12    /* ROWBLOCK's scheme for rows of more than 68 words, walked in equal
+                                   segments of 40..64 words */ };
 int kvp_set_score_kernel(kvp_ctx *ctx, int which);
 
 /* The scorer that the last kvp_score on ctx ran (a KVP_SCORE_* value other than

@@ -17,7 +17,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libkvp.so")
+LIB_PATH = os.environ.get("KVP_LIBRARY") or os.path.join(_HERE, "libkvp.so")    # the in-tree build unless told otherwise
 
 KVP_OK, KVP_EINVAL, KVP_ENOTRACE, KVP_ENOMEM, KVP_EHIP = 0, -1, -2, -3, -4
 KVP_ESHAPE, KVP_ETRACE, KVP_ENOCHAINS, KVP_EINFEASIBLE = -5, -6, -7, -8
@@ -235,8 +235,9 @@ def kvp_chain_stats(ctx, n_chains):
     return list(arr)
 
 
-(KVP_SCORE_AUTO, KVP_SCORE_ROWS, KVP_SCORE_LANES, KVP_SCORE_LANES_8W, KVP_SCORE_DIRECT, KVP_SCORE_DIRECT_8W,
- KVP_SCORE_QUAD, KVP_SCORE_QUAD_4S, KVP_SCORE_WIDE, KVP_SCORE_CHUNK, KVP_SCORE_ROWBLOCK, KVP_SCORE_LINE, KVP_SCORE_ROWSEG) = range(13)
+KVP_SCORE_AUTO, KVP_SCORE_ROWS, KVP_SCORE_LANES, KVP_SCORE_QUAD = 0, 1, 2, 6
+KVP_SCORE_CHUNK, KVP_SCORE_ROWBLOCK, KVP_SCORE_LINE, KVP_SCORE_ROWSEG = 9, 10, 11, 12
+SCORE_KERNEL_NAMES = {1: "rows", 2: "lanes", 6: "quad", 9: "chunk", 10: "rowblock", 11: "line", 12: "rowseg"}
 
 
 def kvp_strict_excess(ctx, d_placements, S, d_excess):

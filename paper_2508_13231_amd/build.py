@@ -21,13 +21,14 @@ def sources():
     return sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every csrc/*.hip for gfx950 (in parallel) and link libkvp.so."""
+def build_library(verbose: bool = False, out: str = LIB, extra_flags=()) -> str:
+    """Compile every csrc/*.hip for gfx950 (in parallel) and link libkvp.so (or `out`, e.g. a build with
+    other -D switches to be loaded through the KVP_LIBRARY environment variable)."""
     from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
-    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"] + list(extra_flags)
     inc = ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc")]
 
     def compile_one(src):
@@ -40,12 +41,12 @@ def build_library(verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(min(8, len(sources()))) as ex:
         objs = list(ex.map(compile_one, sources()))
-    tmp = LIB + f".{os.getpid()}.tmp"
+    tmp = out + f".{os.getpid()}.tmp"
     subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
-    os.replace(tmp, LIB)
+    os.replace(tmp, out)
     for o in objs:
         os.remove(o)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -95,7 +95,12 @@ extern "C" int kvp_set_anneal_lookahead(kvp_ctx *ctx, int proposals_per_round) {
 }
 
 extern "C" int kvp_set_score_kernel(kvp_ctx *ctx, int which) {
-    if (!ctx || which < KVP_SCORE_AUTO || which > KVP_SCORE_ROWSEG) return KVP_EINVAL;
+    switch (which) {
+        case KVP_SCORE_AUTO: case KVP_SCORE_ROWS: case KVP_SCORE_LANES: case KVP_SCORE_QUAD: case KVP_SCORE_CHUNK:
+        case KVP_SCORE_ROWBLOCK: case KVP_SCORE_LINE: case KVP_SCORE_ROWSEG: break;
+        default: return KVP_EINVAL;
+    }
+    if (!ctx) return KVP_EINVAL;
     ctx->score_kernel = which;
     return KVP_OK;
 }

@@ -107,6 +107,10 @@ extern thread_local int kvp_tls_hip_line;
 // ---- device helpers ---------------------------------------------------------
 #if defined(__HIPCC__)
 
+// Load of schedule words.  A launch reads them once, while the trace words are read again by every
+// group of schedules: marked as streaming, they leave the trace its place in the L2.
+#define KVP_LOAD_X(ptr) __builtin_nontemporal_load(ptr)
+
 // Placement of workgroups that each take one (tile of token steps, group of schedules): the
 // hardware hands consecutive workgroups to the eight XCDs in turn (blockIdx & 7), each XCD with an
 // L2 of its own.  The pairs, tile-major, are cut into eight equal runs, one per XCD, and the

@@ -811,7 +811,8 @@ static int launch_log_xor(kvp_ctx *ctx, uint32_t chain0, uint32_t nchains) {
 extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32_t *d_init) {
     if (!ctx || !p) return KVP_EINVAL;
     if (!ctx->has_trace) return KVP_ENOTRACE;
-    if (p->n_chains == 0 || p->n_chains > 65535u * 16u || p->n_levels == 0 || p->max_len < 1 ||
+    if (p->n_chains > 65535u) return KVP_ESHAPE;             // one grid row per chain when the best schedules are rebuilt
+    if (p->n_chains == 0 || p->n_levels == 0 || p->max_len < 1 ||
         p->max_len > KVP_MAX_LEN || !(p->p0 > 0.0 && p->p0 < 1.0) || !(p->alpha > 0.0 && p->alpha <= 1.0) ||
         p->init_mode > KVP_INIT_CONTINUE || p->total_moves == 0)
         return KVP_EINVAL;
@@ -829,18 +830,25 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
     if (p->init_mode == KVP_INIT_CONTINUE) {
         if (!ctx->has_chains) return KVP_ENOCHAINS;
         if (!same_schedule(*p, ctx->sa)) return KVP_EINVAL;
+        if (ctx->moves_done + p->moves > p->total_moves) return KVP_EINVAL;
     } else {
+        if (p->moves > p->total_moves) return KVP_EINVAL;            // before the previous chains are given up
         KVP_HIP(hipStreamSynchronize(ctx->stream));
         kvp_free_chains(ctx);
         ctx->log_cap = p->total_moves;
-        KVP_HIP(hipMalloc((void **)&ctx->d_X, per * C * 4));
-        KVP_HIP(hipMalloc((void **)&ctx->d_cnt, rows * C * 16));
-        KVP_HIP(hipMalloc((void **)&ctx->d_occ, (size_t)q.N * C * 4));
-        KVP_HIP(hipMalloc((void **)&ctx->d_state, sizeof(ChainState) * C));
-        KVP_HIP(hipMalloc((void **)&ctx->d_log, (size_t)ctx->log_cap * C * LOG_WORDS * 4));
-        KVP_HIP(hipMalloc((void **)&ctx->d_cost, sizeof(double) * C));
-        KVP_HIP(hipMalloc((void **)&ctx->d_excess, 4 * (size_t)C));
-        KVP_HIP(hipMalloc((void **)&ctx->d_argmin, 16));
+        const struct { void **p; size_t bytes; } want[] = {
+            {(void **)&ctx->d_X, per * C * 4}, {(void **)&ctx->d_cnt, rows * C * 16}, {(void **)&ctx->d_occ, (size_t)q.N * C * 4},
+            {(void **)&ctx->d_state, sizeof(ChainState) * C}, {(void **)&ctx->d_log, (size_t)ctx->log_cap * C * LOG_WORDS * 4},
+            {(void **)&ctx->d_cost, sizeof(double) * C}, {(void **)&ctx->d_excess, 4 * (size_t)C}, {(void **)&ctx->d_argmin, 16}};
+        for (const auto &w : want) {
+            const hipError_t e = hipMalloc(w.p, w.bytes);
+            if (e != hipSuccess) {
+                kvp_tls_hip_error = (int)e; kvp_tls_hip_line = __LINE__;
+                (void)hipGetLastError();
+                kvp_free_chains(ctx);                                    // nothing half-allocated stays behind
+                return e == hipErrorOutOfMemory ? KVP_ENOMEM : KVP_EHIP;
+            }
+        }
         if (p->init_mode == KVP_INIT_EMPTY) {
             KVP_HIP(hipMemsetAsync(ctx->d_X, 0, per * C * 4, ctx->stream));
         } else {
@@ -865,8 +873,6 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
         ctx->moves_done = 0;
         ctx->has_chains = true;
     }
-    if (ctx->moves_done + p->moves > p->total_moves) return KVP_EINVAL;
-
     SAParams sp;
     sp.seed_lo = (uint32_t)p->seed; sp.seed_hi = (uint32_t)(p->seed >> 32);
     sp.th0 = (uint64_t)(p->op_prob[0] * 4294967296.0);
@@ -1034,7 +1040,7 @@ extern "C" int kvp_best(kvp_ctx *ctx, double *h_cost, uint32_t *h_chain, uint32_
         rc = KVP_EHIP;
     const int rc2 = launch_log_xor(ctx, 0, C);                             // back to the current schedules
     if (hipStreamSynchronize(ctx->stream) != hipSuccess && !rc) rc = KVP_EHIP;
-    *h_chain = win;
+    if (!rc && !rc2) *h_chain = win;
     return rc ? rc : rc2;
 }
 

@@ -186,8 +186,6 @@ int kvp_score_tile_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t 
                           uint32_t *counters, uint32_t *occ);
 int kvp_score_chunk_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
                            uint32_t *counters, uint32_t *occ);
-int kvp_score_wide_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
-                          uint32_t *counters, uint32_t *occ);
 int kvp_score_quad_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
                           uint32_t *counters, uint32_t *occ);
 int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
@@ -215,11 +213,9 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
             {KVP_SCORE_QUAD, kvp_score_quad_launch, true},     {KVP_SCORE_LANES, kvp_score_tile_launch, true},
             {KVP_SCORE_ROWBLOCK, kvp_score_rowblock_launch, false}, {KVP_SCORE_ROWSEG, kvp_score_rowseg_launch, false},
             {KVP_SCORE_LINE, kvp_score_line_launch, false},
-            {KVP_SCORE_CHUNK, kvp_score_chunk_launch, false},  {KVP_SCORE_WIDE, kvp_score_wide_launch, false},
+            {KVP_SCORE_CHUNK, kvp_score_chunk_launch, false},
         };
-        // variants of one launcher share its entry: which variant runs is read from ctx->score_kernel there
-        const int family = forced == KVP_SCORE_QUAD_4S ? KVP_SCORE_QUAD
-                           : (forced >= KVP_SCORE_LANES && forced <= KVP_SCORE_DIRECT_8W) ? KVP_SCORE_LANES : forced;
+        const int family = forced;
         rc = 1;
         for (const auto &o : order)                            // the forced scorer, wherever it is in the order
             if (rc == 1 && o.id == family) rc = o.fn(ctx, d_placements, S, tiles64, nb_total, d_counters, d_occ);

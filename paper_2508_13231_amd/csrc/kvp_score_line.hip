@@ -94,7 +94,7 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     const char *Xs = (const char *)(X + (size_t)sc * sched_words);
     auto x_base = [&](uint32_t i, uint32_t c) { return 4 * (layer_of(i) * N * Wd + min(c * LCW, Wd - LCW) + 4 * p); };
     auto issue_x = [&](int j, uint32_t base, int last_step) __attribute__((always_inline)) {
-        x[j] = *(const l4u *)(Xs + (base + (uint32_t)clamp_i32(step0 + j, 0, last_step) * (4 * Wd)));
+        x[j] = KVP_LOAD_X((const l4u *)(Xs + (base + (uint32_t)clamp_i32(step0 + j, 0, last_step) * (4 * Wd))));
     };
     l4u tr[2 * NT];
     const uint32_t tb0 = 4 * (trow0 * Wd + 4 * tpart), tb1 = 4 * (trow1 * Wd + 4 * tpart);   // byte offsets in V, Pm, Wm

@@ -207,20 +207,15 @@ int launch_quad(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uin
     const uint64_t nwg = (uint64_t)((S + QUAD - 1) / QUAD) * tiles;
     if (nwg > 0x7FFFFFFFull) return 1;
     dim3 grid((uint32_t)nwg), block(QUAD * 64);
-    const bool pf = WD > 1 && ctx->prefix_full, w1 = q.single_write != 0, deep = q.L % 4 == 0 && ctx->score_kernel == KVP_SCORE_QUAD_4S;
+    const bool pf = WD > 1 && ctx->prefix_full, w1 = q.single_write != 0;
 #define KVP_GO(WW, PP, NN)                                                                             \
     score_quad_kernel<WD, WW, PP, NN><<<grid, block, lds, ctx->stream>>>(q, X, S, tiles, nb_total, log2L, \
                                                                         ctx->d_blocksum, ctx->d_tileflag, counters, occ)
-    if (deep) {
-        if (w1 && pf) KVP_GO(true, true, 4); else if (w1) KVP_GO(true, false, 4);
-        else if (pf) KVP_GO(false, true, 4); else KVP_GO(false, false, 4);
-    } else {
-        if (w1 && pf) KVP_GO(true, true, 2); else if (w1) KVP_GO(true, false, 2);
-        else if (pf) KVP_GO(false, true, 2); else KVP_GO(false, false, 2);
-    }
+    if (w1 && pf) KVP_GO(true, true, 2); else if (w1) KVP_GO(true, false, 2);
+    else if (pf) KVP_GO(false, true, 2); else KVP_GO(false, false, 2);
 #undef KVP_GO
     KVP_HIP(hipGetLastError());
-    ctx->last_kernel = deep ? KVP_SCORE_QUAD_4S : KVP_SCORE_QUAD;
+    ctx->last_kernel = KVP_SCORE_QUAD;
     return KVP_OK;
 }
 

@@ -182,11 +182,11 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
         const int before = 4 * ((int)((l * N + n0 + RR * p) * Wd) - (int)Wd);   // byte of the step before the pass; < 0 at step 0
         if (before >= 0 && !edge_tile) {
 #pragma unroll
-            for (int jv = 0; jv < XV; jv++) st.x[jv] = *(const r4u *)(Xs + ((uint32_t)before + xrel[jv]));
+            for (int jv = 0; jv < XV; jv++) st.x[jv] = KVP_LOAD_X((const r4u *)(Xs + ((uint32_t)before + xrel[jv])));
         } else {
             const int hi = 4 * ((int)sched_words - 4);
 #pragma unroll
-            for (int jv = 0; jv < XV; jv++) st.x[jv] = *(const r4u *)(Xs + (uint32_t)min(max(before + (int)xrel[jv], 0), hi));
+            for (int jv = 0; jv < XV; jv++) st.x[jv] = KVP_LOAD_X((const r4u *)(Xs + (uint32_t)min(max(before + (int)xrel[jv], 0), hi)));
         }
     };
     auto issue_t = [&](uint32_t p, uint32_t l) __attribute__((always_inline)) {

@@ -204,193 +204,11 @@ int launch_wd_nw(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, ui
     return KVP_OK;
 }
 
-// ---- variant without LDS staging: every lane loads its own row from memory -------
-//
-// Lane i reads the WD words of row n0+i straight into registers (the 64 rows of
-// a wavefront are contiguous, so the wavefront still touches each cache line
-// once from L2; the vector L1 merges the lanes).  The previous step's row is
-// the neighbouring lane's row, moved over with one DPP wave shift per word;
-// only lane 0 loads its predecessor from memory.  The rows of the next layer are
-// requested before the current ones are scored.
-typedef uint32_t u32x4a __attribute__((ext_vector_type(4), aligned(4)));
-typedef uint32_t u32x2a __attribute__((ext_vector_type(2), aligned(4)));
-
-template <int WD>
-__device__ __forceinline__ void load_row(const uint32_t *__restrict__ p, uint32_t (&r)[WD]) {
-    int w = 0;
-#pragma unroll
-    for (; w + 4 <= WD; w += 4) {
-        const u32x4a v = *(const u32x4a *)(p + w);
-        r[w] = v.x; r[w + 1] = v.y; r[w + 2] = v.z; r[w + 3] = v.w;
-    }
-    if (w + 2 <= WD) {
-        const u32x2a v = *(const u32x2a *)(p + w);
-        r[w] = v.x; r[w + 1] = v.y;
-        w += 2;
-    }
-    if (w < WD) r[w] = p[w];
-}
-
-// lane i receives v of lane i-1; lane 0 keeps `first`
-__device__ __forceinline__ uint32_t from_lane_below(uint32_t v, uint32_t first) {
-    return (uint32_t)__builtin_amdgcn_update_dpp((int)first, (int)v, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);
-}
-
-template <int WD, int NW, bool W1>
-__global__ __launch_bounds__(NW * 64) void score_lane_direct_kernel(
-    DevProblem q, const uint32_t *__restrict__ X, uint32_t tiles, uint32_t nb_total,
-    double *__restrict__ blocksum, uint32_t *__restrict__ tileflag, uint32_t *__restrict__ counters,
-    uint32_t *__restrict__ occ_out) {
-    extern __shared__ double smem_d[];
-    constexpr int WREG = W1 ? 1 : WD;
-    const uint32_t L = q.L, N = q.N;
-    const uint32_t s = blockIdx.x, tile = blockIdx.y;
-    const uint32_t n0 = tile * TILE_N;
-    const uint32_t rows = min((uint32_t)TILE_N, N - n0);
-    const int lane = lane_id();
-    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / KVP_WAVE));
-
-    double *tb = smem_d;                                          // [L][TB_STRIDE]
-    uint32_t *occ_l = (uint32_t *)(tb + (size_t)L * TB_STRIDE);   // [64]
-    uint32_t *misc = occ_l + TILE_N;
-    if (threadIdx.x < TILE_N) occ_l[threadIdx.x] = 0;
-    if (threadIdx.x < 4) misc[threadIdx.x] = 0;
-    __syncthreads();
-
-    const bool active = (uint32_t)lane < rows;
-    const uint32_t n = active ? n0 + lane : n0;                   // idle lanes shadow row n0 (in bounds)
-    uint32_t vv[WD], pm[WD], wm[WREG];
-    load_row<WD>(q.V + (size_t)n * WD, vv);
-    load_row<WD>(q.Pm + (size_t)n * WD, pm);
-    uint32_t wsel = 0;
-    if (W1) {
-        wsel = q.wsel[n];
-        wm[0] = q.Wm[(size_t)n * WD + wsel];
-    } else {
-#pragma unroll
-        for (int w = 0; w < WREG; w++) wm[w] = q.Wm[(size_t)n * WD + w];
-    }
-    const uint32_t wr_n = q.wr[n];
-    // lane 0's predecessor row: the last row of the previous tile (none at step 0: persist is empty there)
-    const uint32_t nprev0 = n0 > 0 ? n0 - 1 : 0;
-    uint32_t occ_acc = 0, fl_acc = 0;
-
-    uint32_t cur[WD], ar[WD], hal[WD], ncur[WD], nar[WD], nhal[WD];
-#pragma unroll
-    for (int w = 0; w < WD; w++) { ncur[w] = 0; nar[w] = 0; nhal[w] = 0; }
-    uint32_t acc_n = 0, nacc = 0;
-    auto rowp = [&](uint32_t l, uint32_t nn) { return X + ((size_t)(s * (size_t)L + l) * N + nn) * WD; };
-    if (wave < L) {
-        load_row<WD>(rowp(wave, n), ncur);
-        load_row<WD>(q.A + ((size_t)wave * N + n) * WD, nar);
-        if (lane == 0) load_row<WD>(rowp(wave, nprev0), nhal);
-        nacc = q.acc[(size_t)wave * N + n];
-    }
-    for (uint32_t l = wave; l < L; l += NW) {
-#pragma unroll
-        for (int w = 0; w < WD; w++) { cur[w] = ncur[w]; ar[w] = nar[w]; hal[w] = nhal[w]; }
-        acc_n = nacc;
-        if (l + NW < L) {                                        // next layer's rows are in flight meanwhile
-            load_row<WD>(rowp(l + NW, n), ncur);
-            load_row<WD>(q.A + ((size_t)(l + NW) * N + n) * WD, nar);
-            if (lane == 0) load_row<WD>(rowp(l + NW, nprev0), nhal);
-            nacc = q.acc[(size_t)(l + NW) * N + n];
-        }
-        uint32_t hr = 0, hw = 0, mi = 0, mg = 0, oc = 0;
-#pragma unroll
-        for (int w = 0; w < WD; w++) {
-            const uint32_t raw = cur[w];
-            const uint32_t xp = from_lane_below(raw, hal[w]);
-            const uint32_t x = raw & vv[w];
-            fl_acc |= raw & ~vv[w];
-            hr += __popc(x & ar[w]);
-            if (!W1) hw += __popc(x & wm[w]);
-            oc += __popc(x);
-            const uint32_t d = (x ^ xp) & pm[w];
-            mi += __popc(d & x);
-            mg += __popc(d);
-        }
-        if (W1) {
-            uint32_t xw = cur[0];
-#pragma unroll
-            for (int w = 1; w < WD; w++) xw = wsel == (uint32_t)w ? cur[w] : xw;
-            hw = __popc(xw & wm[0]);
-        }
-        if (active) {
-            const uint32_t mo = mg - mi;
-            const size_t row = (size_t)l * N + n;
-            tb[(size_t)l * TB_STRIDE + lane] = step_time(q, hr, hw, mi, mo, acc_n, wr_n);
-            occ_acc += oc;
-            if (counters) *(uint4 *)(counters + ((size_t)s * L * N + row) * 4) = make_uint4(hr, hw, mi, mo);
-        } else {
-            fl_acc = 0;
-        }
-    }
-    if (active && occ_acc) atomicAdd(&occ_l[lane], occ_acc);
-    if (fl_acc) atomicOr(&misc[0], 1u);
-    __syncthreads();
-
-    const uint32_t nvalid = rows * L;
-    const uint32_t nblk = (nvalid + 63) / 64;
-    uint32_t g = wave * 64 + lane;
-    uint32_t r = g / L, l = g - r * L;
-    const uint32_t dr = (NW * 64) / L, dl = (NW * 64) - dr * L;
-    for (uint32_t b = wave; b < nblk; b += NW) {
-        double t = g < nvalid ? tb[(size_t)l * TB_STRIDE + r] : 0.0;
-        t = wave_tree_sum_f64(t);
-        if (lane == 0) blocksum[(size_t)s * nb_total + (size_t)tile * L + b] = t;
-        g += NW * 64; r += dr; l += dl;
-        if (l >= L) { l -= L; r++; }
-    }
-    if (threadIdx.x < TILE_N) {
-        uint32_t ex = 0;
-        if (threadIdx.x < rows) {
-            const uint32_t o = occ_l[threadIdx.x];
-            if (occ_out) occ_out[(size_t)s * N + n0 + threadIdx.x] = o;
-            ex = o > q.cap ? o - q.cap : 0;
-        }
-        ex = wave_max_u32(ex);
-        if (threadIdx.x == 0) tileflag[(size_t)s * tiles + tile] = ex | (misc[0] ? 0x80000000u : 0u);
-    }
-}
-
-template <int WD, int NW>
-int launch_direct(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
-                  uint32_t *counters, uint32_t *occ) {
-    const DevProblem &q = ctx->dp;
-    if (!(q.K == 1 && q.wt[0] == 1)) return 1;
-    const size_t lds = (size_t)q.L * TB_STRIDE * 8 + (TILE_N + 4) * 4;
-    if (lds > 64 * 1024) return 1;
-    dim3 grid(S, tiles), block(NW * 64);
-    if (q.single_write)
-        score_lane_direct_kernel<WD, NW, true><<<grid, block, lds, ctx->stream>>>(
-            q, X, tiles, nb_total, ctx->d_blocksum, ctx->d_tileflag, counters, occ);
-    else
-        score_lane_direct_kernel<WD, NW, false><<<grid, block, lds, ctx->stream>>>(
-            q, X, tiles, nb_total, ctx->d_blocksum, ctx->d_tileflag, counters, occ);
-    KVP_HIP(hipGetLastError());
-    ctx->last_kernel = NW == 8 ? KVP_SCORE_DIRECT_8W : KVP_SCORE_DIRECT;
-    return KVP_OK;
-}
-
 template <int WD>
 int launch_wd(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
               uint32_t *counters, uint32_t *occ) {
-    // the variant asked for, if any: LDS-staged (LANES) or not (DIRECT), 4 or 8 wavefronts per workgroup
-    const int f = ctx->score_kernel;
-    const bool direct = f != KVP_SCORE_LANES && f != KVP_SCORE_LANES_8W;
-    const int waves = (f == KVP_SCORE_LANES_8W || f == KVP_SCORE_DIRECT_8W) ? 8 : 4;
-    if (direct) {
-        int rd = waves == 8 ? launch_direct<WD, 8>(ctx, X, S, tiles, nb_total, counters, occ)
-                                      : launch_direct<WD, 4>(ctx, X, S, tiles, nb_total, counters, occ);
-        if (rd != 1) return rd;
-    }
-    // more wavefronts per workgroup only when there are layers enough to keep each busy for long
-    int rc = waves == 8 ? launch_wd_nw<WD, 8>(ctx, X, S, tiles, nb_total, counters, occ)
-                                  : launch_wd_nw<WD, 4>(ctx, X, S, tiles, nb_total, counters, occ);
-    bool eight = waves == 8;
-    if (rc == 1 && eight) { rc = launch_wd_nw<WD, 4>(ctx, X, S, tiles, nb_total, counters, occ); eight = false; }
-    if (rc == KVP_OK) ctx->last_kernel = eight ? KVP_SCORE_LANES_8W : KVP_SCORE_LANES;
+    const int rc = launch_wd_nw<WD, 4>(ctx, X, S, tiles, nb_total, counters, occ);
+    if (rc == KVP_OK) ctx->last_kernel = KVP_SCORE_LANES;
     return rc;
 }
 
