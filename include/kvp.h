@@ -273,8 +273,10 @@ enum { KVP_SCORE_AUTO = 0,
                                    staged at once, read weights as binary digit planes */
        KVP_SCORE_LINE = 11,     /* rows of >= 32 words, any masks: 128-byte chunks scored from registers,
                                    eight lanes per chunk (several sequences) */
-       KVP_SCORE_ROWSEG = 12    /* ROWBLOCK's scheme for rows of more than 68 words, walked in equal
-                                   segments of 40..64 words */ };
+       KVP_SCORE_ROWSEG = 12,   /* ROWBLOCK's scheme for rows of more than 68 words, walked in equal
+                                   segments of 40..64 words */
+       KVP_SCORE_ROWLANE = 13   /* one decoding sequence, rows of 29..36 words, one or two dense digit planes
+                                   (further ones almost empty): a lane per step, a layer of a tile per pass */ };
 int kvp_set_score_kernel(kvp_ctx *ctx, int which);
 
 /* The scorer that the last kvp_score on ctx ran (a KVP_SCORE_* value other than

@@ -236,8 +236,8 @@ def kvp_chain_stats(ctx, n_chains):
 
 
 KVP_SCORE_AUTO, KVP_SCORE_ROWS, KVP_SCORE_LANES, KVP_SCORE_QUAD = 0, 1, 2, 6
-KVP_SCORE_CHUNK, KVP_SCORE_ROWBLOCK, KVP_SCORE_LINE, KVP_SCORE_ROWSEG = 9, 10, 11, 12
-SCORE_KERNEL_NAMES = {1: "rows", 2: "lanes", 6: "quad", 9: "chunk", 10: "rowblock", 11: "line", 12: "rowseg"}
+KVP_SCORE_CHUNK, KVP_SCORE_ROWBLOCK, KVP_SCORE_LINE, KVP_SCORE_ROWSEG, KVP_SCORE_ROWLANE = 9, 10, 11, 12, 13
+SCORE_KERNEL_NAMES = {1: "rows", 2: "lanes", 6: "quad", 9: "chunk", 10: "rowblock", 11: "line", 12: "rowseg", 13: "rowlane"}
 
 
 def kvp_strict_excess(ctx, d_placements, S, d_excess):

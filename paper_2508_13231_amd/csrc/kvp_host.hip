@@ -70,6 +70,7 @@ extern "C" void kvp_destroy(kvp_ctx *ctx) {
     free_dev(ctx->d_trace); free_dev(ctx->d_blocksum); free_dev(ctx->d_tileflag);
     free_dev(ctx->d_cnt_tmp); free_dev(ctx->d_occ_tmp); free_dev(ctx->d_tglobal); free_dev(ctx->d_chunkfull);
     free_dev(ctx->d_aw); free_dev(ctx->d_empty32); free_dev(ctx->d_policy_work); free_dev(ctx->d_policy_x);
+    free_dev(ctx->d_tl); free_dev(ctx->d_sparse);
     delete ctx;
 }
 
@@ -97,7 +98,7 @@ extern "C" int kvp_set_anneal_lookahead(kvp_ctx *ctx, int proposals_per_round) {
 extern "C" int kvp_set_score_kernel(kvp_ctx *ctx, int which) {
     switch (which) {
         case KVP_SCORE_AUTO: case KVP_SCORE_ROWS: case KVP_SCORE_LANES: case KVP_SCORE_QUAD: case KVP_SCORE_CHUNK:
-        case KVP_SCORE_ROWBLOCK: case KVP_SCORE_LINE: case KVP_SCORE_ROWSEG: break;
+        case KVP_SCORE_ROWBLOCK: case KVP_SCORE_LINE: case KVP_SCORE_ROWSEG: case KVP_SCORE_ROWLANE: break;
         default: return KVP_EINVAL;
     }
     if (!ctx) return KVP_EINVAL;
@@ -164,6 +165,8 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     free_dev(ctx->d_trace); ctx->d_trace = nullptr; ctx->has_trace = false;
     free_dev(ctx->d_chunkfull); ctx->d_chunkfull = nullptr; ctx->cf_words = 0;
     free_dev(ctx->d_aw); ctx->d_aw = nullptr; ctx->aw = nullptr; ctx->kb = 0;
+    free_dev(ctx->d_tl); ctx->d_tl = nullptr; ctx->kd = 0;
+    free_dev(ctx->d_sparse); ctx->d_sparse = nullptr;
     free_dev(ctx->d_empty32); ctx->d_empty32 = nullptr;
 
     const size_t nA = (size_t)(L * N * K * Wd), nM = (size_t)(N * Wd);

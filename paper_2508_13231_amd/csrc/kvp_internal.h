@@ -8,6 +8,7 @@
 #include "kvp.h"
 
 #define KVP_WAVE 64
+#define KVP_SPARSE_CAP 64   // list entries per (layer, 32 token steps): one per lane of a wavefront
 
 // Problem as the kernels see it.  Passed by value.
 struct DevProblem {
@@ -63,6 +64,13 @@ struct kvp_ctx {
     const uint32_t *aw = nullptr;        // [L][N][kb][Wd] binary digits of the pages' read weights (may alias A)
     uint32_t kb = 0;                     // digit planes, 0 if the weights need more than five
     uint32_t *d_aw = nullptr;            // owned storage of aw when it is not A
+    // For the row-per-lane scorer (rows of 29..36 words of one decoding sequence): the low `kd` digit planes
+    // per (layer, tile of 64 steps) with a row stride of 36 words, [L][tiles][kd][64][36], and, when there
+    // are more digit planes than kd, the non-zero words of those as a list per (layer, block of 32 steps):
+    // [L][ceil(N/32)][KVP_SPARSE_CAP] entries {mask, row in the block | word << 8 | digit << 16 | 1 << 31}
+    // (0: unused slot).  d_tl is null where that scorer does not apply.
+    uint32_t *d_tl = nullptr; uint32_t kd = 0;
+    uint2 *d_sparse = nullptr;
     uint32_t *d_trace = nullptr;         // one allocation: A, V, Pm, Wm, acc, wr
     // scoring scratch
     double *d_blocksum = nullptr;  size_t blocksum_cap = 0;   // [S][nb]
@@ -237,4 +245,5 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
 int kvp_ensure(kvp_ctx *ctx, void **p, size_t *cap, size_t bytes);
 int kvp_static_scratch_init(int device);     // kvp_score.hip: resolves the device address of the static scratch
 int kvp_bitslice_build(kvp_ctx *ctx);
+int kvp_rowlane_build(kvp_ctx *ctx);          // kvp_score_rowlane.hip: called at the end of kvp_bitslice_build
 void kvp_free_chains(kvp_ctx *ctx);

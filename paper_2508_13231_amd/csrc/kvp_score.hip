@@ -190,6 +190,8 @@ int kvp_score_quad_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t 
                           uint32_t *counters, uint32_t *occ);
 int kvp_score_rowblock_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
                               uint32_t *counters, uint32_t *occ);
+int kvp_score_rowlane_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+                             uint32_t *counters, uint32_t *occ);
 int kvp_score_rowseg_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
                             uint32_t *counters, uint32_t *occ);
 int kvp_score_line_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
@@ -211,6 +213,7 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
         // the order AUTO tries them in: narrow rows first, then by how close each comes to the HBM rate
         struct { int id; launch_fn fn; bool narrow; } const order[] = {
             {KVP_SCORE_QUAD, kvp_score_quad_launch, true},     {KVP_SCORE_LANES, kvp_score_tile_launch, true},
+            {KVP_SCORE_ROWLANE, kvp_score_rowlane_launch, false},
             {KVP_SCORE_ROWBLOCK, kvp_score_rowblock_launch, false}, {KVP_SCORE_ROWSEG, kvp_score_rowseg_launch, false},
             {KVP_SCORE_LINE, kvp_score_line_launch, false},
             {KVP_SCORE_CHUNK, kvp_score_chunk_launch, false},

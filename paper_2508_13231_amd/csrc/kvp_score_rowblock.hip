@@ -377,7 +377,7 @@ int kvp_bitslice_build(kvp_ctx *ctx) {
     uint32_t kb = 0;
     while ((sum >> kb) != 0) kb++;
     if (kb > 5) return KVP_OK;
-    if (q.K == 1 && q.wt[0] == 1) { ctx->aw = q.A; ctx->kb = 1; return KVP_OK; }
+    if (q.K == 1 && q.wt[0] == 1) { ctx->aw = q.A; ctx->kb = 1; return kvp_rowlane_build(ctx); }
     const size_t words = (size_t)q.L * q.N * kb * q.Wd;
     KVP_HIP(hipMalloc((void **)&ctx->d_aw, words * 4));
     const size_t cells = (size_t)q.L * q.N * q.Wd;
@@ -387,7 +387,7 @@ int kvp_bitslice_build(kvp_ctx *ctx) {
     ctx->aw = ctx->d_aw; ctx->kb = kb;
     q.pl = ctx->d_aw; q.pn = kb;
     for (uint32_t k = 0; k < KVP_MAX_PLANES; k++) q.pw[k] = k < kb ? 1u << k : 0;
-    return KVP_OK;
+    return kvp_rowlane_build(ctx);
 }
 
 // Returns KVP_OK if launched, 1 if this kernel does not cover the shape, <0 on error.

@@ -43,4 +43,4 @@ def test_enumerators_match_the_header():
         for name, value in re.findall(r"\b(KVP_[A-Z0-9_]+)\s*=\s*(-?\d+)", body):
             assert getattr(K, name) == int(value), name
             seen += 1
-    assert seen >= 25 and K.KVP_SCORE_ROWSEG == 12
+    assert seen >= 25 and K.KVP_SCORE_ROWLANE == 13

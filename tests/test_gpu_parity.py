@@ -78,6 +78,13 @@ def _cases():
     yield "dec-L48", _decode(39, L=48, N=65, words=17, page_tokens=4)              # 16 * 3
     yield "dec-L96", _decode(40, L=96, N=64, words=16, page_tokens=4)              # 32 * 3: more blocks than lanes
     yield "dec-L112", _decode(41, L=112, N=40, words=20, page_tokens=4, K=2)       # 16 * 7, one short tile
+    # rows of 29 to 36 words of one sequence: a lane per step, a layer of a tile per pass
+    yield "lane-w33-L80-k8", _decode(60, L=80, N=150, words=32, page_tokens=8, K=8, top_frac=0.04, forced=False)   # upper digit planes as lists
+    yield "lane-w33-k8-dense", _decode(60, L=80, N=150, words=32, page_tokens=8, K=8, top_frac=0.04)   # ... too many for the lists: sinks and recent pages read by all heads
+    yield "lane-w36-L16", _decode(61, L=16, N=129, words=34, page_tokens=4)        # 36 words exactly, three tiles, the last of one step
+    yield "lane-w29-L3-k2", _decode(62, L=3, N=70, words=28, page_tokens=2, K=2, top_frac=0.3)        # two dense planes, latencies through memory
+    yield "lane-w31-L24-k5", _decode(63, L=24, N=100, words=29, page_tokens=1, K=5, top_frac=0.03, forced=False)   # 8 * 3; 100 new pages: the live end moves
+    yield "lane-w30-L40", _decode(64, L=40, N=64, words=29, page_tokens=16)       # 8 * 5, one plane, one whole tile
 
 
 def _tokens(seed, L, N, prompt):
@@ -87,12 +94,13 @@ def _tokens(seed, L, N, prompt):
                            sink_tokens=4, recent_tokens=8, cap_frac=0.3, seed=seed))
 
 
-def _decode(seed, L, N, words, page_tokens, K=1, plane_bytes=None):
+def _decode(seed, L, N, words, page_tokens, K=1, plane_bytes=None, top_frac=0.2, forced=True):
     """Decode of one sequence whose prompt fills `words` mask words exactly."""
     from workloads.traces import Recipe, generate
     prompt = words * 32 * page_tokens
     tr = generate(Recipe("dec", L=L, N=N, page_tokens=page_tokens, prompt_lo=prompt, prompt_hi=prompt, K=K,
-                         top_frac=0.2, sink_tokens=4, recent_tokens=8, cap_frac=0.3, seed=seed))
+                         top_frac=top_frac, sink_tokens=4 if forced else 0, recent_tokens=8 if forced else 0, cap_frac=0.3,
+                         seed=seed))
     if plane_bytes is not None:
         tr.plane_bytes = list(plane_bytes)
     return tr
@@ -109,8 +117,10 @@ NATIVE = {
     "lanes": {"tiny", "table1", "rand-odd", "rand-tiles", "gqa70b/16", "gqa70b/4", "rand-512", "tok-p16"},
     "quad": {"llama8b/4", "rand-L16", "rand-L64", "rand-L2"},
     "rowseg": {"dec-w70", "dec-w128", "dec-w130-k3", "dec-w200", "dec-w80-tail6", "dec-long-w70", "dec-grow-w93"},
+    "rowlane": {"lane-w33-L80-k8", "lane-w36-L16", "lane-w29-L3-k2", "lane-w31-L24-k5", "lane-w30-L40", "longctx/2",
+                "dec-long-w20"},
 }
-KERNEL_ID = {"auto": 0, "rows": 1, "lanes": 2, "quad": 6, "chunk": 9, "rowblock": 10, "line": 11, "rowseg": 12}
+KERNEL_ID = {"auto": 0, "rows": 1, "lanes": 2, "quad": 6, "chunk": 9, "rowblock": 10, "line": 11, "rowseg": 12, "rowlane": 13}
 KERNEL_NAME = {v: k for k, v in KERNEL_ID.items()}
 # what AUTO picks on each case, by the library's rules: rows of up to 16 words go to quad (one plane of weight 1
 # and 2, 4, ... 64 layers) or else lanes; wider rows of one decoding sequence to rowblock (up to 68 words) or
@@ -119,20 +129,23 @@ AUTO_PICK = {
     "tiny": "lanes", "table1": "quad", "llama8b/4": "quad", "longctx/8": "quad", "serving/16": "quad", "gqa70b/16": "lanes",
     "rand-odd": "lanes", "rand-wide": "line", "rand-weights": "lanes", "rand-fastdram": "quad", "one-step": "lanes",
     "rand-tiles": "lanes", "rand-512": "lanes", "rand-L16": "quad", "rand-L64": "quad", "rand-L2": "quad", "rand-w40": "line",
-    "rand-w300": "line", "rand-w301": "line", "longctx/4": "rowblock", "longctx/2": "rowblock", "gqa70b/4": "lanes",
+    "rand-w300": "line", "rand-w301": "line", "longctx/4": "rowblock", "longctx/2": "rowlane", "gqa70b/4": "lanes",
     "rand-w16": "lanes", "dec-w21-L3": "rowblock", "dec-w38-k3": "rowblock", "dec-w68-k2": "rowblock", "dec-w16": "lanes",
     "dec-w16-L30": "lanes", "dec-w24-tail": "rowblock", "gqa70b/2": "rowblock", "tok-p16": "lanes", "tok-p4-w20": "rowblock",
     "tok-p16-w17": "rowblock", "dec-w70": "rowseg", "dec-w128": "rowseg", "dec-w130-k3": "rowseg", "dec-w200": "rowseg",
-    "dec-w80-tail6": "rowseg", "dec-long-w20": "rowblock", "dec-long-w70": "rowseg", "dec-grow-w93": "rowseg",
-    "dec-L80-k8": "rowblock", "dec-L24": "rowblock", "dec-L48": "rowblock", "dec-L96": "rowblock", "dec-L112": "rowblock"}
+    "dec-w80-tail6": "rowseg", "dec-long-w20": "rowlane", "dec-long-w70": "rowseg", "dec-grow-w93": "rowseg",
+    "dec-L80-k8": "rowblock", "dec-L24": "rowblock", "dec-L48": "rowblock", "dec-L96": "rowblock", "dec-L112": "rowblock",
+    "lane-w33-L80-k8": "rowlane", "lane-w36-L16": "rowlane", "lane-w29-L3-k2": "rowlane", "lane-w31-L24-k5": "rowlane",
+    "lane-w30-L40": "rowlane", "lane-w33-k8-dense": "rowblock"}
 assert set(AUTO_PICK) == {c[0] for c in CASES}
 
 # every case under the library's own choice and under the general scorer, and every scorer on the cases it is
 # meant for; a scorer forced onto a shape that it does not cover (it must hand over to one that does) on a few
 PAIRS = [(n, "auto") for n, _ in CASES] + [(n, "rows") for n, _ in CASES]
-PAIRS += [(n, k) for k in ("lanes", "quad", "chunk", "rowblock", "line", "rowseg") for n, _ in CASES if n in NATIVE[k]]
+PAIRS += [(n, k) for k in ("lanes", "quad", "chunk", "rowblock", "line", "rowseg", "rowlane") for n, _ in CASES if n in NATIVE[k]]
 PAIRS += [("rand-odd", "quad"), ("rand-odd", "rowblock"), ("rand-wide", "rowblock"), ("rand-wide", "lanes"),
-          ("serving/16", "rowseg"), ("gqa70b/16", "line"), ("dec-w24-tail", "rowblock"), ("tiny", "chunk")]
+          ("serving/16", "rowseg"), ("gqa70b/16", "line"), ("dec-w24-tail", "rowblock"), ("tiny", "chunk"), ("rand-w40", "rowlane"),
+          ("dec-w21-L3", "rowlane"), ("lane-w33-L80-k8", "rowblock"), ("lane-w36-L16", "rowblock"), ("lane-w29-L3-k2", "line")]
 
 _want = {}
 
@@ -172,7 +185,7 @@ def test_score_matches_oracle_bit_for_bit(G, name, kernel):
 def test_set_score_kernel_refuses_values_that_name_no_scorer(G):
     import paper_2508_13231_amd as K
     with G(W.config("table1")) as g:
-        for bad in (-1, 3, 4, 5, 7, 8, 13, 99):
+        for bad in (-1, 3, 4, 5, 7, 8, 14, 99):
             with pytest.raises(K.KvpError) as e:
                 K.kvp_set_score_kernel(g.ctx, bad)
             assert e.value.code == K.KVP_EINVAL
@@ -638,7 +651,7 @@ def _full_shape(name):
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("name,kernel", [("llama8b", "quad"), ("longctx", "rowblock"), ("gqa70b", "rowblock"),
+@pytest.mark.parametrize("name,kernel", [("llama8b", "quad"), ("longctx", "rowblock"), ("gqa70b", "rowlane"),
                                          ("serving", "line")])
 def test_full_size_batch_sampled_against_oracle(G, name, kernel):
     """Full row shapes and batch sizes, default kernel choice: sampled schedules are re-scored one by

@@ -49,7 +49,7 @@ def test_random_shape_everything_but_the_walk(G, seed):
     X = np.concatenate([W.random_placements(tr, 3, seed=seed, density=0.4),
                         W.random_placements(tr, 2, seed=seed + 1, density=0.9, feasible=False)])
     want = [O.score(q, x) for x in X]
-    for kernel in (0, 1, 2, 6, 9, 10, 11, 12):                        # 0: the library's own choice
+    for kernel in (0, 1, 2, 6, 9, 10, 11, 12, 13):                        # 0: the library's own choice
         with G(tr, score_kernel=kernel) as g:
             cost, ex, cnt, occ = g.score(X)
             for s, r in enumerate(want):
@@ -97,7 +97,7 @@ def test_random_wide_single_sequence_every_scorer(G, seed):
                         W.random_placements(tr, 2, seed=seed + 1, density=0.9, feasible=False)])
     want = [O.score(q, x) for x in X]
     used = set()
-    for kernel in (0, 1, 2, 6, 9, 10, 11, 12):
+    for kernel in (0, 1, 2, 6, 9, 10, 11, 12, 13):
         with G(tr, score_kernel=kernel) as g:
             cost, ex, cnt, occ = g.score(X)
             used.add(K.kvp_score_kernel_used(g.ctx))
