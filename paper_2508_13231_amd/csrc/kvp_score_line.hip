@@ -164,6 +164,12 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
             advance(ix, cx);
             int last_step = (int)N - 1;
             asm volatile("" : "+s"(last_step));                        // keeps the nine row offsets out of registers
+            // This iteration's trace words, requested one iteration ago, go to their slot only now, just before
+            // the rows requested during that iteration are needed anyway: loads complete in the order of their
+            // issue, and waiting for the trace words at the end of an iteration would also wait for the rows
+            // requested last, a memory round trip per chunk.  (Nobody reads the slot before the barrier below,
+            // and its last readers have passed the barrier of the iteration before.)
+            if (it > 0) commit_t(it);
             issue_t(it_, ct); advance(it_, ct);                        // trace words of the next iteration
             __syncthreads();                                           // this iteration's trace slot is complete
             const uint32_t *slot = tbuf + (it & 1u) * NT * PLANE + 4 * (uint32_t)lane;
@@ -206,7 +212,6 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            commit_t(it + 1);                                          // arrived while this iteration was scored
         }
         // the rows are complete: the group's lanes add up, lane (g, p) keeps step 8g + p
         uint32_t hr = 0, hw = 0, oc = 0, mi = 0, mg = 0;
