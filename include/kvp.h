@@ -328,7 +328,11 @@ int kvp_baseline(kvp_ctx *ctx, int kind, uint32_t *d_placement);
  *
  * kvp_wr_policy: n candidates (h_w[i], h_r10[i]), HOST arrays, read before the
  * call returns; d_placements: DEVICE [n][L][N][Wd] uint32, written in full, owned
- * by the caller.  One workgroup per candidate.  W above n_steps acts as n_steps.
+ * by the caller.  Steps 2 and 3 are computed once per distinct W, for all token
+ * steps of a batch at once; steps 1 and 4 to 6 by one workgroup per candidate.  W
+ * above n_steps acts as n_steps.  Scratch held by the context: up to 2 GiB for the
+ * window counts and wanted sets of a batch of steps (at least one step's:
+ * distinct W x L x Wd x (32 x count bytes + 4)), plus n x L x Wd x 4 bytes.
  * Errors: KVP_EINVAL (null pointer, W = 0, r10 > 10), KVP_ENOTRACE, KVP_ESHAPE
  * (W x planes above 32767), KVP_ENOMEM, KVP_EHIP. */
 int kvp_wr_policy(kvp_ctx *ctx, uint32_t n, const uint32_t *h_w, const uint32_t *h_r10, uint32_t *d_placements);

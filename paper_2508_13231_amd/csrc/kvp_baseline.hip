@@ -10,6 +10,8 @@
 // recency placement; the evaluation section of the paper compares its search with
 // a static and a reactive LRU placement of this kind.
 //
+// The recency keys of a step follow from the trace alone, so all steps are selected at once, a
+// workgroup each, from keys written by a pass with a thread per pair.
 // One workgroup of 1024 threads makes a selection: a histogram of the keys in
 // LDS gives the threshold key and how many of the pairs AT the threshold still
 // fit; a second sweep numbers those in index order (wavefront ballots and a scan
@@ -55,41 +57,50 @@ __global__ __launch_bounds__(256) void static_fill_kernel(DevProblem q, const ui
     X[i] = chosen[l * q.Wd + w] & q.V[(size_t)n * q.Wd + w];
 }
 
-// the whole recency placement, step after step, in one workgroup: last[g] = last step at which the
-// pair was read since it last (re)started to persist, -1 if never
-__global__ __launch_bounds__(BT) void recency_kernel(DevProblem q, RowDiv rd, uint64_t cap, int32_t *__restrict__ last,
-                                                     uint32_t *__restrict__ X) {
+// The recency placement in two passes.  A pair's key at step n (the last step before n at which it was
+// read since it last (re)started to persist, plus one; 0 if never) depends on the trace alone, so a thread
+// per pair walks the steps [n_lo, n_hi) and writes the keys of all of them, [n - n_lo][G] 16-bit words
+// (0xFFFF: the page does not exist at that step); `last` carries the walk from one batch of steps to the
+// next.  The selections of the steps are then independent: a workgroup per step.
+constexpr uint32_t KEY16_NONE = 0xFFFFu;
+
+__global__ __launch_bounds__(256) void recency_keys_kernel(DevProblem q, RowDiv rd, uint32_t n_lo, uint32_t n_hi,
+                                                           int32_t *__restrict__ last, uint16_t *__restrict__ keys) {
+    const uint32_t G = q.L * q.Wd * 32;
+    const uint32_t g = blockIdx.x * 256 + threadIdx.x;
+    if (g >= G) return;
+    const uint32_t wi = g >> 5, b = g & 31u, l = rd.quot(wi), w = wi - l * q.Wd;
+    int32_t lv = n_lo ? last[g] : -1;
+    for (uint32_t n = n_lo; n < n_hi; n++) {
+        if (n > 0) {
+            if (!((q.Pm[(size_t)n * q.Wd + w] >> b) & 1u)) {
+                lv = -1;                                               // a page that stops persisting forgets its history
+            } else {
+                uint32_t any = 0;
+                for (uint32_t k = 0; k < q.K; k++) any |= q.A[(((size_t)l * q.N + (n - 1)) * q.K + k) * q.Wd + w];
+                if ((any >> b) & 1u) lv = (int32_t)(n - 1);
+            }
+        }
+        const bool alive = (q.V[(size_t)n * q.Wd + w] >> b) & 1u;      // dead bits of the last word are never alive
+        keys[(size_t)(n - n_lo) * G + g] = alive ? (uint16_t)(lv + 1) : (uint16_t)KEY16_NONE;
+    }
+    last[g] = lv;
+}
+
+__global__ __launch_bounds__(BT) void recency_select_kernel(DevProblem q, uint64_t cap, uint32_t n_lo,
+                                                            const uint16_t *__restrict__ keys, uint32_t *__restrict__ X) {
     extern __shared__ uint32_t lds_u[];
     __shared__ SelectShared sh;
-    const uint32_t G = q.L * q.Wd * 32;
-    for (uint32_t g = threadIdx.x; g < G; g += BT) last[g] = -1;
-    __syncthreads();
-    for (uint32_t n = 0; n < q.N; n++) {
-        auto key = [&](uint32_t g) {
-            const uint32_t w = rd.rem(g >> 5), b = g & 31u;
-            const uint32_t vw = q.V[(size_t)n * q.Wd + w];             // dead bits of the last word are never alive
-            int32_t lv = last[g];
-            asm volatile("" : "+v"(lv));                               // loaded whether alive or not: no branch, loads overlap
-            return ((vw >> b) & 1u) ? (uint32_t)(lv + 1) : NOT_A_CANDIDATE;
-        };
-        auto first_key = [&](uint32_t g) {
-            if (n > 0) {
-                const uint32_t wi = g >> 5, b = g & 31u, l = rd.quot(wi), w = wi - l * q.Wd;
-                if (!((q.Pm[(size_t)n * q.Wd + w] >> b) & 1u)) {
-                    last[g] = -1;                                      // a page that stops persisting forgets its history
-                } else {
-                    uint32_t any = 0;
-                    for (uint32_t k = 0; k < q.K; k++) any |= q.A[(((size_t)l * q.N + (n - 1)) * q.K + k) * q.Wd + w];
-                    if ((any >> b) & 1u) last[g] = (int32_t)(n - 1);
-                }
-            }
-            return key(g);
-        };
-        block_select(G, n + 1, cap, lds_u, sh, first_key, key, [&](uint32_t word, uint32_t bits) {
-            const uint32_t l = word / q.Wd, w = word - l * q.Wd;
-            X[((size_t)l * q.N + n) * q.Wd + w] = bits;
-        });
-    }
+    const uint32_t G = q.L * q.Wd * 32, n = n_lo + blockIdx.x;
+    const uint16_t *kn = keys + (size_t)blockIdx.x * G;
+    auto key = [&](uint32_t g) {
+        const uint32_t k = kn[g];
+        return k == KEY16_NONE ? NOT_A_CANDIDATE : k;
+    };
+    block_select(G, n + 1, cap, lds_u, sh, key, key, [&](uint32_t word, uint32_t bits) {
+        const uint32_t l = word / q.Wd, w = word - l * q.Wd;
+        X[((size_t)l * q.N + n) * q.Wd + w] = bits;
+    });
 }
 
 // Static fill, step after step, in one workgroup.  The state is one mask word per (layer, word):
@@ -195,10 +206,22 @@ extern "C" int kvp_baseline(kvp_ctx *ctx, int kind, uint32_t *d_placement) {
         fill_kernel<<<dim3(1), dim3(BT), 0, ctx->stream>>>(q, cap, work, d_placement);
         KVP_HIP(hipGetLastError());
     } else {
+        // batches of steps whose keys fit a gigabyte (at least one step)
+        const uint64_t per_step = (uint64_t)G * sizeof(uint16_t);
+        const uint32_t batch = (uint32_t)(per_step >= (1ull << 30) ? 1 : (1ull << 30) / per_step < q.N ? (1ull << 30) / per_step : q.N);
+        rc = kvp_ensure(ctx, (void **)&ctx->d_sel_keys, &ctx->sel_keys_cap, (size_t)batch * per_step);
+        if (rc) return rc;
         if (lds > 48 * 1024)
-            KVP_HIP(hipFuncSetAttribute((const void *)recency_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        recency_kernel<<<dim3(1), dim3(BT), lds, ctx->stream>>>(q, rd, cap, (int32_t *)work, d_placement);
-        KVP_HIP(hipGetLastError());
+            KVP_HIP(hipFuncSetAttribute((const void *)recency_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        for (uint32_t n_lo = 0; n_lo < q.N; n_lo += batch) {
+            const uint32_t n_hi = n_lo + batch < q.N ? n_lo + batch : q.N;
+            recency_keys_kernel<<<dim3((G + 255) / 256), dim3(256), 0, ctx->stream>>>(q, rd, n_lo, n_hi, (int32_t *)work,
+                                                                                      (uint16_t *)ctx->d_sel_keys);
+            KVP_HIP(hipGetLastError());
+            recency_select_kernel<<<dim3(n_hi - n_lo), dim3(BT), lds, ctx->stream>>>(q, cap, n_lo, (const uint16_t *)ctx->d_sel_keys,
+                                                                                   d_placement);
+            KVP_HIP(hipGetLastError());
+        }
     }
     return KVP_OK;
 }

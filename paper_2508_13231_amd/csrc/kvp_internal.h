@@ -80,6 +80,7 @@ struct kvp_ctx {
     uint8_t *d_empty32 = nullptr;        // [tiles][ceil(Wd/32)] 1: no page of words [32c, 32c+32) exists on the tile
     uint32_t *d_policy_work = nullptr; size_t policy_work_cap = 0;   // (W,R) policy: window counts, pool, wanted per candidate
     uint32_t *d_policy_x = nullptr; size_t policy_x_cap = 0;         // (W,R) search: schedules of a batch and their costs
+    uint32_t *d_sel_keys = nullptr; size_t sel_keys_cap = 0;  // recency placement: 16-bit keys of a batch of steps
     uint32_t *d_cnt_tmp = nullptr; size_t cnt_tmp_cap = 0;    // delta: counters when not given
     uint32_t *d_occ_tmp = nullptr; size_t occ_tmp_cap = 0;
     // annealing state

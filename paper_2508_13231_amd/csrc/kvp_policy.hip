@@ -14,11 +14,14 @@
 //      least-read-in-the-window first, ties to the lower l*P+p;
 //   6. the pool is the placement of step n in every layer's row.
 //
-// kvp_wr_policy turns a batch of (W, R) candidates into schedules, one workgroup
-// per candidate: the window counts slide (one step leaves, one enters), and
-// steps 3 to 5 are three selections by histogram threshold and index-ordered ties
-// (kvp_select.h).  kvp_wr_search is the annealing itself: a host loop over a
-// memoised table T(W, R), filled by scoring whole neighbourhoods of candidates at
+// kvp_wr_policy turns a batch of (W, R) candidates into schedules in three passes over a batch of
+// token steps.  The window counts f and the wanted set (steps 2 and 3) follow from the trace and W
+// alone, so they are computed once per distinct window, for all steps of the batch at once: a thread
+// per pair slides its window count along the steps, then a workgroup per step selects the wanted
+// pages by histogram threshold and index-ordered ties (kvp_select.h).  Only the pool carries from one
+// step to the next: a workgroup per candidate walks the steps, and its two selections (steps 4 and 5)
+// visit the set bits of the pool and wanted masks only.  kvp_wr_search is the annealing itself: a
+// host loop over a memoised table T(W, R), filled by scoring whole neighbourhoods of candidates at
 // once (generator + kvp_score), so the accelerator sees batches, not single points.
 #include <math.h>
 
@@ -37,57 +40,83 @@ __device__ __forceinline__ uint32_t reads_at(const DevProblem &q, uint32_t l, ui
     return s;
 }
 
-// work per candidate: pool[LW] and wanted[LW] mask words, then f[G] window counts.  The counts are
-// what the kernel streams through, several times per step: FT is the narrowest type that holds
-// W * K (a byte for one plane and any window up to 255 steps).
+// Window counts.  Thread (g, u) walks the steps [n_lo, n_hi) for pair g and distinct window u and
+// writes f[u][n - n_lo][g]; fstate[u][g] carries the count into the next batch of steps.  FT is the
+// narrowest type that holds W * K (a byte for one plane and any window up to 255 steps).
 template <class FT>
-__global__ __launch_bounds__(BT) void wr_policy_kernel(DevProblem q, RowDiv rd, uint64_t cap, const uint32_t *__restrict__ cand_w,
-                                                       const uint32_t *__restrict__ cand_r10, uint32_t *work,
-                                                       size_t work_stride, uint32_t *Xall) {
+__global__ __launch_bounds__(256) void wr_counts_kernel(DevProblem q, RowDiv rd, const uint32_t *__restrict__ uw,
+                                                        uint32_t n_lo, uint32_t n_hi, uint32_t B, FT *__restrict__ fstate,
+                                                        FT *__restrict__ fk) {
+    const uint32_t G = q.L * q.Wd * 32, g = blockIdx.x * 256 + threadIdx.x, u = blockIdx.y;
+    if (g >= G) return;
+    const uint32_t wi = g >> 5, b = g & 31u, l = rd.quot(wi), w = wi - l * q.Wd;
+    const uint32_t W = min(uw[u], q.N);
+    uint32_t s = 0;
+    if (n_lo == 0)
+        for (uint32_t m = 0; m < W; m++) s += reads_at(q, l, m, w, b);
+    else
+        s = (uint32_t)fstate[(size_t)u * G + g];
+    FT *out = fk + (size_t)u * B * G + g;
+    for (uint32_t n = n_lo; n < n_hi; n++) {
+        if (n > 0) {                                                   // the window slides: step n-1 leaves, n+W-1 enters
+            s -= reads_at(q, l, n - 1, w, b);
+            if (n + W - 1 < q.N) s += reads_at(q, l, n + W - 1, w, b);
+        }
+        out[(size_t)(n - n_lo) * G] = (FT)s;
+    }
+    fstate[(size_t)u * G + g] = (FT)s;
+}
+
+// Steps 2 and 3 for step n_lo + blockIdx.x and distinct window blockIdx.y: the wanted set as mask words.
+template <class FT>
+__global__ __launch_bounds__(BT) void wr_wanted_kernel(DevProblem q, RowDiv rd, uint64_t cap, const uint32_t *__restrict__ uw,
+                                                       uint32_t n_lo, uint32_t B, const FT *__restrict__ fk,
+                                                       uint32_t *__restrict__ wanted_all) {
+    extern __shared__ uint32_t lds_u[];
+    __shared__ SelectShared sh;
+    const uint32_t LW = q.L * q.Wd, G = LW * 32, u = blockIdx.y, n = n_lo + blockIdx.x;
+    const uint32_t W = min(uw[u], q.N);
+    const FT *f = fk + ((size_t)u * B + blockIdx.x) * G;
+    uint32_t *wanted = wanted_all + ((size_t)u * B + blockIdx.x) * LW;
+    auto key_want = [&](uint32_t g) {
+        const uint32_t w = rd.rem(g >> 5), b = g & 31u;
+        const uint32_t vw = q.V[(size_t)n * q.Wd + w];
+        uint32_t fv = (uint32_t)f[g];
+        asm volatile("" : "+v"(fv));                                   // loaded whether the page exists or not
+        return ((vw >> b) & 1u) && fv > 0 ? fv : NOT_A_CANDIDATE;
+    };
+    block_select(G, W * q.K + 1, cap, lds_u, sh, key_want, key_want, [&](uint32_t word, uint32_t bits) { wanted[word] = bits; });
+}
+
+// Steps 1 and 4 to 6 for candidate blockIdx.x over the steps [n_lo, n_hi): pools[candidate][LW] carries
+// the pool from one batch of steps to the next.
+template <class FT>
+__global__ __launch_bounds__(BT) void wr_pool_kernel(DevProblem q, RowDiv rd, uint64_t cap, const uint32_t *__restrict__ cand_w,
+                                                     const uint32_t *__restrict__ cand_r10, const uint32_t *__restrict__ cand_u,
+                                                     uint32_t n_lo, uint32_t n_hi, uint32_t B, uint32_t *pools,
+                                                     const uint32_t *__restrict__ wanted_all, const FT *__restrict__ fk,
+                                                     uint32_t *Xall) {
     extern __shared__ uint32_t lds_u[];
     __shared__ SelectShared sh;
     __shared__ uint32_t counts[2];
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t LW = q.L * q.Wd, G = LW * 32;
-    const uint32_t W = min(cand_w[blockIdx.x], q.N), r10 = cand_r10[blockIdx.x];
-    uint32_t *pool = work + (size_t)blockIdx.x * work_stride, *wanted = pool + LW;
-    FT *f = (FT *)(wanted + LW);
+    const uint32_t W = min(cand_w[blockIdx.x], q.N), r10 = cand_r10[blockIdx.x], u = cand_u[blockIdx.x];
+    uint32_t *pool = pools + (size_t)blockIdx.x * LW;
     uint32_t *X = Xall + (size_t)blockIdx.x * q.L * q.N * q.Wd;
     const uint32_t fmax = W * q.K, nbins = fmax + 1;
-
-    for (uint32_t wi = tid; wi < LW; wi += BT) pool[wi] = 0;
-    for (uint32_t g = tid; g < G; g += BT) {
-        const uint32_t wi = g >> 5, b = g & 31u, l = rd.quot(wi), w = wi - l * q.Wd;
-        uint32_t s = 0;
-        for (uint32_t m = 0; m < W; m++) s += reads_at(q, l, m, w, b);
-        f[g] = (FT)s;
-    }
+    if (n_lo == 0)
+        for (uint32_t wi = tid; wi < LW; wi += BT) pool[wi] = 0;
     __syncthreads();
-    for (uint32_t n = 0; n < q.N; n++) {
-        if (n > 0)                                                     // the window slides: step n-1 leaves, n+W-1 enters
-            for (uint32_t g = tid; g < G; g += BT) {
-                const uint32_t wi = g >> 5, b = g & 31u, l = rd.quot(wi), w = wi - l * q.Wd;
-                uint32_t s = (uint32_t)f[g] - reads_at(q, l, n - 1, w, b);
-                if (n + W - 1 < q.N) s += reads_at(q, l, n + W - 1, w, b);
-                f[g] = (FT)s;
-            }
-        for (uint32_t wi = tid; wi < LW; wi += BT) pool[wi] &= q.Pm[(size_t)n * q.Wd + rd.rem(wi)];   // step 1
+    for (uint32_t n = n_lo; n < n_hi; n++) {
+        const uint32_t *wanted = wanted_all + ((size_t)u * B + (n - n_lo)) * LW;
+        const FT *f = fk + ((size_t)u * B + (n - n_lo)) * G;
         if (tid < 2) counts[tid] = 0;
         __syncthreads();
-        // steps 2 and 3: the wanted set
-        auto key_want = [&](uint32_t g) {
-            const uint32_t w = rd.rem(g >> 5), b = g & 31u;
-            const uint32_t vw = q.V[(size_t)n * q.Wd + w];
-            uint32_t fv = (uint32_t)f[g];
-            asm volatile("" : "+v"(fv));                               // loaded whether the page exists or not
-            return ((vw >> b) & 1u) && fv > 0 ? fv : NOT_A_CANDIDATE;
-        };
-        block_select(G, nbins, cap, lds_u, sh, key_want, key_want,
-                     [&](uint32_t word, uint32_t bits) { wanted[word] = bits; });
-        // how many are qualified, how many are in the pool
-        uint32_t nq = 0, np = 0;
+        uint32_t nq = 0, np = 0;                                       // how many are qualified, how many in the pool
         for (uint32_t wi = tid; wi < LW; wi += BT) {
-            const uint32_t pw = pool[wi];
+            const uint32_t pw = pool[wi] & q.Pm[(size_t)n * q.Wd + rd.rem(wi)];               // step 1
+            pool[wi] = pw;
             nq += __popc(wanted[wi] & ~pw);
             np += __popc(pw);
         }
@@ -97,28 +126,12 @@ __global__ __launch_bounds__(BT) void wr_policy_kernel(DevProblem q, RowDiv rd, 
         const uint64_t m_in = ((uint64_t)r10 * counts[0] + 5) / 10;    // step 4
         const uint64_t in_pool = counts[1];
         const uint64_t need = in_pool + m_in > cap ? in_pool + m_in - cap : 0;
-        if (need > 0) {                                                // step 5
-            auto key_out = [&](uint32_t g) {
-                const uint32_t wi = g >> 5, b = g & 31u;
-                const uint32_t pw = pool[wi], ww = wanted[wi];
-                uint32_t fv = (uint32_t)f[g];
-                asm volatile("" : "+v"(fv));
-                return ((pw & ~ww) >> b) & 1u ? fmax - fv : NOT_A_CANDIDATE;
-            };
-            block_select(G, nbins, need, lds_u, sh, key_out, key_out,
-                         [&](uint32_t word, uint32_t bits) { pool[word] &= ~bits; });
-        }
-        if (m_in > 0) {                                                // step 4, carried out
-            auto key_in = [&](uint32_t g) {
-                const uint32_t wi = g >> 5, b = g & 31u;
-                const uint32_t pw = pool[wi], ww = wanted[wi];
-                uint32_t fv = (uint32_t)f[g];
-                asm volatile("" : "+v"(fv));
-                return ((ww & ~pw) >> b) & 1u ? fv : NOT_A_CANDIDATE;
-            };
-            block_select(G, nbins, m_in, lds_u, sh, key_in, key_in,
-                         [&](uint32_t word, uint32_t bits) { pool[word] |= bits; });
-        }
+        if (need > 0)                                                  // step 5
+            mask_select(LW, nbins, need, lds_u, sh, [&](uint32_t wi) { return pool[wi] & ~wanted[wi]; },
+                        [&](uint32_t g) { return fmax - (uint32_t)f[g]; }, [&](uint32_t wi, uint32_t bits) { pool[wi] &= ~bits; });
+        if (m_in > 0)                                                  // step 4, carried out
+            mask_select(LW, nbins, m_in, lds_u, sh, [&](uint32_t wi) { return wanted[wi] & ~pool[wi]; },
+                        [&](uint32_t g) { return (uint32_t)f[g]; }, [&](uint32_t wi, uint32_t bits) { pool[wi] |= bits; });
         for (uint32_t wi = tid; wi < LW; wi += BT) {                   // step 6
             const uint32_t l = rd.quot(wi), w = wi - l * q.Wd;
             X[((size_t)l * q.N + n) * q.Wd + w] = pool[wi];
@@ -150,20 +163,49 @@ extern "C" int kvp_wr_policy(kvp_ctx *ctx, uint32_t n, const uint32_t *h_w, cons
     const RowDiv rd(q.Wd, (uint64_t)q.L * q.Wd);
     const uint64_t fmax = (uint64_t)wmax * q.K;
     const size_t fbytes = fmax <= 0xFF ? 1 : fmax <= 0xFFFF ? 2 : 4;
-    const size_t LW = (size_t)q.L * q.Wd, stride = 2 * LW + ((size_t)G64 * fbytes + 3) / 4;      // words per candidate
-    int rc = kvp_ensure(ctx, (void **)&ctx->d_policy_work, &ctx->policy_work_cap, ((size_t)n * stride + 2 * (size_t)n) * 4);
+    // the distinct windows of the batch, and which of them each candidate uses
+    std::vector<uint32_t> host(3 * (size_t)n), uw;
+    for (uint32_t i = 0; i < n; i++) {
+        const uint32_t w = h_w[i] < q.N ? h_w[i] : q.N;
+        uint32_t u = 0;
+        while (u < uw.size() && uw[u] != w) u++;
+        if (u == uw.size()) uw.push_back(w);
+        host[i] = w; host[(size_t)n + i] = h_r10[i]; host[2 * (size_t)n + i] = u;
+    }
+    const uint32_t nu = (uint32_t)uw.size();
+    host.insert(host.end(), uw.begin(), uw.end());
+    // steps per batch: the counts and wanted masks of a batch take two gigabytes at most (one step at least)
+    const size_t LW = (size_t)q.L * q.Wd, G = (size_t)G64;
+    const size_t per_step = (size_t)nu * (G * fbytes + LW * 4);
+    const uint32_t B = (uint32_t)(per_step >= ((size_t)2 << 30) ? 1 : ((size_t)2 << 30) / per_step < q.N ? ((size_t)2 << 30) / per_step : q.N);
+    // layout, in words: candidate table | pools | wanted masks | count state | counts
+    const size_t o_pool = (host.size() + 3) & ~(size_t)3, o_want = o_pool + (size_t)n * LW, o_state = o_want + (size_t)nu * B * LW;
+    const size_t o_f = o_state + ((size_t)nu * G * fbytes + 3) / 4, total = o_f + ((size_t)nu * B * G * fbytes + 3) / 4;
+    int rc = kvp_ensure(ctx, (void **)&ctx->d_policy_work, &ctx->policy_work_cap, total * 4);
     if (rc) return rc;
-    uint32_t *d_w = ctx->d_policy_work + (size_t)n * stride, *d_r = d_w + n;
-    KVP_HIP(hipMemcpyAsync(d_w, h_w, (size_t)n * 4, hipMemcpyHostToDevice, ctx->stream));
-    KVP_HIP(hipMemcpyAsync(d_r, h_r10, (size_t)n * 4, hipMemcpyHostToDevice, ctx->stream));
-    KVP_HIP(hipStreamSynchronize(ctx->stream));                        // the host arrays may go away after the call
+    uint32_t *wk = ctx->d_policy_work;
+    const uint32_t *d_w = wk, *d_r = wk + n, *d_u = wk + 2 * (size_t)n, *d_uw = wk + 3 * (size_t)n;
+    KVP_HIP(hipMemcpyAsync(wk, host.data(), host.size() * 4, hipMemcpyHostToDevice, ctx->stream));
+    KVP_HIP(hipStreamSynchronize(ctx->stream));                        // the host arrays go away after the call
+    const uint64_t cap = ctx->prob.cap_pages;
 #define KVP_POLICY(FT)                                                                                              \
     do {                                                                                                            \
-        if (lds > 48 * 1024)                                                                                        \
-            KVP_HIP(hipFuncSetAttribute((const void *)wr_policy_kernel<FT>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+        if (lds > 48 * 1024) {                                                                                      \
+            KVP_HIP(hipFuncSetAttribute((const void *)wr_wanted_kernel<FT>, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                         (int)lds));                                                                 \
-        wr_policy_kernel<FT><<<dim3(n), dim3(BT), lds, ctx->stream>>>(q, rd, ctx->prob.cap_pages, d_w, d_r,           \
-                                                                       ctx->d_policy_work, stride, d_placements);   \
+            KVP_HIP(hipFuncSetAttribute((const void *)wr_pool_kernel<FT>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                        (int)lds));                                                                 \
+        }                                                                                                           \
+        FT *fstate = (FT *)(wk + o_state), *fk = (FT *)(wk + o_f);                                                  \
+        for (uint32_t n_lo = 0; n_lo < q.N; n_lo += B) {                                                            \
+            const uint32_t n_hi = n_lo + B < q.N ? n_lo + B : q.N;                                                  \
+            wr_counts_kernel<FT><<<dim3((uint32_t)((G + 255) / 256), nu), dim3(256), 0, ctx->stream>>>(             \
+                q, rd, d_uw, n_lo, n_hi, B, fstate, fk);                                                            \
+            wr_wanted_kernel<FT><<<dim3(n_hi - n_lo, nu), dim3(BT), lds, ctx->stream>>>(q, rd, cap, d_uw, n_lo, B, fk, \
+                                                                                       wk + o_want);                \
+            wr_pool_kernel<FT><<<dim3(n), dim3(BT), lds, ctx->stream>>>(q, rd, cap, d_w, d_r, d_u, n_lo, n_hi, B,   \
+                                                                       wk + o_pool, wk + o_want, fk, d_placements); \
+        }                                                                                                           \
     } while (0)
     if (fbytes == 1) KVP_POLICY(uint8_t);
     else if (fbytes == 2) KVP_POLICY(uint16_t);
