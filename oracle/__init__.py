@@ -53,7 +53,7 @@ class _Move(C.Structure):
 class _SAParams(C.Structure):
     _fields_ = [("seed", C.c_uint64), ("total_moves", C.c_uint64), ("move_begin", C.c_uint64),
                 ("move_end", C.c_uint64), ("n_levels", C.c_uint32), ("max_len", C.c_uint32),
-                ("p0", C.c_double), ("alpha", C.c_double), ("op_prob", C.c_double * 3)]
+                ("p0", C.c_double), ("alpha", C.c_double), ("op_prob", C.c_double * 3), ("per_slot", C.c_uint32)]
 
 
 class _SAState(C.Structure):
@@ -97,6 +97,10 @@ def lib():
         L.orc_resolve.restype = C.c_int
         L.orc_resolve.argtypes = [C.POINTER(_Problem), C.c_void_p, C.c_void_p, C.POINTER(_Move),
                                   C.c_void_p, C.c_void_p, C.POINTER(C.c_int)]
+        L.orc_resolve_strict.restype = C.c_int
+        L.orc_resolve_strict.argtypes = L.orc_resolve.argtypes
+        L.orc_slot_occupancy.restype = None
+        L.orc_slot_occupancy.argtypes = [C.POINTER(_Problem), C.c_void_p, C.c_void_p]
         L.orc_init_static_frequency.argtypes = [C.POINTER(_Problem), C.c_void_p]
         L.orc_init_recency.argtypes = [C.POINTER(_Problem), C.c_void_p]
         L.orc_init_static_fill.argtypes = [C.POINTER(_Problem), C.c_void_p]
@@ -244,6 +248,35 @@ def delta(tr, X, move):
     return v, d.value, base.value, f1, f2
 
 
+def slot_occupancy(tr, X) -> np.ndarray:
+    """[N][L]: pages in the pool after layer l of token step n has taken its placement (Eq. 5 read at
+    every inference step)."""
+    q = _problem(tr)
+    X = _u8(X, q.shape)
+    tab = np.zeros((q.N, q.L), dtype=np.uint32)
+    lib().orc_slot_occupancy(C.byref(q.c), X.ctypes.data, tab.ctypes.data)
+    return tab
+
+
+def resolve(tr, X, move, per_slot=False):
+    """(verdict, f1, f2, base): the steps at which a raw move flips its page (f1) and its victim (f2),
+    under the capacity once per token step or, per_slot, at every inference step."""
+    q = _problem(tr)
+    X = _u8(X, q.shape)
+    f1 = np.zeros(q.N, dtype=np.uint8)
+    f2 = np.zeros(q.N, dtype=np.uint8)
+    base = C.c_int(0)
+    if per_slot:
+        view = slot_occupancy(q, X)
+        v = lib().orc_resolve_strict(C.byref(q.c), X.ctypes.data, view.ctypes.data, C.byref(_move(move)),
+                                     f1.ctypes.data, f2.ctypes.data, C.byref(base))
+    else:
+        view = np.ascontiguousarray(score(q, X).occ, dtype=np.uint32)
+        v = lib().orc_resolve(C.byref(q.c), X.ctypes.data, view.ctypes.data, C.byref(_move(move)),
+                              f1.ctypes.data, f2.ctypes.data, C.byref(base))
+    return v, f1, f2, base.value
+
+
 def apply_move(tr, X, move):
     """Schedule after the move (a copy), and the verdict."""
     q = _problem(tr)
@@ -328,9 +361,10 @@ class ChainResult:
 
 
 def anneal_chain(tr, chain, X0, *, seed, total_moves, move_begin=0, move_end=None, n_levels=100,
-                 max_len=63, p0=0.8, alpha=0.9, op_prob=(0.4, 0.4, 0.2), resume=None) -> ChainResult:
+                 max_len=63, p0=0.8, alpha=0.9, op_prob=(0.4, 0.4, 0.2), resume=None, per_slot=False) -> ChainResult:
     q = _problem(tr)
     sp = _SAParams()
+    sp.per_slot = int(bool(per_slot))
     sp.seed, sp.total_moves = int(seed), int(total_moves)
     sp.move_begin = int(move_begin)
     sp.move_end = int(total_moves if move_end is None else move_end)

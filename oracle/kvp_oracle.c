@@ -210,8 +210,39 @@ void orc_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t ou
  */
 static const int SHIFT_D[4] = {-2, -1, 1, 2};
 
-int orc_resolve(const orc_problem *q, const uint8_t *X, const uint32_t *occ, const orc_move *m,
-                uint8_t *f1, uint8_t *f2, int *base) {
+/* May the bit of (l, p) be set at token step n?  `evict`: the victim (l2, pq), which is set at n,
+ * is cleared at the same step.
+ * tab == NULL, Eq. 5 once per token step: yes if the step is below capacity; with a victim always
+ * (the pool of step n gains one page and loses one).
+ * tab != NULL, Eq. 5 at every inference step (n, l'): tab[n][l'] is the pool after layer l' of step
+ * n has taken its placement (orc_slot_occupancy).  Setting (l, p) at n adds the page to the slots
+ * (n, l' >= l) and, if the page persists into n + 1, to the slots (n + 1, l' < l), where layer l
+ * still holds its placement of step n; clearing the victim takes one page off (n, l' >= l2) and,
+ * if it persists, off (n + 1, l' < l2).  Yes if no slot of the two steps ends above the capacity.
+ * Every step of a move is judged against the schedule as it is before the move: two steps of one
+ * page's run add to different slots (l' >= l of a step from its own bit, l' < l from the bit of
+ * the step before), so each slot gains one page at most and what was judged stays true. */
+static int fits(const orc_problem *q, const uint32_t *occ, const uint32_t *tab, int l, int p, int n,
+                int evict, int l2, int pq) {
+    uint64_t cap = q->cap_pages;
+    if (!tab) return evict ? 1 : (uint64_t)occ[n] < cap;
+    int L = q->L, N = q->N;
+    for (int lp = 0; lp < L; lp++) {
+        int64_t v = (int64_t)tab[(size_t)n * L + lp] + (lp >= l) - (evict && lp >= l2);
+        if (v > (int64_t)cap) return 0;
+    }
+    if (n + 1 < N) {
+        int pp = pm_bit(q, n + 1, p), pv = evict && pm_bit(q, n + 1, pq);
+        for (int lp = 0; lp < L; lp++) {
+            int64_t v = (int64_t)tab[(size_t)(n + 1) * L + lp] + (pp && lp < l) - (pv && lp < l2);
+            if (v > (int64_t)cap) return 0;
+        }
+    }
+    return 1;
+}
+
+static int resolve_move(const orc_problem *q, const uint8_t *X, const uint32_t *occ, const uint32_t *tab,
+                        const orc_move *m, uint8_t *f1, uint8_t *f2, int *base) {
     int L = q->L, N = q->N, P = q->P;
     memset(f1, 0, (size_t)N); memset(f2, 0, (size_t)N);
     *base = 0;
@@ -220,7 +251,6 @@ int orc_resolve(const orc_problem *q, const uint8_t *X, const uint32_t *occ, con
         return ORC_NULL;
     int l = (int)m->layer, p = (int)m->page, n1 = (int)m->n1, len = (int)m->len;
     int l2 = (int)m->layer2, pq = (int)m->page2;
-    uint64_t cap = q->cap_pages;
     *base = n1;
     if (!v_bit(q, n1, p)) return ORC_NULL;
     int e = n1 + 1;
@@ -231,15 +261,15 @@ int orc_resolve(const orc_problem *q, const uint8_t *X, const uint32_t *occ, con
         int v = !x1;
         for (int n = n1; n < e; n++) {
             if (x_bit(q, X, l, n, p) == v) continue;
-            if (v && (uint64_t)occ[n] >= cap) { clipped = 1; break; }
+            if (v && !fits(q, occ, tab, l, p, n, 0, 0, 0)) { clipped = 1; break; }
             f1[n] = 1; flips++;
         }
     } else if (m->op == ORC_SWAP) {
         int victim_ok = !(l2 == l && pq == p);
         for (int n = n1; n < e; n++) {
             if (x_bit(q, X, l, n, p)) continue;
-            if ((uint64_t)occ[n] < cap) { f1[n] = 1; flips++; }
-            else if (victim_ok && x_bit(q, X, l2, n, pq)) { f1[n] = 1; f2[n] = 1; flips++; }
+            if (fits(q, occ, tab, l, p, n, 0, 0, 0)) { f1[n] = 1; flips++; }
+            else if (victim_ok && x_bit(q, X, l2, n, pq) && fits(q, occ, tab, l, p, n, 1, l2, pq)) { f1[n] = 1; f2[n] = 1; flips++; }
             else clipped = 1;
         }
     } else { /* SHIFT */
@@ -253,19 +283,31 @@ int orc_resolve(const orc_problem *q, const uint8_t *X, const uint32_t *occ, con
         if (d < 0) {
             int lo = nt + d > n1 ? nt + d : n1;
             for (int n = nt - 1; n >= lo; n--) {          /* these steps hold a, give them not(a) */
-                if (!a && (uint64_t)occ[n] >= cap) { clipped = 1; break; }
+                if (!a && !fits(q, occ, tab, l, p, n, 0, 0, 0)) { clipped = 1; break; }
                 f1[n] = 1; flips++;
             }
         } else {
             for (int n = nt; n < nt + d && n < N && (n == nt || pm_bit(q, n, p)); n++) {
                 if (x_bit(q, X, l, n, p) == a) continue;
-                if (a && (uint64_t)occ[n] >= cap) { clipped = 1; break; }
+                if (a && !fits(q, occ, tab, l, p, n, 0, 0, 0)) { clipped = 1; break; }
                 f1[n] = 1; flips++;
             }
         }
     }
     if (!flips) return ORC_NULL;
     return clipped ? ORC_CLIPPED : ORC_OK;
+}
+
+int orc_resolve(const orc_problem *q, const uint8_t *X, const uint32_t *occ, const orc_move *m,
+                uint8_t *f1, uint8_t *f2, int *base) {
+    return resolve_move(q, X, occ, NULL, m, f1, f2, base);
+}
+
+/* The same moves under Eq. 5 read at every inference step: `tab` is orc_slot_occupancy of X, which
+ * must not exceed the capacity in any slot.  No move ever raises a slot above the capacity. */
+int orc_resolve_strict(const orc_problem *q, const uint8_t *X, const uint32_t *tab, const orc_move *m,
+                       uint8_t *f1, uint8_t *f2, int *base) {
+    return resolve_move(q, X, NULL, tab, m, f1, f2, base);
 }
 
 static void apply_flips(const orc_problem *q, uint8_t *X, uint32_t *occ, const orc_move *m,
@@ -365,6 +407,28 @@ uint32_t orc_strict_excess(const orc_problem *q, const uint8_t *X) {
     }
     free(cur);
     return (uint32_t)(worst > 0x7FFFFFFFull ? 0x7FFFFFFFull : worst);
+}
+
+/* The pool after every slot, tab[n][l], by the same simulation (the count is carried along: a
+ * layer that takes its placement swaps its old pages for its new ones). */
+void orc_slot_occupancy(const orc_problem *q, const uint8_t *X, uint32_t *tab) {
+    int L = q->L, N = q->N, P = q->P;
+    uint8_t *cur = (uint8_t *)calloc((size_t)L * P ? (size_t)L * P : 1, 1);
+    uint32_t occ = 0;
+    for (int n = 0; n < N; n++) {
+        for (int l = 0; l < L; l++)
+            for (int p = 0; p < P; p++)
+                if (!(n > 0 && pm_bit(q, n, p)) && cur[(size_t)l * P + p]) { cur[(size_t)l * P + p] = 0; occ--; }
+        for (int l = 0; l < L; l++) {
+            for (int p = 0; p < P; p++) {
+                uint8_t now = (uint8_t)(x_bit(q, X, l, n, p) && v_bit(q, n, p));
+                occ += now; occ -= cur[(size_t)l * P + p];
+                cur[(size_t)l * P + p] = now;
+            }
+            tab[(size_t)n * L + l] = occ;
+        }
+    }
+    free(cur);
 }
 
 /* ---- starting schedules (the paper's non-migrating and reactive baselines,
@@ -493,6 +557,7 @@ typedef struct {
     uint32_t max_len;         /* longest span of a move, 1..63                  */
     double p0, alpha;         /* initial acceptance of uphill moves; cooling    */
     double op_prob[3];        /* SET, SWAP, SHIFT                               */
+    uint32_t per_slot;        /* 0: Eq. 5 once per token step; 1: at every inference step (n, l) */
 } orc_sa_params;
 
 typedef struct {
@@ -576,7 +641,13 @@ int orc_anneal_chain(const orc_problem *q, const orc_sa_params *sp, uint32_t cha
     double tn1[ORC_WIN], tn2[ORC_WIN];
     uint32_t ex;
     double T0 = orc_score(q, X, &ex, NULL, tcur, occ);
-    if (ex != 0) { free(tcur); free(occ); free(f1); free(f2); return -2; }
+    uint32_t *tab = NULL;                     /* per-slot capacity: the pool after every (n, l) */
+    if (sp->per_slot && ex == 0) {
+        tab = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)L * N);
+        orc_slot_occupancy(q, X, tab);
+        if (orc_strict_excess(q, X) != 0) ex = 1;
+    }
+    if (ex != 0) { free(tcur); free(occ); free(f1); free(f2); free(tab); return -2; }
     uint64_t mpl = sp->total_moves / sp->n_levels; if (mpl < 1) mpl = 1;
 
     if (sp->move_begin == 0) {
@@ -587,7 +658,7 @@ int orc_anneal_chain(const orc_problem *q, const orc_sa_params *sp, uint32_t cha
         for (uint64_t j = 0; j < ORC_CALIB; j++) {
             orc_move m; double u; int base, second;
             orc_draw_move(q, sp, chain, j, 8, &m, &u);
-            if (orc_resolve(q, X, occ, &m, f1, f2, &base) == ORC_NULL) continue;
+            if (resolve_move(q, X, occ, tab, &m, f1, f2, &base) == ORC_NULL) continue;
             double dT = window_delta(q, X, &m, f1, f2, base, tcur, tn1, tn2, &second);
             if (dT > 0.0) { sum = sum + dT; cnt++; }
         }
@@ -600,7 +671,7 @@ int orc_anneal_chain(const orc_problem *q, const orc_sa_params *sp, uint32_t cha
         while (st->level < lvl) { st->C = st->C * sp->alpha; st->level++; }
         orc_move m; double u; int base, second;
         orc_draw_move(q, sp, chain, mi, 0, &m, &u);
-        int verdict = orc_resolve(q, X, occ, &m, f1, f2, &base);
+        int verdict = resolve_move(q, X, occ, tab, &m, f1, f2, &base);
         if (verdict == ORC_NULL) { st->null_moves++; continue; }
         if (verdict == ORC_CLIPPED) st->clipped++;
         double dT = window_delta(q, X, &m, f1, f2, base, tcur, tn1, tn2, &second);
@@ -610,6 +681,7 @@ int orc_anneal_chain(const orc_problem *q, const orc_sa_params *sp, uint32_t cha
         st->accepted++; if (dT > 0.0) st->uphill++;
         int lo = base < 0 ? 0 : base, hi = base + ORC_WIN < N ? base + ORC_WIN : N;
         apply_flips(q, X, occ, &m, f1, f2, lo, hi);
+        if (tab) orc_slot_occupancy(q, X, tab);
         for (int i = 0; i < ORC_WIN; i++) {
             int n = base + i;
             if (n < 0 || n >= N) continue;
@@ -619,7 +691,7 @@ int orc_anneal_chain(const orc_problem *q, const orc_sa_params *sp, uint32_t cha
         st->T_cur = st->T_cur + dT;
         if (st->T_cur < st->T_best) { st->T_best = st->T_cur; st->improved++; memcpy(best_X, X, sz); }
     }
-    free(tcur); free(occ); free(f1); free(f2);
+    free(tcur); free(occ); free(f1); free(f2); free(tab);
     return 0;
 }
 

@@ -482,6 +482,219 @@ def test_strict_excess_bounds(name, scale):
         assert O.strict_excess(q, X) == O.score(q, X).excess & 0x7FFFFFFF
 
 
+# ---- the capacity at every inference step (Eq. 5 with the decision tuple S(n, l) of Sec. III-A) ----
+
+def _slot_table_by_simulation(tr, X):
+    """The pool after every slot, counted from scratch: numpy, no code shared with the oracle."""
+    L, N, P = X.shape
+    cur = np.zeros((L, P), bool)
+    tab = np.zeros((N, L), np.int64)
+    for n in range(N):
+        keep = tr.persist[n].astype(bool) if n > 0 else np.zeros(P, bool)
+        cur &= keep[None]
+        for l in range(L):
+            cur[l] = X[l, n].astype(bool) & tr.alive[n].astype(bool)
+            tab[n, l] = cur.sum()
+    return tab
+
+
+def test_slot_occupancy_by_hand():
+    tr = _mini(L=2, N=2, P=1, cap=1)
+    tr.alive[:] = 1
+    tr.persist[1:] = 1
+    X = np.zeros((2, 2, 1), np.uint8)
+    X[1, 0, 0] = 1
+    X[0, 1, 0] = 1                                   # layer 0 takes its page before layer 1 lets go
+    assert O.slot_occupancy(tr, X).tolist() == [[0, 1], [2, 1]]
+    Y = np.zeros((2, 2, 1), np.uint8)
+    Y[0, 0, 0] = 1
+    Y[1, 1, 0] = 1                                   # layer 0 lets go before layer 1 takes
+    assert O.slot_occupancy(tr, Y).tolist() == [[1, 1], [0, 1]]
+    tr.persist[1, 0] = 0                             # the page is replaced at step 1: gone before slot (1, 0)
+    assert O.slot_occupancy(tr, X).tolist() == [[0, 1], [1, 1]]
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_slot_occupancy_against_simulation_and_the_two_excess_counts(seed):
+    tr = W.random_trace(300 + seed, L=[1, 2, 3, 5, 4][seed], N=17, P=23, K=1, rebirth=True)
+    for X in W.random_placements(tr, 4, seed=seed, density=0.5, feasible=False):
+        tab = O.slot_occupancy(tr, X)
+        assert (tab == _slot_table_by_simulation(tr, X)).all()
+        assert (tab[:, -1] == O.score(tr, X).occ).all()                      # the last slot of a step is the step
+        assert max(int(tab.max()) - tr.cap_pages, 0) == O.strict_excess(tr, X)
+
+
+def _one_page_per_layer(L, N, cap=1):
+    tr = _mini(L=L, N=N, P=1, cap=cap)
+    tr.alive[:] = 1
+    tr.persist[1:] = 1
+    tr.access[:] = 1
+    return tr
+
+
+def test_per_slot_moves_by_hand():
+    # two layers, one page each, room for one; layer 1 holds its page at step 0 only.
+    # slots: step 0 [0 1], step 1 [1 0] (layer 1 lets go at slot (1,1)), step 2 [0 0]
+    tr = _one_page_per_layer(2, 3)
+    X = np.zeros((2, 3, 1), np.uint8)
+    X[1, 0, 0] = 1
+    assert O.slot_occupancy(tr, X).tolist() == [[0, 1], [1, 0], [0, 0]]
+    # layer 0 in at step 1: the step as a whole has room, slot (1,0) has not
+    assert O.resolve(tr, X, _move(0, 0, 0, 1, 1))[0] == 0
+    v, f1, f2, _ = O.resolve(tr, X, _move(0, 0, 0, 1, 1), per_slot=True)
+    assert v == 2 and not f1.any()
+    # layer 1 in at steps 1 and 2: slot (1,1) has room, and so has (2,0), where the page is still held
+    v, f1, f2, _ = O.resolve(tr, X, _move(0, 1, 0, 1, 2), per_slot=True)
+    assert v == 0 and f1.tolist() == [0, 1, 1] and not f2.any()
+    # layer 0 in at step 2: nothing is held there
+    v, f1, f2, _ = O.resolve(tr, X, _move(0, 0, 0, 2, 1), per_slot=True)
+    assert v == 0 and f1.tolist() == [0, 0, 1]
+    # layer 0 in at step 0: slot (0,1) would hold two
+    v, f1, f2, _ = O.resolve(tr, X, _move(0, 0, 0, 0, 1), per_slot=True)
+    assert v == 2
+    # a run that starts on a free slot stops at the blocked one: steps 2.. of layer 0 from step 2 only
+    X2 = X.copy(); X2[1, 2, 0] = 1                   # layer 1 back in at step 2: slots step 2 [0 1]
+    v, f1, f2, _ = O.resolve(tr, X2, _move(0, 0, 0, 1, 2), per_slot=True)
+    assert v == 2                                     # step 1 blocked at once: nothing flips
+
+
+def test_per_slot_eviction_by_hand():
+    # three layers, one page each, room for one
+    tr = _one_page_per_layer(3, 2)
+    X = np.zeros((3, 2, 1), np.uint8)
+    X[2, :, 0] = 1                                   # the last layer holds its page throughout
+    assert O.slot_occupancy(tr, X).tolist() == [[0, 0, 1], [1, 1, 1]]
+    mv = _move(1, 0, 0, 1, 1, 2, 0)                  # layer 0 in at step 1, evicting layer 2's page
+    v, f1, f2, _ = O.resolve(tr, X, mv)
+    assert v == 0 and f1.tolist() == [0, 1] and f2.tolist() == [0, 1]      # the step as a whole: one in, one out
+    v, f1, f2, _ = O.resolve(tr, X, mv, per_slot=True)
+    assert v == 2 and not f1.any() and not f2.any()  # slots (1,0), (1,1) would hold both: the victim leaves too late
+    Y = np.zeros((3, 2, 1), np.uint8)
+    Y[0, :, 0] = 1                                   # now the first layer holds its page
+    assert O.slot_occupancy(tr, Y).tolist() == [[1, 1, 1], [1, 1, 1]]
+    v, f1, f2, _ = O.resolve(tr, Y, _move(1, 2, 0, 1, 1, 0, 0), per_slot=True)
+    assert v == 0 and f1.tolist() == [0, 1] and f2.tolist() == [0, 1]      # the victim leaves at slot (1,0), first
+    # the same at step 0: layer 2's page would still be held at slot (1,0), where layer 0 takes its page back
+    assert O.resolve(tr, Y, _move(1, 2, 0, 0, 1, 0, 0))[0] == 0
+    assert O.resolve(tr, Y, _move(1, 2, 0, 0, 1, 0, 0), per_slot=True)[0] == 2
+    # unless layer 2's page is replaced at step 1 and so does not carry over
+    tr.persist[1, 0] = 0
+    v, f1, f2, _ = O.resolve(tr, Y, _move(1, 2, 0, 0, 1, 0, 0), per_slot=True)
+    assert v == 0 and f1.tolist() == [1, 0] and f2.tolist() == [1, 0]
+
+
+def test_per_slot_eviction_relief_by_hand():
+    # victim in the page's own layer: it leaves in the very slot in which the page comes
+    tr = _mini(L=1, N=1, P=2, cap=1)
+    tr.alive[:] = 1
+    X = np.zeros((1, 1, 2), np.uint8)
+    X[0, 0, 0] = 1
+    v, f1, f2, _ = O.resolve(tr, X, _move(1, 0, 1, 0, 1, 0, 0), per_slot=True)
+    assert v == 0 and f1.tolist() == [1] and f2.tolist() == [1]
+    # a victim that is replaced at the next step frees nothing there: it would have been gone anyway.
+    # Two layers, two pages, room for one; page 0 carries over into step 1, page 1 holds new data at step 1.
+    t2 = _mini(L=2, N=2, P=2, cap=1)
+    t2.alive[:] = 1
+    t2.persist[1, 0] = 1
+    X = np.zeros((2, 2, 2), np.uint8)
+    X[1, 0, 1] = 1                                   # step 0: layer 1 holds page 1 (the victim)
+    X[0, 1, 1] = 1                                   # step 1: layer 0 holds page 1
+    assert O.slot_occupancy(t2, X).tolist() == [[0, 1], [1, 1]]
+    mv = _move(1, 1, 0, 0, 1, 1, 1)                  # layer 1: page 0 in at step 0 for page 1
+    assert O.resolve(t2, X, mv)[0] == 0              # each step as a whole holds one page
+    v, f1, f2, _ = O.resolve(t2, X, mv, per_slot=True)
+    assert v == 2 and not f1.any()                   # page 0 of layer 1 would still be held at slot (1,0)
+    Y = X.copy(); Y[1, 0, 1] = 0; Y[1, 0, 0] = 1
+    assert O.score(t2, Y).excess == 0 and O.strict_excess(t2, Y) == 1
+    t2.persist[1, 1] = 1                             # if page 1 carried over too, its leaving would free slot (1,0)...
+    assert O.slot_occupancy(t2, X).tolist() == [[0, 1], [2, 1]]       # ...but then the start itself overfills it
+    X[0, 1, 1] = 0; X[0, 1, 0] = 1                   # layer 0 holds page 0 at step 1 instead: slots [[0 1] [2 1]] still
+    X[1, 0, 1] = 1
+    t2.cap_pages = 2
+    # room for two.  Without the eviction slot (1,0) would hold three (layer 0's page, and pages 0 and 1 of
+    # layer 1 carried over); with it the victim's leaving frees that slot as well: two
+    v, f1, f2, _ = O.resolve(t2, X, mv, per_slot=True)
+    assert v == 0 and f1.tolist() == [1, 0] and f2.tolist() == [1, 0]
+    Y = X.copy(); Y[1, 0, 1] = 0; Y[1, 0, 0] = 1
+    assert O.slot_occupancy(t2, Y).tolist() == [[0, 1], [2, 1]]
+
+
+def _all_moves(tr, rng, count):
+    for _ in range(count):
+        yield _move(int(rng.integers(0, 3)), int(rng.integers(tr.L)), int(rng.integers(tr.P)), int(rng.integers(tr.N)),
+                    int(rng.integers(1, 6)), int(rng.integers(tr.L)), int(rng.integers(tr.P)), int(rng.integers(4)))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_per_slot_moves_never_overfill_a_slot_and_single_bits_match_brute_force(seed):
+    rng = np.random.default_rng(seed)
+    tr = W.random_trace(400 + seed, L=[2, 3, 4][seed % 3], N=9, P=7, K=1, rebirth=bool(seed % 2))
+    tr.cap_pages = int(rng.integers(1, 6))
+    X = np.zeros((tr.L, tr.N, tr.P), np.uint8)
+    applied = blocked = 0
+    for mv in _all_moves(tr, rng, 1500):
+        assert O.strict_excess(tr, X) == 0
+        v, f1, f2, _ = O.resolve(tr, X, mv, per_slot=True)
+        l, p, n1 = mv["layer"], mv["page"], mv["n1"]
+        if mv["op"] == 0 and mv["len"] == 1 and tr.alive[n1, p] and not X[l, n1, p]:
+            Y = X.copy(); Y[l, n1, p] = 1                # one bit set: allowed exactly when no slot overflows
+            assert (v == 0) == (O.strict_excess(tr, Y) == 0)
+            blocked += v != 0
+        if v == 2:
+            continue
+        Y = X.copy()
+        Y[l, :, p] ^= f1
+        Y[mv["layer2"], :, mv["page2"]] ^= f2
+        assert O.strict_excess(tr, Y) == 0, mv
+        assert not (Y & ~tr.alive[None]).any()
+        if rng.random() < 0.7:
+            X = Y; applied += 1
+    assert applied > 100 and blocked > 0
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_per_slot_optimum_is_no_better_than_per_step_optimum_by_brute_force(seed):
+    tr = W.random_trace(500 + seed, L=2, N=3, P=2, K=1, rebirth=False)
+    tr.alive[:] = 1; tr.persist[1:] = 1                  # 12 bits: every schedule is enumerated
+    tr.cap_pages = 1 + seed % 2
+    best_step, _, _ = O.brute_force(tr)
+    best_slot, n_slot, n_step = math.inf, 0, 0
+    for code in range(1 << 12):
+        X = np.array([(code >> i) & 1 for i in range(12)], np.uint8).reshape(2, 3, 2)
+        sc = O.score(tr, X)
+        if sc.excess:
+            assert O.strict_excess(tr, X) > 0            # a full step is a full slot
+            continue
+        n_step += 1
+        if O.strict_excess(tr, X) == 0:
+            n_slot += 1
+            best_slot = min(best_slot, sc.cost)
+    assert 0 < n_slot < n_step                           # the slot reading really forbids some schedules
+    assert best_slot >= best_step
+    # the walk under the slot reading stays inside its set and cannot beat its optimum
+    r = O.anneal_chain(tr, 0, np.zeros((2, 3, 2), np.uint8), seed=seed, total_moves=400, n_levels=10, max_len=3, per_slot=True)
+    assert O.strict_excess(tr, r.best_X) == 0 and O.strict_excess(tr, r.X) == 0
+    assert r.best_cost >= best_slot
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_per_slot_walk_keeps_every_slot_within_capacity(seed):
+    tr = W.random_trace(600 + seed, L=3, N=30, P=19, K=1, rebirth=True)
+    X0 = [np.zeros((tr.L, tr.N, tr.P), np.uint8), O.init_static_frequency(tr)][seed % 2]
+    a = O.anneal_chain(tr, seed, X0, seed=11 + seed, total_moves=1500, n_levels=10, max_len=7, per_slot=True)
+    b = O.anneal_chain(tr, seed, X0, seed=11 + seed, total_moves=1500, n_levels=10, max_len=7)
+    assert O.strict_excess(tr, a.X) == 0 and O.strict_excess(tr, a.best_X) == 0
+    assert a.accepted > 50 and a.best_cost <= O.cost(tr, X0) and (seed % 2 or a.best_cost < O.cost(tr, X0))
+    assert a.T_cur == pytest.approx(O.cost(tr, a.X), rel=1e-12)
+    assert (a.X != b.X).any()                            # the two readings walk apart
+    # a start that overfills a slot is refused, though every step as a whole fits
+    t2 = _one_page_per_layer(2, 2)
+    bad = np.zeros((2, 2, 1), np.uint8); bad[1, 0, 0] = 1; bad[0, 1, 0] = 1
+    O.anneal_chain(t2, 0, bad, seed=1, total_moves=10, n_levels=1)
+    with pytest.raises(ValueError):
+        O.anneal_chain(t2, 0, bad, seed=1, total_moves=10, n_levels=1, per_slot=True)
+
+
 # ---- token-granular reads inside pages: the plane encoding against the token-level definition ----
 
 def _token_trace(seed=9):
