@@ -228,6 +228,25 @@ int kvp_exchange(kvp_ctx *ctx, uint64_t round, uint32_t *h_traded);
  * KVP_EINVAL. */
 int kvp_set_anneal_lookahead(kvp_ctx *ctx, int proposals_per_round);
 
+/* Which reading of Eq. 5 the walks of kvp_anneal honour (Sec. III-A: a decision S(n, l) is made at
+ * every inference step, layer l of token step n).
+ *   KVP_CAPACITY_PER_STEP (default)  the pool is counted once per token step, when all layers have
+ *       taken their placement of that step: what kvp_score's excess reports.
+ *   KVP_CAPACITY_PER_SLOT            the pool is counted after every inference step: what
+ *       kvp_strict_excess reports.  A move sets the bit of (l, p) at step n only if no slot
+ *       (n, l' >= l) and, when the page persists into n + 1, no slot (n + 1, l' < l) (where layer l
+ *       still holds its placement of step n) would exceed cap_pages; a SWAP's victim (l2, q) counts
+ *       as gone from the slots (n, l' >= l2) and, if it persists, (n + 1, l' < l2).  Every step of a
+ *       move is judged against the schedule before the move.  Starting schedules must fit every
+ *       slot (KVP_EINFEASIBLE); every schedule the walk visits then does.  One wavefront per chain
+ *       prices one proposal after the other (the lookahead knob is not used); per chain L*N*4
+ *       more bytes of device memory.
+ * The mode is read by the next fresh start of kvp_anneal; KVP_INIT_CONTINUE under another mode than
+ * the chains were started with is KVP_EINVAL.  kvp_delta_score always clips per token step.
+ * Errors: KVP_EINVAL (null ctx, unknown mode). */
+enum { KVP_CAPACITY_PER_STEP = 0, KVP_CAPACITY_PER_SLOT = 1 };
+int kvp_set_capacity_mode(kvp_ctx *ctx, int mode);
+
 /* Sec. III-B: run params->moves annealing moves on every chain.  d_init is
  * [C][L][N][Wd] (KVP_INIT_GIVEN), [L][N][Wd] (KVP_INIT_BROADCAST) or NULL.
  * Starting schedules must be admissible (checked, KVP_EINFEASIBLE) and are

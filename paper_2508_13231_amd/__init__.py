@@ -23,13 +23,14 @@ KVP_OK, KVP_EINVAL, KVP_ENOTRACE, KVP_ENOMEM, KVP_EHIP = 0, -1, -2, -3, -4
 KVP_ESHAPE, KVP_ETRACE, KVP_ENOCHAINS, KVP_EINFEASIBLE = -5, -6, -7, -8
 KVP_MAX_LEN = 63
 KVP_INIT_EMPTY, KVP_INIT_GIVEN, KVP_INIT_BROADCAST, KVP_INIT_CONTINUE = 0, 1, 2, 3
+KVP_CAPACITY_PER_STEP, KVP_CAPACITY_PER_SLOT = 0, 1
 KVP_OP_SET, KVP_OP_SWAP, KVP_OP_SHIFT = 0, 1, 2              # kvp_move.op
 KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2       # verdicts of kvp_delta_score
 KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2
 
 EXPORTS = ["kvp_create", "kvp_destroy", "kvp_trace_upload", "kvp_score", "kvp_delta_score", "kvp_anneal",
            "kvp_best", "kvp_chain_placement", "kvp_chain_stats", "kvp_plane_unit", "kvp_strerror", "kvp_last_hip_error",
-           "kvp_set_score_kernel", "kvp_set_anneal_lookahead", "kvp_score_kernel_used", "kvp_baseline", "kvp_wr_policy",
+           "kvp_set_score_kernel", "kvp_set_anneal_lookahead", "kvp_set_capacity_mode", "kvp_score_kernel_used", "kvp_baseline", "kvp_wr_policy",
            "kvp_wr_search", "kvp_strict_excess", "kvp_temper", "kvp_exchange", "kvp_score_static"]
 KVP_STATIC_SCRATCH_BYTES = 32 << 20
 
@@ -124,6 +125,8 @@ def lib():
         L.kvp_exchange.argtypes = [vp, C.c_uint64, vp]
         L.kvp_set_anneal_lookahead.restype = i32
         L.kvp_set_anneal_lookahead.argtypes = [vp, i32]
+        L.kvp_set_capacity_mode.restype = i32
+        L.kvp_set_capacity_mode.argtypes = [vp, i32]
         L.kvp_set_score_kernel.restype = i32
         L.kvp_set_score_kernel.argtypes = [vp, i32]
         L.kvp_wr_policy.restype = i32
@@ -257,6 +260,10 @@ def kvp_exchange(ctx, round: int, count: bool = True) -> int:
     n = C.c_uint32(0)
     _check(lib().kvp_exchange(ctx, int(round), C.byref(n) if count else None), "kvp_exchange")
     return int(n.value) if count else -1
+
+
+def kvp_set_capacity_mode(ctx, mode: int):
+    _check(lib().kvp_set_capacity_mode(ctx, int(mode)), "kvp_set_capacity_mode")
 
 
 def kvp_set_anneal_lookahead(ctx, proposals_per_round: int):

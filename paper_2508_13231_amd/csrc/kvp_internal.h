@@ -56,6 +56,9 @@ struct kvp_ctx {
     int score_kernel = 0;                // KVP_SCORE_AUTO, or the scorer kvp_score tries first
     uint32_t compute_units = 1;          // of the context's GPU
     int anneal_lookahead = 0;            // proposals per round in kvp_anneal: 0 auto, 1 or 4
+    int capacity_mode = 0;               // KVP_CAPACITY_*: what the next fresh start of kvp_anneal walks under
+    int chains_mode = 0;                 // what the present chains walk under
+    uint32_t *d_slot = nullptr;          // per-slot mode: [C][L][N], the pool after every slot of every chain
     bool no_alloc = false;               // set while kvp_score_static runs: kvp_ensure must not allocate
     int last_kernel = 0;                 // scorer that the last kvp_score ran (KVP_SCORE_*), 0 before the first
     bool prefix_full = false;            // on every 64-step tile all mask words but the last are FULL
@@ -246,5 +249,6 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
 int kvp_ensure(kvp_ctx *ctx, void **p, size_t *cap, size_t bytes);
 int kvp_static_scratch_init(int device);     // kvp_score.hip: resolves the device address of the static scratch
 int kvp_bitslice_build(kvp_ctx *ctx);
+int kvp_slot_occupancy_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, uint32_t *d_excess, uint32_t *d_table);
 int kvp_rowlane_build(kvp_ctx *ctx);          // kvp_score_rowlane.hip: called at the end of kvp_bitslice_build
 void kvp_free_chains(kvp_ctx *ctx);

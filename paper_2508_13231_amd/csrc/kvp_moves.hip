@@ -154,9 +154,17 @@ __device__ __forceinline__ MoveLoads<NP> issue_move(const DevProblem &q, const u
 // Resolve a raw move against the schedule X (with its counters and occupancy)
 // and price it, from the words that issue_move requested.  All 64 lanes of the
 // wavefront must call this together.
-template <int NP, bool OCC_LATE = false>
+// SLOT: the capacity holds at every inference step (n, l), not only once per token step: slot is
+// the chain's table [L][N] of the pool after every slot, and a step may take the page if no slot of
+// the two token steps that the bit reaches ends above the capacity: the bit of (l, p) at step n is
+// part of the pool in the slots (n, l' >= l) and, if the page persists, (n + 1, l' < l), where layer l
+// still holds its placement of step n.  An evicted victim (l2, q) leaves the slots (n, l' >= l2) and,
+// if it persists, (n + 1, l' < l2).  Every step is judged against the schedule before the move: two
+// steps of one run add to different slots, so no slot gains more than the one page it was judged for.
+template <int NP, bool OCC_LATE = false, bool SLOT = false>
 __device__ __forceinline__ MoveEval finish_move(const DevProblem &q, const uint32_t *X, const uint32_t *cnt,
-                                                const uint32_t *occ, const kvp_move &m, int lane, MoveLoads<NP> &Ld) {
+                                                const uint32_t *occ, const kvp_move &m, int lane, MoveLoads<NP> &Ld,
+                                                const uint32_t *slot = nullptr) {
     MoveEval R;
     R.verdict = KVP_MOVE_NULL; R.dT = 0.0; R.base = 0; R.flip1 = R.flip2 = 0; R.second = false;
     R.n = -1; R.f1 = R.f2 = R.touch1 = R.touch2 = R.xnew = false;
@@ -181,6 +189,27 @@ __device__ __forceinline__ MoveEval finish_move(const DevProblem &q, const uint3
     bool inb = n < (int)N;
     uint32_t nc = inb ? (uint32_t)n : N - 1;
     if (OCC_LATE) oc = occ[nc];
+    // may this lane's step take the page: as it is (room), or with the victim leaving (evict_fit)
+    bool room = false, evict_fit = true;
+    auto judge = [&]() {
+        if (!SLOT) { room = oc < cap; return; }
+        // largest pool over the slots that gain the page: a1, a2 of step nc (layers below l2, from l2 on),
+        // b1, b2 of step nc + 1 (layers from l2 on, below l2); -1: no such slot
+        int a1 = -1, a2 = -1, b1 = -1, b2 = -1;
+        const bool nxt = inb && nc + 1 < N;
+        const uint32_t nn = nxt ? nc + 1 : nc;
+        for (uint32_t lp = 0; lp < L; lp++) {
+            const int a = (int)slot[(size_t)lp * N + nc], b = (int)slot[(size_t)lp * N + nn];
+            if (lp >= l) { if (lp >= l2) a2 = max(a2, a); else a1 = max(a1, a); }
+            else { if (lp < l2) b2 = max(b2, b); else b1 = max(b1, b); }
+        }
+        const bool pers_p = nxt && ((q.Pm[(size_t)nn * q.Wd + wp] >> bp) & 1u);
+        const bool pers_q = nxt && ((q.Pm[(size_t)nn * q.Wd + (m.page2 >> 5)] >> bq) & 1u);
+        const int64_t c = (int64_t)cap;
+        room = (int64_t)max(a1, a2) + 1 <= c && (!pers_p || (int64_t)max(b1, b2) + 1 <= c);
+        evict_fit = (int64_t)a1 + 1 <= c && (int64_t)a2 <= c &&
+                    (!pers_p || ((int64_t)b1 + 1 <= c && (int64_t)b2 + (pers_q ? 0 : 1) <= c));
+    };
     PageBits P = page_bits<NP>(q, gp, nc, inb, bp);
     PageBits Q = swap ? page_bits<NP>(q, gq, nc, inb, bq) : P;
     if (!(ballot64(P.v) & 1ull)) return R;                 // the page does not exist at n1
@@ -190,6 +219,7 @@ __device__ __forceinline__ MoveEval finish_move(const DevProblem &q, const uint3
     int base = (int)n1;
 
     if (m.op != KVP_OP_SHIFT) {
+        judge();
         const bool cont = lane == 0 || (inb && (uint32_t)lane < len && P.pm);
         const uint64_t bad = ballot64(!cont);
         const int e = bad ? ctz64(bad) : 64;
@@ -198,7 +228,7 @@ __device__ __forceinline__ MoveEval finish_move(const DevProblem &q, const uint3
             const bool v = !x1;
             const bool differ = in_span && (P.x != v);
             if (v) {
-                const uint64_t stop = ballot64(differ && oc >= cap);
+                const uint64_t stop = ballot64(differ && !room);
                 const int fs = stop ? ctz64(stop) : 64;
                 f1 = differ && lane < fs;
                 clipped = stop != 0;
@@ -208,8 +238,7 @@ __device__ __forceinline__ MoveEval finish_move(const DevProblem &q, const uint3
         } else {
             const bool victim_ok = !(same_layer && m.page2 == m.page);
             const bool cand = in_span && !P.x;
-            const bool room = oc < cap;
-            const bool evict = cand && !room && victim_ok && Q.x;
+            const bool evict = cand && !room && victim_ok && Q.x && evict_fit;
             f1 = cand && (room || evict);
             f2 = evict;
             clipped = ballot64(cand && !room && !evict) != 0;
@@ -250,10 +279,11 @@ __device__ __forceinline__ MoveEval finish_move(const DevProblem &q, const uint3
             arrive(gp);
         }
         P = page_bits<NP>(q, gp, nc, inb, bp);
+        judge();
         if (d < 0) {
             const bool target = lane == 1 || (lane == 0 && d == -2 && it >= 2);   // steps hold a, take not(a)
             if (!a) {
-                const uint64_t full = ballot64(target && oc >= cap);
+                const uint64_t full = ballot64(target && !room);
                 const int hs = full ? msb64(full) : -1;
                 f1 = target && lane > hs;
                 clipped = full != 0;
@@ -264,7 +294,7 @@ __device__ __forceinline__ MoveEval finish_move(const DevProblem &q, const uint3
             const bool target = lane == 2 || (lane == 3 && d == 2 && inb && P.pm);
             const bool differ = target && (P.x != a);
             if (a) {
-                const uint64_t stop = ballot64(differ && oc >= cap);
+                const uint64_t stop = ballot64(differ && !room);
                 const int fs = stop ? ctz64(stop) : 64;
                 f1 = differ && lane < fs;
                 clipped = stop != 0;
@@ -440,8 +470,9 @@ __device__ __forceinline__ void next_move(const DevProblem &q, const SAParams &s
 // Write an accepted move into the chain's schedule, counters and occupancy.  Every lane owns one
 // step of the window, so no two lanes write the same word; the new words are made from the ones the
 // move was priced on, so nothing is read back from memory here.
+template <bool SLOT = false>
 __device__ __forceinline__ void apply_move(const DevProblem &q, uint32_t *X, uint32_t *cnt, uint32_t *occ,
-                                           const kvp_move &m, const MoveEval &R) {
+                                           const kvp_move &m, const MoveEval &R, uint32_t *slot = nullptr) {
     const bool same_word = m.layer == m.layer2 && (m.page >> 5) == (m.page2 >> 5);
     uint32_t w1 = R.xw1, w2 = R.xw2;
     if (R.f1) w1 ^= 1u << (m.page & 31);
@@ -451,17 +482,38 @@ __device__ __forceinline__ void apply_move(const DevProblem &q, uint32_t *X, uin
     if (R.touch1) *(uint4 *)(cnt + ((size_t)m.layer * q.N + R.n) * 4) = R.c1;
     if (R.touch2) *(uint4 *)(cnt + ((size_t)m.layer2 * q.N + R.n) * 4) = R.c2;
     if (R.f1 && !R.f2) occ[R.n] = R.oc + (R.xnew ? 1u : 0xFFFFFFFFu);
+    if (SLOT) {
+        // the table of the pool after every slot: a lane's step n gains or loses the page in the slots
+        // l' >= layer from its own flip and in the slots l' < layer from the flip of the step before
+        // (the bit of step n - 1 is still held there if the page persists into n); the same for the victim.
+        const int lane = lane_id();
+        const uint64_t xn = ballot64(R.xnew);
+        const bool fp1 = lane > 0 && ((R.flip1 >> (lane - 1)) & 1ull), fp2 = lane > 0 && ((R.flip2 >> (lane - 1)) & 1ull);
+        if (R.n >= 0 && (R.f1 || R.f2 || fp1 || fp2)) {
+            const uint32_t n = (uint32_t)R.n;
+            const bool pers_p = (q.Pm[(size_t)n * q.Wd + (m.page >> 5)] >> (m.page & 31)) & 1u;
+            const bool pers_q = (q.Pm[(size_t)n * q.Wd + (m.page2 >> 5)] >> (m.page2 & 31)) & 1u;
+            const int own1 = R.f1 ? (R.xnew ? 1 : -1) : 0, own2 = R.f2 ? -1 : 0;
+            const int prev1 = fp1 && pers_p ? (((xn >> (lane - 1)) & 1ull) ? 1 : -1) : 0, prev2 = fp2 && pers_q ? -1 : 0;
+            for (uint32_t lp = 0; lp < q.L; lp++) {
+                const int dl = (lp >= m.layer ? own1 : prev1) + (lp >= m.layer2 ? own2 : prev2);
+                if (dl) slot[(size_t)lp * q.N + n] += (uint32_t)dl;
+            }
+        }
+    }
 }
 
 // ---- the annealing loop: one wavefront per chain --------------------------------
-template <int NP>
+template <int NP, bool SLOT = false>
 __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams sp, uint32_t *__restrict__ Xall,
                                                           uint32_t *__restrict__ cnt_all,
                                                           uint32_t *__restrict__ occ_all,
                                                           ChainState *__restrict__ states,
                                                           uint32_t *__restrict__ log_all, uint64_t log_cap,
-                                                          uint64_t move_begin, uint64_t move_end, int calibrate) {
+                                                          uint64_t move_begin, uint64_t move_end, int calibrate,
+                                                          uint32_t *slot_all = nullptr) {
     const uint32_t chain = blockIdx.x;
+    uint32_t *slot = SLOT ? slot_all + (size_t)chain * q.L * q.N : nullptr;
     const int lane = (int)threadIdx.x;
     const size_t rows = (size_t)q.L * q.N;
     uint32_t *X = Xall + (size_t)chain * rows * q.Wd;
@@ -488,7 +540,9 @@ __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams
         fill_draws(sp, chain, 0, 8, lane, B);
         take_move(q, sp, B, 0, m, u);
         for (uint64_t j = 0; j < CALIB_MOVES; j++) {
-            const MoveEval R = eval_move<NP>(q, X, cnt, occ, m, lane, [&] { next_move(q, sp, chain, 8, lane, B, j + 1, mn, un); });
+            MoveLoads<NP> Ld = issue_move<NP>(q, X, cnt, occ, m, lane);
+            next_move(q, sp, chain, 8, lane, B, j + 1, mn, un);
+            const MoveEval R = finish_move<NP, false, SLOT>(q, X, cnt, occ, m, lane, Ld, slot);
             m = mn;
             if (R.verdict != KVP_MOVE_NULL && R.dT > 0.0) { sum = sum + R.dT; k++; }
         }
@@ -515,7 +569,7 @@ __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams
         MoveLoads<NP> Ln = issue_move<NP>(q, X, cnt, occ, m_nxt, lane);
         const kvp_move m = m_cur;
         const double u = u_cur;
-        const MoveEval R = finish_move<NP>(q, X, cnt, occ, m, lane, Lc);
+        const MoveEval R = finish_move<NP, false, SLOT>(q, X, cnt, occ, m, lane, Lc, slot);
         st.moves_done++;
         bool accept = false;
         if (R.verdict == KVP_MOVE_NULL) {
@@ -527,7 +581,7 @@ __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams
         if (accept) {
             st.accepted++;
             if (R.dT > 0.0) st.uphill++;
-            apply_move(q, X, cnt, occ, m, R);
+            apply_move<SLOT>(q, X, cnt, occ, m, R, slot);
             st.t_cur = st.t_cur + R.dT;
             // edits since the best schedule, so that it can be rebuilt by undoing them
             if (st.log_len < log_cap) {
@@ -830,6 +884,7 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
     if (p->init_mode == KVP_INIT_CONTINUE) {
         if (!ctx->has_chains) return KVP_ENOCHAINS;
         if (!same_schedule(*p, ctx->sa)) return KVP_EINVAL;
+        if (ctx->capacity_mode != ctx->chains_mode) return KVP_EINVAL;   // the chains walk on under the reading they started with
         if (ctx->moves_done + p->moves > p->total_moves) return KVP_EINVAL;
     } else {
         if (p->moves > p->total_moves) return KVP_EINVAL;            // before the previous chains are given up
@@ -867,6 +922,27 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
         free(hex);
         if (e != hipSuccess) { kvp_free_chains(ctx); return KVP_EHIP; }
         if (bad) { kvp_free_chains(ctx); return KVP_EINFEASIBLE; }
+        if (ctx->capacity_mode == KVP_CAPACITY_PER_SLOT) {
+            // the pool after every slot of every chain; a start that overfills a slot is refused
+            const hipError_t ea = hipMalloc((void **)&ctx->d_slot, rows * C * 4);
+            if (ea != hipSuccess) {
+                kvp_tls_hip_error = (int)ea; kvp_tls_hip_line = __LINE__;
+                (void)hipGetLastError();
+                kvp_free_chains(ctx);
+                return ea == hipErrorOutOfMemory ? KVP_ENOMEM : KVP_EHIP;
+            }
+            rc = kvp_slot_occupancy_launch(ctx, ctx->d_X, C, ctx->d_excess, ctx->d_slot);
+            if (rc) { kvp_free_chains(ctx); return rc; }
+            hex = (uint32_t *)malloc(4 * (size_t)C);
+            if (!hex) { kvp_free_chains(ctx); return KVP_ENOMEM; }
+            e = hipMemcpyAsync(hex, ctx->d_excess, 4 * (size_t)C, hipMemcpyDeviceToHost, ctx->stream);
+            if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+            for (uint32_t c = 0; c < C && e == hipSuccess; c++) bad = bad || hex[c] != 0;
+            free(hex);
+            if (e != hipSuccess) { kvp_free_chains(ctx); return KVP_EHIP; }
+            if (bad) { kvp_free_chains(ctx); return KVP_EINFEASIBLE; }
+        }
+        ctx->chains_mode = ctx->capacity_mode;
         init_states_kernel<<<dim3((C + 255) / 256), dim3(256), 0, ctx->stream>>>(ctx->d_state, ctx->d_cost, C);
         KVP_HIP(hipGetLastError());
         ctx->sa = *p;
@@ -885,8 +961,21 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
     uint64_t m0 = ctx->moves_done;
     const uint64_t m_end = m0 + p->moves;
     bool first = ctx->moves_done == 0;
+    const bool per_slot = ctx->chains_mode == KVP_CAPACITY_PER_SLOT;
     auto launch = [&](uint64_t b, uint64_t e, int calibrate) {
         const dim3 grid(C), block(KVP_WAVE);
+        if (per_slot) {
+            if (q.pn == 1)
+                anneal_kernel<1, true><<<grid, block, 0, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
+                                                                       ctx->d_log, ctx->log_cap, b, e, calibrate, ctx->d_slot);
+            else if (q.pn <= 4)
+                anneal_kernel<4, true><<<grid, block, 0, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
+                                                                       ctx->d_log, ctx->log_cap, b, e, calibrate, ctx->d_slot);
+            else
+                anneal_kernel<KVP_MAX_PLANES, true><<<grid, block, 0, ctx->stream>>>(
+                    q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state, ctx->d_log, ctx->log_cap, b, e, calibrate, ctx->d_slot);
+            return;
+        }
         if (q.pn == 1)
             anneal_kernel<1><<<grid, block, 0, ctx->stream>>>(q, sp, ctx->d_X, ctx->d_cnt, ctx->d_occ, ctx->d_state,
                                                              ctx->d_log, ctx->log_cap, b, e, calibrate);
@@ -908,6 +997,7 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
         spec = (uint64_t)C * 4 <= 4ull * ctx->compute_units && state <= (256ull << 20) ? 4 : 1;
     }
     if ((size_t)q.N * 4 > 48 * 1024) spec = 1;                         // the rounds keep the occupancy of all steps in LDS
+    if (per_slot) spec = 1;                                            // the per-slot walk is the serial one
     auto launch_rounds = [&](uint64_t b, uint64_t e) {
         const dim3 grid(C), block(4 * KVP_WAVE);
         const size_t lds = (size_t)q.N * 4;                            // the chain's occupancy

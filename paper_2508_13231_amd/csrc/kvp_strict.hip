@@ -37,8 +37,10 @@ __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
     return v;
 }
 
+// table (may be null): [S][L][N], the pool after every slot
 __global__ __launch_bounds__(SW * KVP_WAVE) void strict_excess_kernel(DevProblem q, const uint32_t *__restrict__ X,
-                                                                      uint32_t S, uint32_t *__restrict__ excess) {
+                                                                      uint32_t S, uint32_t *__restrict__ excess,
+                                                                      uint32_t *__restrict__ table) {
     extern __shared__ uint32_t lds_u[];                                // [SW][2][L]
     const int lane = lane_id();
     const uint32_t wave = threadIdx.x / KVP_WAVE;
@@ -71,7 +73,11 @@ __global__ __launch_bounds__(SW * KVP_WAVE) void strict_excess_kernel(DevProblem
         const uint32_t l = base + (uint32_t)lane;
         const uint32_t a = l < L ? cnt_new[l] : 0u, b = l < L ? cnt_old[l] : 0u;
         const uint32_t a_in = wave_incl_scan_u32(a) + new_before, b_in = wave_incl_scan_u32(b) + old_before;
-        if (l < L) worst = max(worst, a_in + (old_total - b_in));      // slot (n, l)
+        if (l < L) {
+            const uint32_t o = a_in + (old_total - b_in);               // slot (n, l)
+            worst = max(worst, o);
+            if (table) table[((size_t)s * L + l) * q.N + n] = o;
+        }
         new_before = (uint32_t)__builtin_amdgcn_readlane((int)a_in, 63);
         old_before = (uint32_t)__builtin_amdgcn_readlane((int)b_in, 63);
     }
@@ -82,12 +88,8 @@ __global__ __launch_bounds__(SW * KVP_WAVE) void strict_excess_kernel(DevProblem
 
 }  // namespace
 
-extern "C" int kvp_strict_excess(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, uint32_t *d_excess) {
-    if (!ctx) return KVP_EINVAL;
-    if (!ctx->has_trace) return KVP_ENOTRACE;
-    if (S == 0) return KVP_OK;
-    if (!d_placements || !d_excess || ((uintptr_t)d_placements & 3u) || ((uintptr_t)d_excess & 3u)) return KVP_EINVAL;
-    KVP_HIP(hipSetDevice(ctx->device));
+// d_excess [S] and, if not null, d_table [S][L][N]; arguments checked by the caller
+int kvp_slot_occupancy_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, uint32_t *d_excess, uint32_t *d_table) {
     const DevProblem &q = ctx->dp;
     const size_t lds = (size_t)SW * 2 * q.L * 4;
     if (lds > 64 * 1024 || (uint64_t)q.L * q.Wd >= (1ull << 31)) return KVP_ESHAPE;
@@ -97,7 +99,16 @@ extern "C" int kvp_strict_excess(kvp_ctx *ctx, const uint32_t *d_placements, uin
     KVP_HIP(hipGetLastError());
     if (lds > 48 * 1024)
         KVP_HIP(hipFuncSetAttribute((const void *)strict_excess_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    strict_excess_kernel<<<dim3((uint32_t)nwg), dim3(SW * KVP_WAVE), lds, ctx->stream>>>(q, d_placements, S, d_excess);
+    strict_excess_kernel<<<dim3((uint32_t)nwg), dim3(SW * KVP_WAVE), lds, ctx->stream>>>(q, d_placements, S, d_excess, d_table);
     KVP_HIP(hipGetLastError());
     return KVP_OK;
+}
+
+extern "C" int kvp_strict_excess(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, uint32_t *d_excess) {
+    if (!ctx) return KVP_EINVAL;
+    if (!ctx->has_trace) return KVP_ENOTRACE;
+    if (S == 0) return KVP_OK;
+    if (!d_placements || !d_excess || ((uintptr_t)d_placements & 3u) || ((uintptr_t)d_excess & 3u)) return KVP_EINVAL;
+    KVP_HIP(hipSetDevice(ctx->device));
+    return kvp_slot_occupancy_launch(ctx, d_placements, S, d_excess, nullptr);
 }

@@ -453,6 +453,90 @@ def test_anneal_resume_and_modes(G):
         assert e.value.code == K.KVP_ENOCHAINS
 
 
+def _strict_excess_gpu(g, X):
+    import torch
+    import paper_2508_13231_amd as K
+    X = np.asarray(X)
+    X = X[None] if X.ndim == 3 else X
+    d = torch.full((len(X),), -1, dtype=torch.int32, device=g.dev)
+    K.kvp_strict_excess(g.ctx, g.words(X), len(X), d)
+    torch.cuda.synchronize()
+    return d.cpu().numpy().view(np.uint32).tolist()
+
+
+@pytest.mark.parametrize("name,scale,chains,total,max_len,start", [("tiny", 1.0, 4, 3000, 63, "static"),
+                                                                   ("tiny", 1.0, 3, 2000, 7, "empty"),
+                                                                   ("table1", 1.0, 3, 1500, 5, "empty"),
+                                                                   ("llama8b", 0.125, 3, 2500, 63, "static"),
+                                                                   ("serving", 0.0625, 3, 2500, 31, "static"),
+                                                                   ("gqa70b", 0.0625, 2, 2000, 63, "empty"),
+                                                                   ("tok-p16", None, 2, 2000, 63, "static"),
+                                                                   ("rand-tiles", None, 3, 2500, 63, "empty")])
+def test_per_slot_walk_against_oracle(G, name, scale, chains, total, max_len, start):
+    """Annealing under the capacity read at every inference step: the same walk as the oracle's, move for move,
+    and no schedule it returns overfills a slot."""
+    import paper_2508_13231_amd as K
+    import dataclasses
+    tr = dict(CASES)[name] if scale is None else W.config(name, scale)
+    if name == "rand-tiles":
+        tr = dataclasses.replace(tr, cap_pages=20)                   # a pool that fills
+    q = O.Problem(tr)
+    X0 = O.init_static_frequency(q) if start == "static" else np.zeros(q.shape, np.uint8)
+    res, bi = O.anneal(q, range(chains), X0, seed=tr.seed + 1, total_moves=total, max_len=max_len, per_slot=True)
+    per_step, _ = O.anneal(q, range(chains), X0, seed=tr.seed + 1, total_moves=total, max_len=max_len)
+    with G(tr) as g:
+        K.kvp_set_capacity_mode(g.ctx, K.KVP_CAPACITY_PER_SLOT)
+        K.kvp_set_anneal_lookahead(g.ctx, 4)                         # ignored under this reading
+        _anneal_gpu(g, tr, chains, total, moves=total // 3, init=X0, seed=tr.seed + 1, max_len=max_len)
+        _anneal_gpu(g, tr, chains, total, moves=total - total // 3, seed=tr.seed + 1, max_len=max_len, mode=K.KVP_INIT_CONTINUE)
+        cost, chain, words, cc = K.kvp_best(g.ctx, g.shape_words, chains)
+        stats = K.kvp_chain_stats(g.ctx, chains)
+        bests = [g.unpack(K.kvp_chain_placement(g.ctx, c, 1, g.shape_words)) for c in range(chains)]
+        curs = [g.unpack(K.kvp_chain_placement(g.ctx, c, 0, g.shape_words)) for c in range(chains)]
+        assert _strict_excess_gpu(g, np.stack(bests + curs).astype(np.uint8)) == [0] * (2 * chains)
+    for c in range(chains):
+        assert (curs[c] == res[c].X).all() and (bests[c] == res[c].best_X).all() and cc[c] == res[c].best_cost, c
+        assert stats[c].accepted == res[c].accepted and stats[c].null_moves == res[c].null_moves
+        assert stats[c].clipped == res[c].clipped and stats[c].c0 == res[c].C0
+        assert O.strict_excess(q, curs[c]) == 0 and O.strict_excess(q, bests[c]) == 0
+    assert chain == bi and cost == res[bi].best_cost
+    # with one layer a slot is a token step and the two readings are one; otherwise they must have walked apart
+    assert any((res[c].X != per_step[c].X).any() for c in range(chains)) == (tr.L > 1)
+
+
+def test_per_slot_mode_errors_and_start_check(G):
+    import paper_2508_13231_amd as K
+    tr = W.config("llama8b", 0.125)
+    q = O.Problem(tr)
+    # a start that fits every token step as a whole and overfills a slot in between: where a walk that
+    # counts per token step ends up
+    r, _ = O.anneal(q, range(1), O.init_static_frequency(q), seed=5, total_moves=2500)
+    cand = [r[0].X]
+    assert O.score(q, cand[0]).excess == 0 and O.strict_excess(q, cand[0]) > 0
+    with G(tr) as g:
+        with pytest.raises(K.KvpError) as e:
+            K.kvp_set_capacity_mode(g.ctx, 2)
+        assert e.value.code == K.KVP_EINVAL
+        _anneal_gpu(g, tr, 2, 500, init=cand[0], seed=1)             # per token step: accepted
+        K.kvp_set_capacity_mode(g.ctx, K.KVP_CAPACITY_PER_SLOT)
+        with pytest.raises(K.KvpError) as e:                         # the chains were started under the other reading
+            _anneal_gpu(g, tr, 2, 500, moves=0, seed=1, mode=K.KVP_INIT_CONTINUE)
+        assert e.value.code == K.KVP_EINVAL
+        with pytest.raises(K.KvpError) as e:
+            _anneal_gpu(g, tr, 2, 500, init=cand[0], seed=1)
+        assert e.value.code == K.KVP_EINFEASIBLE
+        _anneal_gpu(g, tr, 2, 500, moves=100, seed=1)                # from nothing: fine
+        K.kvp_set_capacity_mode(g.ctx, K.KVP_CAPACITY_PER_STEP)
+        with pytest.raises(K.KvpError) as e:
+            _anneal_gpu(g, tr, 2, 500, moves=100, seed=1, mode=K.KVP_INIT_CONTINUE)
+        assert e.value.code == K.KVP_EINVAL
+        K.kvp_set_capacity_mode(g.ctx, K.KVP_CAPACITY_PER_SLOT)
+        _anneal_gpu(g, tr, 2, 500, moves=400, seed=1, mode=K.KVP_INIT_CONTINUE)
+        want, _ = O.anneal(q, range(2), np.zeros(q.shape, np.uint8), seed=1, total_moves=500, per_slot=True)
+        for c in range(2):
+            assert (g.unpack(K.kvp_chain_placement(g.ctx, c, 0, g.shape_words)) == want[c].X).all()
+
+
 def test_error_paths_reach_no_kernel(G):
     import torch
     import paper_2508_13231_amd as K

@@ -144,3 +144,18 @@ def test_random_shape_walks(G, seed):
                 cur = g.unpack(K.kvp_chain_placement(g.ctx, c, 0, g.shape_words))
                 assert (cur == res[c].X).all() and cc[c] == res[c].best_cost, (lookahead, c)
                 assert stats[c].accepted == res[c].accepted and stats[c].null_moves == res[c].null_moves
+    # the same under the capacity read at every inference step, from a start that fits every slot
+    if O.strict_excess(q, X0) != 0:
+        X0 = O.init_static_frequency(q)
+    res, _ = O.anneal(q, range(chains), X0, seed=sa_seed, total_moves=total, max_len=max_len, per_slot=True)
+    with G(tr) as g:
+        K.kvp_set_capacity_mode(g.ctx, K.KVP_CAPACITY_PER_SLOT)
+        p = K.make_anneal_params(chains, total, seed=sa_seed, init_mode=K.KVP_INIT_BROADCAST, max_len=max_len)
+        K.kvp_anneal(g.ctx, p, g.words(X0))
+        _, _, _, cc = K.kvp_best(g.ctx, g.shape_words, chains)
+        stats = K.kvp_chain_stats(g.ctx, chains)
+        for c in range(chains):
+            cur = g.unpack(K.kvp_chain_placement(g.ctx, c, 0, g.shape_words))
+            assert (cur == res[c].X).all() and cc[c] == res[c].best_cost, ("per slot", c)
+            assert stats[c].accepted == res[c].accepted and stats[c].null_moves == res[c].null_moves
+            assert O.strict_excess(q, cur) == 0
