@@ -294,18 +294,22 @@ def _full_trace(name):
 # (config, moves walked of the config's own cooling schedule, chain ids the oracle walks, proposals per round)
 # Configs 0-2 run their whole budget; the oracle makes 1000 moves a second on config 4 and 80 on config 3, so
 # there both sides walk the first part of the schedule (same length of the cooling levels, same start).
-FULL_ANNEAL = [("tiny", None, tuple(range(16)), 0),
-               ("llama8b", None, (0, 1, 2, 3, 31, 32, 63, 64, 100, 127, 128, 200, 253, 254, 255, 17), 0),
-               ("llama8b", 6000, (1, 254), 1),
-               ("longctx", None, (0, 1023), 0),
-               ("gqa70b", 10000, (0, 511), 0),
-               ("serving", 2000, (0, 511), 0)]
+# Last field: the capacity read at every inference step (there the oracle recounts every slot after every
+# accepted move: 300 moves a minute on config 3).
+FULL_ANNEAL = [("tiny", None, tuple(range(16)), 0, False),
+               ("llama8b", None, (0, 1, 2, 3, 31, 32, 63, 64, 100, 127, 128, 200, 253, 254, 255, 17), 0, False),
+               ("llama8b", 6000, (1, 254), 1, False),
+               ("longctx", None, (0, 1023), 0, False),
+               ("gqa70b", 10000, (0, 511), 0, False),
+               ("serving", 2000, (0, 511), 0, False),
+               ("llama8b", 6000, (1, 254), 0, True),
+               ("gqa70b", 300, (0, 511), 0, True)]
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("name,moves,ids,lookahead", FULL_ANNEAL,
-                         ids=[f"{c[0]}-{c[1] or 'whole'}-{len(c[2])}ids" for c in FULL_ANNEAL])
-def test_full_size_anneal_sampled_chains_against_oracle(G, name, moves, ids, lookahead):
+@pytest.mark.parametrize("name,moves,ids,lookahead,per_slot", FULL_ANNEAL,
+                         ids=[f"{c[0]}-{c[1] or 'whole'}-{len(c[2])}ids" + ("-per-slot" if c[4] else "") for c in FULL_ANNEAL])
+def test_full_size_anneal_sampled_chains_against_oracle(G, name, moves, ids, lookahead, per_slot):
     """The launch configuration of each benchmark config: all its chains, its own cooling schedule (move
     budget and levels), the start broadcast.  The oracle walks some of the chain ids and must arrive where the
     GPU's chains of those ids did; the best objective over those ids must agree within 0.5 %."""
@@ -313,14 +317,16 @@ def test_full_size_anneal_sampled_chains_against_oracle(G, name, moves, ids, loo
     tr, q = _full_trace(name)
     total = tr.moves
     moves = total if moves is None else moves
-    if name in ("tiny", "gqa70b", "serving"):
+    if name in ("tiny", "gqa70b", "serving") or per_slot:
         X0 = O.init_static_frequency(q)
     else:
         X0 = W.random_placements(tr, 1, seed=tr.seed, density=0.25)[0]
     print(f"{name}: {tr.chains} chains, {moves} of {total} moves, oracle on chains {ids}", flush=True)
-    res, _ = O.anneal(q, list(ids), X0, threads=min(len(ids), 16), seed=tr.seed, total_moves=total, move_end=moves)
+    res, _ = O.anneal(q, list(ids), X0, threads=min(len(ids), 16), seed=tr.seed, total_moves=total, move_end=moves,
+                      per_slot=per_slot)
     with G(tr) as g:
         K.kvp_set_anneal_lookahead(g.ctx, lookahead)
+        K.kvp_set_capacity_mode(g.ctx, K.KVP_CAPACITY_PER_SLOT if per_slot else K.KVP_CAPACITY_PER_STEP)
         _anneal_gpu(g, tr, tr.chains, total, moves=moves, init=X0, seed=tr.seed)
         cost, chain, words, cc = K.kvp_best(g.ctx, g.shape_words, tr.chains)
         stats = K.kvp_chain_stats(g.ctx, tr.chains)
@@ -340,6 +346,8 @@ def test_full_size_anneal_sampled_chains_against_oracle(G, name, moves, ids, loo
             cur = g.unpack(K.kvp_chain_placement(g.ctx, c, 0, g.shape_words))
             assert (cur == res[i].X).all() and cc[c] == res[i].best_cost, (name, c)   # the same walk, move for move
             assert (stats[c].accepted, stats[c].null_moves) == (res[i].accepted, res[i].null_moves)
+            if per_slot:
+                assert _strict_excess_gpu(g, cur.astype(np.uint8)) == [0]
             del cur
             if c == chain:
                 assert (g.unpack(words) == res[i].best_X).all()
