@@ -353,7 +353,7 @@ int kvp_baseline(kvp_ctx *ctx, int kind, uint32_t *d_placement);
  * window counts and wanted sets of a batch of steps (at least one step's:
  * distinct W x L x Wd x (32 x count bytes + 4)), plus n x L x Wd x 4 bytes.
  * Errors: KVP_EINVAL (null pointer, W = 0, r10 > 10), KVP_ENOTRACE, KVP_ESHAPE
- * (W x planes above 32767), KVP_ENOMEM, KVP_EHIP. */
+ * (W x planes above 16383), KVP_ENOMEM, KVP_EHIP. */
 int kvp_wr_policy(kvp_ctx *ctx, uint32_t n, const uint32_t *h_w, const uint32_t *h_r10, uint32_t *d_placements);
 
 /* The annealing over (W, R) as Sec. III-B describes it: window moves (W by -2, -1,

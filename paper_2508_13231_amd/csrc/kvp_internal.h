@@ -146,6 +146,22 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
     for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, KVP_WAVE);
     return v;
 }
+// Inclusive prefix sum over the 64 lanes without LDS: shifts inside the rows of 16 lanes, then the
+// last lane of a row is broadcast into the next row (rows 1 and 3), then lane 31 into rows 2 and 3.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);   // lanes without a source get 0
+}
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
+    v += dpp_or_zero<0x111, 0xf>(v);     // row_shr:1
+    v += dpp_or_zero<0x112, 0xf>(v);     // row_shr:2
+    v += dpp_or_zero<0x114, 0xf>(v);     // row_shr:4
+    v += dpp_or_zero<0x118, 0xf>(v);     // row_shr:8
+    v += dpp_or_zero<0x142, 0xa>(v);     // row_bcast:15 into rows 1 and 3
+    v += dpp_or_zero<0x143, 0xc>(v);     // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 __device__ __forceinline__ uint32_t wave_or_u32(uint32_t v) {
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) v |= __shfl_xor(v, o, KVP_WAVE);

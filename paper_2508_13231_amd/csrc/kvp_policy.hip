@@ -89,22 +89,39 @@ __global__ __launch_bounds__(BT) void wr_wanted_kernel(DevProblem q, RowDiv rd, 
 }
 
 // Steps 1 and 4 to 6 for candidate blockIdx.x over the steps [n_lo, n_hi): pools[candidate][LW] carries
-// the pool from one batch of steps to the next.
+// the pool from one batch of steps to the next.  Per step three passes over the L * Wd mask words, every
+// wavefront on its own run of 64-word chunks (lane = word, CU chunks in flight):
+//   pass 0  pool &= persist; how many wanted pages are outside, how many pages are in the pool: that
+//           fixes how many come in (m_in) and how many must leave (need);
+//   pass 1  both selections at once.  Who leaves is chosen among pool & ~wanted by key fmax - f, who comes
+//           among wanted & ~pool by key f; the second set does not depend on the outcome of the first, so
+//           one pass fills both histograms (and one per wavefront each, for the ties);
+//   pass 2  the two thresholds and the index-ordered ties decide every candidate; the new pool word is
+//           stored and written to the schedule rows of step n.
+// Only the set bits of a word are visited (a handful per word), their keys picked out of the word's 32,
+// which were fetched as whole vectors.
+// LDS: [2][nbins] histograms, then [2][BW][nbins] per wavefront if wave_bins.
 template <class FT>
 __global__ __launch_bounds__(BT) void wr_pool_kernel(DevProblem q, RowDiv rd, uint64_t cap, const uint32_t *__restrict__ cand_w,
                                                      const uint32_t *__restrict__ cand_r10, const uint32_t *__restrict__ cand_u,
                                                      uint32_t n_lo, uint32_t n_hi, uint32_t B, uint32_t *pools,
                                                      const uint32_t *__restrict__ wanted_all, const FT *__restrict__ fk,
-                                                     uint32_t *Xall) {
-    extern __shared__ uint32_t lds_u[];
-    __shared__ SelectShared sh;
+                                                     uint32_t *Xall, int wave_bins) {
+    extern __shared__ __align__(16) uint32_t lds_w[];
+    __shared__ SelectShared sh_out, sh_in;
     __shared__ uint32_t counts[2];
-    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const uint32_t LW = q.L * q.Wd, G = LW * 32;
     const uint32_t W = min(cand_w[blockIdx.x], q.N), r10 = cand_r10[blockIdx.x], u = cand_u[blockIdx.x];
     uint32_t *pool = pools + (size_t)blockIdx.x * LW;
     uint32_t *X = Xall + (size_t)blockIdx.x * q.L * q.N * q.Wd;
     const uint32_t fmax = W * q.K, nbins = fmax + 1;
+    uint32_t *hist_out = lds_w, *hist_in = lds_w + nbins;
+    uint32_t *mine_out = wave_bins ? lds_w + (size_t)(2 + wave) * nbins : nullptr;
+    uint32_t *mine_in = wave_bins ? lds_w + (size_t)(2 + BW + wave) * nbins : nullptr;
+    const uint32_t nchunks = (LW + 63) / 64, cpw = (nchunks + BW - 1) / BW;     // chunks of 64 words per wavefront
+    const uint32_t c_lo = min(wave * cpw, nchunks), c_hi = min(c_lo + cpw, nchunks);
+    constexpr int KU = sizeof(FT) == 1 ? CU : sizeof(FT) == 2 ? CU / 2 : 1;    // chunks whose keys are in flight together
     if (n_lo == 0)
         for (uint32_t wi = tid; wi < LW; wi += BT) pool[wi] = 0;
     __syncthreads();
@@ -112,29 +129,155 @@ __global__ __launch_bounds__(BT) void wr_pool_kernel(DevProblem q, RowDiv rd, ui
         const uint32_t *wanted = wanted_all + ((size_t)u * B + (n - n_lo)) * LW;
         const FT *f = fk + ((size_t)u * B + (n - n_lo)) * G;
         if (tid < 2) counts[tid] = 0;
-        __syncthreads();
-        uint32_t nq = 0, np = 0;                                       // how many are qualified, how many in the pool
-        for (uint32_t wi = tid; wi < LW; wi += BT) {
-            const uint32_t pw = pool[wi] & q.Pm[(size_t)n * q.Wd + rd.rem(wi)];               // step 1
-            pool[wi] = pw;
-            nq += __popc(wanted[wi] & ~pw);
-            np += __popc(pw);
+        for (uint32_t k = tid; k < (wave_bins ? (2 + 2 * BW) * nbins : 2 * nbins); k += BT) lds_w[k] = 0;
+        // ---- pass 0
+        uint32_t nq = 0, np = 0;
+        for (uint32_t c0 = c_lo; c0 < c_hi; c0 += CU) {
+            uint32_t pw[CU], ww[CU], pm[CU];
+#pragma unroll
+            for (int j = 0; j < CU; j++) {
+                const uint32_t wi = min((c0 + j) * 64 + lane, LW - 1);
+                pw[j] = pool[wi]; ww[j] = wanted[wi]; pm[j] = q.Pm[(size_t)n * q.Wd + rd.rem(wi)];
+            }
+#pragma unroll
+            for (int j = 0; j < CU; j++) {
+                const uint32_t wi = (c0 + j) * 64 + lane;
+                if (c0 + j >= c_hi || wi >= LW) continue;
+                const uint32_t keep = pw[j] & pm[j];                   // step 1
+                if (keep != pw[j]) pool[wi] = keep;
+                nq += __popc(ww[j] & ~keep);
+                np += __popc(keep);
+            }
         }
         nq = wave_sum_u32(nq); np = wave_sum_u32(np);
+        __syncthreads();                                               // counts and histograms are clear
         if (lane == 0) { atomicAdd(&counts[0], nq); atomicAdd(&counts[1], np); }
         __syncthreads();
         const uint64_t m_in = ((uint64_t)r10 * counts[0] + 5) / 10;    // step 4
         const uint64_t in_pool = counts[1];
-        const uint64_t need = in_pool + m_in > cap ? in_pool + m_in - cap : 0;
-        if (need > 0)                                                  // step 5
-            mask_select(LW, nbins, need, lds_u, sh, [&](uint32_t wi) { return pool[wi] & ~wanted[wi]; },
-                        [&](uint32_t g) { return fmax - (uint32_t)f[g]; }, [&](uint32_t wi, uint32_t bits) { pool[wi] &= ~bits; });
-        if (m_in > 0)                                                  // step 4, carried out
-            mask_select(LW, nbins, m_in, lds_u, sh, [&](uint32_t wi) { return wanted[wi] & ~pool[wi]; },
-                        [&](uint32_t g) { return (uint32_t)f[g]; }, [&](uint32_t wi, uint32_t bits) { pool[wi] |= bits; });
-        for (uint32_t wi = tid; wi < LW; wi += BT) {                   // step 6
-            const uint32_t l = rd.quot(wi), w = wi - l * q.Wd;
-            X[((size_t)l * q.N + n) * q.Wd + w] = pool[wi];
+        const uint64_t need = in_pool + m_in > cap ? in_pool + m_in - cap : 0;   // step 5
+        const bool do_out = need > 0, do_in = m_in > 0;
+        // ---- pass 1
+        if (do_out || do_in)
+            for (uint32_t c0 = c_lo; c0 < c_hi; c0 += KU) {
+                uint32_t mo[KU], mi[KU];
+                WordKeys<FT> kw[KU];
+                // every load of the group is issued whether its word holds a candidate or not: loads under
+                // conditions would each wait for the ones before
+#pragma unroll
+                for (int j = 0; j < KU; j++) {
+                    const uint32_t wi = (c0 + j) * 64 + lane;
+                    const bool in = c0 + j < c_hi && wi < LW;
+                    const uint32_t wc = in ? wi : LW - 1;
+                    const uint32_t pw = pool[wc], ww = wanted[wc];
+                    kw[j].load(f, wc);
+                    mo[j] = do_out && in ? pw & ~ww : 0u;
+                    mi[j] = do_in && in ? ww & ~pw : 0u;
+                }
+#pragma unroll
+                for (int j = 0; j < KU; j++)
+                    for (uint32_t m = mo[j] | mi[j]; m; m &= m - 1) {
+                        const uint32_t b = __ffs(m) - 1, fv = kw[j].get(b);
+                        // a wavefront counts into its own histograms where it has them: sixteen wavefronts
+                        // adding to the same few counters of one histogram take four times as long
+                        if ((mo[j] >> b) & 1u) atomicAdd(mine_out ? &mine_out[fmax - fv] : &hist_out[fmax - fv], 1u);
+                        else atomicAdd(mine_in ? &mine_in[fv] : &hist_in[fv], 1u);
+                    }
+            }
+        __syncthreads();
+        if (wave_bins) {                                               // the workgroup's histograms: the sums
+            for (uint32_t k = tid; k < 2 * nbins; k += BT) {
+                const uint32_t *src = lds_w + (k < nbins ? (size_t)2 * nbins + k : (size_t)(2 + BW) * nbins + (k - nbins));
+                uint32_t sum = 0;
+                for (int w = 0; w < BW; w++) sum += src[(size_t)w * nbins];
+                lds_w[k] = sum;
+            }
+            __syncthreads();
+        }
+        if (do_out) select_threshold(nbins, need, hist_out, sh_out);
+        if (do_in) select_threshold(nbins, m_in, hist_in, sh_in);
+        const uint32_t T_out = sh_out.threshold, r_out = sh_out.take_ties, T_in = sh_in.threshold, r_in = sh_in.take_ties;
+        const bool all_out = sh_out.take_all != 0, all_in = sh_in.take_all != 0;
+        // the ties of every wavefront's words, so that they can be numbered in index order
+        uint32_t t_out = 0, t_in = 0;
+        if (wave_bins) {
+            t_out = do_out && !all_out && T_out < nbins ? mine_out[T_out] : 0u;
+            t_in = do_in && !all_in && T_in < nbins ? mine_in[T_in] : 0u;
+        } else if ((do_out && !all_out) || (do_in && !all_in)) {
+            for (uint32_t c = c_lo; c < c_hi; c++) {
+                const uint32_t wi = c * 64 + lane;
+                const uint32_t pw = wi < LW ? pool[wi] : 0u, ww = wi < LW ? wanted[wi] : 0u;
+                const uint32_t o = do_out ? pw & ~ww : 0u, i = do_in ? ww & ~pw : 0u;
+                if (!__ballot((o | i) != 0)) continue;
+                WordKeys<FT> kw;
+                if (o | i) kw.load(f, wi);
+                for (uint32_t m = o | i; m; m &= m - 1) {
+                    const uint32_t b = __ffs(m) - 1, fv = kw.get(b);
+                    if ((o >> b) & 1u) t_out += fmax - fv == T_out;
+                    else t_in += fv == T_in;
+                }
+            }
+            t_out = wave_sum_u32(t_out); t_in = wave_sum_u32(t_in);
+        }
+        if (lane == 0) { sh_out.wave_ties[wave] = t_out; sh_in.wave_ties[wave] = t_in; }
+        __syncthreads();
+        uint32_t rank_out = 0, rank_in = 0;
+        for (uint32_t w = 0; w < wave; w++) { rank_out += sh_out.wave_ties[w]; rank_in += sh_in.wave_ties[w]; }
+        // ---- pass 2
+        // which of a chunk's ties (bits of `tie`, lane = word) are among the first r in index order, rank0
+        // of them lying before the chunk: all lanes together
+        auto number_ties = [&](uint32_t tie, uint32_t &rank0, uint32_t r) -> uint32_t {
+            if (rank0 >= r || !__ballot(tie != 0)) return 0u;         // the same for the whole wavefront
+            const uint32_t tc = __popc(tie);
+            const uint32_t incl = wave_incl_scan_u32(tc);              // ties in this and the lower lanes
+            uint32_t rank = rank0 + incl - tc;                         // rank of this word's first tie
+            rank0 += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+            if (rank + tc <= r) return tie;                            // all of the word's
+            uint32_t take = 0;
+            for (uint32_t t = tie; t; t &= t - 1, rank++)              // ties below rank r are taken
+                if (rank < r) take |= t & (0u - t);
+            return take;
+        };
+        for (uint32_t c0 = c_lo; c0 < c_hi; c0 += KU) {
+            uint32_t pw[KU], mo[KU], mi[KU];
+            WordKeys<FT> kw[KU];
+#pragma unroll
+            for (int j = 0; j < KU; j++) {
+                const uint32_t wi = (c0 + j) * 64 + lane;
+                const bool in = c0 + j < c_hi && wi < LW;
+                const uint32_t wc = in ? wi : LW - 1;
+                const uint32_t ww = wanted[wc];
+                pw[j] = pool[wc];
+                kw[j].load(f, wc);
+                mo[j] = do_out && in ? pw[j] & ~ww : 0u;
+                mi[j] = do_in && in ? ww & ~pw[j] : 0u;
+            }
+            const bool keys_out = do_out && !all_out, keys_in = do_in && !all_in;
+#pragma unroll
+            for (int j = 0; j < KU; j++) {
+                if (c0 + j >= c_hi) break;                             // the same for the whole wavefront
+                uint32_t out = all_out ? mo[j] : 0u, in = all_in ? mi[j] : 0u, tie_o = 0, tie_i = 0;
+                for (uint32_t m = (keys_out ? mo[j] : 0u) | (keys_in ? mi[j] : 0u); m; m &= m - 1) {
+                    const uint32_t b = __ffs(m) - 1, fv = kw[j].get(b), bit = 1u << b;
+                    if (mo[j] & bit) {
+                        const uint32_t k = fmax - fv;
+                        out |= k > T_out ? bit : 0u;
+                        tie_o |= k == T_out ? bit : 0u;
+                    } else {
+                        in |= fv > T_in ? bit : 0u;
+                        tie_i |= fv == T_in ? bit : 0u;
+                    }
+                }
+                out |= number_ties(tie_o, rank_out, r_out);
+                in |= number_ties(tie_i, rank_in, r_in);
+                const uint32_t wi = (c0 + j) * 64 + lane;
+                if (wi < LW) {
+                    const uint32_t now = (pw[j] & ~out) | in;
+                    if (now != pw[j]) pool[wi] = now;
+                    const uint32_t l = rd.quot(wi), w = wi - l * q.Wd;
+                    X[((size_t)l * q.N + n) * q.Wd + w] = now;         // step 6
+                }
+            }
         }
         __syncthreads();
     }
@@ -158,7 +301,7 @@ extern "C" int kvp_wr_policy(kvp_ctx *ctx, uint32_t n, const uint32_t *h_w, cons
     const uint64_t G64 = (uint64_t)q.L * q.Wd * 32;
     if (G64 >= (1ull << 31)) return KVP_ESHAPE;
     const size_t lds = ((size_t)wmax * q.K + 1) * 4;
-    if (lds > 128 * 1024) return KVP_ESHAPE;
+    if (lds > 64 * 1024) return KVP_ESHAPE;                            // the pool walk keeps two such histograms in LDS
     KVP_HIP(hipSetDevice(ctx->device));
     const RowDiv rd(q.Wd, (uint64_t)q.L * q.Wd);
     const uint64_t fmax = (uint64_t)wmax * q.K;
@@ -180,7 +323,11 @@ extern "C" int kvp_wr_policy(kvp_ctx *ctx, uint32_t n, const uint32_t *h_w, cons
     const uint32_t B = (uint32_t)(per_step >= ((size_t)2 << 30) ? 1 : ((size_t)2 << 30) / per_step < q.N ? ((size_t)2 << 30) / per_step : q.N);
     // layout, in words: candidate table | pools | wanted masks | count state | counts
     const size_t o_pool = (host.size() + 3) & ~(size_t)3, o_want = o_pool + (size_t)n * LW, o_state = o_want + (size_t)nu * B * LW;
-    const size_t o_f = o_state + ((size_t)nu * G * fbytes + 3) / 4, total = o_f + ((size_t)nu * B * G * fbytes + 3) / 4;
+    const size_t o_f = (o_state + ((size_t)nu * G * fbytes + 3) / 4 + 31) & ~(size_t)31;   // a word's 32 counts: whole 16-byte vectors
+    const size_t total = o_f + ((size_t)nu * B * G * fbytes + 3) / 4;
+    // the pool walk keeps two histograms, and two per wavefront beside them when all 34 fit 64 KB
+    const int wave_bins = lds * (2 + 2 * BW) <= 64 * 1024;
+    const size_t lds_pool = wave_bins ? lds * (2 + 2 * BW) : lds * 2;
     int rc = kvp_ensure(ctx, (void **)&ctx->d_policy_work, &ctx->policy_work_cap, total * 4);
     if (rc) return rc;
     uint32_t *wk = ctx->d_policy_work;
@@ -193,9 +340,10 @@ extern "C" int kvp_wr_policy(kvp_ctx *ctx, uint32_t n, const uint32_t *h_w, cons
         if (lds > 48 * 1024) {                                                                                      \
             KVP_HIP(hipFuncSetAttribute((const void *)wr_wanted_kernel<FT>, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                         (int)lds));                                                                 \
-            KVP_HIP(hipFuncSetAttribute((const void *)wr_pool_kernel<FT>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                        (int)lds));                                                                 \
         }                                                                                                           \
+        if (lds_pool > 48 * 1024)                                                                                   \
+            KVP_HIP(hipFuncSetAttribute((const void *)wr_pool_kernel<FT>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                        (int)lds_pool));                                                            \
         FT *fstate = (FT *)(wk + o_state), *fk = (FT *)(wk + o_f);                                                  \
         for (uint32_t n_lo = 0; n_lo < q.N; n_lo += B) {                                                            \
             const uint32_t n_hi = n_lo + B < q.N ? n_lo + B : q.N;                                                  \
@@ -203,8 +351,8 @@ extern "C" int kvp_wr_policy(kvp_ctx *ctx, uint32_t n, const uint32_t *h_w, cons
                 q, rd, d_uw, n_lo, n_hi, B, fstate, fk);                                                            \
             wr_wanted_kernel<FT><<<dim3(n_hi - n_lo, nu), dim3(BT), lds, ctx->stream>>>(q, rd, cap, d_uw, n_lo, B, fk, \
                                                                                        wk + o_want);                \
-            wr_pool_kernel<FT><<<dim3(n), dim3(BT), lds, ctx->stream>>>(q, rd, cap, d_w, d_r, d_u, n_lo, n_hi, B,   \
-                                                                       wk + o_pool, wk + o_want, fk, d_placements); \
+            wr_pool_kernel<FT><<<dim3(n), dim3(BT), lds_pool, ctx->stream>>>(                                       \
+                q, rd, cap, d_w, d_r, d_u, n_lo, n_hi, B, wk + o_pool, wk + o_want, fk, d_placements, wave_bins);   \
         }                                                                                                           \
     } while (0)
     if (fbytes == 1) KVP_POLICY(uint8_t);

@@ -144,77 +144,37 @@ __device__ __forceinline__ void block_select(uint32_t G, uint32_t nbins, uint64_
     __syncthreads();
 }
 
-// The same selection among the set bits of mask words: item g = 32 * wi + b is a candidate when bit
-// b of cand(wi) is set, wi in [0, LW).  key(g) is called for candidates only (three times);
-// emit(wi, bits) once per word in which something is chosen, by the lane that owns the word.
-// The cost follows the number of candidates, not the number of items.
-template <class Cand, class Key, class Emit>
-__device__ __forceinline__ void mask_select(uint32_t LW, uint32_t nbins, uint64_t cap, uint32_t *hist, SelectShared &sh,
-                                            Cand cand, Key key, Emit emit) {
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const uint32_t nchunks = (LW + 63) / 64, cpw = (nchunks + BW - 1) / BW;     // chunks of 64 words per wavefront
-    const uint32_t c_lo = min(wave * cpw, nchunks), c_hi = min(c_lo + cpw, nchunks);
-    for (uint32_t k = tid; k < nbins; k += BT) hist[k] = 0;
-    __syncthreads();
-    for (uint32_t c = c_lo; c < c_hi; c++) {
-        const uint32_t wi = c * 64 + lane;
-        uint32_t m = wi < LW ? cand(wi) : 0;
-        while (m) {
-            const uint32_t b = __ffs(m) - 1;
-            m &= m - 1;
-            atomicAdd(&hist[key(wi * 32 + b)], 1u);
-        }
+// The 32 keys of a mask word, fetched as whole 16-byte vectors (the key of item g is f[g], so a word's
+// keys are 32 consecutive elements; f + 32 * wi must be 16-byte aligned).
+template <class FT>
+struct WordKeys {
+    static constexpr int NV = (int)sizeof(FT) * 2;      // vectors
+    uint4 v[NV];
+    __device__ __forceinline__ void load(const FT *f, uint32_t wi) {
+        const uint4 *p = (const uint4 *)(f + (size_t)wi * 32);
+#pragma unroll
+        for (int j = 0; j < NV; j++) v[j] = p[j];
     }
-    __syncthreads();
-    select_threshold(nbins, cap, hist, sh);
-    const uint32_t T = sh.threshold, r = sh.take_ties;
-    const bool all = sh.take_all != 0;
-    uint32_t ties = 0;
-    if (!all)
-        for (uint32_t c = c_lo; c < c_hi; c++) {
-            const uint32_t wi = c * 64 + lane;
-            uint32_t m = wi < LW ? cand(wi) : 0;
-            while (m) {
-                const uint32_t b = __ffs(m) - 1;
-                m &= m - 1;
-                ties += key(wi * 32 + b) == T;
-            }
+    // key of bit b, b different from lane to lane: the vectors are halved log2(2 NV) times by selects on
+    // the bits of the key's byte offset (no register indexing), then one 64-bit shift picks the key
+    __device__ __forceinline__ uint32_t get(uint32_t b) const {
+        constexpr int NP = NV * 2;                          // 64-bit pieces
+        uint64_t p[NP];
+#pragma unroll
+        for (int j = 0; j < NV; j++) {
+            p[2 * j] = ((uint64_t)v[j].y << 32) | v[j].x;
+            p[2 * j + 1] = ((uint64_t)v[j].w << 32) | v[j].z;
         }
-    ties = wave_sum_u32(ties);
-    if (lane == 0) sh.wave_ties[wave] = ties;
-    __syncthreads();
-    uint32_t rank0 = 0;
-    for (uint32_t w = 0; w < wave; w++) rank0 += sh.wave_ties[w];
-    for (uint32_t c = c_lo; c < c_hi; c++) {
-        const uint32_t wi = c * 64 + lane;
-        const uint32_t m0 = wi < LW ? cand(wi) : 0;
-        uint32_t chosen = m0;
-        if (!all) {
-            uint32_t above = 0, tie = 0;
-            for (uint32_t m = m0; m;) {
-                const uint32_t b = __ffs(m) - 1;
-                m &= m - 1;
-                const uint32_t k = key(wi * 32 + b);
-                above |= (uint32_t)(k > T) << b;
-                tie |= (uint32_t)(k == T) << b;
-            }
-            chosen = above;
-            if (__ballot(tie != 0)) {                                  // the same for the whole wavefront
-                const uint32_t tc = __popc(tie);
-                uint32_t incl = tc;                                    // ties in this and the lower lanes
-                for (uint32_t d = 1; d < 64; d <<= 1) {
-                    const uint32_t up = __shfl_up(incl, d, KVP_WAVE);
-                    if (lane >= d) incl += up;
-                }
-                uint32_t rank = rank0 + incl - tc;                     // rank of this word's first tie
-                for (uint32_t m = tie; m; m &= m - 1, rank++)          // ties below rank r are chosen
-                    if (rank < r) chosen |= m & (0u - m);
-                rank0 += __shfl(incl, 63, KVP_WAVE);
-            }
+        const uint32_t byte = b * (uint32_t)sizeof(FT);
+#pragma unroll
+        for (int half = NP / 2, bit = 8; half >= 1; half >>= 1, bit <<= 1) {
+            const bool hi = byte & (uint32_t)bit;           // pieces are interleaved: piece i covers bytes 8i .. 8i+7
+#pragma unroll
+            for (int i = 0; i < half; i++) p[i] = hi ? p[2 * i + 1] : p[2 * i];
         }
-        if (chosen) emit(wi, chosen);
+        const uint64_t s = p[0] >> ((byte & 7u) * 8u);
+        return sizeof(FT) == 4 ? (uint32_t)s : (uint32_t)s & ((1u << (8 * (sizeof(FT) % 4))) - 1u);
     }
-    __syncthreads();
-}
+};
 
 }  // namespace

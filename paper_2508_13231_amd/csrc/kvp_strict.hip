@@ -21,22 +21,6 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t *p, uint32_t n, 
     if (i < n) p[i] = v;
 }
 
-// Inclusive prefix sum over the 64 lanes without LDS: shifts inside the rows of 16 lanes, then the
-// last lane of a row is broadcast into the next row (rows 1 and 3), then lane 31 into rows 2 and 3.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);   // lanes without a source get 0
-}
-__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
-    v += dpp_or_zero<0x111, 0xf>(v);     // row_shr:1
-    v += dpp_or_zero<0x112, 0xf>(v);     // row_shr:2
-    v += dpp_or_zero<0x114, 0xf>(v);     // row_shr:4
-    v += dpp_or_zero<0x118, 0xf>(v);     // row_shr:8
-    v += dpp_or_zero<0x142, 0xa>(v);     // row_bcast:15 into rows 1 and 3
-    v += dpp_or_zero<0x143, 0xc>(v);     // row_bcast:31 into rows 2 and 3
-    return v;
-}
-
 // table (may be null): [S][L][N], the pool after every slot
 __global__ __launch_bounds__(SW * KVP_WAVE) void strict_excess_kernel(DevProblem q, const uint32_t *__restrict__ X,
                                                                       uint32_t S, uint32_t *__restrict__ excess,
