@@ -101,6 +101,14 @@ def lib():
         L.orc_resolve_strict.argtypes = L.orc_resolve.argtypes
         L.orc_slot_occupancy.restype = None
         L.orc_slot_occupancy.argtypes = [C.POINTER(_Problem), C.c_void_p, C.c_void_p]
+        L.orc_score_slots.restype = C.c_double
+        L.orc_score_slots.argtypes = [C.POINTER(_Problem), C.c_void_p, C.c_void_p, C.POINTER(C.c_uint32), C.c_void_p,
+                                      C.c_void_p]
+        L.orc_slot_bytes.restype = None
+        L.orc_slot_bytes.argtypes = [C.POINTER(_Problem), C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+        L.orc_refine_slots.restype = C.c_int
+        L.orc_refine_slots.argtypes = [C.POINTER(_Problem), C.POINTER(_SAParams), C.c_uint32, C.c_void_p, C.c_void_p,
+                                       C.POINTER(_SAState)]
         L.orc_init_static_frequency.argtypes = [C.POINTER(_Problem), C.c_void_p]
         L.orc_init_recency.argtypes = [C.POINTER(_Problem), C.c_void_p]
         L.orc_init_static_fill.argtypes = [C.POINTER(_Problem), C.c_void_p]
@@ -256,6 +264,73 @@ def slot_occupancy(tr, X) -> np.ndarray:
     tab = np.zeros((q.N, q.L), dtype=np.uint32)
     lib().orc_slot_occupancy(C.byref(q.c), X.ctypes.data, tab.ctypes.data)
     return tab
+
+
+@dataclass
+class SlotScore:
+    cost: float
+    excess: int          # largest overshoot of the pool over all inference steps; bit 31: bits on dead pages; bit 30: a Y out of range
+    slot_t: np.ndarray   # [N*L] latency of inference step g = n*L + l
+    pool: np.ndarray     # [N*L] pages in HBM after step g
+
+
+def score_slots(tr, X, Y) -> SlotScore:
+    """A placement X whose migrating pages move in the inference steps that Y names: a page of layer l that changes
+    tier going into step n moves in step n*L + l - Y[l][n][p]."""
+    q = _problem(tr)
+    X, Y = _u8(X, q.shape), _u8(Y, q.shape)
+    ex = C.c_uint32(0)
+    st = np.zeros(q.N * q.L, dtype=np.float64)
+    pool = np.zeros(q.N * q.L, dtype=np.uint32)
+    T = lib().orc_score_slots(C.byref(q.c), X.ctypes.data, Y.ctypes.data, C.byref(ex), st.ctypes.data, pool.ctypes.data)
+    return SlotScore(T, ex.value, st, pool)
+
+
+def slot_bytes(tr, X, Y, g):
+    """{|H^r|, |E^r|, |H^w|, |E^w|, |M^i|, |M^o|} of inference step g."""
+    q = _problem(tr)
+    X, Y = _u8(X, q.shape), _u8(Y, q.shape)
+    out = np.zeros(6, dtype=np.uint64)
+    lib().orc_slot_bytes(C.byref(q.c), X.ctypes.data, Y.ctypes.data, int(g), out.ctypes.data)
+    return out
+
+
+@dataclass
+class SlotWalk:
+    chain: int
+    Y: np.ndarray
+    T_cur: float
+    T_best: float
+    C0: float
+    accepted: int
+    uphill: int
+    null_moves: int
+    clipped: int
+    improved: int
+    state: object = None
+
+
+def refine_slots(tr, chain, X, Y0, *, seed, total_moves, move_begin=0, move_end=None, n_levels=100, p0=0.8, alpha=0.9,
+                 resume=None) -> SlotWalk:
+    """Annealing over the migration steps Y of the fixed placement X (one chain)."""
+    q = _problem(tr)
+    sp = _SAParams()
+    sp.seed, sp.total_moves = int(seed), int(total_moves)
+    sp.move_begin = int(move_begin)
+    sp.move_end = int(total_moves if move_end is None else move_end)
+    sp.n_levels, sp.max_len, sp.p0, sp.alpha = int(n_levels), 1, float(p0), float(alpha)
+    for i, v in enumerate((0.4, 0.4, 0.2)):
+        sp.op_prob[i] = v
+    X = _u8(X, q.shape)
+    if resume is None:
+        Y, st = np.array(_u8(Y0, q.shape), copy=True), _SAState()
+    else:
+        Y, st = resume.Y.copy(), resume.state
+    rc = lib().orc_refine_slots(C.byref(q.c), C.byref(sp), int(chain), X.ctypes.data, Y.ctypes.data, C.byref(st))
+    if rc != 0:
+        raise ValueError(f"orc_refine_slots failed ({rc}): bad parameters or a start that overfills an inference step")
+    return SlotWalk(int(chain), Y, st.T_cur, st.T_best, st.C0, st.accepted, st.uphill, st.null_moves, st.clipped,
+                    st.improved, st)
 
 
 def resolve(tr, X, move, per_slot=False):

@@ -695,6 +695,170 @@ int orc_anneal_chain(const orc_problem *q, const orc_sa_params *sp, uint32_t cha
     return 0;
 }
 
+/* ---- migration in any inference step (Sec. III-A: the decision S(n, l) places all KV data) ----
+ * In orc_score a page of layer l changes tier only in its own step (n, l).  Here the step is chosen:
+ * a page (l, p) whose placement differs between its steps n-1 and n, and which persists into n,
+ * migrates in the inference step
+ *     g = n*L + l - Y[l][n][p],   Y in 0 .. L-1,
+ * any step after the page's use at (n-1, l) up to its use at (n, l); the bytes are charged to that
+ * step (|M^i|, |M^o| of Eqs. 3-4 at g).  Reads and the new token's write are as before: at (n, l) the
+ * page is where X[l][n] says.  Y is looked at only where a page migrates; Y = 0 everywhere is the
+ * schedule of orc_score.  A value above L-1 on a migrating page counts as 0 and sets bit 30 of the
+ * excess. */
+static int slot_change(const orc_problem *q, const uint8_t *X, int l, int n, int p) {
+    if (n < 1 || !pm_bit(q, n, p)) return 0;
+    int x = x_bit(q, X, l, n, p), xp = x_bit(q, X, l, n - 1, p);
+    return x == xp ? 0 : (x ? 1 : -1);
+}
+
+static int slot_of(const orc_problem *q, const uint8_t *Y, int l, int n, int p) {
+    int y = Y[ix_x(q, l, n, p)];
+    if (y > q->L - 1) y = 0;
+    return n * q->L + l - y;
+}
+
+/* the volumes of inference step g = n*L + l, migration from whichever layers' pages move there */
+void orc_slot_bytes(const orc_problem *q, const uint8_t *X, const uint8_t *Y, int g, uint64_t out[6]) {
+    int L = q->L, N = q->N, n0 = g / L, l0 = g % L;
+    orc_step_bytes(q, X, l0, n0, out);
+    uint64_t mi = 0, mo = 0;
+    for (int l = 0; l < L; l++)
+        for (int n = n0; n <= n0 + 1 && n < N; n++)          /* a page of step n moves in ((n-1)L + l, nL + l] */
+            for (int p = 0; p < q->P; p++) {
+                int c = slot_change(q, X, l, n, p);
+                if (!c || slot_of(q, Y, l, n, p) != g) continue;
+                if (c > 0) mi += q->page_bytes; else mo += q->page_bytes;
+            }
+    out[4] = mi; out[5] = mo;
+}
+
+/* Total latency (Eq. 1 over the inference steps in execution order) and the pool after every
+ * inference step (Eq. 5), simulated as it happens: at the start of token step n the pages that do
+ * not persist into it are gone; in step g the pages that migrate there change tier, and the layer
+ * whose step it is takes its placement (which places its new pages; its migrating pages have moved
+ * by now or move here).  excess = largest overshoot of the pool over all steps; bit 31: bits on
+ * pages that do not exist; bit 30: a Y out of range.  Optional: slot_t [N*L], pool [N*L]. */
+double orc_score_slots(const orc_problem *q, const uint8_t *X, const uint8_t *Y, uint32_t *excess,
+                       double *slot_t, uint32_t *pool_out) {
+    int L = q->L, N = q->N, P = q->P;
+    size_t G = (size_t)L * N;
+    double *t = (double *)malloc(sizeof(double) * (G ? G : 1));
+    for (size_t g = 0; g < G; g++) {
+        uint64_t b[6];
+        orc_slot_bytes(q, X, Y, (int)g, b);
+        t[g] = orc_step_time(q, b);
+    }
+    double T = orc_csum(t, G);
+    uint8_t *cur = (uint8_t *)calloc((size_t)L * P ? (size_t)L * P : 1, 1);
+    uint64_t worst = 0;
+    uint32_t flag = 0;
+    for (int n = 0; n < N; n++) {
+        for (int l = 0; l < L; l++)
+            for (int p = 0; p < P; p++)
+                if (!(n > 0 && pm_bit(q, n, p))) cur[(size_t)l * P + p] = 0;
+        for (int l0 = 0; l0 < L; l0++) {
+            int g = n * L + l0;
+            for (int l = 0; l < L; l++)
+                for (int m = n; m <= n + 1 && m < N; m++)
+                    for (int p = 0; p < P; p++)
+                        if (slot_change(q, X, l, m, p) && slot_of(q, Y, l, m, p) == g)
+                            cur[(size_t)l * P + p] = (uint8_t)x_bit(q, X, l, m, p);
+            for (int p = 0; p < P; p++) cur[(size_t)l0 * P + p] = (uint8_t)x_bit(q, X, l0, n, p);
+            uint64_t occ = 0;
+            for (size_t i = 0; i < (size_t)L * P; i++) occ += cur[i];
+            if (pool_out) pool_out[g] = (uint32_t)occ;
+            if (occ > q->cap_pages && occ - q->cap_pages > worst) worst = occ - q->cap_pages;
+        }
+    }
+    for (int l = 0; l < L; l++)
+        for (int n = 0; n < N; n++)
+            for (int p = 0; p < P; p++) {
+                if (X[ix_x(q, l, n, p)] && !v_bit(q, n, p)) flag |= 0x80000000u;
+                if (slot_change(q, X, l, n, p) && Y[ix_x(q, l, n, p)] > L - 1) flag |= 0x40000000u;
+            }
+    if (excess) *excess = (uint32_t)(worst > 0x3FFFFFFFull ? 0x3FFFFFFFull : worst) | flag;
+    if (slot_t) memcpy(slot_t, t, sizeof(double) * G);
+    free(t); free(cur);
+    return T;
+}
+
+/* Annealing over the migration steps Y of a fixed placement X (the Metropolis skeleton of
+ * Sec. III-B: acceptance exp(-dT/C), C0 from p0 over 256 proposals that are not applied, cooling by
+ * alpha per level).  Proposal mi of a chain: the draw of orc_draw_move on stream 32 (40 for the
+ * calibration), of which layer, page, first step name the page (l, p) at step n and layer2, uniform
+ * in 0 .. L-1, the new Y.  Null if the page does not migrate at n or Y stays.  A page that enters
+ * HBM earlier, or leaves it later, is in the pool during the steps between the old and the new
+ * one: if one of them is full the proposal is dropped (counted as null and as clipped).
+ * dT = (t' - t) at the old step + (t' - t) at the new step, in that order.
+ * X must be feasible with Y at every inference step (-2 otherwise). */
+int orc_refine_slots(const orc_problem *q, const orc_sa_params *sp, uint32_t chain, const uint8_t *X,
+                     uint8_t *Y, orc_sa_state *st) {
+    int L = q->L, N = q->N;
+    size_t G = (size_t)L * N;
+    if (sp->n_levels < 1 || L > 256) return -1;
+    double *t = (double *)malloc(sizeof(double) * (G ? G : 1));
+    uint32_t *pool = (uint32_t *)malloc(sizeof(uint32_t) * (G ? G : 1));
+    uint64_t (*vol)[6] = (uint64_t (*)[6])malloc(sizeof(uint64_t[6]) * (G ? G : 1));
+    uint32_t ex;
+    double T0 = orc_score_slots(q, X, Y, &ex, t, pool);
+    if (ex != 0) { free(t); free(pool); free(vol); return -2; }
+    for (size_t g = 0; g < G; g++) orc_slot_bytes(q, X, Y, (int)g, vol[g]);
+    uint64_t mpl = sp->total_moves / sp->n_levels; if (mpl < 1) mpl = 1;
+    if (sp->move_begin == 0) {
+        memset(st, 0, sizeof *st);
+        st->T_cur = T0; st->T_best = T0;
+    }
+    for (int phase = (sp->move_begin == 0 ? 0 : 1); phase < 2; phase++) {
+        uint64_t first = phase == 0 ? 0 : sp->move_begin, last = phase == 0 ? ORC_CALIB : sp->move_end;
+        double sum = 0.0; uint32_t cnt = 0;
+        for (uint64_t mi = first; mi < last; mi++) {
+            if (phase == 1) {
+                uint64_t lvl = mi / mpl; if (lvl > sp->n_levels - 1) lvl = sp->n_levels - 1;
+                while (st->level < lvl) { st->C = st->C * sp->alpha; st->level++; }
+            }
+            orc_move m; double u;
+            orc_draw_move(q, sp, chain, mi, phase == 0 ? 40 : 32, &m, &u);
+            int l = (int)m.layer, p = (int)m.page, n = (int)m.n1, ynew = (int)m.layer2;
+            int c = slot_change(q, X, l, n, p);
+            size_t iy = ix_x(q, l, n, p);
+            int yold = Y[iy];
+            if (!c || ynew == yold) { if (phase == 1) st->null_moves++; continue; }
+            int g_old = n * L + l - yold, g_new = n * L + l - ynew;
+            /* the steps during which the page is in the pool only after the move */
+            int lo = 0, hi = 0;
+            if (c > 0 && g_new < g_old) { lo = g_new; hi = g_old; }
+            if (c < 0 && g_new > g_old) { lo = g_old; hi = g_new; }
+            int blocked = 0;
+            for (int g = lo; g < hi; g++) if ((uint64_t)pool[g] + 1 > q->cap_pages) blocked = 1;
+            if (blocked) { if (phase == 1) { st->null_moves++; st->clipped++; } continue; }
+            uint64_t bo[6], bn[6];
+            memcpy(bo, vol[g_old], sizeof bo); memcpy(bn, vol[g_new], sizeof bn);
+            int k = c > 0 ? 4 : 5;
+            bo[k] -= q->page_bytes; bn[k] += q->page_bytes;
+            double to = orc_step_time(q, bo), tn = orc_step_time(q, bn);
+            double dT = (to - t[g_old]) + (tn - t[g_new]);
+            if (phase == 0) { if (dT > 0.0) { sum = sum + dT; cnt++; } continue; }
+            if (dT > 0.0) st->uphill_seen++;
+            int accept = (dT <= 0.0) || (st->C > 0.0 && u < exp(-dT / st->C));
+            if (!accept) continue;
+            st->accepted++; if (dT > 0.0) st->uphill++;
+            Y[iy] = (uint8_t)ynew;
+            memcpy(vol[g_old], bo, sizeof bo); memcpy(vol[g_new], bn, sizeof bn);
+            t[g_old] = to; t[g_new] = tn;
+            if (c > 0) { for (int g = g_new; g < g_old; g++) pool[g]++; for (int g = g_old; g < g_new; g++) pool[g]--; }
+            else { for (int g = g_old; g < g_new; g++) pool[g]++; for (int g = g_new; g < g_old; g++) pool[g]--; }
+            st->T_cur = st->T_cur + dT;
+            if (st->T_cur < st->T_best) { st->T_best = st->T_cur; st->improved++; }
+        }
+        if (phase == 0) {
+            st->C0 = cnt ? (sum / (double)cnt) / (-log(sp->p0)) : 0.0;
+            st->C = st->C0; st->level = 0;
+        }
+    }
+    free(t); free(pool); free(vol);
+    return 0;
+}
+
 /* ---- replica exchange between the chains (parallel tempering) ---------------
  * Not in the paper (its search is one annealing run): the standard exchange
  * step of parallel tempering (Swendsen & Wang 1986; Geyer 1991), offered

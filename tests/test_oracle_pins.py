@@ -695,6 +695,165 @@ def test_per_slot_walk_keeps_every_slot_within_capacity(seed):
         O.anneal_chain(t2, 0, bad, seed=1, total_moves=10, n_levels=1, per_slot=True)
 
 
+# ---- migration in any inference step (Sec. III-A: S(n, l) places all KV data; the bytes are charged where they move) ----
+
+def _slot_instance():
+    # two layers, one page each.  Layer 0 keeps its page in HBM and reads it at step 1; layer 1's page comes in for step 1.
+    # B_h = 8, B_k = 2, B_d = 4 bytes/s; a page and a read are 8 bytes.
+    tr = _mini(L=2, N=2, P=1, bw=(8.0, 2.0, 4.0), cap=2, page_bytes=8, token_bytes=8)
+    tr.alive[:] = 1
+    tr.persist[1:] = 1
+    tr.access[0, 1, 0, 0] = 1
+    X = np.zeros((2, 2, 1), np.uint8)
+    X[0, :, 0] = 1
+    X[1, 1, 0] = 1
+    return tr, X
+
+
+def test_slot_score_by_hand():
+    tr, X = _slot_instance()
+    Y = np.zeros_like(X)
+    # in its own step (1,1), step 3 of 4: step 2 reads 8 bytes of HBM (8/8 = 1 s); step 3 moves 8 bytes in:
+    # t^h = 1, t^e = max(0, 8/2, 8/4) = 4
+    s0 = O.score_slots(tr, X, Y)
+    assert s0.slot_t.tolist() == [0.0, 0.0, 1.0, 4.0] and s0.cost == 5.0
+    assert s0.pool.tolist() == [1, 1, 1, 2] and s0.excess == 0
+    assert O.slot_bytes(tr, X, Y, 3).tolist() == [0, 0, 0, 0, 8, 0] and O.slot_bytes(tr, X, Y, 2).tolist() == [8, 0, 0, 0, 0, 0]
+    # one step earlier, in layer 0's step (1,0): t^h = (8 + 8)/8 = 2, t^e = 4: the HBM read hides under the transfer
+    Y[1, 1, 0] = 1
+    s1 = O.score_slots(tr, X, Y)
+    assert s1.slot_t.tolist() == [0.0, 0.0, 4.0, 0.0] and s1.cost == 4.0
+    assert s1.pool.tolist() == [1, 1, 2, 2] and s1.excess == 0          # the page takes its room one step earlier
+    assert O.slot_bytes(tr, X, Y, 2).tolist() == [8, 0, 0, 0, 8, 0] and O.slot_bytes(tr, X, Y, 3).tolist() == [0] * 6
+    tr.cap_pages = 1
+    assert O.score_slots(tr, X, Y).excess == 1 and O.score_slots(tr, X, np.zeros_like(X)).excess == 1
+    # Y is looked at only where a page migrates, and must name one of the L steps up to the page's own
+    Y[:] = 0; Y[0, 1, 0] = 1; Y[1, 0, 0] = 1
+    assert O.score_slots(tr, X, Y).slot_t.tolist() == s0.slot_t.tolist()
+    Y[1, 1, 0] = 2
+    bad = O.score_slots(tr, X, Y)
+    assert bad.excess & 0x40000000 and bad.slot_t.tolist() == s0.slot_t.tolist()
+    # a page that leaves: layer 1 holds its page at step 0 only.  Leaving one step earlier frees the room earlier
+    Z = np.zeros((2, 2, 1), np.uint8); Z[1, 0, 0] = 1
+    tr.cap_pages = 2
+    Y[:] = 0
+    assert O.score_slots(tr, Z, Y).pool.tolist() == [0, 1, 1, 0]
+    assert O.slot_bytes(tr, Z, Y, 3).tolist() == [0, 0, 0, 0, 0, 8]
+    Y[1, 1, 0] = 1
+    assert O.score_slots(tr, Z, Y).pool.tolist() == [0, 1, 0, 0]
+    assert O.slot_bytes(tr, Z, Y, 2).tolist() == [0, 8, 0, 0, 0, 8]                     # layer 0's read now comes from DRAM
+
+
+def _pool_by_simulation(tr, X, Y):
+    """The pool after every inference step, page by page: numpy, no code shared with the oracle."""
+    L, N, P = X.shape
+    alive, persist = tr.alive.astype(bool), tr.persist.astype(bool)
+    x = X.astype(bool) & alive[None]
+    pool = np.zeros(N * L, np.int64)
+    # when does page (l, p) take the value it has at its step n: at its own step, or Y steps earlier if it migrates
+    since = np.zeros((L, N, P), np.int64)
+    for l in range(L):
+        for n in range(N):
+            since[l, n] = n * L + l
+            if n > 0:
+                mig = persist[n] & (x[l, n] != x[l, n - 1])
+                y = np.where(Y[l, n] > L - 1, 0, Y[l, n]).astype(np.int64)
+                since[l, n] -= np.where(mig, y, 0)
+    for g in range(N * L):
+        n0 = g // L
+        cnt = 0
+        for l in range(L):
+            for p in range(P):
+                # the newest step of the page whose value has taken effect by g
+                m = n0 + 1 if n0 + 1 < N and since[l, n0 + 1, p] <= g and persist[n0 + 1, p] else n0
+                if m == n0 and since[l, n0, p] > g:
+                    # its own step of this token step is still to come: the value of the step before, if it carried over
+                    cnt += bool(n0 > 0 and persist[n0, p] and x[l, n0 - 1, p])
+                else:
+                    cnt += bool(x[l, m, p])
+        pool[g] = cnt
+    return pool
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_slot_score_against_the_per_layer_score_and_a_simulation(seed):
+    rng = np.random.default_rng(seed)
+    tr = W.random_trace(700 + seed, L=[1, 2, 3, 4, 5, 3][seed], N=11, P=13, K=1 + seed % 2, rebirth=bool(seed % 2))
+    L = tr.L
+    for X in W.random_placements(tr, 3, seed=seed, density=0.5, feasible=False):
+        Y0 = np.zeros_like(X)
+        s0, ref = O.score_slots(tr, X, Y0), O.score(tr, X)
+        # every page in its own step: the schedule of Eqs. 1-5 as scored before, and the pool of the per-slot count
+        assert s0.cost == ref.cost and (s0.slot_t.reshape(tr.N, L) == ref.step_t.T).all()
+        assert (s0.pool.reshape(tr.N, L) == O.slot_occupancy(tr, X)).all()
+        assert (s0.excess & 0x3FFFFFFF) == O.strict_excess(tr, X)
+        Y = rng.integers(0, L, X.shape).astype(np.uint8)
+        s1 = O.score_slots(tr, X, Y)
+        assert (s1.pool == _pool_by_simulation(tr, X, Y)).all()
+        # bytes are moved, not made: every kind of volume sums to what it was
+        b0 = np.array([O.slot_bytes(tr, X, Y0, g) for g in range(tr.N * L)]).sum(axis=0)
+        b1 = np.array([O.slot_bytes(tr, X, Y, g) for g in range(tr.N * L)]).sum(axis=0)
+        assert (b0 == b1).all() and b0[4] + b0[5] > 0
+        # reads and writes stay in their steps
+        for g in range(tr.N * L):
+            assert (O.slot_bytes(tr, X, Y, g)[:4] == O.slot_bytes(tr, X, Y0, g)[:4]).all()
+        assert s1.cost == O.csum(s1.slot_t)
+
+
+def test_slot_refinement_by_hand_and_against_enumeration():
+    # the hand instance: one page migrates, two steps to choose from; the walk must find the cheaper one
+    tr, X = _slot_instance()
+    r = O.refine_slots(tr, 0, X, np.zeros_like(X), seed=3, total_moves=200, n_levels=5)
+    assert r.Y[1, 1, 0] == 1 and r.T_best == 4.0 and O.score_slots(tr, X, r.Y).cost == 4.0
+    tr.cap_pages = 1                                            # the start already overfills: refused
+    with pytest.raises(ValueError):
+        O.refine_slots(tr, 0, X, np.zeros_like(X), seed=3, total_moves=10, n_levels=1)
+    # a micro instance, all assignments enumerated
+    tr = W.random_trace(811, L=3, N=3, P=2, K=1, rebirth=False)
+    tr.alive[:] = 1; tr.persist[1:] = 1
+    tr.cap_pages = 4
+    X = None
+    for cand in W.random_placements(tr, 60, seed=2, density=0.5):
+        mig = (cand[:, 1:] != cand[:, :-1]).sum()
+        if 3 <= mig <= 5 and O.strict_excess(tr, cand) == 0:
+            X = cand; break
+    assert X is not None
+    where = np.argwhere(X[:, 1:] != X[:, :-1])
+    best, n_ok = math.inf, 0
+    for code in range(3 ** len(where)):
+        Y = np.zeros_like(X)
+        c = code
+        for (l, n, p) in where:
+            Y[l, n + 1, p] = c % 3; c //= 3
+        sc = O.score_slots(tr, X, Y)
+        if sc.excess == 0:
+            n_ok += 1; best = min(best, sc.cost)
+    assert n_ok >= 2 and best <= O.score(tr, X).cost
+    r = O.refine_slots(tr, 1, X, np.zeros_like(X), seed=5, total_moves=3000, n_levels=20)
+    final = O.score_slots(tr, X, r.Y)
+    assert final.excess == 0 and best <= final.cost <= O.score(tr, X).cost
+    assert r.T_cur == pytest.approx(final.cost, rel=1e-12) and r.T_best >= best * (1 - 1e-12)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_slot_refinement_stays_feasible_and_in_slices(seed):
+    tr = W.random_trace(900 + seed, L=4, N=20, P=17, K=1, rebirth=True)
+    q = O.Problem(tr)
+    X = O.anneal_chain(q, 0, np.zeros(q.shape, np.uint8), seed=seed, total_moves=1500, n_levels=10, max_len=7, per_slot=True).X
+    tr2 = tr
+    r = O.refine_slots(q, seed, X, np.zeros_like(X), seed=20 + seed, total_moves=4000, n_levels=10)
+    sc = O.score_slots(q, X, r.Y)
+    assert sc.excess == 0 and r.accepted > 20 and r.T_cur == pytest.approx(sc.cost, rel=1e-12)
+    assert r.T_best <= O.cost(q, X)
+    a = O.refine_slots(q, seed, X, np.zeros_like(X), seed=20 + seed, total_moves=4000, n_levels=10, move_end=1700)
+    b = O.refine_slots(q, seed, X, None, seed=20 + seed, total_moves=4000, n_levels=10, move_begin=1700, resume=a)
+    assert (b.Y == r.Y).all() and b.T_cur == r.T_cur and b.accepted == r.accepted and b.null_moves == r.null_moves
+    if seed == 0:                                               # a tight pool blocks moves that would need room
+        tight = O.Problem(tr2.__class__(**{**tr2.__dict__, "cap_pages": int(O.score_slots(q, X, np.zeros_like(X)).pool.max())}))
+        rt = O.refine_slots(tight, seed, X, np.zeros_like(X), seed=20 + seed, total_moves=4000, n_levels=10)
+        assert rt.clipped > 0 and O.score_slots(tight, X, rt.Y).excess == 0
+
+
 # ---- token-granular reads inside pages: the plane encoding against the token-level definition ----
 
 def _token_trace(seed=9):
