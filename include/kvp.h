@@ -196,6 +196,45 @@ int kvp_delta_score(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, cons
  * KVP_ENOTRACE, KVP_ESHAPE (more than 2048 layers), KVP_EHIP. */
 int kvp_strict_excess(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, uint32_t *d_excess);
 
+/* Sec. III-A: the placement decision at an inference step covers all KV data, so a page may change tier in
+ * another layer's step and its bytes are charged there.  A schedule is then a placement X as above and
+ * a second plane Y of bytes: a page (l, p) whose placement differs between its steps n-1 and n, and which
+ * persists into n, migrates in the inference step
+ *     g = n*L + l - Y[l][n][p],   Y in 0 .. L-1
+ * (any step after its use at (n-1, l) up to its use at (n, l)); Y is not looked at elsewhere, and Y = 0
+ * everywhere is the schedule that kvp_score prices.  Reads and the new token's write are those of X.
+ *
+ * kvp_score_slots: Eqs. 1-4 with |M^i|, |M^o| counted in the step where the pages move, and Eq. 5 after
+ * every inference step (pages born in HBM enter the pool in their own step, pages that do not persist
+ * leave it at the start of the token step).
+ *   d_placements [S][L][N][Wd]  in, DEVICE, 16-byte aligned
+ *   d_slots      [S][L][N][P]   in, DEVICE, one byte per page (P = n_pages)
+ *   d_cost       [S]            out: T in seconds, summed in execution order by the tree of kvp_score
+ *   d_excess     [S]            out: largest overshoot of cap_pages over all inference steps; bit 31: bits
+ *                               on pages that do not exist; bit 30: a Y above L-1 on a migrating page
+ *                               (taken as 0)
+ * Runs on the context's stream; scratch of S*L*N*36 bytes is held by the context.  S = 0 is a no-op.
+ * Errors: KVP_EINVAL (null or misaligned pointer), KVP_ENOTRACE, KVP_ESHAPE (more than 256 layers or 65535 schedules),
+ * KVP_ENOMEM, KVP_EHIP.
+ *
+ * kvp_refine_slots: annealing over Y for ONE fixed placement (the Metropolis rule, start temperature
+ * and cooling of Sec. III-B; the move is this library's): params->n_chains chains, chain c drawing
+ * proposal i from the Philox blocks (i, c, 32..34) under params->seed (40..42 for the 256 calibration
+ * proposals): a page (l, p), a step n and a new Y, uniform.  Null unless the page migrates at n and Y
+ * changes; dropped (counted as null and as clipped) if the page would be in the pool during a step that is
+ * full; dT = the change of the old step's latency + that of the new step's.  Runs moves [0, params->moves)
+ * of a cooling schedule of params->total_moves; max_len and op_prob are not used; init_mode
+ * KVP_INIT_EMPTY (every chain starts from Y = 0, written by the call) or KVP_INIT_GIVEN (from d_slots).
+ *   d_placement  [L][N][Wd]      in, DEVICE, 16-byte aligned
+ *   d_slots      [C][L][N][P]    in (GIVEN) / out, DEVICE: every chain's final Y
+ *   h_stats      [C]             out, HOST, may be NULL: t_cur is the start's cost plus the accepted dT
+ * The call waits for the stream.  Errors: KVP_EINVAL, KVP_ENOTRACE, KVP_ESHAPE, KVP_EINFEASIBLE (a start that
+ * overfills an inference step or holds a Y out of range), KVP_ENOMEM, KVP_EHIP. */
+int kvp_score_slots(kvp_ctx *ctx, const uint32_t *d_placements, const uint8_t *d_slots, uint32_t S, double *d_cost,
+                    uint32_t *d_excess);
+int kvp_refine_slots(kvp_ctx *ctx, const kvp_anneal_params *params, const uint32_t *d_placement, uint8_t *d_slots,
+                     kvp_chain_stats_t *h_stats);
+
 /* Parallel tempering across the chains of kvp_anneal: an extension, not in the paper, whose search
  * (Sec. III-B) is one annealing run; the exchange step is the standard one (Swendsen & Wang 1986,
  * Geyer 1991).  Used between slices of kvp_anneal (KVP_INIT_CONTINUE):

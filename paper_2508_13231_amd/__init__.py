@@ -31,7 +31,8 @@ KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2
 EXPORTS = ["kvp_create", "kvp_destroy", "kvp_trace_upload", "kvp_score", "kvp_delta_score", "kvp_anneal",
            "kvp_best", "kvp_chain_placement", "kvp_chain_stats", "kvp_plane_unit", "kvp_strerror", "kvp_last_hip_error",
            "kvp_set_score_kernel", "kvp_set_anneal_lookahead", "kvp_set_capacity_mode", "kvp_score_kernel_used", "kvp_baseline", "kvp_wr_policy",
-           "kvp_wr_search", "kvp_strict_excess", "kvp_temper", "kvp_exchange", "kvp_score_static"]
+           "kvp_wr_search", "kvp_strict_excess", "kvp_temper", "kvp_exchange", "kvp_score_static", "kvp_score_slots",
+           "kvp_refine_slots"]
 KVP_STATIC_SCRATCH_BYTES = 32 << 20
 
 
@@ -119,6 +120,10 @@ def lib():
         L.kvp_strerror.argtypes = [i32]
         L.kvp_strict_excess.restype = i32
         L.kvp_strict_excess.argtypes = [vp, vp, C.c_uint32, vp]
+        L.kvp_score_slots.restype = i32
+        L.kvp_score_slots.argtypes = [vp, vp, vp, C.c_uint32, vp, vp]
+        L.kvp_refine_slots.restype = i32
+        L.kvp_refine_slots.argtypes = [vp, vp, vp, vp, vp]
         L.kvp_temper.restype = i32
         L.kvp_temper.argtypes = [vp, vp]
         L.kvp_exchange.restype = i32
@@ -245,6 +250,19 @@ SCORE_KERNEL_NAMES = {1: "rows", 2: "lanes", 6: "quad", 9: "chunk", 10: "rowbloc
 
 def kvp_strict_excess(ctx, d_placements, S, d_excess):
     _check(lib().kvp_strict_excess(ctx, _dptr(d_placements), int(S), _dptr(d_excess)), "kvp_strict_excess")
+
+
+def kvp_score_slots(ctx, d_placements, d_slots, S, d_cost, d_excess):
+    _check(lib().kvp_score_slots(ctx, _dptr(d_placements), _dptr(d_slots), int(S), _dptr(d_cost), _dptr(d_excess)),
+           "kvp_score_slots")
+
+
+def kvp_refine_slots(ctx, params, d_placement, d_slots):
+    """Anneal the migration steps of one placement; returns the chains' statistics (d_slots holds their final Y)."""
+    arr = (kvp_chain_stats_t * int(params.n_chains))()
+    _check(lib().kvp_refine_slots(ctx, C.byref(params), _dptr(d_placement), _dptr(d_slots), C.cast(arr, C.c_void_p)),
+           "kvp_refine_slots")
+    return list(arr)
 
 
 def kvp_temper(ctx, factors):

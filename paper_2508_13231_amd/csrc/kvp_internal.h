@@ -58,6 +58,7 @@ struct kvp_ctx {
     int anneal_lookahead = 0;            // proposals per round in kvp_anneal: 0 auto, 1 or 4
     int capacity_mode = 0;               // KVP_CAPACITY_*: what the next fresh start of kvp_anneal walks under
     int chains_mode = 0;                 // what the present chains walk under
+    unsigned char *d_slots_work = nullptr; size_t slots_work_cap = 0;   // migration steps: counters, moves per step, pool
     uint32_t *d_slot = nullptr;          // per-slot mode: [C][L][N], the pool after every slot of every chain
     bool no_alloc = false;               // set while kvp_score_static runs: kvp_ensure must not allocate
     int last_kernel = 0;                 // scorer that the last kvp_score ran (KVP_SCORE_*), 0 before the first
@@ -265,6 +266,9 @@ int kvp_score_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, dou
 int kvp_ensure(kvp_ctx *ctx, void **p, size_t *cap, size_t bytes);
 int kvp_static_scratch_init(int device);     // kvp_score.hip: resolves the device address of the static scratch
 int kvp_bitslice_build(kvp_ctx *ctx);
+int kvp_slots_state_launch(kvp_ctx *ctx, const uint32_t *X, bool broadcast_x, const uint8_t *Y, uint32_t S, double *d_cost,
+                           uint32_t *d_excess, uint32_t **cnt_out, uint32_t **mig_out, uint32_t **pool_out);
+int kvp_blocksum_from_t_launch(kvp_ctx *ctx, uint32_t S, uint32_t nb_total);
 int kvp_slot_occupancy_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, uint32_t *d_excess, uint32_t *d_table);
 int kvp_rowlane_build(kvp_ctx *ctx);          // kvp_score_rowlane.hip: called at the end of kvp_bitslice_build
 void kvp_free_chains(kvp_ctx *ctx);

@@ -9,6 +9,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <vector>
+
 #include "kvp_internal.h"
 
 #define LOG_WORDS 10   // layer, page, layer2, page2, base, flip1 lo/hi, flip2 lo/hi, spare
@@ -1024,6 +1026,169 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
         m0 = m1;
     }
     ctx->moves_done = m_end;
+    return KVP_OK;
+}
+
+// ---- annealing over the inference steps in which pages migrate (kvp_slots.hip has the scoring) ----
+// One wavefront per chain; the placement X is the same for all chains and does not change.  A proposal
+// names a page (l, p) at step n and a new Y: null unless the page migrates there and Y changes.  The
+// move takes the page out of |M^i| or |M^o| of the old step and into the new one's: two step latencies
+// change, dT = (t' - t) at the old step + (t' - t) at the new one.  A page that enters HBM earlier or
+// leaves it later is in the pool during the steps in between: the lanes look at those (at most L - 1)
+// and the proposal is dropped if one is full.  Control flow is the same for all lanes.
+namespace {
+
+__global__ __launch_bounds__(KVP_WAVE) void refine_slots_kernel(DevProblem q, SAParams sp, const uint32_t *__restrict__ X,
+                                                                const uint32_t *__restrict__ cnt, uint8_t *Yall,
+                                                                uint32_t *mig_all, uint32_t *pool_all,
+                                                                ChainState *__restrict__ states, uint64_t move_begin,
+                                                                uint64_t move_end, int calibrate) {
+    const uint32_t chain = blockIdx.x;
+    const int lane = (int)threadIdx.x;
+    const uint32_t L = q.L, N = q.N, Wd = q.Wd;
+    const size_t G = (size_t)L * N;
+    uint8_t *Y = Yall + (size_t)chain * G * q.P;
+    uint32_t *mig = mig_all + (size_t)chain * G * 2, *pool = pool_all + (size_t)chain * G;
+    ChainState st = states[chain];
+    const uint32_t stream = calibrate ? 40u : 32u;
+    double sum = 0.0;
+    uint32_t npos = 0;
+    DrawBatch B;
+    fill_draws(sp, chain, move_begin, stream, lane, B);
+    for (uint64_t mi = move_begin; mi < move_end; mi++) {
+        if (!calibrate) {
+            uint64_t lvl = mi / sp.mpl;
+            if (lvl > sp.n_levels - 1) lvl = sp.n_levels - 1;
+            while (st.level < lvl) { st.c = st.c * sp.alpha; st.level++; }  // geometric cooling
+            st.moves_done++;
+        }
+        kvp_move m;
+        double u;
+        next_move(q, sp, chain, stream, lane, B, mi, m, u);
+        const uint32_t l = m.layer, p = m.page, n = m.n1, ynew = m.layer2, w = p >> 5, b = p & 31u;
+        int c = 0;
+        if (n > 0 && ((q.Pm[(size_t)n * Wd + w] >> b) & 1u)) {
+            const uint32_t x = ((X[((size_t)l * N + n) * Wd + w] & q.V[(size_t)n * Wd + w]) >> b) & 1u;
+            const uint32_t xp = ((X[((size_t)l * N + n - 1) * Wd + w] & q.V[(size_t)(n - 1) * Wd + w]) >> b) & 1u;
+            c = x == xp ? 0 : (x ? 1 : -1);
+        }
+        const size_t iy = ((size_t)l * N + n) * q.P + p;
+        const uint32_t yold = Y[iy];
+        if (c == 0 || ynew == yold) { if (!calibrate) st.null_moves++; continue; }
+        const uint32_t g_own = n * L + l, g_old = g_own - yold, g_new = g_own - ynew;
+        // the steps during which the page is in the pool only after the move
+        uint32_t lo = 0, hi = 0;
+        if (c > 0 && g_new < g_old) { lo = g_new; hi = g_old; }
+        if (c < 0 && g_new > g_old) { lo = g_old; hi = g_new; }
+        bool full = false;
+        for (uint32_t g = lo + (uint32_t)lane; g < hi; g += KVP_WAVE) full = full || pool[g] + 1u > q.cap;
+        if (ballot64(full)) { if (!calibrate) { st.null_moves++; st.clipped++; } continue; }
+        const uint32_t no = g_old / L, lo_ = g_old - no * L, nn = g_new / L, ln = g_new - nn * L;
+        const uint32_t *co = cnt + ((size_t)lo_ * N + no) * 4, *cn = cnt + ((size_t)ln * N + nn) * 4;
+        const uint32_t mio = mig[(size_t)g_old * 2], moo = mig[(size_t)g_old * 2 + 1];
+        const uint32_t min_ = mig[(size_t)g_new * 2], mon = mig[(size_t)g_new * 2 + 1];
+        const uint32_t acco = q.acc[(size_t)lo_ * N + no], accn = q.acc[(size_t)ln * N + nn], wro = q.wr[no], wrn = q.wr[nn];
+        const uint32_t di = c > 0 ? 1u : 0u, dout = c > 0 ? 0u : 1u;
+        const double t_old = step_time(q, co[0], co[1], mio, moo, acco, wro);
+        const double t_old2 = step_time(q, co[0], co[1], mio - di, moo - dout, acco, wro);
+        const double t_new = step_time(q, cn[0], cn[1], min_, mon, accn, wrn);
+        const double t_new2 = step_time(q, cn[0], cn[1], min_ + di, mon + dout, accn, wrn);
+        const double dT = (t_old2 - t_old) + (t_new2 - t_new);
+        if (calibrate) {
+            if (dT > 0.0) { sum = sum + dT; npos++; }
+            continue;
+        }
+        const bool accept = (dT <= 0.0) || (st.c > 0.0 && u < exp(-dT / st.c));   // Metropolis
+        if (!accept) continue;
+        st.accepted++;
+        if (dT > 0.0) st.uphill++;
+        if (lane == 0) {
+            Y[iy] = (uint8_t)ynew;
+            mig[(size_t)g_old * 2] = mio - di; mig[(size_t)g_old * 2 + 1] = moo - dout;
+            mig[(size_t)g_new * 2] = min_ + di; mig[(size_t)g_new * 2 + 1] = mon + dout;
+        }
+        // in the pool from the new step to the old one (or the other way round) where it was not, or no longer
+        const uint32_t a = min(g_old, g_new), e = max(g_old, g_new);
+        const uint32_t delta = ((c > 0) == (g_new < g_old)) ? 1u : 0xFFFFFFFFu;
+        for (uint32_t g = a + (uint32_t)lane; g < e; g += KVP_WAVE) pool[g] += delta;
+        st.t_cur = st.t_cur + dT;
+        if (st.t_cur < st.t_best) { st.t_best = st.t_cur; st.improved++; }
+        // later proposals read, from other lanes, what this one wrote: one wavefront, program order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    if (calibrate) {
+        st.c0 = npos ? (sum / (double)npos) / sp.neg_ln_p0 : 0.0;
+        st.c = st.c0;
+        st.level = 0;
+    }
+    if (lane == 0) states[chain] = st;
+}
+
+}  // namespace
+
+extern "C" int kvp_refine_slots(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32_t *d_placement, uint8_t *d_slots,
+                                kvp_chain_stats_t *h_stats) {
+    if (!ctx || !p || !d_placement || !d_slots || ((uintptr_t)d_placement & 15u)) return KVP_EINVAL;
+    if (!ctx->has_trace) return KVP_ENOTRACE;
+    if (p->n_chains == 0 || p->n_chains > 65535u || p->n_levels == 0 || !(p->p0 > 0.0 && p->p0 < 1.0) ||
+        !(p->alpha > 0.0 && p->alpha <= 1.0) || p->total_moves == 0 || p->moves > p->total_moves ||
+        (p->init_mode != KVP_INIT_EMPTY && p->init_mode != KVP_INIT_GIVEN))
+        return KVP_EINVAL;
+    KVP_HIP(hipSetDevice(ctx->device));
+    const DevProblem &q = ctx->dp;
+    const uint32_t C = p->n_chains;
+    const size_t G = (size_t)q.L * q.N;
+    if (p->init_mode == KVP_INIT_EMPTY) KVP_HIP(hipMemsetAsync(d_slots, 0, (size_t)C * G * q.P, ctx->stream));
+    double *d_cost = nullptr;
+    uint32_t *d_excess = nullptr;
+    ChainState *d_state = nullptr;
+    auto cleanup = [&]() {
+        if (d_cost) (void)hipFree(d_cost);
+        if (d_excess) (void)hipFree(d_excess);
+        if (d_state) (void)hipFree(d_state);
+    };
+    if (hipMalloc((void **)&d_cost, sizeof(double) * C) != hipSuccess || hipMalloc((void **)&d_excess, 4 * (size_t)C) != hipSuccess ||
+        hipMalloc((void **)&d_state, sizeof(ChainState) * C) != hipSuccess) {
+        (void)hipGetLastError();
+        cleanup();
+        return KVP_ENOMEM;
+    }
+    uint32_t *cnt = nullptr, *mig = nullptr, *pool = nullptr;
+    int rc = kvp_slots_state_launch(ctx, d_placement, true, d_slots, C, d_cost, d_excess, &cnt, &mig, &pool);
+    if (rc) { cleanup(); return rc; }
+    std::vector<uint32_t> hex(C);
+    hipError_t e = hipMemcpyAsync(hex.data(), d_excess, 4 * (size_t)C, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) { (void)hipGetLastError(); cleanup(); return KVP_EHIP; }
+    for (uint32_t c = 0; c < C; c++)
+        if (hex[c] & 0x7FFFFFFFu) { cleanup(); return KVP_EINFEASIBLE; }   // a step overfilled, or a Y out of range
+    init_states_kernel<<<dim3((C + 255) / 256), dim3(256), 0, ctx->stream>>>(d_state, d_cost, C);
+    SAParams sp;
+    sp.seed_lo = (uint32_t)p->seed; sp.seed_hi = (uint32_t)(p->seed >> 32);
+    sp.th0 = (uint64_t)(0.4 * 4294967296.0); sp.th1 = (uint64_t)(0.8 * 4294967296.0);   // the operator field is not used
+    sp.mpl = p->total_moves / p->n_levels; if (sp.mpl < 1) sp.mpl = 1;
+    sp.n_levels = p->n_levels; sp.max_len = 1;
+    sp.alpha = p->alpha; sp.neg_ln_p0 = -log(p->p0);
+    refine_slots_kernel<<<dim3(C), dim3(KVP_WAVE), 0, ctx->stream>>>(q, sp, d_placement, cnt, d_slots, mig, pool, d_state, 0,
+                                                                     CALIB_MOVES, 1);
+    for (uint64_t m0 = 0; m0 < p->moves; m0 += 16384) {                // bounded launches: every wavefront exits after a fixed count
+        const uint64_t m1 = m0 + 16384 < p->moves ? m0 + 16384 : p->moves;
+        refine_slots_kernel<<<dim3(C), dim3(KVP_WAVE), 0, ctx->stream>>>(q, sp, d_placement, cnt, d_slots, mig, pool, d_state, m0,
+                                                                         m1, 0);
+    }
+    e = hipGetLastError();
+    std::vector<ChainState> hs(C);
+    if (e == hipSuccess) e = hipMemcpyAsync(hs.data(), d_state, sizeof(ChainState) * C, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    cleanup();
+    if (e != hipSuccess) { kvp_tls_hip_error = (int)e; kvp_tls_hip_line = __LINE__; (void)hipGetLastError(); return KVP_EHIP; }
+    if (h_stats)
+        for (uint32_t c = 0; c < C; c++) {
+            h_stats[c].t_cur = hs[c].t_cur; h_stats[c].t_best = hs[c].t_best; h_stats[c].c0 = hs[c].c0; h_stats[c].c = hs[c].c;
+            h_stats[c].moves_done = hs[c].moves_done; h_stats[c].accepted = hs[c].accepted; h_stats[c].uphill = hs[c].uphill;
+            h_stats[c].null_moves = hs[c].null_moves; h_stats[c].clipped = hs[c].clipped; h_stats[c].improved = hs[c].improved;
+        }
     return KVP_OK;
 }
 

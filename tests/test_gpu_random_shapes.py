@@ -61,6 +61,14 @@ def test_random_shape_everything_but_the_walk(G, seed):
             K.kvp_strict_excess(g.ctx, g.words(X), len(X), d)
             torch.cuda.synchronize()
             assert d.cpu().numpy().view(np.uint32).tolist() == [O.strict_excess(q, x) for x in X]
+            if tr.L <= 24:                                                # pages migrating in steps of their choice
+                Y = rng.integers(0, tr.L + (seed % 3 == 0), X.shape).astype(np.uint8)
+                dc = torch.empty(len(X), dtype=torch.float64, device=g.dev)
+                K.kvp_score_slots(g.ctx, g.words(X), g.to_dev(Y), len(X), dc, d)
+                torch.cuda.synchronize()
+                for s2 in range(len(X)):
+                    r2 = O.score_slots(q, X[s2], Y[s2])
+                    assert dc[s2].item() == r2.cost and d.cpu().numpy().view(np.uint32)[s2] == r2.excess, ("slots", s2)
             for kind, fn in ((K.KVP_BASELINE_STATIC, O.init_static_frequency), (K.KVP_BASELINE_RECENCY, O.init_recency),
                              (K.KVP_BASELINE_FILL, O.init_static_fill)):
                 assert (g.baseline(kind) == fn(q).astype(bool)).all(), kind
