@@ -267,6 +267,12 @@ int kvp_exchange(kvp_ctx *ctx, uint64_t round, uint32_t *h_traded);
  * KVP_EINVAL. */
 int kvp_set_anneal_lookahead(kvp_ctx *ctx, int proposals_per_round);
 
+/* Tuning knob of kvp_anneal, read by its next fresh start: the number of logged edits after which a
+ * chain writes its best schedule out and starts its log afresh (launches are cut to that many moves
+ * per chain).  0 (default): chosen from the sizes, see kvp_anneal; a value of total_moves or more: the
+ * log is not bounded.  The walk and its results do not depend on it.  Errors: KVP_EINVAL (null ctx). */
+int kvp_set_anneal_log_entries(kvp_ctx *ctx, uint64_t entries);
+
 /* Which reading of Eq. 5 the walks of kvp_anneal honour (Sec. III-A: a decision S(n, l) is made at
  * every inference step, layer l of token step n).
  *   KVP_CAPACITY_PER_STEP (default)  the pool is counted once per token step, when all layers have
@@ -295,8 +301,12 @@ int kvp_set_capacity_mode(kvp_ctx *ctx, int mode);
  * earlier call stay as they are.  More than 65535 chains: KVP_ESHAPE.
  * Device memory per chain, held until the next trace or the next fresh start:
  * the schedule (L*N*Wd*4 bytes), its step counters (L*N*16), occupancy (N*4)
- * and the log of accepted edits since the chain's best schedule, sized for the
- * worst case of every move accepted: total_moves * 40 bytes. */
+ * and the log of accepted edits since the chain's best schedule (40 bytes an
+ * entry, one entry per move at most): total_moves entries, or, where that is
+ * more than twice what a schedule takes, 2 * max(16384, schedule bytes / 40)
+ * entries and one more schedule: a chain whose log has passed half of that
+ * writes its best schedule out between two launches and starts its log afresh
+ * (kvp_set_anneal_log_entries sets the half). */
 int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *params, const uint32_t *d_init);
 
 /* Sec. III-B (the search returns the schedule of the best latency found).

@@ -35,7 +35,8 @@ static void free_dev(void *p) { if (p) (void)hipFree(p); }
 void kvp_free_chains(kvp_ctx *ctx) {
     free_dev(ctx->d_X); free_dev(ctx->d_cnt); free_dev(ctx->d_occ); free_dev(ctx->d_state);
     free_dev(ctx->d_log); free_dev(ctx->d_cost); free_dev(ctx->d_excess); free_dev(ctx->d_argmin); free_dev(ctx->d_slot);
-    ctx->d_X = ctx->d_cnt = ctx->d_occ = ctx->d_log = ctx->d_excess = ctx->d_argmin = ctx->d_slot = nullptr;
+    free_dev(ctx->d_Xbest);
+    ctx->d_X = ctx->d_cnt = ctx->d_occ = ctx->d_log = ctx->d_excess = ctx->d_argmin = ctx->d_slot = ctx->d_Xbest = nullptr;
     ctx->d_state = nullptr; ctx->d_cost = nullptr;
     ctx->log_cap = 0; ctx->has_chains = false; ctx->moves_done = 0;
 }
@@ -87,6 +88,12 @@ extern "C" const char *kvp_strerror(int code) {
         case KVP_EINFEASIBLE: return "starting schedule exceeds the HBM capacity";
         default: return "unknown error";
     }
+}
+
+extern "C" int kvp_set_anneal_log_entries(kvp_ctx *ctx, uint64_t entries) {
+    if (!ctx) return KVP_EINVAL;
+    ctx->log_entries = entries;
+    return KVP_OK;
 }
 
 extern "C" int kvp_set_capacity_mode(kvp_ctx *ctx, int mode) {

@@ -59,6 +59,9 @@ struct kvp_ctx {
     int capacity_mode = 0;               // KVP_CAPACITY_*: what the next fresh start of kvp_anneal walks under
     int chains_mode = 0;                 // what the present chains walk under
     unsigned char *d_slots_work = nullptr; size_t slots_work_cap = 0;   // migration steps: counters, moves per step, pool
+    uint32_t *d_Xbest = nullptr;         // bounded log: [C][L][N][Wd], the best schedule of chains that have written it out
+    uint64_t log_soft = 0;               // bounded log: entries after which a chain writes its best schedule out (0: not bounded)
+    uint64_t log_entries = 0;            // kvp_set_anneal_log_entries: 0 = chosen from the sizes
     uint32_t *d_slot = nullptr;          // per-slot mode: [C][L][N], the pool after every slot of every chain
     bool no_alloc = false;               // set while kvp_score_static runs: kvp_ensure must not allocate
     int last_kernel = 0;                 // scorer that the last kvp_score ran (KVP_SCORE_*), 0 before the first

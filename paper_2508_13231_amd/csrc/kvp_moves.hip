@@ -20,6 +20,7 @@ struct ChainState {
     double t_cur, t_best, c0, c;
     uint64_t accepted, uphill, null_moves, clipped, improved, log_len, moves_done;
     uint32_t level, log_overflow;
+    uint32_t best_saved, pad_;   // the best schedule is the chain's snapshot (the log does not lead to it and is not kept)
 };
 
 struct SAParams {
@@ -585,8 +586,10 @@ __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams
             if (R.dT > 0.0) st.uphill++;
             apply_move<SLOT>(q, X, cnt, occ, m, R, slot);
             st.t_cur = st.t_cur + R.dT;
-            // edits since the best schedule, so that it can be rebuilt by undoing them
-            if (st.log_len < log_cap) {
+            // edits since the best schedule, so that it can be rebuilt by undoing them (not while the best
+            // schedule is held as a snapshot: then nothing leads back to it but the snapshot itself)
+            if (st.best_saved) {
+            } else if (st.log_len < log_cap) {
                 if (lane < LOG_WORDS) {
                     uint32_t w;
                     switch (lane) {
@@ -607,7 +610,7 @@ __global__ __launch_bounds__(KVP_WAVE) void anneal_kernel(DevProblem q, SAParams
             } else {
                 st.log_overflow = 1;
             }
-            if (st.t_cur < st.t_best) { st.t_best = st.t_cur; st.improved++; st.log_len = 0; }
+            if (st.t_cur < st.t_best) { st.t_best = st.t_cur; st.improved++; st.log_len = 0; st.best_saved = 0; }
             // Later proposals read, from other lanes, what this one wrote.  The chain is one wavefront:
             // its memory instructions reach the cache in program order, so a fence of wavefront scope
             // (no wait; it only keeps the compiler from moving accesses across) is all that is needed.
@@ -734,7 +737,7 @@ __global__ __launch_bounds__(SPEC * KVP_WAVE) void anneal_rounds_kernel(
             if (w == f) {
                 apply_move(q, X, cnt, s_occ, m, R);
                 // edits since the best schedule, so that it can be rebuilt by undoing them
-                if (st.log_len < log_cap && lane < LOG_WORDS) {
+                if (!st.best_saved && st.log_len < log_cap && lane < LOG_WORDS) {
                     uint32_t e;
                     switch (lane) {
                         case 0: e = m.layer; break;
@@ -752,9 +755,10 @@ __global__ __launch_bounds__(SPEC * KVP_WAVE) void anneal_rounds_kernel(
                 }
             }
             st.t_cur = st.t_cur + dT;
-            if (st.log_len < log_cap) st.log_len++;
+            if (st.best_saved) {}
+            else if (st.log_len < log_cap) st.log_len++;
             else st.log_overflow = 1;
-            if (st.t_cur < st.t_best) { st.t_best = st.t_cur; st.improved++; st.log_len = 0; }
+            if (st.t_cur < st.t_best) { st.t_best = st.t_cur; st.improved++; st.log_len = 0; st.best_saved = 0; }
         }
         // the cooling state as the last proposal reached leaves it
         for (const uint32_t to = level_of(mi + reached - 1); st.level < to; st.level++) st.c = st.c * sp.alpha;
@@ -785,13 +789,15 @@ __global__ __launch_bounds__(SPEC * KVP_WAVE) void anneal_rounds_kernel(
 
 // Apply (or, applied twice, undo) every logged edit of every chain: XOR commutes,
 // so one wavefront per log entry and atomics on the words are enough.
+// Only chains whose log holds more than `longer_than` entries take part.
 __global__ __launch_bounds__(256) void log_xor_kernel(DevProblem q, uint32_t *__restrict__ Xall,
                                                       const ChainState *__restrict__ states,
                                                       const uint32_t *__restrict__ log_all, uint64_t log_cap,
-                                                      uint32_t chain0) {
+                                                      uint32_t chain0, uint64_t longer_than) {
     const uint32_t chain = chain0 + blockIdx.y;
     const int lane = lane_id();
     const uint64_t n_entries = states[chain].log_len;
+    if (n_entries <= longer_than) return;
     const size_t rows = (size_t)q.L * q.N;
     uint32_t *X = Xall + (size_t)chain * rows * q.Wd;
     const uint32_t *log = log_all + (size_t)chain * log_cap * LOG_WORDS;
@@ -805,6 +811,35 @@ __global__ __launch_bounds__(256) void log_xor_kernel(DevProblem q, uint32_t *__
         if (n < 0 || n >= (int)q.N) continue;
         if ((f1 >> lane) & 1ull) atomicXor(&X[((size_t)l * q.N + n) * q.Wd + (p >> 5)], 1u << (p & 31));
         if ((f2 >> lane) & 1ull) atomicXor(&X[((size_t)l2 * q.N + n) * q.Wd + (pq >> 5)], 1u << (pq & 31));
+    }
+}
+
+// Bounding the log: a chain whose log has grown beyond `soft` entries gets its best schedule written out
+// (a copy of the current one, the logged edits undone by log_xor_kernel) and starts its log afresh.
+__global__ __launch_bounds__(256) void snapshot_copy_kernel(const uint32_t *__restrict__ Xall, uint32_t *__restrict__ Xbest,
+                                                            const ChainState *__restrict__ states, size_t per,
+                                                            uint64_t soft) {
+    const uint32_t chain = blockIdx.y;
+    if (states[chain].log_len <= soft) return;
+    const uint32_t *src = Xall + (size_t)chain * per;
+    uint32_t *dst = Xbest + (size_t)chain * per;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < per; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+__global__ void snapshot_commit_kernel(ChainState *states, uint32_t C, uint64_t soft) {
+    const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C || states[c].log_len <= soft) return;
+    states[c].log_len = 0;
+    states[c].best_saved = 1;
+}
+// Chains whose best schedule is a snapshot: exchange it with the current one (applied twice: back again).
+__global__ __launch_bounds__(256) void snapshot_swap_kernel(uint32_t *__restrict__ Xall, uint32_t *__restrict__ Xbest,
+                                                            const ChainState *__restrict__ states, size_t per,
+                                                            uint32_t chain0) {
+    const uint32_t chain = chain0 + blockIdx.y;
+    if (!states[chain].best_saved) return;
+    uint32_t *a = Xall + (size_t)chain * per, *b = Xbest + (size_t)chain * per;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < per; i += (size_t)gridDim.x * 256) {
+        const uint32_t t = a[i]; a[i] = b[i]; b[i] = t;
     }
 }
 
@@ -857,9 +892,29 @@ static bool same_schedule(const kvp_anneal_params &a, const kvp_anneal_params &b
            a.op_prob[0] == b.op_prob[0] && a.op_prob[1] == b.op_prob[1] && a.op_prob[2] == b.op_prob[2];
 }
 
+// current <-> best-so-far schedules of the chains [chain0, chain0 + nchains): the logged edits are XOR-ed in
+// (or out again), and a chain whose best schedule is a snapshot exchanges the two
 static int launch_log_xor(kvp_ctx *ctx, uint32_t chain0, uint32_t nchains) {
+    const size_t per = (size_t)ctx->dp.L * ctx->dp.N * ctx->dp.Wd;
+    if (ctx->d_Xbest) {
+        snapshot_swap_kernel<<<dim3(64, nchains), dim3(256), 0, ctx->stream>>>(ctx->d_X, ctx->d_Xbest, ctx->d_state, per, chain0);
+        KVP_HIP(hipGetLastError());
+    }
     log_xor_kernel<<<dim3(64, nchains), dim3(256), 0, ctx->stream>>>(ctx->dp, ctx->d_X, ctx->d_state, ctx->d_log,
-                                                                    ctx->log_cap, chain0);
+                                                                    ctx->log_cap, chain0, 0);
+    KVP_HIP(hipGetLastError());
+    return KVP_OK;
+}
+
+// Bounded log: after a launch, chains whose log has passed the soft limit write their best schedule out.
+static int compact_logs(kvp_ctx *ctx, uint32_t C) {
+    const size_t per = (size_t)ctx->dp.L * ctx->dp.N * ctx->dp.Wd;
+    snapshot_copy_kernel<<<dim3(64, C), dim3(256), 0, ctx->stream>>>(ctx->d_X, ctx->d_Xbest, ctx->d_state, per, ctx->log_soft);
+    KVP_HIP(hipGetLastError());
+    log_xor_kernel<<<dim3(64, C), dim3(256), 0, ctx->stream>>>(ctx->dp, ctx->d_Xbest, ctx->d_state, ctx->d_log, ctx->log_cap, 0,
+                                                              ctx->log_soft);
+    KVP_HIP(hipGetLastError());
+    snapshot_commit_kernel<<<dim3((C + 255) / 256), dim3(256), 0, ctx->stream>>>(ctx->d_state, C, ctx->log_soft);
     KVP_HIP(hipGetLastError());
     return KVP_OK;
 }
@@ -892,12 +947,23 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
         if (p->moves > p->total_moves) return KVP_EINVAL;            // before the previous chains are given up
         KVP_HIP(hipStreamSynchronize(ctx->stream));
         kvp_free_chains(ctx);
-        ctx->log_cap = p->total_moves;
+        // The log of accepted edits: one entry per move at most, so total_moves entries always suffice.  When
+        // that is more than twice what a schedule takes, the log is bounded instead: launches are cut to `soft`
+        // moves, and a chain whose log has passed `soft` entries after a launch writes its best schedule out
+        // and starts afresh, so 2 * soft entries and one more schedule per chain do, however long the run.
+        const uint64_t sched_entries = (uint64_t)(per * 4 / (LOG_WORDS * 4));
+        uint64_t soft = ctx->log_entries ? ctx->log_entries : (sched_entries > 16384 ? sched_entries : 16384);
+        if (!ctx->log_entries && p->total_moves <= 2 * soft) soft = 0;
+        if (soft >= p->total_moves) soft = 0;
+        ctx->log_soft = soft;
+        ctx->log_cap = soft ? 2 * soft : p->total_moves;
         const struct { void **p; size_t bytes; } want[] = {
+            {(void **)&ctx->d_Xbest, soft ? per * C * 4 : 0},
             {(void **)&ctx->d_X, per * C * 4}, {(void **)&ctx->d_cnt, rows * C * 16}, {(void **)&ctx->d_occ, (size_t)q.N * C * 4},
             {(void **)&ctx->d_state, sizeof(ChainState) * C}, {(void **)&ctx->d_log, (size_t)ctx->log_cap * C * LOG_WORDS * 4},
             {(void **)&ctx->d_cost, sizeof(double) * C}, {(void **)&ctx->d_excess, 4 * (size_t)C}, {(void **)&ctx->d_argmin, 16}};
         for (const auto &w : want) {
+            if (!w.bytes) continue;
             const hipError_t e = hipMalloc(w.p, w.bytes);
             if (e != hipSuccess) {
                 kvp_tls_hip_error = (int)e; kvp_tls_hip_line = __LINE__;
@@ -959,7 +1025,7 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
     sp.n_levels = p->n_levels; sp.max_len = p->max_len;
     sp.alpha = p->alpha; sp.neg_ln_p0 = -log(p->p0);
     // bounded launches: every wavefront runs a fixed number of moves and exits
-    const uint64_t chunk = 16384;
+    const uint64_t chunk = ctx->log_soft && ctx->log_soft < 16384 ? ctx->log_soft : 16384;
     uint64_t m0 = ctx->moves_done;
     const uint64_t m_end = m0 + p->moves;
     bool first = ctx->moves_done == 0;
@@ -1023,6 +1089,7 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
         if (rounds) launch_rounds(m0, m1);
         else launch(m0, m1, 0);
         KVP_HIP(hipGetLastError());
+        if (ctx->log_soft) { const int rcc = compact_logs(ctx, C); if (rcc) return rcc; }
         m0 = m1;
     }
     ctx->moves_done = m_end;

@@ -461,6 +461,39 @@ def test_anneal_resume_and_modes(G):
         assert e.value.code == K.KVP_ENOCHAINS
 
 
+@pytest.mark.parametrize("lookahead", [1, 4], ids=["serial", "four-per-round"])
+@pytest.mark.parametrize("name,scale,entries,per_slot", [("tiny", 1.0, 40, False), ("tiny", 1.0, 7, False),
+                                                         ("llama8b", 0.125, 25, False), ("llama8b", 0.125, 60, True),
+                                                         ("gqa70b", 0.0625, 30, False)])
+def test_anneal_with_a_bounded_log_keeps_every_best_schedule(G, name, scale, entries, per_slot, lookahead):
+    """The log of accepted edits cut to a few entries: chains write their best schedule out again and again.  Walks,
+    best schedules and costs are those of the oracle (and of the unbounded log), also across a continued slice."""
+    import paper_2508_13231_amd as K
+    tr = W.config(name, scale)
+    q = O.Problem(tr)
+    chains, total = 4, 3000
+    X0 = O.init_static_frequency(q)
+    res, bi = O.anneal(q, range(chains), X0, seed=13, total_moves=total, per_slot=per_slot)
+    with G(tr) as g:
+        K.kvp_set_anneal_lookahead(g.ctx, lookahead)
+        K.kvp_set_anneal_log_entries(g.ctx, entries)
+        K.kvp_set_capacity_mode(g.ctx, K.KVP_CAPACITY_PER_SLOT if per_slot else K.KVP_CAPACITY_PER_STEP)
+        _anneal_gpu(g, tr, chains, total, moves=1100, init=X0, seed=13)
+        mid = K.kvp_best(g.ctx, g.shape_words, chains)                # reading the best schedules disturbs nothing
+        _anneal_gpu(g, tr, chains, total, moves=total - 1100, seed=13, mode=K.KVP_INIT_CONTINUE)
+        cost, chain, words, cc = K.kvp_best(g.ctx, g.shape_words, chains)
+        again = K.kvp_best(g.ctx, g.shape_words, chains)
+        assert again[0] == cost and (again[2] == words).all() and (mid[3] >= cc).all()
+        stats = K.kvp_chain_stats(g.ctx, chains)
+        for c in range(chains):
+            best = g.unpack(K.kvp_chain_placement(g.ctx, c, 1, g.shape_words))
+            cur = g.unpack(K.kvp_chain_placement(g.ctx, c, 0, g.shape_words))
+            assert (best == res[c].best_X).all() and (cur == res[c].X).all(), (name, c)
+            assert cc[c] == res[c].best_cost and stats[c].accepted == res[c].accepted and stats[c].improved == res[c].improved
+            assert stats[c].accepted > 4 * entries, "the log never filled: nothing tested"
+        assert chain == bi and (g.unpack(words) == res[bi].best_X).all()
+
+
 def _strict_excess_gpu(g, X):
     import torch
     import paper_2508_13231_amd as K
