@@ -267,6 +267,12 @@ int kvp_exchange(kvp_ctx *ctx, uint64_t round, uint32_t *h_traded);
  * KVP_EINVAL. */
 int kvp_set_anneal_lookahead(kvp_ctx *ctx, int proposals_per_round);
 
+/* Tuning knob of the placement generators (KVP_BASELINE_RECENCY, kvp_wr_policy, kvp_wr_search): they
+ * work through the token steps in batches whose per-step keys, window counts and wanted sets fit this
+ * many bytes of scratch (one step at least).  0 (default): one gigabyte (recency), two (policy).  The
+ * results do not depend on it.  Errors: KVP_EINVAL (null ctx). */
+int kvp_set_generator_batch_bytes(kvp_ctx *ctx, uint64_t bytes);
+
 /* Tuning knob of kvp_anneal, read by its next fresh start: the number of logged edits after which a
  * chain writes its best schedule out and starts its log afresh (launches are cut to that many moves
  * per chain).  0 (default): chosen from the sizes, see kvp_anneal; a value of total_moves or more: the

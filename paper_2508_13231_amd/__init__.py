@@ -30,7 +30,7 @@ KVP_MOVE_OK, KVP_MOVE_CLIPPED, KVP_MOVE_NULL = 0, 1, 2
 
 EXPORTS = ["kvp_create", "kvp_destroy", "kvp_trace_upload", "kvp_score", "kvp_delta_score", "kvp_anneal",
            "kvp_best", "kvp_chain_placement", "kvp_chain_stats", "kvp_plane_unit", "kvp_strerror", "kvp_last_hip_error",
-           "kvp_set_score_kernel", "kvp_set_anneal_lookahead", "kvp_set_capacity_mode", "kvp_set_anneal_log_entries", "kvp_score_kernel_used", "kvp_baseline", "kvp_wr_policy",
+           "kvp_set_score_kernel", "kvp_set_anneal_lookahead", "kvp_set_capacity_mode", "kvp_set_anneal_log_entries", "kvp_set_generator_batch_bytes", "kvp_score_kernel_used", "kvp_baseline", "kvp_wr_policy",
            "kvp_wr_search", "kvp_strict_excess", "kvp_temper", "kvp_exchange", "kvp_score_static", "kvp_score_slots",
            "kvp_refine_slots"]
 KVP_STATIC_SCRATCH_BYTES = 32 << 20
@@ -134,6 +134,8 @@ def lib():
         L.kvp_set_capacity_mode.argtypes = [vp, i32]
         L.kvp_set_anneal_log_entries.restype = i32
         L.kvp_set_anneal_log_entries.argtypes = [vp, C.c_uint64]
+        L.kvp_set_generator_batch_bytes.restype = i32
+        L.kvp_set_generator_batch_bytes.argtypes = [vp, C.c_uint64]
         L.kvp_set_score_kernel.restype = i32
         L.kvp_set_score_kernel.argtypes = [vp, i32]
         L.kvp_wr_policy.restype = i32
@@ -280,6 +282,10 @@ def kvp_exchange(ctx, round: int, count: bool = True) -> int:
     n = C.c_uint32(0)
     _check(lib().kvp_exchange(ctx, int(round), C.byref(n) if count else None), "kvp_exchange")
     return int(n.value) if count else -1
+
+
+def kvp_set_generator_batch_bytes(ctx, nbytes: int):
+    _check(lib().kvp_set_generator_batch_bytes(ctx, int(nbytes)), "kvp_set_generator_batch_bytes")
 
 
 def kvp_set_anneal_log_entries(ctx, entries: int):

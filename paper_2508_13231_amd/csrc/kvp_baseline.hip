@@ -206,9 +206,10 @@ extern "C" int kvp_baseline(kvp_ctx *ctx, int kind, uint32_t *d_placement) {
         fill_kernel<<<dim3(1), dim3(BT), 0, ctx->stream>>>(q, cap, work, d_placement);
         KVP_HIP(hipGetLastError());
     } else {
-        // batches of steps whose keys fit a gigabyte (at least one step)
+        // batches of steps whose keys fit a gigabyte, or what kvp_set_generator_batch_bytes says (at least one step)
         const uint64_t per_step = (uint64_t)G * sizeof(uint16_t);
-        const uint32_t batch = (uint32_t)(per_step >= (1ull << 30) ? 1 : (1ull << 30) / per_step < q.N ? (1ull << 30) / per_step : q.N);
+        const uint64_t budget = ctx->gen_batch_bytes ? ctx->gen_batch_bytes : (1ull << 30);
+        const uint32_t batch = (uint32_t)(per_step >= budget ? 1 : budget / per_step < q.N ? budget / per_step : q.N);
         rc = kvp_ensure(ctx, (void **)&ctx->d_sel_keys, &ctx->sel_keys_cap, (size_t)batch * per_step);
         if (rc) return rc;
         if (lds > 48 * 1024)

@@ -90,6 +90,12 @@ extern "C" const char *kvp_strerror(int code) {
     }
 }
 
+extern "C" int kvp_set_generator_batch_bytes(kvp_ctx *ctx, uint64_t bytes) {
+    if (!ctx) return KVP_EINVAL;
+    ctx->gen_batch_bytes = bytes;
+    return KVP_OK;
+}
+
 extern "C" int kvp_set_anneal_log_entries(kvp_ctx *ctx, uint64_t entries) {
     if (!ctx) return KVP_EINVAL;
     ctx->log_entries = entries;

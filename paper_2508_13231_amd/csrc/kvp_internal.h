@@ -62,6 +62,7 @@ struct kvp_ctx {
     uint32_t *d_Xbest = nullptr;         // bounded log: [C][L][N][Wd], the best schedule of chains that have written it out
     uint64_t log_soft = 0;               // bounded log: entries after which a chain writes its best schedule out (0: not bounded)
     uint64_t log_entries = 0;            // kvp_set_anneal_log_entries: 0 = chosen from the sizes
+    uint64_t gen_batch_bytes = 0;        // kvp_set_generator_batch_bytes: 0 = one / two gigabytes
     uint32_t *d_slot = nullptr;          // per-slot mode: [C][L][N], the pool after every slot of every chain
     bool no_alloc = false;               // set while kvp_score_static runs: kvp_ensure must not allocate
     int last_kernel = 0;                 // scorer that the last kvp_score ran (KVP_SCORE_*), 0 before the first

@@ -317,10 +317,12 @@ extern "C" int kvp_wr_policy(kvp_ctx *ctx, uint32_t n, const uint32_t *h_w, cons
     }
     const uint32_t nu = (uint32_t)uw.size();
     host.insert(host.end(), uw.begin(), uw.end());
-    // steps per batch: the counts and wanted masks of a batch take two gigabytes at most (one step at least)
+    // steps per batch: the counts and wanted masks of a batch take two gigabytes at most, or what
+    // kvp_set_generator_batch_bytes says (one step at least)
     const size_t LW = (size_t)q.L * q.Wd, G = (size_t)G64;
     const size_t per_step = (size_t)nu * (G * fbytes + LW * 4);
-    const uint32_t B = (uint32_t)(per_step >= ((size_t)2 << 30) ? 1 : ((size_t)2 << 30) / per_step < q.N ? ((size_t)2 << 30) / per_step : q.N);
+    const size_t budget = ctx->gen_batch_bytes ? (size_t)ctx->gen_batch_bytes : ((size_t)2 << 30);
+    const uint32_t B = (uint32_t)(per_step >= budget ? 1 : budget / per_step < q.N ? budget / per_step : q.N);
     // layout, in words: candidate table | pools | wanted masks | count state | counts
     const size_t o_pool = (host.size() + 3) & ~(size_t)3, o_want = o_pool + (size_t)n * LW, o_state = o_want + (size_t)nu * B * LW;
     const size_t o_f = (o_state + ((size_t)nu * G * fbytes + 3) / 4 + 31) & ~(size_t)31;   // a word's 32 counts: whole 16-byte vectors

@@ -741,6 +741,31 @@ def test_wr_policy_matches_oracle(G, name, tr):
             assert (g.unpack(got[i]) == want).all(), (name, w, r)
 
 
+@pytest.mark.parametrize("steps_per_batch", [1, 3, 7])
+@pytest.mark.parametrize("name", ["tiny", "serving/16", "rand-tiles", "gqa70b/16"])
+def test_generators_in_small_batches_of_steps(G, name, steps_per_batch):
+    """The recency placement and the look-ahead policy work through the token steps in batches that fit a scratch budget;
+    with a budget of one, three or seven steps the state they carry from batch to batch is exercised on small traces."""
+    import torch
+    import paper_2508_13231_amd as K
+    tr = dict(CASES)[name]
+    q = O.Problem(tr)
+    pairs = tr.L * tr.n_words * 32
+    cands = [(1, 10), (3, 5), (3, 2), (9, 7), (tr.N + 2, 4)]
+    with G(tr) as g:
+        K.kvp_set_generator_batch_bytes(g.ctx, steps_per_batch * pairs * 2)              # 16-bit keys per pair and step
+        assert (g.baseline(K.KVP_BASELINE_RECENCY) == O.init_recency(q).astype(bool)).all()
+        nu = len({min(w, tr.N) for w, _ in cands})
+        fbytes = 1 if max(min(w, tr.N) for w, _ in cands) * tr.K <= 255 else 2
+        K.kvp_set_generator_batch_bytes(g.ctx, steps_per_batch * nu * (pairs * fbytes + pairs // 8))
+        d = torch.full((len(cands), tr.L, tr.N, tr.n_words), -1, dtype=torch.int32, device=g.dev)
+        K.kvp_wr_policy(g.ctx, [c[0] for c in cands], [c[1] for c in cands], d)
+        torch.cuda.synchronize()
+        got = d.cpu().numpy().view(np.uint32)
+        for i, (w, r) in enumerate(cands):
+            assert (g.unpack(got[i]) == O.wr_policy(q, w, r).astype(bool)).all(), (name, w, r)
+
+
 @pytest.mark.parametrize("name,scale,kw", [("tiny", 1.0, dict(w_max=12, total_moves=300, seed=7, stop_rel=0.0, c_min_frac=0.0)),
                                            ("tiny", 1.0, dict(w_max=20, total_moves=2000, seed=1)),
                                            ("llama8b", 0.25, dict(w_max=8, total_moves=60, n_levels=6, seed=3, w0=3, r10_0=9))])
