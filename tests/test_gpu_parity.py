@@ -741,6 +741,24 @@ def test_wr_policy_matches_oracle(G, name, tr):
             assert (g.unpack(got[i]) == want).all(), (name, w, r)
 
 
+def test_wr_policy_with_wide_windows_and_many_planes(G):
+    """Windows x planes above 255 (16-bit window counts) and above 480 (no room for a histogram per wavefront:
+    the ties are counted in a pass of their own)."""
+    import torch
+    import paper_2508_13231_amd as K
+    tr = dict(CASES)["gqa70b/16"]                                     # 8 planes, 128 steps
+    q = O.Problem(tr)
+    cands = [(33, 1), (40, 5), (70, 5), (128, 10), (90, 3)]
+    with G(tr) as g:
+        for batch in ([cands[0], cands[1]], cands[2:], cands):
+            d = torch.full((len(batch), tr.L, tr.N, tr.n_words), -1, dtype=torch.int32, device=g.dev)
+            K.kvp_wr_policy(g.ctx, [c[0] for c in batch], [c[1] for c in batch], d)
+            torch.cuda.synchronize()
+            got = d.cpu().numpy().view(np.uint32)
+            for i, (w, r) in enumerate(batch):
+                assert (g.unpack(got[i]) == O.wr_policy(q, w, r).astype(bool)).all(), (w, r)
+
+
 @pytest.mark.parametrize("steps_per_batch", [1, 3, 7])
 @pytest.mark.parametrize("name", ["tiny", "serving/16", "rand-tiles", "gqa70b/16"])
 def test_generators_in_small_batches_of_steps(G, name, steps_per_batch):
