@@ -106,6 +106,9 @@ def lib():
                                       C.c_void_p]
         L.orc_slot_bytes.restype = None
         L.orc_slot_bytes.argtypes = [C.POINTER(_Problem), C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+        L.orc_draw_slot_move.restype = None
+        L.orc_draw_slot_move.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32,
+                                         C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_double)]
         L.orc_refine_slots.restype = C.c_int
         L.orc_refine_slots.argtypes = [C.POINTER(_Problem), C.POINTER(_SAParams), C.c_uint32, C.c_void_p, C.c_void_p,
                                        C.POINTER(_SAState)]
@@ -308,6 +311,16 @@ class SlotWalk:
     clipped: int
     improved: int
     state: object = None
+
+
+def draw_slot_moves(chain, first, count, *, seed, stream, M, L):
+    """Proposals first .. first+count-1 of the annealing over migration steps: (index of the migrating page, new Y, u)."""
+    idx, y, us = np.zeros(count, np.int64), np.zeros(count, np.int64), np.zeros(count)
+    a, b, u, f = C.c_uint32(0), C.c_uint32(0), C.c_double(0.0), lib().orc_draw_slot_move
+    for j in range(count):
+        f(int(seed), int(chain), int(first) + j, int(stream), int(M), int(L), C.byref(a), C.byref(b), C.byref(u))
+        idx[j], y[j], us[j] = a.value, b.value, u.value
+    return idx, y, us
 
 
 def refine_slots(tr, chain, X, Y0, *, seed, total_moves, move_begin=0, move_end=None, n_levels=100, p0=0.8, alpha=0.9,

@@ -782,20 +782,35 @@ double orc_score_slots(const orc_problem *q, const uint8_t *X, const uint8_t *Y,
     return T;
 }
 
+/* Proposal mi of a chain in the annealing over migration steps: ONE Philox block, counter (mi lo,
+ * mi hi, chain, stream) under the seed.  Word 0 picks one of the M migrating pages (an index in
+ * 0 .. M-1 is the high word of 32 random bits x M), word 1 the new Y in 0 .. L-1, words 2 and 3 give
+ * the 52 bits of the acceptance draw u in (0, 1), as in orc_draw_move.  Exported for the pins. */
+void orc_draw_slot_move(uint64_t seed, uint32_t chain, uint64_t mi, uint32_t stream, uint32_t M, uint32_t L,
+                        uint32_t *idx, uint32_t *ynew, double *u) {
+    uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t ctr[4] = {(uint32_t)mi, (uint32_t)(mi >> 32), chain, stream}, r[4];
+    orc_philox4x32_10(ctr, key, r);
+    *idx = (uint32_t)(((uint64_t)r[0] * M) >> 32);
+    *ynew = (uint32_t)(((uint64_t)r[1] * L) >> 32);
+    uint64_t bits = ((uint64_t)r[2] << 20) | (r[3] >> 12);
+    *u = ((double)bits + 0.5) * (1.0 / 4503599627370496.0);
+}
+
 /* Annealing over the migration steps Y of a fixed placement X (the Metropolis skeleton of
  * Sec. III-B: acceptance exp(-dT/C), C0 from p0 over 256 proposals that are not applied, cooling by
- * alpha per level).  Proposal mi of a chain: the draw of orc_draw_move on stream 32 (40 for the
- * calibration), of which layer, page, first step name the page (l, p) at step n and layer2, uniform
- * in 0 .. L-1, the new Y.  Null if the page does not migrate at n or Y stays.  A page that enters
- * HBM earlier, or leaves it later, is in the pool during the steps between the old and the new
- * one: if one of them is full the proposal is dropped (counted as null and as clipped).
+ * alpha per level).  The pages that migrate are those of X: they are listed once, in the order
+ * (layer, step, page), and a proposal (orc_draw_slot_move, stream 32; 40 for the calibration) names
+ * one of them and a new Y.  Null if Y stays (or nothing migrates at all).  A page that enters HBM
+ * earlier, or leaves it later, is in the pool during the steps between the old and the new one: if
+ * one of them is full the proposal is dropped (counted as null and as clipped).
  * dT = (t' - t) at the old step + (t' - t) at the new step, in that order.
  * X must be feasible with Y at every inference step (-2 otherwise). */
 int orc_refine_slots(const orc_problem *q, const orc_sa_params *sp, uint32_t chain, const uint8_t *X,
                      uint8_t *Y, orc_sa_state *st) {
-    int L = q->L, N = q->N;
+    int L = q->L, N = q->N, P = q->P;
     size_t G = (size_t)L * N;
-    if (sp->n_levels < 1 || L > 256) return -1;
+    if (sp->n_levels < 1 || L > 256 || (uint64_t)G * P >= (1ull << 32)) return -1;
     double *t = (double *)malloc(sizeof(double) * (G ? G : 1));
     uint32_t *pool = (uint32_t *)malloc(sizeof(uint32_t) * (G ? G : 1));
     uint64_t (*vol)[6] = (uint64_t (*)[6])malloc(sizeof(uint64_t[6]) * (G ? G : 1));
@@ -803,6 +818,13 @@ int orc_refine_slots(const orc_problem *q, const orc_sa_params *sp, uint32_t cha
     double T0 = orc_score_slots(q, X, Y, &ex, t, pool);
     if (ex != 0) { free(t); free(pool); free(vol); return -2; }
     for (size_t g = 0; g < G; g++) orc_slot_bytes(q, X, Y, (int)g, vol[g]);
+    /* the migrating pages, in the order (l, n, p) */
+    uint32_t M = 0;
+    for (int l = 0; l < L; l++) for (int n = 0; n < N; n++) for (int p = 0; p < P; p++) M += slot_change(q, X, l, n, p) != 0;
+    uint32_t *list = (uint32_t *)malloc(sizeof(uint32_t) * (M ? M : 1));
+    M = 0;
+    for (int l = 0; l < L; l++) for (int n = 0; n < N; n++) for (int p = 0; p < P; p++)
+        if (slot_change(q, X, l, n, p)) list[M++] = (uint32_t)ix_x(q, l, n, p);
     uint64_t mpl = sp->total_moves / sp->n_levels; if (mpl < 1) mpl = 1;
     if (sp->move_begin == 0) {
         memset(st, 0, sizeof *st);
@@ -816,13 +838,14 @@ int orc_refine_slots(const orc_problem *q, const orc_sa_params *sp, uint32_t cha
                 uint64_t lvl = mi / mpl; if (lvl > sp->n_levels - 1) lvl = sp->n_levels - 1;
                 while (st->level < lvl) { st->C = st->C * sp->alpha; st->level++; }
             }
-            orc_move m; double u;
-            orc_draw_move(q, sp, chain, mi, phase == 0 ? 40 : 32, &m, &u);
-            int l = (int)m.layer, p = (int)m.page, n = (int)m.n1, ynew = (int)m.layer2;
+            uint32_t idx, ydraw; double u;
+            orc_draw_slot_move(sp->seed, chain, mi, phase == 0 ? 40 : 32, M, (uint32_t)L, &idx, &ydraw, &u);
+            if (M == 0) { if (phase == 1) st->null_moves++; continue; }
+            size_t iy = list[idx];
+            int p = (int)(iy % (size_t)P), n = (int)((iy / (size_t)P) % (size_t)N), l = (int)(iy / ((size_t)P * N));
+            int ynew = (int)ydraw, yold = Y[iy];
             int c = slot_change(q, X, l, n, p);
-            size_t iy = ix_x(q, l, n, p);
-            int yold = Y[iy];
-            if (!c || ynew == yold) { if (phase == 1) st->null_moves++; continue; }
+            if (ynew == yold) { if (phase == 1) st->null_moves++; continue; }
             int g_old = n * L + l - yold, g_new = n * L + l - ynew;
             /* the steps during which the page is in the pool only after the move */
             int lo = 0, hi = 0;
@@ -855,7 +878,7 @@ int orc_refine_slots(const orc_problem *q, const orc_sa_params *sp, uint32_t cha
             st->C = st->C0; st->level = 0;
         }
     }
-    free(t); free(pool); free(vol);
+    free(t); free(pool); free(vol); free(list);
     return 0;
 }
 

@@ -1110,6 +1110,49 @@ def test_draw_move_decoded_by_hand_from_the_published_block():
         2, blk[1] * 32 >> 32, blk[2] * 272 >> 32, blk[3] * 256 >> 32) == (2, 18, 85, 36)
 
 
+def test_draw_slot_move_decoded_by_hand_from_the_published_blocks():
+    # The proposal of the annealing over migration steps is one block.  Seed 0, chain 0, move 0, stream 0: counter 0
+    # under key 0, the first published vector 6627e8d5 e169c58d bc57ac4c 9b00dbd8.
+    #   word 0 / 2^32 = 0.399045: migrating page floor(0.399045 * 1000) = 399
+    #   word 1 / 2^32 = 0.880520: new Y floor(0.880520 * 32) = 28
+    #   u = ((bc57ac4c << 20 | 9b00dbd8 >> 12) + 1/2) 2^-52 = 0.7357...
+    idx, y, u = O.draw_slot_moves(0, 0, 1, seed=0, stream=0, M=1000, L=32)
+    assert (idx[0], y[0]) == (399, 28)
+    assert u[0] == ((0xbc57ac4c << 20 | 0x9b00dbd8 >> 12) + 0.5) * 2.0 ** -52 and 0.7357 < u[0] < 0.7358
+    idx, y, _ = O.draw_slot_moves(0, 0, 1, seed=0, stream=0, M=3, L=1)
+    assert (idx[0], y[0]) == (1, 0)                                      # floor(0.399 * 3) = 1; one layer: Y = 0
+    # the third published vector as (move, chain, stream) = counter and seed = key
+    ctr, key = [0x243f6a88, 0x85a308d3, 0x13198a2e, 0x03707344], [0xa4093822, 0x299f31d0]
+    blk = [0xd16cfe09, 0x94fdcceb, 0x5001e420, 0x24126ea1]
+    idx, y, u = O.draw_slot_moves(ctr[2], ctr[0] | ctr[1] << 32, 1, seed=key[0] | key[1] << 32, stream=ctr[3], M=77777, L=80)
+    # 0xd16cfe09 / 2^32 = 0.818069: floor(0.818069 * 77777) = floor(63626.98) = 63626; 0x94fdcceb / 2^32 = 0.581998: 46
+    assert (idx[0], y[0]) == (blk[0] * 77777 >> 32, blk[1] * 80 >> 32) == (63626, 46)
+    assert u[0] == ((blk[2] << 20 | blk[3] >> 12) + 0.5) * 2.0 ** -52
+    # consecutive proposals are consecutive counters: the index and Y are uniform, and not tied to each other
+    idx, y, u = O.draw_slot_moves(3, 0, 60000, seed=99, stream=32, M=10, L=4)
+    for v in range(10):
+        assert _within(int((idx == v).sum()), 60000, 0.1)
+    for v in range(4):
+        assert _within(int((y == v).sum()), 60000, 0.25)
+    assert _within(int(((idx == 3) & (y == 2)).sum()), 60000, 0.025) and _within(int((u < 0.3).sum()), 60000, 0.3)
+    first, _, _ = O.draw_slot_moves(3, 0, 5, seed=99, stream=40, M=10, L=4)
+    assert first.tolist() != idx[:5].tolist()                            # the calibration draws from a stream of its own
+
+
+def test_slot_refinement_proposes_migrating_pages_only():
+    # every proposal names a page that migrates, so the null moves are those whose drawn Y is the old one: about 1 in L
+    tr = W.random_trace(950, L=4, N=20, P=17, K=1, rebirth=True)
+    q = O.Problem(tr)
+    X = O.anneal_chain(q, 0, np.zeros(q.shape, np.uint8), seed=1, total_moves=1500, n_levels=10, max_len=7, per_slot=True).X
+    r = O.refine_slots(q, 0, X, np.zeros_like(X), seed=4, total_moves=8000, n_levels=10)
+    assert _within(r.null_moves - r.clipped, 8000 - r.clipped, 0.25, sigmas=6.0)
+    # only bytes of migrating pages are ever written, and in the order (layer, step, page) the first migrating page
+    # is the one that proposal index 0 names
+    mig = (X[:, 1:] != X[:, :-1]) & tr.persist[None, 1:].astype(bool) & (tr.alive[None, 1:].astype(bool) | tr.alive[None, :-1].astype(bool))
+    assert not (r.Y[:, 1:][~mig]).any() and not r.Y[:, 0].any()
+    assert r.Y.any()
+
+
 def test_draw_move_second_and_third_block_feed_span_victim_direction_and_u():
     tr = _mini(L=7, N=50, P=90)
     seed, chain, mi = 0x0123_4567_89AB_CDEF, 5, (3 << 32) | 17
