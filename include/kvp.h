@@ -218,12 +218,14 @@ int kvp_strict_excess(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, ui
  * KVP_ENOMEM, KVP_EHIP.
  *
  * kvp_refine_slots: annealing over Y for ONE fixed placement (the Metropolis rule, start temperature
- * and cooling of Sec. III-B; the move is this library's): params->n_chains chains, chain c drawing
- * proposal i from the Philox blocks (i, c, 32..34) under params->seed (40..42 for the 256 calibration
- * proposals): a page (l, p), a step n and a new Y, uniform.  Null unless the page migrates at n and Y
- * changes; dropped (counted as null and as clipped) if the page would be in the pool during a step that is
- * full; dT = the change of the old step's latency + that of the new step's.  Runs moves [0, params->moves)
- * of a cooling schedule of params->total_moves; max_len and op_prob are not used; init_mode
+ * and cooling of Sec. III-B; the move is this library's): params->n_chains chains.  The M pages that
+ * migrate are listed once in the order (layer, step, page).  Chain c draws proposal i from the Philox
+ * block (i lo, i hi, c, 32) under params->seed (stream 40 for the 256 calibration proposals): word 0
+ * picks the list entry (high word of word 0 x M), word 1 the new Y (high word of word 1 x L), words 2
+ * and 3 the 52 bits of the acceptance draw.  Null if Y stays (or nothing migrates); dropped (counted
+ * as null and as clipped) if the page would be in the pool during a step that is full; dT = the
+ * change of the old step's latency + that of the new step's.  Runs moves [0, params->moves) of a
+ * cooling schedule of params->total_moves; max_len and op_prob are not used; init_mode
  * KVP_INIT_EMPTY (every chain starts from Y = 0, written by the call) or KVP_INIT_GIVEN (from d_slots).
  *   d_placement  [L][N][Wd]      in, DEVICE, 16-byte aligned
  *   d_slots      [C][L][N][P]    in (GIVEN) / out, DEVICE: every chain's final Y

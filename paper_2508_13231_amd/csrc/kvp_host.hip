@@ -72,6 +72,7 @@ extern "C" void kvp_destroy(kvp_ctx *ctx) {
     free_dev(ctx->d_cnt_tmp); free_dev(ctx->d_occ_tmp); free_dev(ctx->d_tglobal); free_dev(ctx->d_chunkfull);
     free_dev(ctx->d_aw); free_dev(ctx->d_empty32); free_dev(ctx->d_policy_work); free_dev(ctx->d_policy_x);
     free_dev(ctx->d_tl); free_dev(ctx->d_sparse); free_dev(ctx->d_sel_keys); free_dev(ctx->d_slots_work);
+    free_dev(ctx->d_slots_cw); free_dev(ctx->d_slots_list);
     delete ctx;
 }
 

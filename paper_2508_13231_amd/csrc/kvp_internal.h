@@ -59,6 +59,8 @@ struct kvp_ctx {
     int capacity_mode = 0;               // KVP_CAPACITY_*: what the next fresh start of kvp_anneal walks under
     int chains_mode = 0;                 // what the present chains walk under
     unsigned char *d_slots_work = nullptr; size_t slots_work_cap = 0;   // migration steps: counters, moves per step, pool
+    uint32_t *d_slots_cw = nullptr; size_t slots_cw_cap = 0;            // migrating pages per schedule word, scanned
+    uint32_t *d_slots_list = nullptr; size_t slots_list_cap = 0;        // the migrating pages of a placement
     uint32_t *d_Xbest = nullptr;         // bounded log: [C][L][N][Wd], the best schedule of chains that have written it out
     uint64_t log_soft = 0;               // bounded log: entries after which a chain writes its best schedule out (0: not bounded)
     uint64_t log_entries = 0;            // kvp_set_anneal_log_entries: 0 = chosen from the sizes
@@ -272,6 +274,7 @@ int kvp_static_scratch_init(int device);     // kvp_score.hip: resolves the devi
 int kvp_bitslice_build(kvp_ctx *ctx);
 int kvp_slots_state_launch(kvp_ctx *ctx, const uint32_t *X, bool broadcast_x, const uint8_t *Y, uint32_t S, double *d_cost,
                            uint32_t *d_excess, uint32_t **cnt_out, uint32_t **mig_out, uint32_t **pool_out);
+int kvp_slot_list_build(kvp_ctx *ctx, const uint32_t *X, uint32_t **list_out, uint32_t *count_out);
 int kvp_blocksum_from_t_launch(kvp_ctx *ctx, uint32_t S, uint32_t nb_total);
 int kvp_slot_occupancy_launch(kvp_ctx *ctx, const uint32_t *d_placements, uint32_t S, uint32_t *d_excess, uint32_t *d_table);
 int kvp_rowlane_build(kvp_ctx *ctx);          // kvp_score_rowlane.hip: called at the end of kvp_bitslice_build

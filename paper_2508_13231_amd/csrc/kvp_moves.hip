@@ -1097,16 +1097,19 @@ extern "C" int kvp_anneal(kvp_ctx *ctx, const kvp_anneal_params *p, const uint32
 }
 
 // ---- annealing over the inference steps in which pages migrate (kvp_slots.hip has the scoring) ----
-// One wavefront per chain; the placement X is the same for all chains and does not change.  A proposal
-// names a page (l, p) at step n and a new Y: null unless the page migrates there and Y changes.  The
-// move takes the page out of |M^i| or |M^o| of the old step and into the new one's: two step latencies
-// change, dT = (t' - t) at the old step + (t' - t) at the new one.  A page that enters HBM earlier or
-// leaves it later is in the pool during the steps in between: the lanes look at those (at most L - 1)
-// and the proposal is dropped if one is full.  Control flow is the same for all lanes.
+// One wavefront per chain; the placement X is the same for all chains and does not change, so the pages
+// that migrate are known: `list` holds them, M entries (l*N + n)*P + p in ascending order.  A proposal is
+// one Philox block: an entry of the list, a new Y, the acceptance draw; a wavefront computes the blocks
+// of 64 consecutive proposals at once, one per lane.  Null if Y stays.  The move takes the page out of
+// |M^i| or |M^o| of the old step and into the new one's: two step latencies change, dT = (t' - t) at the
+// old step + (t' - t) at the new one.  A page that enters HBM earlier or leaves it later is in the pool
+// during the steps in between: the lanes look at those (at most L - 1) and the proposal is dropped if
+// one is full.  Control flow is the same for all lanes.
 namespace {
 
 __global__ __launch_bounds__(KVP_WAVE) void refine_slots_kernel(DevProblem q, SAParams sp, const uint32_t *__restrict__ X,
-                                                                const uint32_t *__restrict__ cnt, uint8_t *Yall,
+                                                                const uint32_t *__restrict__ cnt,
+                                                                const uint32_t *__restrict__ list, uint32_t M, uint8_t *Yall,
                                                                 uint32_t *mig_all, uint32_t *pool_all,
                                                                 ChainState *__restrict__ states, uint64_t move_begin,
                                                                 uint64_t move_end, int calibrate) {
@@ -1120,8 +1123,16 @@ __global__ __launch_bounds__(KVP_WAVE) void refine_slots_kernel(DevProblem q, SA
     const uint32_t stream = calibrate ? 40u : 32u;
     double sum = 0.0;
     uint32_t npos = 0;
-    DrawBatch B;
-    fill_draws(sp, chain, move_begin, stream, lane, B);
+    uint32_t o0 = 0, o1 = 0, o2 = 0, o3 = 0;      // the block of proposal `first + lane`
+    uint64_t first = move_begin;
+    auto refill = [&](uint64_t from) {
+        uint32_t out[4];
+        const uint64_t mine = from + (uint32_t)lane;
+        philox4x32_10((uint32_t)mine, (uint32_t)(mine >> 32), chain, stream, sp.seed_lo, sp.seed_hi, out);
+        o0 = out[0]; o1 = out[1]; o2 = out[2]; o3 = out[3];
+        first = from;
+    };
+    refill(move_begin);
     for (uint64_t mi = move_begin; mi < move_end; mi++) {
         if (!calibrate) {
             uint64_t lvl = mi / sp.mpl;
@@ -1129,19 +1140,18 @@ __global__ __launch_bounds__(KVP_WAVE) void refine_slots_kernel(DevProblem q, SA
             while (st.level < lvl) { st.c = st.c * sp.alpha; st.level++; }  // geometric cooling
             st.moves_done++;
         }
-        kvp_move m;
-        double u;
-        next_move(q, sp, chain, stream, lane, B, mi, m, u);
-        const uint32_t l = m.layer, p = m.page, n = m.n1, ynew = m.layer2, w = p >> 5, b = p & 31u;
-        int c = 0;
-        if (n > 0 && ((q.Pm[(size_t)n * Wd + w] >> b) & 1u)) {
-            const uint32_t x = ((X[((size_t)l * N + n) * Wd + w] & q.V[(size_t)n * Wd + w]) >> b) & 1u;
-            const uint32_t xp = ((X[((size_t)l * N + n - 1) * Wd + w] & q.V[(size_t)(n - 1) * Wd + w]) >> b) & 1u;
-            c = x == xp ? 0 : (x ? 1 : -1);
-        }
-        const size_t iy = ((size_t)l * N + n) * q.P + p;
+        if (mi - first >= KVP_WAVE) refill(mi);
+        const int at = (int)(uint32_t)(mi - first);
+        const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)o0, at), r1 = (uint32_t)__builtin_amdgcn_readlane((int)o1, at);
+        const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)o2, at), r3 = (uint32_t)__builtin_amdgcn_readlane((int)o3, at);
+        const double u = ((double)(((uint64_t)r2 << 20) | (r3 >> 12)) + 0.5) * (1.0 / 4503599627370496.0);
+        if (M == 0) { if (!calibrate) st.null_moves++; continue; }
+        const uint32_t entry = list[__umulhi(r0, M)], ynew = __umulhi(r1, L);
+        const uint32_t row = entry / q.P, p = entry - row * q.P, l = row / N, n = row - l * N, w = p >> 5, b = p & 31u;
+        const int c = ((X[((size_t)l * N + n) * Wd + w] & q.V[(size_t)n * Wd + w]) >> b) & 1u ? 1 : -1;   // comes in, or goes out
+        const size_t iy = entry;
         const uint32_t yold = Y[iy];
-        if (c == 0 || ynew == yold) { if (!calibrate) st.null_moves++; continue; }
+        if (ynew == yold) { if (!calibrate) st.null_moves++; continue; }
         const uint32_t g_own = n * L + l, g_old = g_own - yold, g_new = g_own - ynew;
         // the steps during which the page is in the pool only after the move
         uint32_t lo = 0, hi = 0;
@@ -1221,8 +1231,9 @@ extern "C" int kvp_refine_slots(kvp_ctx *ctx, const kvp_anneal_params *p, const 
         cleanup();
         return KVP_ENOMEM;
     }
-    uint32_t *cnt = nullptr, *mig = nullptr, *pool = nullptr;
+    uint32_t *cnt = nullptr, *mig = nullptr, *pool = nullptr, *list = nullptr, M = 0;
     int rc = kvp_slots_state_launch(ctx, d_placement, true, d_slots, C, d_cost, d_excess, &cnt, &mig, &pool);
+    if (!rc) rc = kvp_slot_list_build(ctx, d_placement, &list, &M);
     if (rc) { cleanup(); return rc; }
     std::vector<uint32_t> hex(C);
     hipError_t e = hipMemcpyAsync(hex.data(), d_excess, 4 * (size_t)C, hipMemcpyDeviceToHost, ctx->stream);
@@ -1237,12 +1248,12 @@ extern "C" int kvp_refine_slots(kvp_ctx *ctx, const kvp_anneal_params *p, const 
     sp.mpl = p->total_moves / p->n_levels; if (sp.mpl < 1) sp.mpl = 1;
     sp.n_levels = p->n_levels; sp.max_len = 1;
     sp.alpha = p->alpha; sp.neg_ln_p0 = -log(p->p0);
-    refine_slots_kernel<<<dim3(C), dim3(KVP_WAVE), 0, ctx->stream>>>(q, sp, d_placement, cnt, d_slots, mig, pool, d_state, 0,
-                                                                     CALIB_MOVES, 1);
+    refine_slots_kernel<<<dim3(C), dim3(KVP_WAVE), 0, ctx->stream>>>(q, sp, d_placement, cnt, list, M, d_slots, mig, pool, d_state,
+                                                                     0, CALIB_MOVES, 1);
     for (uint64_t m0 = 0; m0 < p->moves; m0 += 16384) {                // bounded launches: every wavefront exits after a fixed count
         const uint64_t m1 = m0 + 16384 < p->moves ? m0 + 16384 : p->moves;
-        refine_slots_kernel<<<dim3(C), dim3(KVP_WAVE), 0, ctx->stream>>>(q, sp, d_placement, cnt, d_slots, mig, pool, d_state, m0,
-                                                                         m1, 0);
+        refine_slots_kernel<<<dim3(C), dim3(KVP_WAVE), 0, ctx->stream>>>(q, sp, d_placement, cnt, list, M, d_slots, mig, pool,
+                                                                         d_state, m0, m1, 0);
     }
     e = hipGetLastError();
     std::vector<ChainState> hs(C);

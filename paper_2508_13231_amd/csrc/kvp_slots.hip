@@ -14,7 +14,8 @@
 //            64-wide summation tree as everywhere (block sums, then added in order);
 //   pool     a prefix sum over the steps gives the pool after every step (Eq. 5) and its largest
 //            overshoot.
-// The same arrays are the state of the chains that anneal Y (kvp_refine_slots in kvp_moves.hip).
+// The same arrays are the state of the chains that anneal Y (kvp_refine_slots in kvp_moves.hip), which
+// draw their proposals from a list of the migrating pages that is also made here.
 // gfx950 only.
 #include "kvp_internal.h"
 #include "kvp_select.h"
@@ -131,9 +132,113 @@ __global__ __launch_bounds__(256) void slot_cost_kernel(uint32_t S, uint32_t nb_
     if (lane == 0) cost[s] = T;
 }
 
+// ---- the migrating pages of one placement, listed in the order (layer, step, page) ----
+// count: migrating pages per schedule word; an exclusive prefix sum over the words (blocks of 1024, the block
+// totals by one workgroup, then added back); fill: every word writes its pages at its offset.
+__device__ __forceinline__ uint32_t migrating_bits(const DevProblem &q, const uint32_t *X, uint32_t l, uint32_t n, uint32_t w) {
+    if (n == 0) return 0;
+    const uint32_t x = X[((size_t)l * q.N + n) * q.Wd + w] & q.V[(size_t)n * q.Wd + w];
+    const uint32_t xp = X[((size_t)l * q.N + n - 1) * q.Wd + w] & q.V[(size_t)(n - 1) * q.Wd + w];
+    return (x ^ xp) & q.Pm[(size_t)n * q.Wd + w];
+}
+
+__global__ __launch_bounds__(256) void slot_list_count_kernel(DevProblem q, RowDiv rd, const uint32_t *__restrict__ X,
+                                                              uint32_t *__restrict__ cw) {
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x, l = blockIdx.y;
+    if (i >= q.N * q.Wd) return;
+    const uint32_t n = rd.quot(i), w = i - n * q.Wd;
+    cw[(size_t)l * q.N * q.Wd + i] = __popc(migrating_bits(q, X, l, n, w));
+}
+
+// in place: v[i] becomes the sum of the elements before it inside its block of 1024; the block's total goes to bsum
+__global__ __launch_bounds__(256) void scan_blocks_kernel(uint32_t *__restrict__ v, uint64_t count, uint32_t *__restrict__ bsum) {
+    __shared__ uint32_t part[256];
+    const uint64_t base = (uint64_t)blockIdx.x * 1024 + (uint64_t)threadIdx.x * 4;
+    uint32_t a[4], sum = 0;
+#pragma unroll
+    for (int j = 0; j < 4; j++) { a[j] = base + j < count ? v[base + j] : 0u; sum += a[j]; }
+    part[threadIdx.x] = sum;
+    __syncthreads();
+    for (uint32_t o = 1; o < 256; o <<= 1) {
+        const uint32_t add = threadIdx.x >= o ? part[threadIdx.x - o] : 0;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    uint32_t run = part[threadIdx.x] - sum;
+#pragma unroll
+    for (int j = 0; j < 4; j++) { if (base + j < count) v[base + j] = run; run += a[j]; }
+    if (threadIdx.x == 255) bsum[blockIdx.x] = part[255];
+}
+// one workgroup: bsum[b] becomes the sum of the totals before block b; total[0] the sum of all
+__global__ __launch_bounds__(256) void scan_totals_kernel(uint32_t *__restrict__ bsum, uint32_t nblocks, uint32_t *__restrict__ total) {
+    __shared__ uint32_t part[256];
+    __shared__ uint32_t carry;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (uint32_t b0 = 0; b0 < nblocks; b0 += 256) {
+        const uint32_t b = b0 + threadIdx.x, mine = b < nblocks ? bsum[b] : 0u;
+        part[threadIdx.x] = mine;
+        __syncthreads();
+        for (uint32_t o = 1; o < 256; o <<= 1) {
+            const uint32_t add = threadIdx.x >= o ? part[threadIdx.x - o] : 0;
+            __syncthreads();
+            part[threadIdx.x] += add;
+            __syncthreads();
+        }
+        if (b < nblocks) bsum[b] = carry + part[threadIdx.x] - mine;
+        __syncthreads();
+        if (threadIdx.x == 255) carry += part[255];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) total[0] = carry;
+}
+
+__global__ __launch_bounds__(256) void slot_list_fill_kernel(DevProblem q, RowDiv rd, const uint32_t *__restrict__ X,
+                                                             const uint32_t *__restrict__ cw, const uint32_t *__restrict__ bsum,
+                                                             uint32_t *__restrict__ list) {
+    const uint32_t i = blockIdx.x * 256 + threadIdx.x, l = blockIdx.y;
+    if (i >= q.N * q.Wd) return;
+    const uint32_t n = rd.quot(i), w = i - n * q.Wd;
+    const uint64_t word = (uint64_t)l * q.N * q.Wd + i;
+    uint32_t at = cw[word] + bsum[word >> 10];
+    for (uint32_t m = migrating_bits(q, X, l, n, w); m; m &= m - 1)
+        list[at++] = (l * q.N + n) * q.P + w * 32 + (uint32_t)(__ffs(m) - 1);
+}
+
 size_t up64(size_t v) { return (v + 63) & ~(size_t)63; }
 
 }  // namespace
+
+// The pages of the placement X (one schedule) that migrate, as entries (l*N + n)*P + p in ascending order: *list_out
+// (device memory of the context, valid until the next call) and their number.  Arguments checked by the caller.
+int kvp_slot_list_build(kvp_ctx *ctx, const uint32_t *X, uint32_t **list_out, uint32_t *count_out) {
+    const DevProblem &q = ctx->dp;
+    const uint64_t row_words = (uint64_t)q.N * q.Wd, words = row_words * q.L;
+    if (row_words >= (1ull << 31) || q.L > 65535u || (uint64_t)q.L * q.N * q.P >= (1ull << 32)) return KVP_ESHAPE;
+    const uint64_t nblocks = (words + 1023) / 1024;
+    if (nblocks >= (1ull << 31)) return KVP_ESHAPE;
+    int rc = kvp_ensure(ctx, (void **)&ctx->d_slots_cw, &ctx->slots_cw_cap, (size_t)(words + nblocks + 4) * 4);
+    if (rc) return rc;
+    uint32_t *cw = ctx->d_slots_cw, *bsum = cw + words, *total = bsum + nblocks;
+    const RowDiv rd(q.Wd, row_words);
+    const dim3 grid((uint32_t)((row_words + 255) / 256), q.L);
+    slot_list_count_kernel<<<grid, dim3(256), 0, ctx->stream>>>(q, rd, X, cw);
+    KVP_HIP(hipGetLastError());
+    scan_blocks_kernel<<<dim3((uint32_t)nblocks), dim3(256), 0, ctx->stream>>>(cw, words, bsum);
+    KVP_HIP(hipGetLastError());
+    scan_totals_kernel<<<dim3(1), dim3(256), 0, ctx->stream>>>(bsum, (uint32_t)nblocks, total);
+    KVP_HIP(hipGetLastError());
+    uint32_t M = 0;
+    KVP_HIP(hipMemcpyAsync(&M, total, 4, hipMemcpyDeviceToHost, ctx->stream));
+    KVP_HIP(hipStreamSynchronize(ctx->stream));
+    if ((rc = kvp_ensure(ctx, (void **)&ctx->d_slots_list, &ctx->slots_list_cap, ((size_t)M + 1) * 4))) return rc;
+    slot_list_fill_kernel<<<grid, dim3(256), 0, ctx->stream>>>(q, rd, X, cw, bsum, ctx->d_slots_list);
+    KVP_HIP(hipGetLastError());
+    *list_out = ctx->d_slots_list;
+    *count_out = M;
+    return KVP_OK;
+}
 
 // The state of S schedules (X[s], or the one X for all if broadcast_x; Y[s]): cost and excess as
 // kvp_score_slots returns them, and the arrays they were made from, which stay valid in the context's

@@ -29,6 +29,7 @@ def _cases():
     yield "rand-tiles", named["rand-tiles"]                              # pages born, dying, re-used
     yield "rand-L16", named["rand-L16"]
     yield "rand-L70", W.random_trace(41, L=70, N=24, P=50, K=2)          # more layers than lanes: ranges of up to 69 steps
+    yield "rand-wide", W.random_trace(43, L=4, N=300, P=8000, K=1)       # 300 000 schedule words: the list of migrating pages is scanned in 293 blocks
 
 
 CASES = list(_cases())
@@ -76,7 +77,7 @@ def _walk_start(q, tr, seed):
     return O.anneal_chain(q, 0, X0, seed=seed, total_moves=2500, n_levels=10, max_len=15, per_slot=True).X
 
 
-@pytest.mark.parametrize("name,tr", [c for c in CASES if c[0] in ("table1", "llama8b/8", "gqa70b/16", "serving/16", "rand-tiles", "rand-L70")],
+@pytest.mark.parametrize("name,tr", [c for c in CASES if c[0] in ("table1", "llama8b/8", "gqa70b/16", "serving/16", "rand-tiles", "rand-L70", "rand-wide")],
                          ids=lambda v: v if isinstance(v, str) else "")
 def test_refine_slots_walks_like_the_oracle(G, name, tr):
     import torch
@@ -86,7 +87,14 @@ def test_refine_slots_walks_like_the_oracle(G, name, tr):
     if name == "rand-L70":
         tr = dataclasses.replace(tr, cap_pages=200)                   # a pool that fills: moves get blocked
     q = O.Problem(tr)
-    X = _walk_start(q, tr, 3)
+    if name == "rand-wide":
+        # where a walk that counts the pool per token step ends (the oracle's per-slot walk takes minutes here),
+        # and a pool just large enough for it at every inference step
+        X = O.anneal_chain(q, 0, O.init_static_frequency(q), seed=3, total_moves=2500, n_levels=10).X
+        tr = dataclasses.replace(tr, cap_pages=int(O.score_slots(q, X, np.zeros_like(X)).pool.max()))
+        q = O.Problem(tr)
+    else:
+        X = _walk_start(q, tr, 3)
     chains, total = 3, 4000
     want = [O.refine_slots(q, c, X, np.zeros_like(X), seed=77, total_moves=total, n_levels=10) for c in range(chains)]
     assert sum(r.accepted for r in want) > 10, "nothing migrates in this start: nothing tested"
