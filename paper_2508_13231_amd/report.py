@@ -106,7 +106,7 @@ class Session:
                                  c_min_frac=0.0, d_best_placement=d)
         T, hit, ex = self.measure(d)
         assert ex == 0 and T == res.best_T
-        out = {"T": T, "hit": hit, "W": res.best_w, "R": res.best_r10 / 10}
+        out = {"T": T, "hit": hit, "W": res.best_w, "R": res.best_r10 / 10, "placement": d}
         if refine_moves:
             p = K.make_anneal_params(chains, refine_moves, seed=7, init_mode=K.KVP_INIT_BROADCAST, p0=p0)
             K.kvp_anneal(self.ctx, p, d)
@@ -117,6 +117,31 @@ class Session:
                 assert ex2 == 0 and T2 == cost
                 out.update(T=T2, hit=hit2, refined=True)
         return out
+
+
+def migrations_moved(tr, d_x, chains=16, proposals=400000):
+    """The schedule d_x with its migrations moved into other layers' inference steps (kvp_refine_slots).  The
+    capacity is counted after every inference step there, so it is first raised by what the schedule's pool
+    exceeds it between two layers.  Returns (T, pages added to the capacity, seconds)."""
+    import dataclasses
+    import torch
+    dev = d_x.device
+    with Session(tr) as s:
+        y0 = torch.zeros((1, tr.L, tr.N, tr.P), dtype=torch.uint8, device=dev)
+        c, e = torch.empty(1, dtype=torch.float64, device=dev), torch.empty(1, dtype=torch.int32, device=dev)
+        K.kvp_score_slots(s.ctx, d_x, y0, 1, c, e)
+        torch.cuda.synchronize()
+        over = int(e.item()) & 0x3FFFFFFF
+    with Session(dataclasses.replace(tr, cap_pages=tr.cap_pages + over)) as s:
+        t0 = time.perf_counter()
+        d_y = torch.empty((chains, tr.L, tr.N, tr.P), dtype=torch.uint8, device=dev)
+        p = K.make_anneal_params(chains, proposals, seed=2, init_mode=K.KVP_INIT_EMPTY)
+        K.kvp_refine_slots(s.ctx, p, d_x, d_y)
+        c, e = torch.empty(chains, dtype=torch.float64, device=dev), torch.empty(chains, dtype=torch.int32, device=dev)
+        K.kvp_score_slots(s.ctx, d_x.unsqueeze(0).expand(chains, -1, -1, -1).contiguous(), d_y, chains, c, e)
+        torch.cuda.synchronize()
+        assert int(e.max().item()) == 0
+        return float(c.min().item()), over, time.perf_counter() - t0
 
 
 def evaluate(tok, w_max, refine_moves, chains):
@@ -150,11 +175,15 @@ def config_row(name, w_max):
         r = s.policy_search(w_max)
         t1 = time.perf_counter()
         out[f"(W,R) policy, W={r['W']} R={r['R']:.1f} ({t1 - t0:.2f} s)"] = (r["T"], r["hit"])
+        policy_x = r["placement"].clone()
         r2 = s.policy_search(w_max, refine_moves=tr.moves, chains=tr.chains)
         out[f"direct search from it, {tr.chains} chains x {tr.moves} moves, p0 = 0.005 ({time.perf_counter() - t1:.2f} s)"] = (r2["T"], r2["hit"])
         t2 = time.perf_counter()
         r3 = s.policy_search(w_max, refine_moves=tr.moves, chains=tr.chains, p0=0.8)
         out[f"the same with the paper's p0 = 0.8 ({time.perf_counter() - t2:.2f} s)"] = (r3["T"], r3["hit"])
+    Tm, over, secs = migrations_moved(tr, policy_x)
+    out[f"the policy's schedule, its migrations moved into other layers' steps (HBM for {over} pages more, the pool "
+        f"counted after every inference step; 16 chains x 400000 proposals, {secs:.2f} s)"] = (Tm, r["hit"])
     print(f"{name}: L={tr.L} N={tr.N} P={tr.P} K={tr.K}, HBM for {tr.cap_pages} pages\n")
     print("| strategy | total decode latency T (s) | HBM hit rate |")
     print("|---|---|---|")
