@@ -70,7 +70,7 @@ extern "C" void kvp_destroy(kvp_ctx *ctx) {
     kvp_free_chains(ctx);
     free_dev(ctx->d_trace); free_dev(ctx->d_blocksum); free_dev(ctx->d_tileflag);
     free_dev(ctx->d_cnt_tmp); free_dev(ctx->d_occ_tmp); free_dev(ctx->d_tglobal); free_dev(ctx->d_chunkfull);
-    free_dev(ctx->d_aw); free_dev(ctx->d_empty32); free_dev(ctx->d_policy_work); free_dev(ctx->d_policy_x);
+    free_dev(ctx->d_aw); free_dev(ctx->d_policy_work); free_dev(ctx->d_policy_x);
     free_dev(ctx->d_tl); free_dev(ctx->d_sparse); free_dev(ctx->d_sel_keys); free_dev(ctx->d_slots_work);
     free_dev(ctx->d_slots_cw); free_dev(ctx->d_slots_list);
     delete ctx;
@@ -187,7 +187,6 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
     free_dev(ctx->d_aw); ctx->d_aw = nullptr; ctx->aw = nullptr; ctx->kb = 0;
     free_dev(ctx->d_tl); ctx->d_tl = nullptr; ctx->kd = 0;
     free_dev(ctx->d_sparse); ctx->d_sparse = nullptr;
-    free_dev(ctx->d_empty32); ctx->d_empty32 = nullptr;
 
     const size_t nA = (size_t)(L * N * K * Wd), nM = (size_t)(N * Wd);
     auto up4 = [](size_t x) { return (x + 3) & ~(size_t)3; };          // keep every array 16-byte aligned
@@ -221,9 +220,7 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
         uint8_t *fullw = (uint8_t *)malloc((size_t)Wd);
         const uint64_t NCH = (Wd + 15) / 16, CFW = (NCH + 31) / 32;
         uint32_t *cfull = (uint32_t *)calloc((size_t)(T64 * CFW ? T64 * CFW : 1), 4);
-        const uint64_t NC32 = (Wd + 31) / 32;
-        uint8_t *emp = (uint8_t *)calloc((size_t)(T64 * NC32 ? T64 * NC32 : 1), 1);
-        if (!cls || !tpe || !fullw || !cfull || !emp) { free(cls); free(tpe); free(fullw); free(cfull); free(emp); return KVP_ENOMEM; }
+        if (!cls || !tpe || !fullw || !cfull) { free(cls); free(tpe); free(fullw); free(cfull); return KVP_ENOMEM; }
         uint32_t *m16 = cls + T64, *m64 = cls + 2 * T64, *m256 = cls + 3 * T64;
         ctx->prefix_full = Wd >= 2 && Wd <= 16;
         ctx->pfw = (uint32_t)Wd;
@@ -240,7 +237,6 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
                     if (n >= n0 && n >= 1 && h_persist[n * Wd + w] != 0xFFFFFFFFu) full = false;
                 }
                 fullw[w] = full;
-                if (!empty) emp[t * NC32 + w / 32] = 1;              // for now: 1 = some page exists
                 if (Wd <= 16)
                     cls[t] |= (uint32_t)(full ? KVP_WORD_FULL : empty ? KVP_WORD_EMPTY : KVP_WORD_MIXED) << (2 * w);
                 if (w + 1 < Wd && !full) ctx->prefix_full = false;
@@ -265,18 +261,14 @@ extern "C" int kvp_trace_upload(kvp_ctx *ctx, const kvp_problem *pr, const uint3
                     if (all) M[k][t] |= 1u << i;
                 }
         }
-        for (size_t i = 0; i < T64 * NC32; i++) emp[i] = !emp[i];
         hipError_t ec = hipMemcpyAsync(d + oCls, cls, 4 * T64 * 4, hipMemcpyHostToDevice, ctx->stream);
         if (ec == hipSuccess) ec = hipMemcpyAsync(d + oTile, tpe, 2 * T64 * 4, hipMemcpyHostToDevice, ctx->stream);
-        if (ec == hipSuccess) ec = hipMalloc((void **)&ctx->d_empty32, (size_t)(T64 * NC32 ? T64 * NC32 : 1));
-        if (ec == hipSuccess)
-            ec = hipMemcpyAsync(ctx->d_empty32, emp, (size_t)(T64 * NC32), hipMemcpyHostToDevice, ctx->stream);
         if (ec == hipSuccess) ec = hipMalloc((void **)&ctx->d_chunkfull, (size_t)T64 * CFW * 4);
         if (ec == hipSuccess)
             ec = hipMemcpyAsync(ctx->d_chunkfull, cfull, (size_t)T64 * CFW * 4, hipMemcpyHostToDevice, ctx->stream);
         if (ec == hipSuccess) ec = hipStreamSynchronize(ctx->stream);
         ctx->cf_words = (uint32_t)CFW;
-        free(cls); free(tpe); free(fullw); free(cfull); free(emp);
+        free(cls); free(tpe); free(fullw); free(cfull);
         KVP_HIP(ec);
     }
     int rc = kvp_trace_totals_launch(ctx, d + oAcc, d + oWr, d + oSel);

@@ -87,7 +87,6 @@ struct kvp_ctx {
     uint32_t *d_tileflag = nullptr; size_t tileflag_cap = 0;  // [S][tiles]
     double *d_tglobal = nullptr; size_t tglobal_cap = 0;      // [S][L][N] step latencies (wide rows)
     uint32_t *d_chunkfull = nullptr; uint32_t cf_words = 0;   // [tiles][cf_words] bit c: chunk c of 16 words is FULL
-    uint8_t *d_empty32 = nullptr;        // [tiles][ceil(Wd/32)] 1: no page of words [32c, 32c+32) exists on the tile
     uint32_t *d_policy_work = nullptr; size_t policy_work_cap = 0;   // (W,R) policy: window counts, pool, wanted per candidate
     uint32_t *d_policy_x = nullptr; size_t policy_x_cap = 0;         // (W,R) search: schedules of a batch and their costs
     uint32_t *d_sel_keys = nullptr; size_t sel_keys_cap = 0;  // recency placement: 16-bit keys of a batch of steps

@@ -11,12 +11,17 @@
 //     persist, written) are the same for the four schedules: fetched once per
 //     workgroup, one chunk ahead, into a double-buffered LDS slot laid out in the
 //     order the lanes read it (16 bytes per lane, consecutive lanes consecutive).
-//     Chunks none of whose pages exists on the tile are only checked for stray bits.
+//   * The loop over the chunks has no branch around a load or around the counting: every
+//     row vector is requested again, into the same registers, right after its last use.
+//     (A branch that skips the counting for chunks without pages made the compiler keep
+//     two sets of row registers and copy one to the other at the end of each iteration,
+//     which waits for every load in flight: slower than counting zeros.)
 //   * At the end of a row the eight lanes of a group add their counters and lane
 //     (g, p) keeps step 8g + p: Eqs. 2-4 and the summation tree then run once per
 //     layer with one step per lane, as in the other lane-per-step scorers.
 //   * The last chunk of a row is shifted left to end at the row's end; the words
-//     it shares with the chunk before are zeroed after the load.
+//     it shares with the chunk before count nothing: their trace words are zeroed on
+//     the way to LDS, and a lane mask keeps them out of the test for stray bits.
 #include "kvp_internal.h"
 
 namespace {
@@ -46,7 +51,7 @@ __device__ __forceinline__ int clamp_i32(int v, int lo, int hi) { return min(max
 template <int KB, bool POW2>
 __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     DevProblem q, const uint32_t *__restrict__ Aw, const uint32_t *__restrict__ X, uint32_t S, uint32_t tiles,
-    uint32_t nb_total, uint32_t log2L, const uint8_t *__restrict__ chunkempty,
+    uint32_t nb_total, uint32_t log2L,
     double *__restrict__ blocksum, double *__restrict__ tglobal, uint32_t *__restrict__ tileflag,
     uint32_t *__restrict__ counters, uint32_t *__restrict__ occ_out) {
     extern __shared__ double smem_d[];
@@ -112,12 +117,16 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
         tr[2 * KB + 2] = *(const l4u *)(Pb + tb0); tr[2 * KB + 3] = *(const l4u *)(Pb + tb1);
         tr[2 * KB + 4] = *(const l4u *)(Wb + tb0); tr[2 * KB + 5] = *(const l4u *)(Wb + tb1);
     };
-    auto commit_t = [&](uint32_t it) __attribute__((always_inline)) {
+    // `shared`: leading words of the chunk that the chunk before has counted already (the last chunk of a row
+    // whose width is no multiple of 32): their trace words go to the slot as zeros, so nothing is counted twice
+    auto commit_t = [&](uint32_t it, uint32_t shared) __attribute__((always_inline)) {
         uint32_t *slot = tbuf + (it & 1u) * NT * PLANE;
+        const uint32_t b = 4 * tpart;
+        const a4u keep = {b + 0 < shared ? 0u : ~0u, b + 1 < shared ? 0u : ~0u, b + 2 < shared ? 0u : ~0u, b + 3 < shared ? 0u : ~0u};
 #pragma unroll
         for (int a = 0; a < NT; a++) {
-            *(a4u *)(slot + a * PLANE + tl0) = (a4u)tr[2 * a];
-            *(a4u *)(slot + a * PLANE + tl1) = (a4u)tr[2 * a + 1];
+            *(a4u *)(slot + a * PLANE + tl0) = (a4u)tr[2 * a] & keep;
+            *(a4u *)(slot + a * PLANE + tl1) = (a4u)tr[2 * a + 1] & keep;
         }
     };
 
@@ -136,7 +145,7 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
         for (int j = 0; j < 9; j++) issue_x(j, b0, (int)N - 1);
         advance(ix, cx);
     }
-    commit_t(0);
+    commit_t(0, 0);
     for (uint32_t i = 0; i < L; i++) {
         const uint32_t l = layer_of(i);
         const uint32_t acc_n = q.acc[(size_t)l * N + n];               // used when the row ends
@@ -151,15 +160,11 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
         for (uint32_t c = 0; c < NCH; c++, it++) {
             const uint32_t w0 = min(c * LCW, Wd - LCW);
             const uint32_t skip = c * LCW - w0;                       // leading words already counted (last chunk only)
-            const bool empty = skip == 0 && chunkempty[(size_t)tile * NCH + c] != 0;
-            if (skip) {
-                const uint32_t b = 4 * p;
-#pragma unroll
-                for (int j = 0; j < 9; j++) {
-                    x[j].x = b + 0 < skip ? 0u : x[j].x; x[j].y = b + 1 < skip ? 0u : x[j].y;
-                    x[j].z = b + 2 < skip ? 0u : x[j].z; x[j].w = b + 3 < skip ? 0u : x[j].w;
-                }
-            }
+            // The row words themselves are never changed under a condition (every one of them would then be waited
+            // for at the top of the iteration): the shared words count nothing because their trace words are zero,
+            // and `kp` keeps them out of the test for stray bits.
+            const a4u kp = {4 * p + 0 < skip ? 0u : ~0u, 4 * p + 1 < skip ? 0u : ~0u, 4 * p + 2 < skip ? 0u : ~0u,
+                            4 * p + 3 < skip ? 0u : ~0u};
             const uint32_t nbase = x_base(ix, cx);
             advance(ix, cx);
             int last_step = (int)N - 1;
@@ -169,48 +174,40 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
             // issue, and waiting for the trace words at the end of an iteration would also wait for the rows
             // requested last, a memory round trip per chunk.  (Nobody reads the slot before the barrier below,
             // and its last readers have passed the barrier of the iteration before.)
-            if (it > 0) commit_t(it);
+            if (it > 0) commit_t(it, skip);
             issue_t(it_, ct); advance(it_, ct);                        // trace words of the next iteration
             __syncthreads();                                           // this iteration's trace slot is complete
             const uint32_t *slot = tbuf + (it & 1u) * NT * PLANE + 4 * (uint32_t)lane;
-            if (empty) {
-                // no page of these 32 words exists on any step of the tile: any bit is a bit too many
+            // The trace vectors of step j+1 are requested from LDS before step j is scored, and
+            // the scheduler is kept from hoisting them any further: otherwise all eight steps'
+            // vectors would be live at once.
+            a4u tv[2][NT];
+            auto fetch = [&](int j, a4u *dst) __attribute__((always_inline)) {
+                const uint32_t *sj = slot + j * 256;               // [row % 8 = j][lane][4]
 #pragma unroll
-                for (int j = 1; j < 9; j++) fl_acc |= x[j].x | x[j].y | x[j].z | x[j].w;
+                for (int a = 0; a < NT; a++) dst[a] = *(const a4u *)(sj + a * PLANE);
+            };
+            fetch(0, tv[0]);
 #pragma unroll
-                for (int j = 0; j < 9; j++) issue_x(j, nbase, last_step);
-            } else {
-                // The trace vectors of step j+1 are requested from LDS before step j is scored, and
-                // the scheduler is kept from hoisting them any further: otherwise all eight steps'
-                // vectors would be live at once.
-                a4u tv[2][NT];
-                auto fetch = [&](int j, a4u *dst) __attribute__((always_inline)) {
-                    const uint32_t *sj = slot + j * 256;               // [row % 8 = j][lane][4]
+            for (int j = 0; j < 8; j++) {
+                if (j < 7) fetch(j + 1, tv[(j + 1) & 1]);
+                const a4u *cv = tv[j & 1];
 #pragma unroll
-                    for (int a = 0; a < NT; a++) dst[a] = *(const a4u *)(sj + a * PLANE);
-                };
-                fetch(0, tv[0]);
+                for (int e = 0; e < 4; e++) {
+                    const uint32_t raw = x[j + 1][e], xp = x[j][e];
+                    const uint32_t xx = raw & cv[KB][e];           // alive
+                    fl_acc |= raw & ~cv[KB][e] & kp[e];
+                    const uint32_t d = (xx ^ xp) & cv[KB + 1][e];  // persist
 #pragma unroll
-                for (int j = 0; j < 8; j++) {
-                    if (j < 7) fetch(j + 1, tv[(j + 1) & 1]);
-                    const a4u *cv = tv[j & 1];
-#pragma unroll
-                    for (int e = 0; e < 4; e++) {
-                        const uint32_t raw = x[j + 1][e], xp = x[j][e];
-                        const uint32_t xx = raw & cv[KB][e];           // alive
-                        fl_acc |= raw & ~cv[KB][e];
-                        const uint32_t d = (xx ^ xp) & cv[KB + 1][e];  // persist
-#pragma unroll
-                        for (int k = 0; k < KB; k++) count(chr[j][k], xx & cv[k][e]);
-                        count(chw[j], xx & cv[KB + 2][e]);             // written
-                        count(coc[j], xx);
-                        count(cmi[j], d & xx);
-                        count(cmg[j], d);
-                    }
-                    issue_x(j, nbase, last_step);                      // its last use was as the step before
-                    if (j == 7) issue_x(8, nbase, last_step);
-                    __builtin_amdgcn_sched_barrier(0);
+                    for (int k = 0; k < KB; k++) count(chr[j][k], xx & cv[k][e]);
+                    count(chw[j], xx & cv[KB + 2][e]);             // written
+                    count(coc[j], xx);
+                    count(cmi[j], d & xx);
+                    count(cmg[j], d);
                 }
+                issue_x(j, nbase, last_step);                      // its last use was as the step before
+                if (j == 7) issue_x(8, nbase, last_step);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         // the rows are complete: the group's lanes add up, lane (g, p) keeps step 8g + p
@@ -274,7 +271,7 @@ int kvp_blocksum_from_t_launch(kvp_ctx *ctx, uint32_t S, uint32_t nb_total);
 int kvp_score_line_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
                           uint32_t *counters, uint32_t *occ) {
     const DevProblem &q = ctx->dp;
-    if (!ctx->aw || !ctx->d_empty32 || q.Wd < LCW) return 1;
+    if (!ctx->aw || q.Wd < LCW) return 1;
     const uint32_t KB = ctx->kb;
     if (KB > 4) return 1;                                             // registers: five counters per step and digit
     if ((size_t)q.L * q.N * q.Wd * KB >= (1ull << 30)) return 1;      // 32-bit byte offsets inside a schedule and the planes
@@ -295,7 +292,7 @@ int kvp_score_line_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t 
         KVP_HIP(hipFuncSetAttribute((const void *)score_line_kernel<KK, PP>,                                   \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                   \
         score_line_kernel<KK, PP><<<grid, block, lds, ctx->stream>>>(                                          \
-            q, ctx->aw, X, S, tiles, nb_total, log2L, ctx->d_empty32, ctx->d_blocksum,                          \
+            q, ctx->aw, X, S, tiles, nb_total, log2L, ctx->d_blocksum,                                          \
             ctx->d_tglobal, ctx->d_tileflag, counters, occ);                                                   \
     } while (0)
 #define KVP_K(KK) case KK: if (pow2) KVP_GO(KK, true); else KVP_GO(KK, false); break;
