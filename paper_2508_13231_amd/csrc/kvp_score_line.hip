@@ -1,14 +1,14 @@
 // Scorer for wide rows (n_words >= 32): the schedule rows never touch LDS.
 //
-//   * A workgroup is four wavefronts scoring the same 64 token steps of four
-//     schedules.  A row is walked in chunks of 32 words = one 128-byte line when
+//   * A workgroup is four or eight wavefronts scoring the same 64 token steps of as
+//     many schedules.  A row is walked in chunks of 32 words = one 128-byte line when
 //     rows are line-aligned.  Lane (g, p), g = lane / 8, p = lane % 8, takes the
 //     16-byte part p of the chunk for the steps 8g .. 8g+7 and for step 8g-1: nine
 //     loads per lane and chunk, each wavefront instruction covering whole lines.
 //     A lane scores its parts straight from registers, the row above being the
 //     previous register, and keeps five counters per step until the row ends.
 //   * The trace words of a chunk (binary digit planes of the read weights, alive,
-//     persist, written) are the same for the four schedules: fetched once per
+//     persist, written) are the same for those schedules: fetched once per
 //     workgroup, one chunk ahead, into a double-buffered LDS slot laid out in the
 //     order the lanes read it (16 bytes per lane, consecutive lanes consecutive).
 //   * The loop over the chunks has no branch around a load or around the counting: every
@@ -20,8 +20,8 @@
 //     (g, p) keeps step 8g + p: Eqs. 2-4 and the summation tree then run once per
 //     layer with one step per lane, as in the other lane-per-step scorers.
 //   * The last chunk of a row is shifted left to end at the row's end; the words
-//     it shares with the chunk before count nothing: their trace words are zeroed on
-//     the way to LDS, and a lane mask keeps them out of the test for stray bits.
+//     it shares with the chunk before are cleared in the registers by a lane mask that
+//     is all ones in every other chunk.
 #include "kvp_internal.h"
 
 namespace {
@@ -29,7 +29,6 @@ namespace {
 typedef uint32_t l4u __attribute__((ext_vector_type(4), aligned(4)));    // rows may be only 4-byte aligned
 typedef uint32_t a4u __attribute__((ext_vector_type(4)));                // LDS vectors are 16-byte aligned
 
-constexpr int LQ = 4;           // schedules (= wavefronts) per workgroup
 constexpr int LCW = 32;         // words per chunk
 constexpr int PLANE = 64 * LCW; // words of one trace array in a slot
 
@@ -46,9 +45,9 @@ __device__ __forceinline__ void count(uint32_t &acc, uint32_t v) {
 }
 __device__ __forceinline__ int clamp_i32(int v, int lo, int hi) { return min(max(v, lo), hi); }
 
-// KB: digit planes of the read weights; POW2: L is a power of two in 2..64.
-// No load is consumed in the iteration that issues it, and all are unconditional.
-template <int KB, bool POW2>
+// KB: digit planes of the read weights; POW2: L is a power of two in 2..64; LQ: schedules (= wavefronts)
+// per workgroup, 4 or 8.  No load is consumed in the iteration that issues it, and all are unconditional.
+template <int KB, bool POW2, int LQ>
 __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     DevProblem q, const uint32_t *__restrict__ Aw, const uint32_t *__restrict__ X, uint32_t S, uint32_t tiles,
     uint32_t nb_total, uint32_t log2L,
@@ -56,6 +55,7 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     uint32_t *__restrict__ counters, uint32_t *__restrict__ occ_out) {
     extern __shared__ double smem_d[];
     constexpr int NT = KB + 3;                                          // digit planes, alive, persist, written
+    constexpr int TV = 8 / LQ;     // vectors of each trace array that a thread moves per chunk (64 rows x 8 parts)
     const uint32_t L = q.L, N = q.N, Wd = q.Wd;
     const uint32_t NCH = (Wd + LCW - 1) / LCW;
     const uint32_t tid = threadIdx.x;
@@ -80,11 +80,16 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     // whose trace words the loader repeats too, and are never owned by an active lane.
     const int step0 = (int)(n0 + 8 * g) - 1;
     const uint32_t sched_words = L * N * Wd;                           // < 2^31 (checked by the host)
-    // trace vectors of this thread: rows tid/8 and 32 + tid/8 of the tile, part tid%8
-    const uint32_t trow0 = min(n0 + (tid >> 3), N - 1), trow1 = min(n0 + 32 + (tid >> 3), N - 1), tpart = tid & 7u;
-    // LDS word of (array a, row) for part tpart: [a][row % 8][row / 8][part][4]
-    auto lds_of = [&](uint32_t row) { return (((row & 7u) * 8 + (row >> 3)) * 8 + tpart) * 4; };
-    const uint32_t tl0 = lds_of(tid >> 3), tl1 = lds_of(32 + (tid >> 3));
+    // trace vectors of this thread: rows tid/8 + 8 LQ v of the tile, part tid%8
+    const uint32_t tpart = tid & 7u;
+    uint32_t tl[TV], tb[TV], ta[TV];      // LDS word of (row, part): [a][row % 8][row / 8][part][4]; byte offsets in V, Pm, Wm; in the planes
+#pragma unroll
+    for (int v = 0; v < TV; v++) {
+        const uint32_t r = (tid >> 3) + 8 * LQ * v, trow = min(n0 + r, N - 1);
+        tl[v] = (((r & 7u) * 8 + (r >> 3)) * 8 + tpart) * 4;
+        tb[v] = 4 * (trow * Wd + 4 * tpart);
+        ta[v] = 4 * (trow * KB * Wd + 4 * tpart);
+    }
 
     // The nine row vectors of the lane.  Vector j is reloaded for the next iteration as soon as the
     // current one has no more use for it, so one iteration's worth of rows is in flight all the time
@@ -101,33 +106,26 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     auto issue_x = [&](int j, uint32_t base, int last_step) __attribute__((always_inline)) {
         x[j] = KVP_LOAD_X((const l4u *)(Xs + (base + (uint32_t)clamp_i32(step0 + j, 0, last_step) * (4 * Wd))));
     };
-    l4u tr[2 * NT];
-    const uint32_t tb0 = 4 * (trow0 * Wd + 4 * tpart), tb1 = 4 * (trow1 * Wd + 4 * tpart);   // byte offsets in V, Pm, Wm
-    const uint32_t ta0 = 4 * (trow0 * KB * Wd + 4 * tpart), ta1 = 4 * (trow1 * KB * Wd + 4 * tpart);   // in the digit planes
+    l4u tr[TV * NT];
     auto issue_t = [&](uint32_t i, uint32_t c) __attribute__((always_inline)) {
         const uint32_t w0b = 4 * min(c * LCW, Wd - LCW);
         const char *Al = (const char *)Aw + (size_t)layer_of(i) * N * KB * Wd * 4 + w0b;
-#pragma unroll
-        for (int k = 0; k < KB; k++) {
-            tr[2 * k] = *(const l4u *)(Al + (ta0 + 4 * k * Wd));
-            tr[2 * k + 1] = *(const l4u *)(Al + (ta1 + 4 * k * Wd));
-        }
         const char *Vb = (const char *)q.V + w0b, *Pb = (const char *)q.Pm + w0b, *Wb = (const char *)q.Wm + w0b;
-        tr[2 * KB] = *(const l4u *)(Vb + tb0);     tr[2 * KB + 1] = *(const l4u *)(Vb + tb1);
-        tr[2 * KB + 2] = *(const l4u *)(Pb + tb0); tr[2 * KB + 3] = *(const l4u *)(Pb + tb1);
-        tr[2 * KB + 4] = *(const l4u *)(Wb + tb0); tr[2 * KB + 5] = *(const l4u *)(Wb + tb1);
-    };
-    // `shared`: leading words of the chunk that the chunk before has counted already (the last chunk of a row
-    // whose width is no multiple of 32): their trace words go to the slot as zeros, so nothing is counted twice
-    auto commit_t = [&](uint32_t it, uint32_t shared) __attribute__((always_inline)) {
-        uint32_t *slot = tbuf + (it & 1u) * NT * PLANE;
-        const uint32_t b = 4 * tpart;
-        const a4u keep = {b + 0 < shared ? 0u : ~0u, b + 1 < shared ? 0u : ~0u, b + 2 < shared ? 0u : ~0u, b + 3 < shared ? 0u : ~0u};
 #pragma unroll
-        for (int a = 0; a < NT; a++) {
-            *(a4u *)(slot + a * PLANE + tl0) = (a4u)tr[2 * a] & keep;
-            *(a4u *)(slot + a * PLANE + tl1) = (a4u)tr[2 * a + 1] & keep;
+        for (int v = 0; v < TV; v++) {
+#pragma unroll
+            for (int k = 0; k < KB; k++) tr[TV * k + v] = *(const l4u *)(Al + (ta[v] + 4 * k * Wd));
+            tr[TV * KB + v] = *(const l4u *)(Vb + tb[v]);
+            tr[TV * (KB + 1) + v] = *(const l4u *)(Pb + tb[v]);
+            tr[TV * (KB + 2) + v] = *(const l4u *)(Wb + tb[v]);
         }
+    };
+    auto commit_t = [&](uint32_t it) __attribute__((always_inline)) {
+        uint32_t *slot = tbuf + (it & 1u) * NT * PLANE;
+#pragma unroll
+        for (int a = 0; a < NT; a++)
+#pragma unroll
+            for (int v = 0; v < TV; v++) *(a4u *)(slot + a * PLANE + tl[v]) = (a4u)tr[TV * a + v];
     };
 
     uint32_t fl_acc = 0, occ_acc = 0;
@@ -145,7 +143,7 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
         for (int j = 0; j < 9; j++) issue_x(j, b0, (int)N - 1);
         advance(ix, cx);
     }
-    commit_t(0, 0);
+    commit_t(0);
     for (uint32_t i = 0; i < L; i++) {
         const uint32_t l = layer_of(i);
         const uint32_t acc_n = q.acc[(size_t)l * N + n];               // used when the row ends
@@ -160,9 +158,9 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
         for (uint32_t c = 0; c < NCH; c++, it++) {
             const uint32_t w0 = min(c * LCW, Wd - LCW);
             const uint32_t skip = c * LCW - w0;                       // leading words already counted (last chunk only)
-            // The row words themselves are never changed under a condition (every one of them would then be waited
-            // for at the top of the iteration): the shared words count nothing because their trace words are zero,
-            // and `kp` keeps them out of the test for stray bits.
+            // Those words are cleared in every row vector just before its first use, in every chunk (the mask is all
+            // ones but in the last): cleared under a condition, every vector would be waited for at the top of the
+            // iteration.
             const a4u kp = {4 * p + 0 < skip ? 0u : ~0u, 4 * p + 1 < skip ? 0u : ~0u, 4 * p + 2 < skip ? 0u : ~0u,
                             4 * p + 3 < skip ? 0u : ~0u};
             const uint32_t nbase = x_base(ix, cx);
@@ -174,7 +172,7 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
             // issue, and waiting for the trace words at the end of an iteration would also wait for the rows
             // requested last, a memory round trip per chunk.  (Nobody reads the slot before the barrier below,
             // and its last readers have passed the barrier of the iteration before.)
-            if (it > 0) commit_t(it, skip);
+            if (it > 0) commit_t(it);
             issue_t(it_, ct); advance(it_, ct);                        // trace words of the next iteration
             __syncthreads();                                           // this iteration's trace slot is complete
             const uint32_t *slot = tbuf + (it & 1u) * NT * PLANE + 4 * (uint32_t)lane;
@@ -188,15 +186,17 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
                 for (int a = 0; a < NT; a++) dst[a] = *(const a4u *)(sj + a * PLANE);
             };
             fetch(0, tv[0]);
+            x[0] = (l4u)((a4u)x[0] & kp);
 #pragma unroll
             for (int j = 0; j < 8; j++) {
                 if (j < 7) fetch(j + 1, tv[(j + 1) & 1]);
+                x[j + 1] = (l4u)((a4u)x[j + 1] & kp);
                 const a4u *cv = tv[j & 1];
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
                     const uint32_t raw = x[j + 1][e], xp = x[j][e];
                     const uint32_t xx = raw & cv[KB][e];           // alive
-                    fl_acc |= raw & ~cv[KB][e] & kp[e];
+                    fl_acc |= raw & ~cv[KB][e];
                     const uint32_t d = (xx ^ xp) & cv[KB + 1][e];  // persist
 #pragma unroll
                     for (int k = 0; k < KB; k++) count(chr[j][k], xx & cv[k][e]);
@@ -267,31 +267,23 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
 
 int kvp_blocksum_from_t_launch(kvp_ctx *ctx, uint32_t S, uint32_t nb_total);
 
-// Returns KVP_OK if launched, 1 if this kernel does not cover the shape, <0 on error.
-int kvp_score_line_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
-                          uint32_t *counters, uint32_t *occ) {
+namespace {
+
+template <int LQ>
+int launch_line(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total, uint32_t log2L,
+                bool pow2, uint32_t *counters, uint32_t *occ) {
     const DevProblem &q = ctx->dp;
-    if (!ctx->aw || q.Wd < LCW) return 1;
     const uint32_t KB = ctx->kb;
-    if (KB > 4) return 1;                                             // registers: five counters per step and digit
-    if ((size_t)q.L * q.N * q.Wd * KB >= (1ull << 30)) return 1;      // 32-bit byte offsets inside a schedule and the planes
-    uint32_t log2L = 0;
-    while ((1u << log2L) < q.L) log2L++;
-    const bool pow2 = q.L >= 2 && q.L <= 64 && (1u << log2L) == q.L;
     const size_t lds = 2 * (size_t)(KB + 3) * PLANE * 4 + (pow2 ? (size_t)6 * LQ * 64 * 8 : 0);
     if (lds > 160 * 1024) return 1;
     const uint64_t nwg = xcd_grid(tiles, (S + LQ - 1) / LQ);
     if (nwg > 0x7FFFFFFFull) return 1;
-    if (!pow2) {
-        int rc = kvp_ensure(ctx, (void **)&ctx->d_tglobal, &ctx->tglobal_cap, (size_t)S * q.L * q.N * sizeof(double));
-        if (rc) return rc;
-    }
     dim3 grid((uint32_t)nwg), block(LQ * 64);
 #define KVP_GO(KK, PP)                                                                                         \
     do {                                                                                                       \
-        KVP_HIP(hipFuncSetAttribute((const void *)score_line_kernel<KK, PP>,                                   \
+        KVP_HIP(hipFuncSetAttribute((const void *)score_line_kernel<KK, PP, LQ>,                               \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                   \
-        score_line_kernel<KK, PP><<<grid, block, lds, ctx->stream>>>(                                          \
+        score_line_kernel<KK, PP, LQ><<<grid, block, lds, ctx->stream>>>(                                      \
             q, ctx->aw, X, S, tiles, nb_total, log2L, ctx->d_blocksum,                                          \
             ctx->d_tglobal, ctx->d_tileflag, counters, occ);                                                   \
     } while (0)
@@ -303,6 +295,33 @@ int kvp_score_line_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t 
 #undef KVP_K
 #undef KVP_GO
     KVP_HIP(hipGetLastError());
+    return KVP_OK;
+}
+
+}  // namespace
+
+// Returns KVP_OK if launched, 1 if this kernel does not cover the shape, <0 on error.
+int kvp_score_line_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total,
+                          uint32_t *counters, uint32_t *occ) {
+    const DevProblem &q = ctx->dp;
+    if (!ctx->aw || q.Wd < LCW) return 1;
+    const uint32_t KB = ctx->kb;
+    if (KB > 4) return 1;                                             // registers: five counters per step and digit
+    if ((size_t)q.L * q.N * q.Wd * KB >= (1ull << 30)) return 1;      // 32-bit byte offsets inside a schedule and the planes
+    uint32_t log2L = 0;
+    while ((1u << log2L) < q.L) log2L++;
+    const bool pow2 = q.L >= 2 && q.L <= 64 && (1u << log2L) == q.L;
+    if (!pow2) {
+        int rc = kvp_ensure(ctx, (void **)&ctx->d_tglobal, &ctx->tglobal_cap, (size_t)S * q.L * q.N * sizeof(double));
+        if (rc) return rc;
+    }
+    // Eight schedules per workgroup share each fetch of the trace (half the trace bytes through L2 and the
+    // fabric of four); a compute unit then holds one workgroup, so that is taken only when there are enough
+    // groups of eight to give every compute unit one.
+    const bool wide = (uint64_t)((S + 7) / 8) * tiles >= ctx->compute_units;
+    int rc = wide ? launch_line<8>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ)
+                  : launch_line<4>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ);
+    if (rc) return rc;
     ctx->last_kernel = KVP_SCORE_LINE;
     if (!pow2) return kvp_blocksum_from_t_launch(ctx, S, nb_total);
     return KVP_OK;

@@ -182,6 +182,33 @@ def test_score_matches_oracle_bit_for_bit(G, name, kernel):
         assert (cost2 == cost).all() and (ex2 == ex).all()
 
 
+@pytest.mark.parametrize("L,N,P,K,S", [(2, 200, 1100, 2, 515), (3, 130, 2080, 1, 683)],
+                         ids=["L2-w35-k2", "L3-w65"])
+def test_line_scorer_with_eight_schedules_per_workgroup(G, L, N, P, K, S):
+    """Batches with a group of eight schedules for every compute unit take the line scorer's wider workgroup
+    (eight wavefronts share each fetch of the trace): every schedule against the oracle.  S is no multiple of
+    eight (spare wavefronts in the last group), the last tile is ragged, and the last chunk of a row overlaps
+    the one before."""
+    import torch
+    tr = W.random_trace(90 + L, L=L, N=N, P=P, K=K)
+    tiles = (N + 63) // 64
+    assert ((S + 7) // 8) * tiles >= torch.cuda.get_device_properties(0).multi_processor_count
+    assert S % 8 and N % 64 and tr.n_words % 32
+    X = np.concatenate([W.random_placements(tr, S - 2, seed=3, density=0.4),
+                        W.random_placements(tr, 2, seed=4, density=0.9, feasible=False)])
+    q = O.Problem(tr)
+    with G(tr, score_kernel=KERNEL_ID["line"]) as g:
+        cost, ex, cnt, occ = g.score(X)
+        assert KERNEL_NAME[g.kernel_used()] == "line"
+        from gpu_util import expected_counters
+        for s in range(S):
+            r = O.score(q, X[s])
+            assert cost[s] == r.cost and ex[s] == r.excess, s
+            assert (occ[s] == r.occ).all(), s
+            if s % 64 == 0 or s >= S - 8:
+                assert (cnt[s].astype(np.uint64) == expected_counters(r, tr, g.unit)).all(), s
+
+
 def test_set_score_kernel_refuses_values_that_name_no_scorer(G):
     import paper_2508_13231_amd as K
     with G(W.config("table1")) as g:
