@@ -226,10 +226,11 @@ def kvp_anneal(ctx, params: kvp_anneal_params, d_init=None):
     _check(lib().kvp_anneal(ctx, C.byref(params), _dptr(d_init)), "kvp_anneal")
 
 
-def kvp_best(ctx, shape_words, n_chains=None):
-    """(cost, chain, placement words [L][N][Wd], per-chain costs or None)."""
+def kvp_best(ctx, shape_words=None, n_chains=None):
+    """(cost, chain, placement words [L][N][Wd] or None, per-chain costs or None).  Without `shape_words`
+    the winner's schedule stays on the device (no copy to the host)."""
     cost, chain = C.c_double(0.0), C.c_uint32(0)
-    pl = np.zeros(shape_words, dtype=np.uint32)
+    pl = np.empty(shape_words, dtype=np.uint32) if shape_words is not None else None
     cc = np.zeros(int(n_chains), dtype=np.float64) if n_chains else None
     _check(lib().kvp_best(ctx, C.byref(cost), C.byref(chain), _hptr(pl), _hptr(cc)), "kvp_best")
     return cost.value, chain.value, pl, cc

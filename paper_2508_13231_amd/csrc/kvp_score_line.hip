@@ -3,10 +3,12 @@
 //   * A workgroup is four or eight wavefronts scoring the same 64 token steps of as
 //     many schedules.  A row is walked in chunks of 32 words = one 128-byte line when
 //     rows are line-aligned.  Lane (g, p), g = lane / 8, p = lane % 8, takes the
-//     16-byte part p of the chunk for the steps 8g .. 8g+7 and for step 8g-1: nine
-//     loads per lane and chunk, each wavefront instruction covering whole lines.
-//     A lane scores its parts straight from registers, the row above being the
-//     previous register, and keeps five counters per step until the row ends.
+//     16-byte part p of the chunk for the steps 8g .. 8g+7: eight loads per lane and
+//     chunk, each wavefront instruction covering whole lines.  A lane scores its
+//     parts straight from registers, the row above being the previous register (for
+//     a lane's first step: the last register of the lane eight below, or, in the
+//     first group, a ninth load of the step before the tile), and keeps five counters
+//     per step until the row ends.
 //   * The trace words of a chunk (binary digit planes of the read weights, alive,
 //     persist, written) are the same for those schedules: fetched once per
 //     workgroup, one chunk ahead, into a double-buffered LDS slot laid out in the
@@ -43,7 +45,6 @@ __device__ __forceinline__ uint32_t oct_sum(uint32_t v) {               // sum o
 __device__ __forceinline__ void count(uint32_t &acc, uint32_t v) {
     asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(v));
 }
-__device__ __forceinline__ int clamp_i32(int v, int lo, int hi) { return min(max(v, lo), hi); }
 
 // KB: digit planes of the read weights; POW2: L is a power of two in 2..64; LQ: schedules (= wavefronts)
 // per workgroup, 4 or 8.  No load is consumed in the iteration that issues it, and all are unconditional.
@@ -75,9 +76,9 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     const bool active = (uint32_t)lane < rows;
     const uint32_t n = n0 + (active ? (uint32_t)lane : rows - 1);      // idle lanes shadow the last row
     const uint32_t wr_n = q.wr[n];
-    // Steps of the lane's nine loads: 8g-1 .. 8g+7 of the tile, kept inside the trace.  Step 0 is its
-    // own predecessor (nothing differs, nothing migrates); steps past the end repeat the last one,
-    // whose trace words the loader repeats too, and are never owned by an active lane.
+    // The lane's steps are 8g .. 8g+7 of the tile, kept inside the trace: steps past the end repeat the
+    // last one, whose trace words the loader repeats too, and are never owned by an active lane.  Step 0
+    // is its own predecessor (nothing differs, nothing migrates).
     const int step0 = (int)(n0 + 8 * g) - 1;
     const uint32_t sched_words = L * N * Wd;                           // < 2^31 (checked by the host)
     // trace vectors of this thread: rows tid/8 + 8 LQ v of the tile, part tid%8
@@ -103,8 +104,14 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     // schedule and the digit planes stay below 4 GiB).
     const char *Xs = (const char *)(X + (size_t)sc * sched_words);
     auto x_base = [&](uint32_t i, uint32_t c) { return 4 * (layer_of(i) * N * Wd + min(c * LCW, Wd - LCW) + 4 * p); };
+    // Vector j >= 1 is the lane's step 8g + j - 1; vector 0 is the step before the TILE, the same 128 bytes for
+    // every lane (one request), which only the first group of lanes uses: the step before the first of any other
+    // group is the last step of the group below, taken from those lanes' registers.  (Requested by both groups,
+    // an iteration apart, such a row came from memory twice more often than not: the rows are streamed through
+    // L2 without being kept.)
     auto issue_x = [&](int j, uint32_t base, int last_step) __attribute__((always_inline)) {
-        x[j] = KVP_LOAD_X((const l4u *)(Xs + (base + (uint32_t)clamp_i32(step0 + j, 0, last_step) * (4 * Wd))));
+        const int row = j == 0 ? (int)(n0 ? n0 - 1 : 0) : min(step0 + j, last_step);
+        x[j] = KVP_LOAD_X((const l4u *)(Xs + (base + (uint32_t)row * (4 * Wd))));
     };
     l4u tr[TV * NT];
     auto issue_t = [&](uint32_t i, uint32_t c) __attribute__((always_inline)) {
@@ -140,7 +147,7 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     {
         const uint32_t b0 = x_base(0, 0);
 #pragma unroll
-        for (int j = 0; j < 9; j++) issue_x(j, b0, (int)N - 1);
+        for (int j = 8; j >= 0; j--) issue_x(j, b0, (int)N - 1);
         advance(ix, cx);
     }
     commit_t(0);
@@ -185,16 +192,21 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
 #pragma unroll
                 for (int a = 0; a < NT; a++) dst[a] = *(const a4u *)(sj + a * PLANE);
             };
-            fetch(0, tv[0]);
-            x[0] = (l4u)((a4u)x[0] & kp);
+            // The steps are taken from the lane's last to its first: the last step's row arrives first and hands
+            // its words to the group above right away; the step before the tile is needed last.
+            fetch(7, tv[1]);
+            a4u below;                                                 // the last step of the group of lanes below
 #pragma unroll
-            for (int j = 0; j < 8; j++) {
-                if (j < 7) fetch(j + 1, tv[(j + 1) & 1]);
-                x[j + 1] = (l4u)((a4u)x[j + 1] & kp);
+            for (int e = 0; e < 4; e++)
+                below[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (lane - 8), (int)x[8][e]);
+#pragma unroll
+            for (int j = 7; j >= 0; j--) {
+                if (j > 0) fetch(j - 1, tv[(j - 1) & 1]);
                 const a4u *cv = tv[j & 1];
+                const a4u before = j > 0 ? (a4u)x[j] : (g == 0 ? (a4u)x[0] : below);
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
-                    const uint32_t raw = x[j + 1][e], xp = x[j][e];
+                    const uint32_t raw = x[j + 1][e] & kp[e], xp = before[e] & kp[e];
                     const uint32_t xx = raw & cv[KB][e];           // alive
                     fl_acc |= raw & ~cv[KB][e];
                     const uint32_t d = (xx ^ xp) & cv[KB + 1][e];  // persist
@@ -205,8 +217,8 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
                     count(cmi[j], d & xx);
                     count(cmg[j], d);
                 }
-                issue_x(j, nbase, last_step);                      // its last use was as the step before
-                if (j == 7) issue_x(8, nbase, last_step);
+                issue_x(j + 1, nbase, last_step);                  // its last use was as this step's own row
+                if (j == 0) issue_x(0, nbase, last_step);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
