@@ -28,6 +28,12 @@ namespace {
 
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));   // native vector: stays in registers
 
+// acc += popcount(v) as the one instruction the hardware has for it (left to itself the compiler
+// counts into fresh registers and adds them up three at a time)
+__device__ __forceinline__ void count(uint32_t &acc, uint32_t v) {
+    asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(v));
+}
+
 constexpr int QUAD = 4;              // schedules (= wavefronts) per workgroup
 constexpr int A_SLOT = QUAD * 64 * 4;   // words of one trace slot: one 16-byte vector per thread
 
@@ -133,21 +139,21 @@ __global__ __launch_bounds__(QUAD * 64) void score_quad_kernel(
             if (w < W0) {
                 // all 32 pages exist and persist on every step of the tile: no masking needed
                 // (at step 0 prv is cur, so nothing migrates there either)
-                hr += __popc(raw & ar[w]);
-                if (!W1) hw += __popc(raw & wm[w]);
-                oc += __popc(raw);
+                count(hr, raw & ar[w]);
+                if (!W1) count(hw, raw & wm[w]);
+                count(oc, raw);
                 const uint32_t d = raw ^ xp;
-                mi += __popc(d & raw);
-                mg += __popc(d);
+                count(mi, d & raw);
+                count(mg, d);
             } else {
                 const uint32_t x = raw & vv[w - W0];
                 fl_acc |= raw & ~vv[w - W0];
-                hr += __popc(x & ar[w]);
-                if (!W1) hw += __popc(x & wm[w]);
-                oc += __popc(x);
+                count(hr, x & ar[w]);
+                if (!W1) count(hw, x & wm[w]);
+                count(oc, x);
                 const uint32_t d = (x ^ xp) & pm[w - W0];
-                mi += __popc(d & x);
-                mg += __popc(d);
+                count(mi, d & x);
+                count(mg, d);
             }
         }
         if (W1) hw = __popc(cur[wsel] & wm[0]);                // written pages exist, so raw & wm == x & wm
