@@ -33,7 +33,6 @@ constexpr int LXV = 10;         // 16-byte vectors per lane and layer: ceil(65 *
 constexpr int LGEN = 7;         // words between the unmasked groups of four and the sequence's end
 constexpr int LQMAX = 7;        // largest odd factor of L whose tree stays on chip
 
-__device__ __forceinline__ void put4(uint32_t *p, r4u v) { p[0] = v.x; p[1] = v.y; p[2] = v.z; p[3] = v.w; }
 // acc += popcount(v) as the one instruction the hardware has for it
 __device__ __forceinline__ void count(uint32_t &acc, uint32_t v) {
     asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(v));
@@ -90,9 +89,12 @@ __global__ __launch_bounds__(NW * 64) void score_rowlane_kernel(
     for (int jv = 0; jv < LXV; jv++) {
         const uint32_t vi = min((uint32_t)lane + 64u * jv, LROWS * PPR - 1);
         const uint32_t row = vi / PPR, part = vi - row * PPR;
-        const uint32_t w0 = min(4 * part, Wd - 4);                     // a row's last vector ends at the row's end
-        xrel[jv] = 4 * (row * Wd + w0);
-        xlds[jv] = row * LRS + w0;
+        // Every vector starts at a multiple of four words of its row, so that it goes to LDS as one 16-byte
+        // write (an LDS instruction costs some four cycles whatever its width, and four-byte writes at this
+        // stride twice that).  A row's last vector then runs up to three words into the next row: they land in
+        // the row's padding, which nobody reads.
+        xrel[jv] = 4 * (row * Wd + 4 * part);
+        xlds[jv] = row * LRS + 4 * part;
     }
     const uint32_t sched_words = L * N * Wd;                           // < 2^29 (checked by the host)
     const uint32_t qinv = 65536u / qodd + 1u;
@@ -110,18 +112,30 @@ __global__ __launch_bounds__(NW * 64) void score_rowlane_kernel(
     uint2 spe[2] = {make_uint2(0u, 0u), make_uint2(0u, 0u)};
     const char *Xs = (const char *)(X + (size_t)sc * sched_words);
     const bool edge_tile = rows < 64;
+    const bool batch_end = sc == S - 1 && tile == tiles - 1;           // the tile's last row of the last layer ends the batch
     // The parked rows of layer l start at the step before the tile.  Step 0 has none: there the offsets are
     // clamped from below and lane 0 uses the step itself as its predecessor (nothing migrates at step 0).
+    // Where the rows end with the schedule (the last layer of a tile that the trace does not fill, and the very
+    // end of the batch), a vector that would run past the end is fetched from the schedule's last 16 bytes
+    // instead and its words are moved down to where they belong.
     auto issue_x = [&](Stage &st, uint32_t l) __attribute__((always_inline)) {
         const int before = 4 * ((int)((l * N + n0) * Wd) - (int)Wd);
-        if (before >= 0 && !edge_tile) {
+        if (before >= 0 && !edge_tile && !(batch_end && l == L - 1)) {
 #pragma unroll
             for (int jv = 0; jv < LXV; jv++) st.x[jv] = KVP_LOAD_X((const r4u *)(Xs + ((uint32_t)before + xrel[jv])));
         } else {
             const int hi = 4 * ((int)sched_words - 4);
 #pragma unroll
-            for (int jv = 0; jv < LXV; jv++)
-                st.x[jv] = KVP_LOAD_X((const r4u *)(Xs + (uint32_t)min(max(before + (int)xrel[jv], 0), hi)));
+            for (int jv = 0; jv < LXV; jv++) {
+                const int at = before + (int)xrel[jv];
+                const r4u v = KVP_LOAD_X((const r4u *)(Xs + (uint32_t)min(max(at, 0), hi)));
+                const int d = at > hi ? (at - hi) >> 2 : 0;            // words that the fetch was moved back by
+                r4u w = v;
+                w.x = d == 1 ? v.y : d == 2 ? v.z : d == 3 ? v.w : v.x;
+                w.y = d == 1 ? v.z : d == 2 ? v.w : v.y;
+                w.z = d == 1 ? v.w : v.z;
+                st.x[jv] = w;
+            }
         }
     };
     const char *Tt = (const char *)TL + (size_t)tile * SLOT * 4 + 16u * tid;
@@ -154,7 +168,7 @@ __global__ __launch_bounds__(NW * 64) void score_rowlane_kernel(
     auto layer = [&](Stage &st, uint32_t i) __attribute__((always_inline)) {
         const uint32_t lnext = layer_of(min(i + 1, L - 1));
 #pragma unroll
-        for (int jv = 0; jv < LXV; jv++) put4(xbuf + xlds[jv], st.x[jv]);
+        for (int jv = 0; jv < LXV; jv++) *(a4u *)(xbuf + xlds[jv]) = (a4u)st.x[jv];
         uint2 e0 = spe[0], e1 = spe[1];
         // (loads complete in the order of their issue: the digit planes, wanted at the end of this layer, go
         // first, so that waiting for them does not wait for the rows, which have until the next layer starts)
