@@ -34,7 +34,15 @@ constexpr int RQ = 4;          // schedules (= wavefronts) per workgroup
 constexpr int RR = 32;         // token steps per pass (two lanes per step)
 constexpr int TWMAX = 4;       // words at the end of a row that may need masks
 
+typedef uint32_t a2u __attribute__((ext_vector_type(2)));               // 8-byte aligned LDS words
+
 __device__ __forceinline__ void put4(uint32_t *p, r4u v) { p[0] = v.x; p[1] = v.y; p[2] = v.z; p[3] = v.w; }
+// The same at an even word of LDS: two 8-byte writes.  (An LDS instruction costs some four cycles of the LDS
+// pipeline whatever its width, and a 4-byte write at a lane stride of four words twice that.)
+__device__ __forceinline__ void put22(uint32_t *p, r4u v) {
+    *(a2u *)p = (a2u){v.x, v.y};
+    *(a2u *)(p + 2) = (a2u){v.z, v.w};
+}
 __device__ __forceinline__ uint32_t pair_sum(uint32_t v) {            // v + the other lane of the row
     return v + (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
 }
@@ -204,7 +212,10 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
     auto commit_t = [&](uint32_t slot) __attribute__((always_inline)) {
         uint32_t *dst = tbuf + slot * KB * TPL;
 #pragma unroll
-        for (int jt = 0; jt < TV; jt++) put4(dst + tlds[jt], tr[jt]);
+        for (int jt = 0; jt < TV; jt++) {
+            if (Wd & 1u) put4(dst + tlds[jt], tr[jt]);
+            else put22(dst + tlds[jt], tr[jt]);
+        }
     };
 
     const uint32_t row_off = r * RS;
@@ -216,8 +227,14 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
     // one pass: stage st holds the rows of (layer i-th in visiting order, pass p)
     auto pass = [&](Stage &st, const uint32_t p, uint32_t i) __attribute__((always_inline)) {
         const uint32_t lnext = layer_of(min(i + 1, L - 1));
+        // rows of an even number of words: every vector starts at an even word of LDS (the row stride is even)
+        if (Wd & 1u) {
 #pragma unroll
-        for (int jv = 0; jv < XV; jv++) put4(xbuf + xlds[jv], st.x[jv]);
+            for (int jv = 0; jv < XV; jv++) put4(xbuf + xlds[jv], st.x[jv]);
+        } else {
+#pragma unroll
+            for (int jv = 0; jv < XV; jv++) put22(xbuf + xlds[jv], st.x[jv]);
+        }
         issue_t(p ^ 1u, p ? lnext : layer_of(i));                      // digit planes of the next pass
         issue_x(st, p, lnext);                                         // rows of two passes ahead
         __syncthreads();                                               // this pass's trace slot is complete
