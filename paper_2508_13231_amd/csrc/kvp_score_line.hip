@@ -22,8 +22,8 @@
 //     (g, p) keeps step 8g + p: Eqs. 2-4 and the summation tree then run once per
 //     layer with one step per lane, as in the other lane-per-step scorers.
 //   * The last chunk of a row is shifted left to end at the row's end; the words
-//     it shares with the chunk before are cleared in the registers by a lane mask that
-//     is all ones in every other chunk.
+//     it shares with the chunk before count nothing: their alive and persist words are
+//     zeroed on the way to LDS, and a lane mask takes them out of the chunk's stray bits.
 #include "kvp_internal.h"
 
 namespace {
@@ -127,12 +127,18 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
             tr[TV * (KB + 2) + v] = *(const l4u *)(Wb + tb[v]);
         }
     };
-    auto commit_t = [&](uint32_t it) __attribute__((always_inline)) {
+    // `keep`: all ones, but zero for the words that the row's last chunk shares with the chunk before.  Their alive
+    // and persist words go to the slot as zeros, so they count nothing a second time (a thread moves the same part
+    // of a chunk as its lane scores: tid % 8 = lane % 8).
+    auto commit_t = [&](uint32_t it, a4u keep) __attribute__((always_inline)) {
         uint32_t *slot = tbuf + (it & 1u) * NT * PLANE;
 #pragma unroll
         for (int a = 0; a < NT; a++)
 #pragma unroll
-            for (int v = 0; v < TV; v++) *(a4u *)(slot + a * PLANE + tl[v]) = (a4u)tr[TV * a + v];
+            for (int v = 0; v < TV; v++) {
+                const a4u t = (a4u)tr[TV * a + v];
+                *(a4u *)(slot + a * PLANE + tl[v]) = (a == KB || a == KB + 1) ? (t & keep) : t;
+            }
     };
 
     uint32_t fl_acc = 0, occ_acc = 0;
@@ -150,7 +156,7 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
         for (int j = 8; j >= 0; j--) issue_x(j, b0, (int)N - 1);
         advance(ix, cx);
     }
-    commit_t(0);
+    commit_t(0, (a4u){~0u, ~0u, ~0u, ~0u});
     for (uint32_t i = 0; i < L; i++) {
         const uint32_t l = layer_of(i);
         const uint32_t acc_n = q.acc[(size_t)l * N + n];               // used when the row ends
@@ -165,9 +171,10 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
         for (uint32_t c = 0; c < NCH; c++, it++) {
             const uint32_t w0 = min(c * LCW, Wd - LCW);
             const uint32_t skip = c * LCW - w0;                       // leading words already counted (last chunk only)
-            // Those words are cleared in every row vector just before its first use, in every chunk (the mask is all
-            // ones but in the last): cleared under a condition, every vector would be waited for at the top of the
-            // iteration.
+            // `kp` is all ones but for those words.  The row vectors themselves are left alone (cleared under a
+            // condition, every one of them would be waited for at the top of the iteration; cleared always, that is 36
+            // instructions per chunk): the shared words count nothing because their alive and persist words are zero
+            // in the slot, and `kp` takes them out of the chunk's stray bits at its end.
             const a4u kp = {4 * p + 0 < skip ? 0u : ~0u, 4 * p + 1 < skip ? 0u : ~0u, 4 * p + 2 < skip ? 0u : ~0u,
                             4 * p + 3 < skip ? 0u : ~0u};
             const uint32_t nbase = x_base(ix, cx);
@@ -179,7 +186,7 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
             // issue, and waiting for the trace words at the end of an iteration would also wait for the rows
             // requested last, a memory round trip per chunk.  (Nobody reads the slot before the barrier below,
             // and its last readers have passed the barrier of the iteration before.)
-            if (it > 0) commit_t(it);
+            if (it > 0) commit_t(it, kp);
             issue_t(it_, ct); advance(it_, ct);                        // trace words of the next iteration
             __syncthreads();                                           // this iteration's trace slot is complete
             const uint32_t *slot = tbuf + (it & 1u) * NT * PLANE + 4 * (uint32_t)lane;
@@ -195,6 +202,7 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
             // The steps are taken from the lane's last to its first: the last step's row arrives first and hands
             // its words to the group above right away; the step before the tile is needed last.
             fetch(7, tv[1]);
+            a4u fl_e = {0u, 0u, 0u, 0u};                               // stray bits of this chunk, per word of the lane's part
             a4u below;                                                 // the last step of the group of lanes below
 #pragma unroll
             for (int e = 0; e < 4; e++)
@@ -206,9 +214,9 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
                 const a4u before = j > 0 ? (a4u)x[j] : (g == 0 ? (a4u)x[0] : below);
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
-                    const uint32_t raw = x[j + 1][e] & kp[e], xp = before[e] & kp[e];
+                    const uint32_t raw = x[j + 1][e], xp = before[e];
                     const uint32_t xx = raw & cv[KB][e];           // alive
-                    fl_acc |= raw & ~cv[KB][e];
+                    fl_e[e] |= raw & ~cv[KB][e];
                     const uint32_t d = (xx ^ xp) & cv[KB + 1][e];  // persist
 #pragma unroll
                     for (int k = 0; k < KB; k++) count(chr[j][k], xx & cv[k][e]);
@@ -221,6 +229,7 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
                 if (j == 0) issue_x(0, nbase, last_step);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            fl_acc |= (fl_e.x & kp.x) | (fl_e.y & kp.y) | (fl_e.z & kp.z) | (fl_e.w & kp.w);
         }
         // the rows are complete: the group's lanes add up, lane (g, p) keeps step 8g + p
         uint32_t hr = 0, hw = 0, oc = 0, mi = 0, mg = 0;
