@@ -46,9 +46,10 @@ __device__ __forceinline__ void count(uint32_t &acc, uint32_t v) {
     asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(v));
 }
 
-// KB: digit planes of the read weights; POW2: L is a power of two in 2..64; LQ: schedules (= wavefronts)
-// per workgroup, 4 or 8.  No load is consumed in the iteration that issues it, and all are unconditional.
-template <int KB, bool POW2, int LQ>
+// KB: digit planes of the read weights; POW2: L is a power of two in 2..64; LQ: wavefronts per workgroup,
+// 4 or 8; PS: schedules per wavefront, 1 or 2 (a wavefront then scores the chunk for one schedule after the
+// other from the same trace slot).  No load is consumed in the iteration that issues it, and all are unconditional.
+template <int KB, bool POW2, int LQ, int PS>
 __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     DevProblem q, const uint32_t *__restrict__ Aw, const uint32_t *__restrict__ X, uint32_t S, uint32_t tiles,
     uint32_t nb_total, uint32_t log2L,
@@ -63,10 +64,8 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     const int lane = lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / KVP_WAVE));
     uint32_t tile, group;                                             // see xcd_pair for the placement
-    if (!xcd_pair(tiles, (S + LQ - 1) / LQ, tile, group)) return;
-    const uint32_t s = group * LQ + wave;
-    const bool has_s = s < S;
-    const uint32_t sc = has_s ? s : S - 1;                             // spare wavefronts shadow the last schedule
+    if (!xcd_pair(tiles, (S + LQ * PS - 1) / (LQ * PS), tile, group)) return;
+    const uint32_t s0 = (group * LQ + wave) * PS;                      // the wavefront's schedules: s0 .. s0 + PS - 1
     const uint32_t n0 = tile * 64;
     const uint32_t rows = min(64u, N - n0);
     uint32_t *tbuf = (uint32_t *)smem_d;                               // two slots of NT * PLANE words
@@ -102,16 +101,19 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     };
     // All addresses are a wavefront-uniform base plus a 32-bit byte offset (the host checks that a
     // schedule and the digit planes stay below 4 GiB).
-    const char *Xs = (const char *)(X + (size_t)sc * sched_words);
+    const char *Xs[PS];
+#pragma unroll
+    for (int u = 0; u < PS; u++)                                       // spare places shadow the last schedule
+        Xs[u] = (const char *)(X + (size_t)min(s0 + u, S - 1) * sched_words);
     auto x_base = [&](uint32_t i, uint32_t c) { return 4 * (layer_of(i) * N * Wd + min(c * LCW, Wd - LCW) + 4 * p); };
     // Vector j >= 1 is the lane's step 8g + j - 1; vector 0 is the step before the TILE, the same 128 bytes for
     // every lane (one request), which only the first group of lanes uses: the step before the first of any other
     // group is the last step of the group below, taken from those lanes' registers.  (Requested by both groups,
     // an iteration apart, such a row came from memory twice more often than not: the rows are streamed through
     // L2 without being kept.)
-    auto issue_x = [&](int j, uint32_t base, int last_step) __attribute__((always_inline)) {
+    auto issue_x = [&](int j, const char *Xu, uint32_t base, int last_step) __attribute__((always_inline)) {
         const int row = j == 0 ? (int)(n0 ? n0 - 1 : 0) : min(step0 + j, last_step);
-        x[j] = KVP_LOAD_X((const l4u *)(Xs + (base + (uint32_t)row * (4 * Wd))));
+        x[j] = KVP_LOAD_X((const l4u *)(Xu + (base + (uint32_t)row * (4 * Wd))));
     };
     l4u tr[TV * NT];
     auto issue_t = [&](uint32_t i, uint32_t c) __attribute__((always_inline)) {
@@ -141,33 +143,35 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
             }
     };
 
-    uint32_t fl_acc = 0, occ_acc = 0;
-    // partial sums of the binary counter: touched once per layer, so they live in LDS ([level][thread])
+    uint32_t fl_acc[PS], occ_acc[PS];
+    double total[PS];
+#pragma unroll
+    for (int u = 0; u < PS; u++) { fl_acc[u] = 0; occ_acc[u] = 0; total[u] = 0.0; }
+    // partial sums of the binary counter: touched once per layer, so they live in LDS ([schedule][level][thread])
     double *stk = smem_d + (size_t)NT * PLANE + tid;
-    double total = 0.0;
     uint32_t it_ = 0, ct = 0;                // iteration whose trace words are requested next
     uint32_t ix = 0, cx = 0;                 // the iteration after the one being scored
     uint32_t it = 0;                         // iterations done: (layer, chunk) pairs in order
 
     issue_t(it_, ct); advance(it_, ct);
-    {
-        const uint32_t b0 = x_base(0, 0);
+    uint32_t cbase = x_base(0, 0);           // where the chunk being scored starts in a schedule
 #pragma unroll
-        for (int j = 8; j >= 0; j--) issue_x(j, b0, (int)N - 1);
-        advance(ix, cx);
-    }
+    for (int j = 8; j >= 0; j--) issue_x(j, Xs[0], cbase, (int)N - 1);
+    advance(ix, cx);
     commit_t(0, (a4u){~0u, ~0u, ~0u, ~0u});
     for (uint32_t i = 0; i < L; i++) {
         const uint32_t l = layer_of(i);
         const uint32_t acc_n = q.acc[(size_t)l * N + n];               // used when the row ends
         // counters of the steps 8g .. 8g+7 on this layer, this lane's parts only
-        uint32_t chr[8][KB], chw[8], coc[8], cmi[8], cmg[8];
+        uint32_t chr[PS][8][KB], chw[PS][8], coc[PS][8], cmi[PS][8], cmg[PS][8];
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
+        for (int u = 0; u < PS; u++)
 #pragma unroll
-            for (int k = 0; k < KB; k++) chr[j][k] = 0;
-            chw[j] = coc[j] = cmi[j] = cmg[j] = 0;
-        }
+            for (int j = 0; j < 8; j++) {
+#pragma unroll
+                for (int k = 0; k < KB; k++) chr[u][j][k] = 0;
+                chw[u][j] = coc[u][j] = cmi[u][j] = cmg[u][j] = 0;
+            }
         for (uint32_t c = 0; c < NCH; c++, it++) {
             const uint32_t w0 = min(c * LCW, Wd - LCW);
             const uint32_t skip = c * LCW - w0;                       // leading words already counted (last chunk only)
@@ -199,89 +203,106 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
 #pragma unroll
                 for (int a = 0; a < NT; a++) dst[a] = *(const a4u *)(sj + a * PLANE);
             };
-            // The steps are taken from the lane's last to its first: the last step's row arrives first and hands
-            // its words to the group above right away; the step before the tile is needed last.
-            fetch(7, tv[1]);
-            a4u fl_e = {0u, 0u, 0u, 0u};                               // stray bits of this chunk, per word of the lane's part
-            a4u below;                                                 // the last step of the group of lanes below
 #pragma unroll
-            for (int e = 0; e < 4; e++)
-                below[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (lane - 8), (int)x[8][e]);
+            for (int u = 0; u < PS; u++) {
+                // the rows requested while this schedule is scored: the same chunk of the wavefront's next
+                // schedule, or the next chunk of its first
+                const char *Xn = u + 1 < PS ? Xs[u + 1 < PS ? u + 1 : 0] : Xs[0];
+                const uint32_t bn = u + 1 < PS ? cbase : nbase;
+                // The steps are taken from the lane's last to its first: the last step's row arrives first and
+                // hands its words to the group above right away; the step before the tile is needed last.
+                fetch(7, tv[1]);
+                a4u fl_e = {0u, 0u, 0u, 0u};                           // stray bits of this chunk, per word of the lane's part
+                a4u below;                                             // the last step of the group of lanes below
 #pragma unroll
-            for (int j = 7; j >= 0; j--) {
-                if (j > 0) fetch(j - 1, tv[(j - 1) & 1]);
-                const a4u *cv = tv[j & 1];
-                const a4u before = j > 0 ? (a4u)x[j] : (g == 0 ? (a4u)x[0] : below);
+                for (int e = 0; e < 4; e++)
+                    below[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (lane - 8), (int)x[8][e]);
 #pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    const uint32_t raw = x[j + 1][e], xp = before[e];
-                    const uint32_t xx = raw & cv[KB][e];           // alive
-                    fl_e[e] |= raw & ~cv[KB][e];
-                    const uint32_t d = (xx ^ xp) & cv[KB + 1][e];  // persist
+                for (int j = 7; j >= 0; j--) {
+                    if (j > 0) fetch(j - 1, tv[(j - 1) & 1]);
+                    const a4u *cv = tv[j & 1];
+                    const a4u before = j > 0 ? (a4u)x[j] : (g == 0 ? (a4u)x[0] : below);
 #pragma unroll
-                    for (int k = 0; k < KB; k++) count(chr[j][k], xx & cv[k][e]);
-                    count(chw[j], xx & cv[KB + 2][e]);             // written
-                    count(coc[j], xx);
-                    count(cmi[j], d & xx);
-                    count(cmg[j], d);
+                    for (int e = 0; e < 4; e++) {
+                        const uint32_t raw = x[j + 1][e], xp = before[e];
+                        const uint32_t xx = raw & cv[KB][e];       // alive
+                        fl_e[e] |= raw & ~cv[KB][e];
+                        const uint32_t d = (xx ^ xp) & cv[KB + 1][e];  // persist
+#pragma unroll
+                        for (int k = 0; k < KB; k++) count(chr[u][j][k], xx & cv[k][e]);
+                        count(chw[u][j], xx & cv[KB + 2][e]);      // written
+                        count(coc[u][j], xx);
+                        count(cmi[u][j], d & xx);
+                        count(cmg[u][j], d);
+                    }
+                    issue_x(j + 1, Xn, bn, last_step);             // its last use was as this step's own row
+                    if (j == 0) issue_x(0, Xn, bn, last_step);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                issue_x(j + 1, nbase, last_step);                  // its last use was as this step's own row
-                if (j == 0) issue_x(0, nbase, last_step);
-                __builtin_amdgcn_sched_barrier(0);
+                fl_acc[u] |= (fl_e.x & kp.x) | (fl_e.y & kp.y) | (fl_e.z & kp.z) | (fl_e.w & kp.w);
             }
-            fl_acc |= (fl_e.x & kp.x) | (fl_e.y & kp.y) | (fl_e.z & kp.z) | (fl_e.w & kp.w);
+            cbase = nbase;
         }
         // the rows are complete: the group's lanes add up, lane (g, p) keeps step 8g + p
-        uint32_t hr = 0, hw = 0, oc = 0, mi = 0, mg = 0;
 #pragma unroll
-        for (int j = 0; j < 8; j++) {
-            uint32_t h = 0;
+        for (int u = 0; u < PS; u++) {
+            const uint32_t s = s0 + u;
+            const bool has_s = s < S;
+            uint32_t hr = 0, hw = 0, oc = 0, mi = 0, mg = 0;
 #pragma unroll
-            for (int k = 0; k < KB; k++) h += chr[j][k] << k;
-            h = oct_sum(h);
-            const uint32_t w = oct_sum(chw[j]), o = oct_sum(coc[j]), m1 = oct_sum(cmi[j]), m2 = oct_sum(cmg[j]);
-            const bool mine = p == (uint32_t)j;
-            hr = mine ? h : hr; hw = mine ? w : hw; oc = mine ? o : oc; mi = mine ? m1 : mi; mg = mine ? m2 : mg;
-            __builtin_amdgcn_sched_barrier(0);                         // one step at a time: few temporaries
-        }
-        const uint32_t mo = mg - mi;
-        double t = step_time(q, hr, hw, mi, mo, acc_n, wr_n);          // Eqs. 2-4
-        t = active ? t : 0.0;                                          // rows past the end of the trace pad with +0.0
-        occ_acc += oc;
-        if (counters && has_s && active)
-            *(uint4 *)(counters + (((size_t)s * L + l) * N + n) * 4) = make_uint4(hr, hw, mi, mo);
-        if (POW2) {
-            // folds of the summation tree that join the steps of one block (lanes)
-            for (uint32_t m = (64u >> log2L) >> 1; m >= 1; m >>= 1) t = fold_xor_f64(t, m);
-            // folds that join layers: binary counter over the bit-reversed visiting order
-            double carry = t;
-            bool parked = false;
+            for (int j = 0; j < 8; j++) {
+                uint32_t h = 0;
 #pragma unroll
-            for (int j = 0; j < 6; j++) {
-                if (!parked && (uint32_t)j < log2L) {
-                    if (((i >> j) & 1u) == 0) { stk[j * LQ * 64] = carry; parked = true; }
-                    else carry = stk[j * LQ * 64] + carry;
-                }
+                for (int k = 0; k < KB; k++) h += chr[u][j][k] << k;
+                h = oct_sum(h);
+                const uint32_t w = oct_sum(chw[u][j]), o = oct_sum(coc[u][j]), m1 = oct_sum(cmi[u][j]), m2 = oct_sum(cmg[u][j]);
+                const bool mine = p == (uint32_t)j;
+                hr = mine ? h : hr; hw = mine ? w : hw; oc = mine ? o : oc; mi = mine ? m1 : mi; mg = mine ? m2 : mg;
+                __builtin_amdgcn_sched_barrier(0);                     // one step at a time: few temporaries
             }
-            if (!parked) total = carry;                                // only at the last layer
-        } else if (has_s && active) {
-            tglobal[((size_t)s * L + l) * N + n] = t;
+            const uint32_t mo = mg - mi;
+            double t = step_time(q, hr, hw, mi, mo, acc_n, wr_n);      // Eqs. 2-4
+            t = active ? t : 0.0;                                      // rows past the end of the trace pad with +0.0
+            occ_acc[u] += oc;
+            if (counters && has_s && active)
+                *(uint4 *)(counters + (((size_t)s * L + l) * N + n) * 4) = make_uint4(hr, hw, mi, mo);
+            if (POW2) {
+                // folds of the summation tree that join the steps of one block (lanes)
+                for (uint32_t m = (64u >> log2L) >> 1; m >= 1; m >>= 1) t = fold_xor_f64(t, m);
+                // folds that join layers: binary counter over the bit-reversed visiting order
+                double *su = stk + (size_t)u * 6 * LQ * 64;
+                double carry = t;
+                bool parked = false;
+#pragma unroll
+                for (int j = 0; j < 6; j++) {
+                    if (!parked && (uint32_t)j < log2L) {
+                        if (((i >> j) & 1u) == 0) { su[j * LQ * 64] = carry; parked = true; }
+                        else carry = su[j * LQ * 64] + carry;
+                    }
+                }
+                if (!parked) total[u] = carry;                         // only at the last layer
+            } else if (has_s && active) {
+                tglobal[((size_t)s * L + l) * N + n] = t;
+            }
         }
     }
-    if (!has_s) return;
-    if (POW2) {
-        const uint32_t bpl = 64u >> log2L;                             // block b of the tile: steps [b*bpl, (b+1)*bpl)
-        if (((uint32_t)lane & (bpl - 1)) == 0 && (uint32_t)lane < rows)
-            blocksum[(size_t)s * nb_total + (size_t)tile * L + (uint32_t)lane / bpl] = total;
+#pragma unroll
+    for (int u = 0; u < PS; u++) {
+        const uint32_t s = s0 + u;
+        // (every lane takes part in the two reductions; only the stores depend on the schedule being there)
+        uint32_t ex = 0;
+        if (active) ex = occ_acc[u] > q.cap ? occ_acc[u] - q.cap : 0;
+        ex = wave_max_u32(ex);
+        const uint32_t fl = wave_or_u32(fl_acc[u]);
+        if (s >= S) continue;
+        if (POW2) {
+            const uint32_t bpl = 64u >> log2L;                         // block b of the tile: steps [b*bpl, (b+1)*bpl)
+            if (((uint32_t)lane & (bpl - 1)) == 0 && (uint32_t)lane < rows)
+                blocksum[(size_t)s * nb_total + (size_t)tile * L + (uint32_t)lane / bpl] = total[u];
+        }
+        if (active && occ_out) occ_out[(size_t)s * N + n] = occ_acc[u];   // Eq. 5 per token step
+        if (lane == 0) tileflag[(size_t)s * tiles + tile] = ex | (fl ? 0x80000000u : 0u);
     }
-    uint32_t ex = 0;
-    if (active) {
-        if (occ_out) occ_out[(size_t)s * N + n] = occ_acc;            // Eq. 5 per token step
-        ex = occ_acc > q.cap ? occ_acc - q.cap : 0;
-    }
-    ex = wave_max_u32(ex);
-    const uint32_t fl = wave_or_u32(fl_acc);
-    if (lane == 0) tileflag[(size_t)s * tiles + tile] = ex | (fl ? 0x80000000u : 0u);
 }
 
 }  // namespace
@@ -290,28 +311,35 @@ int kvp_blocksum_from_t_launch(kvp_ctx *ctx, uint32_t S, uint32_t nb_total);
 
 namespace {
 
-template <int LQ>
+template <int LQ, int PS>
 int launch_line(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total, uint32_t log2L,
                 bool pow2, uint32_t *counters, uint32_t *occ) {
     const DevProblem &q = ctx->dp;
     const uint32_t KB = ctx->kb;
-    const size_t lds = 2 * (size_t)(KB + 3) * PLANE * 4 + (pow2 ? (size_t)6 * LQ * 64 * 8 : 0);
+    const size_t lds = 2 * (size_t)(KB + 3) * PLANE * 4 + (pow2 ? (size_t)6 * LQ * PS * 64 * 8 : 0);
     if (lds > 160 * 1024) return 1;
-    const uint64_t nwg = xcd_grid(tiles, (S + LQ - 1) / LQ);
+    const uint64_t nwg = xcd_grid(tiles, (S + LQ * PS - 1) / (LQ * PS));
     if (nwg > 0x7FFFFFFFull) return 1;
     dim3 grid((uint32_t)nwg), block(LQ * 64);
 #define KVP_GO(KK, PP)                                                                                         \
     do {                                                                                                       \
-        KVP_HIP(hipFuncSetAttribute((const void *)score_line_kernel<KK, PP, LQ>,                               \
+        KVP_HIP(hipFuncSetAttribute((const void *)score_line_kernel<KK, PP, LQ, PS>,                             \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                   \
-        score_line_kernel<KK, PP, LQ><<<grid, block, lds, ctx->stream>>>(                                      \
+        score_line_kernel<KK, PP, LQ, PS><<<grid, block, lds, ctx->stream>>>(                                 \
             q, ctx->aw, X, S, tiles, nb_total, log2L, ctx->d_blocksum,                                          \
             ctx->d_tglobal, ctx->d_tileflag, counters, occ);                                                   \
     } while (0)
 #define KVP_K(KK) case KK: if (pow2) KVP_GO(KK, true); else KVP_GO(KK, false); break;
-    switch (KB) {
-        KVP_K(1) KVP_K(2) KVP_K(3) KVP_K(4)
-        default: return 1;
+    if constexpr (PS == 2) {                                           // registers: one digit plane only
+        switch (KB) {
+            KVP_K(1)
+            default: return 1;
+        }
+    } else {
+        switch (KB) {
+            KVP_K(1) KVP_K(2) KVP_K(3) KVP_K(4)
+            default: return 1;
+        }
     }
 #undef KVP_K
 #undef KVP_GO
@@ -336,12 +364,15 @@ int kvp_score_line_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t 
         int rc = kvp_ensure(ctx, (void **)&ctx->d_tglobal, &ctx->tglobal_cap, (size_t)S * q.L * q.N * sizeof(double));
         if (rc) return rc;
     }
-    // Eight schedules per workgroup share each fetch of the trace (half the trace bytes through L2 and the
-    // fabric of four); a compute unit then holds one workgroup, so that is taken only when there are enough
-    // groups of eight to give every compute unit one.
-    const bool wide = (uint64_t)((S + 7) / 8) * tiles >= ctx->compute_units;
-    int rc = wide ? launch_line<8>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ)
-                  : launch_line<4>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ);
+    // The more schedules share each fetch of the trace, the fewer trace bytes cross from L2 to the compute
+    // units (as many as schedule bytes with four): eight wavefronts per workgroup, one workgroup per compute
+    // unit, and two schedules per wavefront on top, each taken only when that leaves every compute unit a
+    // workgroup.
+    const uint64_t cus = ctx->compute_units;
+    int rc;
+    if (KB == 1 && (uint64_t)((S + 15) / 16) * tiles >= cus) rc = launch_line<8, 2>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ);
+    else if ((uint64_t)((S + 7) / 8) * tiles >= cus) rc = launch_line<8, 1>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ);
+    else rc = launch_line<4, 1>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ);
     if (rc) return rc;
     ctx->last_kernel = KVP_SCORE_LINE;
     if (!pow2) return kvp_blocksum_from_t_launch(ctx, S, nb_total);

@@ -182,18 +182,20 @@ def test_score_matches_oracle_bit_for_bit(G, name, kernel):
         assert (cost2 == cost).all() and (ex2 == ex).all()
 
 
-@pytest.mark.parametrize("L,N,P,K,S", [(2, 200, 1100, 2, 515), (3, 130, 2080, 1, 683)],
-                         ids=["L2-w35-k2", "L3-w65"])
-def test_line_scorer_with_eight_schedules_per_workgroup(G, L, N, P, K, S):
+@pytest.mark.parametrize("L,N,P,K,S,per", [(2, 200, 1100, 2, 515, 8), (3, 130, 2080, 1, 683, 8),
+                                             (2, 200, 1100, 1, 1011, 16), (3, 130, 1056, 1, 1365, 16)],
+                         ids=["L2-w35-k2", "L3-w65", "L2-w35-two-per-wavefront", "L3-w33-two-per-wavefront"])
+def test_line_scorer_with_eight_schedules_per_workgroup(G, L, N, P, K, S, per):
     """Batches with a group of eight schedules for every compute unit take the line scorer's wider workgroup
-    (eight wavefronts share each fetch of the trace): every schedule against the oracle.  S is no multiple of
-    eight (spare wavefronts in the last group), the last tile is ragged, and the last chunk of a row overlaps
-    the one before."""
+    (eight wavefronts share each fetch of the trace), and with a group of sixteen (one access plane) every
+    wavefront scores two schedules: every schedule against the oracle.  S is no multiple of the group (spare
+    places in the last one), the last tile is ragged, and the last chunk of a row overlaps the one before."""
     import torch
     tr = W.random_trace(90 + L, L=L, N=N, P=P, K=K)
     tiles = (N + 63) // 64
-    assert ((S + 7) // 8) * tiles >= torch.cuda.get_device_properties(0).multi_processor_count
-    assert S % 8 and N % 64 and tr.n_words % 32
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert ((S + per - 1) // per) * tiles >= cus and (per == 16 or K > 1 or ((S + 15) // 16) * tiles < cus)
+    assert S % per and N % 64 and tr.n_words % 32
     X = np.concatenate([W.random_placements(tr, S - 2, seed=3, density=0.4),
                         W.random_placements(tr, 2, seed=4, density=0.9, feasible=False)])
     q = O.Problem(tr)
