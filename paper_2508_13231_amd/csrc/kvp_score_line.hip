@@ -1,7 +1,7 @@
 // Scorer for wide rows (n_words >= 32): the schedule rows never touch LDS.
 //
-//   * A workgroup is four or eight wavefronts scoring the same 64 token steps of as
-//     many schedules.  A row is walked in chunks of 32 words = one 128-byte line when
+//   * A workgroup is eight wavefronts scoring the same 64 token steps of eight or
+//     sixteen schedules.  A row is walked in chunks of 32 words = one 128-byte line when
 //     rows are line-aligned.  Lane (g, p), g = lane / 8, p = lane % 8, takes the
 //     16-byte part p of the chunk for the steps 8g .. 8g+7: eight loads per lane and
 //     chunk, each wavefront instruction covering whole lines.  A lane scores its
@@ -47,7 +47,7 @@ __device__ __forceinline__ void count(uint32_t &acc, uint32_t v) {
 }
 
 // KB: digit planes of the read weights; POW2: L is a power of two in 2..64; LQ: wavefronts per workgroup,
-// 4 or 8; PS: schedules per wavefront, 1 or 2 (a wavefront then scores the chunk for one schedule after the
+// 4 or 8 (8 is what the launcher takes); PS: schedules per wavefront, 1 or 2 (a wavefront then scores the chunk for one schedule after the
 // other from the same trace slot).  No load is consumed in the iteration that issues it, and all are unconditional.
 template <int KB, bool POW2, int LQ, int PS>
 __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
@@ -365,14 +365,19 @@ int kvp_score_line_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t 
         if (rc) return rc;
     }
     // The more schedules share each fetch of the trace, the fewer trace bytes cross from L2 to the compute
-    // units (as many as schedule bytes with four): eight wavefronts per workgroup, one workgroup per compute
-    // unit, and two schedules per wavefront on top, each taken only when that leaves every compute unit a
-    // workgroup.
+    // units (as many as schedule bytes with four schedules per workgroup, which ran at 0.69 of the memory's
+    // peak): a workgroup is eight wavefronts, one workgroup per compute unit (0.80), and with one digit plane
+    // (registers) a wavefront may take two schedules (0.85).  A workgroup then takes twice as long, and the
+    // launch is over when its last round of workgroups is, however few they are: two per wavefront when
+    // rounds x group / rate is no larger that way.
     const uint64_t cus = ctx->compute_units;
-    int rc;
-    if (KB == 1 && (uint64_t)((S + 15) / 16) * tiles >= cus) rc = launch_line<8, 2>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ);
-    else if ((uint64_t)((S + 7) / 8) * tiles >= cus) rc = launch_line<8, 1>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ);
-    else rc = launch_line<4, 1>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ);
+    auto estimate = [&](uint32_t group, double rate) {
+        const uint64_t wgs = (uint64_t)((S + group - 1) / group) * tiles;
+        return (double)((wgs + cus - 1) / cus) * group / rate;
+    };
+    const bool two = KB == 1 && estimate(16, 0.85) <= estimate(8, 0.80);
+    int rc = two ? launch_line<8, 2>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ)
+                 : launch_line<8, 1>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ);
     if (rc) return rc;
     ctx->last_kernel = KVP_SCORE_LINE;
     if (!pow2) return kvp_blocksum_from_t_launch(ctx, S, nb_total);
