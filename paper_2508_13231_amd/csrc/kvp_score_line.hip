@@ -51,8 +51,8 @@ __device__ __forceinline__ void count(uint32_t &acc, uint32_t v) {
 // other from the same trace slot).  No load is consumed in the iteration that issues it, and all are unconditional.
 template <int KB, bool POW2, int LQ, int PS>
 __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
-    DevProblem q, const uint32_t *__restrict__ Aw, const uint32_t *__restrict__ X, uint32_t S, uint32_t tiles,
-    uint32_t nb_total, uint32_t log2L,
+    DevProblem q, const uint32_t *__restrict__ Aw, const uint32_t *__restrict__ X, uint32_t s_first, uint32_t S,
+    uint32_t tiles, uint32_t nb_total, uint32_t log2L,
     double *__restrict__ blocksum, double *__restrict__ tglobal, uint32_t *__restrict__ tileflag,
     uint32_t *__restrict__ counters, uint32_t *__restrict__ occ_out) {
     extern __shared__ double smem_d[];
@@ -64,8 +64,9 @@ __global__ __launch_bounds__(LQ * 64) void score_line_kernel(
     const int lane = lane_id();
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid / KVP_WAVE));
     uint32_t tile, group;                                             // see xcd_pair for the placement
-    if (!xcd_pair(tiles, (S + LQ * PS - 1) / (LQ * PS), tile, group)) return;
-    const uint32_t s0 = (group * LQ + wave) * PS;                      // the wavefront's schedules: s0 .. s0 + PS - 1
+    // the launch scores the schedules [s_first, S) of the batch
+    if (!xcd_pair(tiles, (S - s_first + LQ * PS - 1) / (LQ * PS), tile, group)) return;
+    const uint32_t s0 = s_first + (group * LQ + wave) * PS;            // the wavefront's schedules: s0 .. s0 + PS - 1
     const uint32_t n0 = tile * 64;
     const uint32_t rows = min(64u, N - n0);
     uint32_t *tbuf = (uint32_t *)smem_d;                               // two slots of NT * PLANE words
@@ -312,13 +313,13 @@ int kvp_blocksum_from_t_launch(kvp_ctx *ctx, uint32_t S, uint32_t nb_total);
 namespace {
 
 template <int LQ, int PS>
-int launch_line(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uint32_t nb_total, uint32_t log2L,
+int launch_line(kvp_ctx *ctx, const uint32_t *X, uint32_t s_first, uint32_t S, uint32_t tiles, uint32_t nb_total, uint32_t log2L,
                 bool pow2, uint32_t *counters, uint32_t *occ) {
     const DevProblem &q = ctx->dp;
     const uint32_t KB = ctx->kb;
     const size_t lds = 2 * (size_t)(KB + 3) * PLANE * 4 + (pow2 ? (size_t)6 * LQ * PS * 64 * 8 : 0);
     if (lds > 160 * 1024) return 1;
-    const uint64_t nwg = xcd_grid(tiles, (S + LQ * PS - 1) / (LQ * PS));
+    const uint64_t nwg = xcd_grid(tiles, (S - s_first + LQ * PS - 1) / (LQ * PS));
     if (nwg > 0x7FFFFFFFull) return 1;
     dim3 grid((uint32_t)nwg), block(LQ * 64);
 #define KVP_GO(KK, PP)                                                                                         \
@@ -326,7 +327,7 @@ int launch_line(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t tiles, uin
         KVP_HIP(hipFuncSetAttribute((const void *)score_line_kernel<KK, PP, LQ, PS>,                             \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                   \
         score_line_kernel<KK, PP, LQ, PS><<<grid, block, lds, ctx->stream>>>(                                 \
-            q, ctx->aw, X, S, tiles, nb_total, log2L, ctx->d_blocksum,                                          \
+            q, ctx->aw, X, s_first, S, tiles, nb_total, log2L, ctx->d_blocksum,                                        \
             ctx->d_tglobal, ctx->d_tileflag, counters, occ);                                                   \
     } while (0)
 #define KVP_K(KK) case KK: if (pow2) KVP_GO(KK, true); else KVP_GO(KK, false); break;
@@ -367,17 +368,26 @@ int kvp_score_line_launch(kvp_ctx *ctx, const uint32_t *X, uint32_t S, uint32_t 
     // The more schedules share each fetch of the trace, the fewer trace bytes cross from L2 to the compute
     // units (as many as schedule bytes with four schedules per workgroup, which ran at 0.69 of the memory's
     // peak): a workgroup is eight wavefronts, one workgroup per compute unit (0.80), and with one digit plane
-    // (registers) a wavefront may take two schedules (0.85).  A workgroup then takes twice as long, and the
-    // launch is over when its last round of workgroups is, however few they are: two per wavefront when
-    // rounds x group / rate is no larger that way.
+    // (registers) a wavefront may take two schedules (0.85).  A workgroup then takes twice as long, and a launch
+    // is over when its last round of workgroups is, however few they are.  So the schedules that fill whole
+    // rounds of workgroups of sixteen go first, and the rest follow in workgroups of eight; a batch that does
+    // not fill one such round takes sixteen only if rounds x group / rate is no larger that way.
     const uint64_t cus = ctx->compute_units;
     auto estimate = [&](uint32_t group, double rate) {
         const uint64_t wgs = (uint64_t)((S + group - 1) / group) * tiles;
         return (double)((wgs + cus - 1) / cus) * group / rate;
     };
-    const bool two = KB == 1 && estimate(16, 0.85) <= estimate(8, 0.80);
-    int rc = two ? launch_line<8, 2>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ)
-                 : launch_line<8, 1>(ctx, X, S, tiles, nb_total, log2L, pow2, counters, occ);
+    int rc;
+    if (KB != 1) {
+        rc = launch_line<8, 1>(ctx, X, 0, S, tiles, nb_total, log2L, pow2, counters, occ);
+    } else {
+        const uint64_t rounds = (uint64_t)(S / 16) * tiles / cus;      // whole rounds of workgroups of sixteen
+        uint64_t groups = rounds * cus / tiles;
+        uint32_t s_two = groups * 16 > S ? S : (uint32_t)(groups * 16);
+        if (rounds == 0) s_two = estimate(16, 0.85) <= estimate(8, 0.80) ? S : 0;
+        rc = s_two ? launch_line<8, 2>(ctx, X, 0, s_two, tiles, nb_total, log2L, pow2, counters, occ) : KVP_OK;
+        if (!rc && s_two < S) rc = launch_line<8, 1>(ctx, X, s_two, S, tiles, nb_total, log2L, pow2, counters, occ);
+    }
     if (rc) return rc;
     ctx->last_kernel = KVP_SCORE_LINE;
     if (!pow2) return kvp_blocksum_from_t_launch(ctx, S, nb_total);

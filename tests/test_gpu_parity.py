@@ -182,29 +182,37 @@ def test_score_matches_oracle_bit_for_bit(G, name, kernel):
         assert (cost2 == cost).all() and (ex2 == ex).all()
 
 
-def _line_group(S, tiles, cus, planes):
-    """Schedules per workgroup that the line scorer takes for a batch (its own rule, restated): sixteen if
-    rounds x group / rate is no larger that way and there is one digit plane, else eight."""
+def _line_split(S, tiles, cus, planes):
+    """How many of a batch's schedules the line scorer takes in workgroups of sixteen (its own rule, restated):
+    with one digit plane those that fill whole rounds of such workgroups, the rest in workgroups of eight; a
+    batch that fills no such round goes one way or the other by rounds x group / rate."""
     def est(group, rate):
         wgs = -(-S // group) * tiles
         return -(-wgs // cus) * group / rate
-    return 16 if planes == 1 and est(16, 0.85) <= est(8, 0.80) else 8
+    if planes != 1:
+        return 0
+    rounds = (S // 16) * tiles // cus
+    if rounds == 0:
+        return S if est(16, 0.85) <= est(8, 0.80) else 0
+    return rounds * cus // tiles * 16
 
 
-@pytest.mark.parametrize("L,N,P,K,S,per", [(2, 200, 1100, 2, 515, 8), (3, 130, 1056, 1, 1365, 8),
-                                             (2, 200, 1100, 1, 1011, 16), (3, 130, 2080, 1, 683, 16)],
-                         ids=["L2-w35-k2", "L3-w33", "L2-w35-two-per-wavefront", "L3-w65-two-per-wavefront"])
+@pytest.mark.parametrize("L,N,P,K,S,per", [(2, 200, 1100, 2, 515, "8"), (3, 130, 1056, 1, 1365, "8"),
+                                             (2, 200, 1100, 1, 1011, "16"), (3, 130, 2080, 1, 683, "16"),
+                                             (2, 200, 1100, 1, 1099, "16+8")],
+                         ids=["L2-w35-k2", "L3-w33", "L2-w35-two-per-wavefront", "L3-w65-two-per-wavefront", "L2-w35-both"])
 def test_line_scorer_with_eight_schedules_per_workgroup(G, L, N, P, K, S, per):
-    """Batches with a group of eight schedules for every compute unit take the line scorer's wider workgroup
-    (eight wavefronts share each fetch of the trace), and with a group of sixteen (one access plane) every
-    wavefront scores two schedules: every schedule against the oracle.  S is no multiple of the group (spare
-    places in the last one), the last tile is ragged, and the last chunk of a row overlaps the one before."""
+    """Batches of many schedules on the line scorer, every schedule against the oracle: in workgroups of eight
+    schedules, of sixteen (two per wavefront, one access plane), and split into whole rounds of sixteen and a
+    rest of eight.  S is no multiple of the group (spare places in the last one), the last tile is ragged, and
+    the last chunk of a row overlaps the one before."""
     import torch
     tr = W.random_trace(90 + L, L=L, N=N, P=P, K=K)
     tiles = (N + 63) // 64
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    assert _line_group(S, tiles, cus, K) == per
-    assert S % per and N % 64 and tr.n_words % 32
+    two = _line_split(S, tiles, cus, K)
+    assert {"8": two == 0, "16": two == S, "16+8": 0 < two < S}[per], two
+    assert S % 16 and S % 8 and N % 64 and tr.n_words % 32
     X = np.concatenate([W.random_placements(tr, S - 2, seed=3, density=0.4),
                         W.random_placements(tr, 2, seed=4, density=0.9, feasible=False)])
     q = O.Problem(tr)
