@@ -14,7 +14,9 @@
 //     weight (sum over planes of plane_bytes/unit): K planes of equal size become
 //     floor(log2 K) + 1 digit planes, and hr = sum_j 2^j popcount(x & digit_j).
 //     The digit planes of a pass are fetched once per workgroup into a
-//     double-buffered LDS slot, one pass ahead; the rows two passes ahead.
+//     double-buffered LDS slot, one pass ahead, and so are the rows, into registers
+//     (two passes ahead cost 36 more registers and, on rows of 66 words, the third
+//     wavefront per SIMD: 6 % slower).
 //   * On a tile of 64 steps the words below the first one that is not FULL there need
 //     no masks; the at most four words from there to the sequence's end use alive /
 //     persist words that do not depend on the layer and stay in registers for the
@@ -168,7 +170,7 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
     const uint32_t sched_words = L * N * Wd;                           // < 2^31 (checked by the host)
 
     struct Stage { r4u x[XV]; };
-    Stage st0, st1;
+    Stage st0;
     uint32_t acc_nx = 0;                                               // read units of the lane's step, next layer
     r4u tr[TV];
     // i-th layer in visiting order (i / q by a multiplication: exact for i < 256, q <= 7; the host checks)
@@ -236,7 +238,7 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
             for (int jv = 0; jv < XV; jv++) put22(xbuf + xlds[jv], st.x[jv]);
         }
         issue_t(p ^ 1u, p ? lnext : layer_of(i));                      // digit planes of the next pass
-        issue_x(st, p, lnext);                                         // rows of two passes ahead
+        issue_x(st, p ^ 1u, p ? lnext : layer_of(i));                  // rows of the next pass
         __syncthreads();                                               // this pass's trace slot is complete
         // (addresses and masks below are rebuilt in every pass from these two copies: kept across the
         // layer loop they would occupy some sixty registers)
@@ -352,14 +354,13 @@ __global__ __launch_bounds__(RQ * 64) void score_rowblock_kernel(
     };
     issue_t(0, layer_of(0));
     issue_x(st0, 0, layer_of(0));
-    issue_x(st1, 1, layer_of(0));
     acc_nx = q.acc[(size_t)layer_of(0) * N + n];
     commit_t(0);
     for (uint32_t i = 0; i < L; i++) {
         const uint32_t acc_n = acc_nx;
         acc_nx = q.acc[(size_t)layer_of(min(i + 1, L - 1)) * N + n];
         pass(st0, 0, i);
-        pass(st1, 1, i);
+        pass(st0, 1, i);
         layer_end(i, acc_n);
     }
     if (!has_s) return;
