@@ -37,7 +37,7 @@ TARGETS = ["llama8b", "longctx", "gqa70b", "serving"]      # the headline is the
 # HBM bytes per kvp_score launch (scoring kernel + finalize) from rocprofv3 FETCH_SIZE / WRITE_SIZE, each
 # scaled by what the same counter reads for a device copy of 1 GiB; keyed by (workload, S, scorer that ran).
 # Any other workload, batch size or kernel choice reports null.  Source: profiles/kvp_score_<workload>.md.
-MEASURED_TRAFFIC = {("llama8b", 14564, "quad"): 4.514e9, ("longctx", 1024, "rowblock"): 9.535e9,
+MEASURED_TRAFFIC = {("llama8b", 14564, "quad"): 4.514e9, ("longctx", 1024, "rowblock"): 9.432e9,
                     ("gqa70b", 512, "rowlane"): 11.776e9, ("serving", 512, "line"): 72.046e9}
 
 
