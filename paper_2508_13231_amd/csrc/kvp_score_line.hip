@@ -13,6 +13,9 @@
 //     persist, written) are the same for those schedules: fetched once per
 //     workgroup, one chunk ahead, into a double-buffered LDS slot laid out in the
 //     order the lanes read it (16 bytes per lane, consecutive lanes consecutive).
+//     With sixteen schedules a wavefront scores the chunk for one schedule and then
+//     for another from the same slot: the registers that the first one's rows leave
+//     are refilled with the second one's, then with the first one's next chunk.
 //   * The loop over the chunks has no branch around a load or around the counting: every
 //     row vector is requested again, into the same registers, right after its last use.
 //     (A branch that skips the counting for chunks without pages made the compiler keep
